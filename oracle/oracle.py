@@ -1,0 +1,186 @@
+"""ctypes front end of the CPU oracle (oracle/sgc_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+cpu_baseline leg of the benchmark. Nothing here touches the HIP library, and the
+HIP library never calls into this module.
+
+Every function takes and returns numpy arrays on the host. `step` strings the
+pieces together in the order of Alg. 2 of the paper for a batch of independent
+chunks (MESGC, Sec. 4.4).
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sgc_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+
+def build(force=False):
+    """Compile the C oracle with gcc (plain -O2, no contraction of a*b+c)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fPIC", "-shared", "-o", _LIB, _SRC, "-lm"]
+        )
+    return _LIB
+
+
+def _p(a, ct):
+    return a.ctypes.data_as(ctypes.POINTER(ct)) if a is not None else None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+    return _lib
+
+
+def _c(a, dt):
+    return np.ascontiguousarray(a, dtype=dt)
+
+
+def topk(g, k):
+    """Sparsify_k per chunk (Sec. 4.2, Def. 1). g: [C, d] float32 or uint16 (bf16 bits)."""
+    g = np.ascontiguousarray(g)
+    C, d = g.shape
+    idx = np.empty((C, k), np.int32)
+    val = np.empty((C, k), np.float32)
+    if g.dtype == np.float32:
+        rc = lib().oracle_topk_f32(_p(g, ctypes.c_float), ctypes.c_int64(C), d, k, _p(idx, ctypes.c_int32), _p(val, ctypes.c_float))
+    elif g.dtype == np.uint16:
+        rc = lib().oracle_topk_bf16(_p(g, ctypes.c_uint16), ctypes.c_int64(C), d, k, _p(idx, ctypes.c_int32), _p(val, ctypes.c_float))
+    else:
+        raise TypeError(g.dtype)
+    if rc:
+        raise ValueError("oracle_topk rc=%d" % rc)
+    return idx, val
+
+
+def project(idx, val, At):
+    """p = A Sparsify(G), q = A Sparsify(G^2) (eq. 5-6). At: [d, r] float32."""
+    idx = _c(idx, np.int32)
+    val = _c(val, np.float32)
+    At = _c(At, np.float32)
+    C, k = idx.shape
+    d, r = At.shape
+    p = np.empty((C, r), np.float32)
+    q = np.empty((C, r), np.float32)
+    rc = lib().oracle_project(_p(idx, ctypes.c_int32), _p(val, ctypes.c_float), ctypes.c_int64(C), k, _p(At, ctypes.c_float), d, r, _p(p, ctypes.c_float), _p(q, ctypes.c_float))
+    if rc:
+        raise ValueError("oracle_project rc=%d" % rc)
+    return p, q
+
+
+def philox4x32_10(ctr, key):
+    ctr = _c(ctr, np.uint32)
+    key = _c(key, np.uint32)
+    out = np.empty(4, np.uint32)
+    lib().oracle_philox4x32_10(_p(ctr, ctypes.c_uint32), _p(key, ctypes.c_uint32), _p(out, ctypes.c_uint32))
+    return out
+
+
+def normal_pair(w0, w1, scale=1.0):
+    out = np.empty(2, np.float32)
+    lib().oracle_normal_pair(ctypes.c_uint32(int(w0)), ctypes.c_uint32(int(w1)), ctypes.c_float(scale), _p(out, ctypes.c_float))
+    return out
+
+
+def philox_matrix(seed, d, r, i0=0, rows=None):
+    """Rows [i0, i0+rows) of At for the counter-based matrix (Sec. 4.3 distribution)."""
+    rows = d - i0 if rows is None else rows
+    out = np.empty((rows, r), np.float32)
+    rc = lib().oracle_philox_matrix(ctypes.c_uint64(seed), r, ctypes.c_int64(i0), ctypes.c_int64(rows), _p(out, ctypes.c_float))
+    if rc:
+        raise ValueError("oracle_philox_matrix rc=%d" % rc)
+    return out
+
+
+def adam(p, q, m, v, step, beta1=0.9, beta2=0.999):
+    """Alg. 2 lines 2-5. Returns (m_new, v_new, mhat, vhat); inputs are not modified."""
+    p = _c(p, np.float32)
+    q = _c(q, np.float32)
+    m = np.array(m, np.float32, copy=True, order="C")
+    v = np.array(v, np.float32, copy=True, order="C")
+    mh = np.empty_like(m)
+    vh = np.empty_like(v)
+    rc = lib().oracle_adam(_p(p, ctypes.c_float), _p(q, ctypes.c_float), _p(m, ctypes.c_float), _p(v, ctypes.c_float), _p(mh, ctypes.c_float), _p(vh, ctypes.c_float), ctypes.c_int64(m.size), int(step), ctypes.c_double(beta1), ctypes.c_double(beta2))
+    if rc:
+        raise ValueError("oracle_adam rc=%d" % rc)
+    return m, v, mh, vh
+
+
+def colnorms(At):
+    At = _c(At, np.float32)
+    d, r = At.shape
+    out = np.empty(d, np.float64)
+    lib().oracle_colnorms(_p(At, ctypes.c_float), d, r, _p(out, ctypes.c_double))
+    return out
+
+
+def omp(y, At, k, norm=None, forced=None, want_top2=False):
+    """OMP_A(y) for one right-hand side (Sec. 4.3 eq. 9).
+
+    Returns dict(sel, x, x64, res, top2). `forced` dictates the first selections.
+    """
+    y = _c(y, np.float32)
+    At = _c(At, np.float32)
+    d, r = At.shape
+    assert y.shape == (r,)
+    sel = np.empty(k, np.int32)
+    x = np.empty(k, np.float32)
+    x64 = np.empty(k, np.float64)
+    res = np.empty(r, np.float64)
+    top2 = np.empty(2 * k, np.float64) if want_top2 else None
+    norm = _c(norm, np.float64) if norm is not None else None
+    forced = _c(forced, np.int32) if forced is not None else None
+    nf = 0 if forced is None else forced.size
+    rc = lib().oracle_omp(_p(y, ctypes.c_float), _p(At, ctypes.c_float), d, r, k, _p(norm, ctypes.c_double), _p(forced, ctypes.c_int32), nf, _p(sel, ctypes.c_int32), _p(x, ctypes.c_float), _p(x64, ctypes.c_double), _p(res, ctypes.c_double), _p(top2, ctypes.c_double))
+    if rc:
+        raise ValueError("oracle_omp rc=%d" % rc)
+    return dict(sel=sel, x=x, x64=x64, res=res, top2=None if top2 is None else top2.reshape(k, 2))
+
+
+def omp_batch(Y, At, k):
+    Y = _c(Y, np.float32)
+    At = _c(At, np.float32)
+    N, r = Y.shape
+    d = At.shape[0]
+    sel = np.empty((N, k), np.int32)
+    x = np.empty((N, k), np.float32)
+    rc = lib().oracle_omp_batch(_p(Y, ctypes.c_float), N, _p(At, ctypes.c_float), d, r, k, _p(sel, ctypes.c_int32), _p(x, ctypes.c_float))
+    if rc:
+        raise ValueError("oracle_omp_batch rc=%d" % rc)
+    return sel, x
+
+
+def apply(W, d, sel_m, x_m, sel_v, x_v, alpha=1.0, eps=1e-8, lr=1e-3):
+    """W <- W - lr * alpha * x / (sqrt(z) + eps) on the recovered supports (eq. 11, eq. 3)."""
+    W = np.array(W, np.float32, copy=True, order="C")
+    sel_m = _c(sel_m, np.int32)
+    sel_v = _c(sel_v, np.int32)
+    x_m = _c(x_m, np.float32)
+    x_v = _c(x_v, np.float32)
+    C, k = sel_m.shape
+    assert W.size == C * d
+    rc = lib().oracle_apply(_p(W, ctypes.c_float), ctypes.c_int64(C), d, k, _p(sel_m, ctypes.c_int32), _p(x_m, ctypes.c_float), _p(sel_v, ctypes.c_int32), _p(x_v, ctypes.c_float), ctypes.c_double(alpha), ctypes.c_double(eps), ctypes.c_double(lr))
+    if rc:
+        raise ValueError("oracle_apply rc=%d" % rc)
+    return W
+
+
+def step(g, W, m, v, t, At, k, beta1=0.9, beta2=0.999, eps=1e-8, lr=1e-3, alpha=1.0):
+    """One full SGC step (Alg. 2 + the weight update) on C chunks. g: [C, d]."""
+    C, d = g.shape
+    idx, val = topk(g, k)
+    p, q = project(idx, val, At)
+    m2, v2, mh, vh = adam(p, q, m, v, t, beta1, beta2)
+    Y = np.concatenate([mh.reshape(C, -1), vh.reshape(C, -1)], axis=0)
+    sel, x = omp_batch(Y, At, k)
+    W2 = apply(W, d, sel[:C], x[:C], sel[C:], x[C:], alpha, eps, lr)
+    return dict(idx=idx, val=val, p=p, q=q, m=m2, v=v2, mhat=mh, vhat=vh, sel_m=sel[:C], x_m=x[:C], sel_v=sel[C:], x_v=x[C:], W=W2)

@@ -1,0 +1,367 @@
+"""Pins of the CPU oracle against things that are not the oracle: brute force, library
+routines, published test vectors, closed forms and invariants. CPU only."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from paper_2502_00311_amd import synth
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# --------------------------------------------------------------------------- top-k
+def brute_topk(g, k):
+    """Sparsify_k by a full stable sort on (-|g|, position) (Sec. 4.2)."""
+    mag = np.abs(g.astype(np.float64))
+    order = np.lexsort((np.arange(g.size), -mag))[:k]
+    pos = np.sort(order)
+    return pos.astype(np.int32), g[pos]
+
+
+@pytest.mark.parametrize("d,k", [(1, 1), (7, 3), (64, 64), (1000, 17), (4096, 32), (5003, 256)])
+def test_topk_matches_full_sort(d, k):
+    rng = np.random.default_rng(d * 31 + k)
+    g = rng.standard_t(3, size=(5, d)).astype(np.float32)
+    idx, val = orc.topk(g, k)
+    for c in range(g.shape[0]):
+        pos, v = brute_topk(g[c], k)
+        assert np.array_equal(idx[c], pos)
+        assert np.array_equal(val[c], v)
+
+
+def test_topk_ties_lower_position_wins_and_sign_is_kept():
+    g = np.array([[1.0, -2.0, 2.0, -2.0, 0.5, 2.0, -0.0, 0.0]], np.float32)
+    idx, val = orc.topk(g, 3)
+    assert idx.tolist() == [[1, 2, 3]]
+    assert val.tolist() == [[-2.0, 2.0, -2.0]]
+    idx, val = orc.topk(np.zeros((1, 6), np.float32), 2)
+    assert idx.tolist() == [[0, 1]]
+    # quantised values: many ties at the threshold
+    rng = np.random.default_rng(5)
+    g = rng.integers(-4, 5, size=(3, 300)).astype(np.float32)
+    idx, val = orc.topk(g, 40)
+    for c in range(3):
+        pos, v = brute_topk(g[c], 40)
+        assert np.array_equal(idx[c], pos) and np.array_equal(val[c], v)
+
+
+def test_topk_bf16_matches_full_sort_on_widened_values():
+    rng = np.random.default_rng(11)
+    g32 = rng.standard_t(2.5, size=(4, 3000)).astype(np.float32)
+    bits = synth.f32_to_bf16_bits(g32)
+    wide = synth.bf16_bits_to_f32(bits)
+    idx, val = orc.topk(bits, 100)
+    for c in range(4):
+        pos, v = brute_topk(wide[c], 100)
+        assert np.array_equal(idx[c], pos)
+        assert np.array_equal(val[c], v)
+
+
+def test_bf16_rounding_is_nearest_even():
+    # 1 + 2^-8 is halfway between bf16 1.0 and 1+2^-7: ties to even -> 1.0; 1+3*2^-8 -> 1+2^-6
+    x = np.array([1.0 + 2.0**-8, 1.0 + 3 * 2.0**-8, 1.0 + 2.0**-8 + 2.0**-20], np.float32)
+    back = synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(x))
+    assert back.tolist() == [1.0, 1.0 + 2.0**-6, 1.0 + 2.0**-7]
+
+
+def test_chunked_vs_global_sparsification_bound():
+    """Thm. 1: E||chunked - global||^2 <= 2 (1 - s/d) G_max, G_max = ||G||^2 here."""
+    rng = np.random.default_rng(3)
+    c, dc, sc = 8, 512, 16
+    for _ in range(5):
+        G = rng.standard_t(3, size=c * dc).astype(np.float32)
+        idx, val = orc.topk(G.reshape(c, dc), sc)
+        chunked = np.zeros(c * dc)
+        for i in range(c):
+            chunked[i * dc + idx[i]] = val[i]
+        gi, gv = orc.topk(G.reshape(1, -1), c * sc)
+        glob = np.zeros(c * dc)
+        glob[gi[0]] = gv[0]
+        lhs = np.sum((chunked - glob) ** 2)
+        assert lhs <= 2 * (1 - c * sc / (c * dc)) * np.sum(G.astype(np.float64) ** 2)
+
+
+# ---------------------------------------------------------------------- projection
+def test_projection_equals_dense_matvec():
+    rng = np.random.default_rng(0)
+    d, r, k, C = 700, 96, 23, 4
+    At = synth.gaussian_matrix(9, d, r)
+    g = rng.standard_normal((C, d)).astype(np.float32)
+    idx, val = orc.topk(g, k)
+    p, q = orc.project(idx, val, At)
+    A = At.astype(np.float64).T  # r x d
+    for c in range(C):
+        gs = np.zeros(d)
+        gs[idx[c]] = val[c]
+        gs2 = np.zeros(d)
+        gs2[idx[c]] = (val[c] * val[c]).astype(np.float64)  # float square, as a float G^2 holds
+        assert np.allclose(p[c], A @ gs, rtol=0, atol=1e-6 * np.abs(A @ gs).max())
+        assert np.allclose(q[c], A @ gs2, rtol=0, atol=1e-6 * np.abs(A @ gs2).max())
+    # a transposed operand or an index slip would not survive a one-hot gradient
+    one = np.zeros((1, d), np.float32)
+    one[0, 123] = -3.0
+    idx, val = orc.topk(one, 1)
+    p, q = orc.project(idx, val, At)
+    assert np.array_equal(p[0], (-3.0 * At[123].astype(np.float64)).astype(np.float32))
+    assert np.array_equal(q[0], (9.0 * At[123].astype(np.float64)).astype(np.float32))
+
+
+# -------------------------------------------------------------------------- Philox
+def test_philox_known_answers():
+    rows = [l.split() for l in open(os.path.join(GOLD, "philox4x32_10_kat.txt")) if not l.startswith("#")]
+    assert len(rows) == 3
+    for row in rows:
+        w = [int(x, 16) for x in row]
+        out = orc.philox4x32_10(w[0:4], w[4:6])
+        assert [int(x) for x in out] == w[6:10]
+
+
+def test_normal_transform_against_exact_box_muller():
+    rng = np.random.default_rng(1)
+    w = rng.integers(0, 2**32, size=(20000, 2), dtype=np.uint64)
+    # corners of the input space
+    w[:8, 0] = [0, 1, 2**32 - 1, 2**31, 511, 512, 2**32 - 512, 2**9 * 3]
+    w[:8, 1] = [0, 2**32 - 1, 2**29, 2**29 - 1, 2**31, 3 * 2**29 + 5, 2**30, 7 * 2**29]
+    worst = 0.0
+    for a, b in w:
+        z = orc.normal_pair(a, b, 1.0).astype(np.float64)
+        u = (((int(a) >> 9) << 1) | 1) * 2.0**-24
+        oct_ = int(b) >> 29
+        frac = ((int(b) >> 6) & 0x7FFFFF) + 0.5
+        theta = (oct_ + frac * 2.0**-23) * (np.pi / 4)
+        rad = np.sqrt(-2.0 * np.log(u))
+        ex = np.array([rad * np.cos(theta), rad * np.sin(theta)])
+        worst = max(worst, np.abs(z - ex).max() / max(1.0, rad))
+    assert worst < 6e-7
+
+
+def test_philox_matrix_layout_and_statistics():
+    d, r = 512, 256
+    At = orc.philox_matrix(0x1234567890ABCDEF, d, r)
+    # layout: counter (i, j/4), words (0,1) -> rows 4b,4b+1 and (2,3) -> rows 4b+2,4b+3
+    key = [0x90ABCDEF, 0x12345678]
+    scale = np.float32(1.0 / np.sqrt(r))
+    for i, jb in [(0, 0), (5, 3), (511, 63)]:
+        wds = orc.philox4x32_10([i, jb, 0, 0], key)
+        z01 = orc.normal_pair(wds[0], wds[1], scale)
+        z23 = orc.normal_pair(wds[2], wds[3], scale)
+        assert np.array_equal(At[i, 4 * jb:4 * jb + 4], np.concatenate([z01, z23]))
+    # sub-blocks equal the corresponding rows of the full matrix
+    assert np.array_equal(orc.philox_matrix(0x1234567890ABCDEF, d, r, 100, 7), At[100:107])
+    # a different seed gives a different matrix
+    assert not np.array_equal(orc.philox_matrix(2, d, r, 0, 4), At[:4])
+    z = At.astype(np.float64).ravel() * np.sqrt(r)
+    n = z.size
+    assert abs(z.mean()) < 4 / np.sqrt(n)
+    assert abs(z.var() - 1) < 4 * np.sqrt(2 / n)
+    assert abs((z**4).mean() - 3) < 4 * np.sqrt(96 / n)
+    from scipy import stats
+    assert stats.kstest(z, "norm").pvalue > 1e-3
+    # rows and columns are uncorrelated: Gram of 64 columns is close to identity
+    G = At[:64].astype(np.float64) @ At[:64].astype(np.float64).T
+    assert np.abs(G - np.eye(64)).max() < 6 / np.sqrt(r)
+
+
+# ---------------------------------------------------------------------------- Adam
+def test_adam_hand_derived_steps():
+    rows = [list(map(float, l.split())) for l in open(os.path.join(GOLD, "adam_step1_closed_form.txt")) if not l.startswith("#")]
+    for p, q, m1, v1, mh1, vh1, m2s, v2s, m2c, v2c, mh2c, vh2c in rows:
+        P = np.array([p], np.float32)
+        Q = np.array([q], np.float32)
+        z = np.zeros(1, np.float32)
+        m, v, mh, vh = orc.adam(P, Q, z, z, 1)
+        assert np.allclose([m[0], v[0], mh[0], vh[0]], [m1, v1, mh1, vh1], rtol=2e-6, atol=0)
+        mm, vv, mh2, vh2 = orc.adam(P, Q, m, v, 2)
+        assert np.allclose([mm[0], vv[0], mh2[0], vh2[0]], [m2s, v2s, p, q], rtol=2e-6, atol=0)
+        mm, vv, mh2, vh2 = orc.adam(3 * P, 5 * Q, m, v, 2)
+        assert np.allclose([mm[0], vv[0], mh2[0], vh2[0]], [m2c, v2c, mh2c, vh2c], rtol=2e-6, atol=0)
+
+
+def test_adam_moments_are_the_projection_of_dense_adam_moments():
+    """Eq. 10: M_t = A sum_i h_i(beta1) G~_i, i.e. the compressed moment equals A times the
+    dense AdamW first moment (Alg. 1) of the sparsified gradients; same for V with G~^2."""
+    rng = np.random.default_rng(4)
+    d, r, k = 600, 80, 12
+    At = synth.gaussian_matrix(3, d, r)
+    A = At.astype(np.float64).T
+    m = np.zeros(r, np.float32)
+    v = np.zeros(r, np.float32)
+    Md = np.zeros(d)
+    Vd = np.zeros(d)
+    b1, b2 = 0.9, 0.999
+    for t in range(1, 6):
+        g = rng.standard_normal((1, d)).astype(np.float32)
+        idx, val = orc.topk(g, k)
+        p, q = orc.project(idx, val, At)
+        m, v, mh, vh = orc.adam(p[0], q[0], m, v, t)
+        gs = np.zeros(d)
+        gs[idx[0]] = val[0]
+        Md = b1 * Md + (1 - b1) * gs
+        Vd = b2 * Vd + (1 - b2) * gs**2
+        assert np.allclose(m, A @ Md, rtol=0, atol=5e-6 * np.abs(A @ Md).max())
+        assert np.allclose(v, A @ Vd, rtol=0, atol=5e-6 * np.abs(A @ Vd).max())
+        assert np.allclose(mh, A @ (Md / (1 - b1**t)), rtol=0, atol=5e-6 * np.abs(mh).max())
+        assert np.allclose(vh, A @ (Vd / (1 - b2**t)), rtol=0, atol=5e-6 * np.abs(vh).max())
+
+
+def test_state_counts_printed_in_the_paper():
+    for line in open(os.path.join(GOLD, "paper_state_counts.txt")):
+        if line.startswith("#"):
+            continue
+        kappa, c, sc, states = map(int, line.split())
+        r = kappa * sc  # measurements per chunk
+        m = np.zeros((c, r), np.float32)
+        v = np.zeros((c, r), np.float32)
+        assert m.size + v.size == states
+
+
+# ----------------------------------------------------------------------------- OMP
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_omp_exact_recovery_of_sparse_signals(seed):
+    """Sec. 4.3: a k-sparse x is reconstructed from y = A x when A is iid normal with enough
+    measurements (here r >= 4 k ln d)."""
+    d, k, r = 1024, 8, 256
+    At = synth.gaussian_matrix(seed + 20, d, r)
+    x, pos = synth.sparse_signal(seed, d, k)
+    y = (At.astype(np.float64).T @ x).astype(np.float32)
+    out = orc.omp(y, At, k)
+    assert sorted(out["sel"].tolist()) == pos.tolist()
+    rec = np.zeros(d)
+    rec[out["sel"]] = out["x64"]
+    assert np.abs(rec - x).max() < 1e-5
+    assert np.linalg.norm(out["res"]) < 1e-5 * np.linalg.norm(y)
+
+
+def exhaustive_best_support(y, A, k):
+    best, arg = np.inf, None
+    for S in itertools.combinations(range(A.shape[1]), k):
+        sol, *_ = np.linalg.lstsq(A[:, S], y, rcond=None)
+        rn = np.linalg.norm(y - A[:, S] @ sol)
+        if rn < best:
+            best, arg = rn, S
+    return arg, best
+
+
+@pytest.mark.parametrize("d,k,r,seed", [(12, 1, 6, 0), (16, 2, 8, 1), (20, 3, 10, 2), (18, 3, 9, 3)])
+def test_omp_equals_exhaustive_search_on_tiny_problems(d, k, r, seed):
+    At = synth.gaussian_matrix(seed + 50, d, r)
+    A = At.astype(np.float64).T
+    x, pos = synth.sparse_signal(seed + 9, d, k)
+    y = (A @ x).astype(np.float32)
+    S, rn = exhaustive_best_support(y.astype(np.float64), A, k)
+    assert rn < 1e-6 and list(S) == pos.tolist()
+    out = orc.omp(y, At, k)
+    assert sorted(out["sel"].tolist()) == list(S)
+    sol, *_ = np.linalg.lstsq(A[:, out["sel"]], y.astype(np.float64), rcond=None)
+    assert np.allclose(out["x64"], sol, rtol=1e-9, atol=1e-12)
+
+
+def test_omp_first_pick_is_best_single_atom_fit_with_unequal_column_norms():
+    """The selection rule divides by the column norm (App. B): the first pick is the atom whose
+    one-atom least-squares fit leaves the smallest residual, whatever the column scales."""
+    rng = np.random.default_rng(8)
+    d, r = 200, 40
+    At = synth.gaussian_matrix(4, d, r) * rng.uniform(0.05, 20, size=(d, 1)).astype(np.float32)
+    A = At.astype(np.float64).T
+    for t in range(10):
+        y = rng.standard_normal(r).astype(np.float32)
+        out = orc.omp(y, At, 1)
+        resid = [np.linalg.norm(y - A[:, i] * (A[:, i] @ y) / (A[:, i] @ A[:, i])) for i in range(d)]
+        assert out["sel"][0] == int(np.argmin(resid))
+
+
+def test_omp_invariants_in_the_noisy_regime():
+    """Each iteration is the least-squares fit on the chosen support: residual orthogonal to the
+    selected columns, residual norm non-increasing, values equal to a library least squares, and
+    every pick maximises the normalised correlation with the previous residual."""
+    rng = np.random.default_rng(12)
+    d, r, k = 400, 64, 10
+    At = synth.gaussian_matrix(6, d, r)
+    A = At.astype(np.float64).T
+    nrm = np.linalg.norm(A, axis=0)
+    assert np.allclose(orc.colnorms(At), nrm, rtol=1e-14)
+    y = rng.standard_normal(r).astype(np.float32)  # not sparse at all
+    full = orc.omp(y, At, k, want_top2=True)
+    prev = np.linalg.norm(y)
+    res = y.astype(np.float64)
+    for j in range(1, k + 1):
+        score = np.abs(A.T @ res) / nrm
+        score[full["sel"][: j - 1]] = -1
+        assert full["sel"][j - 1] == int(np.argmax(score))
+        top = np.sort(score)[::-1][:2]
+        assert np.allclose(full["top2"][j - 1], top, rtol=1e-10)
+        pre = orc.omp(y, At, j)
+        assert np.array_equal(pre["sel"], full["sel"][:j])
+        S = pre["sel"]
+        sol, *_ = np.linalg.lstsq(A[:, S], y.astype(np.float64), rcond=None)
+        assert np.allclose(pre["x64"], sol, rtol=1e-9, atol=1e-12)
+        res = y - A[:, S] @ sol
+        assert np.allclose(pre["res"], res, atol=1e-12)
+        assert np.abs(A[:, S].T @ pre["res"]).max() < 1e-10 * np.linalg.norm(y)
+        assert np.linalg.norm(pre["res"]) <= prev + 1e-12
+        prev = np.linalg.norm(pre["res"])
+
+
+def test_omp_forced_prefix_and_zero_input():
+    rng = np.random.default_rng(13)
+    d, r, k = 300, 48, 6
+    At = synth.gaussian_matrix(7, d, r)
+    y = rng.standard_normal(r).astype(np.float32)
+    full = orc.omp(y, At, k)
+    again = orc.omp(y, At, k, forced=full["sel"][:4])
+    assert np.array_equal(again["sel"], full["sel"]) and np.array_equal(again["x"], full["x"])
+    other = orc.omp(y, At, 3, forced=np.array([5, 9], np.int32))
+    assert other["sel"][:2].tolist() == [5, 9] and other["sel"][2] not in (5, 9)
+    zero = orc.omp(np.zeros(r, np.float32), At, 4)
+    assert zero["sel"].tolist() == [0, 1, 2, 3] and not zero["x"].any()
+    sel, x = orc.omp_batch(np.stack([y, np.zeros(r, np.float32)]), At, k)
+    assert np.array_equal(sel[0], full["sel"]) and np.array_equal(x[0], full["x"])
+    assert sel[1].tolist() == list(range(k))
+
+
+# ----------------------------------------------------------------------- full step
+def test_apply_formula_by_hand():
+    # eq. 11 with alpha=2, eps=0.5, lr=0.1: N = 2*x/(sqrt(z)+0.5)
+    d = 8
+    W = np.arange(8, dtype=np.float32).reshape(1, 8)
+    sel_m = np.array([[6, 1, 3]], np.int32)
+    x_m = np.array([[3.0, -1.0, 2.0]], np.float32)
+    sel_v = np.array([[1, 6, 5]], np.int32)
+    x_v = np.array([[4.0, -9.0, 1.0]], np.float32)
+    out = orc.apply(W, d, sel_m, x_m, sel_v, x_v, alpha=2.0, eps=0.5, lr=0.1)
+    exp = np.arange(8, dtype=np.float64)
+    exp[6] -= 0.1 * 2 * 3.0 / (0.0 + 0.5)      # negative second moment -> 0
+    exp[1] -= 0.1 * 2 * -1.0 / (2.0 + 0.5)
+    exp[3] -= 0.1 * 2 * 2.0 / (0.0 + 0.5)      # missing second moment -> 0
+    assert np.allclose(out.ravel(), exp, rtol=1e-6)
+
+
+def test_first_step_closed_form_in_exact_recovery_regime():
+    """With zero initial moments Mhat_1 = p and Vhat_1 = q (Alg. 2), so when OMP recovers the
+    k-sparse G~ and G~^2 exactly, N_1 = alpha G~/(|G~| + eps) on the top-k support (eq. 11)."""
+    w = synth.shrink(synth.CFG1, C=3, d=2048, r=512, k=8)
+    g = synth.gradients(w, 1)
+    At = synth.gaussian_matrix(1, w.d, w.r)
+    W0 = synth.weights(w)
+    z = np.zeros((w.C, w.r), np.float32)
+    alpha, eps, lr = 2.0, 1e-8, 1e-3
+    out = orc.step(g, W0, z, z, 1, At, w.k, alpha=alpha, eps=eps, lr=lr)
+    assert np.allclose(out["mhat"], out["p"], rtol=2e-6, atol=0)
+    assert np.allclose(out["vhat"], out["q"], rtol=2e-6, atol=0)
+    exp = W0.astype(np.float64).copy().reshape(w.C, w.d)
+    for c in range(w.C):
+        assert sorted(out["sel_m"][c].tolist()) == out["idx"][c].tolist()
+        assert sorted(out["sel_v"][c].tolist()) == out["idx"][c].tolist()
+        gv = out["val"][c].astype(np.float64)
+        exp[c, out["idx"][c]] -= lr * alpha * gv / (np.abs(gv) + eps)
+    dW = out["W"].reshape(w.C, w.d).astype(np.float64) - W0.reshape(w.C, w.d)
+    ref = exp - W0.reshape(w.C, w.d)
+    assert np.abs(dW - ref).max() < 1e-4 * np.abs(ref).max()
+    # untouched positions are bit-identical
+    mask = np.ones((w.C, w.d), bool)
+    for c in range(w.C):
+        mask[c, out["idx"][c]] = False
+    assert np.array_equal(out["W"].reshape(w.C, w.d)[mask], W0.reshape(w.C, w.d)[mask])
