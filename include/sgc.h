@@ -1,0 +1,174 @@
+/*
+ * sgc.h - C ABI of the MI355X (gfx950) hot path of Sparse Gradient Compression (SGC).
+ *
+ * One optimizer step of SGC on C independent gradient chunks of length d (MESGC form,
+ * paper Sec. 4.4, with one measurement matrix A shared by all chunks) is four calls:
+ *
+ *   sgc_sparsify_project   Alg. 2 line 1   idx,val = Sparsify_k(G);  p = A G~,  q = A G~^2
+ *   sgc_adam_compressed    Alg. 2 lines 2-5 moments in R^r and their bias-corrected copies
+ *   sgc_recover_omp        Alg. 2 line 6   x = OMP_A(mhat), z = OMP_A(vhat)  (eq. 9, App. B)
+ *   sgc_apply              eq. 11 + eq. 3  W <- W - lr * alpha * x / (sqrt(z) + eps)
+ *
+ * Conventions
+ *   - Plain C. Every array pointer is a DEVICE pointer owned by the caller unless the
+ *     parameter comment says "host". The library never allocates or frees device memory;
+ *     scratch space is a caller-provided workspace whose size is queried first.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream). Every call only
+ *     enqueues work on that stream and returns; results are ready after the stream is
+ *     synchronised. Calls on one stream execute in order.
+ *   - Arguments are validated on the host before anything is launched. On error nothing is
+ *     launched and a negative sgc_status is returned; the library never aborts or throws.
+ *   - Chunk-local positions (`idx`, `sel`) are int32 in [0, d).
+ *   - A is r x d with iid N(0, 1/r) entries (Sec. 4.3). It is handled transposed: "At" is
+ *     d x r row-major, row i of At = column i of A (r contiguous floats).
+ */
+#ifndef SGC_H
+#define SGC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t sgc_status;
+enum {
+    SGC_OK = 0,
+    SGC_ERR_NULL = -1,      /* a required pointer is NULL */
+    SGC_ERR_SHAPE = -2,     /* k == 0, k > d, k > r, n % d != 0, r % 4 != 0, size out of range */
+    SGC_ERR_DTYPE = -3,     /* unknown gradient type or matrix mode */
+    SGC_ERR_ALIGN = -4,     /* a pointer is not aligned to 16 bytes */
+    SGC_ERR_WORKSPACE = -5, /* workspace smaller than sgc_omp_workspace_bytes() */
+    SGC_ERR_STEP = -6,      /* step < 1, or a hyper-parameter outside its range */
+    SGC_ERR_DEVICE = -7     /* a HIP call failed (launch error, no device) */
+};
+
+/* gradient element type of sgc_sparsify_project */
+enum { SGC_GRAD_F32 = 0, SGC_GRAD_BF16 = 1 };
+
+/* how the measurement matrix is provided */
+enum {
+    SGC_MATRIX_STORED = 0, /* At resident in device memory */
+    SGC_MATRIX_PHILOX = 1  /* entries regenerated on the fly from `seed`; At is ignored */
+};
+
+/*
+ * Measurement matrix A (Sec. 4.3: iid zero-mean normal entries, standard deviation 1/sqrt(r);
+ * Sec. 4.4: the same A for every chunk).
+ *
+ * SGC_MATRIX_PHILOX defines A[j][i] (row j, column i) as follows: Philox4x32-10 with key
+ * (seed & 0xffffffff, seed >> 32) and counter (i, j/4, 0, 0) gives words w0..w3; (w0,w1) and
+ * (w2,w3) each feed one Box-Muller pair evaluated in float with fixed polynomials, giving rows
+ * 4*(j/4)+0,1 and +2,3; the result is scaled by (float)(1/sqrt((double)r)). The transform uses
+ * only exactly rounded operations, so sgc_matrix_fill reproduces the same bits everywhere.
+ *
+ * inv_colnorm[i] = 1/||A_:i||_2 (float), needed by sgc_recover_omp only; fill it with
+ * sgc_matrix_colnorms.
+ */
+typedef struct sgc_matrix {
+    int32_t mode; /* SGC_MATRIX_STORED | SGC_MATRIX_PHILOX */
+    int32_t d;    /* columns of A = chunk length */
+    int32_t r;    /* rows of A = measurements per chunk; multiple of 4 */
+    int32_t reserved;
+    uint64_t seed;            /* PHILOX mode */
+    const float *At;          /* device [d][r], STORED mode; 16-byte aligned */
+    const float *inv_colnorm; /* device [d]; may be NULL for sgc_sparsify_project */
+} sgc_matrix;
+
+/* AdamW-style hyper-parameters of Alg. 2 / eq. 11 (host values; no weight-decay term appears
+ * in the paper's update, none is applied). */
+typedef struct sgc_hyper {
+    double beta1; /* in [0,1) */
+    double beta2; /* in [0,1) */
+    double eps;   /* > 0 */
+    double lr;    /* eta of eq. 3 */
+    double alpha; /* scaling factor of eq. 11 */
+} sgc_hyper;
+
+/* static string for a status code */
+const char *sgc_status_string(sgc_status s);
+
+/*
+ * Materialise rows [row0, row0+rows) of At of the PHILOX matrix with the given seed and r into
+ * At_out (device, [rows][r] floats, 16-byte aligned). Used to obtain a stored copy of a
+ * generated matrix and to check the generator. Errors: NULL, SHAPE (r <= 0, r % 4, rows < 0).
+ */
+sgc_status sgc_matrix_fill(uint64_t seed, int32_t r, int64_t row0, int64_t rows, float *At_out,
+                           void *stream);
+
+/*
+ * inv_colnorm_out[i] = 1/||A_:i||_2 for i in [0, A->d) (device, [d] floats). A->inv_colnorm is
+ * not read. The norm is accumulated in double from the float entries (App. B selection rule
+ * divides the correlation by this norm). A zero column yields 0.
+ */
+sgc_status sgc_matrix_colnorms(const sgc_matrix *A /* host */, float *inv_colnorm_out,
+                               void *stream);
+
+/*
+ * Alg. 2 line 1 for n/d chunks: per chunk keep the k entries of largest magnitude
+ * (Sparsify_k, Sec. 4.2 / Def. 1) and project the kept values and their squares with A
+ * (eq. 5-6).
+ *   grad       [n] elements of grad_type (float, or bfloat16 as 16-bit patterns), chunk c is
+ *              grad[c*d .. c*d+d)
+ *   idx        out [n/d][k] chunk-local positions, ascending within a chunk
+ *   val        out [n/d][k] the kept (signed) values widened to float
+ *   p, q       out [n/d][r]; q may be NULL
+ * Magnitudes are ordered by the bit pattern with the sign cleared; among equal magnitudes
+ * the lower position is kept. Squares are formed in float; sums are accumulated in float in
+ * the order of ascending position.
+ * Errors: NULL, SHAPE (d<=0, k<=0, k>d, k>r, n%d, r%4, k>4096), DTYPE, ALIGN.
+ */
+sgc_status sgc_sparsify_project(const void *grad, int32_t grad_type, int64_t n, int32_t d,
+                                int32_t k, const sgc_matrix *A /* host */, int32_t *idx,
+                                float *val, float *p, float *q, void *stream);
+
+/*
+ * Alg. 2 lines 2-5 on `count` state elements (count = chunks * r):
+ *   m <- beta1 m + (1-beta1) p,  v <- beta2 v + (1-beta2) q          (in place, persistent)
+ *   mhat = m / (1 - beta1^step), vhat = v / (1 - beta2^step)         (outputs for the recovery)
+ * The stored state is the uncorrected moment, as in Adam; `step` counts from 1.
+ * Errors: NULL, SHAPE (count < 0), STEP (step < 1 or betas outside [0,1)), ALIGN.
+ */
+sgc_status sgc_adam_compressed(const float *p, const float *q, float *m, float *v, float *mhat,
+                               float *vhat, int64_t count, int32_t step,
+                               const sgc_hyper *h /* host */, void *stream);
+
+/* bytes of workspace sgc_recover_omp needs for N right-hand sides; 0 on invalid sizes */
+size_t sgc_omp_workspace_bytes(int32_t N, int32_t d, int32_t r, int32_t k);
+
+/*
+ * Batched orthogonal matching pursuit (eq. 9; selection rule and output of App. B): for each
+ * of the N right-hand sides y_n in R^r, k iterations of
+ *     lambda = argmax over unselected i of |<A_:i, res>| / ||A_:i||   (lowest i on exact ties)
+ *     x      = argmin || y_n - A_Lambda x ||_2 ,   res = y_n - A_Lambda x
+ *   y    [N][r]
+ *   sel  out [N][k] selected positions in selection order
+ *   x    out [N][k] least-squares values aligned with sel
+ *   ws   workspace of at least sgc_omp_workspace_bytes(N, d, r, k) bytes, 256-byte aligned;
+ *        contents are scratch
+ * All N correlations of one iteration are one dense contraction At * R on the float matrix
+ * cores; the near-maximal candidates are then re-scored in double, and the least-squares
+ * update (inverse-Cholesky form of App. B) and the residual are computed in double.
+ * Requires A->inv_colnorm. Errors: NULL, SHAPE (k<=0, k>d, k>r, r%4, N<=0), DTYPE, ALIGN,
+ * WORKSPACE.
+ */
+sgc_status sgc_recover_omp(const float *y, int32_t N, const sgc_matrix *A /* host */, int32_t k,
+                           int32_t *sel, float *x, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * eq. 11 and eq. 3 on the recovered supports of C chunks:
+ *   for each position i in sel_m[c]: z = value of i in (sel_v[c], x_v[c]) or 0 if absent,
+ *   W[c*d+i] -= lr * alpha * x_i / (sqrt(max(z,0)) + eps)
+ * Positions outside sel_m[c] are not touched.
+ *   W [C*d] in/out; sel_m,x_m / sel_v,x_v [C][k] as returned by sgc_recover_omp for mhat / vhat.
+ * Errors: NULL, SHAPE (k<=0, k>d, k>4096, C<0).
+ */
+sgc_status sgc_apply(float *W, int64_t C, int32_t d, int32_t k, const int32_t *sel_m,
+                     const float *x_m, const int32_t *sel_v, const float *x_v,
+                     const sgc_hyper *h /* host */, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SGC_H */

@@ -1,0 +1,175 @@
+// C ABI of libsgc: host-side argument validation and kernel launches. Nothing here computes;
+// every step of the path runs in the kernels of the sibling files.
+#include <math.h>
+
+#include "sgc_internal.h"
+
+namespace sgc {
+
+MatrixView make_view(const sgc_matrix *A)
+{
+    MatrixView v{};
+    v.At = A->At;
+    v.inv_colnorm = A->inv_colnorm;
+    v.d = A->d;
+    v.r = A->r;
+    v.key0 = (uint32_t)(A->seed & 0xffffffffull);
+    v.key1 = (uint32_t)(A->seed >> 32);
+    v.scale = (float)(1.0 / sqrt((double)A->r));
+    v.generated = A->mode == SGC_MATRIX_PHILOX ? 1 : 0;
+    return v;
+}
+
+static bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+static sgc_status check_matrix(const sgc_matrix *A, bool need_norms)
+{
+    if (!A)
+        return SGC_ERR_NULL;
+    if (A->mode != SGC_MATRIX_STORED && A->mode != SGC_MATRIX_PHILOX)
+        return SGC_ERR_DTYPE;
+    if (A->d <= 0 || A->r <= 0 || (A->r & 3) || A->d > (1 << 30))
+        return SGC_ERR_SHAPE;
+    if (A->mode == SGC_MATRIX_STORED) {
+        if (!A->At)
+            return SGC_ERR_NULL;
+        if (!aligned16(A->At))
+            return SGC_ERR_ALIGN;
+    }
+    if (need_norms && !A->inv_colnorm)
+        return SGC_ERR_NULL;
+    return SGC_OK;
+}
+
+static sgc_status from_hip(hipError_t e) { return e == hipSuccess ? SGC_OK : SGC_ERR_DEVICE; }
+
+} // namespace sgc
+
+using namespace sgc;
+
+extern "C" {
+
+const char *sgc_status_string(sgc_status s)
+{
+    switch (s) {
+    case SGC_OK: return "ok";
+    case SGC_ERR_NULL: return "required pointer is NULL";
+    case SGC_ERR_SHAPE: return "invalid size";
+    case SGC_ERR_DTYPE: return "unknown element type or matrix mode";
+    case SGC_ERR_ALIGN: return "pointer not aligned";
+    case SGC_ERR_WORKSPACE: return "workspace too small";
+    case SGC_ERR_STEP: return "invalid step or hyper-parameter";
+    case SGC_ERR_DEVICE: return "HIP error";
+    default: return "unknown status";
+    }
+}
+
+sgc_status sgc_matrix_fill(uint64_t seed, int32_t r, int64_t row0, int64_t rows, float *At_out, void *stream)
+{
+    if (!At_out)
+        return SGC_ERR_NULL;
+    if (r <= 0 || (r & 3) || rows < 0 || row0 < 0 || row0 + rows > (1ll << 30))
+        return SGC_ERR_SHAPE;
+    if (!aligned16(At_out))
+        return SGC_ERR_ALIGN;
+    const float scale = (float)(1.0 / sqrt((double)r));
+    return from_hip(launch_matrix_fill((uint32_t)(seed & 0xffffffffull), (uint32_t)(seed >> 32), scale, r, row0,
+                                       rows, At_out, (hipStream_t)stream));
+}
+
+sgc_status sgc_matrix_colnorms(const sgc_matrix *A, float *inv_colnorm_out, void *stream)
+{
+    sgc_status st = check_matrix(A, false);
+    if (st != SGC_OK)
+        return st;
+    if (!inv_colnorm_out)
+        return SGC_ERR_NULL;
+    return from_hip(launch_colnorms(make_view(A), inv_colnorm_out, (hipStream_t)stream));
+}
+
+sgc_status sgc_sparsify_project(const void *grad, int32_t grad_type, int64_t n, int32_t d, int32_t k,
+                                const sgc_matrix *A, int32_t *idx, float *val, float *p, float *q, void *stream)
+{
+    if (!grad || !idx || !val || !p)
+        return SGC_ERR_NULL;
+    sgc_status st = check_matrix(A, false);
+    if (st != SGC_OK)
+        return st;
+    if (grad_type != SGC_GRAD_F32 && grad_type != SGC_GRAD_BF16)
+        return SGC_ERR_DTYPE;
+    if (d <= 0 || d != A->d || k <= 0 || k > d || k > A->r || k > 4096 || n < 0 || n % d != 0)
+        return SGC_ERR_SHAPE;
+    if (!aligned16(grad) || !aligned16(p) || (q && !aligned16(q)))
+        return SGC_ERR_ALIGN;
+    const int64_t C = n / d;
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = launch_topk(grad, grad_type, C, d, k, idx, val, s);
+    if (e != hipSuccess)
+        return SGC_ERR_DEVICE;
+    return from_hip(launch_project(idx, val, C, k, make_view(A), p, q, s));
+}
+
+sgc_status sgc_adam_compressed(const float *p, const float *q, float *m, float *v, float *mhat, float *vhat,
+                               int64_t count, int32_t step, const sgc_hyper *h, void *stream)
+{
+    if (!p || !q || !m || !v || !mhat || !vhat || !h)
+        return SGC_ERR_NULL;
+    if (count < 0)
+        return SGC_ERR_SHAPE;
+    if (step < 1 || !(h->beta1 >= 0.0 && h->beta1 < 1.0) || !(h->beta2 >= 0.0 && h->beta2 < 1.0))
+        return SGC_ERR_STEP;
+    if (!aligned16(p) || !aligned16(q) || !aligned16(m) || !aligned16(v) || !aligned16(mhat) || !aligned16(vhat))
+        return SGC_ERR_ALIGN;
+    const double c1 = 1.0 - pow(h->beta1, (double)step), c2 = 1.0 - pow(h->beta2, (double)step);
+    return from_hip(launch_adam(p, q, m, v, mhat, vhat, count, (float)h->beta1, (float)(1.0 - h->beta1),
+                                (float)h->beta2, (float)(1.0 - h->beta2), (float)(1.0 / c1), (float)(1.0 / c2),
+                                (hipStream_t)stream));
+}
+
+static bool omp_sizes_ok(int32_t N, int32_t d, int32_t r, int32_t k)
+{
+    if (N <= 0 || d <= 0 || r <= 0 || (r & 3) || k <= 0 || k > d || k > r || d > (1 << 30))
+        return false;
+    // LDS of the update kernel: one column (r floats) and two k-vectors of doubles
+    if ((size_t)r * 4 + 16 + (size_t)k * 16 > 60 * 1024)
+        return false;
+    return true;
+}
+
+size_t sgc_omp_workspace_bytes(int32_t N, int32_t d, int32_t r, int32_t k)
+{
+    if (!omp_sizes_ok(N, d, r, k))
+        return 0;
+    return carve_workspace(nullptr, N, d, r, k).bytes;
+}
+
+sgc_status sgc_recover_omp(const float *y, int32_t N, const sgc_matrix *A, int32_t k, int32_t *sel, float *x,
+                           void *ws, size_t ws_bytes, void *stream)
+{
+    if (!y || !sel || !x || !ws)
+        return SGC_ERR_NULL;
+    sgc_status st = check_matrix(A, true);
+    if (st != SGC_OK)
+        return st;
+    if (!omp_sizes_ok(N, A->d, A->r, k))
+        return SGC_ERR_SHAPE;
+    if (!aligned16(y) || ((uintptr_t)ws & 255u))
+        return SGC_ERR_ALIGN;
+    const OmpWorkspace w = carve_workspace(ws, N, A->d, A->r, k);
+    if (ws_bytes < w.bytes)
+        return SGC_ERR_WORKSPACE;
+    return from_hip(launch_omp(y, N, make_view(A), k, sel, x, w, (hipStream_t)stream));
+}
+
+sgc_status sgc_apply(float *W, int64_t C, int32_t d, int32_t k, const int32_t *sel_m, const float *x_m,
+                     const int32_t *sel_v, const float *x_v, const sgc_hyper *h, void *stream)
+{
+    if (!W || !sel_m || !x_m || !sel_v || !x_v || !h)
+        return SGC_ERR_NULL;
+    if (C < 0 || d <= 0 || k <= 0 || k > d || k > 4096)
+        return SGC_ERR_SHAPE;
+    return from_hip(launch_apply(W, C, d, k, sel_m, x_m, sel_v, x_v, (float)h->alpha, (float)h->eps, (float)h->lr,
+                                 (hipStream_t)stream));
+}
+
+} // extern "C"

@@ -1,0 +1,80 @@
+// Internal declarations shared by the HIP translation units of libsgc (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/sgc.h"
+
+namespace sgc {
+
+// Device view of the measurement matrix.
+struct MatrixView {
+    const float *At;          // [d][r] or nullptr in generated mode
+    const float *inv_colnorm; // [d] or nullptr
+    int32_t d, r;
+    uint32_t key0, key1; // Philox key
+    float scale;         // (float)(1/sqrt((double)r))
+    int32_t generated;   // 0 stored, 1 Philox
+};
+
+MatrixView make_view(const sgc_matrix *A);
+
+// ---- correlation GEMM tiling (see omp_corr.hip) ----
+constexpr int CORR_BM = 128; // rows of At (positions i) per workgroup
+constexpr int CORR_BN = 128; // right-hand sides per workgroup
+
+inline int corr_tiles_m(int d) { return (d + CORR_BM - 1) / CORR_BM; }
+
+// Workspace layout of sgc_recover_omp (all offsets 256-byte aligned).
+struct OmpWorkspace {
+    double *res64;     // [N][r] residual
+    double *F;         // [N][k][k] inverse Cholesky factor, column t at F[(n*k+t)*k .. +t]
+    double *avec;      // [N][k] coefficients in the orthonormal basis
+    double *xs;        // [N][k] current least-squares solution
+    float *res32;      // [N][r] residual rounded to float (operand of the contraction)
+    float *cols;       // [N][k][r] selected columns of A
+    uint64_t *partial; // [N][tiles_m][2] best and second-best packed (score, position) per tile
+    uint32_t *bitmap;  // [N][words] selected positions
+    int32_t *cand;     // [N][2*tiles_m] candidate positions for re-scoring
+    int32_t words;     // bitmap words per right-hand side
+    int32_t tiles_m;
+    size_t bytes;
+};
+OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_t k);
+
+// launchers (each returns hipGetLastError() of its launches)
+hipError_t launch_topk(const void *grad, int grad_type, int64_t C, int32_t d, int32_t k, int32_t *idx,
+                       float *val, hipStream_t s);
+hipError_t launch_project(const int32_t *idx, const float *val, int64_t C, int32_t k, const MatrixView &A,
+                          float *p, float *q, hipStream_t s);
+hipError_t launch_adam(const float *p, const float *q, float *m, float *v, float *mhat, float *vhat,
+                       int64_t count, float b1, float omb1, float b2, float omb2, float ibc1, float ibc2,
+                       hipStream_t s);
+hipError_t launch_matrix_fill(uint32_t key0, uint32_t key1, float scale, int32_t r, int64_t row0,
+                              int64_t rows, float *out, hipStream_t s);
+hipError_t launch_colnorms(const MatrixView &A, float *out, hipStream_t s);
+hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k, int32_t *sel, float *x,
+                      const OmpWorkspace &ws, hipStream_t s);
+hipError_t launch_apply(float *W, int64_t C, int32_t d, int32_t k, const int32_t *sel_m, const float *x_m,
+                        const int32_t *sel_v, const float *x_v, float alpha, float eps, float lr,
+                        hipStream_t s);
+
+// ---- small device helpers ----
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1)
+        v += __shfl_down(v, off, 64);
+    return v; // valid in lane 0
+}
+
+__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int mask)
+{
+    uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+    lo = __shfl_xor(lo, mask, 64);
+    hi = __shfl_xor(hi, mask, 64);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+} // namespace sgc

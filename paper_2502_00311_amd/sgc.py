@@ -1,0 +1,169 @@
+"""Thin binding over the C ABI of libsgc.so (include/sgc.h): argument marshalling only.
+
+Function names and argument order mirror the C entry points. Tensors are torch tensors on the
+GPU (torch is used for device memory and streams, nothing else); every step of the path runs in
+the HIP kernels. There is no fallback: a missing library or a failing call raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "csrc", "libsgc.so")
+
+OK = 0
+ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_ALIGN, ERR_WORKSPACE, ERR_STEP, ERR_DEVICE = -1, -2, -3, -4, -5, -6, -7
+GRAD_F32, GRAD_BF16 = 0, 1
+MATRIX_STORED, MATRIX_PHILOX = 0, 1
+
+EXPORTS = [
+    "sgc_status_string", "sgc_matrix_fill", "sgc_matrix_colnorms", "sgc_sparsify_project",
+    "sgc_adam_compressed", "sgc_omp_workspace_bytes", "sgc_recover_omp", "sgc_apply",
+]
+
+
+class sgc_matrix(ctypes.Structure):
+    _fields_ = [
+        ("mode", ctypes.c_int32), ("d", ctypes.c_int32), ("r", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("seed", ctypes.c_uint64), ("At", ctypes.c_void_p), ("inv_colnorm", ctypes.c_void_p),
+    ]
+
+
+class sgc_hyper(ctypes.Structure):
+    _fields_ = [("beta1", ctypes.c_double), ("beta2", ctypes.c_double), ("eps", ctypes.c_double),
+                ("lr", ctypes.c_double), ("alpha", ctypes.c_double)]
+
+
+class SgcError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s failed: %d (%s)" % (where, status, status_string(status)))
+
+
+_lib = None
+
+
+def lib():
+    """Load libsgc.so (built in-tree by csrc/build.py). Raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libsgc.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, u64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64, ctypes.c_size_t
+        L.sgc_status_string.restype = ctypes.c_char_p
+        L.sgc_status_string.argtypes = [i32]
+        L.sgc_matrix_fill.restype = i32
+        L.sgc_matrix_fill.argtypes = [u64, i32, i64, i64, vp, vp]
+        L.sgc_matrix_colnorms.restype = i32
+        L.sgc_matrix_colnorms.argtypes = [ctypes.POINTER(sgc_matrix), vp, vp]
+        L.sgc_sparsify_project.restype = i32
+        L.sgc_sparsify_project.argtypes = [vp, i32, i64, i32, i32, ctypes.POINTER(sgc_matrix), vp, vp, vp, vp, vp]
+        L.sgc_adam_compressed.restype = i32
+        L.sgc_adam_compressed.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, ctypes.POINTER(sgc_hyper), vp]
+        L.sgc_omp_workspace_bytes.restype = sz
+        L.sgc_omp_workspace_bytes.argtypes = [i32, i32, i32, i32]
+        L.sgc_recover_omp.restype = i32
+        L.sgc_recover_omp.argtypes = [vp, i32, ctypes.POINTER(sgc_matrix), i32, vp, vp, vp, sz, vp]
+        L.sgc_apply.restype = i32
+        L.sgc_apply.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, ctypes.POINTER(sgc_hyper), vp]
+        _lib = L
+    return _lib
+
+
+def status_string(status):
+    return lib().sgc_status_string(int(status)).decode()
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _check(status, where):
+    if status != OK:
+        raise SgcError(status, where)
+
+
+def hyper(beta1=0.9, beta2=0.999, eps=1e-8, lr=1e-3, alpha=1.0):
+    return sgc_hyper(beta1, beta2, eps, lr, alpha)
+
+
+class Matrix:
+    """Host-side descriptor of the measurement matrix plus the device buffers it points to."""
+
+    def __init__(self, d, r, At=None, seed=0, inv_colnorm=None):
+        self.d, self.r, self.seed = int(d), int(r), int(seed)
+        self.At = At                    # torch [d, r] float32 on the GPU, or None (generated)
+        self.inv_colnorm = inv_colnorm  # torch [d] float32 on the GPU, or None
+        self.mode = MATRIX_STORED if At is not None else MATRIX_PHILOX
+
+    def c(self):
+        return sgc_matrix(self.mode, self.d, self.r, 0, self.seed,
+                          self.At.data_ptr() if self.At is not None else None,
+                          self.inv_colnorm.data_ptr() if self.inv_colnorm is not None else None)
+
+
+def sgc_matrix_fill(seed, r, row0, rows, At_out, stream=None):
+    _check(lib().sgc_matrix_fill(seed, r, row0, rows, _ptr(At_out), _stream(stream)), "sgc_matrix_fill")
+
+
+def sgc_matrix_colnorms(A, inv_colnorm_out, stream=None):
+    _check(lib().sgc_matrix_colnorms(ctypes.byref(A.c()), _ptr(inv_colnorm_out), _stream(stream)), "sgc_matrix_colnorms")
+
+
+def sgc_sparsify_project(grad, n, d, k, A, idx, val, p, q, stream=None):
+    gt = GRAD_BF16 if grad.dtype in (torch.bfloat16, torch.int16, torch.uint16) else GRAD_F32
+    _check(lib().sgc_sparsify_project(_ptr(grad), gt, n, d, k, ctypes.byref(A.c()), _ptr(idx), _ptr(val), _ptr(p), _ptr(q), _stream(stream)), "sgc_sparsify_project")
+
+
+def sgc_adam_compressed(p, q, m, v, mhat, vhat, count, step, h, stream=None):
+    _check(lib().sgc_adam_compressed(_ptr(p), _ptr(q), _ptr(m), _ptr(v), _ptr(mhat), _ptr(vhat), count, step, ctypes.byref(h), _stream(stream)), "sgc_adam_compressed")
+
+
+def sgc_omp_workspace_bytes(N, d, r, k):
+    return int(lib().sgc_omp_workspace_bytes(N, d, r, k))
+
+
+def sgc_recover_omp(y, N, A, k, sel, x, ws, stream=None):
+    _check(lib().sgc_recover_omp(_ptr(y), N, ctypes.byref(A.c()), k, _ptr(sel), _ptr(x), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_recover_omp")
+
+
+def sgc_apply(W, C, d, k, sel_m, x_m, sel_v, x_v, h, stream=None):
+    _check(lib().sgc_apply(_ptr(W), C, d, k, _ptr(sel_m), _ptr(x_m), _ptr(sel_v), _ptr(x_v), ctypes.byref(h), _stream(stream)), "sgc_apply")
+
+
+class StepBuffers:
+    """Device buffers of one SGC step on C chunks (allocation only; no arithmetic)."""
+
+    def __init__(self, C, d, r, k, device="cuda"):
+        f32, i32 = torch.float32, torch.int32
+        self.C, self.d, self.r, self.k = C, d, r, k
+        self.idx = torch.empty((C, k), dtype=i32, device=device)
+        self.val = torch.empty((C, k), dtype=f32, device=device)
+        self.p = torch.empty((C, r), dtype=f32, device=device)
+        self.q = torch.empty((C, r), dtype=f32, device=device)
+        self.m = torch.zeros((C, r), dtype=f32, device=device)
+        self.v = torch.zeros((C, r), dtype=f32, device=device)
+        self.hat = torch.empty((2 * C, r), dtype=f32, device=device)  # [mhat; vhat]
+        self.sel = torch.empty((2 * C, k), dtype=i32, device=device)
+        self.x = torch.empty((2 * C, k), dtype=f32, device=device)
+        nbytes = sgc_omp_workspace_bytes(2 * C, d, r, k)
+        if nbytes == 0:
+            raise SgcError(ERR_SHAPE, "sgc_omp_workspace_bytes")
+        self.ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def step(grad, W, buf, A, t, h, stream=None):
+    """The four calls of one step, in order (Alg. 2 then the weight update)."""
+    C, d, r, k = buf.C, buf.d, buf.r, buf.k
+    sgc_sparsify_project(grad, C * d, d, k, A, buf.idx, buf.val, buf.p, buf.q, stream)
+    sgc_adam_compressed(buf.p, buf.q, buf.m, buf.v, buf.hat[:C], buf.hat[C:], C * r, t, h, stream)
+    sgc_recover_omp(buf.hat, 2 * C, A, k, buf.sel, buf.x, buf.ws, stream)
+    sgc_apply(W, C, d, k, buf.sel[:C], buf.x[:C], buf.sel[C:], buf.x[C:], h, stream)

@@ -1,0 +1,131 @@
+"""Host-side checks of the C ABI: the library loads, exports every function the header declares,
+and rejects bad arguments before anything is launched (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2502_00311_amd import sgc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sgc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sgc_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function():
+    L = sgc.lib()
+    names = declared_functions()
+    assert set(names) == set(sgc.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_status_strings():
+    assert sgc.status_string(0) == "ok"
+    for s in range(-7, 0):
+        assert sgc.status_string(s) not in ("ok", "unknown status")
+    assert sgc.status_string(-99) == "unknown status"
+
+
+FAKE = ctypes.c_void_p(0x1000)      # aligned, never dereferenced: validation fails first
+ODD = ctypes.c_void_p(0x1004)
+
+
+def mat(mode=0, d=64, r=16, At=0x1000, inv=0x1000, seed=1):
+    return sgc.sgc_matrix(mode, d, r, 0, seed, At, inv)
+
+
+def test_sparsify_project_rejects_bad_arguments():
+    L = sgc.lib()
+    f = L.sgc_sparsify_project
+    A = mat()
+    ok_args = dict(grad=FAKE, gt=0, n=128, d=64, k=4, A=ctypes.byref(A), idx=FAKE, val=FAKE, p=FAKE, q=FAKE)
+
+    def call(**kw):
+        a = dict(ok_args, **kw)
+        return f(a["grad"], a["gt"], a["n"], a["d"], a["k"], a["A"], a["idx"], a["val"], a["p"], a["q"], None)
+
+    assert call(grad=None) == sgc.ERR_NULL
+    assert call(idx=None) == sgc.ERR_NULL
+    assert call(p=None) == sgc.ERR_NULL
+    assert call(A=None) == sgc.ERR_NULL
+    assert call(gt=7) == sgc.ERR_DTYPE
+    assert call(k=0) == sgc.ERR_SHAPE
+    assert call(k=65) == sgc.ERR_SHAPE          # k > d
+    assert call(k=17) == sgc.ERR_SHAPE          # k > r
+    assert call(n=100) == sgc.ERR_SHAPE         # n % d
+    assert call(d=32) == sgc.ERR_SHAPE          # d != A.d
+    assert call(grad=ODD) == sgc.ERR_ALIGN
+    assert call(p=ODD) == sgc.ERR_ALIGN
+    bad = mat(r=18)
+    assert call(A=ctypes.byref(bad)) == sgc.ERR_SHAPE
+    bad = mat(mode=5)
+    assert call(A=ctypes.byref(bad)) == sgc.ERR_DTYPE
+    bad = mat(At=None)
+    assert call(A=ctypes.byref(bad)) == sgc.ERR_NULL
+    bad = mat(At=0x1004)
+    assert call(A=ctypes.byref(bad)) == sgc.ERR_ALIGN
+
+
+def test_adam_rejects_bad_arguments():
+    L = sgc.lib()
+    h = sgc.hyper()
+
+    def call(p=FAKE, q=FAKE, m=FAKE, v=FAKE, mh=FAKE, vh=FAKE, count=16, step=1, hh=h):
+        return L.sgc_adam_compressed(p, q, m, v, mh, vh, count, step, ctypes.byref(hh) if hh is not None else None, None)
+
+    assert call(m=None) == sgc.ERR_NULL
+    assert call(hh=None) == sgc.ERR_NULL
+    assert call(count=-1) == sgc.ERR_SHAPE
+    assert call(step=0) == sgc.ERR_STEP
+    assert call(hh=sgc.hyper(beta1=1.0)) == sgc.ERR_STEP
+    assert call(hh=sgc.hyper(beta2=-0.1)) == sgc.ERR_STEP
+    assert call(v=ODD) == sgc.ERR_ALIGN
+
+
+def test_omp_rejects_bad_arguments_and_sizes_workspace():
+    L = sgc.lib()
+    A = mat(d=4096, r=256)
+    need = sgc.sgc_omp_workspace_bytes(2, 4096, 256, 32)
+    assert need > 2 * 32 * 256 * 4
+    assert sgc.sgc_omp_workspace_bytes(0, 4096, 256, 32) == 0
+    assert sgc.sgc_omp_workspace_bytes(2, 4096, 250, 32) == 0     # r % 4
+    assert sgc.sgc_omp_workspace_bytes(2, 4096, 256, 300) == 0    # k > r
+    # workspace grows with every dimension
+    assert sgc.sgc_omp_workspace_bytes(4, 4096, 256, 32) > need
+    assert sgc.sgc_omp_workspace_bytes(2, 8192, 256, 32) > need
+    assert sgc.sgc_omp_workspace_bytes(2, 4096, 512, 32) > need
+    assert sgc.sgc_omp_workspace_bytes(2, 4096, 256, 64) > need
+
+    def call(y=FAKE, N=2, AA=A, k=32, sel=FAKE, x=FAKE, ws=FAKE, nbytes=need):
+        return L.sgc_recover_omp(y, N, ctypes.byref(AA) if AA is not None else None, k, sel, x, ws, nbytes, None)
+
+    assert call(y=None) == sgc.ERR_NULL
+    assert call(ws=None) == sgc.ERR_NULL
+    assert call(AA=None) == sgc.ERR_NULL
+    assert call(AA=mat(d=4096, r=256, inv=None)) == sgc.ERR_NULL
+    assert call(N=0) == sgc.ERR_SHAPE
+    assert call(k=0) == sgc.ERR_SHAPE
+    assert call(k=257) == sgc.ERR_SHAPE
+    assert call(nbytes=need - 1) == sgc.ERR_WORKSPACE
+    assert call(ws=ctypes.c_void_p(0x1010)) == sgc.ERR_ALIGN
+
+
+def test_apply_and_matrix_helpers_reject_bad_arguments():
+    L = sgc.lib()
+    h = sgc.hyper()
+    assert L.sgc_apply(None, 1, 64, 4, FAKE, FAKE, FAKE, FAKE, ctypes.byref(h), None) == sgc.ERR_NULL
+    assert L.sgc_apply(FAKE, 1, 64, 0, FAKE, FAKE, FAKE, FAKE, ctypes.byref(h), None) == sgc.ERR_SHAPE
+    assert L.sgc_apply(FAKE, 1, 64, 65, FAKE, FAKE, FAKE, FAKE, ctypes.byref(h), None) == sgc.ERR_SHAPE
+    assert L.sgc_apply(FAKE, -1, 64, 4, FAKE, FAKE, FAKE, FAKE, ctypes.byref(h), None) == sgc.ERR_SHAPE
+    assert L.sgc_matrix_fill(1, 16, 0, 4, None, None) == sgc.ERR_NULL
+    assert L.sgc_matrix_fill(1, 18, 0, 4, FAKE, None) == sgc.ERR_SHAPE
+    assert L.sgc_matrix_fill(1, 16, 0, -4, FAKE, None) == sgc.ERR_SHAPE
+    A = mat()
+    assert L.sgc_matrix_colnorms(ctypes.byref(A), None, None) == sgc.ERR_NULL
+    assert L.sgc_matrix_colnorms(None, FAKE, None) == sgc.ERR_NULL
