@@ -1,0 +1,180 @@
+#!/usr/bin/env python3
+"""Benchmark of the SGC per-step hot path on one MI355X.
+
+A step = one pass of the whole path (sparsify+project, compressed Adam, batched OMP on mhat and
+vhat, apply) over one batch of synthetic gradient chunks, through the C ABI of libsgc.so. The
+default workload is the second configuration of the benchmark definition: 64 chunks x d=65536,
+r=2048, k=256, float gradients, one stored Gaussian A, consecutive steps with persistent moments.
+Inputs (A, all gradients of the run) are resident in HBM before the timed region.
+
+Prints ONE JSON line: whole-job throughput, the roofline of the dominant kernel (the OMP
+correlation contraction, float MFMA) from HIP events recorded around every launch, and the CPU
+oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense float matrix peak
+# HBM bytes per launch of the correlation kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (profiles/), keyed by workload name; None until measured.
+MEASURED_TRAFFIC = {}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", type=int, default=2, help="configuration index 1..5 (default 2)")
+    ap.add_argument("--chunks", type=int, default=0, help="override the number of chunks (0 = as defined)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (chunks are independent and would shard by "
+              "chunk range, but no multi-GPU path is built); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2502_00311_amd import sgc, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    sgc.lib()  # fails loudly if the HIP library is not built
+    dev = "cuda:0"
+    w = synth.CONFIGS[args.workload]
+    if args.chunks:
+        w = synth.shrink(w, C=args.chunks)
+    C, d, r, k = w.C, w.d, w.r, w.k
+    K, Wm = args.steps, args.warmup
+
+    # ---- inputs, resident before timing ----
+    At_host = None
+    if w.matrix == "stored":
+        At_host = synth.gaussian_matrix(w.a_seed, d, r)
+        A = sgc.Matrix(d, r, At=torch.from_numpy(At_host).to(dev))
+    else:
+        A = sgc.Matrix(d, r, At=None, seed=w.a_seed)
+    A.inv_colnorm = torch.empty(d, dtype=torch.float32, device=dev)
+    sgc.sgc_matrix_colnorms(A, A.inv_colnorm)
+    nsteps = max(K, Wm, 1)
+    grads = []
+    for t in range(1, nsteps + 1):
+        g = synth.gradients(w, t)
+        grads.append(torch.from_numpy(g.view(np.int16) if w.grad == "bf16" else g).to(dev))
+    W0 = torch.from_numpy(synth.weights(w)).to(dev)
+    Wt = W0.clone()
+    buf = sgc.StepBuffers(C, d, r, k, device=dev)
+    h = sgc.hyper()
+
+    def reset():
+        buf.m.zero_()
+        buf.v.zero_()
+        Wt.copy_(W0)
+
+    def run(n):
+        for t in range(1, n + 1):
+            sgc.step(grads[t - 1], Wt, buf, A, t, h)
+
+    run(Wm)
+    torch.cuda.synchronize()
+    reset()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(K)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    value = C * d / (ms_per_step * 1e-3)
+
+    # ---- same steps again with HIP events around every kernel launch ----
+    reset()
+    torch.cuda.synchronize()
+    sgc.sgc_profile_enable(True)
+    t2 = time.perf_counter()
+    run(K)
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
+    prof = sgc.sgc_profile_read()
+    sgc.sgc_profile_enable(False)
+    corr_ms, corr_n = prof["omp_corr"]
+    flops_per_launch = 2.0 * d * r * (2 * C)
+    avg_ms = corr_ms / max(corr_n, 1)
+    achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12
+    roofline = {
+        "bound": "mfma", "kernel": "omp corr_kernel (At*R, float 32x32x2 MFMA, fused argmax epilogue)",
+        "achieved": round(achieved, 3), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+        "frac": round(achieved / MFMA_F32_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC.get(w.name),
+        "flops_per_launch": flops_per_launch, "avg_launch_ms": round(avg_ms, 5), "launches": corr_n,
+    }
+    kernels = {n: {"ms_per_step": round(ms / K, 4), "launches_per_step": cnt / K} for n, (ms, cnt) in prof.items()}
+    # HBM-bound companions (algorithmic bytes / event time)
+    bytes_adam = 32.0 * C * r
+    bytes_topk = (2.0 if w.grad == "bf16" else 4.0) * C * d + 8.0 * C * k
+    for name, nbytes in (("adam", bytes_adam), ("topk", bytes_topk)):
+        ms, cnt = prof[name]
+        if cnt:
+            kernels[name]["algorithmic_GBps"] = round(nbytes / (ms / cnt * 1e-3) / 1e9, 2)
+
+    out = {
+        "metric": "gradient elements/s per full SGC step (1 GPU)", "value": round(value, 1), "unit": "elements/s",
+        "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "chunks": C, "d": d, "r": r, "k": k, "grad": w.grad, "matrix": w.matrix,
+                   "rhs_per_omp_call": 2 * C},
+        "roofline": roofline,
+        "ms_per_step_with_events": round((t3 - t2) * 1e3 / K, 3),
+        "kernels": kernels,
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, At_host)
+    print(json.dumps(out))
+    return 0
+
+
+def cpu_baseline(w, At_host):
+    """The CPU oracle (single thread, as it stands) on chunk 0 of step 1 of the same workload."""
+    import numpy as np
+    from oracle import oracle as orc
+    from paper_2502_00311_amd import synth
+
+    if At_host is None:
+        At_host = orc.philox_matrix(w.a_seed, w.d, w.r)
+    g = synth.gradients(w, 1, chunks=[0])
+    norm = orc.colnorms(At_host)
+    t0 = time.perf_counter()
+    idx, val = orc.topk(g, w.k)
+    p, q = orc.project(idx, val, At_host)
+    z = np.zeros((1, w.r), np.float32)
+    m, v, mh, vh = orc.adam(p, q, z, z, 1)
+    t1 = time.perf_counter()
+    # OMP cost does not depend on the data: time OMP(mhat) with all k iterations, count OMP(vhat) the same.
+    # Configurations whose single right-hand side would take minutes are timed on the first iterations
+    # (every iteration scans all d columns, which dominates) and scaled to k.
+    per_iter = 2.0 * w.d * w.r / 2.0e9
+    iters = w.k if per_iter * w.k <= 45 else max(8, int(30 / per_iter))
+    o = orc.omp(mh[0], At_host, iters, norm=norm)
+    t2 = time.perf_counter()
+    Wc = synth.weights(w, chunks=[0])
+    orc.apply(Wc, w.d, o["sel"][None], o["x"][None], o["sel"][None], np.abs(o["x"])[None])
+    t3 = time.perf_counter()
+    t_chunk = (t1 - t0) + 2.0 * (t2 - t1) * (w.k / iters) + (t3 - t2)
+    return {
+        "value": round(w.d / t_chunk, 2), "unit": "elements/s", "cores": 1, "kind": "oracle",
+        "sample": "chunk 0 of step 1 (1 of %d chunks): top-k, projection, Adam, OMP(mhat) timed for %d of %d "
+                  "iterations and scaled, OMP(vhat) counted at the same cost, apply; %.1f s of CPU work measured"
+                  % (w.C, iters, w.k, t3 - t0),
+        "host_cores": os.cpu_count(),
+    }
+
+
+if __name__ == "__main__":
+    sys.exit(main())

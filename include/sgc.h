@@ -168,6 +168,24 @@ sgc_status sgc_apply(float *W, int64_t C, int32_t d, int32_t k, const int32_t *s
                      const float *x_m, const int32_t *sel_v, const float *x_v,
                      const sgc_hyper *h /* host */, void *stream);
 
+/*
+ * Instrumentation (not a step of the method): per-kernel timing with HIP events recorded on the
+ * caller's stream around every kernel the library launches while enabled.
+ *   sgc_profile_enable(1) starts collecting (and discards what was collected), (0) stops.
+ *   sgc_profile_read waits for the recorded events, then fills `out` (host) with the summed
+ *   duration in milliseconds and the launch count per kernel class, and clears the collection.
+ * Kernel classes: 0 top-k, 1 projection, 2 Adam, 3 OMP correlation contraction, 4 OMP
+ * select+update, 5 apply, 6 other (init, matrix helpers).
+ * Not thread-safe; meant for a single measuring thread. Errors: NULL, DEVICE.
+ */
+enum { SGC_PROFILE_CLASSES = 7 };
+typedef struct sgc_profile {
+    double ms[SGC_PROFILE_CLASSES];
+    int64_t launches[SGC_PROFILE_CLASSES];
+} sgc_profile;
+sgc_status sgc_profile_enable(int32_t on);
+sgc_status sgc_profile_read(sgc_profile *out /* host */);
+
 #ifdef __cplusplus
 }
 #endif

@@ -63,6 +63,7 @@ hipError_t launch_adam(const float *p, const float *q, float *m, float *v, float
         blocks = 256 * 16;
     if (blocks < 1)
         blocks = 1;
+    ProfileScope prof(KC_ADAM, s);
     adam_kernel<<<dim3((unsigned)blocks), 256, 0, s>>>(p, q, m, v, mhat, vhat, count,
                                                        AdamCoef{b1, omb1, b2, omb2, ibc1, ibc2});
     return hipGetLastError();

@@ -45,6 +45,7 @@ hipError_t launch_apply(float *W, int64_t C, int32_t d, int32_t k, const int32_t
 {
     if (C == 0)
         return hipSuccess;
+    ProfileScope prof(KC_APPLY, s);
     apply_kernel<<<dim3((unsigned)C), APPLY_THREADS, 0, s>>>(W, d, k, sel_m, x_m, sel_v, x_v, alpha, eps, lr);
     return hipGetLastError();
 }

@@ -50,6 +50,7 @@ hipError_t launch_matrix_fill(uint32_t key0, uint32_t key1, float scale, int32_t
     int64_t blocks = (total + 255) / 256;
     if (blocks > 256 * 32)
         blocks = 256 * 32;
+    ProfileScope prof(KC_OTHER, s);
     matrix_fill_kernel<<<dim3((unsigned)blocks), 256, 0, s>>>(key0, key1, scale, r, row0, rows, out);
     return hipGetLastError();
 }
@@ -57,6 +58,7 @@ hipError_t launch_matrix_fill(uint32_t key0, uint32_t key1, float scale, int32_t
 hipError_t launch_colnorms(const MatrixView &A, float *out, hipStream_t s)
 {
     const unsigned blocks = (unsigned)((A.d + 3) / 4);
+    ProfileScope prof(KC_OTHER, s);
     if (A.generated)
         colnorm_kernel<true><<<dim3(blocks), 256, 0, s>>>(A, out);
     else

@@ -499,18 +499,28 @@ __global__ __launch_bounds__(SEL_THREADS) void select_update_kernel(MatrixView A
 hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k, int32_t *sel, float *x,
                       const OmpWorkspace &ws, hipStream_t s)
 {
-    omp_init_kernel<<<dim3((unsigned)N), 256, 0, s>>>(y, A.r, ws.words, ws.res64, ws.res32, ws.bitmap);
+    {
+        ProfileScope prof(KC_OTHER, s);
+        omp_init_kernel<<<dim3((unsigned)N), 256, 0, s>>>(y, A.r, ws.words, ws.res64, ws.res32, ws.bitmap);
+    }
     const dim3 cgrid((unsigned)ws.tiles_m, (unsigned)((N + CORR_BN - 1) / CORR_BN));
     const size_t smem = (((size_t)A.r * 4 + 15) & ~(size_t)15) + 2 * sizeof(double) * (size_t)k;
     SelectArgs P{y, k, 0, sel, x, ws};
     for (int32_t it = 0; it < k; ++it) {
         P.it = it;
-        if (A.generated) {
-            corr_kernel<true><<<cgrid, CORR_THREADS, 0, s>>>(A, ws.res32, N, ws.bitmap, ws.words, ws.partial, ws.tiles_m);
-            select_update_kernel<true><<<dim3((unsigned)N), SEL_THREADS, smem, s>>>(A, P);
-        } else {
-            corr_kernel<false><<<cgrid, CORR_THREADS, 0, s>>>(A, ws.res32, N, ws.bitmap, ws.words, ws.partial, ws.tiles_m);
-            select_update_kernel<false><<<dim3((unsigned)N), SEL_THREADS, smem, s>>>(A, P);
+        {
+            ProfileScope prof(KC_CORR, s);
+            if (A.generated)
+                corr_kernel<true><<<cgrid, CORR_THREADS, 0, s>>>(A, ws.res32, N, ws.bitmap, ws.words, ws.partial, ws.tiles_m);
+            else
+                corr_kernel<false><<<cgrid, CORR_THREADS, 0, s>>>(A, ws.res32, N, ws.bitmap, ws.words, ws.partial, ws.tiles_m);
+        }
+        {
+            ProfileScope prof(KC_SELECT, s);
+            if (A.generated)
+                select_update_kernel<true><<<dim3((unsigned)N), SEL_THREADS, smem, s>>>(A, P);
+            else
+                select_update_kernel<false><<<dim3((unsigned)N), SEL_THREADS, smem, s>>>(A, P);
         }
     }
     return hipGetLastError();

@@ -1,0 +1,95 @@
+// Per-kernel timing with HIP events on the caller's stream (instrumentation only).
+#include <vector>
+
+#include "sgc_internal.h"
+
+namespace sgc {
+
+bool g_profile_on = false;
+
+namespace {
+struct Span {
+    int cls;
+    hipEvent_t a, b;
+};
+std::vector<Span> g_spans;
+std::vector<hipEvent_t> g_pool;
+hipEvent_t g_open = nullptr;
+int g_open_cls = 0;
+bool g_failed = false;
+
+hipEvent_t get_event()
+{
+    if (!g_pool.empty()) {
+        hipEvent_t e = g_pool.back();
+        g_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) {
+        g_failed = true;
+        return nullptr;
+    }
+    return e;
+}
+} // namespace
+
+void profile_begin(int cls, hipStream_t s)
+{
+    g_open = get_event();
+    g_open_cls = cls;
+    if (g_open && hipEventRecord(g_open, s) != hipSuccess)
+        g_failed = true;
+}
+
+void profile_end(hipStream_t s)
+{
+    hipEvent_t e = get_event();
+    if (e && hipEventRecord(e, s) != hipSuccess)
+        g_failed = true;
+    if (g_open && e)
+        g_spans.push_back(Span{g_open_cls, g_open, e});
+    g_open = nullptr;
+}
+
+} // namespace sgc
+
+using namespace sgc;
+
+extern "C" {
+
+sgc_status sgc_profile_enable(int32_t on)
+{
+    for (auto &sp : g_spans) {
+        g_pool.push_back(sp.a);
+        g_pool.push_back(sp.b);
+    }
+    g_spans.clear();
+    g_failed = false;
+    g_profile_on = on != 0;
+    return SGC_OK;
+}
+
+sgc_status sgc_profile_read(sgc_profile *out)
+{
+    if (!out)
+        return SGC_ERR_NULL;
+    for (int c = 0; c < SGC_PROFILE_CLASSES; ++c) {
+        out->ms[c] = 0.0;
+        out->launches[c] = 0;
+    }
+    sgc_status st = g_failed ? SGC_ERR_DEVICE : SGC_OK;
+    for (auto &sp : g_spans) {
+        float ms = 0.f;
+        if (hipEventSynchronize(sp.b) != hipSuccess || hipEventElapsedTime(&ms, sp.a, sp.b) != hipSuccess)
+            st = SGC_ERR_DEVICE;
+        out->ms[sp.cls] += (double)ms;
+        out->launches[sp.cls] += 1;
+        g_pool.push_back(sp.a);
+        g_pool.push_back(sp.b);
+    }
+    g_spans.clear();
+    return st;
+}
+
+} // extern "C"

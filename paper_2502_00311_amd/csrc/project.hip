@@ -72,6 +72,7 @@ hipError_t launch_project(const int32_t *idx, const float *val, int64_t C, int32
         const unsigned gy = (unsigned)(C - c0 < 65535 ? C - c0 : 65535);
         const dim3 grid(gx, gy);
         float *qq = q ? q + c0 * A.r : nullptr;
+        ProfileScope prof(KC_PROJECT, s);
         if (A.generated)
             project_kernel<true><<<grid, PROJ_THREADS, 0, s>>>(idx + c0 * k, val + c0 * k, k, A, p + c0 * A.r, qq);
         else

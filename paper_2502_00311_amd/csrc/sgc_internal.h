@@ -60,6 +60,26 @@ hipError_t launch_apply(float *W, int64_t C, int32_t d, int32_t k, const int32_t
                         const int32_t *sel_v, const float *x_v, float alpha, float eps, float lr,
                         hipStream_t s);
 
+// ---- optional per-kernel timing (see profile.hip) ----
+enum KernelClass { KC_TOPK = 0, KC_PROJECT, KC_ADAM, KC_CORR, KC_SELECT, KC_APPLY, KC_OTHER };
+extern bool g_profile_on;
+void profile_begin(int cls, hipStream_t s);
+void profile_end(hipStream_t s);
+struct ProfileScope {
+    hipStream_t s;
+    bool on;
+    ProfileScope(int cls, hipStream_t st) : s(st), on(g_profile_on)
+    {
+        if (on)
+            profile_begin(cls, s);
+    }
+    ~ProfileScope()
+    {
+        if (on)
+            profile_end(s);
+    }
+};
+
 // ---- small device helpers ----
 __device__ __forceinline__ double wave_sum(double v)
 {

@@ -166,6 +166,7 @@ hipError_t launch_topk(const void *grad, int grad_type, int64_t C, int32_t d, in
     if (C == 0)
         return hipSuccess;
     const dim3 grid((unsigned)C);
+    ProfileScope prof(KC_TOPK, s);
     if (grad_type == SGC_GRAD_F32) {
         if (d <= 16384)
             topk_kernel<float, 256><<<grid, 256, 0, s>>>((const float *)grad, d, k, idx, val);

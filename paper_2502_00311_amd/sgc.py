@@ -20,7 +20,9 @@ MATRIX_STORED, MATRIX_PHILOX = 0, 1
 EXPORTS = [
     "sgc_status_string", "sgc_matrix_fill", "sgc_matrix_colnorms", "sgc_sparsify_project",
     "sgc_adam_compressed", "sgc_omp_workspace_bytes", "sgc_recover_omp", "sgc_apply",
+    "sgc_profile_enable", "sgc_profile_read",
 ]
+PROFILE_CLASSES = ["topk", "project", "adam", "omp_corr", "omp_select_update", "apply", "other"]
 
 
 class sgc_matrix(ctypes.Structure):
@@ -33,6 +35,10 @@ class sgc_matrix(ctypes.Structure):
 class sgc_hyper(ctypes.Structure):
     _fields_ = [("beta1", ctypes.c_double), ("beta2", ctypes.c_double), ("eps", ctypes.c_double),
                 ("lr", ctypes.c_double), ("alpha", ctypes.c_double)]
+
+
+class sgc_profile(ctypes.Structure):
+    _fields_ = [("ms", ctypes.c_double * 7), ("launches", ctypes.c_int64 * 7)]
 
 
 class SgcError(RuntimeError):
@@ -68,6 +74,10 @@ def lib():
         L.sgc_recover_omp.argtypes = [vp, i32, ctypes.POINTER(sgc_matrix), i32, vp, vp, vp, sz, vp]
         L.sgc_apply.restype = i32
         L.sgc_apply.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, ctypes.POINTER(sgc_hyper), vp]
+        L.sgc_profile_enable.restype = i32
+        L.sgc_profile_enable.argtypes = [i32]
+        L.sgc_profile_read.restype = i32
+        L.sgc_profile_read.argtypes = [ctypes.POINTER(sgc_profile)]
         _lib = L
     return _lib
 
@@ -137,6 +147,17 @@ def sgc_recover_omp(y, N, A, k, sel, x, ws, stream=None):
 
 def sgc_apply(W, C, d, k, sel_m, x_m, sel_v, x_v, h, stream=None):
     _check(lib().sgc_apply(_ptr(W), C, d, k, _ptr(sel_m), _ptr(x_m), _ptr(sel_v), _ptr(x_v), ctypes.byref(h), _stream(stream)), "sgc_apply")
+
+
+def sgc_profile_enable(on):
+    _check(lib().sgc_profile_enable(1 if on else 0), "sgc_profile_enable")
+
+
+def sgc_profile_read():
+    """{class name: (total ms, launches)} of the kernels launched since sgc_profile_enable(True)."""
+    out = sgc_profile()
+    _check(lib().sgc_profile_read(ctypes.byref(out)), "sgc_profile_read")
+    return {n: (out.ms[i], out.launches[i]) for i, n in enumerate(PROFILE_CLASSES)}
 
 
 class StepBuffers:
