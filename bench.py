@@ -34,6 +34,9 @@ def main():
     ap.add_argument("--workload", type=int, default=2, help="configuration index 1..5 (default 2)")
     ap.add_argument("--chunks", type=int, default=0, help="override the number of chunks (0 = as defined)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain 1 GiB device copies (reference for the rocprofv3 FETCH_SIZE / "
+                         "WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (chunks are independent and would shard by "
@@ -133,6 +136,13 @@ def main():
         "ms_per_step_with_events": round((t3 - t2) * 1e3 / K, 3),
         "kernels": kernels,
     }
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, At_host)
