@@ -153,7 +153,7 @@ sgc_status sgc_recover_omp(const float *y, int32_t N, const sgc_matrix *A, int32
         return st;
     if (!omp_sizes_ok(N, A->d, A->r, k))
         return SGC_ERR_SHAPE;
-    if (!aligned16(y) || ((uintptr_t)ws & 255u))
+    if (!aligned16(y) || !aligned16(A->inv_colnorm) || ((uintptr_t)ws & 255u))
         return SGC_ERR_ALIGN;
     const OmpWorkspace w = carve_workspace(ws, N, A->d, A->r, k);
     if (ws_bytes < w.bytes)

@@ -1,18 +1,19 @@
 // Batched orthogonal matching pursuit (paper Sec. 4.3 eq. 9; selection rule, inverse-Cholesky
 // update and output of App. B) for N right-hand sides that share the measurement matrix A.
 //
-// Per iteration two kernels run:
+// Per iteration:
 //   corr_kernel    P = At * R for all right-hand sides at once: a dense float contraction on the
 //                  matrix cores (32x32x2 MFMA, LDS-staged 128x128 tiles). P is never written: the
 //                  epilogue scales by 1/||A_:i||, masks selected positions and keeps the two best
 //                  (score, position) pairs of every 128-row tile per right-hand side.
-//   select_update  one workgroup per right-hand side: re-scores the near-maximal candidates in
-//                  double (so the argmax does not depend on float rounding), appends the winning
-//                  column, extends F = L^-H (App. B) by mat-vecs only, and recomputes the residual
-//                  y - A_Lambda x in double.
+//   pick / factor / residual   re-score the near-maximal candidates in double (so the argmax does
+//                  not depend on float rounding), append the winning column, extend F = L^-H
+//                  (App. B) by mat-vecs only, and recompute the residual y - A_Lambda x in double.
 // App. B precomputes the Gram matrix A^H A (d x d) to avoid the contraction; here the contraction
 // is kept (it is what the matrix cores are for) and only inner products with selected columns are
 // formed, so memory stays O(N k r).
+#include <stdlib.h>
+
 #include "philox_normal.h"
 #include "sgc_internal.h"
 
@@ -20,9 +21,6 @@ namespace sgc {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int CORR_BK = 32;       // contraction depth staged per step
-constexpr int CORR_LD = CORR_BK + 4; // LDS row stride in floats (16-byte aligned, conflict-free b128 reads)
-constexpr int CORR_THREADS = 256;
 constexpr float RESCORE_TOL = 0x1.0p-10f; // candidates within this relative distance of the float maximum
 
 OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_t k)
@@ -44,7 +42,8 @@ OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_
     w.cols = (float *)take(sizeof(float) * (size_t)N * k * r);
     w.partial = (uint64_t *)take(sizeof(uint64_t) * (size_t)N * w.tiles_m * 2);
     w.bitmap = (uint32_t *)take(sizeof(uint32_t) * (size_t)N * w.words);
-    w.cand = (int32_t *)take(sizeof(int32_t) * (size_t)N * w.tiles_m * 2);
+    w.wv = (double *)take(sizeof(double) * (size_t)N * k);
+    w.gb = (double *)take(sizeof(double) * (size_t)N * 2);
     w.bytes = off;
     return w;
 }
@@ -74,42 +73,42 @@ __device__ __forceinline__ void top2_insert(uint64_t key, uint64_t &best, uint64
 }
 
 // Correlation contraction + fused selection epilogue.
-//   grid.x = tiles over positions i (128 each), grid.y = tiles over right-hand sides (128 each)
-//   wave (wm, wn) of the 2x2 wave grid owns a 64x64 sub-tile = 2x2 MFMA blocks of 32x32.
+//   grid.x = tiles over positions i (BM each), grid.y = tiles over right-hand sides (BN each)
+//   WMW x WNW wavefronts; each owns a (BM/WMW) x (BN/WNW) sub-tile made of 32x32 MFMA blocks.
 // MFMA 32x32x2 operands: lane l supplies At[row l%32][depth l/32] and R[rhs l%32][depth l/32]. Each
 // lane reads four consecutive depths with one 16-byte LDS read; lanes 32..63 read depths +4..+7, so
 // four MFMAs cover eight depths (the sum over depth does not depend on their order).
 // Accumulator register v of lane l holds position 8*(v/4) + 4*(l/32) + v%4 of right-hand side l%32.
-template <bool GENERATED>
-__global__ __launch_bounds__(CORR_THREADS, 2) void corr_kernel(MatrixView A, const float *__restrict__ R,
-                                                               int32_t N, const uint32_t *__restrict__ bitmap,
-                                                               int32_t words, uint64_t *__restrict__ partial,
-                                                               int32_t tiles_m)
+// LDS rows are padded by 4 floats: 16-byte aligned and conflict-free for the 16-byte reads.
+template <bool GENERATED, int BM, int BN, int BK, int WMW, int WNW, int MINB>
+__global__ __launch_bounds__(WMW * WNW * 64, MINB) void corr_kernel(MatrixView A, const float *__restrict__ R,
+                                                                    int32_t N, const uint32_t *__restrict__ bitmap,
+                                                                    int32_t words, uint64_t *__restrict__ partial,
+                                                                    int32_t tiles_m)
 {
-    __shared__ __attribute__((aligned(16))) float lds_a[2][CORR_BM * CORR_LD];
-    __shared__ __attribute__((aligned(16))) float lds_b[2][CORR_BN * CORR_LD];
+    constexpr int T = WMW * WNW * 64;
+    constexpr int LD = BK + 4;
+    constexpr int MB = BM / WMW / 32, NB = BN / WNW / 32; // MFMA blocks per wavefront
+    constexpr int LA = BM * BK / 4 / T, LB = BN * BK / 4 / T; // 16-byte pieces per thread per stage
+    constexpr int C4 = BK / 4;
+    static_assert(BM * BK / 4 % T == 0 && BN * BK / 4 % T == 0, "tile does not divide among the threads");
+    extern __shared__ __attribute__((aligned(16))) float corr_lds[];
+    float *lds_a = corr_lds;               // [2][BM*LD]
+    float *lds_b = corr_lds + 2 * BM * LD; // [2][BN*LD]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WNW, wn = wave % WNW;
     const int32_t d = A.d, r = A.r;
-    const int32_t m0 = blockIdx.x * CORR_BM;
-    const int32_t n0 = blockIdx.y * CORR_BN;
+    const int32_t m0 = blockIdx.x * BM;
+    const int32_t n0 = blockIdx.y * BN;
 
-    // global -> register staging: 4 float4 of the At tile and 4 of the R tile per thread
-    float4 ga[4], gb[4];
-    int lrow[4], lcol[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int f = tid + CORR_THREADS * u;
-        lrow[u] = f >> 3;
-        lcol[u] = (f & 7) << 2;
-    }
+    float4 ga[LA], gb[LB];
     auto load_global = [&](int32_t k0) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int32_t i = m0 + lrow[u];
-            const int32_t kk = k0 + lcol[u];
+        for (int u = 0; u < LA; ++u) {
+            const int f = tid + T * u;
+            const int32_t i = m0 + f / C4, kk = k0 + (f % C4) * 4;
             float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
             if (i < d && kk < r) {
                 if (GENERATED)
@@ -118,7 +117,11 @@ __global__ __launch_bounds__(CORR_THREADS, 2) void corr_kernel(MatrixView A, con
                     a = *reinterpret_cast<const float4 *>(A.At + (int64_t)i * r + kk);
             }
             ga[u] = a;
-            const int32_t n = n0 + lrow[u];
+        }
+#pragma unroll
+        for (int u = 0; u < LB; ++u) {
+            const int f = tid + T * u;
+            const int32_t n = n0 + f / C4, kk = k0 + (f % C4) * 4;
             float4 b = make_float4(0.f, 0.f, 0.f, 0.f);
             if (n < N && kk < r)
                 b = *reinterpret_cast<const float4 *>(R + (int64_t)n * r + kk);
@@ -127,22 +130,27 @@ __global__ __launch_bounds__(CORR_THREADS, 2) void corr_kernel(MatrixView A, con
     };
     auto store_lds = [&](int buf) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            *reinterpret_cast<float4 *>(&lds_a[buf][lrow[u] * CORR_LD + lcol[u]]) = ga[u];
-            *reinterpret_cast<float4 *>(&lds_b[buf][lrow[u] * CORR_LD + lcol[u]]) = gb[u];
+        for (int u = 0; u < LA; ++u) {
+            const int f = tid + T * u;
+            *reinterpret_cast<float4 *>(&lds_a[buf * BM * LD + (f / C4) * LD + (f % C4) * 4]) = ga[u];
+        }
+#pragma unroll
+        for (int u = 0; u < LB; ++u) {
+            const int f = tid + T * u;
+            *reinterpret_cast<float4 *>(&lds_b[buf * BN * LD + (f / C4) * LD + (f % C4) * 4]) = gb[u];
         }
     };
 
-    floatx16 acc[2][2];
+    floatx16 acc[MB][NB];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < MB; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < NB; ++b)
 #pragma unroll
             for (int v = 0; v < 16; ++v)
                 acc[a][b][v] = 0.f;
 
-    const int nkb = (r + CORR_BK - 1) / CORR_BK;
+    const int nkb = (r + BK - 1) / BK;
     load_global(0);
     store_lds(0);
     __syncthreads();
@@ -150,24 +158,28 @@ __global__ __launch_bounds__(CORR_THREADS, 2) void corr_kernel(MatrixView A, con
     for (int kb = 0; kb < nkb; ++kb) {
         const int buf = kb & 1;
         if (kb + 1 < nkb)
-            load_global((kb + 1) * CORR_BK);
-        const float *pa = &lds_a[buf][(wm * 64 + l32) * CORR_LD + lhalf * 4];
-        const float *pb = &lds_b[buf][(wn * 64 + l32) * CORR_LD + lhalf * 4];
+            load_global((kb + 1) * BK);
+        const float *pa = &lds_a[buf * BM * LD + (wm * (BM / WMW) + l32) * LD + lhalf * 4];
+        const float *pb = &lds_b[buf * BN * LD + (wn * (BN / WNW) + l32) * LD + lhalf * 4];
 #pragma unroll
-        for (int ks = 0; ks < CORR_BK; ks += 8) {
-            const float4 a0 = *reinterpret_cast<const float4 *>(pa + ks);
-            const float4 a1 = *reinterpret_cast<const float4 *>(pa + 32 * CORR_LD + ks);
-            const float4 b0 = *reinterpret_cast<const float4 *>(pb + ks);
-            const float4 b1 = *reinterpret_cast<const float4 *>(pb + 32 * CORR_LD + ks);
-            const float av[2][4] = {{a0.x, a0.y, a0.z, a0.w}, {a1.x, a1.y, a1.z, a1.w}};
-            const float bv[2][4] = {{b0.x, b0.y, b0.z, b0.w}, {b1.x, b1.y, b1.z, b1.w}};
+        for (int ks = 0; ks < BK; ks += 8) {
+            float4 av[MB], bv[NB];
+#pragma unroll
+            for (int a = 0; a < MB; ++a)
+                av[a] = *reinterpret_cast<const float4 *>(pa + a * 32 * LD + ks);
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+                bv[b] = *reinterpret_cast<const float4 *>(pb + b * 32 * LD + ks);
 #pragma unroll
             for (int t = 0; t < 4; ++t)
 #pragma unroll
-                for (int a = 0; a < 2; ++a)
+                for (int a = 0; a < MB; ++a)
 #pragma unroll
-                    for (int b = 0; b < 2; ++b)
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[a][t], bv[b][t], acc[a][b], 0, 0, 0);
+                    for (int b = 0; b < NB; ++b) {
+                        const float x = t == 0 ? av[a].x : (t == 1 ? av[a].y : (t == 2 ? av[a].z : av[a].w));
+                        const float y = t == 0 ? bv[b].x : (t == 1 ? bv[b].y : (t == 2 ? bv[b].z : bv[b].w));
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(x, y, acc[a][b], 0, 0, 0);
+                    }
         }
         if (kb + 1 < nkb)
             store_lds(buf ^ 1);
@@ -175,28 +187,52 @@ __global__ __launch_bounds__(CORR_THREADS, 2) void corr_kernel(MatrixView A, con
     }
 
     // ---- epilogue: normalise, mask, keep the two best per right-hand side ----
-    uint64_t *red = reinterpret_cast<uint64_t *>(&lds_a[0][0]); // [2 wm][128 rhs][2]
+    uint64_t *red = reinterpret_cast<uint64_t *>(corr_lds); // [WMW][BN][2]
+    // reciprocal norms of this lane's MB x 16 positions (4 runs of 4 consecutive positions per block)
+    // and the selection masks, fetched together before any of them is used
+    float4 inv[MB][4];
+    uint32_t msk[MB][NB];
+#pragma unroll
+    for (int a = 0; a < MB; ++a) {
+        const int32_t ibase = m0 + wm * (BM / WMW) + a * 32;
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            const int32_t i0 = ibase + 8 * qd + 4 * lhalf;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (i0 + 3 < d) {
+                v = *reinterpret_cast<const float4 *>(A.inv_colnorm + i0);
+            } else {
+                if (i0 < d) v.x = A.inv_colnorm[i0];
+                if (i0 + 1 < d) v.y = A.inv_colnorm[i0 + 1];
+                if (i0 + 2 < d) v.z = A.inv_colnorm[i0 + 2];
+            }
+            inv[a][qd] = v;
+        }
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int32_t n = n0 + wn * (BN / WNW) + b * 32 + l32;
+            msk[a][b] = (n < N && ibase < d) ? bitmap[(int64_t)n * words + (ibase >> 5)] : 0xffffffffu;
+        }
+    }
     __syncthreads();
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-        const int nl = wn * 64 + b * 32 + l32; // right-hand side within the tile
-        const int32_t n = n0 + nl;
+    for (int b = 0; b < NB; ++b) {
+        const int nl = wn * (BN / WNW) + b * 32 + l32; // right-hand side within the tile
         uint64_t best = 0, second = 0;
 #pragma unroll
-        for (int a = 0; a < 2; ++a) {
-            const int32_t ibase = m0 + wm * 64 + a * 32;
-            uint32_t mask = 0xffffffffu;
-            if (n < N && ibase < d)
-                mask = bitmap[(int64_t)n * words + (ibase >> 5)];
+        for (int a = 0; a < MB; ++a) {
+            const int32_t ibase = m0 + wm * (BM / WMW) + a * 32;
+            const uint32_t mask = msk[a][b];
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int off = 8 * (v >> 2) + 4 * lhalf + (v & 3);
                 const int32_t i = ibase + off;
-                if (i < d && !((mask >> off) & 1u)) {
-                    const float score = fabsf(acc[a][b][v]) * A.inv_colnorm[i];
-                    const uint64_t key = ((uint64_t)__float_as_uint(score) << 32) | (uint64_t)(0xffffffffu - (uint32_t)i);
-                    top2_insert(key, best, second);
-                }
+                const float4 nv = inv[a][v >> 2];
+                const float in = (v & 3) == 0 ? nv.x : ((v & 3) == 1 ? nv.y : ((v & 3) == 2 ? nv.z : nv.w));
+                const float score = fabsf(acc[a][b][v]) * in;
+                const bool ok = i < d && !((mask >> off) & 1u);
+                const uint64_t key = ok ? (((uint64_t)__float_as_uint(score) << 32) | (uint64_t)(0xffffffffu - (uint32_t)i)) : 0ull;
+                top2_insert(key, best, second);
             }
         }
         // the other half-wave holds the remaining positions of the same right-hand side
@@ -204,17 +240,20 @@ __global__ __launch_bounds__(CORR_THREADS, 2) void corr_kernel(MatrixView A, con
         top2_insert(ob, best, second);
         top2_insert(os, best, second);
         if (lhalf == 0) {
-            red[(wm * CORR_BN + nl) * 2 + 0] = best;
-            red[(wm * CORR_BN + nl) * 2 + 1] = second;
+            red[(wm * BN + nl) * 2 + 0] = best;
+            red[(wm * BN + nl) * 2 + 1] = second;
         }
     }
     __syncthreads();
-    if (tid < CORR_BN) {
+    if (tid < BN) {
         const int32_t n = n0 + tid;
         if (n < N) {
             uint64_t best = red[tid * 2], second = red[tid * 2 + 1];
-            top2_insert(red[(CORR_BN + tid) * 2], best, second);
-            top2_insert(red[(CORR_BN + tid) * 2 + 1], best, second);
+#pragma unroll
+            for (int w = 1; w < WMW; ++w) {
+                top2_insert(red[(w * BN + tid) * 2], best, second);
+                top2_insert(red[(w * BN + tid) * 2 + 1], best, second);
+            }
             uint64_t *o = partial + ((int64_t)n * tiles_m + blockIdx.x) * 2;
             o[0] = best;
             o[1] = second;
@@ -222,15 +261,71 @@ __global__ __launch_bounds__(CORR_THREADS, 2) void corr_kernel(MatrixView A, con
     }
 }
 
-// ----------------------------------------------------------------------------------------------
-constexpr int SEL_THREADS = 256;
-constexpr int SEL_WAVES = SEL_THREADS / 64;
+// One tiling of the contraction: sizes, and a launcher that raises the dynamic-LDS limit once.
+struct CorrShape {
+    int bm, bn;
+};
+template <bool GENERATED, int BM, int BN, int BK, int WMW, int WNW, int MINB>
+static hipError_t corr_launch(const MatrixView &A, const float *R, int32_t N, const OmpWorkspace &ws, int32_t tiles_m,
+                              hipStream_t s)
+{
+    constexpr size_t smem = (size_t)2 * (BM + BN) * (BK + 4) * sizeof(float);
+    auto kern = corr_kernel<GENERATED, BM, BN, BK, WMW, WNW, MINB>;
+    static bool raised = false;
+    if (!raised) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess)
+            return e;
+        raised = true;
+    }
+    const dim3 grid((unsigned)tiles_m, (unsigned)((N + BN - 1) / BN));
+    kern<<<grid, WMW * WNW * 64, smem, s>>>(A, R, N, ws.bitmap, ws.words, ws.partial, tiles_m);
+    return hipSuccess;
+}
 
-struct SelectArgs {
-    const float *y;   // [N][r]
-    int32_t k, it;    // sparsity, current iteration (0-based)
-    int32_t *sel;     // [N][k]
-    float *x;         // [N][k]
+// variant table: index -> (BM, BN, BK, waves, occupancy)
+static int corr_variant_bm(int variant)
+{
+    switch (variant) {
+    case 1: case 3: case 4: return 256;
+    default: return 128;
+    }
+}
+template <bool GENERATED>
+static hipError_t corr_dispatch(int variant, const MatrixView &A, const float *R, int32_t N, const OmpWorkspace &ws,
+                                int32_t tiles_m, hipStream_t s)
+{
+    switch (variant) {
+    case 1: return corr_launch<GENERATED, 256, 128, 32, 4, 2, 1>(A, R, N, ws, tiles_m, s);
+    case 2: return corr_launch<GENERATED, 128, 128, 16, 2, 2, 2>(A, R, N, ws, tiles_m, s);
+    case 3: return corr_launch<GENERATED, 256, 128, 16, 4, 2, 2>(A, R, N, ws, tiles_m, s);
+    case 4: return corr_launch<GENERATED, 256, 128, 32, 2, 2, 1>(A, R, N, ws, tiles_m, s);
+    case 5: return corr_launch<GENERATED, 128, 128, 16, 2, 2, 3>(A, R, N, ws, tiles_m, s);
+    default: return corr_launch<GENERATED, 128, 128, 32, 2, 2, 2>(A, R, N, ws, tiles_m, s);
+    }
+}
+
+// ----------------------------------------------------------------------------------------------
+// Selection and least-squares update, three kernels per iteration:
+//   pick_kernel      re-scores the near-maximal candidates in double and fixes lambda; then
+//                    w_t = <A_:lambda_t, A_:lambda> for the earlier selections (a row-major mat-vec over
+//                    the stored columns, one wavefront per row, spread over several workgroups)
+//   factor_kernel    the small dense part of App. B: c = F^H w, gamma, the new coefficient, the new
+//                    column of F and x = F a, all in double
+//   residual_kernel  res = y - A_Lambda x in double (a column-major mat-vec over the stored columns,
+//                    one thread per four measurements), plus the float copy for the next contraction
+constexpr int PICK_THREADS = 512;
+constexpr int PICK_WAVES = PICK_THREADS / 64;
+constexpr int PICK_CAND_CAP = 64;
+constexpr int FACTOR_MAX_THREADS = 1024;
+constexpr int RES_THREADS = 64;
+
+struct IterArgs {
+    const float *y; // [N][r]
+    int32_t k, it;  // sparsity, current iteration (0-based)
+    int32_t *sel;   // [N][k]
+    float *x;       // [N][k]
     OmpWorkspace ws;
 };
 
@@ -242,34 +337,35 @@ __device__ __forceinline__ float4 column_quad(const MatrixView &A, int32_t i, in
     return reinterpret_cast<const float4 *>(A.At + (int64_t)i * A.r)[jb];
 }
 
-// dynamic LDS: float a_col[r]; double w[k]; double c[k]
+// grid (N, slices). Every slice of a right-hand side repeats the (cheap) selection so that no
+// grid-wide synchronisation is needed; slice 0 also stores the column and the scalars.
+// dynamic LDS: float a_col[r]
 template <bool GENERATED>
-__global__ __launch_bounds__(SEL_THREADS) void select_update_kernel(MatrixView A, SelectArgs P)
+__global__ __launch_bounds__(PICK_THREADS) void pick_kernel(MatrixView A, IterArgs P)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const int32_t r = A.r, r4 = A.r >> 2, k = P.k, it = P.it;
     float *a_col = reinterpret_cast<float *>(smem);
-    double *w_s = reinterpret_cast<double *>(smem + (((size_t)r * 4 + 15) & ~(size_t)15));
-    double *c_s = w_s + k;
+    __shared__ uint64_t s_u64[PICK_WAVES];
+    __shared__ double s_red[2][PICK_WAVES];
+    __shared__ double s_cscore[PICK_WAVES];
+    __shared__ int32_t s_cidx[PICK_WAVES];
+    __shared__ int32_t s_cand[PICK_CAND_CAP];
+    __shared__ int32_t s_lambda, s_ncand;
 
-    __shared__ uint64_t s_u64[SEL_WAVES];
-    __shared__ double s_red[3][SEL_WAVES];
-    __shared__ double s_cscore[SEL_WAVES];
-    __shared__ int32_t s_cidx[SEL_WAVES];
-    __shared__ int32_t s_ncand, s_lambda;
-    __shared__ double s_gamma, s_coef;
-
+    const int32_t r = A.r, r4 = A.r >> 2, k = P.k, it = P.it;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t n = blockIdx.x;
+    const int slice = blockIdx.y, nslices = gridDim.y;
+    if (slice != 0 && slice * PICK_WAVES >= it)
+        return; // no earlier selection falls to this slice
     const OmpWorkspace &W = P.ws;
     const int32_t np = W.tiles_m * 2;
     const uint64_t *part = W.partial + n * np;
     const double *res64 = W.res64 + n * r;
-    int32_t *cand = W.cand + n * np;
 
     // (1) float maximum over the tile partials
     uint64_t best = 0;
-    for (int32_t e = tid; e < np; e += SEL_THREADS) {
+    for (int32_t e = tid; e < np; e += PICK_THREADS) {
         const uint64_t v = part[e];
         best = v > best ? v : best;
     }
@@ -284,42 +380,58 @@ __global__ __launch_bounds__(SEL_THREADS) void select_update_kernel(MatrixView A
         s_ncand = 0;
     __syncthreads();
 #pragma unroll
-    for (int u = 0; u < SEL_WAVES; ++u)
+    for (int u = 0; u < PICK_WAVES; ++u)
         best = s_u64[u] > best ? s_u64[u] : best;
     const float smax = __uint_as_float((uint32_t)(best >> 32));
     const float thr = smax * (1.0f - RESCORE_TOL);
 
     // (2) candidates: every kept pair whose float score is within the tolerance of the maximum
-    for (int32_t e = tid; e < np; e += SEL_THREADS) {
+    for (int32_t e = tid; e < np; e += PICK_THREADS) {
         const uint64_t v = part[e];
         if (v != 0 && __uint_as_float((uint32_t)(v >> 32)) >= thr) {
             const int32_t slot = atomicAdd(&s_ncand, 1);
-            cand[slot] = (int32_t)(0xffffffffu - (uint32_t)v);
+            if (slot < PICK_CAND_CAP)
+                s_cand[slot] = (int32_t)(0xffffffffu - (uint32_t)v);
         }
     }
     __syncthreads();
     const int32_t ncand = s_ncand;
 
-    // (3) re-score in double, one wavefront per candidate; best = (score desc, position asc)
+    // (3) a single candidate is the argmax; several are re-scored in double, one wavefront per
+    //     candidate, winner = (score desc, position asc). More candidates than the list holds (an
+    //     all-zero residual) are walked straight from the partials.
     double wbest = -1.0;
     int32_t widx = 0x7fffffff;
-    for (int32_t cdx = wave; cdx < ncand; cdx += SEL_WAVES) {
-        const int32_t i = cand[cdx];
-        double dot = 0.0, nrm = 0.0;
-        for (int32_t jb = lane; jb < r4; jb += 64) {
-            const float4 a = column_quad<GENERATED>(A, i, jb);
-            const double *rr = res64 + 4 * jb;
-            dot += (double)a.x * rr[0] + (double)a.y * rr[1] + (double)a.z * rr[2] + (double)a.w * rr[3];
-            nrm += (double)a.x * a.x + (double)a.y * a.y + (double)a.z * a.z + (double)a.w * a.w;
-        }
-        dot = wave_sum(dot);
-        nrm = wave_sum(nrm);
-        dot = __shfl(dot, 0, 64);
-        nrm = __shfl(nrm, 0, 64);
-        const double score = nrm > 0.0 ? fabs(dot) / sqrt(nrm) : 0.0;
-        if (score > wbest || (score == wbest && i < widx)) {
-            wbest = score;
-            widx = i;
+    if (ncand == 1) {
+        wbest = 0.0;
+        widx = s_cand[0];
+    } else {
+        const bool listed = ncand <= PICK_CAND_CAP;
+        const int32_t count = listed ? ncand : np;
+        for (int32_t e = wave; e < count; e += PICK_WAVES) {
+            int32_t i;
+            if (listed) {
+                i = s_cand[e];
+            } else {
+                const uint64_t v = part[e];
+                if (v == 0 || !(__uint_as_float((uint32_t)(v >> 32)) >= thr))
+                    continue;
+                i = (int32_t)(0xffffffffu - (uint32_t)v);
+            }
+            double dot = 0.0, nrm = 0.0;
+            for (int32_t jb = lane; jb < r4; jb += 64) {
+                const float4 a = column_quad<GENERATED>(A, i, jb);
+                const double *rr = res64 + 4 * jb;
+                dot += (double)a.x * rr[0] + (double)a.y * rr[1] + (double)a.z * rr[2] + (double)a.w * rr[3];
+                nrm += (double)a.x * a.x + (double)a.y * a.y + (double)a.z * a.z + (double)a.w * a.w;
+            }
+            dot = __shfl(wave_sum(dot), 0, 64);
+            nrm = __shfl(wave_sum(nrm), 0, 64);
+            const double score = nrm > 0.0 ? fabs(dot) / sqrt(nrm) : 0.0;
+            if (score > wbest || (score == wbest && i < widx)) {
+                wbest = score;
+                widx = i;
+            }
         }
     }
     if (lane == 0) {
@@ -330,7 +442,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_update_kernel(MatrixView A
     if (tid == 0) {
         double bs = s_cscore[0];
         int32_t bi = s_cidx[0];
-        for (int u = 1; u < SEL_WAVES; ++u)
+        for (int u = 1; u < PICK_WAVES; ++u)
             if (s_cscore[u] > bs || (s_cscore[u] == bs && s_cidx[u] < bi)) {
                 bs = s_cscore[u];
                 bi = s_cidx[u];
@@ -346,68 +458,117 @@ __global__ __launch_bounds__(SEL_THREADS) void select_update_kernel(MatrixView A
     __syncthreads();
     const int32_t lam = s_lambda;
 
-    // (4) the new column: to LDS and to the column store; g = ||a||^2, b = <a, y>
+    // (3) the new column to LDS; slice 0 stores it and g = ||a||^2, b = <a, y>
     float *cols = W.cols + (n * k) * (int64_t)r;
     {
         double g = 0.0, b = 0.0;
         const float *yy = P.y + n * r;
-        for (int32_t jb = tid; jb < r4; jb += SEL_THREADS) {
+        for (int32_t jb = tid; jb < r4; jb += PICK_THREADS) {
             const float4 a = column_quad<GENERATED>(A, lam, jb);
             reinterpret_cast<float4 *>(a_col)[jb] = a;
-            reinterpret_cast<float4 *>(cols + (int64_t)it * r)[jb] = a;
-            const float4 yv = reinterpret_cast<const float4 *>(yy)[jb];
-            g += (double)a.x * a.x + (double)a.y * a.y + (double)a.z * a.z + (double)a.w * a.w;
-            b += (double)a.x * yv.x + (double)a.y * yv.y + (double)a.z * yv.z + (double)a.w * yv.w;
+            if (slice == 0) {
+                reinterpret_cast<float4 *>(cols + (int64_t)it * r)[jb] = a;
+                const float4 yv = reinterpret_cast<const float4 *>(yy)[jb];
+                g += (double)a.x * a.x + (double)a.y * a.y + (double)a.z * a.z + (double)a.w * a.w;
+                b += (double)a.x * yv.x + (double)a.y * yv.y + (double)a.z * yv.z + (double)a.w * yv.w;
+            }
         }
-        g = wave_sum(g);
-        b = wave_sum(b);
-        if (lane == 0) {
-            s_red[0][wave] = g;
-            s_red[1][wave] = b;
+        if (slice == 0) {
+            g = wave_sum(g);
+            b = wave_sum(b);
+            if (lane == 0) {
+                s_red[0][wave] = g;
+                s_red[1][wave] = b;
+            }
         }
     }
     __syncthreads();
-    double g = 0.0, b = 0.0;
-#pragma unroll
-    for (int u = 0; u < SEL_WAVES; ++u) {
-        g += s_red[0][u];
-        b += s_red[1][u];
+    if (slice == 0 && tid == 0) {
+        double g = 0.0, b = 0.0;
+        for (int u = 0; u < PICK_WAVES; ++u) {
+            g += s_red[0][u];
+            b += s_red[1][u];
+        }
+        W.gb[n * 2] = g;
+        W.gb[n * 2 + 1] = b;
+        P.sel[n * k + it] = lam;
+        W.bitmap[n * W.words + (lam >> 5)] |= 1u << (lam & 31);
     }
 
-    // (5) w_t = <A_:lambda_t, a> for the earlier selections, one wavefront per t
-    for (int32_t t = wave; t < it; t += SEL_WAVES) {
-        const float4 *ct = reinterpret_cast<const float4 *>(cols + (int64_t)t * r);
-        double s = 0.0;
+    // (4) w_t = <A_:lambda_t, a>, one wavefront per earlier selection, two rows in flight
+    double *wv = W.wv + n * k;
+    const int32_t gw = slice * PICK_WAVES + wave, GW = nslices * PICK_WAVES;
+    for (int32_t t = gw; t < it; t += 2 * GW) {
+        const int32_t t2 = t + GW;
+        const bool two = t2 < it;
+        const float4 *c0 = reinterpret_cast<const float4 *>(cols + (int64_t)t * r);
+        const float4 *c1 = reinterpret_cast<const float4 *>(cols + (int64_t)(two ? t2 : t) * r);
+        double s0 = 0.0, s1 = 0.0;
         for (int32_t jb = lane; jb < r4; jb += 64) {
-            const float4 u = ct[jb];
+            const float4 u0 = c0[jb];
+            const float4 u1 = c1[jb];
             const float4 a = reinterpret_cast<const float4 *>(a_col)[jb];
-            s += (double)u.x * a.x + (double)u.y * a.y + (double)u.z * a.z + (double)u.w * a.w;
+            s0 += (double)u0.x * a.x + (double)u0.y * a.y + (double)u0.z * a.z + (double)u0.w * a.w;
+            s1 += (double)u1.x * a.x + (double)u1.y * a.y + (double)u1.z * a.z + (double)u1.w * a.w;
         }
-        s = wave_sum(s);
-        if (lane == 0)
-            w_s[t] = s;
+        s0 = wave_sum(s0);
+        s1 = wave_sum(s1);
+        if (lane == 0) {
+            wv[t] = s0;
+            if (two)
+                wv[t2] = s1;
+        }
     }
-    __syncthreads();
+}
 
-    // (6) c = F^H w (coordinates of a in the orthonormal basis Q = A_Lambda F); column t of F is
-    //     stored contiguously with entries 0..t
+// grid N; 256 threads (k <= 128) or 1024. dynamic LDS: double w[k]; double c[k]
+__global__ __launch_bounds__(FACTOR_MAX_THREADS) void factor_kernel(IterArgs P)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int32_t k = P.k, it = P.it;
+    double *w_s = reinterpret_cast<double *>(smem);
+    double *c_s = w_s + k;
+    __shared__ double s_red[2][FACTOR_MAX_THREADS / 64];
+    __shared__ double s_part[FACTOR_MAX_THREADS / 256][256];
+    __shared__ double s_gamma, s_coef;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nthreads = blockDim.x, nwaves = blockDim.x >> 6;
+    const int64_t n = blockIdx.x;
+    const OmpWorkspace &W = P.ws;
     double *F = W.F + (n * k) * (int64_t)k;
-    for (int32_t t = wave; t < it; t += SEL_WAVES) {
-        const double *ft = F + (int64_t)t * k;
-        double s = 0.0;
-        for (int32_t u = lane; u <= t; u += 64)
-            s += ft[u] * w_s[u];
-        s = wave_sum(s);
-        if (lane == 0)
-            c_s[t] = s;
+    double *avec = W.avec + n * k;
+    double *xs = W.xs + n * k;
+
+    for (int32_t t = tid; t < it; t += nthreads)
+        w_s[t] = W.wv[n * k + t];
+    __syncthreads();
+    // c = F^H w (coordinates of the new column in the orthonormal basis Q = A_Lambda F); column t
+    // of F is contiguous with entries 0..t. One wavefront per column, two columns in flight.
+    for (int32_t t = wave; t < it; t += 2 * nwaves) {
+        const int32_t t2 = t + nwaves;
+        const bool two = t2 < it;
+        const double *f0 = F + (int64_t)t * k;
+        const double *f1 = F + (int64_t)(two ? t2 : t) * k;
+        const int32_t top = two ? t2 : t;
+        double s0 = 0.0, s1 = 0.0;
+        for (int32_t u = lane; u <= top; u += 64) {
+            const double wu = w_s[u];
+            s0 += (u <= t ? f0[u] : 0.0) * wu;
+            s1 += f1[u] * wu;
+        }
+        s0 = wave_sum(s0);
+        s1 = wave_sum(s1);
+        if (lane == 0) {
+            c_s[t] = s0;
+            if (two)
+                c_s[t2] = s1;
+        }
     }
     __syncthreads();
-
-    // (7) gamma = 1/sqrt(g - c.c); new coefficient a_it = gamma (b - c.avec)
-    double *avec = W.avec + n * k;
+    // gamma = 1/sqrt(g - c.c); new coefficient a_it = gamma (b - c.avec)
     {
         double cc = 0.0, ca = 0.0;
-        for (int32_t t = tid; t < it; t += SEL_THREADS) {
+        for (int32_t t = tid; t < it; t += nthreads) {
             cc += c_s[t] * c_s[t];
             ca += c_s[t] * avec[t];
         }
@@ -421,10 +582,11 @@ __global__ __launch_bounds__(SEL_THREADS) void select_update_kernel(MatrixView A
         if (tid == 0) {
             cc = 0.0;
             ca = 0.0;
-            for (int u = 0; u < SEL_WAVES; ++u) {
+            for (int u = 0; u < nwaves; ++u) {
                 cc += s_red[0][u];
                 ca += s_red[1][u];
             }
+            const double g = W.gb[n * 2], b = W.gb[n * 2 + 1];
             const double rem = g - cc;
             const double gamma = rem > 0.0 ? 1.0 / sqrt(rem) : 0.0;
             const double coef = gamma * (b - ca);
@@ -432,68 +594,99 @@ __global__ __launch_bounds__(SEL_THREADS) void select_update_kernel(MatrixView A
             s_coef = coef;
             avec[it] = coef;
             F[(int64_t)it * k + it] = gamma;
+            xs[it] = coef * gamma;
+            if (it == k - 1)
+                P.x[n * k + it] = (float)(coef * gamma);
         }
         __syncthreads();
     }
     const double gamma = s_gamma, coef = s_coef;
-
-    // (8) new column of F: -gamma F c on rows < it; x <- [x; 0] + coef * F_:it. x goes to w_s.
-    double *xs = W.xs + n * k;
-    for (int32_t u = tid; u <= it; u += SEL_THREADS) {
-        double xn;
+    // new column of F: f_u = -gamma (F c)_u on rows u < it, and x <- [x; 0] + coef * F_:it.
+    // Thread (u, h): row u, h-th part of the sum over columns t = u..it-1 (F[t*k+u] is coalesced
+    // over u); loads are issued eight at a time.
+    const int H = nthreads >> 8, ul = tid & 255, h = tid >> 8;
+    for (int32_t u0 = 0; u0 < it; u0 += 256) {
+        const int32_t u = u0 + ul;
+        double s = 0.0;
         if (u < it) {
-            double s = 0.0;
-            for (int32_t t = u; t < it; ++t)
+            const int32_t len = it - u;
+            int32_t t = u + (int32_t)(((int64_t)h * len) / H);
+            const int32_t te = u + (int32_t)(((int64_t)(h + 1) * len) / H);
+            for (; t + 8 <= te; t += 8) {
+                double f[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+                    f[q] = F[(int64_t)(t + q) * k + u];
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+                    s += f[q] * c_s[t + q];
+            }
+            for (; t < te; ++t)
                 s += F[(int64_t)t * k + u] * c_s[t];
-            const double f = -gamma * s;
+        }
+        s_part[h][ul] = s;
+        __syncthreads();
+        if (h == 0 && u < it) {
+            double tot = 0.0;
+            for (int q = 0; q < H; ++q)
+                tot += s_part[q][ul];
+            const double f = -gamma * tot;
             F[(int64_t)it * k + u] = f;
-            xn = xs[u] + coef * f;
-        } else {
-            xn = coef * gamma;
+            const double xn = xs[u] + coef * f;
+            xs[u] = xn;
+            if (it == k - 1)
+                P.x[n * k + u] = (float)xn;
         }
-        xs[u] = xn;
-        if (it == k - 1)
-            P.x[n * k + u] = (float)xn;
+        __syncthreads();
     }
-    __syncthreads(); // all reads of w_s (step 6) are done
-    for (int32_t u = tid; u <= it; u += SEL_THREADS)
-        w_s[u] = xs[u];
-    __syncthreads();
+}
 
-    // (9) residual = y - A_Lambda x, in double; float copy for the next contraction
-    {
-        const float *yy = P.y + n * r;
-        for (int32_t jb = tid; jb < r4; jb += SEL_THREADS) {
-            const float4 yv = reinterpret_cast<const float4 *>(yy)[jb];
-            double e0 = yv.x, e1 = yv.y, e2 = yv.z, e3 = yv.w;
-            for (int32_t t = 0; t < it; ++t) {
-                const float4 u = reinterpret_cast<const float4 *>(cols + (int64_t)t * r)[jb];
-                const double xt = w_s[t];
-                e0 -= xt * u.x;
-                e1 -= xt * u.y;
-                e2 -= xt * u.z;
-                e3 -= xt * u.w;
-            }
-            {
-                const float4 u = reinterpret_cast<const float4 *>(a_col)[jb];
-                const double xt = w_s[it];
-                e0 -= xt * u.x;
-                e1 -= xt * u.y;
-                e2 -= xt * u.z;
-                e3 -= xt * u.w;
-            }
-            double *ro = W.res64 + n * r + 4 * jb;
-            ro[0] = e0;
-            ro[1] = e1;
-            ro[2] = e2;
-            ro[3] = e3;
-            reinterpret_cast<float4 *>(W.res32 + n * r)[jb] = make_float4((float)e0, (float)e1, (float)e2, (float)e3);
+// grid (N, r/256): one thread per four measurements. dynamic LDS: double x[it+1]
+__global__ __launch_bounds__(RES_THREADS) void residual_kernel(IterArgs P, int32_t r)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    double *x_s = reinterpret_cast<double *>(smem);
+    const int32_t k = P.k, it = P.it, r4 = r >> 2;
+    const int64_t n = blockIdx.x;
+    const OmpWorkspace &W = P.ws;
+    for (int32_t t = threadIdx.x; t <= it; t += RES_THREADS)
+        x_s[t] = W.xs[n * k + t];
+    __syncthreads();
+    const int32_t jb = blockIdx.y * RES_THREADS + threadIdx.x;
+    if (jb >= r4)
+        return;
+    const float4 yv = reinterpret_cast<const float4 *>(P.y + n * r)[jb];
+    double e0 = yv.x, e1 = yv.y, e2 = yv.z, e3 = yv.w;
+    const float4 *cj = reinterpret_cast<const float4 *>(W.cols + (n * k) * (int64_t)r) + jb;
+    int32_t t = 0;
+    for (; t + 8 <= it + 1; t += 8) {
+        float4 u[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            u[q] = cj[(int64_t)(t + q) * r4];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const double xt = x_s[t + q];
+            e0 -= xt * u[q].x;
+            e1 -= xt * u[q].y;
+            e2 -= xt * u[q].z;
+            e3 -= xt * u[q].w;
         }
     }
-    if (tid == 0) {
-        P.sel[n * k + it] = lam;
-        W.bitmap[n * W.words + (lam >> 5)] |= 1u << (lam & 31);
+    for (; t <= it; ++t) {
+        const float4 u = cj[(int64_t)t * r4];
+        const double xt = x_s[t];
+        e0 -= xt * u.x;
+        e1 -= xt * u.y;
+        e2 -= xt * u.z;
+        e3 -= xt * u.w;
     }
+    double *ro = W.res64 + n * r + 4 * jb;
+    ro[0] = e0;
+    ro[1] = e1;
+    ro[2] = e2;
+    ro[3] = e3;
+    reinterpret_cast<float4 *>(W.res32 + n * r)[jb] = make_float4((float)e0, (float)e1, (float)e2, (float)e3);
 }
 
 hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k, int32_t *sel, float *x,
@@ -503,24 +696,36 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
         ProfileScope prof(KC_OTHER, s);
         omp_init_kernel<<<dim3((unsigned)N), 256, 0, s>>>(y, A.r, ws.words, ws.res64, ws.res32, ws.bitmap);
     }
-    const dim3 cgrid((unsigned)ws.tiles_m, (unsigned)((N + CORR_BN - 1) / CORR_BN));
-    const size_t smem = (((size_t)A.r * 4 + 15) & ~(size_t)15) + 2 * sizeof(double) * (size_t)k;
-    SelectArgs P{y, k, 0, sel, x, ws};
+    // tiling of the contraction (SGC_CORR_VARIANT overrides the choice, for tuning runs)
+    int variant = 0;
+    if (const char *env = getenv("SGC_CORR_VARIANT"))
+        variant = atoi(env);
+    OmpWorkspace wsv = ws;
+    wsv.tiles_m = (A.d + corr_variant_bm(variant) - 1) / corr_variant_bm(variant);
+    int slices = 2048 / N;
+    slices = slices < 1 ? 1 : (slices > 8 ? 8 : slices);
+    const dim3 pgrid((unsigned)N, (unsigned)slices);
+    const dim3 rgrid((unsigned)N, (unsigned)(((A.r >> 2) + RES_THREADS - 1) / RES_THREADS));
+    const size_t pick_smem = ((size_t)A.r * 4 + 15) & ~(size_t)15;
+    const size_t factor_smem = 2 * sizeof(double) * (size_t)k;
+    IterArgs P{y, k, 0, sel, x, wsv};
     for (int32_t it = 0; it < k; ++it) {
         P.it = it;
         {
             ProfileScope prof(KC_CORR, s);
-            if (A.generated)
-                corr_kernel<true><<<cgrid, CORR_THREADS, 0, s>>>(A, ws.res32, N, ws.bitmap, ws.words, ws.partial, ws.tiles_m);
-            else
-                corr_kernel<false><<<cgrid, CORR_THREADS, 0, s>>>(A, ws.res32, N, ws.bitmap, ws.words, ws.partial, ws.tiles_m);
+            const hipError_t e = A.generated ? corr_dispatch<true>(variant, A, ws.res32, N, wsv, wsv.tiles_m, s)
+                                             : corr_dispatch<false>(variant, A, ws.res32, N, wsv, wsv.tiles_m, s);
+            if (e != hipSuccess)
+                return e;
         }
         {
             ProfileScope prof(KC_SELECT, s);
             if (A.generated)
-                select_update_kernel<true><<<dim3((unsigned)N), SEL_THREADS, smem, s>>>(A, P);
+                pick_kernel<true><<<pgrid, PICK_THREADS, pick_smem, s>>>(A, P);
             else
-                select_update_kernel<false><<<dim3((unsigned)N), SEL_THREADS, smem, s>>>(A, P);
+                pick_kernel<false><<<pgrid, PICK_THREADS, pick_smem, s>>>(A, P);
+            factor_kernel<<<dim3((unsigned)N), k <= 128 ? 256 : FACTOR_MAX_THREADS, factor_smem, s>>>(P);
+            residual_kernel<<<rgrid, RES_THREADS, sizeof(double) * (size_t)(it + 1), s>>>(P, A.r);
         }
     }
     return hipGetLastError();

@@ -36,7 +36,8 @@ struct OmpWorkspace {
     float *cols;       // [N][k][r] selected columns of A
     uint64_t *partial; // [N][tiles_m][2] best and second-best packed (score, position) per tile
     uint32_t *bitmap;  // [N][words] selected positions
-    int32_t *cand;     // [N][2*tiles_m] candidate positions for re-scoring
+    double *wv;        // [N][k] inner products of the new column with the earlier selections
+    double *gb;        // [N][2] squared norm of the new column, its inner product with y
     int32_t words;     // bitmap words per right-hand side
     int32_t tiles_m;
     size_t bytes;
