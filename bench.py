@@ -108,7 +108,10 @@ def main():
     prof = sgc.sgc_profile_read()
     sgc.sgc_profile_enable(False)
     corr_ms, corr_n = prof["omp_corr"]
-    flops_per_launch = 2.0 * d * r * (2 * C)
+    fill_ms, _ = prof["omp_matrix_fill"]
+    # one launch covers all d positions (stored / in-kernel generated A) or one panel of them
+    launches_per_iter = corr_n / (K * k)
+    flops_per_launch = 2.0 * d * r * (2 * C) / launches_per_iter
     avg_ms = corr_ms / max(corr_n, 1)
     achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12
     roofline = {
@@ -117,6 +120,8 @@ def main():
         "frac": round(achieved / MFMA_F32_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC.get(w.name),
         "flops_per_launch": flops_per_launch, "avg_launch_ms": round(avg_ms, 5), "launches": corr_n,
     }
+    if fill_ms > 0:  # generated A produced by a separate fill kernel: the rate including that time
+        roofline["achieved_incl_matrix_fill"] = round(flops_per_launch * corr_n / ((corr_ms + fill_ms) * 1e-3) / 1e12, 3)
     kernels = {n: {"ms_per_step": round(ms / K, 4), "launches_per_step": cnt / K} for n, (ms, cnt) in prof.items()}
     # HBM-bound companions (algorithmic bytes / event time)
     bytes_adam = 32.0 * C * r

@@ -175,10 +175,11 @@ sgc_status sgc_apply(float *W, int64_t C, int32_t d, int32_t k, const int32_t *s
  *   sgc_profile_read waits for the recorded events, then fills `out` (host) with the summed
  *   duration in milliseconds and the launch count per kernel class, and clears the collection.
  * Kernel classes: 0 top-k, 1 projection, 2 Adam, 3 OMP correlation contraction, 4 OMP
- * select+update, 5 apply, 6 other (init, matrix helpers).
+ * select+update, 5 apply, 6 other (init, matrix helpers), 7 refill of the generated-matrix panel
+ * inside the OMP iterations.
  * Not thread-safe; meant for a single measuring thread. Errors: NULL, DEVICE.
  */
-enum { SGC_PROFILE_CLASSES = 7 };
+enum { SGC_PROFILE_CLASSES = 8 };
 typedef struct sgc_profile {
     double ms[SGC_PROFILE_CLASSES];
     int64_t launches[SGC_PROFILE_CLASSES];

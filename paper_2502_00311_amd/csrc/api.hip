@@ -17,6 +17,7 @@ MatrixView make_view(const sgc_matrix *A)
     v.key1 = (uint32_t)(A->seed >> 32);
     v.scale = (float)(1.0 / sqrt((double)A->r));
     v.generated = A->mode == SGC_MATRIX_PHILOX ? 1 : 0;
+    v.row0 = 0;
     return v;
 }
 

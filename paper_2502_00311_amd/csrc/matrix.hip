@@ -42,7 +42,7 @@ __global__ __launch_bounds__(256) void colnorm_kernel(MatrixView A, float *__res
 }
 
 hipError_t launch_matrix_fill(uint32_t key0, uint32_t key1, float scale, int32_t r, int64_t row0, int64_t rows,
-                              float *out, hipStream_t s)
+                              float *out, hipStream_t s, int profile_class)
 {
     if (rows == 0)
         return hipSuccess;
@@ -50,7 +50,7 @@ hipError_t launch_matrix_fill(uint32_t key0, uint32_t key1, float scale, int32_t
     int64_t blocks = (total + 255) / 256;
     if (blocks > 256 * 32)
         blocks = 256 * 32;
-    ProfileScope prof(KC_OTHER, s);
+    ProfileScope prof(profile_class, s);
     matrix_fill_kernel<<<dim3((unsigned)blocks), 256, 0, s>>>(key0, key1, scale, r, row0, rows, out);
     return hipGetLastError();
 }

@@ -42,6 +42,16 @@ OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_
     w.cols = (float *)take(sizeof(float) * (size_t)N * k * r);
     w.partial = (uint64_t *)take(sizeof(uint64_t) * (size_t)N * w.tiles_m * 2);
     w.bitmap = (uint32_t *)take(sizeof(uint32_t) * (size_t)N * w.words);
+    // panel of a generated matrix: at most 64 MiB (stays in the 256 MiB memory-side cache), whole tiles
+    {
+        int64_t rows = ((int64_t)64 << 20) / ((int64_t)r * 4);
+        rows = rows / 256 * 256;
+        if (rows < 256)
+            rows = 256;
+        const int64_t dpad = ((int64_t)d + 255) / 256 * 256;
+        w.panel_rows = (int32_t)(rows < dpad ? rows : dpad);
+        w.panel = (float *)take(sizeof(float) * (size_t)w.panel_rows * r);
+    }
     w.wv = (double *)take(sizeof(double) * (size_t)N * k);
     w.gb = (double *)take(sizeof(double) * (size_t)N * 2);
     w.bytes = off;
@@ -100,8 +110,9 @@ __global__ __launch_bounds__(WMW * WNW * 64, MINB) void corr_kernel(MatrixView A
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WNW, wn = wave % WNW;
     const int32_t d = A.d, r = A.r;
-    const int32_t m0 = blockIdx.x * BM;
+    const int32_t m0 = A.row0 + blockIdx.x * BM; // row0 is a multiple of BM
     const int32_t n0 = blockIdx.y * BN;
+    const float *At0 = A.At - (int64_t)A.row0 * r;
 
     float4 ga[LA], gb[LB];
     auto load_global = [&](int32_t k0) {
@@ -114,7 +125,7 @@ __global__ __launch_bounds__(WMW * WNW * 64, MINB) void corr_kernel(MatrixView A
                 if (GENERATED)
                     a = matrix_quad((uint32_t)i, (uint32_t)(kk >> 2), A.key0, A.key1, A.scale);
                 else
-                    a = *reinterpret_cast<const float4 *>(A.At + (int64_t)i * r + kk);
+                    a = *reinterpret_cast<const float4 *>(At0 + (int64_t)i * r + kk);
             }
             ga[u] = a;
         }
@@ -254,7 +265,7 @@ __global__ __launch_bounds__(WMW * WNW * 64, MINB) void corr_kernel(MatrixView A
                 top2_insert(red[(w * BN + tid) * 2], best, second);
                 top2_insert(red[(w * BN + tid) * 2 + 1], best, second);
             }
-            uint64_t *o = partial + ((int64_t)n * tiles_m + blockIdx.x) * 2;
+            uint64_t *o = partial + ((int64_t)n * tiles_m + m0 / BM) * 2;
             o[0] = best;
             o[1] = second;
         }
@@ -266,8 +277,8 @@ struct CorrShape {
     int bm, bn;
 };
 template <bool GENERATED, int BM, int BN, int BK, int WMW, int WNW, int MINB>
-static hipError_t corr_launch(const MatrixView &A, const float *R, int32_t N, const OmpWorkspace &ws, int32_t tiles_m,
-                              hipStream_t s)
+static hipError_t corr_launch(const MatrixView &A, int32_t rows, const float *R, int32_t N, const OmpWorkspace &ws,
+                              int32_t tiles_m, hipStream_t s)
 {
     constexpr size_t smem = (size_t)2 * (BM + BN) * (BK + 4) * sizeof(float);
     auto kern = corr_kernel<GENERATED, BM, BN, BK, WMW, WNW, MINB>;
@@ -279,7 +290,7 @@ static hipError_t corr_launch(const MatrixView &A, const float *R, int32_t N, co
             return e;
         raised = true;
     }
-    const dim3 grid((unsigned)tiles_m, (unsigned)((N + BN - 1) / BN));
+    const dim3 grid((unsigned)((rows + BM - 1) / BM), (unsigned)((N + BN - 1) / BN));
     kern<<<grid, WMW * WNW * 64, smem, s>>>(A, R, N, ws.bitmap, ws.words, ws.partial, tiles_m);
     return hipSuccess;
 }
@@ -293,16 +304,16 @@ static int corr_variant_bm(int variant)
     }
 }
 template <bool GENERATED>
-static hipError_t corr_dispatch(int variant, const MatrixView &A, const float *R, int32_t N, const OmpWorkspace &ws,
-                                int32_t tiles_m, hipStream_t s)
+static hipError_t corr_dispatch(int variant, const MatrixView &A, int32_t rows, const float *R, int32_t N,
+                                const OmpWorkspace &ws, int32_t tiles_m, hipStream_t s)
 {
     switch (variant) {
-    case 1: return corr_launch<GENERATED, 256, 128, 32, 4, 2, 1>(A, R, N, ws, tiles_m, s);
-    case 2: return corr_launch<GENERATED, 128, 128, 16, 2, 2, 2>(A, R, N, ws, tiles_m, s);
-    case 3: return corr_launch<GENERATED, 256, 128, 16, 4, 2, 2>(A, R, N, ws, tiles_m, s);
-    case 4: return corr_launch<GENERATED, 256, 128, 32, 2, 2, 1>(A, R, N, ws, tiles_m, s);
-    case 5: return corr_launch<GENERATED, 128, 128, 16, 2, 2, 3>(A, R, N, ws, tiles_m, s);
-    default: return corr_launch<GENERATED, 128, 128, 32, 2, 2, 2>(A, R, N, ws, tiles_m, s);
+    case 1: return corr_launch<GENERATED, 256, 128, 32, 4, 2, 1>(A, rows, R, N, ws, tiles_m, s);
+    case 2: return corr_launch<GENERATED, 128, 128, 16, 2, 2, 2>(A, rows, R, N, ws, tiles_m, s);
+    case 3: return corr_launch<GENERATED, 256, 128, 16, 4, 2, 2>(A, rows, R, N, ws, tiles_m, s);
+    case 4: return corr_launch<GENERATED, 256, 128, 32, 2, 2, 1>(A, rows, R, N, ws, tiles_m, s);
+    case 5: return corr_launch<GENERATED, 128, 128, 16, 2, 2, 3>(A, rows, R, N, ws, tiles_m, s);
+    default: return corr_launch<GENERATED, 128, 128, 32, 2, 2, 2>(A, rows, R, N, ws, tiles_m, s);
     }
 }
 
@@ -709,21 +720,48 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
     const size_t pick_smem = ((size_t)A.r * 4 + 15) & ~(size_t)15;
     const size_t factor_smem = 2 * sizeof(double) * (size_t)k;
     IterArgs P{y, k, 0, sel, x, wsv};
+    // A generated matrix is regenerated inside the contraction when few right-hand-side tiles share
+    // it; with many tiles (each would regenerate all of A) it is produced once per iteration, panel
+    // by panel, into a cache-sized scratch and consumed from there.
+    const bool panels = A.generated && (N + CORR_BN - 1) / CORR_BN >= 4;
+    MatrixView Apick = A; // the view pick_kernel fetches columns from
+    if (panels && ws.panel_rows >= A.d) {
+        Apick.generated = 0;
+        Apick.At = ws.panel;
+    }
     for (int32_t it = 0; it < k; ++it) {
         P.it = it;
         {
             ProfileScope prof(KC_CORR, s);
-            const hipError_t e = A.generated ? corr_dispatch<true>(variant, A, ws.res32, N, wsv, wsv.tiles_m, s)
-                                             : corr_dispatch<false>(variant, A, ws.res32, N, wsv, wsv.tiles_m, s);
+            hipError_t e = hipSuccess;
+            if (panels) {
+                for (int32_t p0 = 0; p0 < A.d && e == hipSuccess; p0 += ws.panel_rows) {
+                    const int32_t rows = A.d - p0 < ws.panel_rows ? A.d - p0 : ws.panel_rows;
+                    if (it == 0 || ws.panel_rows < A.d) { // a single panel holding all of A is filled once
+                        e = launch_matrix_fill(A.key0, A.key1, A.scale, A.r, p0, rows, ws.panel, s, KC_FILL);
+                        if (e != hipSuccess)
+                            break;
+                    }
+                    MatrixView Ap = A;
+                    Ap.generated = 0;
+                    Ap.At = ws.panel;
+                    Ap.row0 = p0;
+                    e = corr_dispatch<false>(variant, Ap, rows, ws.res32, N, wsv, wsv.tiles_m, s);
+                }
+            } else if (A.generated) {
+                e = corr_dispatch<true>(variant, A, A.d, ws.res32, N, wsv, wsv.tiles_m, s);
+            } else {
+                e = corr_dispatch<false>(variant, A, A.d, ws.res32, N, wsv, wsv.tiles_m, s);
+            }
             if (e != hipSuccess)
                 return e;
         }
         {
             ProfileScope prof(KC_SELECT, s);
-            if (A.generated)
-                pick_kernel<true><<<pgrid, PICK_THREADS, pick_smem, s>>>(A, P);
+            if (Apick.generated)
+                pick_kernel<true><<<pgrid, PICK_THREADS, pick_smem, s>>>(Apick, P);
             else
-                pick_kernel<false><<<pgrid, PICK_THREADS, pick_smem, s>>>(A, P);
+                pick_kernel<false><<<pgrid, PICK_THREADS, pick_smem, s>>>(Apick, P);
             factor_kernel<<<dim3((unsigned)N), k <= 128 ? 256 : FACTOR_MAX_THREADS, factor_smem, s>>>(P);
             residual_kernel<<<rgrid, RES_THREADS, sizeof(double) * (size_t)(it + 1), s>>>(P, A.r);
         }

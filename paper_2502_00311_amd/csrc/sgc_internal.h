@@ -16,6 +16,7 @@ struct MatrixView {
     uint32_t key0, key1; // Philox key
     float scale;         // (float)(1/sqrt((double)r))
     int32_t generated;   // 0 stored, 1 Philox
+    int32_t row0;        // position held by At[0] (non-zero for a panel of a generated matrix)
 };
 
 MatrixView make_view(const sgc_matrix *A);
@@ -38,11 +39,16 @@ struct OmpWorkspace {
     uint32_t *bitmap;  // [N][words] selected positions
     double *wv;        // [N][k] inner products of the new column with the earlier selections
     double *gb;        // [N][2] squared norm of the new column, its inner product with y
+    float *panel;      // [panel_rows][r] rows of a generated matrix, refilled every iteration
+    int32_t panel_rows; // multiple of 256
     int32_t words;     // bitmap words per right-hand side
     int32_t tiles_m;
     size_t bytes;
 };
 OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_t k);
+
+// kernel classes of the optional per-kernel timing (see profile.hip)
+enum KernelClass { KC_TOPK = 0, KC_PROJECT, KC_ADAM, KC_CORR, KC_SELECT, KC_APPLY, KC_OTHER, KC_FILL };
 
 // launchers (each returns hipGetLastError() of its launches)
 hipError_t launch_topk(const void *grad, int grad_type, int64_t C, int32_t d, int32_t k, int32_t *idx,
@@ -53,7 +59,7 @@ hipError_t launch_adam(const float *p, const float *q, float *m, float *v, float
                        int64_t count, float b1, float omb1, float b2, float omb2, float ibc1, float ibc2,
                        hipStream_t s);
 hipError_t launch_matrix_fill(uint32_t key0, uint32_t key1, float scale, int32_t r, int64_t row0,
-                              int64_t rows, float *out, hipStream_t s);
+                              int64_t rows, float *out, hipStream_t s, int profile_class = KC_OTHER);
 hipError_t launch_colnorms(const MatrixView &A, float *out, hipStream_t s);
 hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k, int32_t *sel, float *x,
                       const OmpWorkspace &ws, hipStream_t s);
@@ -62,7 +68,6 @@ hipError_t launch_apply(float *W, int64_t C, int32_t d, int32_t k, const int32_t
                         hipStream_t s);
 
 // ---- optional per-kernel timing (see profile.hip) ----
-enum KernelClass { KC_TOPK = 0, KC_PROJECT, KC_ADAM, KC_CORR, KC_SELECT, KC_APPLY, KC_OTHER };
 extern bool g_profile_on;
 void profile_begin(int cls, hipStream_t s);
 void profile_end(hipStream_t s);

@@ -22,7 +22,7 @@ EXPORTS = [
     "sgc_adam_compressed", "sgc_omp_workspace_bytes", "sgc_recover_omp", "sgc_apply",
     "sgc_profile_enable", "sgc_profile_read",
 ]
-PROFILE_CLASSES = ["topk", "project", "adam", "omp_corr", "omp_select_update", "apply", "other"]
+PROFILE_CLASSES = ["topk", "project", "adam", "omp_corr", "omp_select_update", "apply", "other", "omp_matrix_fill"]
 
 
 class sgc_matrix(ctypes.Structure):
@@ -38,7 +38,7 @@ class sgc_hyper(ctypes.Structure):
 
 
 class sgc_profile(ctypes.Structure):
-    _fields_ = [("ms", ctypes.c_double * 7), ("launches", ctypes.c_int64 * 7)]
+    _fields_ = [("ms", ctypes.c_double * 8), ("launches", ctypes.c_int64 * 8)]
 
 
 class SgcError(RuntimeError):

@@ -80,7 +80,8 @@ def run_topk_project(g, k, A):
 @pytest.mark.parametrize("C,d,k,r,mode", [
     (3, 1, 1, 4, "stored"), (4, 7, 3, 8, "stored"), (5, 1000, 17, 32, "philox"), (2, 4096, 32, 256, "stored"),
     (3, 5003, 256, 256, "stored"), (2, 16384, 64, 1024, "philox"), (2, 20001, 100, 128, "stored"),
-    (2, 65536, 256, 2048, "stored"),
+    (2, 65536, 256, 2048, "stored"), (2, 65537, 300, 512, "philox"), (1, 70001, 129, 256, "philox"),
+    (3, 16385, 64, 64, "philox"), (2, 4100, 4, 8, "philox"),
 ])
 def test_sparsify_project_matches_oracle(C, d, k, r, mode):
     say("sparsify_project", C, d, k, r, mode)
@@ -198,6 +199,25 @@ def test_omp_matches_oracle_on_noisy_right_hand_sides(N, d, r, k, mode):
     rsel, rx = orc.omp_batch(Y, At, k)
     assert np.array_equal(sel, rsel)
     assert rowwise_relerr(x, rx) < TOL
+
+
+@pytest.mark.parametrize("N,d,r,k", [
+    (600, 3000, 64, 6),      # many right-hand-side tiles: the generated matrix goes through one panel
+    (520, 2500, 8192, 3),    # long columns: two panels, the second one ragged
+])
+def test_omp_generated_matrix_with_many_right_hand_sides(N, d, r, k):
+    say("omp panels", N, d, r, k)
+    rng = np.random.default_rng(N + d)
+    A, At = make_matrix("philox", 33, d, r)
+    Y = rng.standard_normal((N, r)).astype(np.float32)
+    Y[7] = 0.0
+    sel, x = run_omp(Y, A, k)
+    norm = orc.colnorms(At)
+    for n in [0, 1, 7, 127, 128, 300, N - 2, N - 1]:   # the oracle checks a sample of the right-hand sides
+        ref = orc.omp(Y[n], At, k, norm=norm)
+        assert np.array_equal(sel[n], ref["sel"]), n
+        assert relerr(x[n], ref["x"]) < TOL
+    assert all(len(set(row.tolist())) == k for row in sel)
 
 
 def test_omp_exact_recovery_zero_and_oversized_k():
