@@ -57,9 +57,11 @@ __device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t v, uint32_t *w
     return v + add;
 }
 
+// General path: every pass re-reads the chunk from memory (L2 after the first pass). Works for any
+// chunk length and element type; also the fallback of the register-resident kernel.
 template <typename T, int THREADS>
-__global__ __launch_bounds__(THREADS) void topk_kernel(const T *__restrict__ g, int32_t d, int32_t k,
-                                                       int32_t *__restrict__ idx, float *__restrict__ val)
+__device__ __forceinline__ void topk_general(const T *__restrict__ gc, int32_t d, int32_t k,
+                                             int32_t *__restrict__ oidx, float *__restrict__ oval)
 {
     constexpr int NW = THREADS / 64;
     __shared__ uint32_t hist[2048];
@@ -68,9 +70,6 @@ __global__ __launch_bounds__(THREADS) void topk_kernel(const T *__restrict__ g, 
     __shared__ uint32_t w_gt[NW], w_eq[NW];
 
     const int tid = threadIdx.x;
-    const T *gc = g + (int64_t)blockIdx.x * d;
-    int32_t *oidx = idx + (int64_t)blockIdx.x * k;
-    float *oval = val + (int64_t)blockIdx.x * k;
 
     uint32_t prefix = 0;              // decided high bits of the threshold key
     uint32_t need = (uint32_t)k;      // entries still to take among keys that match the prefix
@@ -162,156 +161,173 @@ __global__ __launch_bounds__(THREADS) void topk_kernel(const T *__restrict__ g, 
     }
 }
 
-// Register-resident variant for float chunks of up to 16 * 4 * THREADS elements: the chunk is read
-// from HBM exactly once (16-byte loads, each wavefront owning a contiguous slice), the three radix
-// passes and the ordered emission run on registers. Positions at or beyond d are loaded as 0.0f:
-// such entries carry the smallest key and the largest positions, so they never change the k-th
-// largest key of the real entries and are never emitted.
-template <int THREADS>
-__global__ __launch_bounds__(THREADS) void topk_f32_regs_kernel(const float *__restrict__ g, int32_t d, int32_t k,
-                                                                int32_t *__restrict__ idx, float *__restrict__ val,
-                                                                int32_t vector_loads)
+template <typename T, int THREADS>
+__global__ __launch_bounds__(THREADS) void topk_kernel(const T *__restrict__ g, int32_t d, int32_t k,
+                                                       int32_t *__restrict__ idx, float *__restrict__ val)
 {
-    constexpr int NW = THREADS / 64, ROWS = 16;
-    __shared__ uint32_t hist[2048];
-    __shared__ uint32_t wave_tot[NW];
-    __shared__ uint32_t s_bin, s_need;
-    __shared__ uint32_t w_gt[NW], w_eq[NW];
+    topk_general<T, THREADS>(g + (int64_t)blockIdx.x * d, d, k, idx + (int64_t)blockIdx.x * k,
+                             val + (int64_t)blockIdx.x * k);
+}
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+constexpr uint32_t TOPK_CAND_CAP = 2048; // candidate entries kept in LDS
+
+// The kth largest of n sign-cleared keys held in LDS (any float bit patterns; the sign bit is
+// ignored), found by one wavefront: a bitwise binary search on the 31-bit key whose counts are
+// wavefront ballots. Also returns how many keys are larger than / equal to the result.
+__device__ __forceinline__ uint32_t wave_kth_largest(const uint32_t *keys, uint32_t n, uint32_t kth, uint32_t &gt,
+                                                     uint32_t &eq)
+{
+    const uint32_t lane = threadIdx.x & 63;
+    uint32_t thr = 0;
+    for (int bit = 30; bit >= 0; --bit) {
+        const uint32_t cand = thr | (1u << bit);
+        uint32_t cnt = 0;
+        for (uint32_t s0 = 0; s0 < n; s0 += 64) {
+            const uint32_t s = s0 + lane;
+            const bool ge = s < n && (keys[s] & 0x7fffffffu) >= cand;
+            cnt += (uint32_t)__popcll(__ballot(ge));
+        }
+        thr = cnt >= kth ? cand : thr;
+    }
+    gt = 0;
+    eq = 0;
+    for (uint32_t s0 = 0; s0 < n; s0 += 64) {
+        const uint32_t s = s0 + lane;
+        const uint32_t key = s < n ? (keys[s] & 0x7fffffffu) : 0u;
+        gt += (uint32_t)__popcll(__ballot(s < n && key > thr));
+        eq += (uint32_t)__popcll(__ballot(s < n && key == thr));
+    }
+    return thr;
+}
+
+// Register-resident variant for float chunks of up to 16 * 4 * THREADS elements with k <= THREADS:
+// the chunk is read from HBM once (16-byte loads, each wavefront owning a contiguous slice) and
+// stays in registers. A lower bound of the threshold comes from the k-th largest of the per-thread
+// maxima (at least k entries reach it); the entries that reach it - usually little more than k - go
+// to an LDS list, and the exact k-th largest key is selected on the list. Both selections are done
+// by one wavefront with ballots, so the path needs a handful of barriers. When the list overflows
+// or entries tie at the threshold (tie-breaking needs position order), the workgroup falls back to
+// the general path on the same chunk (then in L2); both paths compute the same unique result.
+// Positions at or beyond d are loaded as 0.0f: the smallest key, never inside the k largest unless
+// the threshold itself is 0, which is a tie case.
+template <int THREADS, int MINBLOCKS>
+__global__ __launch_bounds__(THREADS, MINBLOCKS) void topk_f32_regs_kernel(const float *__restrict__ g, int32_t d,
+                                                                          int32_t k, int32_t *__restrict__ idx,
+                                                                          float *__restrict__ val,
+                                                                          int32_t vector_loads)
+{
+    constexpr int ROWS = 16;
+    __shared__ uint32_t tmax_s[THREADS];
+    __shared__ float cand_val[TOPK_CAND_CAP];
+    __shared__ int32_t cand_pos[TOPK_CAND_CAP];
+    __shared__ uint32_t s_thr, s_need, s_ties, s_ncand;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6); // wavefront index, kept scalar
     const float *gc = g + (int64_t)blockIdx.x * d;
     int32_t *oidx = idx + (int64_t)blockIdx.x * k;
     float *oval = val + (int64_t)blockIdx.x * k;
-    const int32_t wbase = w * (ROWS * 256) + lane * 4; // element (j, e) of this lane sits at wbase + 256 j + e
-
-    float4 v[ROWS];
-#pragma unroll
-    for (int j = 0; j < ROWS; ++j) {
-        const int32_t i0 = wbase + j * 256;
-        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (vector_loads && i0 + 3 < d) {
-            t = *reinterpret_cast<const float4 *>(gc + i0);
-        } else {
-            if (i0 < d) t.x = gc[i0];
-            if (i0 + 1 < d) t.y = gc[i0 + 1];
-            if (i0 + 2 < d) t.z = gc[i0 + 2];
-            if (i0 + 3 < d) t.w = gc[i0 + 3];
-        }
-        v[j] = t;
-    }
+    const int32_t wslice = w * (ROWS * 256);  // first position of this wavefront's slice
+    const int32_t wbase = wslice + lane * 4;  // element (j, e) of this lane sits at wbase + 256 j + e
     auto key_of = [](float f) { return __float_as_uint(f) & 0x7fffffffu; };
 
-    uint32_t prefix = 0, need = (uint32_t)k;
-    for (int pass = 0; pass < 3; ++pass) {
-        const int shift = pass == 0 ? 20 : (pass == 1 ? 9 : 0);
-        const int bits = pass == 2 ? 9 : 11;
-        const int decided = pass == 0 ? 31 : (pass == 1 ? 20 : 9);
-        const int nb = 1 << bits;
-        for (int b = tid; b < nb; b += THREADS)
-            hist[b] = 0;
-        __syncthreads();
+    float4 v[ROWS];
+    if (vector_loads && wslice + ROWS * 256 <= d) {
+        // the whole slice is inside the chunk: plain 16-byte loads off one scalar base
+        const float4 *src = reinterpret_cast<const float4 *>(gc + wslice) + lane;
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j)
+            v[j] = src[j * 64];
+    } else {
 #pragma unroll
         for (int j = 0; j < ROWS; ++j) {
-            const float e4[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const uint32_t key = key_of(e4[e]);
-                if (pass == 0 || (key >> decided) == prefix)
-                    atomicAdd(&hist[(key >> shift) & (uint32_t)(nb - 1)], 1u);
+            const int32_t i0 = wbase + j * 256;
+            float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (vector_loads && i0 + 3 < d) {
+                t = *reinterpret_cast<const float4 *>(gc + i0);
+            } else {
+                if (i0 < d) t.x = gc[i0];
+                if (i0 + 1 < d) t.y = gc[i0 + 1];
+                if (i0 + 2 < d) t.z = gc[i0 + 2];
+                if (i0 + 3 < d) t.w = gc[i0 + 3];
             }
+            v[j] = t;
         }
-        __syncthreads();
-        const int per = (nb + THREADS - 1) / THREADS;
-        const int hi = nb - tid * per;
-        const int lo = hi - per < 0 ? 0 : hi - per;
-        uint32_t local = 0;
-        for (int b = hi - 1; b >= lo && b >= 0; --b)
-            local += hist[b];
-        const uint32_t incl = block_inclusive_scan<THREADS>(local, wave_tot);
-        const uint32_t excl = incl - local;
-        if (excl < need && need <= incl) {
-            uint32_t run = excl;
-            for (int b = hi - 1; b >= lo; --b) {
-                const uint32_t h = hist[b];
-                if (run + h >= need) {
-                    s_bin = (uint32_t)b;
-                    s_need = need - run;
-                    break;
-                }
-                run += h;
-            }
-        }
-        __syncthreads();
-        prefix = (prefix << bits) | s_bin;
-        need = s_need;
-        __syncthreads();
     }
-    const uint32_t thr = prefix;
-
-    // per-wavefront totals of keys above / equal to the threshold
-    uint32_t cgt = 0, ceq = 0;
+    uint32_t tmax = 0;
 #pragma unroll
     for (int j = 0; j < ROWS; ++j) {
-        const float e4[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const uint32_t key = key_of(e4[e]);
-            cgt += key > thr ? 1u : 0u;
-            ceq += key == thr ? 1u : 0u;
-        }
+        const uint32_t a = key_of(v[j].x), b = key_of(v[j].y), c = key_of(v[j].z), e = key_of(v[j].w);
+        const uint32_t ab = a > b ? a : b, ce = c > e ? c : e;
+        const uint32_t m = ab > ce ? ab : ce;
+        tmax = m > tmax ? m : tmax;
     }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        cgt += __shfl_xor(cgt, off, 64);
-        ceq += __shfl_xor(ceq, off, 64);
-    }
-    if (lane == 0) {
-        w_gt[w] = cgt;
-        w_eq[w] = ceq;
+    tmax_s[tid] = tmax;
+    if (tid == 0)
+        s_ncand = 0;
+    __syncthreads();
+    if (w == 0) {
+        uint32_t gt, eq;
+        const uint32_t bound = wave_kth_largest(tmax_s, THREADS, (uint32_t)k, gt, eq);
+        if (lane == 0)
+            s_thr = bound;
     }
     __syncthreads();
-    uint32_t run_gt = 0, run_eq = 0;
-    for (int u = 0; u < w; ++u) {
-        run_gt += w_gt[u];
-        run_eq += w_eq[u];
-    }
-    // ordered emission: position order inside the slice is (row j, lane, e)
+    const uint32_t bound = s_thr;
 #pragma unroll
     for (int j = 0; j < ROWS; ++j) {
         const float e4[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
-        bool gt[4], eq[4];
-        bool any = false;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const uint32_t key = key_of(e4[e]);
-            gt[e] = key > thr;
-            eq[e] = key == thr;
-            any = any || gt[e] || eq[e];
-        }
-        if (__ballot(any) == 0ull)
+        const bool h0 = key_of(e4[0]) >= bound, h1 = key_of(e4[1]) >= bound, h2 = key_of(e4[2]) >= bound,
+                   h3 = key_of(e4[3]) >= bound;
+        if (__ballot(h0 || h1 || h2 || h3) == 0ull)
             continue;
-        uint32_t gt_before = run_gt, eq_before = run_eq, tot_gt = 0, tot_eq = 0;
+        const bool hit[4] = {h0, h1, h2, h3};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const uint64_t bg = __ballot(gt[e]), be = __ballot(eq[e]);
-            gt_before += __builtin_amdgcn_mbcnt_hi((uint32_t)(bg >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bg, 0u));
-            eq_before += __builtin_amdgcn_mbcnt_hi((uint32_t)(be >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)be, 0u));
-            tot_gt += (uint32_t)__popcll(bg);
-            tot_eq += (uint32_t)__popcll(be);
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            if (gt[e] || (eq[e] && eq_before < need)) {
-                const uint32_t slot = gt_before + (eq_before < need ? eq_before : need);
-                oidx[slot] = wbase + j * 256 + e;
-                oval[slot] = e4[e];
+            const uint64_t bh = __ballot(hit[e]);
+            if (bh == 0ull)
+                continue;
+            uint32_t base = 0;
+            if (lane == 0)
+                base = atomicAdd(&s_ncand, (uint32_t)__popcll(bh));
+            base = __builtin_amdgcn_readfirstlane(base);
+            const uint32_t mine = base + __builtin_amdgcn_mbcnt_hi((uint32_t)(bh >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bh, 0u));
+            if (hit[e] && mine < TOPK_CAND_CAP) {
+                cand_val[mine] = e4[e];
+                cand_pos[mine] = wbase + j * 256 + e;
             }
-            gt_before += gt[e] ? 1u : 0u;
-            eq_before += eq[e] ? 1u : 0u;
         }
-        run_gt += tot_gt;
-        run_eq += tot_eq;
     }
+    __syncthreads();
+    const uint32_t nc = s_ncand;
+    const bool listed = nc <= TOPK_CAND_CAP;
+    if (listed && w == 0) {
+        uint32_t gt, eq;
+        const uint32_t t = wave_kth_largest(reinterpret_cast<const uint32_t *>(cand_val), nc, (uint32_t)k, gt, eq);
+        if (lane == 0) {
+            s_thr = t;
+            s_need = (uint32_t)k - gt;
+            s_ties = eq;
+        }
+    }
+    __syncthreads();
+    if (listed && s_ties == s_need) {
+        // exactly k listed entries have key >= thr: each goes to its rank by position
+        const uint32_t thr = s_thr;
+        for (uint32_t t = tid; t < nc; t += THREADS) {
+            const float mine_val = cand_val[t];
+            if (key_of(mine_val) < thr)
+                continue;
+            const int32_t mine = cand_pos[t];
+            int32_t rank = 0;
+            for (uint32_t u = 0; u < nc; ++u)
+                rank += (key_of(cand_val[u]) >= thr && cand_pos[u] < mine) ? 1 : 0;
+            oidx[rank] = mine;
+            oval[rank] = mine_val;
+        }
+        return;
+    }
+    topk_general<float, THREADS>(gc, d, k, oidx, oval);
 }
 
 hipError_t launch_topk(const void *grad, int grad_type, int64_t C, int32_t d, int32_t k, int32_t *idx,
@@ -323,10 +339,10 @@ hipError_t launch_topk(const void *grad, int grad_type, int64_t C, int32_t d, in
     ProfileScope prof(KC_TOPK, s);
     if (grad_type == SGC_GRAD_F32) {
         const int32_t vec = (d % 4 == 0) ? 1 : 0; // every chunk then starts 16-byte aligned
-        if (d <= 16 * 4 * 256)
-            topk_f32_regs_kernel<256><<<grid, 256, 0, s>>>((const float *)grad, d, k, idx, val, vec);
-        else if (d <= 16 * 4 * 1024)
-            topk_f32_regs_kernel<1024><<<grid, 1024, 0, s>>>((const float *)grad, d, k, idx, val, vec);
+        if (d <= 16 * 4 * 256 && k <= 256)
+            topk_f32_regs_kernel<256, 5><<<grid, 256, 0, s>>>((const float *)grad, d, k, idx, val, vec);
+        else if (d <= 16 * 4 * 1024 && k <= 1024)
+            topk_f32_regs_kernel<1024, 1><<<grid, 1024, 0, s>>>((const float *)grad, d, k, idx, val, vec);
         else
             topk_kernel<float, 1024><<<grid, 1024, 0, s>>>((const float *)grad, d, k, idx, val);
     } else {
