@@ -1,0 +1,112 @@
+"""Parity at the full sizes of the benchmark configurations, in the launch configuration bench.py
+times. The oracle cannot run a whole recovery at these sizes, so it checks sampled outputs one by
+one: top-k on sampled chunks, projections and moments on all or sampled chunks, single OMP picks
+by replaying the GPU's own prefix (the pick must be the oracle's argmax given that prefix), the
+least-squares values on the final support, and the weight update from the GPU's recovered vectors."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2502_00311_amd import sgc, synth
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4
+DEV = "cuda"
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def relerr(a, ref):
+    a = np.asarray(a, np.float64)
+    ref = np.asarray(ref, np.float64)
+    den = np.abs(ref).max()
+    return float(np.abs(a - ref).max() / (den if den > 0 else 1.0))
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def run_and_check(w, steps, chunk_sample, pick_sample):
+    """pick_sample: list of (rhs index in [0, 2C), iteration j) pairs replayed in the oracle."""
+    C, d, r, k = w.C, w.d, w.r, w.k
+    say(w.name, "C", C, "d", d, "r", r, "k", k)
+    if w.matrix == "stored":
+        At = synth.gaussian_matrix(w.a_seed, d, r)
+        A = sgc.Matrix(d, r, At=dev(At))
+    else:
+        At = orc.philox_matrix(w.a_seed, d, r)
+        A = sgc.Matrix(d, r, At=None, seed=w.a_seed)
+    A.inv_colnorm = torch.empty(d, dtype=torch.float32, device=DEV)
+    sgc.sgc_matrix_colnorms(A, A.inv_colnorm)
+    norm = orc.colnorms(At)
+    buf = sgc.StepBuffers(C, d, r, k)
+    W = dev(synth.weights(w))
+    h = sgc.hyper()
+    m_prev = np.zeros((C, r), np.float32)
+    v_prev = np.zeros((C, r), np.float32)
+    for t in range(1, steps + 1):
+        say("  step", t, "generate")
+        g = synth.gradients(w, t)
+        W_prev = W.cpu().numpy()
+        sgc.step(dev(g.view(np.int16) if w.grad == "bf16" else g), W, buf, A, t, h)
+        torch.cuda.synchronize()
+        idx, val = buf.idx.cpu().numpy(), buf.val.cpu().numpy()
+        p, q = buf.p.cpu().numpy(), buf.q.cpu().numpy()
+        m, v = buf.m.cpu().numpy(), buf.v.cpu().numpy()
+        hat = buf.hat.cpu().numpy()
+        sel, x = buf.sel.cpu().numpy(), buf.x.cpu().numpy()
+        # a1/a2 on sampled chunks
+        say("  top-k / projection on", len(chunk_sample), "chunks")
+        ridx, rval = orc.topk(g[chunk_sample], k)
+        assert np.array_equal(idx[chunk_sample], ridx)
+        assert np.array_equal(val[chunk_sample].view(np.uint32), rval.view(np.uint32))
+        rp, rq = orc.project(ridx, rval, At)
+        for o, c in enumerate(chunk_sample):
+            assert relerr(p[c], rp[o]) < TOL and relerr(q[c], rq[o]) < TOL
+        # a3 on everything (elementwise, cheap)
+        rm, rv, rmh, rvh = orc.adam(p, q, m_prev, v_prev, t)
+        assert relerr(m, rm) < 1e-6 and relerr(v, rv) < 1e-6
+        assert relerr(hat[:C], rmh) < 1e-6 and relerr(hat[C:], rvh) < 1e-6
+        # a4: every selection is a set of distinct valid positions
+        assert sel.min() >= 0 and sel.max() < d
+        srt = np.sort(sel, axis=1)
+        assert (srt[:, 1:] != srt[:, :-1]).all()
+        # a4: sampled single picks, replaying the GPU's own prefix in the oracle
+        for n, j in pick_sample:
+            rep = orc.omp(hat[n], At, j + 1, norm=norm, forced=sel[n, :j])
+            assert rep["sel"][j] == sel[n, j], "rhs %d pick %d: gpu %d oracle %d" % (n, j, sel[n, j], rep["sel"][j])
+        # a4: least-squares values on the full support for two right-hand sides
+        for n in sorted({ps[0] for ps in pick_sample})[:2]:
+            rep = orc.omp(hat[n], At, k, norm=norm, forced=sel[n])
+            assert relerr(x[n], rep["x"]) < TOL
+        # a5 from the GPU's recovered vectors
+        rW = orc.apply(W_prev, d, sel[:C], x[:C], sel[C:], x[C:])
+        Wn = W.cpu().numpy()
+        dW, rdW = (Wn - W_prev).reshape(C, d), (rW - W_prev).reshape(C, d)
+        for c in chunk_sample:
+            assert relerr(dW[c], rdW[c]) < TOL
+        assert np.array_equal(Wn[rW == W_prev], W_prev[rW == W_prev])
+        m_prev, v_prev = m, v
+
+
+def test_cfg2_full_size_two_steps():
+    w = synth.CFG2
+    picks = [(0, 0), (5, 1), (64, 17), (127, 100), (31, 255), (100, 200)]
+    run_and_check(w, 2, list(range(0, w.C, 7)), picks)
+
+
+def test_cfg3_full_size():
+    w = synth.CFG3
+    picks = [(0, 0), (1023, 5), (1024, 63), (2047, 40), (777, 63)]
+    run_and_check(w, 1, list(range(0, w.C, 101)), picks)
+
+
+def test_cfg4_full_size():
+    w = synth.CFG4
+    C = w.C
+    picks = [(0, 0), (C - 1, 63), (C, 10), (2 * C - 1, 63), (9000, 31), (C + 4321, 50)]
+    run_and_check(w, 1, list(range(0, C, 997)), picks)
