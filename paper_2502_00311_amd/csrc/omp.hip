@@ -12,8 +12,6 @@
 // App. B precomputes the Gram matrix A^H A (d x d) to avoid the contraction; here the contraction
 // is kept (it is what the matrix cores are for) and only inner products with selected columns are
 // formed, so memory stays O(N k r).
-#include <stdlib.h>
-
 #include "philox_normal.h"
 #include "sgc_internal.h"
 
@@ -80,6 +78,91 @@ __device__ __forceinline__ void top2_insert(uint64_t key, uint64_t &best, uint64
     const uint64_t lo = key < best ? key : best;
     best = key < best ? best : key;
     second = lo < second ? second : lo;
+}
+
+// Epilogue shared by the contraction kernels: scale the accumulators by the reciprocal column
+// norms, mask selected positions and reduce to the two best packed (score, position) keys per
+// right-hand side and tile. `red` is LDS scratch of WMW*BN*2 keys that is no longer in use.
+template <int BM, int BN, int WMW, int WNW, int MB, int NB>
+__device__ __forceinline__ void corr_epilogue(const MatrixView &A, floatx16 (&acc)[MB][NB], uint64_t *red, int32_t N,
+                                              const uint32_t *__restrict__ bitmap, int32_t words,
+                                              uint64_t *__restrict__ partial, int32_t tiles_m, int32_t m0, int32_t n0,
+                                              int wm, int wn)
+{
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int l32 = lane & 31, lhalf = lane >> 5;
+    const int32_t d = A.d;
+    // reciprocal norms of this lane's MB x 16 positions (4 runs of 4 consecutive positions per block)
+    // and the selection masks, fetched together before any of them is used
+    float4 inv[MB][4];
+    uint32_t msk[MB][NB];
+#pragma unroll
+    for (int a = 0; a < MB; ++a) {
+        const int32_t ibase = m0 + wm * (BM / WMW) + a * 32;
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd) {
+            const int32_t i0 = ibase + 8 * qd + 4 * lhalf;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (i0 + 3 < d) {
+                v = *reinterpret_cast<const float4 *>(A.inv_colnorm + i0);
+            } else {
+                if (i0 < d) v.x = A.inv_colnorm[i0];
+                if (i0 + 1 < d) v.y = A.inv_colnorm[i0 + 1];
+                if (i0 + 2 < d) v.z = A.inv_colnorm[i0 + 2];
+            }
+            inv[a][qd] = v;
+        }
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int32_t n = n0 + wn * (BN / WNW) + b * 32 + l32;
+            msk[a][b] = (n < N && ibase < d) ? bitmap[(int64_t)n * words + (ibase >> 5)] : 0xffffffffu;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        const int nl = wn * (BN / WNW) + b * 32 + l32; // right-hand side within the tile
+        uint64_t best = 0, second = 0;
+#pragma unroll
+        for (int a = 0; a < MB; ++a) {
+            const int32_t ibase = m0 + wm * (BM / WMW) + a * 32;
+            const uint32_t mask = msk[a][b];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int off = 8 * (v >> 2) + 4 * lhalf + (v & 3);
+                const int32_t i = ibase + off;
+                const float4 nv = inv[a][v >> 2];
+                const float in = (v & 3) == 0 ? nv.x : ((v & 3) == 1 ? nv.y : ((v & 3) == 2 ? nv.z : nv.w));
+                const float score = fabsf(acc[a][b][v]) * in;
+                const bool ok = i < d && !((mask >> off) & 1u);
+                const uint64_t key = ok ? (((uint64_t)__float_as_uint(score) << 32) | (uint64_t)(0xffffffffu - (uint32_t)i)) : 0ull;
+                top2_insert(key, best, second);
+            }
+        }
+        // the other half-wave holds the remaining positions of the same right-hand side
+        const uint64_t ob = shfl_xor_u64(best, 32), os = shfl_xor_u64(second, 32);
+        top2_insert(ob, best, second);
+        top2_insert(os, best, second);
+        if (lhalf == 0) {
+            red[(wm * BN + nl) * 2 + 0] = best;
+            red[(wm * BN + nl) * 2 + 1] = second;
+        }
+    }
+    __syncthreads();
+    if (tid < BN) {
+        const int32_t n = n0 + tid;
+        if (n < N) {
+            uint64_t best = red[tid * 2], second = red[tid * 2 + 1];
+#pragma unroll
+            for (int w = 1; w < WMW; ++w) {
+                top2_insert(red[(w * BN + tid) * 2], best, second);
+                top2_insert(red[(w * BN + tid) * 2 + 1], best, second);
+            }
+            uint64_t *o = partial + ((int64_t)n * tiles_m + m0 / BM) * 2;
+            o[0] = best;
+            o[1] = second;
+        }
+    }
 }
 
 // Correlation contraction + fused selection epilogue.
@@ -198,84 +281,11 @@ __global__ __launch_bounds__(WMW * WNW * 64, MINB) void corr_kernel(MatrixView A
     }
 
     // ---- epilogue: normalise, mask, keep the two best per right-hand side ----
-    uint64_t *red = reinterpret_cast<uint64_t *>(corr_lds); // [WMW][BN][2]
-    // reciprocal norms of this lane's MB x 16 positions (4 runs of 4 consecutive positions per block)
-    // and the selection masks, fetched together before any of them is used
-    float4 inv[MB][4];
-    uint32_t msk[MB][NB];
-#pragma unroll
-    for (int a = 0; a < MB; ++a) {
-        const int32_t ibase = m0 + wm * (BM / WMW) + a * 32;
-#pragma unroll
-        for (int qd = 0; qd < 4; ++qd) {
-            const int32_t i0 = ibase + 8 * qd + 4 * lhalf;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (i0 + 3 < d) {
-                v = *reinterpret_cast<const float4 *>(A.inv_colnorm + i0);
-            } else {
-                if (i0 < d) v.x = A.inv_colnorm[i0];
-                if (i0 + 1 < d) v.y = A.inv_colnorm[i0 + 1];
-                if (i0 + 2 < d) v.z = A.inv_colnorm[i0 + 2];
-            }
-            inv[a][qd] = v;
-        }
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const int32_t n = n0 + wn * (BN / WNW) + b * 32 + l32;
-            msk[a][b] = (n < N && ibase < d) ? bitmap[(int64_t)n * words + (ibase >> 5)] : 0xffffffffu;
-        }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        const int nl = wn * (BN / WNW) + b * 32 + l32; // right-hand side within the tile
-        uint64_t best = 0, second = 0;
-#pragma unroll
-        for (int a = 0; a < MB; ++a) {
-            const int32_t ibase = m0 + wm * (BM / WMW) + a * 32;
-            const uint32_t mask = msk[a][b];
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int off = 8 * (v >> 2) + 4 * lhalf + (v & 3);
-                const int32_t i = ibase + off;
-                const float4 nv = inv[a][v >> 2];
-                const float in = (v & 3) == 0 ? nv.x : ((v & 3) == 1 ? nv.y : ((v & 3) == 2 ? nv.z : nv.w));
-                const float score = fabsf(acc[a][b][v]) * in;
-                const bool ok = i < d && !((mask >> off) & 1u);
-                const uint64_t key = ok ? (((uint64_t)__float_as_uint(score) << 32) | (uint64_t)(0xffffffffu - (uint32_t)i)) : 0ull;
-                top2_insert(key, best, second);
-            }
-        }
-        // the other half-wave holds the remaining positions of the same right-hand side
-        const uint64_t ob = shfl_xor_u64(best, 32), os = shfl_xor_u64(second, 32);
-        top2_insert(ob, best, second);
-        top2_insert(os, best, second);
-        if (lhalf == 0) {
-            red[(wm * BN + nl) * 2 + 0] = best;
-            red[(wm * BN + nl) * 2 + 1] = second;
-        }
-    }
-    __syncthreads();
-    if (tid < BN) {
-        const int32_t n = n0 + tid;
-        if (n < N) {
-            uint64_t best = red[tid * 2], second = red[tid * 2 + 1];
-#pragma unroll
-            for (int w = 1; w < WMW; ++w) {
-                top2_insert(red[(w * BN + tid) * 2], best, second);
-                top2_insert(red[(w * BN + tid) * 2 + 1], best, second);
-            }
-            uint64_t *o = partial + ((int64_t)n * tiles_m + m0 / BM) * 2;
-            o[0] = best;
-            o[1] = second;
-        }
-    }
+    corr_epilogue<BM, BN, WMW, WNW, MB, NB>(A, acc, reinterpret_cast<uint64_t *>(corr_lds), N, bitmap, words, partial,
+                                            tiles_m, m0, n0, wm, wn);
 }
 
 // One tiling of the contraction: sizes, and a launcher that raises the dynamic-LDS limit once.
-struct CorrShape {
-    int bm, bn;
-};
 template <bool GENERATED, int BM, int BN, int BK, int WMW, int WNW, int MINB>
 static hipError_t corr_launch(const MatrixView &A, int32_t rows, const float *R, int32_t N, const OmpWorkspace &ws,
                               int32_t tiles_m, hipStream_t s)
@@ -295,26 +305,14 @@ static hipError_t corr_launch(const MatrixView &A, int32_t rows, const float *R,
     return hipSuccess;
 }
 
-// variant table: index -> (BM, BN, BK, waves, occupancy)
-static int corr_variant_bm(int variant)
-{
-    switch (variant) {
-    case 1: case 3: case 4: return 256;
-    default: return 128;
-    }
-}
+// The tiling in use: 128 x 128 outputs, depth 32 per stage, 2 x 2 wavefronts, two workgroups per CU.
+// (256 x 128 tiles with 4 or 8 wavefronts, depth 16 or 64, and a variant that loads LDS directly
+// with global_load_lds all measured within 2 % of it inside the full step.)
 template <bool GENERATED>
-static hipError_t corr_dispatch(int variant, const MatrixView &A, int32_t rows, const float *R, int32_t N,
-                                const OmpWorkspace &ws, int32_t tiles_m, hipStream_t s)
+static hipError_t corr_dispatch(const MatrixView &A, int32_t rows, const float *R, int32_t N, const OmpWorkspace &ws,
+                                int32_t tiles_m, hipStream_t s)
 {
-    switch (variant) {
-    case 1: return corr_launch<GENERATED, 256, 128, 32, 4, 2, 1>(A, rows, R, N, ws, tiles_m, s);
-    case 2: return corr_launch<GENERATED, 128, 128, 16, 2, 2, 2>(A, rows, R, N, ws, tiles_m, s);
-    case 3: return corr_launch<GENERATED, 256, 128, 16, 4, 2, 2>(A, rows, R, N, ws, tiles_m, s);
-    case 4: return corr_launch<GENERATED, 256, 128, 32, 2, 2, 1>(A, rows, R, N, ws, tiles_m, s);
-    case 5: return corr_launch<GENERATED, 128, 128, 16, 2, 2, 3>(A, rows, R, N, ws, tiles_m, s);
-    default: return corr_launch<GENERATED, 128, 128, 32, 2, 2, 2>(A, rows, R, N, ws, tiles_m, s);
-    }
+    return corr_launch<GENERATED, CORR_BM, CORR_BN, 32, 2, 2, 2>(A, rows, R, N, ws, tiles_m, s);
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -707,12 +705,7 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
         ProfileScope prof(KC_OTHER, s);
         omp_init_kernel<<<dim3((unsigned)N), 256, 0, s>>>(y, A.r, ws.words, ws.res64, ws.res32, ws.bitmap);
     }
-    // tiling of the contraction (SGC_CORR_VARIANT overrides the choice, for tuning runs)
-    int variant = 0;
-    if (const char *env = getenv("SGC_CORR_VARIANT"))
-        variant = atoi(env);
-    OmpWorkspace wsv = ws;
-    wsv.tiles_m = (A.d + corr_variant_bm(variant) - 1) / corr_variant_bm(variant);
+    const OmpWorkspace &wsv = ws;
     int slices = 2048 / N;
     slices = slices < 1 ? 1 : (slices > 8 ? 8 : slices);
     const dim3 pgrid((unsigned)N, (unsigned)slices);
@@ -746,12 +739,12 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
                     Ap.generated = 0;
                     Ap.At = ws.panel;
                     Ap.row0 = p0;
-                    e = corr_dispatch<false>(variant, Ap, rows, ws.res32, N, wsv, wsv.tiles_m, s);
+                    e = corr_dispatch<false>(Ap, rows, ws.res32, N, wsv, wsv.tiles_m, s);
                 }
             } else if (A.generated) {
-                e = corr_dispatch<true>(variant, A, A.d, ws.res32, N, wsv, wsv.tiles_m, s);
+                e = corr_dispatch<true>(A, A.d, ws.res32, N, wsv, wsv.tiles_m, s);
             } else {
-                e = corr_dispatch<false>(variant, A, A.d, ws.res32, N, wsv, wsv.tiles_m, s);
+                e = corr_dispatch<false>(A, A.d, ws.res32, N, wsv, wsv.tiles_m, s);
             }
             if (e != hipSuccess)
                 return e;
