@@ -12,6 +12,8 @@
 // App. B precomputes the Gram matrix A^H A (d x d) to avoid the contraction; here the contraction
 // is kept (it is what the matrix cores are for) and only inner products with selected columns are
 // formed, so memory stays O(N k r).
+#include <type_traits>
+
 #include "philox_normal.h"
 #include "sgc_internal.h"
 
@@ -303,6 +305,215 @@ static hipError_t corr_launch(const MatrixView &A, int32_t rows, const float *R,
     const dim3 grid((unsigned)((rows + BM - 1) / BM), (unsigned)((N + BN - 1) / BN));
     kern<<<grid, WMW * WNW * 64, smem, s>>>(A, R, N, ws.bitmap, ws.words, ws.partial, tiles_m);
     return hipSuccess;
+}
+
+// Software-pipelined contraction for full tiles of a stored matrix (rows % 256 == 0, N % 128 == 0,
+// r % 64 == 0): 256 x 128 outputs per workgroup, one wavefront per SIMD, each wavefront a 128 x 64
+// sub-tile (4 x 2 MFMA blocks, accumulators in AGPRs). A depth-32 stage is 4 groups of 32 MFMAs;
+// every memory operation is issued in the shadow of an MFMA and the order is pinned:
+//   group 0..2  fragment reads of the next group (double-buffered in registers)
+//   group 2     LDS writes of the staged next stage (into the stage read one iteration earlier)
+//   barrier
+//   group 3     fragment reads of the next stage's first group; global loads two stages ahead
+// so the matrix pipe only waits for the barrier itself. Addresses are a uniform base plus one per-lane
+// offset (no per-row bounds checks: tiles are full), and the depth loop is unrolled by two so that
+// LDS stage offsets are immediates.
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+constexpr int CORRP_BM = 256, CORRP_BN = 128;
+
+__global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, const float *__restrict__ R, int32_t N,
+                                                                const uint32_t *__restrict__ bitmap, int32_t words,
+                                                                uint64_t *__restrict__ partial, int32_t tiles_m)
+{
+    constexpr int BM = CORRP_BM, BN = CORRP_BN, BK = 32, LD = BK + 4, MB = 4, NB = 2;
+    constexpr int LA = 8, LB = 4; // 16-byte pieces per thread per stage
+    typedef float floatx4 __attribute__((ext_vector_type(4)));
+    extern __shared__ __attribute__((aligned(16))) float corr_lds[];
+    float *lds = corr_lds; // A stages [2][BM*LD], then R stages [2][BN*LD]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int32_t r = A.r;
+    const int32_t m0 = A.row0 + blockIdx.x * BM, n0 = blockIdx.y * BN;
+    const int l32 = lane & 31, lhalf = lane >> 5;
+    const float *abase = A.At + (int64_t)(blockIdx.x * BM) * r;
+    const float *bbase = R + (int64_t)n0 * r;
+    const uint32_t lane_off = (uint32_t)((tid >> 3) * r + ((tid & 7) << 2));
+    const int ldst0 = (tid >> 3) * LD + ((tid & 7) << 2);
+    const int nkb = r / BK;
+
+    floatx4 g[LA + LB];
+    floatx4 fa[2][MB], fb[2][NB];
+    floatx16 acc[MB][NB];
+#pragma unroll
+    for (int a = 0; a < MB; ++a)
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                acc[a][b][v] = 0.f;
+    const int ra = (wm * 128 + l32) * LD + lhalf * 4; // fragment read offsets (floats)
+    const int rb = 2 * BM * LD + (wn * 64 + l32) * LD + lhalf * 4;
+
+    auto gload = [&](int u, int kb) { // staging piece u of stage kb (the last stage again beyond the end)
+        const int kk = (kb < nkb ? kb : nkb - 1) * BK;
+        const float *p = u < LA ? abase + ((int64_t)(32 * u) * r + kk) : bbase + ((int64_t)(32 * (u - LA)) * r + kk);
+        g[u] = *reinterpret_cast<const floatx4 *>(p + lane_off);
+    };
+    auto lwrite = [&](int u, int buf) {
+        const int off = u < LA ? buf * BM * LD + 32 * u * LD : 2 * BM * LD + buf * BN * LD + 32 * (u - LA) * LD;
+        *reinterpret_cast<floatx4 *>(lds + ldst0 + off) = g[u];
+    };
+    auto fread = [&](int which, int op, int buf, int ks) { // op 0..3: block row of At, 4..5: block of R
+        if (op < MB)
+            fa[which][op] = *reinterpret_cast<const floatx4 *>(lds + ra + buf * BM * LD + op * 32 * LD + ks * 8);
+        else
+            fb[which][op - MB] = *reinterpret_cast<const floatx4 *>(lds + rb + buf * BN * LD + (op - MB) * 32 * LD + ks * 8);
+    };
+    auto mfma = [&](int which, int m) { // m = 0..31: depth t = m / 8 of the fragment, block (m % 8) / 2, m % 2
+        const int t = m >> 3, a = (m & 7) >> 1, b = m & 1;
+        const floatx4 x4 = fa[which][a], y4 = fb[which][b];
+        const float x = t == 0 ? x4.x : (t == 1 ? x4.y : (t == 2 ? x4.z : x4.w));
+        const float y = t == 0 ? y4.x : (t == 1 ? y4.y : (t == 2 ? y4.z : y4.w));
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(x, y, acc[a][b], 0, 0, 0);
+    };
+
+    // prologue: stage 0 -> LDS, stage 1 -> staging registers, fragments of (stage 0, group 0)
+    static_for<0, LA + LB>([&](auto uc) { gload(decltype(uc)::value, 0); });
+    static_for<0, LA + LB>([&](auto uc) { lwrite(decltype(uc)::value, 0); });
+    static_for<0, LA + LB>([&](auto uc) { gload(decltype(uc)::value, 1); });
+    __syncthreads();
+    static_for<0, MB + NB>([&](auto oc) { fread(0, decltype(oc)::value, 0, 0); });
+
+    auto stage = [&](int kb, auto bufc) {
+        constexpr int buf = decltype(bufc)::value;
+        static_for<0, 32>([&](auto mc) {
+            constexpr int m = decltype(mc)::value;
+            mfma(0, m);
+            if constexpr (m < MB + NB)
+                fread(1, m, buf, 1);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        static_for<0, 32>([&](auto mc) {
+            constexpr int m = decltype(mc)::value;
+            mfma(1, m);
+            if constexpr (m < MB + NB)
+                fread(0, m, buf, 2);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        static_for<0, 32>([&](auto mc) {
+            constexpr int m = decltype(mc)::value;
+            mfma(0, m);
+            if constexpr (m < MB + NB)
+                fread(1, m, buf, 3);
+            else if constexpr (m >= 8 && m < 8 + LA + LB)
+                lwrite(m - 8, buf ^ 1);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        __syncthreads();
+        static_for<0, 32>([&](auto mc) {
+            constexpr int m = decltype(mc)::value;
+            mfma(1, m);
+            if constexpr (m < MB + NB)
+                fread(0, m, buf ^ 1, 0);
+            else if constexpr (m >= 8 && m < 8 + LA + LB)
+                gload(m - 8, kb + 2);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+    for (int kb = 0; kb < nkb; kb += 2) {
+        stage(kb, std::integral_constant<int, 0>{});
+        stage(kb + 1, std::integral_constant<int, 1>{});
+    }
+    __syncthreads();
+
+    // epilogue, one 32-row block of accumulators at a time (keeps the register peak low); same
+    // reduction as corr_epilogue
+    uint64_t *red = reinterpret_cast<uint64_t *>(corr_lds);
+    const int32_t d = A.d;
+    uint64_t best[NB], second[NB];
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        best[b] = 0;
+        second[b] = 0;
+    }
+#pragma unroll
+    for (int a = 0; a < MB; ++a) {
+        const int32_t ibase = m0 + wm * 128 + a * 32;
+        float4 inv[4];
+#pragma unroll
+        for (int qd = 0; qd < 4; ++qd)
+            inv[qd] = *reinterpret_cast<const float4 *>(A.inv_colnorm + ibase + 8 * qd + 4 * lhalf);
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int32_t n = n0 + wn * 64 + b * 32 + l32;
+            const uint32_t mask = bitmap[(int64_t)n * words + (ibase >> 5)];
+            asm volatile("; accumulator block stays in AGPRs up to here" : "+a"(acc[a][b]));
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int off = 8 * (v >> 2) + 4 * lhalf + (v & 3);
+                const int32_t i = ibase + off;
+                const float4 nv = inv[v >> 2];
+                const float in = (v & 3) == 0 ? nv.x : ((v & 3) == 1 ? nv.y : ((v & 3) == 2 ? nv.z : nv.w));
+                const float score = fabsf(acc[a][b][v]) * in;
+                const bool ok = i < d && !((mask >> off) & 1u);
+                const uint64_t key = ok ? (((uint64_t)__float_as_uint(score) << 32) | (uint64_t)(0xffffffffu - (uint32_t)i)) : 0ull;
+                top2_insert(key, best[b], second[b]);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        const int nl = wn * 64 + b * 32 + l32;
+        const uint64_t ob = shfl_xor_u64(best[b], 32), os = shfl_xor_u64(second[b], 32);
+        top2_insert(ob, best[b], second[b]);
+        top2_insert(os, best[b], second[b]);
+        if (lhalf == 0) {
+            red[(wm * BN + nl) * 2 + 0] = best[b];
+            red[(wm * BN + nl) * 2 + 1] = second[b];
+        }
+    }
+    __syncthreads();
+    if (tid < BN) {
+        const int32_t n = n0 + tid;
+        uint64_t b0 = red[tid * 2], s0 = red[tid * 2 + 1];
+        top2_insert(red[(BN + tid) * 2], b0, s0);
+        top2_insert(red[(BN + tid) * 2 + 1], b0, s0);
+        uint64_t *o = partial + ((int64_t)n * tiles_m + m0 / BM) * 2;
+        o[0] = b0;
+        o[1] = s0;
+    }
+}
+
+static hipError_t corr_pipelined_launch(const MatrixView &A, int32_t rows, const float *R, int32_t N,
+                                        const OmpWorkspace &ws, int32_t tiles_m, hipStream_t s)
+{
+    constexpr size_t smem = (size_t)2 * (CORRP_BM + CORRP_BN) * 36 * sizeof(float);
+    static bool raised = false;
+    if (!raised) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_pipelined_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess)
+            return e;
+        raised = true;
+    }
+    const dim3 grid((unsigned)(rows / CORRP_BM), (unsigned)(N / CORRP_BN));
+    corr_pipelined_kernel<<<grid, 256, smem, s>>>(A, R, N, ws.bitmap, ws.words, ws.partial, tiles_m);
+    return hipSuccess;
+}
+
+// whether the pipelined kernel covers this problem (full tiles, stored rows, even number of stages)
+static bool corr_pipelined_ok(const MatrixView &A, int32_t N, int32_t panel_rows)
+{
+    return A.d % CORRP_BM == 0 && N % CORRP_BN == 0 && A.r % 64 == 0 && panel_rows % CORRP_BM == 0;
 }
 
 // The tiling in use: 128 x 128 outputs, depth 32 per stage, 2 x 2 wavefronts, two workgroups per CU.
@@ -705,7 +916,12 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
         ProfileScope prof(KC_OTHER, s);
         omp_init_kernel<<<dim3((unsigned)N), 256, 0, s>>>(y, A.r, ws.words, ws.res64, ws.res32, ws.bitmap);
     }
-    const OmpWorkspace &wsv = ws;
+    // stored rows (a stored matrix, or panels of a generated one) in full tiles take the pipelined
+    // kernel (256-row tiles); everything else the general one (128-row tiles)
+    const bool panels = A.generated && (N + CORR_BN - 1) / CORR_BN >= 4;
+    const bool pipelined = (!A.generated || panels) && corr_pipelined_ok(A, N, ws.panel_rows);
+    OmpWorkspace wsv = ws;
+    wsv.tiles_m = pipelined ? A.d / CORRP_BM : corr_tiles_m(A.d);
     int slices = 2048 / N;
     slices = slices < 1 ? 1 : (slices > 8 ? 8 : slices);
     const dim3 pgrid((unsigned)N, (unsigned)slices);
@@ -716,7 +932,6 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
     // A generated matrix is regenerated inside the contraction when few right-hand-side tiles share
     // it; with many tiles (each would regenerate all of A) it is produced once per iteration, panel
     // by panel, into a cache-sized scratch and consumed from there.
-    const bool panels = A.generated && (N + CORR_BN - 1) / CORR_BN >= 4;
     MatrixView Apick = A; // the view pick_kernel fetches columns from
     if (panels && ws.panel_rows >= A.d) {
         Apick.generated = 0;
@@ -739,12 +954,14 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
                     Ap.generated = 0;
                     Ap.At = ws.panel;
                     Ap.row0 = p0;
-                    e = corr_dispatch<false>(Ap, rows, ws.res32, N, wsv, wsv.tiles_m, s);
+                    e = pipelined ? corr_pipelined_launch(Ap, rows, ws.res32, N, wsv, wsv.tiles_m, s)
+                                  : corr_dispatch<false>(Ap, rows, ws.res32, N, wsv, wsv.tiles_m, s);
                 }
             } else if (A.generated) {
                 e = corr_dispatch<true>(A, A.d, ws.res32, N, wsv, wsv.tiles_m, s);
             } else {
-                e = corr_dispatch<false>(A, A.d, ws.res32, N, wsv, wsv.tiles_m, s);
+                e = pipelined ? corr_pipelined_launch(A, A.d, ws.res32, N, wsv, wsv.tiles_m, s)
+                              : corr_dispatch<false>(A, A.d, ws.res32, N, wsv, wsv.tiles_m, s);
             }
             if (e != hipSuccess)
                 return e;
