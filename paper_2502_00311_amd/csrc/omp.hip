@@ -312,9 +312,10 @@ static hipError_t corr_launch(const MatrixView &A, int32_t rows, const float *R,
 // sub-tile (4 x 2 MFMA blocks, accumulators in AGPRs). A depth-32 stage is 4 groups of 32 MFMAs;
 // every memory operation is issued in the shadow of an MFMA and the order is pinned:
 //   group 0..2  fragment reads of the next group (double-buffered in registers)
-//   group 2     LDS writes of the staged next stage (into the stage read one iteration earlier)
+//   group 2     LDS writes of the staged next stage (into the stage read one iteration earlier), then
+//               the global loads two stages ahead into the registers just freed
 //   barrier
-//   group 3     fragment reads of the next stage's first group; global loads two stages ahead
+//   group 3     fragment reads of the next stage's first group
 // so the matrix pipe only waits for the barrier itself. Addresses are a uniform base plus one per-lane
 // offset (no per-row bounds checks: tiles are full), and the depth loop is unrolled by two so that
 // LDS stage offsets are immediates.
@@ -413,8 +414,10 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
             mfma(0, m);
             if constexpr (m < MB + NB)
                 fread(1, m, buf, 3);
-            else if constexpr (m >= 8 && m < 8 + LA + LB)
-                lwrite(m - 8, buf ^ 1);
+            else if constexpr (m >= 6 && m < 6 + LA + LB)
+                lwrite(m - 6, buf ^ 1);
+            else if constexpr (m >= 20 && m < 20 + LA + LB)
+                gload(m - 20, kb + 2);
             __builtin_amdgcn_sched_barrier(0);
         });
         __syncthreads();
@@ -423,8 +426,6 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
             mfma(1, m);
             if constexpr (m < MB + NB)
                 fread(0, m, buf ^ 1, 0);
-            else if constexpr (m >= 8 && m < 8 + LA + LB)
-                gload(m - 8, kb + 2);
             __builtin_amdgcn_sched_barrier(0);
         });
     };
@@ -517,8 +518,9 @@ static bool corr_pipelined_ok(const MatrixView &A, int32_t N, int32_t panel_rows
 }
 
 // The tiling in use: 128 x 128 outputs, depth 32 per stage, 2 x 2 wavefronts, two workgroups per CU.
-// (256 x 128 tiles with 4 or 8 wavefronts, depth 16 or 64, and a variant that loads LDS directly
-// with global_load_lds all measured within 2 % of it inside the full step.)
+// It is the general kernel: any d, N, r % 4 == 0, generated or stored A. (Other shapes of this
+// compiler-scheduled kernel - 256 x 128 with 4 or 8 wavefronts, depth 16 or 64, LDS filled directly
+// with global_load_lds - all measured within 2 % of it inside the full step.)
 template <bool GENERATED>
 static hipError_t corr_dispatch(const MatrixView &A, int32_t rows, const float *R, int32_t N, const OmpWorkspace &ws,
                                 int32_t tiles_m, hipStream_t s)

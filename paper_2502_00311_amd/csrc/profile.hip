@@ -14,8 +14,11 @@ struct Span {
 };
 std::vector<Span> g_spans;
 std::vector<hipEvent_t> g_pool;
-hipEvent_t g_open = nullptr;
-int g_open_cls = 0;
+struct Open {
+    int cls;
+    hipEvent_t a;
+};
+std::vector<Open> g_open; // scopes nest (a panel refill inside a contraction scope)
 bool g_failed = false;
 
 hipEvent_t get_event()
@@ -36,10 +39,10 @@ hipEvent_t get_event()
 
 void profile_begin(int cls, hipStream_t s)
 {
-    g_open = get_event();
-    g_open_cls = cls;
-    if (g_open && hipEventRecord(g_open, s) != hipSuccess)
+    hipEvent_t a = get_event();
+    if (a && hipEventRecord(a, s) != hipSuccess)
         g_failed = true;
+    g_open.push_back(Open{cls, a});
 }
 
 void profile_end(hipStream_t s)
@@ -47,9 +50,12 @@ void profile_end(hipStream_t s)
     hipEvent_t e = get_event();
     if (e && hipEventRecord(e, s) != hipSuccess)
         g_failed = true;
-    if (g_open && e)
-        g_spans.push_back(Span{g_open_cls, g_open, e});
-    g_open = nullptr;
+    if (g_open.empty())
+        return;
+    const Open o = g_open.back();
+    g_open.pop_back();
+    if (o.a && e)
+        g_spans.push_back(Span{o.cls, o.a, e});
 }
 
 } // namespace sgc
