@@ -911,6 +911,107 @@ __global__ __launch_bounds__(RES_THREADS) void residual_kernel(IterArgs P, int32
     reinterpret_cast<float4 *>(W.res32 + n * r)[jb] = make_float4((float)e0, (float)e1, (float)e2, (float)e3);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Host side of the recovery.
+struct OmpPlan {
+    bool panels;     // generated A produced into ws.panel and consumed from there
+    bool pipelined;  // full tiles of stored rows: corr_pipelined_kernel
+    int32_t tiles_m; // position tiles of the contraction in use (stride of ws.partial)
+    MatrixView Apick; // the view pick_kernel fetches columns from
+    size_t pick_smem, factor_smem;
+};
+
+// the workspace as seen by the right-hand sides [n0, ...): every per-right-hand-side array shifted
+static OmpWorkspace shift_workspace(const OmpWorkspace &ws, int32_t n0, int32_t r, int32_t k, int32_t tiles_m)
+{
+    OmpWorkspace w = ws;
+    w.tiles_m = tiles_m;
+    w.res64 += (int64_t)n0 * r;
+    w.F += (int64_t)n0 * k * k;
+    w.avec += (int64_t)n0 * k;
+    w.xs += (int64_t)n0 * k;
+    w.res32 += (int64_t)n0 * r;
+    w.cols += (int64_t)n0 * k * r;
+    w.partial += (int64_t)n0 * tiles_m * 2;
+    w.bitmap += (int64_t)n0 * ws.words;
+    w.wv += (int64_t)n0 * k;
+    w.gb += (int64_t)n0 * 2;
+    return w;
+}
+
+// one iteration (contraction, then selection and least-squares update) for Ng right-hand sides whose
+// arrays start at y / sel / x / w, enqueued on s
+static hipError_t omp_iteration(const OmpPlan &pl, const MatrixView &A, const float *y, int32_t Ng, int32_t k,
+                                int32_t it, int32_t *sel, float *x, const OmpWorkspace &w, hipStream_t s)
+{
+    {
+        ProfileScope prof(KC_CORR, s);
+        hipError_t e = hipSuccess;
+        if (pl.panels) {
+            for (int32_t p0 = 0; p0 < A.d && e == hipSuccess; p0 += w.panel_rows) {
+                const int32_t rows = A.d - p0 < w.panel_rows ? A.d - p0 : w.panel_rows;
+                if (w.panel_rows < A.d) { // a matrix larger than the panel is refilled panel by panel
+                    e = launch_matrix_fill(A.key0, A.key1, A.scale, A.r, p0, rows, w.panel, s, KC_FILL);
+                    if (e != hipSuccess)
+                        break;
+                }
+                MatrixView Ap = A;
+                Ap.generated = 0;
+                Ap.At = w.panel;
+                Ap.row0 = p0;
+                e = pl.pipelined ? corr_pipelined_launch(Ap, rows, w.res32, Ng, w, pl.tiles_m, s)
+                                 : corr_dispatch<false>(Ap, rows, w.res32, Ng, w, pl.tiles_m, s);
+            }
+        } else if (A.generated) {
+            e = corr_dispatch<true>(A, A.d, w.res32, Ng, w, pl.tiles_m, s);
+        } else {
+            e = pl.pipelined ? corr_pipelined_launch(A, A.d, w.res32, Ng, w, pl.tiles_m, s)
+                             : corr_dispatch<false>(A, A.d, w.res32, Ng, w, pl.tiles_m, s);
+        }
+        if (e != hipSuccess)
+            return e;
+    }
+    {
+        ProfileScope prof(KC_SELECT, s);
+        int slices = 2048 / Ng;
+        slices = slices < 1 ? 1 : (slices > 8 ? 8 : slices);
+        const dim3 pgrid((unsigned)Ng, (unsigned)slices);
+        const dim3 rgrid((unsigned)Ng, (unsigned)(((A.r >> 2) + RES_THREADS - 1) / RES_THREADS));
+        IterArgs P{y, k, it, sel, x, w};
+        if (pl.Apick.generated)
+            pick_kernel<true><<<pgrid, PICK_THREADS, pl.pick_smem, s>>>(pl.Apick, P);
+        else
+            pick_kernel<false><<<pgrid, PICK_THREADS, pl.pick_smem, s>>>(pl.Apick, P);
+        factor_kernel<<<dim3((unsigned)Ng), k <= 128 ? 256 : FACTOR_MAX_THREADS, pl.factor_smem, s>>>(P);
+        residual_kernel<<<rgrid, RES_THREADS, sizeof(double) * (size_t)(it + 1), s>>>(P, A.r);
+    }
+    return hipSuccess;
+}
+
+// A second stream (default priority) and two events per device, created on first use, so that the
+// two halves of a large batch can run their iterations side by side: while one half is in its
+// memory-bound selection / update kernels the other half's contraction keeps the matrix cores busy.
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    bool ok = false, tried = false;
+};
+static SideStream *side_stream()
+{
+    static SideStream per_device[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+        return nullptr;
+    SideStream &ss = per_device[dev];
+    if (!ss.tried) {
+        ss.tried = true;
+        ss.ok = hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking) == hipSuccess &&
+                hipEventCreateWithFlags(&ss.fork, hipEventDisableTiming) == hipSuccess &&
+                hipEventCreateWithFlags(&ss.join, hipEventDisableTiming) == hipSuccess;
+    }
+    return ss.ok ? &ss : nullptr;
+}
+
 hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k, int32_t *sel, float *x,
                       const OmpWorkspace &ws, hipStream_t s)
 {
@@ -918,67 +1019,56 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
         ProfileScope prof(KC_OTHER, s);
         omp_init_kernel<<<dim3((unsigned)N), 256, 0, s>>>(y, A.r, ws.words, ws.res64, ws.res32, ws.bitmap);
     }
-    // stored rows (a stored matrix, or panels of a generated one) in full tiles take the pipelined
-    // kernel (256-row tiles); everything else the general one (128-row tiles)
-    const bool panels = A.generated && (N + CORR_BN - 1) / CORR_BN >= 4;
-    const bool pipelined = (!A.generated || panels) && corr_pipelined_ok(A, N, ws.panel_rows);
-    OmpWorkspace wsv = ws;
-    wsv.tiles_m = pipelined ? A.d / CORRP_BM : corr_tiles_m(A.d);
-    int slices = 2048 / N;
-    slices = slices < 1 ? 1 : (slices > 8 ? 8 : slices);
-    const dim3 pgrid((unsigned)N, (unsigned)slices);
-    const dim3 rgrid((unsigned)N, (unsigned)(((A.r >> 2) + RES_THREADS - 1) / RES_THREADS));
-    const size_t pick_smem = ((size_t)A.r * 4 + 15) & ~(size_t)15;
-    const size_t factor_smem = 2 * sizeof(double) * (size_t)k;
-    IterArgs P{y, k, 0, sel, x, wsv};
     // A generated matrix is regenerated inside the contraction when few right-hand-side tiles share
-    // it; with many tiles (each would regenerate all of A) it is produced once per iteration, panel
-    // by panel, into a cache-sized scratch and consumed from there.
-    MatrixView Apick = A; // the view pick_kernel fetches columns from
-    if (panels && ws.panel_rows >= A.d) {
-        Apick.generated = 0;
-        Apick.At = ws.panel;
+    // it; with many tiles (each would regenerate all of A) it is produced into a cache-sized scratch,
+    // once per call if it fits, else panel by panel in every iteration, and consumed from there.
+    // Stored rows in full tiles take the pipelined kernel (256-row tiles), everything else the
+    // general one (128-row tiles).
+    OmpPlan pl{};
+    pl.panels = A.generated && (N + CORR_BN - 1) / CORR_BN >= 4;
+    pl.pipelined = (!A.generated || pl.panels) && corr_pipelined_ok(A, N, ws.panel_rows);
+    pl.tiles_m = pl.pipelined ? A.d / CORRP_BM : corr_tiles_m(A.d);
+    pl.pick_smem = ((size_t)A.r * 4 + 15) & ~(size_t)15;
+    pl.factor_smem = 2 * sizeof(double) * (size_t)k;
+    pl.Apick = A;
+    const bool whole_matrix_panel = pl.panels && ws.panel_rows >= A.d;
+    if (whole_matrix_panel) {
+        hipError_t e = launch_matrix_fill(A.key0, A.key1, A.scale, A.r, 0, A.d, ws.panel, s, KC_FILL);
+        if (e != hipSuccess)
+            return e;
+        pl.Apick.generated = 0;
+        pl.Apick.At = ws.panel;
     }
-    for (int32_t it = 0; it < k; ++it) {
-        P.it = it;
-        {
-            ProfileScope prof(KC_CORR, s);
-            hipError_t e = hipSuccess;
-            if (panels) {
-                for (int32_t p0 = 0; p0 < A.d && e == hipSuccess; p0 += ws.panel_rows) {
-                    const int32_t rows = A.d - p0 < ws.panel_rows ? A.d - p0 : ws.panel_rows;
-                    if (it == 0 || ws.panel_rows < A.d) { // a single panel holding all of A is filled once
-                        e = launch_matrix_fill(A.key0, A.key1, A.scale, A.r, p0, rows, ws.panel, s, KC_FILL);
-                        if (e != hipSuccess)
-                            break;
-                    }
-                    MatrixView Ap = A;
-                    Ap.generated = 0;
-                    Ap.At = ws.panel;
-                    Ap.row0 = p0;
-                    e = pipelined ? corr_pipelined_launch(Ap, rows, ws.res32, N, wsv, wsv.tiles_m, s)
-                                  : corr_dispatch<false>(Ap, rows, ws.res32, N, wsv, wsv.tiles_m, s);
-                }
-            } else if (A.generated) {
-                e = corr_dispatch<true>(A, A.d, ws.res32, N, wsv, wsv.tiles_m, s);
-            } else {
-                e = pipelined ? corr_pipelined_launch(A, A.d, ws.res32, N, wsv, wsv.tiles_m, s)
-                              : corr_dispatch<false>(A, A.d, ws.res32, N, wsv, wsv.tiles_m, s);
-            }
+    // two halves side by side when the batch is large (not while kernels are being timed one by one,
+    // and not when both halves would have to share a panel that is refilled inside the iterations)
+    const int32_t N0 = (N / 2 + CORR_BN - 1) / CORR_BN * CORR_BN;
+    SideStream *ss = nullptr;
+    if (N >= 4 * CORR_BN && N0 < N && !g_profile_on && !(pl.panels && !whole_matrix_panel))
+        ss = side_stream();
+    if (!ss) {
+        const OmpWorkspace w = shift_workspace(ws, 0, A.r, k, pl.tiles_m);
+        for (int32_t it = 0; it < k; ++it) {
+            hipError_t e = omp_iteration(pl, A, y, N, k, it, sel, x, w, s);
             if (e != hipSuccess)
                 return e;
         }
-        {
-            ProfileScope prof(KC_SELECT, s);
-            if (Apick.generated)
-                pick_kernel<true><<<pgrid, PICK_THREADS, pick_smem, s>>>(Apick, P);
-            else
-                pick_kernel<false><<<pgrid, PICK_THREADS, pick_smem, s>>>(Apick, P);
-            factor_kernel<<<dim3((unsigned)N), k <= 128 ? 256 : FACTOR_MAX_THREADS, factor_smem, s>>>(P);
-            residual_kernel<<<rgrid, RES_THREADS, sizeof(double) * (size_t)(it + 1), s>>>(P, A.r);
-        }
+        return hipGetLastError();
     }
-    return hipGetLastError();
+    const OmpWorkspace w0 = shift_workspace(ws, 0, A.r, k, pl.tiles_m);
+    const OmpWorkspace w1 = shift_workspace(ws, N0, A.r, k, pl.tiles_m);
+    if (hipEventRecord(ss->fork, s) != hipSuccess || hipStreamWaitEvent(ss->stream, ss->fork, 0) != hipSuccess)
+        return hipErrorUnknown;
+    hipError_t e = hipSuccess;
+    for (int32_t it = 0; it < k && e == hipSuccess; ++it) {
+        e = omp_iteration(pl, A, y, N0, k, it, sel, x, w0, s);
+        if (e == hipSuccess)
+            e = omp_iteration(pl, A, y + (int64_t)N0 * A.r, N - N0, k, it, sel + (int64_t)N0 * k, x + (int64_t)N0 * k,
+                              w1, ss->stream);
+    }
+    // join even after a failed launch so that the caller's stream never runs ahead of the side stream
+    if (hipEventRecord(ss->join, ss->stream) != hipSuccess || hipStreamWaitEvent(s, ss->join, 0) != hipSuccess)
+        return hipErrorUnknown;
+    return e != hipSuccess ? e : hipGetLastError();
 }
 
 } // namespace sgc
