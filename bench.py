@@ -23,7 +23,7 @@ sys.path.insert(0, ROOT)
 MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense float matrix peak
 # HBM bytes per launch of the correlation kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/), keyed by workload name; None until measured.
-MEASURED_TRAFFIC = {"cfg2_64x65536": 5.564e8}  # profiles/cfg2_corr_kernel_hbm_traffic.md
+MEASURED_TRAFFIC = {"cfg2_64x65536": 5.531e8}  # profiles/cfg2_corr_kernel_hbm_traffic.md
 
 
 def main():
@@ -115,7 +115,7 @@ def main():
     avg_ms = corr_ms / max(corr_n, 1)
     achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12
     roofline = {
-        "bound": "mfma", "kernel": "omp corr_kernel (At*R, float 32x32x2 MFMA, fused argmax epilogue)",
+        "bound": "mfma", "kernel": "omp correlation contraction At*R (float 32x32x2 MFMA, fused argmax epilogue)",
         "achieved": round(achieved, 3), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
         "frac": round(achieved / MFMA_F32_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC.get(w.name),
         "flops_per_launch": flops_per_launch, "avg_launch_ms": round(avg_ms, 5), "launches": corr_n,
