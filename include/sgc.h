@@ -150,8 +150,8 @@ size_t sgc_omp_workspace_bytes(int32_t N, int32_t d, int32_t r, int32_t k);
  * All N correlations of one iteration are one dense contraction At * R on the float matrix
  * cores; the near-maximal candidates are then re-scored in double, and the least-squares
  * update (inverse-Cholesky form of App. B) and the residual are computed in double.
- * Requires A->inv_colnorm. Errors: NULL, SHAPE (k<=0, k>d, k>r, r%4, N<=0), DTYPE, ALIGN,
- * WORKSPACE.
+ * Requires A->inv_colnorm. Errors: NULL, SHAPE (k<=0, k>d, k>r, k>1024, r%4, 4r+16k > 60 KiB, N<=0), DTYPE,
+ * ALIGN, WORKSPACE.
  */
 sgc_status sgc_recover_omp(const float *y, int32_t N, const sgc_matrix *A /* host */, int32_t k,
                            int32_t *sel, float *x, void *ws, size_t ws_bytes, void *stream);

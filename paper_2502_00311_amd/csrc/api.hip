@@ -129,7 +129,7 @@ sgc_status sgc_adam_compressed(const float *p, const float *q, float *m, float *
 
 static bool omp_sizes_ok(int32_t N, int32_t d, int32_t r, int32_t k)
 {
-    if (N <= 0 || d <= 0 || r <= 0 || (r & 3) || k <= 0 || k > d || k > r || d > (1 << 30))
+    if (N <= 0 || d <= 0 || r <= 0 || (r & 3) || k <= 0 || k > d || k > r || k > 1024 || d > (1 << 30))
         return false;
     // LDS of the update kernel: one column (r floats) and two k-vectors of doubles
     if ((size_t)r * 4 + 16 + (size_t)k * 16 > 60 * 1024)

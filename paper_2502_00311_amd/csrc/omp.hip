@@ -743,15 +743,19 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(MatrixView A, IterAr
     }
 }
 
-// grid N; 256 threads (k <= 128) or 1024. dynamic LDS: double w[k]; double c[k]
+// grid N; 256 threads (k <= 128) or 1024. dynamic LDS: double w[k]; double fsum[k]
+// One pass over F: a wavefront takes column t of F (entries 0..t, contiguous), forms
+// c_t = <F_:t, w> (coordinate t of the new column in the orthonormal basis Q = A_Lambda F) and at once
+// adds c_t F_:t to its share of F c; the shares are then summed in wavefront order.
+// ROWS = rows of F per lane (k <= 64 * ROWS); TWO = two columns in flight per wavefront
+template <int FACTOR_ROWS, bool TWO>
 __global__ __launch_bounds__(FACTOR_MAX_THREADS) void factor_kernel(IterArgs P)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int32_t k = P.k, it = P.it;
     double *w_s = reinterpret_cast<double *>(smem);
-    double *c_s = w_s + k;
+    double *fsum = w_s + k;
     __shared__ double s_red[2][FACTOR_MAX_THREADS / 64];
-    __shared__ double s_part[FACTOR_MAX_THREADS / 256][256];
     __shared__ double s_gamma, s_coef;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nthreads = blockDim.x, nwaves = blockDim.x >> 6;
@@ -761,105 +765,93 @@ __global__ __launch_bounds__(FACTOR_MAX_THREADS) void factor_kernel(IterArgs P)
     double *avec = W.avec + n * k;
     double *xs = W.xs + n * k;
 
-    for (int32_t t = tid; t < it; t += nthreads)
+    for (int32_t t = tid; t < it; t += nthreads) {
         w_s[t] = W.wv[n * k + t];
+        fsum[t] = 0.0;
+    }
     __syncthreads();
-    // c = F^H w (coordinates of the new column in the orthonormal basis Q = A_Lambda F); column t
-    // of F is contiguous with entries 0..t. One wavefront per column, two columns in flight.
-    for (int32_t t = wave; t < it; t += 2 * nwaves) {
+    const int nq = (it + 63) >> 6; // 64-row slabs in use
+    double facc[FACTOR_ROWS];
+#pragma unroll
+    for (int q = 0; q < FACTOR_ROWS; ++q)
+        facc[q] = 0.0;
+    double cc = 0.0, ca = 0.0; // c.c and c.avec over this wavefront's columns
+    for (int32_t t = wave; t < it; t += (TWO ? 2 : 1) * nwaves) {
         const int32_t t2 = t + nwaves;
-        const bool two = t2 < it;
+        const bool two = TWO && t2 < it;
         const double *f0 = F + (int64_t)t * k;
         const double *f1 = F + (int64_t)(two ? t2 : t) * k;
-        const int32_t top = two ? t2 : t;
-        double s0 = 0.0, s1 = 0.0;
-        for (int32_t u = lane; u <= top; u += 64) {
-            const double wu = w_s[u];
-            s0 += (u <= t ? f0[u] : 0.0) * wu;
-            s1 += f1[u] * wu;
+        double v0[FACTOR_ROWS], v1[FACTOR_ROWS];
+        double d0 = 0.0, d1 = 0.0;
+#pragma unroll
+        for (int q = 0; q < FACTOR_ROWS; ++q) {
+            v0[q] = 0.0;
+            v1[q] = 0.0;
+            if (q < nq) {
+                const int32_t u = q * 64 + lane;
+                if (u <= t)
+                    v0[q] = f0[u];
+                if (two && u <= t2)
+                    v1[q] = f1[u];
+                const double wu = u < it ? w_s[u] : 0.0;
+                d0 += v0[q] * wu;
+                d1 += v1[q] * wu;
+            }
         }
-        s0 = wave_sum(s0);
-        s1 = wave_sum(s1);
-        if (lane == 0) {
-            c_s[t] = s0;
-            if (two)
-                c_s[t2] = s1;
+        d0 = __shfl(wave_sum(d0), 0, 64);
+        d1 = __shfl(wave_sum(d1), 0, 64);
+#pragma unroll
+        for (int q = 0; q < FACTOR_ROWS; ++q)
+            if (q < nq)
+                facc[q] += v0[q] * d0 + v1[q] * d1;
+        cc += d0 * d0 + d1 * d1;
+        ca += d0 * avec[t] + (two ? d1 * avec[t2] : 0.0);
+    }
+    if (lane == 0) {
+        s_red[0][wave] = cc;
+        s_red[1][wave] = ca;
+    }
+    // F c = sum of the wavefronts' shares, added in wavefront order (deterministic)
+    for (int wv = 0; wv < nwaves; ++wv) {
+        if (wave == wv) {
+#pragma unroll
+            for (int q = 0; q < FACTOR_ROWS; ++q) {
+                const int32_t u = q * 64 + lane;
+                if (q < nq && u < it)
+                    fsum[u] += facc[q];
+            }
         }
+        __syncthreads();
+    }
+    // gamma = 1/sqrt(g - c.c); new coefficient a_it = gamma (b - c.avec)
+    if (tid == 0) {
+        double tcc = 0.0, tca = 0.0;
+        for (int u = 0; u < nwaves; ++u) {
+            tcc += s_red[0][u];
+            tca += s_red[1][u];
+        }
+        const double g = W.gb[n * 2], b = W.gb[n * 2 + 1];
+        const double rem = g - tcc;
+        const double gamma = rem > 0.0 ? 1.0 / sqrt(rem) : 0.0;
+        const double coef = gamma * (b - tca);
+        s_gamma = gamma;
+        s_coef = coef;
+        avec[it] = coef;
+        F[(int64_t)it * k + it] = gamma;
+        xs[it] = coef * gamma;
+        if (it == k - 1)
+            P.x[n * k + it] = (float)(coef * gamma);
     }
     __syncthreads();
-    // gamma = 1/sqrt(g - c.c); new coefficient a_it = gamma (b - c.avec)
-    {
-        double cc = 0.0, ca = 0.0;
-        for (int32_t t = tid; t < it; t += nthreads) {
-            cc += c_s[t] * c_s[t];
-            ca += c_s[t] * avec[t];
-        }
-        cc = wave_sum(cc);
-        ca = wave_sum(ca);
-        if (lane == 0) {
-            s_red[0][wave] = cc;
-            s_red[1][wave] = ca;
-        }
-        __syncthreads();
-        if (tid == 0) {
-            cc = 0.0;
-            ca = 0.0;
-            for (int u = 0; u < nwaves; ++u) {
-                cc += s_red[0][u];
-                ca += s_red[1][u];
-            }
-            const double g = W.gb[n * 2], b = W.gb[n * 2 + 1];
-            const double rem = g - cc;
-            const double gamma = rem > 0.0 ? 1.0 / sqrt(rem) : 0.0;
-            const double coef = gamma * (b - ca);
-            s_gamma = gamma;
-            s_coef = coef;
-            avec[it] = coef;
-            F[(int64_t)it * k + it] = gamma;
-            xs[it] = coef * gamma;
-            if (it == k - 1)
-                P.x[n * k + it] = (float)(coef * gamma);
-        }
-        __syncthreads();
-    }
     const double gamma = s_gamma, coef = s_coef;
-    // new column of F: f_u = -gamma (F c)_u on rows u < it, and x <- [x; 0] + coef * F_:it.
-    // Thread (u, h): row u, h-th part of the sum over columns t = u..it-1 (F[t*k+u] is coalesced
-    // over u); loads are issued eight at a time.
-    const int H = nthreads >> 8, ul = tid & 255, h = tid >> 8;
-    for (int32_t u0 = 0; u0 < it; u0 += 256) {
-        const int32_t u = u0 + ul;
-        double s = 0.0;
-        if (u < it) {
-            const int32_t len = it - u;
-            int32_t t = u + (int32_t)(((int64_t)h * len) / H);
-            const int32_t te = u + (int32_t)(((int64_t)(h + 1) * len) / H);
-            for (; t + 8 <= te; t += 8) {
-                double f[8];
-#pragma unroll
-                for (int q = 0; q < 8; ++q)
-                    f[q] = F[(int64_t)(t + q) * k + u];
-#pragma unroll
-                for (int q = 0; q < 8; ++q)
-                    s += f[q] * c_s[t + q];
-            }
-            for (; t < te; ++t)
-                s += F[(int64_t)t * k + u] * c_s[t];
-        }
-        s_part[h][ul] = s;
-        __syncthreads();
-        if (h == 0 && u < it) {
-            double tot = 0.0;
-            for (int q = 0; q < H; ++q)
-                tot += s_part[q][ul];
-            const double f = -gamma * tot;
-            F[(int64_t)it * k + u] = f;
-            const double xn = xs[u] + coef * f;
-            xs[u] = xn;
-            if (it == k - 1)
-                P.x[n * k + u] = (float)xn;
-        }
-        __syncthreads();
+    // new column of F: -gamma F c on rows < it, and x <- [x; 0] + coef * F_:it
+    for (int32_t u = tid; u < it; u += nthreads) {
+        const double f = -gamma * fsum[u];
+        F[(int64_t)it * k + u] = f;
+        const double xn = xs[u] + coef * f;
+        xs[u] = xn;
+        if (it == k - 1)
+            P.x[n * k + u] = (float)xn;
     }
 }
 
@@ -982,7 +974,12 @@ static hipError_t omp_iteration(const OmpPlan &pl, const MatrixView &A, const fl
             pick_kernel<true><<<pgrid, PICK_THREADS, pl.pick_smem, s>>>(pl.Apick, P);
         else
             pick_kernel<false><<<pgrid, PICK_THREADS, pl.pick_smem, s>>>(pl.Apick, P);
-        factor_kernel<<<dim3((unsigned)Ng), k <= 128 ? 256 : FACTOR_MAX_THREADS, pl.factor_smem, s>>>(P);
+        if (k <= 128)
+            factor_kernel<2, true><<<dim3((unsigned)Ng), 256, pl.factor_smem, s>>>(P);
+        else if (k <= 256)
+            factor_kernel<4, true><<<dim3((unsigned)Ng), FACTOR_MAX_THREADS, pl.factor_smem, s>>>(P);
+        else
+            factor_kernel<16, false><<<dim3((unsigned)Ng), FACTOR_MAX_THREADS, pl.factor_smem, s>>>(P);
         residual_kernel<<<rgrid, RES_THREADS, sizeof(double) * (size_t)(it + 1), s>>>(P, A.r);
     }
     return hipSuccess;

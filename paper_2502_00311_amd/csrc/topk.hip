@@ -179,6 +179,32 @@ __device__ __forceinline__ uint32_t wave_kth_largest(const uint32_t *keys, uint3
 {
     const uint32_t lane = threadIdx.x & 63;
     uint32_t thr = 0;
+    gt = 0;
+    eq = 0;
+    if (n <= 64 * 8) {
+        // the usual case: the keys fit eight registers per lane, the search never touches LDS again
+        uint32_t kr[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const uint32_t s = q * 64 + lane;
+            kr[q] = s < n ? (keys[s] & 0x7fffffffu) : 0u; // padding keys are 0: never >= a candidate
+        }
+        for (int bit = 30; bit >= 0; --bit) {
+            const uint32_t cand = thr | (1u << bit);
+            uint32_t cnt = 0;
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+                cnt += (uint32_t)__popcll(__ballot(kr[q] >= cand));
+            thr = cnt >= kth ? cand : thr;
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const bool in = q * 64 + lane < n;
+            gt += (uint32_t)__popcll(__ballot(in && kr[q] > thr));
+            eq += (uint32_t)__popcll(__ballot(in && kr[q] == thr));
+        }
+        return thr;
+    }
     for (int bit = 30; bit >= 0; --bit) {
         const uint32_t cand = thr | (1u << bit);
         uint32_t cnt = 0;
@@ -189,8 +215,6 @@ __device__ __forceinline__ uint32_t wave_kth_largest(const uint32_t *keys, uint3
         }
         thr = cnt >= kth ? cand : thr;
     }
-    gt = 0;
-    eq = 0;
     for (uint32_t s0 = 0; s0 < n; s0 += 64) {
         const uint32_t s = s0 + lane;
         const uint32_t key = s < n ? (keys[s] & 0x7fffffffu) : 0u;
