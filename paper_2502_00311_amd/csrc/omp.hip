@@ -549,6 +549,11 @@ struct IterArgs {
     int32_t *sel;   // [N][k]
     float *x;       // [N][k]
     OmpWorkspace ws;
+    // rows of At resident in memory (a stored matrix, or a generated one produced whole into the
+    // panel): the least-squares passes then fetch the selected columns from here through `sel`,
+    // where a matrix shared by many right-hand sides stays in cache, and ws.cols is not used.
+    // NULL: the selected columns are kept per right-hand side in ws.cols.
+    const float *At_rows;
 };
 
 template <bool GENERATED>
@@ -689,7 +694,8 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(MatrixView A, IterAr
             const float4 a = column_quad<GENERATED>(A, lam, jb);
             reinterpret_cast<float4 *>(a_col)[jb] = a;
             if (slice == 0) {
-                reinterpret_cast<float4 *>(cols + (int64_t)it * r)[jb] = a;
+                if (!P.At_rows)
+                    reinterpret_cast<float4 *>(cols + (int64_t)it * r)[jb] = a;
                 const float4 yv = reinterpret_cast<const float4 *>(yy)[jb];
                 g += (double)a.x * a.x + (double)a.y * a.y + (double)a.z * a.z + (double)a.w * a.w;
                 b += (double)a.x * yv.x + (double)a.y * yv.y + (double)a.z * yv.z + (double)a.w * yv.w;
@@ -719,12 +725,16 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(MatrixView A, IterAr
 
     // (4) w_t = <A_:lambda_t, a>, one wavefront per earlier selection, two rows in flight
     double *wv = W.wv + n * k;
+    const int32_t *selp = P.sel + n * k;
     const int32_t gw = slice * PICK_WAVES + wave, GW = nslices * PICK_WAVES;
     for (int32_t t = gw; t < it; t += 2 * GW) {
         const int32_t t2 = t + GW;
         const bool two = t2 < it;
-        const float4 *c0 = reinterpret_cast<const float4 *>(cols + (int64_t)t * r);
-        const float4 *c1 = reinterpret_cast<const float4 *>(cols + (int64_t)(two ? t2 : t) * r);
+        const int32_t tb = two ? t2 : t;
+        const float4 *c0 = reinterpret_cast<const float4 *>(
+            P.At_rows ? P.At_rows + (int64_t)selp[t] * r : cols + (int64_t)t * r);
+        const float4 *c1 = reinterpret_cast<const float4 *>(
+            P.At_rows ? P.At_rows + (int64_t)selp[tb] * r : cols + (int64_t)tb * r);
         double s0 = 0.0, s1 = 0.0;
         for (int32_t jb = lane; jb < r4; jb += 64) {
             const float4 u0 = c0[jb];
@@ -855,29 +865,33 @@ __global__ __launch_bounds__(FACTOR_MAX_THREADS) void factor_kernel(IterArgs P)
     }
 }
 
-// grid (N, r/256): one thread per four measurements. dynamic LDS: double x[it+1]
+// grid (N, r/256): one thread per four measurements. dynamic LDS: double x[it+1]; int64 row[it+1]
 __global__ __launch_bounds__(RES_THREADS) void residual_kernel(IterArgs P, int32_t r)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     double *x_s = reinterpret_cast<double *>(smem);
+    int64_t *row_s = reinterpret_cast<int64_t *>(x_s + (P.it + 1)); // offset of column t in float4 units
     const int32_t k = P.k, it = P.it, r4 = r >> 2;
     const int64_t n = blockIdx.x;
     const OmpWorkspace &W = P.ws;
-    for (int32_t t = threadIdx.x; t <= it; t += RES_THREADS)
+    for (int32_t t = threadIdx.x; t <= it; t += RES_THREADS) {
         x_s[t] = W.xs[n * k + t];
+        row_s[t] = (P.At_rows ? (int64_t)P.sel[n * k + t] : (int64_t)t) * r4;
+    }
     __syncthreads();
     const int32_t jb = blockIdx.y * RES_THREADS + threadIdx.x;
     if (jb >= r4)
         return;
     const float4 yv = reinterpret_cast<const float4 *>(P.y + n * r)[jb];
     double e0 = yv.x, e1 = yv.y, e2 = yv.z, e3 = yv.w;
-    const float4 *cj = reinterpret_cast<const float4 *>(W.cols + (n * k) * (int64_t)r) + jb;
+    const float4 *cj = (P.At_rows ? reinterpret_cast<const float4 *>(P.At_rows)
+                                  : reinterpret_cast<const float4 *>(W.cols + (n * k) * (int64_t)r)) + jb;
     int32_t t = 0;
     for (; t + 8 <= it + 1; t += 8) {
         float4 u[8];
 #pragma unroll
         for (int q = 0; q < 8; ++q)
-            u[q] = cj[(int64_t)(t + q) * r4];
+            u[q] = cj[row_s[t + q]];
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             const double xt = x_s[t + q];
@@ -888,7 +902,7 @@ __global__ __launch_bounds__(RES_THREADS) void residual_kernel(IterArgs P, int32
         }
     }
     for (; t <= it; ++t) {
-        const float4 u = cj[(int64_t)t * r4];
+        const float4 u = cj[row_s[t]];
         const double xt = x_s[t];
         e0 -= xt * u.x;
         e1 -= xt * u.y;
@@ -969,7 +983,7 @@ static hipError_t omp_iteration(const OmpPlan &pl, const MatrixView &A, const fl
         slices = slices < 1 ? 1 : (slices > 8 ? 8 : slices);
         const dim3 pgrid((unsigned)Ng, (unsigned)slices);
         const dim3 rgrid((unsigned)Ng, (unsigned)(((A.r >> 2) + RES_THREADS - 1) / RES_THREADS));
-        IterArgs P{y, k, it, sel, x, w};
+        IterArgs P{y, k, it, sel, x, w, pl.Apick.generated ? nullptr : pl.Apick.At};
         if (pl.Apick.generated)
             pick_kernel<true><<<pgrid, PICK_THREADS, pl.pick_smem, s>>>(pl.Apick, P);
         else
@@ -980,7 +994,7 @@ static hipError_t omp_iteration(const OmpPlan &pl, const MatrixView &A, const fl
             factor_kernel<4, true><<<dim3((unsigned)Ng), FACTOR_MAX_THREADS, pl.factor_smem, s>>>(P);
         else
             factor_kernel<16, false><<<dim3((unsigned)Ng), FACTOR_MAX_THREADS, pl.factor_smem, s>>>(P);
-        residual_kernel<<<rgrid, RES_THREADS, sizeof(double) * (size_t)(it + 1), s>>>(P, A.r);
+        residual_kernel<<<rgrid, RES_THREADS, 16 * (size_t)(it + 1), s>>>(P, A.r);
     }
     return hipSuccess;
 }

@@ -385,7 +385,8 @@ def test_full_step_cfg1_as_specified():
     (synth.shrink(synth.CFG3, C=6, d=4096, r=256, k=16), 1),      # generated matrix, row-scaled gradients
     (synth.shrink(synth.CFG4, C=7, d=2048, r=128, k=8), 2),       # layer-scaled gradients
     (synth.shrink(synth.CFG5, C=2, d=8192, r=512, k=64), 1),      # bf16 gradients
-], ids=["cfg2s", "cfg3s", "cfg4s", "cfg5s"])
+    (synth.shrink(synth.CFG5, C=2, d=32768, r=1024, k=128), 1),   # the stress shape scaled down, run in full
+], ids=["cfg2s", "cfg3s", "cfg4s", "cfg5s", "cfg5_scaled_down"])
 def test_full_step_on_shrunk_workloads(w, steps):
     say(w.name, w.C, w.d, w.r, w.k)
     check_steps_against_oracle(w, steps, alpha=2.0)
