@@ -159,6 +159,39 @@ def omp_batch(Y, At, k):
     return sel, x
 
 
+def lstsq_support(y, At, sel):
+    """argmin_x || y - A_sel x ||_2 in double (normal equations, Cholesky) on a given support."""
+    y = _c(y, np.float32)
+    At = _c(At, np.float32)
+    sel = _c(sel, np.int32)
+    d, r = At.shape
+    x64 = np.zeros(sel.size, np.float64)
+    rc = lib().oracle_lstsq_support(_p(y, ctypes.c_float), _p(At, ctypes.c_float), d, r, _p(sel, ctypes.c_int32), sel.size, _p(x64, ctypes.c_double))
+    if rc:
+        raise ValueError("oracle_lstsq_support rc=%d" % rc)
+    return x64
+
+
+def omp_shared(Ym, Yv, At, k, norm=None):
+    """Shared-support recovery of C chunks: support and x from OMP on Ym[c], z = least-squares fit
+    of Yv[c] on that support (Sec. 4.3, the remark after eq. 11). Returns sel, x, z, each [C, k]."""
+    Ym = _c(Ym, np.float32)
+    Yv = _c(Yv, np.float32)
+    At = _c(At, np.float32)
+    C, r = Ym.shape
+    d = At.shape[0]
+    assert Yv.shape == (C, r) and At.shape[1] == r
+    norm = _c(norm if norm is not None else colnorms(At), np.float64)
+    sel = np.empty((C, k), np.int32)
+    x = np.empty((C, k), np.float32)
+    z = np.empty((C, k), np.float32)
+    for c in range(C):
+        rc = lib().oracle_omp_shared(_p(Ym[c], ctypes.c_float), _p(Yv[c], ctypes.c_float), _p(At, ctypes.c_float), d, r, k, _p(norm, ctypes.c_double), _p(sel[c], ctypes.c_int32), _p(x[c], ctypes.c_float), _p(z[c], ctypes.c_float))
+        if rc:
+            raise ValueError("oracle_omp_shared rc=%d" % rc)
+    return sel, x, z
+
+
 def apply(W, d, sel_m, x_m, sel_v, x_v, alpha=1.0, eps=1e-8, lr=1e-3):
     """W <- W - lr * alpha * x / (sqrt(z) + eps) on the recovered supports (eq. 11, eq. 3)."""
     W = np.array(W, np.float32, copy=True, order="C")
@@ -174,12 +207,17 @@ def apply(W, d, sel_m, x_m, sel_v, x_v, alpha=1.0, eps=1e-8, lr=1e-3):
     return W
 
 
-def step(g, W, m, v, t, At, k, beta1=0.9, beta2=0.999, eps=1e-8, lr=1e-3, alpha=1.0):
-    """One full SGC step (Alg. 2 + the weight update) on C chunks. g: [C, d]."""
+def step(g, W, m, v, t, At, k, beta1=0.9, beta2=0.999, eps=1e-8, lr=1e-3, alpha=1.0, shared_support=False):
+    """One full SGC step (Alg. 2 + the weight update) on C chunks. g: [C, d].
+    shared_support: recover the support from mhat only and fit vhat on it."""
     C, d = g.shape
     idx, val = topk(g, k)
     p, q = project(idx, val, At)
     m2, v2, mh, vh = adam(p, q, m, v, t, beta1, beta2)
+    if shared_support:
+        sel_s, x_s, z_s = omp_shared(mh.reshape(C, -1), vh.reshape(C, -1), At, k)
+        W2 = apply(W, d, sel_s, x_s, sel_s, z_s, alpha, eps, lr)
+        return dict(idx=idx, val=val, p=p, q=q, m=m2, v=v2, mhat=mh, vhat=vh, sel_m=sel_s, x_m=x_s, sel_v=sel_s, x_v=z_s, W=W2)
     Y = np.concatenate([mh.reshape(C, -1), vh.reshape(C, -1)], axis=0)
     sel, x = omp_batch(Y, At, k)
     W2 = apply(W, d, sel[:C], x[:C], sel[C:], x[C:], alpha, eps, lr)

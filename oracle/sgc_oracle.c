@@ -19,8 +19,9 @@
  * float64 mat-vec for the projection; published Philox4x32-10 known-answer
  * vectors and an exact Box-Muller evaluation for the generated matrix; the
  * closed form of the first Adam step; exact sparse recovery, exhaustive
- * support search and least-squares identities for OMP; the closed form of the
- * first full step in the exact-recovery regime.
+ * support search and least-squares identities for OMP; a library least-squares
+ * routine and exact joint recovery for the shared-support fit; the closed form
+ * of the first full step in the exact-recovery regime.
  */
 #include <math.h>
 #include <stdint.h>
@@ -489,6 +490,69 @@ int oracle_omp_batch(const float *y, int32_t N, const float *At, int32_t d, int3
         rc = oracle_omp(y + (int64_t)n * r, At, d, r, k, norm, NULL, 0, sel + (int64_t)n * k,
                         x + (int64_t)n * k, NULL, NULL, NULL);
     free(norm);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Shared-support recovery. Sec. 4.3 (text after eq. 11) argues that the two  */
+/* moments have the same sparsity pattern, so that both recovered vectors     */
+/* have their non-zeros at the same positions. This variant makes that hold   */
+/* by construction: the support Lambda is found by OMP on the first moment    */
+/* alone, and the second moment is fitted on that same support,               */
+/*     z = argmin || y_v - A_Lambda z ||_2 .                                  */
+/* ------------------------------------------------------------------------ */
+
+/* least squares on a given support: x64[k] = argmin || y - A_sel x ||_2 by the normal
+ * equations (Gram matrix and right-hand side in double, Cholesky). sel[k] distinct positions.
+ * returns 0, -1 on a bad argument, -4 if the Gram matrix is not positive definite */
+int oracle_lstsq_support(const float *y, const float *At, int32_t d, int32_t r, const int32_t *sel,
+                         int32_t k, double *x64)
+{
+    if (k < 0 || k > r)
+        return -1;
+    for (int32_t t = 0; t < k; ++t)
+        if (sel[t] < 0 || sel[t] >= d)
+            return -1;
+    if (k == 0)
+        return 0;
+    double *G = (double *)calloc((size_t)k * k, sizeof(double));
+    double *L = (double *)calloc((size_t)k * k, sizeof(double));
+    double *b = (double *)calloc((size_t)k, sizeof(double));
+    for (int32_t t = 0; t < k; ++t) {
+        const float *at = At + (int64_t)sel[t] * r;
+        for (int32_t u = 0; u <= t; ++u) {
+            const float *au = At + (int64_t)sel[u] * r;
+            double s = 0.0;
+            for (int32_t j = 0; j < r; ++j)
+                s += (double)at[j] * (double)au[j];
+            G[(size_t)t * k + u] = s;
+            G[(size_t)u * k + t] = s;
+        }
+        double by = 0.0;
+        for (int32_t j = 0; j < r; ++j)
+            by += (double)at[j] * (double)y[j];
+        b[t] = by;
+    }
+    int rc = spd_solve(G, k, k, b, x64, L) ? -4 : 0;
+    free(G);
+    free(L);
+    free(b);
+    return rc;
+}
+
+/* y_m[r], y_v[r]: the two bias-corrected moments of one chunk. sel[k], x[k]: OMP_A(y_m);
+ * z[k]: least-squares fit of y_v on the same support, aligned with sel. */
+int oracle_omp_shared(const float *y_m, const float *y_v, const float *At, int32_t d, int32_t r,
+                      int32_t k, const double *norm, int32_t *sel, float *x, float *z)
+{
+    int rc = oracle_omp(y_m, At, d, r, k, norm, NULL, 0, sel, x, NULL, NULL, NULL);
+    if (rc)
+        return rc;
+    double *z64 = (double *)calloc((size_t)(k > 0 ? k : 1), sizeof(double));
+    rc = oracle_lstsq_support(y_v, At, d, r, sel, k, z64);
+    for (int32_t t = 0; t < k && rc == 0; ++t)
+        z[t] = (float)z64[t];
+    free(z64);
     return rc;
 }
 

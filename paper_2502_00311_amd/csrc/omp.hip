@@ -945,58 +945,58 @@ static OmpWorkspace shift_workspace(const OmpWorkspace &ws, int32_t n0, int32_t 
     return w;
 }
 
-// one iteration (contraction, then selection and least-squares update) for Ng right-hand sides whose
-// arrays start at y / sel / x / w, enqueued on s
-static hipError_t omp_iteration(const OmpPlan &pl, const MatrixView &A, const float *y, int32_t Ng, int32_t k,
-                                int32_t it, int32_t *sel, float *x, const OmpWorkspace &w, hipStream_t s)
+// One iteration for Ng right-hand sides whose arrays start at y / sel / x / w, enqueued on s:
+// the contraction ...
+static hipError_t omp_contraction(const OmpPlan &pl, const MatrixView &A, int32_t Ng, const OmpWorkspace &w,
+                                  hipStream_t s)
 {
-    {
-        ProfileScope prof(KC_CORR, s);
-        hipError_t e = hipSuccess;
-        if (pl.panels) {
-            for (int32_t p0 = 0; p0 < A.d && e == hipSuccess; p0 += w.panel_rows) {
-                const int32_t rows = A.d - p0 < w.panel_rows ? A.d - p0 : w.panel_rows;
-                if (w.panel_rows < A.d) { // a matrix larger than the panel is refilled panel by panel
-                    e = launch_matrix_fill(A.key0, A.key1, A.scale, A.r, p0, rows, w.panel, s, KC_FILL);
-                    if (e != hipSuccess)
-                        break;
-                }
-                MatrixView Ap = A;
-                Ap.generated = 0;
-                Ap.At = w.panel;
-                Ap.row0 = p0;
-                e = pl.pipelined ? corr_pipelined_launch(Ap, rows, w.res32, Ng, w, pl.tiles_m, s)
-                                 : corr_dispatch<false>(Ap, rows, w.res32, Ng, w, pl.tiles_m, s);
+    ProfileScope prof(KC_CORR, s);
+    hipError_t e = hipSuccess;
+    if (pl.panels) {
+        for (int32_t p0 = 0; p0 < A.d && e == hipSuccess; p0 += w.panel_rows) {
+            const int32_t rows = A.d - p0 < w.panel_rows ? A.d - p0 : w.panel_rows;
+            if (w.panel_rows < A.d) { // a matrix larger than the panel is refilled panel by panel
+                e = launch_matrix_fill(A.key0, A.key1, A.scale, A.r, p0, rows, w.panel, s, KC_FILL);
+                if (e != hipSuccess)
+                    break;
             }
-        } else if (A.generated) {
-            e = corr_dispatch<true>(A, A.d, w.res32, Ng, w, pl.tiles_m, s);
-        } else {
-            e = pl.pipelined ? corr_pipelined_launch(A, A.d, w.res32, Ng, w, pl.tiles_m, s)
-                             : corr_dispatch<false>(A, A.d, w.res32, Ng, w, pl.tiles_m, s);
+            MatrixView Ap = A;
+            Ap.generated = 0;
+            Ap.At = w.panel;
+            Ap.row0 = p0;
+            e = pl.pipelined ? corr_pipelined_launch(Ap, rows, w.res32, Ng, w, pl.tiles_m, s)
+                             : corr_dispatch<false>(Ap, rows, w.res32, Ng, w, pl.tiles_m, s);
         }
-        if (e != hipSuccess)
-            return e;
+    } else if (A.generated) {
+        e = corr_dispatch<true>(A, A.d, w.res32, Ng, w, pl.tiles_m, s);
+    } else {
+        e = pl.pipelined ? corr_pipelined_launch(A, A.d, w.res32, Ng, w, pl.tiles_m, s)
+                         : corr_dispatch<false>(A, A.d, w.res32, Ng, w, pl.tiles_m, s);
     }
-    {
-        ProfileScope prof(KC_SELECT, s);
-        int slices = 2048 / Ng;
-        slices = slices < 1 ? 1 : (slices > 8 ? 8 : slices);
-        const dim3 pgrid((unsigned)Ng, (unsigned)slices);
-        const dim3 rgrid((unsigned)Ng, (unsigned)(((A.r >> 2) + RES_THREADS - 1) / RES_THREADS));
-        IterArgs P{y, k, it, sel, x, w, pl.Apick.generated ? nullptr : pl.Apick.At};
-        if (pl.Apick.generated)
-            pick_kernel<true><<<pgrid, PICK_THREADS, pl.pick_smem, s>>>(pl.Apick, P);
-        else
-            pick_kernel<false><<<pgrid, PICK_THREADS, pl.pick_smem, s>>>(pl.Apick, P);
-        if (k <= 128)
-            factor_kernel<2, true><<<dim3((unsigned)Ng), 256, pl.factor_smem, s>>>(P);
-        else if (k <= 256)
-            factor_kernel<4, true><<<dim3((unsigned)Ng), FACTOR_MAX_THREADS, pl.factor_smem, s>>>(P);
-        else
-            factor_kernel<16, false><<<dim3((unsigned)Ng), FACTOR_MAX_THREADS, pl.factor_smem, s>>>(P);
-        residual_kernel<<<rgrid, RES_THREADS, 16 * (size_t)(it + 1), s>>>(P, A.r);
-    }
-    return hipSuccess;
+    return e;
+}
+
+// ... then the selection and the least-squares update
+static void omp_select_update(const OmpPlan &pl, const MatrixView &A, const float *y, int32_t Ng, int32_t k,
+                              int32_t it, int32_t *sel, float *x, const OmpWorkspace &w, hipStream_t s)
+{
+    ProfileScope prof(KC_SELECT, s);
+    int slices = 2048 / Ng;
+    slices = slices < 1 ? 1 : (slices > 8 ? 8 : slices);
+    const dim3 pgrid((unsigned)Ng, (unsigned)slices);
+    const dim3 rgrid((unsigned)Ng, (unsigned)(((A.r >> 2) + RES_THREADS - 1) / RES_THREADS));
+    IterArgs P{y, k, it, sel, x, w, pl.Apick.generated ? nullptr : pl.Apick.At};
+    if (pl.Apick.generated)
+        pick_kernel<true><<<pgrid, PICK_THREADS, pl.pick_smem, s>>>(pl.Apick, P);
+    else
+        pick_kernel<false><<<pgrid, PICK_THREADS, pl.pick_smem, s>>>(pl.Apick, P);
+    if (k <= 128)
+        factor_kernel<2, true><<<dim3((unsigned)Ng), 256, pl.factor_smem, s>>>(P);
+    else if (k <= 256)
+        factor_kernel<4, true><<<dim3((unsigned)Ng), FACTOR_MAX_THREADS, pl.factor_smem, s>>>(P);
+    else
+        factor_kernel<16, false><<<dim3((unsigned)Ng), FACTOR_MAX_THREADS, pl.factor_smem, s>>>(P);
+    residual_kernel<<<rgrid, RES_THREADS, 16 * (size_t)(it + 1), s>>>(P, A.r);
 }
 
 // A second stream (default priority) and two events per device, created on first use, so that the
@@ -1059,9 +1059,10 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
     if (!ss) {
         const OmpWorkspace w = shift_workspace(ws, 0, A.r, k, pl.tiles_m);
         for (int32_t it = 0; it < k; ++it) {
-            hipError_t e = omp_iteration(pl, A, y, N, k, it, sel, x, w, s);
+            hipError_t e = omp_contraction(pl, A, N, w, s);
             if (e != hipSuccess)
                 return e;
+            omp_select_update(pl, A, y, N, k, it, sel, x, w, s);
         }
         return hipGetLastError();
     }
@@ -1071,10 +1072,15 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
         return hipErrorUnknown;
     hipError_t e = hipSuccess;
     for (int32_t it = 0; it < k && e == hipSuccess; ++it) {
-        e = omp_iteration(pl, A, y, N0, k, it, sel, x, w0, s);
-        if (e == hipSuccess)
-            e = omp_iteration(pl, A, y + (int64_t)N0 * A.r, N - N0, k, it, sel + (int64_t)N0 * k, x + (int64_t)N0 * k,
-                              w1, ss->stream);
+        e = omp_contraction(pl, A, N0, w0, s);
+        if (e != hipSuccess)
+            break;
+        omp_select_update(pl, A, y, N0, k, it, sel, x, w0, s);
+        e = omp_contraction(pl, A, N - N0, w1, ss->stream);
+        if (e != hipSuccess)
+            break;
+        omp_select_update(pl, A, y + (int64_t)N0 * A.r, N - N0, k, it, sel + (int64_t)N0 * k, x + (int64_t)N0 * k, w1,
+                          ss->stream);
     }
     // join even after a failed launch so that the caller's stream never runs ahead of the side stream
     if (hipEventRecord(ss->join, ss->stream) != hipSuccess || hipStreamWaitEvent(s, ss->join, 0) != hipSuccess)

@@ -339,7 +339,8 @@ def test_apply_formula_by_hand():
     assert np.allclose(out.ravel(), exp, rtol=1e-6)
 
 
-def test_first_step_closed_form_in_exact_recovery_regime():
+@pytest.mark.parametrize("shared", [False, True])
+def test_first_step_closed_form_in_exact_recovery_regime(shared):
     """With zero initial moments Mhat_1 = p and Vhat_1 = q (Alg. 2), so when OMP recovers the
     k-sparse G~ and G~^2 exactly, N_1 = alpha G~/(|G~| + eps) on the top-k support (eq. 11)."""
     w = synth.shrink(synth.CFG1, C=3, d=2048, r=512, k=8)
@@ -348,7 +349,7 @@ def test_first_step_closed_form_in_exact_recovery_regime():
     W0 = synth.weights(w)
     z = np.zeros((w.C, w.r), np.float32)
     alpha, eps, lr = 2.0, 1e-8, 1e-3
-    out = orc.step(g, W0, z, z, 1, At, w.k, alpha=alpha, eps=eps, lr=lr)
+    out = orc.step(g, W0, z, z, 1, At, w.k, alpha=alpha, eps=eps, lr=lr, shared_support=shared)
     assert np.allclose(out["mhat"], out["p"], rtol=2e-6, atol=0)
     assert np.allclose(out["vhat"], out["q"], rtol=2e-6, atol=0)
     exp = W0.astype(np.float64).copy().reshape(w.C, w.d)
@@ -365,3 +366,53 @@ def test_first_step_closed_form_in_exact_recovery_regime():
     for c in range(w.C):
         mask[c, out["idx"][c]] = False
     assert np.array_equal(out["W"].reshape(w.C, w.d)[mask], W0.reshape(w.C, w.d)[mask])
+
+
+# --------------------------------------------------------------------------- shared-support recovery
+@pytest.mark.parametrize("d,r,k,seed", [(50, 20, 1, 0), (300, 64, 7, 1), (1000, 128, 32, 2)])
+def test_lstsq_on_a_support_equals_the_library_routine(d, r, k, seed):
+    rng = np.random.default_rng(seed)
+    At = synth.gaussian_matrix(seed + 40, d, r)
+    sel = rng.permutation(d)[:k].astype(np.int32)
+    y = rng.standard_normal(r).astype(np.float32)
+    ref, *_ = np.linalg.lstsq(At[sel].astype(np.float64).T, y.astype(np.float64), rcond=None)
+    got = orc.lstsq_support(y, At, sel)
+    assert np.abs(got - ref).max() < 1e-10 * max(1.0, np.abs(ref).max())
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_shared_support_recovers_both_moments_of_a_sparse_pair(seed):
+    """Two k-sparse vectors with the same non-zero positions (G~ and G~^2 in Sec. 4.3) measured with
+    the same A: the support comes from the first alone and both are reconstructed, each aligned with
+    the selection order."""
+    d, k, r = 1024, 8, 256
+    At = synth.gaussian_matrix(seed + 60, d, r)
+    x, pos = synth.sparse_signal(seed, d, k)
+    z = x * x * 3.0
+    A64 = At.astype(np.float64).T
+    ym = (A64 @ x).astype(np.float32)[None]
+    yv = (A64 @ z).astype(np.float32)[None]
+    sel, xs, zs = orc.omp_shared(ym, yv, At, k)
+    assert sorted(sel[0].tolist()) == pos.tolist()
+    assert np.array_equal(sel[0], orc.omp(ym[0], At, k)["sel"])
+    assert np.abs(xs[0] - x[sel[0]]).max() < 1e-5 * np.abs(x).max()
+    assert np.abs(zs[0] - z[sel[0]]).max() < 1e-5 * np.abs(z).max()
+
+
+def test_shared_support_fit_in_the_noisy_regime_is_the_projection_onto_the_support():
+    """z is the least-squares fit of the SECOND right-hand side: its residual is orthogonal to the
+    selected columns, and it differs from the fit of the first."""
+    d, k, r = 400, 12, 48
+    rng = np.random.default_rng(5)
+    At = synth.gaussian_matrix(77, d, r)
+    ym = rng.standard_normal((2, r)).astype(np.float32)
+    yv = rng.standard_normal((2, r)).astype(np.float32)
+    sel, xs, zs = orc.omp_shared(ym, yv, At, k)
+    for c in range(2):
+        As = At[sel[c]].astype(np.float64).T
+        for y, sol in ((ym[c], xs[c]), (yv[c], zs[c])):
+            ref, *_ = np.linalg.lstsq(As, y.astype(np.float64), rcond=None)
+            assert np.abs(sol - ref).max() < 1e-5 * np.abs(ref).max()
+        res = yv[c].astype(np.float64) - As @ orc.lstsq_support(yv[c], At, sel[c])
+        assert np.abs(As.T @ res).max() < 1e-10 * np.linalg.norm(yv[c])
+        assert np.abs(zs[c] - xs[c]).max() > 1e-3
