@@ -33,6 +33,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", type=int, default=2, help="configuration index 1..5 (default 2)")
     ap.add_argument("--chunks", type=int, default=0, help="override the number of chunks (0 = as defined)")
+    ap.add_argument("--shared-support", action="store_true",
+                    help="recover one support per chunk from mhat and fit vhat on it (sgc_recover_omp_shared) "
+                         "instead of the two independent recoveries of Alg. 2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (reference for the rocprofv3 FETCH_SIZE / "
@@ -84,7 +87,7 @@ def main():
 
     def run(n):
         for t in range(1, n + 1):
-            sgc.step(grads[t - 1], Wt, buf, A, t, h)
+            sgc.step(grads[t - 1], Wt, buf, A, t, h, shared_support=args.shared_support)
 
     run(Wm)
     torch.cuda.synchronize()
@@ -111,13 +114,15 @@ def main():
     fill_ms, _ = prof["omp_matrix_fill"]
     # one launch covers all d positions (stored / in-kernel generated A) or one panel of them
     launches_per_iter = corr_n / (K * k)
-    flops_per_launch = 2.0 * d * r * (2 * C) / launches_per_iter
+    nrhs = C if args.shared_support else 2 * C
+    flops_per_launch = 2.0 * d * r * nrhs / launches_per_iter
     avg_ms = corr_ms / max(corr_n, 1)
     achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12
     roofline = {
         "bound": "mfma", "kernel": "omp correlation contraction At*R (float 32x32x2 MFMA, fused argmax epilogue)",
         "achieved": round(achieved, 3), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
-        "frac": round(achieved / MFMA_F32_PEAK_TFLOPS, 4), "traffic": MEASURED_TRAFFIC.get(w.name),
+        "frac": round(achieved / MFMA_F32_PEAK_TFLOPS, 4),
+        "traffic": None if args.shared_support else MEASURED_TRAFFIC.get(w.name),
         "flops_per_launch": flops_per_launch, "avg_launch_ms": round(avg_ms, 5), "launches": corr_n,
     }
     if fill_ms > 0:  # generated A produced by a separate fill kernel: the rate including that time
@@ -136,7 +141,8 @@ def main():
         "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "chunks": C, "d": d, "r": r, "k": k, "grad": w.grad, "matrix": w.matrix,
-                   "rhs_per_omp_call": 2 * C},
+                   "rhs_per_omp_call": nrhs,
+                   "recovery": "shared_support" if args.shared_support else "two_supports"},
         "roofline": roofline,
         "ms_per_step_with_events": round((t3 - t2) * 1e3 / K, 3),
         "kernels": kernels,
@@ -150,12 +156,12 @@ def main():
         torch.cuda.synchronize()
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, At_host)
+        out["cpu_baseline"] = cpu_baseline(w, At_host, args.shared_support)
     print(json.dumps(out))
     return 0
 
 
-def cpu_baseline(w, At_host):
+def cpu_baseline(w, At_host, shared_support=False):
     """The CPU oracle (single thread, as it stands) on chunk 0 of step 1 of the same workload."""
     import numpy as np
     from oracle import oracle as orc
@@ -181,12 +187,18 @@ def cpu_baseline(w, At_host):
     Wc = synth.weights(w, chunks=[0])
     orc.apply(Wc, w.d, o["sel"][None], o["x"][None], o["sel"][None], np.abs(o["x"])[None])
     t3 = time.perf_counter()
-    t_chunk = (t1 - t0) + 2.0 * (t2 - t1) * (w.k / iters) + (t3 - t2)
+    t_fit = 0.0
+    if shared_support:
+        t4 = time.perf_counter()
+        orc.lstsq_support(vh[0], At_host, o["sel"])
+        t_fit = time.perf_counter() - t4
+    t_chunk = (t1 - t0) + (1.0 if shared_support else 2.0) * (t2 - t1) * (w.k / iters) + (t3 - t2) + t_fit
     return {
         "value": round(w.d / t_chunk, 2), "unit": "elements/s", "cores": 1, "kind": "oracle",
         "sample": "chunk 0 of step 1 (1 of %d chunks): top-k, projection, Adam, OMP(mhat) timed for %d of %d "
-                  "iterations and scaled, OMP(vhat) counted at the same cost, apply; %.1f s of CPU work measured"
-                  % (w.C, iters, w.k, t3 - t0),
+                  "iterations and scaled, %s, apply; %.1f s of CPU work measured"
+                  % (w.C, iters, w.k, "least-squares fit of vhat on the support" if shared_support
+                     else "OMP(vhat) counted at the same cost", t3 - t0 + t_fit),
         "host_cores": os.cpu_count(),
     }
 

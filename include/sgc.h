@@ -8,6 +8,7 @@
  *   sgc_adam_compressed    Alg. 2 lines 2-5 moments in R^r and their bias-corrected copies
  *   sgc_recover_omp        Alg. 2 line 6   x = OMP_A(mhat), z = OMP_A(vhat)  (eq. 9, App. B)
  *   sgc_apply              eq. 11 + eq. 3  W <- W - lr * alpha * x / (sqrt(z) + eps)
+ * (sgc_recover_omp_shared is a variant of the third call that finds one support per chunk.)
  *
  * Conventions
  *   - Plain C. Every array pointer is a DEVICE pointer owned by the caller unless the
@@ -155,6 +156,22 @@ size_t sgc_omp_workspace_bytes(int32_t N, int32_t d, int32_t r, int32_t k);
  */
 sgc_status sgc_recover_omp(const float *y, int32_t N, const sgc_matrix *A /* host */, int32_t k,
                            int32_t *sel, float *x, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Shared-support recovery for C chunks. Sec. 4.3 (the remark after eq. 11) rests the element-wise
+ * division of eq. 11 on both recovered moments having their non-zeros at the same positions; this
+ * call makes that hold by construction and halves the contraction work: the support and x come
+ * from OMP on y_m alone (exactly sgc_recover_omp with N = C), and the second moment is fitted on
+ * the same support, z = argmin || y_v - A_Lambda z ||_2 (in double, from the inverse Cholesky
+ * factor the recovery has built).
+ *   y_m, y_v  [C][r]  the bias-corrected first / second moments
+ *   sel       out [C][k] selection order;  x, z  out [C][k] aligned with sel
+ *   ws        at least sgc_omp_workspace_bytes(C, d, r, k) bytes, 256-byte aligned
+ * Feed sgc_apply with (sel, x, sel, z). Errors: as sgc_recover_omp.
+ */
+sgc_status sgc_recover_omp_shared(const float *y_m, const float *y_v, int32_t C,
+                                  const sgc_matrix *A /* host */, int32_t k, int32_t *sel, float *x,
+                                  float *z, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * eq. 11 and eq. 3 on the recovered supports of C chunks:

@@ -162,6 +162,24 @@ sgc_status sgc_recover_omp(const float *y, int32_t N, const sgc_matrix *A, int32
     return from_hip(launch_omp(y, N, make_view(A), k, sel, x, w, (hipStream_t)stream));
 }
 
+sgc_status sgc_recover_omp_shared(const float *y_m, const float *y_v, int32_t C, const sgc_matrix *A, int32_t k,
+                                  int32_t *sel, float *x, float *z, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!y_m || !y_v || !sel || !x || !z || !ws)
+        return SGC_ERR_NULL;
+    sgc_status st = check_matrix(A, true);
+    if (st != SGC_OK)
+        return st;
+    if (!omp_sizes_ok(C, A->d, A->r, k))
+        return SGC_ERR_SHAPE;
+    if (!aligned16(y_m) || !aligned16(y_v) || !aligned16(A->inv_colnorm) || ((uintptr_t)ws & 255u))
+        return SGC_ERR_ALIGN;
+    const OmpWorkspace w = carve_workspace(ws, C, A->d, A->r, k);
+    if (ws_bytes < w.bytes)
+        return SGC_ERR_WORKSPACE;
+    return from_hip(launch_omp(y_m, C, make_view(A), k, sel, x, w, (hipStream_t)stream, y_v, z));
+}
+
 sgc_status sgc_apply(float *W, int64_t C, int32_t d, int32_t k, const int32_t *sel_m, const float *x_m,
                      const int32_t *sel_v, const float *x_v, const sgc_hyper *h, void *stream)
 {

@@ -517,7 +517,8 @@ static bool corr_pipelined_ok(const MatrixView &A, int32_t N, int32_t panel_rows
     return A.d % CORRP_BM == 0 && N % CORRP_BN == 0 && A.r % 64 == 0 && panel_rows % CORRP_BM == 0;
 }
 
-// The tiling in use: 128 x 128 outputs, depth 32 per stage, 2 x 2 wavefronts, two workgroups per CU.
+// The tiling in use: 128 x 128 outputs (128 x 64 when there are at most 64 right-hand sides), depth 32
+// per stage, 2 x 2 wavefronts, two workgroups per CU.
 // It is the general kernel: any d, N, r % 4 == 0, generated or stored A. (Other shapes of this
 // compiler-scheduled kernel - 256 x 128 with 4 or 8 wavefronts, depth 16 or 64, LDS filled directly
 // with global_load_lds - all measured within 2 % of it inside the full step.)
@@ -525,6 +526,8 @@ template <bool GENERATED>
 static hipError_t corr_dispatch(const MatrixView &A, int32_t rows, const float *R, int32_t N, const OmpWorkspace &ws,
                                 int32_t tiles_m, hipStream_t s)
 {
+    if (N <= 64) // a single half-width tile of right-hand sides: no matrix-core work on padding
+        return corr_launch<GENERATED, CORR_BM, 64, 32, 2, 2, 2>(A, rows, R, N, ws, tiles_m, s);
     return corr_launch<GENERATED, CORR_BM, CORR_BN, 32, 2, 2, 2>(A, rows, R, N, ws, tiles_m, s);
 }
 
@@ -917,6 +920,60 @@ __global__ __launch_bounds__(RES_THREADS) void residual_kernel(IterArgs P, int32
     reinterpret_cast<float4 *>(W.res32 + n * r)[jb] = make_float4((float)e0, (float)e1, (float)e2, (float)e3);
 }
 
+// Least-squares fit of a second right-hand side on the support already found (shared-support
+// recovery): z = (A_L^T A_L)^-1 A_L^T y_fit = F (F^T (A_L^T y_fit)) with the finished inverse
+// Cholesky factor F of the support (App. B), all in double. grid N; dynamic LDS: double b[k], u[k]
+constexpr int REFIT_THREADS = 1024;
+__global__ __launch_bounds__(REFIT_THREADS) void refit_kernel(IterArgs P, const float *__restrict__ y_fit,
+                                                              float *__restrict__ z, int32_t r)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    double *b_s = reinterpret_cast<double *>(smem);
+    double *u_s = b_s + P.k;
+    const int32_t k = P.k, r4 = r >> 2;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    constexpr int NW = REFIT_THREADS / 64;
+    const int64_t n = blockIdx.x;
+    const OmpWorkspace &W = P.ws;
+    const int32_t *selp = P.sel + n * k;
+    const float *cols = W.cols + (n * k) * (int64_t)r;
+    const float4 *yy = reinterpret_cast<const float4 *>(y_fit + n * r);
+    // b_t = <A_:lambda_t, y_fit>, one wavefront per selected column
+    for (int32_t t = wave; t < k; t += NW) {
+        const float4 *c = reinterpret_cast<const float4 *>(
+            P.At_rows ? P.At_rows + (int64_t)selp[t] * r : cols + (int64_t)t * r);
+        double acc = 0.0;
+        for (int32_t jb = lane; jb < r4; jb += 64) {
+            const float4 a = c[jb];
+            const float4 yv = yy[jb];
+            acc += (double)a.x * yv.x + (double)a.y * yv.y + (double)a.z * yv.z + (double)a.w * yv.w;
+        }
+        acc = wave_sum(acc);
+        if (lane == 0)
+            b_s[t] = acc;
+    }
+    __syncthreads();
+    // u = F^T b: column t of F (rows 0..t, contiguous) against b
+    const double *F = W.F + (n * k) * (int64_t)k;
+    for (int32_t t = wave; t < k; t += NW) {
+        const double *f = F + (int64_t)t * k;
+        double acc = 0.0;
+        for (int32_t v = lane; v <= t; v += 64)
+            acc += f[v] * b_s[v];
+        acc = wave_sum(acc);
+        if (lane == 0)
+            u_s[t] = acc;
+    }
+    __syncthreads();
+    // z = F u: row v of F holds the entries of columns t >= v
+    for (int32_t v = tid; v < k; v += REFIT_THREADS) {
+        double acc = 0.0;
+        for (int32_t t = v; t < k; ++t)
+            acc += F[(int64_t)t * k + v] * u_s[t];
+        z[n * k + v] = (float)acc;
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Host side of the recovery.
 struct OmpPlan {
@@ -1023,8 +1080,12 @@ static SideStream *side_stream()
     return ss.ok ? &ss : nullptr;
 }
 
+static hipError_t omp_iterations(const OmpPlan &pl, bool whole_matrix_panel, const float *y, int32_t N,
+                                 const MatrixView &A, int32_t k, int32_t *sel, float *x, const OmpWorkspace &ws,
+                                 hipStream_t s);
+
 hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k, int32_t *sel, float *x,
-                      const OmpWorkspace &ws, hipStream_t s)
+                      const OmpWorkspace &ws, hipStream_t s, const float *y_fit, float *z)
 {
     {
         ProfileScope prof(KC_OTHER, s);
@@ -1050,6 +1111,22 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
         pl.Apick.generated = 0;
         pl.Apick.At = ws.panel;
     }
+    hipError_t e = omp_iterations(pl, whole_matrix_panel, y, N, A, k, sel, x, ws, s);
+    if (e != hipSuccess || !y_fit)
+        return e;
+    {
+        ProfileScope prof(KC_SELECT, s);
+        const OmpWorkspace w = shift_workspace(ws, 0, A.r, k, pl.tiles_m);
+        IterArgs P{y, k, k, sel, x, w, pl.Apick.generated ? nullptr : pl.Apick.At};
+        refit_kernel<<<dim3((unsigned)N), REFIT_THREADS, 2 * sizeof(double) * (size_t)k, s>>>(P, y_fit, z, A.r);
+    }
+    return hipGetLastError();
+}
+
+static hipError_t omp_iterations(const OmpPlan &pl, bool whole_matrix_panel, const float *y, int32_t N,
+                                 const MatrixView &A, int32_t k, int32_t *sel, float *x, const OmpWorkspace &ws,
+                                 hipStream_t s)
+{
     // two halves side by side when the batch is large (not while kernels are being timed one by one,
     // and not when both halves would have to share a panel that is refilled inside the iterations)
     const int32_t N0 = (N / 2 + CORR_BN - 1) / CORR_BN * CORR_BN;

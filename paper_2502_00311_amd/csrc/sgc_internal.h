@@ -62,7 +62,7 @@ hipError_t launch_matrix_fill(uint32_t key0, uint32_t key1, float scale, int32_t
                               int64_t rows, float *out, hipStream_t s, int profile_class = KC_OTHER);
 hipError_t launch_colnorms(const MatrixView &A, float *out, hipStream_t s);
 hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k, int32_t *sel, float *x,
-                      const OmpWorkspace &ws, hipStream_t s);
+                      const OmpWorkspace &ws, hipStream_t s, const float *y_fit = nullptr, float *z = nullptr);
 hipError_t launch_apply(float *W, int64_t C, int32_t d, int32_t k, const int32_t *sel_m, const float *x_m,
                         const int32_t *sel_v, const float *x_v, float alpha, float eps, float lr,
                         hipStream_t s);

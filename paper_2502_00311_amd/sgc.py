@@ -19,7 +19,7 @@ MATRIX_STORED, MATRIX_PHILOX = 0, 1
 
 EXPORTS = [
     "sgc_status_string", "sgc_matrix_fill", "sgc_matrix_colnorms", "sgc_sparsify_project",
-    "sgc_adam_compressed", "sgc_omp_workspace_bytes", "sgc_recover_omp", "sgc_apply",
+    "sgc_adam_compressed", "sgc_omp_workspace_bytes", "sgc_recover_omp", "sgc_recover_omp_shared", "sgc_apply",
     "sgc_profile_enable", "sgc_profile_read",
 ]
 PROFILE_CLASSES = ["topk", "project", "adam", "omp_corr", "omp_select_update", "apply", "other", "omp_matrix_fill"]
@@ -72,6 +72,8 @@ def lib():
         L.sgc_omp_workspace_bytes.argtypes = [i32, i32, i32, i32]
         L.sgc_recover_omp.restype = i32
         L.sgc_recover_omp.argtypes = [vp, i32, ctypes.POINTER(sgc_matrix), i32, vp, vp, vp, sz, vp]
+        L.sgc_recover_omp_shared.restype = i32
+        L.sgc_recover_omp_shared.argtypes = [vp, vp, i32, ctypes.POINTER(sgc_matrix), i32, vp, vp, vp, vp, sz, vp]
         L.sgc_apply.restype = i32
         L.sgc_apply.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, ctypes.POINTER(sgc_hyper), vp]
         L.sgc_profile_enable.restype = i32
@@ -145,6 +147,10 @@ def sgc_recover_omp(y, N, A, k, sel, x, ws, stream=None):
     _check(lib().sgc_recover_omp(_ptr(y), N, ctypes.byref(A.c()), k, _ptr(sel), _ptr(x), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_recover_omp")
 
 
+def sgc_recover_omp_shared(y_m, y_v, C, A, k, sel, x, z, ws, stream=None):
+    _check(lib().sgc_recover_omp_shared(_ptr(y_m), _ptr(y_v), C, ctypes.byref(A.c()), k, _ptr(sel), _ptr(x), _ptr(z), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_recover_omp_shared")
+
+
 def sgc_apply(W, C, d, k, sel_m, x_m, sel_v, x_v, h, stream=None):
     _check(lib().sgc_apply(_ptr(W), C, d, k, _ptr(sel_m), _ptr(x_m), _ptr(sel_v), _ptr(x_v), ctypes.byref(h), _stream(stream)), "sgc_apply")
 
@@ -181,10 +187,16 @@ class StepBuffers:
         self.ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
 
 
-def step(grad, W, buf, A, t, h, stream=None):
-    """The four calls of one step, in order (Alg. 2 then the weight update)."""
+def step(grad, W, buf, A, t, h, stream=None, shared_support=False):
+    """The four calls of one step, in order (Alg. 2 then the weight update). shared_support: one
+    support per chunk from mhat with vhat fitted on it; then buf.sel[:C], buf.x[:C] hold the support
+    and x, buf.x[C:] holds z, and buf.sel[C:] is not written."""
     C, d, r, k = buf.C, buf.d, buf.r, buf.k
     sgc_sparsify_project(grad, C * d, d, k, A, buf.idx, buf.val, buf.p, buf.q, stream)
     sgc_adam_compressed(buf.p, buf.q, buf.m, buf.v, buf.hat[:C], buf.hat[C:], C * r, t, h, stream)
+    if shared_support:
+        sgc_recover_omp_shared(buf.hat[:C], buf.hat[C:], C, A, k, buf.sel[:C], buf.x[:C], buf.x[C:], buf.ws, stream)
+        sgc_apply(W, C, d, k, buf.sel[:C], buf.x[:C], buf.sel[:C], buf.x[C:], h, stream)
+        return
     sgc_recover_omp(buf.hat, 2 * C, A, k, buf.sel, buf.x, buf.ws, stream)
     sgc_apply(W, C, d, k, buf.sel[:C], buf.x[:C], buf.sel[C:], buf.x[C:], h, stream)
