@@ -338,7 +338,9 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
     constexpr int LA = 8, LB = 4; // 16-byte pieces per thread per stage
     typedef float floatx4 __attribute__((ext_vector_type(4)));
     extern __shared__ __attribute__((aligned(16))) float corr_lds[];
-    float *lds = corr_lds; // A stages [2][BM*LD], then R stages [2][BN*LD]
+    float *lds = corr_lds; // A stages [2][BM*LD], then R stages [2][BN*LD], then what the epilogue needs:
+    float *inv_s = corr_lds + 2 * (BM + BN) * LD;                       // reciprocal norms of the BM positions
+    uint32_t *msk_s = reinterpret_cast<uint32_t *>(inv_s + BM);         // selection words [BN][BM/32]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int32_t r = A.r;
@@ -386,8 +388,22 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
         acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(x, y, acc[a][b], 0, 0, 0);
     };
 
-    // prologue: stage 0 -> LDS, stage 1 -> staging registers, fragments of (stage 0, group 0)
+    // prologue: stage 0 -> LDS, stage 1 -> staging registers, fragments of (stage 0, group 0); the
+    // epilogue's operands are fetched here too, so that it does not wait for memory at the end
     static_for<0, LA + LB>([&](auto uc) { gload(decltype(uc)::value, 0); });
+    {
+        const float nv = A.inv_colnorm[m0 + tid];
+        uint32_t mw[BN * (BM / 32) / 256];
+#pragma unroll
+        for (int u = 0; u < BN * (BM / 32) / 256; ++u) {
+            const int e = tid + 256 * u;
+            mw[u] = bitmap[(int64_t)(n0 + (e >> 3)) * words + (m0 >> 5) + (e & 7)];
+        }
+        inv_s[tid] = nv;
+#pragma unroll
+        for (int u = 0; u < BN * (BM / 32) / 256; ++u)
+            msk_s[tid + 256 * u] = mw[u];
+    }
     static_for<0, LA + LB>([&](auto uc) { lwrite(decltype(uc)::value, 0); });
     static_for<0, LA + LB>([&](auto uc) { gload(decltype(uc)::value, 1); });
     __syncthreads();
@@ -435,51 +451,89 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
     }
     __syncthreads();
 
-    // epilogue, one 32-row block of accumulators at a time (keeps the register peak low); same
-    // reduction as corr_epilogue
+    // epilogue, one 32-row block of accumulators at a time (keeps the register peak low). Inside a
+    // wavefront's 128 positions the two best are kept as 32-bit keys: the float score bits with the
+    // low byte replaced by 255 - (position within the 128), so an unsigned max is the argmax with the
+    // lower position winning among equal keys, and a selected position is key 0, below every live
+    // one. Dropping 8 mantissa bits (2^-15 relative) is far inside the band of near-maximal
+    // candidates that the selection kernel re-scores in double anyway.
+    // Selected positions are left in on the first scan: their columns are orthogonal to the residual,
+    // so they only reach the top two when the whole residual is rounding noise or zero; the two
+    // winners are then tested against the selection bitmap and, if any lane of the wavefront holds a
+    // selected one, the scan is repeated with the selected positions forced to key 0.
     uint64_t *red = reinterpret_cast<uint64_t *>(corr_lds);
-    const int32_t d = A.d;
-    uint64_t best[NB], second[NB];
+    uint32_t best[NB], second[NB], msk[MB][NB];
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        best[b] = 0;
-        second[b] = 0;
-    }
+    for (int a = 0; a < MB; ++a)
 #pragma unroll
-    for (int a = 0; a < MB; ++a) {
-        const int32_t ibase = m0 + wm * 128 + a * 32;
-        float4 inv[4];
-#pragma unroll
-        for (int qd = 0; qd < 4; ++qd)
-            inv[qd] = *reinterpret_cast<const float4 *>(A.inv_colnorm + ibase + 8 * qd + 4 * lhalf);
+        for (int b = 0; b < NB; ++b)
+            msk[a][b] = msk_s[(wn * 64 + b * 32 + l32) * (BM / 32) + wm * 4 + a];
+    auto scan = [&](auto maskedc) {
+        constexpr bool MASKED = decltype(maskedc)::value;
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-            const int32_t n = n0 + wn * 64 + b * 32 + l32;
-            const uint32_t mask = bitmap[(int64_t)n * words + (ibase >> 5)];
-            asm volatile("; accumulator block stays in AGPRs up to here" : "+a"(acc[a][b]));
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int off = 8 * (v >> 2) + 4 * lhalf + (v & 3);
-                const int32_t i = ibase + off;
-                const float4 nv = inv[v >> 2];
-                const float in = (v & 3) == 0 ? nv.x : ((v & 3) == 1 ? nv.y : ((v & 3) == 2 ? nv.z : nv.w));
-                const float score = fabsf(acc[a][b][v]) * in;
-                const bool ok = i < d && !((mask >> off) & 1u);
-                const uint64_t key = ok ? (((uint64_t)__float_as_uint(score) << 32) | (uint64_t)(0xffffffffu - (uint32_t)i)) : 0ull;
-                top2_insert(key, best[b], second[b]);
-            }
+            best[b] = 0;
+            second[b] = 0;
         }
-        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int a = 0; a < MB; ++a) {
+            float4 inv[4];
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd)
+                inv[qd] = *reinterpret_cast<const float4 *>(inv_s + wm * 128 + a * 32 + 8 * qd + 4 * lhalf);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                // this lane's 16 positions of the block are bits 8*(v/4) + v%4 of the shifted word
+                const uint32_t mask = msk[a][b] >> (4 * lhalf);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int bit = 8 * (v >> 2) + (v & 3);
+                    const float4 nv = inv[v >> 2];
+                    const float in = (v & 3) == 0 ? nv.x : ((v & 3) == 1 ? nv.y : ((v & 3) == 2 ? nv.z : nv.w));
+                    const float score = fabsf(acc[a][b][v]) * in;
+                    // low byte: 255 - (a*32 + bit); the lane's own 4*lhalf is accounted for when widening
+                    uint32_t key = (__float_as_uint(score) & 0xffffff00u) | (uint32_t)(255 - (a * 32 + bit));
+                    if (MASKED)
+                        key = ((mask >> bit) & 1u) ? 0u : key;
+                    second[b] = max(second[b], min(key, best[b]));
+                    best[b] = max(best[b], key);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    scan(std::false_type{});
+    uint32_t hit = 0;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+#pragma unroll
+        for (int which = 0; which < 2; ++which) {
+            const uint32_t k32 = which ? second[b] : best[b];
+            const uint32_t pos = 255u - (k32 & 0xffu) + 4u * (uint32_t)lhalf; // within the wavefront's 128
+#pragma unroll
+            for (int a = 0; a < MB; ++a) // straight-line: every block's word is tested
+                hit |= ((msk[a][b] >> (pos & 31u)) & 1u) & (uint32_t)((pos >> 5) == (uint32_t)a);
+        }
     }
+    if (__builtin_amdgcn_ballot_w64(hit != 0u) != 0ull)
+        scan(std::true_type{});
+    const uint32_t pos0 = (uint32_t)(m0 + wm * 128);
+    auto widen = [&](uint32_t k32) -> uint64_t { // (score bits, ~position) as the selection kernel reads it
+        if (k32 == 0)
+            return 0ull;
+        const uint32_t i = pos0 + (255u - (k32 & 0xffu)) + 4u * (uint32_t)lhalf;
+        return ((uint64_t)(k32 & 0xffffff00u) << 32) | (uint64_t)(0xffffffffu - i);
+    };
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         const int nl = wn * 64 + b * 32 + l32;
-        const uint64_t ob = shfl_xor_u64(best[b], 32), os = shfl_xor_u64(second[b], 32);
-        top2_insert(ob, best[b], second[b]);
-        top2_insert(os, best[b], second[b]);
+        uint64_t wb = widen(best[b]), ws2 = widen(second[b]);
+        const uint64_t ob = shfl_xor_u64(wb, 32), os = shfl_xor_u64(ws2, 32);
+        top2_insert(ob, wb, ws2);
+        top2_insert(os, wb, ws2);
         if (lhalf == 0) {
-            red[(wm * BN + nl) * 2 + 0] = best[b];
-            red[(wm * BN + nl) * 2 + 1] = second[b];
+            red[(wm * BN + nl) * 2 + 0] = wb;
+            red[(wm * BN + nl) * 2 + 1] = ws2;
         }
     }
     __syncthreads();
@@ -497,7 +551,8 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
 static hipError_t corr_pipelined_launch(const MatrixView &A, int32_t rows, const float *R, int32_t N,
                                         const OmpWorkspace &ws, int32_t tiles_m, hipStream_t s)
 {
-    constexpr size_t smem = (size_t)2 * (CORRP_BM + CORRP_BN) * 36 * sizeof(float);
+    constexpr size_t smem = (size_t)2 * (CORRP_BM + CORRP_BN) * 36 * sizeof(float) + CORRP_BM * sizeof(float) +
+                            (size_t)CORRP_BN * (CORRP_BM / 32) * sizeof(uint32_t);
     static bool raised = false;
     if (!raised) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_pipelined_kernel),
