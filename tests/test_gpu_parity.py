@@ -243,6 +243,36 @@ def test_omp_exact_recovery_zero_and_oversized_k():
     assert np.array_equal(sel[3], rsel[3]) and relerr(x[3], rx[3]) < TOL
 
 
+def test_omp_full_tiles_with_zero_and_sparse_right_hand_sides():
+    """Full tiles of a stored matrix (the pipelined contraction): all-zero right-hand sides and ones
+    sparser than k drive the residual to zero / rounding noise, where already selected positions can
+    reach the top of a tile and must still never be selected twice."""
+    N, d, r, k = 128, 1024, 256, 8
+    A, At = make_matrix("stored", 20, d, r)
+    A64 = At.astype(np.float64).T
+    rng = np.random.default_rng(12)
+    Y = rng.standard_normal((N, r)).astype(np.float32)
+    Y[0] = 0.0
+    Y[77] = 0.0
+    sparse_rows = {}
+    for n, ks in ((1, 8), (2, 3), (64, 5), (127, 1)):
+        xs, pos = synth.sparse_signal(n, d, ks)
+        Y[n] = (A64 @ xs).astype(np.float32)
+        sparse_rows[n] = (ks, pos)
+    sel, x = run_omp(Y, A, k)
+    assert all(len(set(row.tolist())) == k for row in sel) and sel.min() >= 0 and sel.max() < d
+    assert sel[0].tolist() == list(range(k)) and sel[77].tolist() == list(range(k)) and not x[0].any()
+    norm = orc.colnorms(At)
+    for n, (ks, pos) in sparse_rows.items():
+        assert sorted(sel[n][:ks].tolist()) == pos.tolist(), n
+        ref = orc.omp(Y[n], At, ks, norm=norm)
+        assert np.array_equal(sel[n][:ks], ref["sel"]) and relerr(x[n][:ks], ref["x"]) < TOL
+        assert np.abs(x[n][ks:]).max(initial=0.0) < 1e-5 * np.abs(x[n][:ks]).max()
+    for n in (3, 50, 126):   # ordinary noisy right-hand sides in the same launch
+        ref = orc.omp(Y[n], At, k, norm=norm)
+        assert np.array_equal(sel[n], ref["sel"]) and relerr(x[n], ref["x"]) < TOL
+
+
 def test_omp_is_deterministic():
     rng = np.random.default_rng(5)
     A, At = make_matrix("philox", 4, 3000, 128)
