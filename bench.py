@@ -23,7 +23,7 @@ sys.path.insert(0, ROOT)
 MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense float matrix peak
 # HBM bytes per launch of the correlation kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/), keyed by workload name; None until measured.
-MEASURED_TRAFFIC = {"cfg2_64x65536": 5.531e8}  # profiles/cfg2_corr_kernel_hbm_traffic.md
+MEASURED_TRAFFIC = {"cfg2_64x65536": 5.528e8}  # profiles/cfg2_corr_kernel_hbm_traffic.md
 
 
 def main():
