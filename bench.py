@@ -36,6 +36,9 @@ def main():
     ap.add_argument("--shared-support", action="store_true",
                     help="recover one support per chunk from mhat and fit vhat on it (sgc_recover_omp_shared) "
                          "instead of the two independent recoveries of Alg. 2")
+    ap.add_argument("--materialize", action="store_true",
+                    help="a generated matrix is written out once with sgc_matrix_fill (outside the timed region) "
+                         "and handed over as a stored one: what a caller with HBM to spare would do")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (reference for the rocprofv3 FETCH_SIZE / "
@@ -66,6 +69,10 @@ def main():
     if w.matrix == "stored":
         At_host = synth.gaussian_matrix(w.a_seed, d, r)
         A = sgc.Matrix(d, r, At=torch.from_numpy(At_host).to(dev))
+    elif args.materialize:
+        At_dev = torch.empty((d, r), dtype=torch.float32, device=dev)
+        sgc.sgc_matrix_fill(w.a_seed, r, 0, d, At_dev)
+        A = sgc.Matrix(d, r, At=At_dev)
     else:
         A = sgc.Matrix(d, r, At=None, seed=w.a_seed)
     A.inv_colnorm = torch.empty(d, dtype=torch.float32, device=dev)
@@ -140,7 +147,8 @@ def main():
         "metric": "gradient elements/s per full SGC step (1 GPU)", "value": round(value, 1), "unit": "elements/s",
         "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w.name, "chunks": C, "d": d, "r": r, "k": k, "grad": w.grad, "matrix": w.matrix,
+        "config": {"workload": w.name, "chunks": C, "d": d, "r": r, "k": k, "grad": w.grad,
+                   "matrix": "philox, materialised by the caller" if (args.materialize and w.matrix != "stored") else w.matrix,
                    "rhs_per_omp_call": nrhs,
                    "recovery": "shared_support" if args.shared_support else "two_supports"},
         "roofline": roofline,

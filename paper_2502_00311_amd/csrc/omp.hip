@@ -307,8 +307,8 @@ static hipError_t corr_launch(const MatrixView &A, int32_t rows, const float *R,
     return hipSuccess;
 }
 
-// Software-pipelined contraction for full tiles of a stored matrix (rows % 256 == 0, N % 128 == 0,
-// r % 64 == 0): 256 x 128 outputs per workgroup, one wavefront per SIMD, each wavefront a 128 x 64
+// Software-pipelined contraction for full position tiles of a stored matrix (rows % 256 == 0,
+// r % 64 == 0; a ragged last tile of right-hand sides computes on copies of the last one): 256 x 128 outputs per workgroup, one wavefront per SIMD, each wavefront a 128 x 64
 // sub-tile (4 x 2 MFMA blocks, accumulators in AGPRs). A depth-32 stage is 4 groups of 32 MFMAs;
 // every memory operation is issued in the shadow of an MFMA and the order is pinned:
 //   group 0..2  fragment reads of the next group (double-buffered in registers)
@@ -349,6 +349,13 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
     const float *abase = A.At + (int64_t)(blockIdx.x * BM) * r;
     const float *bbase = R + (int64_t)n0 * r;
     const uint32_t lane_off = (uint32_t)((tid >> 3) * r + ((tid & 7) << 2));
+    // right-hand sides past the end of a ragged last tile re-read the last one; their results are dropped
+    uint32_t rhs_off[LB];
+#pragma unroll
+    for (int u = 0; u < LB; ++u) {
+        const int32_t n = n0 + 32 * u + (tid >> 3);
+        rhs_off[u] = (uint32_t)(((n < N ? n : N - 1) - n0) * r + ((tid & 7) << 2));
+    }
     const int ldst0 = (tid >> 3) * LD + ((tid & 7) << 2);
     const int nkb = r / BK;
 
@@ -367,8 +374,10 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
 
     auto gload = [&](int u, int kb) { // staging piece u of stage kb (the last stage again beyond the end)
         const int kk = (kb < nkb ? kb : nkb - 1) * BK;
-        const float *p = u < LA ? abase + ((int64_t)(32 * u) * r + kk) : bbase + ((int64_t)(32 * (u - LA)) * r + kk);
-        g[u] = *reinterpret_cast<const floatx4 *>(p + lane_off);
+        if (u < LA)
+            g[u] = *reinterpret_cast<const floatx4 *>(abase + ((int64_t)(32 * u) * r + kk) + lane_off);
+        else
+            g[u] = *reinterpret_cast<const floatx4 *>(bbase + kk + rhs_off[u < LA ? 0 : u - LA]);
     };
     auto lwrite = [&](int u, int buf) {
         const int off = u < LA ? buf * BM * LD + 32 * u * LD : 2 * BM * LD + buf * BN * LD + 32 * (u - LA) * LD;
@@ -397,7 +406,8 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
 #pragma unroll
         for (int u = 0; u < BN * (BM / 32) / 256; ++u) {
             const int e = tid + 256 * u;
-            mw[u] = bitmap[(int64_t)(n0 + (e >> 3)) * words + (m0 >> 5) + (e & 7)];
+            const int32_t n = n0 + (e >> 3);
+            mw[u] = bitmap[(int64_t)(n < N ? n : N - 1) * words + (m0 >> 5) + (e & 7)];
         }
         inv_s[tid] = nv;
 #pragma unroll
@@ -537,7 +547,7 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
         }
     }
     __syncthreads();
-    if (tid < BN) {
+    if (tid < BN && n0 + tid < N) {
         const int32_t n = n0 + tid;
         uint64_t b0 = red[tid * 2], s0 = red[tid * 2 + 1];
         top2_insert(red[(BN + tid) * 2], b0, s0);
@@ -561,15 +571,17 @@ static hipError_t corr_pipelined_launch(const MatrixView &A, int32_t rows, const
             return e;
         raised = true;
     }
-    const dim3 grid((unsigned)(rows / CORRP_BM), (unsigned)(N / CORRP_BN));
+    const dim3 grid((unsigned)(rows / CORRP_BM), (unsigned)((N + CORRP_BN - 1) / CORRP_BN));
     corr_pipelined_kernel<<<grid, 256, smem, s>>>(A, R, N, ws.bitmap, ws.words, ws.partial, tiles_m);
     return hipSuccess;
 }
 
-// whether the pipelined kernel covers this problem (full tiles, stored rows, even number of stages)
+// whether the pipelined kernel covers this problem (full tiles of positions, stored rows, even number
+// of stages; the last tile of right-hand sides may be ragged, but a batch that fits the half-width tile
+// of the general kernel is left to it)
 static bool corr_pipelined_ok(const MatrixView &A, int32_t N, int32_t panel_rows)
 {
-    return A.d % CORRP_BM == 0 && N % CORRP_BN == 0 && A.r % 64 == 0 && panel_rows % CORRP_BM == 0;
+    return A.d % CORRP_BM == 0 && N > 64 && A.r % 64 == 0 && panel_rows % CORRP_BM == 0;
 }
 
 // The tiling in use: 128 x 128 outputs (128 x 64 when there are at most 64 right-hand sides), depth 32

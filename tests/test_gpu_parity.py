@@ -243,11 +243,12 @@ def test_omp_exact_recovery_zero_and_oversized_k():
     assert np.array_equal(sel[3], rsel[3]) and relerr(x[3], rx[3]) < TOL
 
 
-def test_omp_full_tiles_with_zero_and_sparse_right_hand_sides():
+@pytest.mark.parametrize("N", [128, 200])   # 200: a ragged second tile of right-hand sides
+def test_omp_full_tiles_with_zero_and_sparse_right_hand_sides(N):
     """Full tiles of a stored matrix (the pipelined contraction): all-zero right-hand sides and ones
     sparser than k drive the residual to zero / rounding noise, where already selected positions can
     reach the top of a tile and must still never be selected twice."""
-    N, d, r, k = 128, 1024, 256, 8
+    d, r, k = 1024, 256, 8
     A, At = make_matrix("stored", 20, d, r)
     A64 = At.astype(np.float64).T
     rng = np.random.default_rng(12)
@@ -268,7 +269,7 @@ def test_omp_full_tiles_with_zero_and_sparse_right_hand_sides():
         ref = orc.omp(Y[n], At, ks, norm=norm)
         assert np.array_equal(sel[n][:ks], ref["sel"]) and relerr(x[n][:ks], ref["x"]) < TOL
         assert np.abs(x[n][ks:]).max(initial=0.0) < 1e-5 * np.abs(x[n][:ks]).max()
-    for n in (3, 50, 126):   # ordinary noisy right-hand sides in the same launch
+    for n in (3, 50, 126, N - 2, N - 1):   # ordinary noisy right-hand sides in the same launch
         ref = orc.omp(Y[n], At, k, norm=norm)
         assert np.array_equal(sel[n], ref["sel"]) and relerr(x[n], ref["x"]) < TOL
 
