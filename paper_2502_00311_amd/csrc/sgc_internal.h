@@ -95,6 +95,14 @@ __device__ __forceinline__ double wave_sum(double v)
     return v; // valid in lane 0
 }
 
+// 16-byte load of data that is read once: marked non-temporal so that it streams past the caches
+__device__ __forceinline__ float4 load_once_f4(const float *p)
+{
+    typedef float floatx4_t __attribute__((ext_vector_type(4)));
+    const floatx4_t t = __builtin_nontemporal_load(reinterpret_cast<const floatx4_t *>(p));
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+
 __device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int mask)
 {
     uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);

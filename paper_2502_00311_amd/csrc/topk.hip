@@ -244,7 +244,7 @@ __global__ __launch_bounds__(THREADS, MINBLOCKS) void topk_f32_regs_kernel(const
     __shared__ uint32_t tmax_s[THREADS];
     __shared__ float cand_val[TOPK_CAND_CAP];
     __shared__ int32_t cand_pos[TOPK_CAND_CAP];
-    __shared__ uint32_t s_thr, s_need, s_ties, s_ncand;
+    __shared__ uint32_t s_thr, s_need, s_ties, s_ncand, s_nan;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6); // wavefront index, kept scalar
@@ -258,10 +258,10 @@ __global__ __launch_bounds__(THREADS, MINBLOCKS) void topk_f32_regs_kernel(const
     float4 v[ROWS];
     if (vector_loads && wslice + ROWS * 256 <= d) {
         // the whole slice is inside the chunk: plain 16-byte loads off one scalar base
-        const float4 *src = reinterpret_cast<const float4 *>(gc + wslice) + lane;
+        const float *src = gc + wslice + lane * 4;
 #pragma unroll
         for (int j = 0; j < ROWS; ++j)
-            v[j] = src[j * 64];
+            v[j] = load_once_f4(src + j * 256);
     } else {
 #pragma unroll
         for (int j = 0; j < ROWS; ++j) {
@@ -287,9 +287,13 @@ __global__ __launch_bounds__(THREADS, MINBLOCKS) void topk_f32_regs_kernel(const
         tmax = m > tmax ? m : tmax;
     }
     tmax_s[tid] = tmax;
-    if (tid == 0)
+    if (tid == 0) {
         s_ncand = 0;
+        s_nan = 0;
+    }
     __syncthreads();
+    if (tmax > 0x7f800000u)
+        s_nan = 1; // a NaN pattern in the chunk: its order is defined on the bits, not on float compares
     if (w == 0) {
         uint32_t gt, eq;
         const uint32_t bound = wave_kth_largest(tmax_s, THREADS, (uint32_t)k, gt, eq);
@@ -298,17 +302,24 @@ __global__ __launch_bounds__(THREADS, MINBLOCKS) void topk_f32_regs_kernel(const
     }
     __syncthreads();
     const uint32_t bound = s_thr;
+    // The candidate test is a float compare on |x| (one instruction per entry), which orders finite
+    // values and infinities exactly like the keys; chunks with a NaN or with a subnormal / zero bound
+    // take the general path.
+    if (s_nan != 0u || bound < 0x00800000u) {
+        topk_general<float, THREADS>(gc, d, k, oidx, oval);
+        return;
+    }
+    const float boundf = __uint_as_float(bound);
 #pragma unroll
     for (int j = 0; j < ROWS; ++j) {
         const float e4[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
-        const bool h0 = key_of(e4[0]) >= bound, h1 = key_of(e4[1]) >= bound, h2 = key_of(e4[2]) >= bound,
-                   h3 = key_of(e4[3]) >= bound;
-        if (__ballot(h0 || h1 || h2 || h3) == 0ull)
+        const uint64_t hits[4] = {__ballot(fabsf(e4[0]) >= boundf), __ballot(fabsf(e4[1]) >= boundf),
+                                  __ballot(fabsf(e4[2]) >= boundf), __ballot(fabsf(e4[3]) >= boundf)};
+        if ((hits[0] | hits[1] | hits[2] | hits[3]) == 0ull)
             continue;
-        const bool hit[4] = {h0, h1, h2, h3};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const uint64_t bh = __ballot(hit[e]);
+            const uint64_t bh = hits[e];
             if (bh == 0ull)
                 continue;
             uint32_t base = 0;
@@ -316,7 +327,7 @@ __global__ __launch_bounds__(THREADS, MINBLOCKS) void topk_f32_regs_kernel(const
                 base = atomicAdd(&s_ncand, (uint32_t)__popcll(bh));
             base = __builtin_amdgcn_readfirstlane(base);
             const uint32_t mine = base + __builtin_amdgcn_mbcnt_hi((uint32_t)(bh >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bh, 0u));
-            if (hit[e] && mine < TOPK_CAND_CAP) {
+            if (fabsf(e4[e]) >= boundf && mine < TOPK_CAND_CAP) {
                 cand_val[mine] = e4[e];
                 cand_pos[mine] = wbase + j * 256 + e;
             }
@@ -336,8 +347,44 @@ __global__ __launch_bounds__(THREADS, MINBLOCKS) void topk_f32_regs_kernel(const
     }
     __syncthreads();
     if (listed && s_ties == s_need) {
-        // exactly k listed entries have key >= thr: each goes to its rank by position
+        // exactly k listed entries have key >= thr: they are packed to the front of a second list
+        // (wavefront-aggregated append; the order does not matter), then each goes to its rank by
+        // position among those k
         const uint32_t thr = s_thr;
+        if (tid == 0)
+            s_ncand = 0;
+        __syncthreads();
+        int32_t *win_pos = cand_pos + TOPK_CAND_CAP / 2; // nc <= cap/2 is checked below
+        float *win_val = cand_val + TOPK_CAND_CAP / 2;
+        if (nc <= TOPK_CAND_CAP / 2) {
+            for (uint32_t t0 = 0; t0 < nc; t0 += THREADS) {
+                const uint32_t t = t0 + tid;
+                const float cv = t < nc ? cand_val[t] : 0.f;
+                const bool win = t < nc && key_of(cv) >= thr;
+                const uint64_t bh = __ballot(win);
+                if (bh != 0ull) {
+                    uint32_t base = 0;
+                    if (lane == 0)
+                        base = atomicAdd(&s_ncand, (uint32_t)__popcll(bh));
+                    base = __builtin_amdgcn_readfirstlane(base);
+                    const uint32_t mine = base + __builtin_amdgcn_mbcnt_hi((uint32_t)(bh >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bh, 0u));
+                    if (win) {
+                        win_pos[mine] = cand_pos[t];
+                        win_val[mine] = cv;
+                    }
+                }
+            }
+            __syncthreads();
+            for (int32_t t = tid; t < k; t += THREADS) {
+                const int32_t mine = win_pos[t];
+                int32_t rank = 0;
+                for (int32_t u = 0; u < k; ++u)
+                    rank += win_pos[u] < mine ? 1 : 0;
+                oidx[rank] = mine;
+                oval[rank] = win_val[t];
+            }
+            return;
+        }
         for (uint32_t t = tid; t < nc; t += THREADS) {
             const float mine_val = cand_val[t];
             if (key_of(mine_val) < thr)

@@ -111,6 +111,31 @@ def test_topk_ties_zeros_and_quantised_values():
         assert np.array_equal(val.view(np.uint32), rval.view(np.uint32))
 
 
+def test_topk_nan_inf_and_subnormal_patterns():
+    """Order is defined on the bit pattern with the sign cleared: NaN patterns above infinity,
+    subnormals below every normal value. Chunks: NaNs and infinities among normal values; only
+    subnormals and zeros (the k-th largest is subnormal); plain values next to them in one launch."""
+    rng = np.random.default_rng(8)
+    C, d, k = 4, 16384, 64
+    g = rng.standard_normal((C, d)).astype(np.float32)
+    bits = g.view(np.uint32)
+    bits[0, 5] = 0x7fc00000; bits[0, 9000] = 0xffc00123; bits[0, 77] = 0x7f800000; bits[0, 16383] = 0xff800000
+    g[1] = 0.0
+    sub = rng.integers(1, 0x007fffff, size=200).astype(np.uint32)
+    bits[1, rng.permutation(d)[:200]] = sub | (rng.integers(0, 2, size=200).astype(np.uint32) << 31)
+    bits[2, 100:140] = 0x7f800000   # 40 infinities, tie among themselves
+    gd = dev(g)
+    A, At = make_matrix("stored", 3, d, 64)
+    idx = torch.empty((C, k), dtype=torch.int32, device=DEV)
+    val = torch.empty((C, k), dtype=torch.float32, device=DEV)
+    p = torch.empty((C, 64), dtype=torch.float32, device=DEV)
+    sgc.sgc_sparsify_project(gd, C * d, d, k, A, idx, val, p, None)
+    torch.cuda.synchronize()
+    ridx, rval = orc.topk(g, k)
+    assert np.array_equal(idx.cpu().numpy(), ridx)
+    assert np.array_equal(val.cpu().numpy().view(np.uint32), rval.view(np.uint32))
+
+
 @pytest.mark.parametrize("C,d,k", [(3, 3000, 100), (2, 16384, 64), (2, 262144, 1024)])
 def test_topk_bf16(C, d, k):
     say("topk bf16", C, d, k)
