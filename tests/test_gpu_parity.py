@@ -214,6 +214,7 @@ def run_omp(Y, A, k):
     (2, 4096, 256, 32, "stored"),    # cfg1 shape
     (130, 700, 64, 8, "philox"),     # two right-hand-side tiles, ragged
     (3, 2000, 100, 10, "stored"),    # depth not a multiple of the staging depth
+    (2, 2048, 512, 320, "stored"),   # k > 256: sixteen rows of F per lane in the update kernel
 ])
 def test_omp_matches_oracle_on_noisy_right_hand_sides(N, d, r, k, mode):
     say("omp", N, d, r, k, mode)
@@ -297,6 +298,30 @@ def test_omp_full_tiles_with_zero_and_sparse_right_hand_sides(N):
     for n in (3, 50, 126, N - 2, N - 1):   # ordinary noisy right-hand sides in the same launch
         ref = orc.omp(Y[n], At, k, norm=norm)
         assert np.array_equal(sel[n], ref["sel"]) and relerr(x[n], ref["x"]) < TOL
+
+
+def test_omp_largest_k_sampled_picks_and_values():
+    """k = 1024, the largest the entry point accepts. A full oracle run costs k^4; instead sampled
+    picks are checked one by one (oracle least squares on the GPU's prefix, then the argmax of the
+    normalised correlation over the unselected positions) and the values on the full support."""
+    N, d, r, k = 2, 1600, 1536, 1024
+    say("omp k=1024")
+    A, At = make_matrix("philox", 27, d, r)
+    rng = np.random.default_rng(3)
+    Y = rng.standard_normal((N, r)).astype(np.float32)
+    sel, x = run_omp(Y, A, k)
+    assert all(len(set(row.tolist())) == k for row in sel)
+    norm = orc.colnorms(At)
+    A64 = At.astype(np.float64)
+    for n in range(N):
+        for j in (0, 1, 63, 64, 255, 256, 700, 1023):
+            res = Y[n].astype(np.float64)
+            if j:
+                res = res - A64[sel[n, :j]].T @ orc.lstsq_support(Y[n], At, sel[n, :j])
+            score = np.abs(A64 @ res) / norm
+            score[sel[n, :j]] = -1.0
+            assert int(np.argmax(score)) == sel[n, j], (n, j)
+        assert relerr(x[n], orc.lstsq_support(Y[n], At, sel[n])) < TOL
 
 
 def test_omp_is_deterministic():
