@@ -192,6 +192,20 @@ def omp_shared(Ym, Yv, At, k, norm=None):
     return sel, x, z
 
 
+def reproject(sel, x, At_new, scale=1.0):
+    """out = scale * A' x for sparse vectors given as (positions, values) (App. C, Alg. 4 l.10-11)."""
+    sel = _c(sel, np.int32)
+    x = _c(x, np.float32)
+    At_new = _c(At_new, np.float32)
+    N, k = sel.shape
+    d, r = At_new.shape
+    out = np.empty((N, r), np.float32)
+    rc = lib().oracle_reproject(_p(sel, ctypes.c_int32), _p(x, ctypes.c_float), ctypes.c_int64(N), k, _p(At_new, ctypes.c_float), d, r, ctypes.c_double(scale), _p(out, ctypes.c_float))
+    if rc:
+        raise ValueError("oracle_reproject rc=%d" % rc)
+    return out
+
+
 def apply(W, d, sel_m, x_m, sel_v, x_v, alpha=1.0, eps=1e-8, lr=1e-3):
     """W <- W - lr * alpha * x / (sqrt(z) + eps) on the recovered supports (eq. 11, eq. 3)."""
     W = np.array(W, np.float32, copy=True, order="C")
@@ -207,9 +221,12 @@ def apply(W, d, sel_m, x_m, sel_v, x_v, alpha=1.0, eps=1e-8, lr=1e-3):
     return W
 
 
-def step(g, W, m, v, t, At, k, beta1=0.9, beta2=0.999, eps=1e-8, lr=1e-3, alpha=1.0, shared_support=False):
+def step(g, W, m, v, t, At, k, beta1=0.9, beta2=0.999, eps=1e-8, lr=1e-3, alpha=1.0, shared_support=False,
+         At_new=None):
     """One full SGC step (Alg. 2 + the weight update) on C chunks. g: [C, d].
-    shared_support: recover the support from mhat only and fit vhat on it."""
+    shared_support: recover the support from mhat only and fit vhat on it.
+    At_new: SGCA (App. C): after the update the returned state m, v is re-aligned with the new matrix,
+    m = (1 - beta1^t) A' OMP_A(mhat), v = (1 - beta2^t) A' OMP_A(vhat); the caller continues with At_new."""
     C, d = g.shape
     idx, val = topk(g, k)
     p, q = project(idx, val, At)
@@ -217,8 +234,14 @@ def step(g, W, m, v, t, At, k, beta1=0.9, beta2=0.999, eps=1e-8, lr=1e-3, alpha=
     if shared_support:
         sel_s, x_s, z_s = omp_shared(mh.reshape(C, -1), vh.reshape(C, -1), At, k)
         W2 = apply(W, d, sel_s, x_s, sel_s, z_s, alpha, eps, lr)
+        if At_new is not None:
+            m2 = reproject(sel_s, x_s, At_new, 1.0 - beta1 ** t)
+            v2 = reproject(sel_s, z_s, At_new, 1.0 - beta2 ** t)
         return dict(idx=idx, val=val, p=p, q=q, m=m2, v=v2, mhat=mh, vhat=vh, sel_m=sel_s, x_m=x_s, sel_v=sel_s, x_v=z_s, W=W2)
     Y = np.concatenate([mh.reshape(C, -1), vh.reshape(C, -1)], axis=0)
     sel, x = omp_batch(Y, At, k)
     W2 = apply(W, d, sel[:C], x[:C], sel[C:], x[C:], alpha, eps, lr)
+    if At_new is not None:
+        m2 = reproject(sel[:C], x[:C], At_new, 1.0 - beta1 ** t)
+        v2 = reproject(sel[C:], x[C:], At_new, 1.0 - beta2 ** t)
     return dict(idx=idx, val=val, p=p, q=q, m=m2, v=v2, mhat=mh, vhat=vh, sel_m=sel[:C], x_m=x[:C], sel_v=sel[C:], x_v=x[C:], W=W2)

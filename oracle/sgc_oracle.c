@@ -20,8 +20,9 @@
  * vectors and an exact Box-Muller evaluation for the generated matrix; the
  * closed form of the first Adam step; exact sparse recovery, exhaustive
  * support search and least-squares identities for OMP; a library least-squares
- * routine and exact joint recovery for the shared-support fit; the closed form
- * of the first full step in the exact-recovery regime.
+ * routine and exact joint recovery for the shared-support fit; a dense mat-vec
+ * and the eq. 10 invariant across a change of matrix for the re-projection; the
+ * closed form of the first full step in the exact-recovery regime.
  */
 #include <math.h>
 #include <stdint.h>
@@ -554,6 +555,35 @@ int oracle_omp_shared(const float *y_m, const float *y_v, const float *At, int32
         z[t] = (float)z64[t];
     free(z64);
     return rc;
+}
+
+/* ------------------------------------------------------------------------ */
+/* SGCA re-projection (App. C, Alg. 4 lines 9-12): every T steps a new matrix */
+/* A' is drawn and the compressed moments are re-aligned with it,             */
+/*     M <- A' OMP_A(M),   V <- A' OMP_A(V).                                  */
+/* Given a recovered sparse vector (positions sel, values x) this is          */
+/*     out = scale * A' x .                                                   */
+/* OMP commutes with a positive scale of its input, so when x was recovered   */
+/* from the bias-corrected moment (what the step already computes) and the    */
+/* stored state is the uncorrected one, scale = 1 - beta^t gives the          */
+/* re-aligned state; with x recovered from the state itself, scale = 1.       */
+/* ------------------------------------------------------------------------ */
+int oracle_reproject(const int32_t *sel, const float *x, int64_t N, int32_t k, const float *At_new,
+                     int32_t d, int32_t r, double scale, float *out)
+{
+    for (int64_t n = 0; n < N; ++n) {
+        for (int32_t j = 0; j < r; ++j) {
+            double s = 0.0;
+            for (int32_t t = 0; t < k; ++t) {
+                int32_t i = sel[n * k + t];
+                if (i < 0 || i >= d)
+                    return -1;
+                s += (double)At_new[(int64_t)i * r + j] * (double)x[n * k + t];
+            }
+            out[n * r + j] = (float)(scale * s);
+        }
+    }
+    return 0;
 }
 
 /* ------------------------------------------------------------------------ */

@@ -416,3 +416,51 @@ def test_shared_support_fit_in_the_noisy_regime_is_the_projection_onto_the_suppo
         res = yv[c].astype(np.float64) - As @ orc.lstsq_support(yv[c], At, sel[c])
         assert np.abs(As.T @ res).max() < 1e-10 * np.linalg.norm(yv[c])
         assert np.abs(zs[c] - xs[c]).max() > 1e-3
+
+
+# --------------------------------------------------------------------------- SGCA re-projection
+def test_reprojection_equals_dense_matvec_and_scales():
+    rng = np.random.default_rng(11)
+    d, r, k, N = 700, 48, 9, 3
+    At2 = synth.gaussian_matrix(9, d, r)
+    sel = np.stack([rng.permutation(d)[:k] for _ in range(N)]).astype(np.int32)   # selection order, not sorted
+    x = rng.standard_normal((N, k)).astype(np.float32)
+    out = orc.reproject(sel, x, At2, scale=0.271)
+    for n in range(N):
+        dense = np.zeros(d)
+        dense[sel[n]] = x[n]
+        ref = 0.271 * (At2.astype(np.float64).T @ dense)
+        assert np.abs(out[n] - ref).max() < 1e-6 * np.abs(ref).max()
+
+
+@pytest.mark.parametrize("shared", [False, True])
+def test_sgca_keeps_the_moments_aligned_with_the_new_matrix(shared):
+    """App. C: after M <- A' OMP_A(M) the state is the projection, with the NEW matrix, of the same
+    dense moment (eq. 10 with A' in place of A), and stays so over the following steps. Gradients
+    with one fixed k-sparse support keep every recovery exact."""
+    d, r, k, C = 1024, 256, 8, 2
+    A1 = synth.gaussian_matrix(31, d, r)
+    A2 = synth.gaussian_matrix(32, d, r)
+    rng = np.random.default_rng(2)
+    support = np.sort(rng.permutation(d)[:k])
+    m = np.zeros((C, r), np.float32)
+    v = np.zeros((C, r), np.float32)
+    W = np.zeros(C * d, np.float32)
+    Md = np.zeros((C, d))
+    Vd = np.zeros((C, d))
+    b1, b2 = 0.9, 0.999
+    At = A1
+    for t in range(1, 5):
+        g = np.zeros((C, d), np.float32)
+        g[:, support] = rng.standard_normal((C, k)).astype(np.float32) + 3.0 * np.sign(rng.standard_normal((C, k))).astype(np.float32)
+        out = orc.step(g, W, m, v, t, At, k, shared_support=shared, At_new=A2 if t == 2 else None)
+        Md = b1 * Md + (1 - b1) * g.astype(np.float64)
+        Vd = b2 * Vd + (1 - b2) * g.astype(np.float64) ** 2
+        if t == 2:
+            At = A2
+        A64 = At.astype(np.float64).T
+        for c in range(C):
+            assert sorted(out["sel_m"][c].tolist()) == support.tolist()
+            assert np.abs(out["m"][c] - A64 @ Md[c]).max() < 2e-5 * np.abs(A64 @ Md[c]).max(), t
+            assert np.abs(out["v"][c] - A64 @ Vd[c]).max() < 2e-5 * np.abs(A64 @ Vd[c]).max(), t
+        m, v, W = out["m"], out["v"], out["W"]
