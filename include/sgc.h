@@ -174,6 +174,21 @@ sgc_status sgc_recover_omp_shared(const float *y_m, const float *y_v, int32_t C,
                                   float *z, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * SGCA re-alignment of compressed moments with a new measurement matrix (App. C, Alg. 4 lines
+ * 9-12: every T steps A' is drawn and M <- A' OMP_A(M), V <- A' OMP_A(V), A <- A'):
+ *   out[n] = scale * A' x_n   for N sparse vectors given as (sel[n], x[n]), k entries each,
+ * as returned by sgc_recover_omp / sgc_recover_omp_shared; positions must be in [0, d).
+ * OMP commutes with a positive scaling of its input, so the vectors the step has already recovered
+ * from the bias-corrected moments serve: scale = 1 - beta1^step gives the re-aligned (uncorrected)
+ * first-moment state from OMP(mhat), scale = 1 - beta2^step the second from OMP(vhat); vectors
+ * recovered from the state itself take scale = 1. `out` ([N][r], 16-byte aligned) may be the state
+ * array itself. Sums are accumulated in float in list order, then scaled.
+ * Errors: NULL, SHAPE (N < 0, k <= 0, k > d, k > 4096, r % 4), DTYPE, ALIGN.
+ */
+sgc_status sgc_reproject(const int32_t *sel, const float *x, int64_t N, int32_t k,
+                         const sgc_matrix *A_new /* host */, double scale, float *out, void *stream);
+
+/*
  * eq. 11 and eq. 3 on the recovered supports of C chunks:
  *   for each position i in sel_m[c]: z = value of i in (sel_v[c], x_v[c]) or 0 if absent,
  *   W[c*d+i] -= lr * alpha * x_i / (sqrt(max(z,0)) + eps)

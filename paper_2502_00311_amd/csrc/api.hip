@@ -180,6 +180,21 @@ sgc_status sgc_recover_omp_shared(const float *y_m, const float *y_v, int32_t C,
     return from_hip(launch_omp(y_m, C, make_view(A), k, sel, x, w, (hipStream_t)stream, y_v, z));
 }
 
+sgc_status sgc_reproject(const int32_t *sel, const float *x, int64_t N, int32_t k, const sgc_matrix *A_new,
+                         double scale, float *out, void *stream)
+{
+    if (!sel || !x || !out)
+        return SGC_ERR_NULL;
+    sgc_status st = check_matrix(A_new, false);
+    if (st != SGC_OK)
+        return st;
+    if (N < 0 || k <= 0 || k > A_new->d || k > 4096)
+        return SGC_ERR_SHAPE;
+    if (!aligned16(out))
+        return SGC_ERR_ALIGN;
+    return from_hip(launch_project(sel, x, N, k, make_view(A_new), out, nullptr, (hipStream_t)stream, (float)scale));
+}
+
 sgc_status sgc_apply(float *W, int64_t C, int32_t d, int32_t k, const int32_t *sel_m, const float *x_m,
                      const int32_t *sel_v, const float *x_v, const sgc_hyper *h, void *stream)
 {

@@ -15,7 +15,7 @@ template <bool GENERATED>
 __global__ __launch_bounds__(PROJ_THREADS) void project_kernel(const int32_t *__restrict__ idx,
                                                                const float *__restrict__ val, int32_t k,
                                                                MatrixView A, float *__restrict__ p,
-                                                               float *__restrict__ q)
+                                                               float *__restrict__ q, float out_scale)
 {
     __shared__ int32_t s_idx[PROJ_STAGE];
     __shared__ float s_val[PROJ_STAGE];
@@ -54,14 +54,16 @@ __global__ __launch_bounds__(PROJ_THREADS) void project_kernel(const int32_t *__
         }
     }
     if (active) {
-        reinterpret_cast<float4 *>(p + c * A.r)[jb] = ap;
+        // out_scale is 1 for the projection (an exact multiplication); the re-projection scales its sum
+        reinterpret_cast<float4 *>(p + c * A.r)[jb] =
+            make_float4(ap.x * out_scale, ap.y * out_scale, ap.z * out_scale, ap.w * out_scale);
         if (q)
             reinterpret_cast<float4 *>(q + c * A.r)[jb] = aq;
     }
 }
 
 hipError_t launch_project(const int32_t *idx, const float *val, int64_t C, int32_t k, const MatrixView &A,
-                          float *p, float *q, hipStream_t s)
+                          float *p, float *q, hipStream_t s, float out_scale)
 {
     if (C == 0)
         return hipSuccess;
@@ -74,9 +76,11 @@ hipError_t launch_project(const int32_t *idx, const float *val, int64_t C, int32
         float *qq = q ? q + c0 * A.r : nullptr;
         ProfileScope prof(KC_PROJECT, s);
         if (A.generated)
-            project_kernel<true><<<grid, PROJ_THREADS, 0, s>>>(idx + c0 * k, val + c0 * k, k, A, p + c0 * A.r, qq);
+            project_kernel<true><<<grid, PROJ_THREADS, 0, s>>>(idx + c0 * k, val + c0 * k, k, A, p + c0 * A.r, qq,
+                                                               out_scale);
         else
-            project_kernel<false><<<grid, PROJ_THREADS, 0, s>>>(idx + c0 * k, val + c0 * k, k, A, p + c0 * A.r, qq);
+            project_kernel<false><<<grid, PROJ_THREADS, 0, s>>>(idx + c0 * k, val + c0 * k, k, A, p + c0 * A.r, qq,
+                                                                out_scale);
     }
     return hipGetLastError();
 }

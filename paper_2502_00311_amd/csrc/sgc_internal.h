@@ -54,7 +54,7 @@ enum KernelClass { KC_TOPK = 0, KC_PROJECT, KC_ADAM, KC_CORR, KC_SELECT, KC_APPL
 hipError_t launch_topk(const void *grad, int grad_type, int64_t C, int32_t d, int32_t k, int32_t *idx,
                        float *val, hipStream_t s);
 hipError_t launch_project(const int32_t *idx, const float *val, int64_t C, int32_t k, const MatrixView &A,
-                          float *p, float *q, hipStream_t s);
+                          float *p, float *q, hipStream_t s, float out_scale = 1.0f);
 hipError_t launch_adam(const float *p, const float *q, float *m, float *v, float *mhat, float *vhat,
                        int64_t count, float b1, float omb1, float b2, float omb2, float ibc1, float ibc2,
                        hipStream_t s);

@@ -19,7 +19,8 @@ MATRIX_STORED, MATRIX_PHILOX = 0, 1
 
 EXPORTS = [
     "sgc_status_string", "sgc_matrix_fill", "sgc_matrix_colnorms", "sgc_sparsify_project",
-    "sgc_adam_compressed", "sgc_omp_workspace_bytes", "sgc_recover_omp", "sgc_recover_omp_shared", "sgc_apply",
+    "sgc_adam_compressed", "sgc_omp_workspace_bytes", "sgc_recover_omp", "sgc_recover_omp_shared", "sgc_reproject",
+    "sgc_apply",
     "sgc_profile_enable", "sgc_profile_read",
 ]
 PROFILE_CLASSES = ["topk", "project", "adam", "omp_corr", "omp_select_update", "apply", "other", "omp_matrix_fill"]
@@ -74,6 +75,8 @@ def lib():
         L.sgc_recover_omp.argtypes = [vp, i32, ctypes.POINTER(sgc_matrix), i32, vp, vp, vp, sz, vp]
         L.sgc_recover_omp_shared.restype = i32
         L.sgc_recover_omp_shared.argtypes = [vp, vp, i32, ctypes.POINTER(sgc_matrix), i32, vp, vp, vp, vp, sz, vp]
+        L.sgc_reproject.restype = i32
+        L.sgc_reproject.argtypes = [vp, vp, i64, i32, ctypes.POINTER(sgc_matrix), ctypes.c_double, vp, vp]
         L.sgc_apply.restype = i32
         L.sgc_apply.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, ctypes.POINTER(sgc_hyper), vp]
         L.sgc_profile_enable.restype = i32
@@ -151,6 +154,10 @@ def sgc_recover_omp_shared(y_m, y_v, C, A, k, sel, x, z, ws, stream=None):
     _check(lib().sgc_recover_omp_shared(_ptr(y_m), _ptr(y_v), C, ctypes.byref(A.c()), k, _ptr(sel), _ptr(x), _ptr(z), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_recover_omp_shared")
 
 
+def sgc_reproject(sel, x, N, k, A_new, scale, out, stream=None):
+    _check(lib().sgc_reproject(_ptr(sel), _ptr(x), N, k, ctypes.byref(A_new.c()), scale, _ptr(out), _stream(stream)), "sgc_reproject")
+
+
 def sgc_apply(W, C, d, k, sel_m, x_m, sel_v, x_v, h, stream=None):
     _check(lib().sgc_apply(_ptr(W), C, d, k, _ptr(sel_m), _ptr(x_m), _ptr(sel_v), _ptr(x_v), ctypes.byref(h), _stream(stream)), "sgc_apply")
 
@@ -187,16 +194,24 @@ class StepBuffers:
         self.ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
 
 
-def step(grad, W, buf, A, t, h, stream=None, shared_support=False):
+def step(grad, W, buf, A, t, h, stream=None, shared_support=False, A_new=None):
     """The four calls of one step, in order (Alg. 2 then the weight update). shared_support: one
     support per chunk from mhat with vhat fitted on it; then buf.sel[:C], buf.x[:C] hold the support
-    and x, buf.x[C:] holds z, and buf.sel[C:] is not written."""
+    and x, buf.x[C:] holds z, and buf.sel[C:] is not written. A_new: SGCA (App. C): after the update
+    the state buf.m, buf.v is re-aligned with A_new from the vectors just recovered; the caller passes
+    A_new as A from the next step on."""
     C, d, r, k = buf.C, buf.d, buf.r, buf.k
     sgc_sparsify_project(grad, C * d, d, k, A, buf.idx, buf.val, buf.p, buf.q, stream)
     sgc_adam_compressed(buf.p, buf.q, buf.m, buf.v, buf.hat[:C], buf.hat[C:], C * r, t, h, stream)
     if shared_support:
         sgc_recover_omp_shared(buf.hat[:C], buf.hat[C:], C, A, k, buf.sel[:C], buf.x[:C], buf.x[C:], buf.ws, stream)
         sgc_apply(W, C, d, k, buf.sel[:C], buf.x[:C], buf.sel[:C], buf.x[C:], h, stream)
+        if A_new is not None:
+            sgc_reproject(buf.sel[:C], buf.x[:C], C, k, A_new, 1.0 - h.beta1 ** t, buf.m, stream)
+            sgc_reproject(buf.sel[:C], buf.x[C:], C, k, A_new, 1.0 - h.beta2 ** t, buf.v, stream)
         return
     sgc_recover_omp(buf.hat, 2 * C, A, k, buf.sel, buf.x, buf.ws, stream)
     sgc_apply(W, C, d, k, buf.sel[:C], buf.x[:C], buf.sel[C:], buf.x[C:], h, stream)
+    if A_new is not None:
+        sgc_reproject(buf.sel[:C], buf.x[:C], C, k, A_new, 1.0 - h.beta1 ** t, buf.m, stream)
+        sgc_reproject(buf.sel[C:], buf.x[C:], C, k, A_new, 1.0 - h.beta2 ** t, buf.v, stream)
