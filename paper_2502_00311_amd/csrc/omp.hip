@@ -35,7 +35,8 @@ OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_
     w.tiles_m = corr_tiles_m(d);
     w.words = (d + 31) / 32;
     w.res64 = (double *)take(sizeof(double) * (size_t)N * r);
-    w.F = (double *)take(sizeof(double) * (size_t)N * k * k);
+    w.f_stride = (int64_t)k * k + 288;
+    w.F = (double *)take(sizeof(double) * (size_t)N * w.f_stride);
     w.avec = (double *)take(sizeof(double) * (size_t)N * k);
     w.xs = (double *)take(sizeof(double) * (size_t)N * k);
     w.res32 = (float *)take(sizeof(float) * (size_t)N * r);
@@ -624,6 +625,7 @@ struct IterArgs {
     // where a matrix shared by many right-hand sides stays in cache, and ws.cols is not used.
     // NULL: the selected columns are kept per right-hand side in ws.cols.
     const float *At_rows;
+    int32_t share_table; // factor_kernel: its dynamic LDS also holds the [wavefront][k] table of shares
 };
 
 template <bool GENERATED>
@@ -823,12 +825,13 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(MatrixView A, IterAr
     }
 }
 
-// grid N; 256 threads (k <= 128) or 1024. dynamic LDS: double w[k]; double fsum[k]
+// grid N; 256 threads (k <= 128) or 1024. dynamic LDS: double w[k]; double fsum[k]; the table of
+// shares [wavefronts][k] if it fits; double a[k]
 // One pass over F: a wavefront takes column t of F (entries 0..t, contiguous), forms
 // c_t = <F_:t, w> (coordinate t of the new column in the orthonormal basis Q = A_Lambda F) and at once
 // adds c_t F_:t to its share of F c; the shares are then summed in wavefront order.
-// ROWS = rows of F per lane (k <= 64 * ROWS); TWO = two columns in flight per wavefront
-template <int FACTOR_ROWS, bool TWO>
+// ROWS = rows of F per lane (k <= 64 * ROWS); FLIGHT = columns in flight per wavefront
+template <int FACTOR_ROWS, int FLIGHT>
 __global__ __launch_bounds__(FACTOR_MAX_THREADS) void factor_kernel(IterArgs P)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -841,12 +844,17 @@ __global__ __launch_bounds__(FACTOR_MAX_THREADS) void factor_kernel(IterArgs P)
     const int nthreads = blockDim.x, nwaves = blockDim.x >> 6;
     const int64_t n = blockIdx.x;
     const OmpWorkspace &W = P.ws;
-    double *F = W.F + (n * k) * (int64_t)k;
+    double *F = W.F + n * W.f_stride;
     double *avec = W.avec + n * k;
     double *xs = W.xs + n * k;
 
+    // everything the update needs from memory besides F is fetched up front (one latency, not four)
+    double *a_s = fsum + k + (P.share_table ? (int64_t)nwaves * k : 0); // coefficients a_0 .. a_{it-1}
+    const double gb_g = W.gb[n * 2], gb_b = W.gb[n * 2 + 1];
+    const double x_mine = tid < it ? xs[tid] : 0.0; // row tid of the solution (rows >= nthreads: read late)
     for (int32_t t = tid; t < it; t += nthreads) {
         w_s[t] = W.wv[n * k + t];
+        a_s[t] = avec[t];
         fsum[t] = 0.0;
     }
     __syncthreads();
@@ -856,52 +864,73 @@ __global__ __launch_bounds__(FACTOR_MAX_THREADS) void factor_kernel(IterArgs P)
     for (int q = 0; q < FACTOR_ROWS; ++q)
         facc[q] = 0.0;
     double cc = 0.0, ca = 0.0; // c.c and c.avec over this wavefront's columns
-    for (int32_t t = wave; t < it; t += (TWO ? 2 : 1) * nwaves) {
-        const int32_t t2 = t + nwaves;
-        const bool two = TWO && t2 < it;
-        const double *f0 = F + (int64_t)t * k;
-        const double *f1 = F + (int64_t)(two ? t2 : t) * k;
-        double v0[FACTOR_ROWS], v1[FACTOR_ROWS];
-        double d0 = 0.0, d1 = 0.0;
+    for (int32_t t0 = wave; t0 < it; t0 += FLIGHT * nwaves) {
+        // FLIGHT columns t0, t0 + nwaves, ... in flight: all loads are issued before any is used
+        double v[FLIGHT][FACTOR_ROWS], dt[FLIGHT];
 #pragma unroll
-        for (int q = 0; q < FACTOR_ROWS; ++q) {
-            v0[q] = 0.0;
-            v1[q] = 0.0;
-            if (q < nq) {
+        for (int c = 0; c < FLIGHT; ++c) {
+            const int32_t t = t0 + c * nwaves;
+            const double *f = F + (int64_t)(t < it ? t : t0) * k;
+#pragma unroll
+            for (int q = 0; q < FACTOR_ROWS; ++q) {
                 const int32_t u = q * 64 + lane;
-                if (u <= t)
-                    v0[q] = f0[u];
-                if (two && u <= t2)
-                    v1[q] = f1[u];
-                const double wu = u < it ? w_s[u] : 0.0;
-                d0 += v0[q] * wu;
-                d1 += v1[q] * wu;
+                v[c][q] = (q < nq && t < it && u <= t) ? f[u] : 0.0;
             }
         }
-        d0 = __shfl(wave_sum(d0), 0, 64);
-        d1 = __shfl(wave_sum(d1), 0, 64);
 #pragma unroll
-        for (int q = 0; q < FACTOR_ROWS; ++q)
-            if (q < nq)
-                facc[q] += v0[q] * d0 + v1[q] * d1;
-        cc += d0 * d0 + d1 * d1;
-        ca += d0 * avec[t] + (two ? d1 * avec[t2] : 0.0);
+        for (int c = 0; c < FLIGHT; ++c) {
+            double acc = 0.0;
+#pragma unroll
+            for (int q = 0; q < FACTOR_ROWS; ++q) {
+                const int32_t u = q * 64 + lane;
+                acc += v[c][q] * ((q < nq && u < it) ? w_s[u] : 0.0);
+            }
+            dt[c] = __shfl(wave_sum(acc), 0, 64);
+        }
+#pragma unroll
+        for (int c = 0; c < FLIGHT; ++c) {
+            const int32_t t = t0 + c * nwaves;
+#pragma unroll
+            for (int q = 0; q < FACTOR_ROWS; ++q)
+                facc[q] += v[c][q] * dt[c];
+            cc += dt[c] * dt[c];
+            ca += t < it ? dt[c] * a_s[t] : 0.0;
+        }
     }
     if (lane == 0) {
         s_red[0][wave] = cc;
         s_red[1][wave] = ca;
     }
-    // F c = sum of the wavefronts' shares, added in wavefront order (deterministic)
-    for (int wv = 0; wv < nwaves; ++wv) {
-        if (wave == wv) {
+    // F c = sum of the wavefronts' shares, added in wavefront order (deterministic): through a
+    // [wavefront][k] table when it fits (one barrier), else one wavefront after the other
+    if (P.share_table) {
+        double *share = fsum + k;
 #pragma unroll
-            for (int q = 0; q < FACTOR_ROWS; ++q) {
-                const int32_t u = q * 64 + lane;
-                if (q < nq && u < it)
-                    fsum[u] += facc[q];
-            }
+        for (int q = 0; q < FACTOR_ROWS; ++q) {
+            const int32_t u = q * 64 + lane;
+            if (q < nq && u < it)
+                share[wave * k + u] = facc[q];
         }
         __syncthreads();
+        for (int32_t u = tid; u < it; u += nthreads) {
+            double a = 0.0;
+            for (int wv = 0; wv < nwaves; ++wv)
+                a += share[wv * k + u];
+            fsum[u] = a;
+        }
+        __syncthreads();
+    } else {
+        for (int wv = 0; wv < nwaves; ++wv) {
+            if (wave == wv) {
+#pragma unroll
+                for (int q = 0; q < FACTOR_ROWS; ++q) {
+                    const int32_t u = q * 64 + lane;
+                    if (q < nq && u < it)
+                        fsum[u] += facc[q];
+                }
+            }
+            __syncthreads();
+        }
     }
     // gamma = 1/sqrt(g - c.c); new coefficient a_it = gamma (b - c.avec)
     if (tid == 0) {
@@ -910,7 +939,7 @@ __global__ __launch_bounds__(FACTOR_MAX_THREADS) void factor_kernel(IterArgs P)
             tcc += s_red[0][u];
             tca += s_red[1][u];
         }
-        const double g = W.gb[n * 2], b = W.gb[n * 2 + 1];
+        const double g = gb_g, b = gb_b;
         const double rem = g - tcc;
         const double gamma = rem > 0.0 ? 1.0 / sqrt(rem) : 0.0;
         const double coef = gamma * (b - tca);
@@ -928,7 +957,7 @@ __global__ __launch_bounds__(FACTOR_MAX_THREADS) void factor_kernel(IterArgs P)
     for (int32_t u = tid; u < it; u += nthreads) {
         const double f = -gamma * fsum[u];
         F[(int64_t)it * k + u] = f;
-        const double xn = xs[u] + coef * f;
+        const double xn = (u == tid ? x_mine : xs[u]) + coef * f;
         xs[u] = xn;
         if (it == k - 1)
             P.x[n * k + u] = (float)xn;
@@ -1021,7 +1050,7 @@ __global__ __launch_bounds__(REFIT_THREADS) void refit_kernel(IterArgs P, const 
     }
     __syncthreads();
     // u = F^T b: column t of F (rows 0..t, contiguous) against b
-    const double *F = W.F + (n * k) * (int64_t)k;
+    const double *F = W.F + n * W.f_stride;
     for (int32_t t = wave; t < k; t += NW) {
         const double *f = F + (int64_t)t * k;
         double acc = 0.0;
@@ -1049,6 +1078,7 @@ struct OmpPlan {
     int32_t tiles_m; // position tiles of the contraction in use (stride of ws.partial)
     MatrixView Apick; // the view pick_kernel fetches columns from
     size_t pick_smem, factor_smem;
+    bool factor_share_table; // factor_kernel sums its wavefronts' shares through an LDS table
 };
 
 // the workspace as seen by the right-hand sides [n0, ...): every per-right-hand-side array shifted
@@ -1057,7 +1087,7 @@ static OmpWorkspace shift_workspace(const OmpWorkspace &ws, int32_t n0, int32_t 
     OmpWorkspace w = ws;
     w.tiles_m = tiles_m;
     w.res64 += (int64_t)n0 * r;
-    w.F += (int64_t)n0 * k * k;
+    w.F += (int64_t)n0 * ws.f_stride;
     w.avec += (int64_t)n0 * k;
     w.xs += (int64_t)n0 * k;
     w.res32 += (int64_t)n0 * r;
@@ -1109,17 +1139,17 @@ static void omp_select_update(const OmpPlan &pl, const MatrixView &A, const floa
     slices = slices < 1 ? 1 : (slices > 8 ? 8 : slices);
     const dim3 pgrid((unsigned)Ng, (unsigned)slices);
     const dim3 rgrid((unsigned)Ng, (unsigned)(((A.r >> 2) + RES_THREADS - 1) / RES_THREADS));
-    IterArgs P{y, k, it, sel, x, w, pl.Apick.generated ? nullptr : pl.Apick.At};
+    IterArgs P{y, k, it, sel, x, w, pl.Apick.generated ? nullptr : pl.Apick.At, pl.factor_share_table ? 1 : 0};
     if (pl.Apick.generated)
         pick_kernel<true><<<pgrid, PICK_THREADS, pl.pick_smem, s>>>(pl.Apick, P);
     else
         pick_kernel<false><<<pgrid, PICK_THREADS, pl.pick_smem, s>>>(pl.Apick, P);
     if (k <= 128)
-        factor_kernel<2, true><<<dim3((unsigned)Ng), 256, pl.factor_smem, s>>>(P);
+        factor_kernel<2, 4><<<dim3((unsigned)Ng), 256, pl.factor_smem, s>>>(P);
     else if (k <= 256)
-        factor_kernel<4, true><<<dim3((unsigned)Ng), FACTOR_MAX_THREADS, pl.factor_smem, s>>>(P);
+        factor_kernel<4, 6><<<dim3((unsigned)Ng), FACTOR_MAX_THREADS, pl.factor_smem, s>>>(P);
     else
-        factor_kernel<16, false><<<dim3((unsigned)Ng), FACTOR_MAX_THREADS, pl.factor_smem, s>>>(P);
+        factor_kernel<16, 1><<<dim3((unsigned)Ng), FACTOR_MAX_THREADS, pl.factor_smem, s>>>(P);
     residual_kernel<<<rgrid, RES_THREADS, 16 * (size_t)(it + 1), s>>>(P, A.r);
 }
 
@@ -1168,7 +1198,13 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
     pl.pipelined = (!A.generated || pl.panels) && corr_pipelined_ok(A, N, ws.panel_rows);
     pl.tiles_m = pl.pipelined ? A.d / CORRP_BM : corr_tiles_m(A.d);
     pl.pick_smem = ((size_t)A.r * 4 + 15) & ~(size_t)15;
-    pl.factor_smem = 2 * sizeof(double) * (size_t)k;
+    pl.factor_smem = 3 * sizeof(double) * (size_t)k;
+    {
+        const size_t table = sizeof(double) * (size_t)k * (k <= 128 ? 4 : 16); // one row per wavefront
+        pl.factor_share_table = pl.factor_smem + table <= 48 * 1024;
+        if (pl.factor_share_table)
+            pl.factor_smem += table;
+    }
     pl.Apick = A;
     const bool whole_matrix_panel = pl.panels && ws.panel_rows >= A.d;
     if (whole_matrix_panel) {
@@ -1184,7 +1220,7 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
     {
         ProfileScope prof(KC_SELECT, s);
         const OmpWorkspace w = shift_workspace(ws, 0, A.r, k, pl.tiles_m);
-        IterArgs P{y, k, k, sel, x, w, pl.Apick.generated ? nullptr : pl.Apick.At};
+        IterArgs P{y, k, k, sel, x, w, pl.Apick.generated ? nullptr : pl.Apick.At, 0};
         refit_kernel<<<dim3((unsigned)N), REFIT_THREADS, 2 * sizeof(double) * (size_t)k, s>>>(P, y_fit, z, A.r);
     }
     return hipGetLastError();

@@ -30,7 +30,9 @@ inline int corr_tiles_m(int d) { return (d + CORR_BM - 1) / CORR_BM; }
 // Workspace layout of sgc_recover_omp (all offsets 256-byte aligned).
 struct OmpWorkspace {
     double *res64;     // [N][r] residual
-    double *F;         // [N][k][k] inverse Cholesky factor, column t at F[(n*k+t)*k .. +t]
+    double *F;         // [N][f_stride] inverse Cholesky factor, column t of n at F[n*f_stride + t*k .. +t]
+    int64_t f_stride;  // k*k plus a pad, so that equal columns of different right-hand sides (read at the
+                       // same time by all workgroups) do not sit a power of two apart in memory
     double *avec;      // [N][k] coefficients in the orthonormal basis
     double *xs;        // [N][k] current least-squares solution
     float *res32;      // [N][r] residual rounded to float (operand of the contraction)
