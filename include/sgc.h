@@ -19,6 +19,10 @@
  *     synchronised. Calls on one stream execute in order.
  *   - Arguments are validated on the host before anything is launched. On error nothing is
  *     launched and a negative sgc_status is returned; the library never aborts or throws.
+ *   - Work goes to the device that is current when a call is made; all pointers of a call must
+ *     live there. The library keeps a little per-device host state (a second stream for large
+ *     recoveries, the timing collection), so calls from several host threads must be serialised
+ *     by the caller.
  *   - Chunk-local positions (`idx`, `sel`) are int32 in [0, d).
  *   - A is r x d with iid N(0, 1/r) entries (Sec. 4.3). It is handled transposed: "At" is
  *     d x r row-major, row i of At = column i of A (r contiguous floats).

@@ -129,3 +129,32 @@ def test_apply_and_matrix_helpers_reject_bad_arguments():
     A = mat()
     assert L.sgc_matrix_colnorms(ctypes.byref(A), None, None) == sgc.ERR_NULL
     assert L.sgc_matrix_colnorms(None, FAKE, None) == sgc.ERR_NULL
+
+
+def test_shared_recovery_and_reprojection_reject_bad_arguments():
+    L = sgc.lib()
+    A = mat(d=4096, r=256)
+    need = sgc.sgc_omp_workspace_bytes(2, 4096, 256, 32)
+
+    def shared(ym=FAKE, yv=FAKE, C=2, AA=A, k=32, sel=FAKE, x=FAKE, z=FAKE, ws=FAKE, nbytes=need):
+        return L.sgc_recover_omp_shared(ym, yv, C, ctypes.byref(AA) if AA is not None else None, k, sel, x, z, ws, nbytes, None)
+
+    assert shared(yv=None) == sgc.ERR_NULL
+    assert shared(z=None) == sgc.ERR_NULL
+    assert shared(AA=mat(d=4096, r=256, inv=None)) == sgc.ERR_NULL
+    assert shared(C=0) == sgc.ERR_SHAPE
+    assert shared(k=1025) == sgc.ERR_SHAPE
+    assert shared(yv=ODD) == sgc.ERR_ALIGN
+    assert shared(nbytes=need - 1) == sgc.ERR_WORKSPACE
+
+    def reproject(sel=FAKE, x=FAKE, N=2, k=8, AA=A, scale=0.5, out=FAKE):
+        return L.sgc_reproject(sel, x, N, k, ctypes.byref(AA) if AA is not None else None, scale, out, None)
+
+    assert reproject(sel=None) == sgc.ERR_NULL
+    assert reproject(out=None) == sgc.ERR_NULL
+    assert reproject(AA=None) == sgc.ERR_NULL
+    assert reproject(N=-1) == sgc.ERR_SHAPE
+    assert reproject(k=0) == sgc.ERR_SHAPE
+    assert reproject(k=4097) == sgc.ERR_SHAPE
+    assert reproject(out=ODD) == sgc.ERR_ALIGN
+    assert reproject(AA=mat(mode=9)) == sgc.ERR_DTYPE
