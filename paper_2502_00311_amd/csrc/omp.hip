@@ -2,13 +2,15 @@
 // update and output of App. B) for N right-hand sides that share the measurement matrix A.
 //
 // Per iteration:
-//   corr_kernel    P = At * R for all right-hand sides at once: a dense float contraction on the
-//                  matrix cores (32x32x2 MFMA, LDS-staged 128x128 tiles). P is never written: the
-//                  epilogue scales by 1/||A_:i||, masks selected positions and keeps the two best
-//                  (score, position) pairs of every 128-row tile per right-hand side.
+//   contraction    P = At * R for all right-hand sides at once: a dense float contraction on the
+//                  matrix cores (32x32x2 MFMA, LDS-staged tiles; corr_pipelined_kernel for full
+//                  position tiles of resident rows, corr_kernel for everything else). P is never
+//                  written: the epilogue scales by 1/||A_:i||, leaves out selected positions and keeps
+//                  the two best (score, position) pairs of every position tile per right-hand side.
 //   pick / factor / residual   re-score the near-maximal candidates in double (so the argmax does
 //                  not depend on float rounding), append the winning column, extend F = L^-H
 //                  (App. B) by mat-vecs only, and recompute the residual y - A_Lambda x in double.
+// After the last iteration refit_kernel can fit a second right-hand side on the support found.
 // App. B precomputes the Gram matrix A^H A (d x d) to avoid the contraction; here the contraction
 // is kept (it is what the matrix cores are for) and only inner products with selected columns are
 // formed, so memory stays O(N k r).
@@ -603,10 +605,10 @@ static hipError_t corr_dispatch(const MatrixView &A, int32_t rows, const float *
 // Selection and least-squares update, three kernels per iteration:
 //   pick_kernel      re-scores the near-maximal candidates in double and fixes lambda; then
 //                    w_t = <A_:lambda_t, A_:lambda> for the earlier selections (a row-major mat-vec over
-//                    the stored columns, one wavefront per row, spread over several workgroups)
+//                    the selected columns, one wavefront per row, spread over several workgroups)
 //   factor_kernel    the small dense part of App. B: c = F^H w, gamma, the new coefficient, the new
 //                    column of F and x = F a, all in double
-//   residual_kernel  res = y - A_Lambda x in double (a column-major mat-vec over the stored columns,
+//   residual_kernel  res = y - A_Lambda x in double (a column-major mat-vec over the selected columns,
 //                    one thread per four measurements), plus the float copy for the next contraction
 constexpr int PICK_THREADS = 512;
 constexpr int PICK_WAVES = PICK_THREADS / 64;
