@@ -602,19 +602,18 @@ static hipError_t corr_dispatch(const MatrixView &A, int32_t rows, const float *
 }
 
 // ----------------------------------------------------------------------------------------------
-// Selection and least-squares update, three kernels per iteration:
+// Selection and least-squares update, two kernels per iteration:
 //   pick_kernel      re-scores the near-maximal candidates in double and fixes lambda; then
 //                    w_t = <A_:lambda_t, A_:lambda> for the earlier selections (a row-major mat-vec over
 //                    the selected columns, one wavefront per row, spread over several workgroups)
-//   factor_kernel    the small dense part of App. B: c = F^H w, gamma, the new coefficient, the new
-//                    column of F and x = F a, all in double
-//   residual_kernel  res = y - A_Lambda x in double (a column-major mat-vec over the selected columns,
-//                    one thread per four measurements), plus the float copy for the next contraction
+//   update_kernel    the small dense part of App. B: c = F^H w, gamma, the new coefficient, the new
+//                    column of F and x = F a, all in double; then res = y - A_Lambda x in double (a
+//                    column-major mat-vec over the selected columns), plus the float copy for the
+//                    next contraction
 constexpr int PICK_THREADS = 512;
 constexpr int PICK_WAVES = PICK_THREADS / 64;
 constexpr int PICK_CAND_CAP = 64;
 constexpr int FACTOR_MAX_THREADS = 1024;
-constexpr int RES_THREADS = 64;
 
 struct IterArgs {
     const float *y; // [N][r]
@@ -627,7 +626,7 @@ struct IterArgs {
     // where a matrix shared by many right-hand sides stays in cache, and ws.cols is not used.
     // NULL: the selected columns are kept per right-hand side in ws.cols.
     const float *At_rows;
-    int32_t share_table; // factor_kernel: its dynamic LDS also holds the [wavefront][k] table of shares
+    int32_t share_table; // update_kernel: its dynamic LDS also holds the [wavefront][k] table of shares
 };
 
 template <bool GENERATED>
@@ -827,14 +826,18 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(MatrixView A, IterAr
     }
 }
 
-// grid N; 256 threads (k <= 128) or 1024. dynamic LDS: double w[k]; double fsum[k]; the table of
-// shares [wavefronts][k] if it fits; double a[k]
-// One pass over F: a wavefront takes column t of F (entries 0..t, contiguous), forms
-// c_t = <F_:t, w> (coordinate t of the new column in the orthonormal basis Q = A_Lambda F) and at once
-// adds c_t F_:t to its share of F c; the shares are then summed in wavefront order.
+// grid N; 256 threads (k <= 128) or 1024. dynamic LDS: double w[k]; double fsum[k]; double a[k];
+// scratch (the table of shares [wavefronts][k] if it fits, later the partial residuals)
+// First the small dense part of App. B in one pass over F: a wavefront takes column t of F (entries
+// 0..t, contiguous), forms c_t = <F_:t, w> (coordinate t of the new column in the orthonormal basis
+// Q = A_Lambda F) and at once adds c_t F_:t to its share of F c; the shares are then summed in
+// wavefront order. Then, in the same workgroup (the dependency is per right-hand side only),
+// res = y - A_Lambda x as a column mat-vec in double: a thread owns four measurements; when there are
+// fewer such quads than threads, several threads share one and take every G-th column, and their
+// parts are added in a fixed order.
 // ROWS = rows of F per lane (k <= 64 * ROWS); FLIGHT = columns in flight per wavefront
 template <int FACTOR_ROWS, int FLIGHT>
-__global__ __launch_bounds__(FACTOR_MAX_THREADS) void factor_kernel(IterArgs P)
+__global__ __launch_bounds__(FACTOR_MAX_THREADS) void update_kernel(IterArgs P, int32_t r)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int32_t k = P.k, it = P.it;
@@ -851,7 +854,8 @@ __global__ __launch_bounds__(FACTOR_MAX_THREADS) void factor_kernel(IterArgs P)
     double *xs = W.xs + n * k;
 
     // everything the update needs from memory besides F is fetched up front (one latency, not four)
-    double *a_s = fsum + k + (P.share_table ? (int64_t)nwaves * k : 0); // coefficients a_0 .. a_{it-1}
+    double *a_s = fsum + k;    // coefficients a_0 .. a_{it-1}
+    double *scratch = a_s + k; // shares of F c, later partial residuals
     const double gb_g = W.gb[n * 2], gb_b = W.gb[n * 2 + 1];
     const double x_mine = tid < it ? xs[tid] : 0.0; // row tid of the solution (rows >= nthreads: read late)
     for (int32_t t = tid; t < it; t += nthreads) {
@@ -906,7 +910,7 @@ __global__ __launch_bounds__(FACTOR_MAX_THREADS) void factor_kernel(IterArgs P)
     // F c = sum of the wavefronts' shares, added in wavefront order (deterministic): through a
     // [wavefront][k] table when it fits (one barrier), else one wavefront after the other
     if (P.share_table) {
-        double *share = fsum + k;
+        double *share = scratch;
 #pragma unroll
         for (int q = 0; q < FACTOR_ROWS; ++q) {
             const int32_t u = q * 64 + lane;
@@ -950,72 +954,103 @@ __global__ __launch_bounds__(FACTOR_MAX_THREADS) void factor_kernel(IterArgs P)
         avec[it] = coef;
         F[(int64_t)it * k + it] = gamma;
         xs[it] = coef * gamma;
-        if (it == k - 1)
-            P.x[n * k + it] = (float)(coef * gamma);
     }
     __syncthreads();
     const double gamma = s_gamma, coef = s_coef;
     // new column of F: -gamma F c on rows < it, and x <- [x; 0] + coef * F_:it
-    for (int32_t u = tid; u < it; u += nthreads) {
-        const double f = -gamma * fsum[u];
-        F[(int64_t)it * k + u] = f;
-        const double xn = (u == tid ? x_mine : xs[u]) + coef * f;
-        xs[u] = xn;
+    // (w and fsum are dead from here: they become x and the float4 offsets of the selected columns)
+    double *x_s = w_s;
+    int64_t *row_s = reinterpret_cast<int64_t *>(fsum);
+    const int32_t r4 = r >> 2;
+    for (int32_t u = tid; u <= it; u += nthreads) {
+        double xn;
+        if (u < it) {
+            const double f = -gamma * fsum[u];
+            F[(int64_t)it * k + u] = f;
+            xn = (u == tid ? x_mine : xs[u]) + coef * f;
+            xs[u] = xn;
+        } else {
+            xn = coef * gamma;
+        }
         if (it == k - 1)
             P.x[n * k + u] = (float)xn;
-    }
-}
-
-// grid (N, r/256): one thread per four measurements. dynamic LDS: double x[it+1]; int64 row[it+1]
-__global__ __launch_bounds__(RES_THREADS) void residual_kernel(IterArgs P, int32_t r)
-{
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    double *x_s = reinterpret_cast<double *>(smem);
-    int64_t *row_s = reinterpret_cast<int64_t *>(x_s + (P.it + 1)); // offset of column t in float4 units
-    const int32_t k = P.k, it = P.it, r4 = r >> 2;
-    const int64_t n = blockIdx.x;
-    const OmpWorkspace &W = P.ws;
-    for (int32_t t = threadIdx.x; t <= it; t += RES_THREADS) {
-        x_s[t] = W.xs[n * k + t];
-        row_s[t] = (P.At_rows ? (int64_t)P.sel[n * k + t] : (int64_t)t) * r4;
+        x_s[u] = xn;
+        row_s[u] = (P.At_rows ? (int64_t)P.sel[n * k + u] : (int64_t)u) * r4;
     }
     __syncthreads();
-    const int32_t jb = blockIdx.y * RES_THREADS + threadIdx.x;
-    if (jb >= r4)
-        return;
-    const float4 yv = reinterpret_cast<const float4 *>(P.y + n * r)[jb];
-    double e0 = yv.x, e1 = yv.y, e2 = yv.z, e3 = yv.w;
-    const float4 *cj = (P.At_rows ? reinterpret_cast<const float4 *>(P.At_rows)
-                                  : reinterpret_cast<const float4 *>(W.cols + (n * k) * (int64_t)r)) + jb;
-    int32_t t = 0;
-    for (; t + 8 <= it + 1; t += 8) {
-        float4 u[8];
+
+    // ---- residual ----
+    const float4 *cbase = P.At_rows ? reinterpret_cast<const float4 *>(P.At_rows)
+                                    : reinterpret_cast<const float4 *>(W.cols + (n * k) * (int64_t)r);
+    const int32_t G = r4 < nthreads ? nthreads / r4 : 1; // threads sharing one quad of measurements
+    double *parts = scratch;                              // [G-1][r4][4]
+    for (int32_t jb0 = 0; jb0 < r4; jb0 += nthreads) {
+        const int32_t jb = G > 1 ? tid % r4 : jb0 + tid;
+        const int32_t g = G > 1 ? tid / r4 : 0;
+        const bool active = jb < r4 && g < G;
+        double e0 = 0.0, e1 = 0.0, e2 = 0.0, e3 = 0.0;
+        if (active) {
+            if (g == 0) {
+                const float4 yv = reinterpret_cast<const float4 *>(P.y + n * r)[jb];
+                e0 = yv.x;
+                e1 = yv.y;
+                e2 = yv.z;
+                e3 = yv.w;
+            }
+            const float4 *cj = cbase + jb;
+            int32_t t = g;
+            for (; t + 7 * G <= it; t += 8 * G) {
+                float4 u[8];
 #pragma unroll
-        for (int q = 0; q < 8; ++q)
-            u[q] = cj[row_s[t + q]];
+                for (int q = 0; q < 8; ++q)
+                    u[q] = cj[row_s[t + q * G]];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const double xt = x_s[t + q];
-            e0 -= xt * u[q].x;
-            e1 -= xt * u[q].y;
-            e2 -= xt * u[q].z;
-            e3 -= xt * u[q].w;
+                for (int q = 0; q < 8; ++q) {
+                    const double xt = x_s[t + q * G];
+                    e0 -= xt * u[q].x;
+                    e1 -= xt * u[q].y;
+                    e2 -= xt * u[q].z;
+                    e3 -= xt * u[q].w;
+                }
+            }
+            for (; t <= it; t += G) {
+                const float4 u = cj[row_s[t]];
+                const double xt = x_s[t];
+                e0 -= xt * u.x;
+                e1 -= xt * u.y;
+                e2 -= xt * u.z;
+                e3 -= xt * u.w;
+            }
+        }
+        if (G > 1) {
+            if (active && g > 0) {
+                double *o = parts + ((int64_t)(g - 1) * r4 + jb) * 4;
+                o[0] = e0;
+                o[1] = e1;
+                o[2] = e2;
+                o[3] = e3;
+            }
+            __syncthreads();
+            if (active && g == 0) {
+                for (int32_t gg = 1; gg < G; ++gg) {
+                    const double *o = parts + ((int64_t)(gg - 1) * r4 + jb) * 4;
+                    e0 += o[0];
+                    e1 += o[1];
+                    e2 += o[2];
+                    e3 += o[3];
+                }
+            }
+        }
+        if (active && g == 0) {
+            double *ro = W.res64 + n * r + 4 * jb;
+            ro[0] = e0;
+            ro[1] = e1;
+            ro[2] = e2;
+            ro[3] = e3;
+            reinterpret_cast<float4 *>(W.res32 + n * r)[jb] =
+                make_float4((float)e0, (float)e1, (float)e2, (float)e3);
         }
     }
-    for (; t <= it; ++t) {
-        const float4 u = cj[row_s[t]];
-        const double xt = x_s[t];
-        e0 -= xt * u.x;
-        e1 -= xt * u.y;
-        e2 -= xt * u.z;
-        e3 -= xt * u.w;
-    }
-    double *ro = W.res64 + n * r + 4 * jb;
-    ro[0] = e0;
-    ro[1] = e1;
-    ro[2] = e2;
-    ro[3] = e3;
-    reinterpret_cast<float4 *>(W.res32 + n * r)[jb] = make_float4((float)e0, (float)e1, (float)e2, (float)e3);
 }
 
 // Least-squares fit of a second right-hand side on the support already found (shared-support
@@ -1080,7 +1115,7 @@ struct OmpPlan {
     int32_t tiles_m; // position tiles of the contraction in use (stride of ws.partial)
     MatrixView Apick; // the view pick_kernel fetches columns from
     size_t pick_smem, factor_smem;
-    bool factor_share_table; // factor_kernel sums its wavefronts' shares through an LDS table
+    bool factor_share_table; // update_kernel sums its wavefronts' shares through an LDS table
 };
 
 // the workspace as seen by the right-hand sides [n0, ...): every per-right-hand-side array shifted
@@ -1140,19 +1175,17 @@ static void omp_select_update(const OmpPlan &pl, const MatrixView &A, const floa
     int slices = 2048 / Ng;
     slices = slices < 1 ? 1 : (slices > 8 ? 8 : slices);
     const dim3 pgrid((unsigned)Ng, (unsigned)slices);
-    const dim3 rgrid((unsigned)Ng, (unsigned)(((A.r >> 2) + RES_THREADS - 1) / RES_THREADS));
     IterArgs P{y, k, it, sel, x, w, pl.Apick.generated ? nullptr : pl.Apick.At, pl.factor_share_table ? 1 : 0};
     if (pl.Apick.generated)
         pick_kernel<true><<<pgrid, PICK_THREADS, pl.pick_smem, s>>>(pl.Apick, P);
     else
         pick_kernel<false><<<pgrid, PICK_THREADS, pl.pick_smem, s>>>(pl.Apick, P);
     if (k <= 128)
-        factor_kernel<2, 4><<<dim3((unsigned)Ng), 256, pl.factor_smem, s>>>(P);
+        update_kernel<2, 4><<<dim3((unsigned)Ng), 256, pl.factor_smem, s>>>(P, A.r);
     else if (k <= 256)
-        factor_kernel<4, 6><<<dim3((unsigned)Ng), FACTOR_MAX_THREADS, pl.factor_smem, s>>>(P);
+        update_kernel<4, 6><<<dim3((unsigned)Ng), FACTOR_MAX_THREADS, pl.factor_smem, s>>>(P, A.r);
     else
-        factor_kernel<16, 1><<<dim3((unsigned)Ng), FACTOR_MAX_THREADS, pl.factor_smem, s>>>(P);
-    residual_kernel<<<rgrid, RES_THREADS, 16 * (size_t)(it + 1), s>>>(P, A.r);
+        update_kernel<16, 1><<<dim3((unsigned)Ng), FACTOR_MAX_THREADS, pl.factor_smem, s>>>(P, A.r);
 }
 
 // A second stream (default priority) and two events per device, created on first use, so that the
@@ -1202,10 +1235,12 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
     pl.pick_smem = ((size_t)A.r * 4 + 15) & ~(size_t)15;
     pl.factor_smem = 3 * sizeof(double) * (size_t)k;
     {
-        const size_t table = sizeof(double) * (size_t)k * (k <= 128 ? 4 : 16); // one row per wavefront
+        const size_t threads = k <= 128 ? 256 : FACTOR_MAX_THREADS;
+        const size_t table = sizeof(double) * (size_t)k * (threads / 64); // one row per wavefront
+        const size_t parts = (size_t)(A.r >> 2) < threads ? threads * 4 * sizeof(double) : 0; // partial residuals
         pl.factor_share_table = pl.factor_smem + table <= 48 * 1024;
-        if (pl.factor_share_table)
-            pl.factor_smem += table;
+        const size_t scratch = pl.factor_share_table && table > parts ? table : parts;
+        pl.factor_smem += scratch;
     }
     pl.Apick = A;
     const bool whole_matrix_panel = pl.panels && ws.panel_rows >= A.d;
