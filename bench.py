@@ -39,6 +39,9 @@ def main():
     ap.add_argument("--materialize", action="store_true",
                     help="a generated matrix is written out once with sgc_matrix_fill (outside the timed region) "
                          "and handed over as a stored one: what a caller with HBM to spare would do")
+    ap.add_argument("--gram", action="store_true",
+                    help="build the optional table of column inner products (sgc_matrix_gram, 8 d^2 bytes, once, "
+                         "outside the timed region) and let the recovery use it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (reference for the rocprofv3 FETCH_SIZE / "
@@ -77,6 +80,14 @@ def main():
         A = sgc.Matrix(d, r, At=None, seed=w.a_seed)
     A.inv_colnorm = torch.empty(d, dtype=torch.float32, device=dev)
     sgc.sgc_matrix_colnorms(A, A.inv_colnorm)
+    gram_ms = None
+    if args.gram:
+        A.gram = torch.empty((d, d), dtype=torch.float64, device=dev)
+        torch.cuda.synchronize()
+        tg = time.perf_counter()
+        sgc.sgc_matrix_gram(A, A.gram)
+        torch.cuda.synchronize()
+        gram_ms = (time.perf_counter() - tg) * 1e3
     nsteps = max(K, Wm, 1)
     grads = []
     for t in range(1, nsteps + 1):
@@ -150,9 +161,11 @@ def main():
         "config": {"workload": w.name, "chunks": C, "d": d, "r": r, "k": k, "grad": w.grad,
                    "matrix": "philox, materialised by the caller" if (args.materialize and w.matrix != "stored") else w.matrix,
                    "rhs_per_omp_call": nrhs,
-                   "recovery": "shared_support" if args.shared_support else "two_supports"},
+                   "recovery": "shared_support" if args.shared_support else "two_supports",
+                   "gram_table": bool(args.gram)},
         "roofline": roofline,
         "ms_per_step_with_events": round((t3 - t2) * 1e3 / K, 3),
+        "gram_build_ms": None if gram_ms is None else round(gram_ms, 2),
         "kernels": kernels,
     }
 

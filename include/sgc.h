@@ -79,6 +79,8 @@ typedef struct sgc_matrix {
     uint64_t seed;            /* PHILOX mode */
     const float *At;          /* device [d][r], STORED mode; 16-byte aligned */
     const float *inv_colnorm; /* device [d]; may be NULL for sgc_sparsify_project */
+    const double *gram;       /* device [d][d] or NULL: optional table for sgc_recover_omp* (see
+                                 sgc_matrix_gram) */
 } sgc_matrix;
 
 /* AdamW-style hyper-parameters of Alg. 2 / eq. 11 (host values; no weight-decay term appears
@@ -109,6 +111,18 @@ sgc_status sgc_matrix_fill(uint64_t seed, int32_t r, int64_t row0, int64_t rows,
  */
 sgc_status sgc_matrix_colnorms(const sgc_matrix *A /* host */, float *inv_colnorm_out,
                                void *stream);
+
+/*
+ * gram_out[i][j] = <A_:i, A_:j> for all pairs of columns (device, [d][d] doubles = 8 d^2 bytes,
+ * row-major, 16-byte aligned), accumulated in double from the float entries on the double matrix
+ * cores. This is the Gram matrix A^H A that App. B precomputes. It is optional: with A->gram set,
+ * sgc_recover_omp* take the inner products between the new column and the earlier selections from
+ * this table instead of a pass over the selected columns (same values up to double rounding). A
+ * per-matrix table like inv_colnorm: build it once for as long as A is in use, where 8 d^2 bytes
+ * are affordable (2 GiB at d = 16384, 32 GiB at d = 65536). A->gram and A->inv_colnorm are not read.
+ * Errors: NULL, SHAPE (d > 65536), DTYPE, ALIGN.
+ */
+sgc_status sgc_matrix_gram(const sgc_matrix *A /* host */, double *gram_out, void *stream);
 
 /*
  * Alg. 2 line 1 for n/d chunks: per chunk keep the k entries of largest magnitude

@@ -11,6 +11,7 @@ MatrixView make_view(const sgc_matrix *A)
     MatrixView v{};
     v.At = A->At;
     v.inv_colnorm = A->inv_colnorm;
+    v.gram = A->gram;
     v.d = A->d;
     v.r = A->r;
     v.key0 = (uint32_t)(A->seed & 0xffffffffull);
@@ -86,6 +87,20 @@ sgc_status sgc_matrix_colnorms(const sgc_matrix *A, float *inv_colnorm_out, void
     if (!inv_colnorm_out)
         return SGC_ERR_NULL;
     return from_hip(launch_colnorms(make_view(A), inv_colnorm_out, (hipStream_t)stream));
+}
+
+sgc_status sgc_matrix_gram(const sgc_matrix *A, double *gram_out, void *stream)
+{
+    sgc_status st = check_matrix(A, false);
+    if (st != SGC_OK)
+        return st;
+    if (!gram_out)
+        return SGC_ERR_NULL;
+    if (A->d > 65536) // gridDim.y of the tile grid; a larger table would not fit in memory anyway
+        return SGC_ERR_SHAPE;
+    if (!aligned16(gram_out))
+        return SGC_ERR_ALIGN;
+    return from_hip(launch_gram(make_view(A), gram_out, (hipStream_t)stream));
 }
 
 sgc_status sgc_sparsify_project(const void *grad, int32_t grad_type, int64_t n, int32_t d, int32_t k,

@@ -40,7 +40,8 @@ OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_
     w.f_stride = (int64_t)k * k + 288;
     w.F = (double *)take(sizeof(double) * (size_t)N * w.f_stride);
     w.avec = (double *)take(sizeof(double) * (size_t)N * k);
-    w.xs = (double *)take(sizeof(double) * (size_t)N * k);
+    w.xs = (double *)take(sizeof(double) * (size_t)N * k * 2);
+    w.xs_half = (int64_t)N * k;
     w.res32 = (float *)take(sizeof(float) * (size_t)N * r);
     w.cols = (float *)take(sizeof(float) * (size_t)N * k * r);
     w.partial = (uint64_t *)take(sizeof(uint64_t) * (size_t)N * w.tiles_m * 2);
@@ -796,9 +797,18 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(MatrixView A, IterAr
         W.bitmap[n * W.words + (lam >> 5)] |= 1u << (lam & 31);
     }
 
-    // (4) w_t = <A_:lambda_t, a>, one wavefront per earlier selection, two rows in flight
+    // (4) w_t = <A_:lambda_t, a>: from the table of column inner products if there is one, ...
     double *wv = W.wv + n * k;
     const int32_t *selp = P.sel + n * k;
+    if (A.gram) {
+        if (slice == 0) {
+            const double *grow = A.gram + (int64_t)lam * A.d;
+            for (int32_t t = tid; t < it; t += PICK_THREADS)
+                wv[t] = grow[selp[t]];
+        }
+        return;
+    }
+    // ... else one wavefront per earlier selection, two rows in flight
     const int32_t gw = slice * PICK_WAVES + wave, GW = nslices * PICK_WAVES;
     for (int32_t t = gw; t < it; t += 2 * GW) {
         const int32_t t2 = t + GW;
@@ -826,7 +836,7 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(MatrixView A, IterAr
     }
 }
 
-// grid N; 256 threads (k <= 128) or 1024. dynamic LDS: double w[k]; double fsum[k]; double a[k];
+// grid (N, slices); 256 threads (k <= 128) or 1024. dynamic LDS: double w[k]; double fsum[k]; double a[k];
 // scratch (the table of shares [wavefronts][k] if it fits, later the partial residuals)
 // First the small dense part of App. B in one pass over F: a wavefront takes column t of F (entries
 // 0..t, contiguous), forms c_t = <F_:t, w> (coordinate t of the new column in the orthonormal basis
@@ -851,7 +861,13 @@ __global__ __launch_bounds__(FACTOR_MAX_THREADS) void update_kernel(IterArgs P, 
     const OmpWorkspace &W = P.ws;
     double *F = W.F + n * W.f_stride;
     double *avec = W.avec + n * k;
-    double *xs = W.xs + n * k;
+    // several workgroups (slices) may serve one right-hand side: each repeats the factor pass and takes
+    // its share of the residual; slice 0 stores the factor and the solution. The solution is
+    // double-buffered so that a late slice still reads the previous iteration's values.
+    const int slice = blockIdx.y, nslices = gridDim.y;
+    const bool writer = slice == 0;
+    const double *xs = W.xs + (int64_t)((it + 1) & 1) * W.xs_half + n * k;
+    double *xs_new = W.xs + (int64_t)(it & 1) * W.xs_half + n * k;
 
     // everything the update needs from memory besides F is fetched up front (one latency, not four)
     double *a_s = fsum + k;    // coefficients a_0 .. a_{it-1}
@@ -951,9 +967,10 @@ __global__ __launch_bounds__(FACTOR_MAX_THREADS) void update_kernel(IterArgs P, 
         const double coef = gamma * (b - tca);
         s_gamma = gamma;
         s_coef = coef;
-        avec[it] = coef;
-        F[(int64_t)it * k + it] = gamma;
-        xs[it] = coef * gamma;
+        if (writer) {
+            avec[it] = coef;
+            F[(int64_t)it * k + it] = gamma;
+        }
     }
     __syncthreads();
     const double gamma = s_gamma, coef = s_coef;
@@ -966,14 +983,17 @@ __global__ __launch_bounds__(FACTOR_MAX_THREADS) void update_kernel(IterArgs P, 
         double xn;
         if (u < it) {
             const double f = -gamma * fsum[u];
-            F[(int64_t)it * k + u] = f;
+            if (writer)
+                F[(int64_t)it * k + u] = f;
             xn = (u == tid ? x_mine : xs[u]) + coef * f;
-            xs[u] = xn;
         } else {
             xn = coef * gamma;
         }
-        if (it == k - 1)
-            P.x[n * k + u] = (float)xn;
+        if (writer) {
+            xs_new[u] = xn;
+            if (it == k - 1)
+                P.x[n * k + u] = (float)xn;
+        }
         x_s[u] = xn;
         row_s[u] = (P.At_rows ? (int64_t)P.sel[n * k + u] : (int64_t)u) * r4;
     }
@@ -982,12 +1002,17 @@ __global__ __launch_bounds__(FACTOR_MAX_THREADS) void update_kernel(IterArgs P, 
     // ---- residual ----
     const float4 *cbase = P.At_rows ? reinterpret_cast<const float4 *>(P.At_rows)
                                     : reinterpret_cast<const float4 *>(W.cols + (n * k) * (int64_t)r);
-    const int32_t G = r4 < nthreads ? nthreads / r4 : 1; // threads sharing one quad of measurements
-    double *parts = scratch;                              // [G-1][r4][4]
-    for (int32_t jb0 = 0; jb0 < r4; jb0 += nthreads) {
-        const int32_t jb = G > 1 ? tid % r4 : jb0 + tid;
-        const int32_t g = G > 1 ? tid / r4 : 0;
-        const bool active = jb < r4 && g < G;
+    // this slice's quads of measurements: [q0, q0 + nq4)
+    const int32_t per = (r4 + nslices - 1) / nslices;
+    const int32_t q0 = slice * per;
+    const int32_t nq4 = q0 >= r4 ? 0 : (r4 - q0 < per ? r4 - q0 : per);
+    const int32_t G = (nq4 > 0 && nq4 < nthreads) ? nthreads / nq4 : 1; // threads sharing one quad
+    double *parts = scratch;                                              // [G-1][nq4][4]
+    for (int32_t jb0 = 0; jb0 < nq4; jb0 += nthreads) {
+        const int32_t jl = G > 1 ? tid % nq4 : jb0 + tid; // quad within the slice
+        const int32_t jb = q0 + jl;
+        const int32_t g = G > 1 ? tid / nq4 : 0;
+        const bool active = jl < nq4 && g < G;
         double e0 = 0.0, e1 = 0.0, e2 = 0.0, e3 = 0.0;
         if (active) {
             if (g == 0) {
@@ -1024,7 +1049,7 @@ __global__ __launch_bounds__(FACTOR_MAX_THREADS) void update_kernel(IterArgs P, 
         }
         if (G > 1) {
             if (active && g > 0) {
-                double *o = parts + ((int64_t)(g - 1) * r4 + jb) * 4;
+                double *o = parts + ((int64_t)(g - 1) * nq4 + jl) * 4;
                 o[0] = e0;
                 o[1] = e1;
                 o[2] = e2;
@@ -1033,7 +1058,7 @@ __global__ __launch_bounds__(FACTOR_MAX_THREADS) void update_kernel(IterArgs P, 
             __syncthreads();
             if (active && g == 0) {
                 for (int32_t gg = 1; gg < G; ++gg) {
-                    const double *o = parts + ((int64_t)(gg - 1) * r4 + jb) * 4;
+                    const double *o = parts + ((int64_t)(gg - 1) * nq4 + jl) * 4;
                     e0 += o[0];
                     e1 += o[1];
                     e2 += o[2];
@@ -1174,18 +1199,25 @@ static void omp_select_update(const OmpPlan &pl, const MatrixView &A, const floa
     ProfileScope prof(KC_SELECT, s);
     int slices = 2048 / Ng;
     slices = slices < 1 ? 1 : (slices > 8 ? 8 : slices);
+    if (pl.Apick.gram)
+        slices = 1; // no pass over the selected columns to spread
     const dim3 pgrid((unsigned)Ng, (unsigned)slices);
     IterArgs P{y, k, it, sel, x, w, pl.Apick.generated ? nullptr : pl.Apick.At, pl.factor_share_table ? 1 : 0};
     if (pl.Apick.generated)
         pick_kernel<true><<<pgrid, PICK_THREADS, pl.pick_smem, s>>>(pl.Apick, P);
     else
         pick_kernel<false><<<pgrid, PICK_THREADS, pl.pick_smem, s>>>(pl.Apick, P);
+    // One workgroup per right-hand side. (The kernel can spread a right-hand side over several slices,
+    // each repeating the factor pass and taking a share of the residual; measured at 128 right-hand
+    // sides that is slower, 42 us against 31 us per launch, because the repeated passes over F cost
+    // more than the wider residual pass saves.)
+    const dim3 ugrid((unsigned)Ng, 1u);
     if (k <= 128)
-        update_kernel<2, 4><<<dim3((unsigned)Ng), 256, pl.factor_smem, s>>>(P, A.r);
+        update_kernel<2, 4><<<ugrid, 256, pl.factor_smem, s>>>(P, A.r);
     else if (k <= 256)
-        update_kernel<4, 6><<<dim3((unsigned)Ng), FACTOR_MAX_THREADS, pl.factor_smem, s>>>(P, A.r);
+        update_kernel<4, 6><<<ugrid, FACTOR_MAX_THREADS, pl.factor_smem, s>>>(P, A.r);
     else
-        update_kernel<16, 1><<<dim3((unsigned)Ng), FACTOR_MAX_THREADS, pl.factor_smem, s>>>(P, A.r);
+        update_kernel<16, 1><<<ugrid, FACTOR_MAX_THREADS, pl.factor_smem, s>>>(P, A.r);
 }
 
 // A second stream (default priority) and two events per device, created on first use, so that the
@@ -1237,7 +1269,7 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
     {
         const size_t threads = k <= 128 ? 256 : FACTOR_MAX_THREADS;
         const size_t table = sizeof(double) * (size_t)k * (threads / 64); // one row per wavefront
-        const size_t parts = (size_t)(A.r >> 2) < threads ? threads * 4 * sizeof(double) : 0; // partial residuals
+        const size_t parts = threads * 4 * sizeof(double); // partial residuals of threads sharing a quad
         pl.factor_share_table = pl.factor_smem + table <= 48 * 1024;
         const size_t scratch = pl.factor_share_table && table > parts ? table : parts;
         pl.factor_smem += scratch;

@@ -12,6 +12,7 @@ namespace sgc {
 struct MatrixView {
     const float *At;          // [d][r] or nullptr in generated mode
     const float *inv_colnorm; // [d] or nullptr
+    const double *gram;       // [d][d] inner products of the columns of A, or nullptr
     int32_t d, r;
     uint32_t key0, key1; // Philox key
     float scale;         // (float)(1/sqrt((double)r))
@@ -21,7 +22,7 @@ struct MatrixView {
 
 MatrixView make_view(const sgc_matrix *A);
 
-// ---- correlation GEMM tiling (see omp_corr.hip) ----
+// ---- correlation GEMM tiling (see omp.hip) ----
 constexpr int CORR_BM = 128; // rows of At (positions i) per workgroup
 constexpr int CORR_BN = 128; // right-hand sides per workgroup
 
@@ -34,7 +35,8 @@ struct OmpWorkspace {
     int64_t f_stride;  // k*k plus a pad, so that equal columns of different right-hand sides (read at the
                        // same time by all workgroups) do not sit a power of two apart in memory
     double *avec;      // [N][k] coefficients in the orthonormal basis
-    double *xs;        // [N][k] current least-squares solution
+    double *xs;        // [2][N][k] least-squares solution: iteration j reads half (j+1)&1, writes half j&1
+    int64_t xs_half;   // elements between the two halves of xs
     float *res32;      // [N][r] residual rounded to float (operand of the contraction)
     float *cols;       // [N][k][r] selected columns of A
     uint64_t *partial; // [N][tiles_m][2] best and second-best packed (score, position) per tile
@@ -63,6 +65,7 @@ hipError_t launch_adam(const float *p, const float *q, float *m, float *v, float
 hipError_t launch_matrix_fill(uint32_t key0, uint32_t key1, float scale, int32_t r, int64_t row0,
                               int64_t rows, float *out, hipStream_t s, int profile_class = KC_OTHER);
 hipError_t launch_colnorms(const MatrixView &A, float *out, hipStream_t s);
+hipError_t launch_gram(const MatrixView &A, double *out, hipStream_t s);
 hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k, int32_t *sel, float *x,
                       const OmpWorkspace &ws, hipStream_t s, const float *y_fit = nullptr, float *z = nullptr);
 hipError_t launch_apply(float *W, int64_t C, int32_t d, int32_t k, const int32_t *sel_m, const float *x_m,

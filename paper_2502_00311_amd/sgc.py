@@ -18,7 +18,7 @@ GRAD_F32, GRAD_BF16 = 0, 1
 MATRIX_STORED, MATRIX_PHILOX = 0, 1
 
 EXPORTS = [
-    "sgc_status_string", "sgc_matrix_fill", "sgc_matrix_colnorms", "sgc_sparsify_project",
+    "sgc_status_string", "sgc_matrix_fill", "sgc_matrix_colnorms", "sgc_matrix_gram", "sgc_sparsify_project",
     "sgc_adam_compressed", "sgc_omp_workspace_bytes", "sgc_recover_omp", "sgc_recover_omp_shared", "sgc_reproject",
     "sgc_apply",
     "sgc_profile_enable", "sgc_profile_read",
@@ -30,6 +30,7 @@ class sgc_matrix(ctypes.Structure):
     _fields_ = [
         ("mode", ctypes.c_int32), ("d", ctypes.c_int32), ("r", ctypes.c_int32), ("reserved", ctypes.c_int32),
         ("seed", ctypes.c_uint64), ("At", ctypes.c_void_p), ("inv_colnorm", ctypes.c_void_p),
+        ("gram", ctypes.c_void_p),
     ]
 
 
@@ -65,6 +66,8 @@ def lib():
         L.sgc_matrix_fill.argtypes = [u64, i32, i64, i64, vp, vp]
         L.sgc_matrix_colnorms.restype = i32
         L.sgc_matrix_colnorms.argtypes = [ctypes.POINTER(sgc_matrix), vp, vp]
+        L.sgc_matrix_gram.restype = i32
+        L.sgc_matrix_gram.argtypes = [ctypes.POINTER(sgc_matrix), vp, vp]
         L.sgc_sparsify_project.restype = i32
         L.sgc_sparsify_project.argtypes = [vp, i32, i64, i32, i32, ctypes.POINTER(sgc_matrix), vp, vp, vp, vp, vp]
         L.sgc_adam_compressed.restype = i32
@@ -113,16 +116,18 @@ def hyper(beta1=0.9, beta2=0.999, eps=1e-8, lr=1e-3, alpha=1.0):
 class Matrix:
     """Host-side descriptor of the measurement matrix plus the device buffers it points to."""
 
-    def __init__(self, d, r, At=None, seed=0, inv_colnorm=None):
+    def __init__(self, d, r, At=None, seed=0, inv_colnorm=None, gram=None):
         self.d, self.r, self.seed = int(d), int(r), int(seed)
         self.At = At                    # torch [d, r] float32 on the GPU, or None (generated)
         self.inv_colnorm = inv_colnorm  # torch [d] float32 on the GPU, or None
+        self.gram = gram                # torch [d, d] float64 on the GPU, or None
         self.mode = MATRIX_STORED if At is not None else MATRIX_PHILOX
 
     def c(self):
         return sgc_matrix(self.mode, self.d, self.r, 0, self.seed,
                           self.At.data_ptr() if self.At is not None else None,
-                          self.inv_colnorm.data_ptr() if self.inv_colnorm is not None else None)
+                          self.inv_colnorm.data_ptr() if self.inv_colnorm is not None else None,
+                          self.gram.data_ptr() if self.gram is not None else None)
 
 
 def sgc_matrix_fill(seed, r, row0, rows, At_out, stream=None):
@@ -131,6 +136,10 @@ def sgc_matrix_fill(seed, r, row0, rows, At_out, stream=None):
 
 def sgc_matrix_colnorms(A, inv_colnorm_out, stream=None):
     _check(lib().sgc_matrix_colnorms(ctypes.byref(A.c()), _ptr(inv_colnorm_out), _stream(stream)), "sgc_matrix_colnorms")
+
+
+def sgc_matrix_gram(A, gram_out, stream=None):
+    _check(lib().sgc_matrix_gram(ctypes.byref(A.c()), _ptr(gram_out), _stream(stream)), "sgc_matrix_gram")
 
 
 def sgc_sparsify_project(grad, n, d, k, A, idx, val, p, q, stream=None):
