@@ -158,3 +158,15 @@ def test_shared_recovery_and_reprojection_reject_bad_arguments():
     assert reproject(k=4097) == sgc.ERR_SHAPE
     assert reproject(out=ODD) == sgc.ERR_ALIGN
     assert reproject(AA=mat(mode=9)) == sgc.ERR_DTYPE
+
+
+def test_gram_rejects_bad_arguments():
+    L = sgc.lib()
+    A = mat()
+    assert L.sgc_matrix_gram(ctypes.byref(A), None, None) == sgc.ERR_NULL
+    assert L.sgc_matrix_gram(None, FAKE, None) == sgc.ERR_NULL
+    assert L.sgc_matrix_gram(ctypes.byref(A), ODD, None) == sgc.ERR_ALIGN
+    big = mat(mode=1, d=65537, r=16, At=None)
+    assert L.sgc_matrix_gram(ctypes.byref(big), FAKE, None) == sgc.ERR_SHAPE
+    bad = mat(r=18)
+    assert L.sgc_matrix_gram(ctypes.byref(bad), FAKE, None) == sgc.ERR_SHAPE
