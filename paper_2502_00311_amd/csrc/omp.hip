@@ -334,12 +334,18 @@ __device__ __forceinline__ void static_for(F &&f)
 
 constexpr int CORRP_BM = 256, CORRP_BN = 128;
 
+// NB = 2: the 256 x 128 tile described above. NB = 1: a 256 x 64 tile for at most 64 right-hand sides
+// (each wavefront 128 x 32, groups of 16 MFMAs; the LDS write and the global load of a staging piece
+// follow the same MFMA of group 2, so the load still leads its use by a whole stage).
+template <int NB>
 __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, const float *__restrict__ R, int32_t N,
                                                                 const uint32_t *__restrict__ bitmap, int32_t words,
                                                                 uint64_t *__restrict__ partial, int32_t tiles_m)
 {
-    constexpr int BM = CORRP_BM, BN = CORRP_BN, BK = 32, LD = BK + 4, MB = 4, NB = 2;
-    constexpr int LA = 8, LB = 4; // 16-byte pieces per thread per stage
+    constexpr int BM = CORRP_BM, BN = 64 * NB, BK = 32, LD = BK + 4, MB = 4;
+    constexpr int WN = 32 * NB;            // right-hand sides per wavefront
+    constexpr int GM = 4 * MB * NB;        // MFMAs per group (8 depths)
+    constexpr int LA = 8, LB = 2 * NB;     // 16-byte pieces per thread per stage
     typedef float floatx4 __attribute__((ext_vector_type(4)));
     extern __shared__ __attribute__((aligned(16))) float corr_lds[];
     float *lds = corr_lds; // A stages [2][BM*LD], then R stages [2][BN*LD], then what the epilogue needs:
@@ -374,7 +380,7 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
             for (int v = 0; v < 16; ++v)
                 acc[a][b][v] = 0.f;
     const int ra = (wm * 128 + l32) * LD + lhalf * 4; // fragment read offsets (floats)
-    const int rb = 2 * BM * LD + (wn * 64 + l32) * LD + lhalf * 4;
+    const int rb = 2 * BM * LD + (wn * WN + l32) * LD + lhalf * 4;
 
     auto gload = [&](int u, int kb) { // staging piece u of stage kb (the last stage again beyond the end)
         const int kk = (kb < nkb ? kb : nkb - 1) * BK;
@@ -393,8 +399,8 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
         else
             fb[which][op - MB] = *reinterpret_cast<const floatx4 *>(lds + rb + buf * BN * LD + (op - MB) * 32 * LD + ks * 8);
     };
-    auto mfma = [&](int which, int m) { // m = 0..31: depth t = m / 8 of the fragment, block (m % 8) / 2, m % 2
-        const int t = m >> 3, a = (m & 7) >> 1, b = m & 1;
+    auto mfma = [&](int which, int m) { // m = 0..GM-1: depth t of the fragment, then block row a, block column b
+        const int t = m / (MB * NB), a = (m % (MB * NB)) / NB, b = m % NB;
         const floatx4 x4 = fa[which][a], y4 = fb[which][b];
         const float x = t == 0 ? x4.x : (t == 1 ? x4.y : (t == 2 ? x4.z : x4.w));
         const float y = t == 0 ? y4.x : (t == 1 ? y4.y : (t == 2 ? y4.z : y4.w));
@@ -425,33 +431,38 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
 
     auto stage = [&](int kb, auto bufc) {
         constexpr int buf = decltype(bufc)::value;
-        static_for<0, 32>([&](auto mc) {
+        static_for<0, GM>([&](auto mc) {
             constexpr int m = decltype(mc)::value;
             mfma(0, m);
             if constexpr (m < MB + NB)
                 fread(1, m, buf, 1);
             __builtin_amdgcn_sched_barrier(0);
         });
-        static_for<0, 32>([&](auto mc) {
+        static_for<0, GM>([&](auto mc) {
             constexpr int m = decltype(mc)::value;
             mfma(1, m);
             if constexpr (m < MB + NB)
                 fread(0, m, buf, 2);
             __builtin_amdgcn_sched_barrier(0);
         });
-        static_for<0, 32>([&](auto mc) {
+        static_for<0, GM>([&](auto mc) {
             constexpr int m = decltype(mc)::value;
             mfma(0, m);
-            if constexpr (m < MB + NB)
+            if constexpr (m < MB + NB) {
                 fread(1, m, buf, 3);
-            else if constexpr (m >= 6 && m < 6 + LA + LB)
-                lwrite(m - 6, buf ^ 1);
-            else if constexpr (m >= 20 && m < 20 + LA + LB)
-                gload(m - 20, kb + 2);
+            } else if constexpr (NB == 2) {
+                if constexpr (m >= 6 && m < 6 + LA + LB)
+                    lwrite(m - 6, buf ^ 1);
+                else if constexpr (m >= 20 && m < 20 + LA + LB)
+                    gload(m - 20, kb + 2);
+            } else if constexpr (m < MB + NB + LA + LB) {
+                lwrite(m - (MB + NB), buf ^ 1);
+                gload(m - (MB + NB), kb + 2);
+            }
             __builtin_amdgcn_sched_barrier(0);
         });
         __syncthreads();
-        static_for<0, 32>([&](auto mc) {
+        static_for<0, GM>([&](auto mc) {
             constexpr int m = decltype(mc)::value;
             mfma(1, m);
             if constexpr (m < MB + NB)
@@ -481,7 +492,7 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
     for (int a = 0; a < MB; ++a)
 #pragma unroll
         for (int b = 0; b < NB; ++b)
-            msk[a][b] = msk_s[(wn * 64 + b * 32 + l32) * (BM / 32) + wm * 4 + a];
+            msk[a][b] = msk_s[(wn * WN + b * 32 + l32) * (BM / 32) + wm * 4 + a];
     auto scan = [&](auto maskedc) {
         constexpr bool MASKED = decltype(maskedc)::value;
 #pragma unroll
@@ -540,7 +551,7 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
     };
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-        const int nl = wn * 64 + b * 32 + l32;
+        const int nl = wn * WN + b * 32 + l32;
         uint64_t wb = widen(best[b]), ws2 = widen(second[b]);
         const uint64_t ob = shfl_xor_u64(wb, 32), os = shfl_xor_u64(ws2, 32);
         top2_insert(ob, wb, ws2);
@@ -562,30 +573,43 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
     }
 }
 
-static hipError_t corr_pipelined_launch(const MatrixView &A, int32_t rows, const float *R, int32_t N,
-                                        const OmpWorkspace &ws, int32_t tiles_m, hipStream_t s)
+template <int NB>
+static hipError_t corr_pipelined_launch_nb(const MatrixView &A, int32_t rows, const float *R, int32_t N,
+                                           const OmpWorkspace &ws, int32_t tiles_m, hipStream_t s)
 {
-    constexpr size_t smem = (size_t)2 * (CORRP_BM + CORRP_BN) * 36 * sizeof(float) + CORRP_BM * sizeof(float) +
-                            (size_t)CORRP_BN * (CORRP_BM / 32) * sizeof(uint32_t);
+    constexpr int BN = 64 * NB;
+    constexpr size_t smem = (size_t)2 * (CORRP_BM + BN) * 36 * sizeof(float) + CORRP_BM * sizeof(float) +
+                            (size_t)BN * (CORRP_BM / 32) * sizeof(uint32_t);
     static bool raised = false;
     if (!raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_pipelined_kernel),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_pipelined_kernel<NB>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess)
             return e;
         raised = true;
     }
-    const dim3 grid((unsigned)(rows / CORRP_BM), (unsigned)((N + CORRP_BN - 1) / CORRP_BN));
-    corr_pipelined_kernel<<<grid, 256, smem, s>>>(A, R, N, ws.bitmap, ws.words, ws.partial, tiles_m);
+    const dim3 grid((unsigned)(rows / CORRP_BM), (unsigned)((N + BN - 1) / BN));
+    corr_pipelined_kernel<NB><<<grid, 256, smem, s>>>(A, R, N, ws.bitmap, ws.words, ws.partial, tiles_m);
     return hipSuccess;
 }
 
+static hipError_t corr_pipelined_launch(const MatrixView &A, int32_t rows, const float *R, int32_t N,
+                                        const OmpWorkspace &ws, int32_t tiles_m, hipStream_t s)
+{
+    if (N <= 64)
+        return corr_pipelined_launch_nb<1>(A, rows, R, N, ws, tiles_m, s);
+    return corr_pipelined_launch_nb<2>(A, rows, R, N, ws, tiles_m, s);
+}
+
 // whether the pipelined kernel covers this problem (full tiles of positions, stored rows, even number
-// of stages; the last tile of right-hand sides may be ragged, but a batch that fits the half-width tile
-// of the general kernel is left to it)
+// of stages; the last tile of right-hand sides may be ragged)
 static bool corr_pipelined_ok(const MatrixView &A, int32_t N, int32_t panel_rows)
 {
-    return A.d % CORRP_BM == 0 && N > 64 && A.r % 64 == 0 && panel_rows % CORRP_BM == 0;
+    // at most 64 right-hand sides and few position tiles: the general kernel's 128-row tiles give
+    // twice the workgroups, which matters more than the schedule when the chip is far from full
+    if (N <= 64 && A.d / CORRP_BM < 128)
+        return false;
+    return A.d % CORRP_BM == 0 && A.r % 64 == 0 && panel_rows % CORRP_BM == 0;
 }
 
 // The tiling in use: 128 x 128 outputs (128 x 64 when there are at most 64 right-hand sides), depth 32

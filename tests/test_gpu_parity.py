@@ -215,6 +215,8 @@ def run_omp(Y, A, k):
     (130, 700, 64, 8, "philox"),     # two right-hand-side tiles, ragged
     (3, 2000, 100, 10, "stored"),    # depth not a multiple of the staging depth
     (2, 2048, 512, 320, "stored"),   # k > 256: sixteen rows of F per lane in the update kernel
+    (3, 32768, 64, 5, "stored"),     # many full position tiles, few right-hand sides: the half-width pipelined tile
+    (64, 32768, 128, 3, "stored"),   # the same tile completely filled
 ])
 def test_omp_matches_oracle_on_noisy_right_hand_sides(N, d, r, k, mode):
     say("omp", N, d, r, k, mode)
