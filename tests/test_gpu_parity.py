@@ -490,3 +490,24 @@ def test_resume_from_copied_state_is_bitwise_identical():
     torch.cuda.synchronize()
     assert np.array_equal(W.cpu().numpy().view(np.uint32), straight["W"].view(np.uint32))
     assert np.array_equal(buf.m.cpu().numpy().view(np.uint32), straight["m"].view(np.uint32))
+
+
+# ------------------------------------------------------------- streams and instrumentation
+def test_large_batch_two_streams_equals_single_stream_and_profile_counts():
+    """A batch of 600 right-hand sides runs its two halves on two streams; with per-kernel timing
+    enabled it runs on the caller's stream alone. Both must give bitwise the same result, and the
+    timing collection must count one contraction and one selection/update scope per iteration."""
+    N, d, r, k = 600, 3000, 64, 6
+    rng = np.random.default_rng(77)
+    A, At = make_matrix("philox", 33, d, r)
+    Y = rng.standard_normal((N, r)).astype(np.float32)
+    a = run_omp(Y, A, k)
+    sgc.sgc_profile_enable(True)
+    b = run_omp(Y, A, k)
+    prof = sgc.sgc_profile_read()
+    sgc.sgc_profile_enable(False)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1].view(np.uint32), b[1].view(np.uint32))
+    assert prof["omp_corr"][1] == k and prof["omp_select_update"][1] == k
+    assert prof["omp_matrix_fill"][1] == 1 and prof["omp_corr"][0] > 0.0
+    c = run_omp(Y, A, k)    # and again on two streams after the collection is switched off
+    assert np.array_equal(a[0], c[0]) and np.array_equal(a[1].view(np.uint32), c[1].view(np.uint32))
