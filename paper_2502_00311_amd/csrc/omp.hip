@@ -782,6 +782,19 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(MatrixView A, IterAr
     }
     __syncthreads();
     const int32_t lam = s_lambda;
+    // with a table of column inner products, w_t = <A_:lambda_t, a> is a gather from its row lambda:
+    // requested here, before the column itself is fetched, so that both travel at the same time
+    constexpr int GQ = (1024 + PICK_THREADS - 1) / PICK_THREADS; // k <= 1024
+    double gram_w[GQ];
+    if (A.gram && slice == 0) {
+        const double *grow = A.gram + (int64_t)lam * A.d;
+        const int32_t *selq = P.sel + n * k;
+#pragma unroll
+        for (int q = 0; q < GQ; ++q) {
+            const int32_t t = tid + q * PICK_THREADS;
+            gram_w[q] = t < it ? grow[selq[t]] : 0.0;
+        }
+    }
 
     // (3) the new column to LDS; slice 0 stores it and g = ||a||^2, b = <a, y>
     float *cols = W.cols + (n * k) * (int64_t)r;
@@ -826,9 +839,12 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(MatrixView A, IterAr
     const int32_t *selp = P.sel + n * k;
     if (A.gram) {
         if (slice == 0) {
-            const double *grow = A.gram + (int64_t)lam * A.d;
-            for (int32_t t = tid; t < it; t += PICK_THREADS)
-                wv[t] = grow[selp[t]];
+#pragma unroll
+            for (int q = 0; q < GQ; ++q) {
+                const int32_t t = tid + q * PICK_THREADS;
+                if (t < it)
+                    wv[t] = gram_w[q];
+            }
         }
         return;
     }
