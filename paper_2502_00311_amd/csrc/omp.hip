@@ -1247,11 +1247,10 @@ static void omp_select_update(const OmpPlan &pl, const MatrixView &A, const floa
         pick_kernel<true><<<pgrid, PICK_THREADS, pl.pick_smem, s>>>(pl.Apick, P);
     else
         pick_kernel<false><<<pgrid, PICK_THREADS, pl.pick_smem, s>>>(pl.Apick, P);
-    // One workgroup per right-hand side. (The kernel can spread a right-hand side over several slices,
-    // each repeating the factor pass and taking a share of the residual; measured at 128 right-hand
-    // sides that is slower, 42 us against 31 us per launch, because the repeated passes over F cost
-    // more than the wider residual pass saves.)
-    const dim3 ugrid((unsigned)Ng, 1u);
+    // One workgroup per right-hand side, two when there are so few that half the chip would idle
+    // (each repeats the factor pass and takes half of the residual). More slices were measured
+    // slower: the repeated passes over F cost more than the wider residual pass saves.
+    const dim3 ugrid((unsigned)Ng, Ng <= 128 ? 2u : 1u);
     if (k <= 128)
         update_kernel<2, 4><<<ugrid, 256, pl.factor_smem, s>>>(P, A.r);
     else if (k <= 256)
