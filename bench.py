@@ -42,6 +42,9 @@ def main():
     ap.add_argument("--gram", action="store_true",
                     help="build the optional table of column inner products (sgc_matrix_gram, 8 d^2 bytes, once, "
                          "outside the timed region) and let the recovery use it")
+    ap.add_argument("--screen-bf16", action="store_true",
+                    help="screen the correlation contraction on the bfloat16 matrix cores (split operands, three "
+                         "products); candidates are re-scored in double either way")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (reference for the rocprofv3 FETCH_SIZE / "
@@ -80,6 +83,8 @@ def main():
         A = sgc.Matrix(d, r, At=None, seed=w.a_seed)
     A.inv_colnorm = torch.empty(d, dtype=torch.float32, device=dev)
     sgc.sgc_matrix_colnorms(A, A.inv_colnorm)
+    if args.screen_bf16:
+        A.flags = sgc.MATRIX_FLAG_SCREEN_BF16
     gram_ms = None
     if args.gram:
         A.gram = torch.empty((d, d), dtype=torch.float64, device=dev)
@@ -136,11 +141,17 @@ def main():
     flops_per_launch = 2.0 * d * r * nrhs / launches_per_iter
     avg_ms = corr_ms / max(corr_n, 1)
     achieved = flops_per_launch / (avg_ms * 1e-3) / 1e12
+    peak = MFMA_F32_PEAK_TFLOPS
+    kernel_name = "omp correlation contraction At*R (float 32x32x2 MFMA, fused argmax epilogue)"
+    if args.screen_bf16:  # three bfloat16 products per float product, priced against the bfloat16 peak
+        achieved *= 3.0
+        peak = 2500.0
+        kernel_name = "omp correlation contraction At*R (3 x bf16 32x32x16 MFMA on split operands, fused argmax epilogue)"
     roofline = {
-        "bound": "mfma", "kernel": "omp correlation contraction At*R (float 32x32x2 MFMA, fused argmax epilogue)",
-        "achieved": round(achieved, 3), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
-        "frac": round(achieved / MFMA_F32_PEAK_TFLOPS, 4),
-        "traffic": None if args.shared_support else MEASURED_TRAFFIC.get(w.name),
+        "bound": "mfma", "kernel": kernel_name,
+        "achieved": round(achieved, 3), "peak": peak, "unit": "TFLOP/s",
+        "frac": round(achieved / peak, 4),
+        "traffic": None if (args.shared_support or args.screen_bf16) else MEASURED_TRAFFIC.get(w.name),
         "flops_per_launch": flops_per_launch, "avg_launch_ms": round(avg_ms, 5), "launches": corr_n,
     }
     if fill_ms > 0:  # generated A produced by a separate fill kernel: the rate including that time
@@ -162,7 +173,8 @@ def main():
                    "matrix": "philox, materialised by the caller" if (args.materialize and w.matrix != "stored") else w.matrix,
                    "rhs_per_omp_call": nrhs,
                    "recovery": "shared_support" if args.shared_support else "two_supports",
-                   "gram_table": bool(args.gram)},
+                   "gram_table": bool(args.gram),
+                   "contraction": "bf16 split (3 products), float accumulate" if args.screen_bf16 else "float"},
         "roofline": roofline,
         "ms_per_step_with_events": round((t3 - t2) * 1e3 / K, 3),
         "gram_build_ms": None if gram_ms is None else round(gram_ms, 2),

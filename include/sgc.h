@@ -52,6 +52,17 @@ enum {
 /* gradient element type of sgc_sparsify_project */
 enum { SGC_GRAD_F32 = 0, SGC_GRAD_BF16 = 1 };
 
+/*
+ * Option bit of sgc_matrix.flags, read by sgc_recover_omp* only. The correlation contraction only
+ * has to find the candidates for the argmax: every position whose float score lies within 2^-10 of
+ * the largest is re-scored in double before the selection is made. With this bit the contraction is
+ * computed on the bfloat16 matrix cores from operands split in two bfloat16 terms (three products,
+ * float accumulation, scores within ~1e-5 relative of the float ones) instead of on the float matrix
+ * cores: the recovered support and values are unchanged, the contraction is several times faster.
+ * Off by default: the default contraction is float throughout.
+ */
+enum { SGC_MATRIX_FLAG_SCREEN_BF16 = 1 };
+
 /* how the measurement matrix is provided */
 enum {
     SGC_MATRIX_STORED = 0, /* At resident in device memory */
@@ -75,7 +86,7 @@ typedef struct sgc_matrix {
     int32_t mode; /* SGC_MATRIX_STORED | SGC_MATRIX_PHILOX */
     int32_t d;    /* columns of A = chunk length */
     int32_t r;    /* rows of A = measurements per chunk; multiple of 4 */
-    int32_t reserved;
+    int32_t flags; /* 0, or SGC_MATRIX_FLAG_SCREEN_BF16 */
     uint64_t seed;            /* PHILOX mode */
     const float *At;          /* device [d][r], STORED mode; 16-byte aligned */
     const float *inv_colnorm; /* device [d]; may be NULL for sgc_sparsify_project */

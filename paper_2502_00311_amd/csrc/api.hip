@@ -19,6 +19,7 @@ MatrixView make_view(const sgc_matrix *A)
     v.scale = (float)(1.0 / sqrt((double)A->r));
     v.generated = A->mode == SGC_MATRIX_PHILOX ? 1 : 0;
     v.row0 = 0;
+    v.flags = A->flags;
     return v;
 }
 

@@ -291,6 +291,138 @@ __global__ __launch_bounds__(WMW * WNW * 64, MINB) void corr_kernel(MatrixView A
                                             tiles_m, m0, n0, wm, wn);
 }
 
+// Screening variant of the contraction on the bfloat16 matrix cores (an option of the matrix, never the
+// default). Every float operand is split into two bfloat16 terms, a = hi + lo with |a - hi - lo| <=
+// 2^-17 |a|, and the product is taken as hi*hi + hi*lo + lo*hi in three v_mfma_f32_32x32x16_bf16 with
+// float accumulation: scores agree with the float contraction to ~1e-5 relative, far inside the 2^-10
+// band of near-maximal candidates that the selection kernel re-scores in double, so the selected
+// support does not change while the matrix-core time drops by a factor of five (16 x the rate, three
+// products). 128 x 128 outputs per workgroup, 2 x 2 wavefronts of 64 x 64, depth 32 per stage; the float
+// tiles are fetched two stages ahead into registers, split on the way into LDS (one buffer of four
+// bfloat16 planes), and consumed as 16-byte fragments: lane l supplies row l % 32, depths 8 (l / 32) .. +7
+// of a 16-deep block, for both operands alike.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+constexpr int SPLIT_ROWB = 80; // bytes per LDS row: 32 bfloat16 + 16 bytes of padding (conflict-free 16-byte reads)
+
+__device__ __forceinline__ void split_bf16(const float4 &a, uint2 &hi, uint2 &lo)
+{
+    const bf16x2 h0 = {(__bf16)a.x, (__bf16)a.y}, h1 = {(__bf16)a.z, (__bf16)a.w};
+    const bf16x2 l0 = {(__bf16)(a.x - (float)h0[0]), (__bf16)(a.y - (float)h0[1])};
+    const bf16x2 l1 = {(__bf16)(a.z - (float)h1[0]), (__bf16)(a.w - (float)h1[1])};
+    hi = make_uint2(*reinterpret_cast<const uint32_t *>(&h0), *reinterpret_cast<const uint32_t *>(&h1));
+    lo = make_uint2(*reinterpret_cast<const uint32_t *>(&l0), *reinterpret_cast<const uint32_t *>(&l1));
+}
+
+__global__ __launch_bounds__(256, 2) void corr_split_kernel(MatrixView A, const float *__restrict__ R, int32_t N,
+                                                            const uint32_t *__restrict__ bitmap, int32_t words,
+                                                            uint64_t *__restrict__ partial, int32_t tiles_m)
+{
+    constexpr int BM = 128, BN = 128, BK = 32, MB = 2, NB = 2, LQ = 4; // LQ float4 per thread, tile and stage
+    constexpr int PLANE = 128 * SPLIT_ROWB;
+    extern __shared__ __attribute__((aligned(16))) float corr_lds[];
+    unsigned char *lds = reinterpret_cast<unsigned char *>(corr_lds); // planes: A hi, A lo, R hi, R lo
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int32_t d = A.d, r = A.r;
+    const int32_t m0 = A.row0 + blockIdx.x * BM, n0 = blockIdx.y * BN;
+    const float *At0 = A.At - (int64_t)A.row0 * r;
+
+    float4 ga[2][LQ], gb[2][LQ];
+    auto load_global = [&](int set, int32_t k0) {
+#pragma unroll
+        for (int u = 0; u < LQ; ++u) {
+            const int f = tid + 256 * u; // 128 rows x 8 quads
+            const int32_t row = f >> 3, kk = k0 + (f & 7) * 4;
+            float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
+            if (m0 + row < d && kk < r)
+                a = *reinterpret_cast<const float4 *>(At0 + (int64_t)(m0 + row) * r + kk);
+            if (n0 + row < N && kk < r)
+                b = *reinterpret_cast<const float4 *>(R + (int64_t)(n0 + row) * r + kk);
+            ga[set][u] = a;
+            gb[set][u] = b;
+        }
+    };
+    auto store_lds = [&](int set) {
+#pragma unroll
+        for (int u = 0; u < LQ; ++u) {
+            const int f = tid + 256 * u;
+            const int off = (f >> 3) * SPLIT_ROWB + (f & 7) * 8;
+            uint2 hi, lo;
+            split_bf16(ga[set][u], hi, lo);
+            *reinterpret_cast<uint2 *>(lds + off) = hi;
+            *reinterpret_cast<uint2 *>(lds + PLANE + off) = lo;
+            split_bf16(gb[set][u], hi, lo);
+            *reinterpret_cast<uint2 *>(lds + 2 * PLANE + off) = hi;
+            *reinterpret_cast<uint2 *>(lds + 3 * PLANE + off) = lo;
+        }
+    };
+
+    floatx16 acc[MB][NB];
+#pragma unroll
+    for (int a = 0; a < MB; ++a)
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                acc[a][b][v] = 0.f;
+
+    const int nkb = (r + BK - 1) / BK;
+    const int l32 = lane & 31, lhalf = lane >> 5;
+    const unsigned char *pa = lds + (wm * 64 + l32) * SPLIT_ROWB + lhalf * 16;
+    const unsigned char *pb = lds + 2 * PLANE + (wn * 64 + l32) * SPLIT_ROWB + lhalf * 16;
+    load_global(0, 0);
+    if (nkb > 1)
+        load_global(1, BK);
+    auto stage = [&](int kb, auto setc) {
+        constexpr int set = decltype(setc)::value;
+        store_lds(set);
+        __syncthreads();
+        if (kb + 2 < nkb)
+            load_global(set, (kb + 2) * BK);
+#pragma unroll
+        for (int kq = 0; kq < BK / 16; ++kq) {
+            bf16x8 ah[MB], al[MB], bh[NB], bl[NB];
+#pragma unroll
+            for (int a = 0; a < MB; ++a) {
+                ah[a] = *reinterpret_cast<const bf16x8 *>(pa + a * 32 * SPLIT_ROWB + kq * 32);
+                al[a] = *reinterpret_cast<const bf16x8 *>(pa + PLANE + a * 32 * SPLIT_ROWB + kq * 32);
+            }
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                bh[b] = *reinterpret_cast<const bf16x8 *>(pb + b * 32 * SPLIT_ROWB + kq * 32);
+                bl[b] = *reinterpret_cast<const bf16x8 *>(pb + PLANE + b * 32 * SPLIT_ROWB + kq * 32);
+            }
+            // the three products of a block are issued four MFMAs apart (no back-to-back dependency)
+#pragma unroll
+            for (int prod = 0; prod < 3; ++prod)
+#pragma unroll
+                for (int a = 0; a < MB; ++a)
+#pragma unroll
+                    for (int b = 0; b < NB; ++b)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(prod == 0 ? al[a] : ah[a],
+                                                                            prod == 1 ? bl[b] : bh[b], acc[a][b], 0, 0, 0);
+        }
+        __syncthreads();
+    };
+    for (int kb = 0; kb < nkb; kb += 2) {
+        stage(kb, std::integral_constant<int, 0>{});
+        if (kb + 1 < nkb)
+            stage(kb + 1, std::integral_constant<int, 1>{});
+    }
+    corr_epilogue<BM, BN, 2, 2, MB, NB>(A, acc, reinterpret_cast<uint64_t *>(corr_lds), N, bitmap, words, partial,
+                                        tiles_m, m0, n0, wm, wn);
+}
+
+static hipError_t corr_split_launch(const MatrixView &A, int32_t rows, const float *R, int32_t N,
+                                    const OmpWorkspace &ws, int32_t tiles_m, hipStream_t s)
+{
+    constexpr size_t smem = (size_t)4 * 128 * SPLIT_ROWB;
+    const dim3 grid((unsigned)((rows + 127) / 128), (unsigned)((N + 127) / 128));
+    corr_split_kernel<<<grid, 256, smem, s>>>(A, R, N, ws.bitmap, ws.words, ws.partial, tiles_m);
+    return hipSuccess;
+}
+
 // One tiling of the contraction: sizes, and a launcher that raises the dynamic-LDS limit once.
 template <bool GENERATED, int BM, int BN, int BK, int WMW, int WNW, int MINB>
 static hipError_t corr_launch(const MatrixView &A, int32_t rows, const float *R, int32_t N, const OmpWorkspace &ws,
@@ -1177,6 +1309,7 @@ __global__ __launch_bounds__(REFIT_THREADS) void refit_kernel(IterArgs P, const 
 struct OmpPlan {
     bool panels;     // generated A produced into ws.panel and consumed from there
     bool pipelined;  // full tiles of stored rows: corr_pipelined_kernel
+    bool screen;     // resident rows and the matrix asks for it: corr_split_kernel
     int32_t tiles_m; // position tiles of the contraction in use (stride of ws.partial)
     MatrixView Apick; // the view pick_kernel fetches columns from
     size_t pick_smem, factor_smem;
@@ -1220,14 +1353,16 @@ static hipError_t omp_contraction(const OmpPlan &pl, const MatrixView &A, int32_
             Ap.generated = 0;
             Ap.At = w.panel;
             Ap.row0 = p0;
-            e = pl.pipelined ? corr_pipelined_launch(Ap, rows, w.res32, Ng, w, pl.tiles_m, s)
-                             : corr_dispatch<false>(Ap, rows, w.res32, Ng, w, pl.tiles_m, s);
+            e = pl.screen      ? corr_split_launch(Ap, rows, w.res32, Ng, w, pl.tiles_m, s)
+                : pl.pipelined ? corr_pipelined_launch(Ap, rows, w.res32, Ng, w, pl.tiles_m, s)
+                               : corr_dispatch<false>(Ap, rows, w.res32, Ng, w, pl.tiles_m, s);
         }
     } else if (A.generated) {
         e = corr_dispatch<true>(A, A.d, w.res32, Ng, w, pl.tiles_m, s);
     } else {
-        e = pl.pipelined ? corr_pipelined_launch(A, A.d, w.res32, Ng, w, pl.tiles_m, s)
-                         : corr_dispatch<false>(A, A.d, w.res32, Ng, w, pl.tiles_m, s);
+        e = pl.screen      ? corr_split_launch(A, A.d, w.res32, Ng, w, pl.tiles_m, s)
+            : pl.pipelined ? corr_pipelined_launch(A, A.d, w.res32, Ng, w, pl.tiles_m, s)
+                           : corr_dispatch<false>(A, A.d, w.res32, Ng, w, pl.tiles_m, s);
     }
     return e;
 }
@@ -1302,6 +1437,11 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
     OmpPlan pl{};
     pl.panels = A.generated && (N + CORR_BN - 1) / CORR_BN >= 4;
     pl.pipelined = (!A.generated || pl.panels) && corr_pipelined_ok(A, N, ws.panel_rows);
+    // the bfloat16 screening contraction needs resident rows; a matrix regenerated inside the
+    // contraction keeps the float kernel (its time is the generator's anyway)
+    pl.screen = (A.flags & SGC_MATRIX_FLAG_SCREEN_BF16) && (!A.generated || pl.panels);
+    if (pl.screen)
+        pl.pipelined = false;
     pl.tiles_m = pl.pipelined ? A.d / CORRP_BM : corr_tiles_m(A.d);
     pl.pick_smem = ((size_t)A.r * 4 + 15) & ~(size_t)15;
     pl.factor_smem = 3 * sizeof(double) * (size_t)k;

@@ -18,6 +18,7 @@ struct MatrixView {
     float scale;         // (float)(1/sqrt((double)r))
     int32_t generated;   // 0 stored, 1 Philox
     int32_t row0;        // position held by At[0] (non-zero for a panel of a generated matrix)
+    int32_t flags;       // SGC_MATRIX_FLAG_*
 };
 
 MatrixView make_view(const sgc_matrix *A);

@@ -16,6 +16,7 @@ OK = 0
 ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_ALIGN, ERR_WORKSPACE, ERR_STEP, ERR_DEVICE = -1, -2, -3, -4, -5, -6, -7
 GRAD_F32, GRAD_BF16 = 0, 1
 MATRIX_STORED, MATRIX_PHILOX = 0, 1
+MATRIX_FLAG_SCREEN_BF16 = 1
 
 EXPORTS = [
     "sgc_status_string", "sgc_matrix_fill", "sgc_matrix_colnorms", "sgc_matrix_gram", "sgc_sparsify_project",
@@ -28,7 +29,7 @@ PROFILE_CLASSES = ["topk", "project", "adam", "omp_corr", "omp_select_update", "
 
 class sgc_matrix(ctypes.Structure):
     _fields_ = [
-        ("mode", ctypes.c_int32), ("d", ctypes.c_int32), ("r", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("mode", ctypes.c_int32), ("d", ctypes.c_int32), ("r", ctypes.c_int32), ("flags", ctypes.c_int32),
         ("seed", ctypes.c_uint64), ("At", ctypes.c_void_p), ("inv_colnorm", ctypes.c_void_p),
         ("gram", ctypes.c_void_p),
     ]
@@ -121,10 +122,11 @@ class Matrix:
         self.At = At                    # torch [d, r] float32 on the GPU, or None (generated)
         self.inv_colnorm = inv_colnorm  # torch [d] float32 on the GPU, or None
         self.gram = gram                # torch [d, d] float64 on the GPU, or None
+        self.flags = 0                  # MATRIX_FLAG_*
         self.mode = MATRIX_STORED if At is not None else MATRIX_PHILOX
 
     def c(self):
-        return sgc_matrix(self.mode, self.d, self.r, 0, self.seed,
+        return sgc_matrix(self.mode, self.d, self.r, self.flags, self.seed,
                           self.At.data_ptr() if self.At is not None else None,
                           self.inv_colnorm.data_ptr() if self.inv_colnorm is not None else None,
                           self.gram.data_ptr() if self.gram is not None else None)
