@@ -43,6 +43,7 @@ OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_
     w.xs = (double *)take(sizeof(double) * (size_t)N * k * 2);
     w.xs_half = (int64_t)N * k;
     w.res32 = (float *)take(sizeof(float) * (size_t)N * r);
+    w.res16 = reinterpret_cast<uint16_t *>(w.res32);
     w.cols = (float *)take(sizeof(float) * (size_t)N * k * r);
     w.partial = (uint64_t *)take(sizeof(uint64_t) * (size_t)N * w.tiles_m * 2);
     w.bitmap = (uint32_t *)take(sizeof(uint32_t) * (size_t)N * w.words);
@@ -56,6 +57,13 @@ OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_
         w.panel_rows = (int32_t)(rows < dpad ? rows : dpad);
         w.panel = (float *)take(sizeof(float) * (size_t)w.panel_rows * r);
     }
+    // bfloat16 planes of the matrix rows for the screening contraction: the whole matrix if that is at
+    // most 2 GiB, else one panel's worth (a stored matrix beyond that is split inside the contraction)
+    {
+        const int64_t dpad = ((int64_t)d + 127) / 128 * 128;
+        w.a16_rows = dpad * r * 4 <= ((int64_t)2 << 30) ? (int32_t)dpad : w.panel_rows;
+        w.a16 = (uint16_t *)take(sizeof(float) * (size_t)w.a16_rows * r);
+    }
     w.wv = (double *)take(sizeof(double) * (size_t)N * k);
     w.gb = (double *)take(sizeof(double) * (size_t)N * 2);
     w.bytes = off;
@@ -63,15 +71,34 @@ OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_
 }
 
 // ----------------------------------------------------------------------------------------------
+// a = hi + lo in bfloat16 (round to nearest even each), |a - hi - lo| <= 2^-17 |a|
+__device__ __forceinline__ void split_bf16_1(float a, uint16_t &hi, uint16_t &lo)
+{
+    const __bf16 h = (__bf16)a;
+    const __bf16 l = (__bf16)(a - (float)h);
+    hi = *reinterpret_cast<const uint16_t *>(&h);
+    lo = *reinterpret_cast<const uint16_t *>(&l);
+}
+
+// res_split != 0: the float copy of the residual is written in split32 format instead (see corr_split_kernel)
 __global__ __launch_bounds__(256) void omp_init_kernel(const float *__restrict__ y, int32_t r, int32_t words,
                                                        double *__restrict__ res64, float *__restrict__ res32,
-                                                       uint32_t *__restrict__ bitmap)
+                                                       uint32_t *__restrict__ bitmap, int32_t res_split)
 {
     const int64_t n = blockIdx.x;
+    uint16_t *res16 = reinterpret_cast<uint16_t *>(res32);
     for (int32_t j = threadIdx.x; j < r; j += 256) {
         const float v = y[n * r + j];
         res64[n * r + j] = (double)v;
-        res32[n * r + j] = v;
+        if (res_split) { // split32 row: the same 4 r bytes as the float row
+            uint16_t hi, lo;
+            split_bf16_1(v, hi, lo);
+            uint16_t *o = res16 + n * 2 * r + (j >> 5) * 64 + (j & 31);
+            o[0] = hi;
+            o[32] = lo;
+        } else {
+            res32[n * r + j] = v;
+        }
     }
     for (int32_t w = threadIdx.x; w < words; w += 256)
         bitmap[n * words + w] = 0u;
@@ -293,17 +320,23 @@ __global__ __launch_bounds__(WMW * WNW * 64, MINB) void corr_kernel(MatrixView A
 
 // Screening variant of the contraction on the bfloat16 matrix cores (an option of the matrix, never the
 // default). Every float operand is split into two bfloat16 terms, a = hi + lo with |a - hi - lo| <=
-// 2^-17 |a|, and the product is taken as hi*hi + hi*lo + lo*hi in three v_mfma_f32_32x32x16_bf16 with
+// 2^-17 |a|, and the product is taken as lo*hi + hi*lo + hi*hi in three v_mfma_f32_32x32x16_bf16 with
 // float accumulation: scores agree with the float contraction to ~1e-5 relative, far inside the 2^-10
 // band of near-maximal candidates that the selection kernel re-scores in double, so the selected
 // support does not change while the matrix-core time drops by a factor of five (16 x the rate, three
-// products). 128 x 128 outputs per workgroup, 2 x 2 wavefronts of 64 x 64, depth 32 per stage; the float
-// tiles are fetched two stages ahead into registers, split on the way into LDS (one buffer of four
-// bfloat16 planes), and consumed as 16-byte fragments: lane l supplies row l % 32, depths 8 (l / 32) .. +7
-// of a 16-deep block, for both operands alike.
+// products).
+// Split format ("split32", r % 32 == 0): a row of r floats becomes r/32 blocks of 128 bytes, each the 32
+// high parts followed by the 32 low parts of 32 consecutive depths, so a row keeps its 4r bytes and a
+// depth-32 stage of a row is one contiguous 128-byte piece, as for floats. The rows of At are split
+// once per call (or per panel fill) into ws.a16, the residuals are written in this format by the
+// update kernel.
+// Kernel: 128 x 128 outputs per workgroup, 2 x 2 wavefronts of 64 x 64, depth 32 per stage; pieces are
+// fetched two stages ahead into registers and copied to LDS as they are (rows padded to 144 bytes:
+// 16-byte accesses without bank conflicts); a fragment is 16 bytes: lane l supplies row l % 32, depths
+// 8 (l / 32) .. +7 of a 16-deep block, for both operands alike.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-constexpr int SPLIT_ROWB = 80; // bytes per LDS row: 32 bfloat16 + 16 bytes of padding (conflict-free 16-byte reads)
+constexpr int SPLIT_ROWB = 144; // bytes per LDS row: 32 high parts, 32 low parts, 16 bytes of padding
 
 __device__ __forceinline__ void split_bf16(const float4 &a, uint2 &hi, uint2 &lo)
 {
@@ -314,47 +347,53 @@ __device__ __forceinline__ void split_bf16(const float4 &a, uint2 &hi, uint2 &lo
     lo = make_uint2(*reinterpret_cast<const uint32_t *>(&l0), *reinterpret_cast<const uint32_t *>(&l1));
 }
 
-__global__ __launch_bounds__(256, 2) void corr_split_kernel(MatrixView A, const float *__restrict__ R, int32_t N,
+// byte offset, inside a split32 row, of the high parts of the float quad jb (depths 4 jb .. 4 jb + 3);
+// the low parts sit 64 bytes further
+__device__ __forceinline__ int64_t split32_quad_offset(int32_t jb)
+{
+    return (int64_t)(jb >> 3) * 128 + (jb & 7) * 8;
+}
+
+// As: rows of At in split32 format, row 0 = position A.row0; Rs: the residuals in split32 format.
+__global__ __launch_bounds__(256, 2) void corr_split_kernel(MatrixView A, const unsigned char *__restrict__ As,
+                                                            const unsigned char *__restrict__ Rs, int32_t N,
                                                             const uint32_t *__restrict__ bitmap, int32_t words,
                                                             uint64_t *__restrict__ partial, int32_t tiles_m)
 {
-    constexpr int BM = 128, BN = 128, BK = 32, MB = 2, NB = 2, LQ = 4; // LQ float4 per thread, tile and stage
-    constexpr int PLANE = 128 * SPLIT_ROWB;
+    constexpr int BM = 128, BN = 128, MB = 2, NB = 2, LQ = 4; // LQ 16-byte pieces per thread, tile and stage
+    constexpr int TILE = 128 * SPLIT_ROWB;
     extern __shared__ __attribute__((aligned(16))) float corr_lds[];
-    unsigned char *lds = reinterpret_cast<unsigned char *>(corr_lds); // planes: A hi, A lo, R hi, R lo
+    unsigned char *lds = reinterpret_cast<unsigned char *>(corr_lds); // A tile, then R tile
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int32_t d = A.d, r = A.r;
+    const int64_t rowb = (int64_t)r * 4; // bytes per row, as for floats
     const int32_t m0 = A.row0 + blockIdx.x * BM, n0 = blockIdx.y * BN;
-    const float *At0 = A.At - (int64_t)A.row0 * r;
+    const unsigned char *As0 = As - (int64_t)A.row0 * rowb;
 
-    float4 ga[2][LQ], gb[2][LQ];
-    auto load_global = [&](int set, int32_t k0) {
+    uint4 ga[2][LQ], gb[2][LQ];
+    auto load_global = [&](int set, int32_t kb) {
 #pragma unroll
         for (int u = 0; u < LQ; ++u) {
-            const int f = tid + 256 * u; // 128 rows x 8 quads
-            const int32_t row = f >> 3, kk = k0 + (f & 7) * 4;
-            float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
-            if (m0 + row < d && kk < r)
-                a = *reinterpret_cast<const float4 *>(At0 + (int64_t)(m0 + row) * r + kk);
-            if (n0 + row < N && kk < r)
-                b = *reinterpret_cast<const float4 *>(R + (int64_t)(n0 + row) * r + kk);
+            const int f = tid + 256 * u; // 128 rows x 8 pieces
+            const int32_t row = f >> 3;
+            const int64_t off = (int64_t)kb * 128 + (f & 7) * 16;
+            uint4 a = make_uint4(0u, 0u, 0u, 0u), b = a;
+            if (m0 + row < d)
+                a = *reinterpret_cast<const uint4 *>(As0 + (int64_t)(m0 + row) * rowb + off);
+            if (n0 + row < N)
+                b = *reinterpret_cast<const uint4 *>(Rs + (int64_t)(n0 + row) * rowb + off);
             ga[set][u] = a;
             gb[set][u] = b;
         }
     };
-    auto store_lds = [&](int set) {
+    auto store_lds = [&](int set, int buf) { // LDS: two stage buffers, each the A tile then the R tile
 #pragma unroll
         for (int u = 0; u < LQ; ++u) {
             const int f = tid + 256 * u;
-            const int off = (f >> 3) * SPLIT_ROWB + (f & 7) * 8;
-            uint2 hi, lo;
-            split_bf16(ga[set][u], hi, lo);
-            *reinterpret_cast<uint2 *>(lds + off) = hi;
-            *reinterpret_cast<uint2 *>(lds + PLANE + off) = lo;
-            split_bf16(gb[set][u], hi, lo);
-            *reinterpret_cast<uint2 *>(lds + 2 * PLANE + off) = hi;
-            *reinterpret_cast<uint2 *>(lds + 3 * PLANE + off) = lo;
+            const int off = buf * 2 * TILE + (f >> 3) * SPLIT_ROWB + (f & 7) * 16;
+            *reinterpret_cast<uint4 *>(lds + off) = ga[set][u];
+            *reinterpret_cast<uint4 *>(lds + TILE + off) = gb[set][u];
         }
     };
 
@@ -367,31 +406,33 @@ __global__ __launch_bounds__(256, 2) void corr_split_kernel(MatrixView A, const 
             for (int v = 0; v < 16; ++v)
                 acc[a][b][v] = 0.f;
 
-    const int nkb = (r + BK - 1) / BK;
+    const int nkb = r / 32;
     const int l32 = lane & 31, lhalf = lane >> 5;
     const unsigned char *pa = lds + (wm * 64 + l32) * SPLIT_ROWB + lhalf * 16;
-    const unsigned char *pb = lds + 2 * PLANE + (wn * 64 + l32) * SPLIT_ROWB + lhalf * 16;
+    const unsigned char *pb = lds + TILE + (wn * 64 + l32) * SPLIT_ROWB + lhalf * 16;
+    // stage kb computes from LDS buffer kb & 1 while stage kb + 1 waits in registers (set (kb + 1) & 1)
+    // and stage kb + 2 is being fetched into the set just emptied; one barrier per stage
     load_global(0, 0);
+    store_lds(0, 0);
     if (nkb > 1)
-        load_global(1, BK);
-    auto stage = [&](int kb, auto setc) {
-        constexpr int set = decltype(setc)::value;
-        store_lds(set);
-        __syncthreads();
-        if (kb + 2 < nkb)
-            load_global(set, (kb + 2) * BK);
+        load_global(1, 1);
+    if (nkb > 2)
+        load_global(0, 2);
+    __syncthreads();
+    auto stage = [&](int kb, auto bufc) {
+        constexpr int buf = decltype(bufc)::value; // also the register set that is being refilled: kb & 1
 #pragma unroll
-        for (int kq = 0; kq < BK / 16; ++kq) {
+        for (int kq = 0; kq < 2; ++kq) {
             bf16x8 ah[MB], al[MB], bh[NB], bl[NB];
 #pragma unroll
             for (int a = 0; a < MB; ++a) {
-                ah[a] = *reinterpret_cast<const bf16x8 *>(pa + a * 32 * SPLIT_ROWB + kq * 32);
-                al[a] = *reinterpret_cast<const bf16x8 *>(pa + PLANE + a * 32 * SPLIT_ROWB + kq * 32);
+                ah[a] = *reinterpret_cast<const bf16x8 *>(pa + buf * 2 * TILE + a * 32 * SPLIT_ROWB + kq * 32);
+                al[a] = *reinterpret_cast<const bf16x8 *>(pa + buf * 2 * TILE + a * 32 * SPLIT_ROWB + 64 + kq * 32);
             }
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                bh[b] = *reinterpret_cast<const bf16x8 *>(pb + b * 32 * SPLIT_ROWB + kq * 32);
-                bl[b] = *reinterpret_cast<const bf16x8 *>(pb + PLANE + b * 32 * SPLIT_ROWB + kq * 32);
+                bh[b] = *reinterpret_cast<const bf16x8 *>(pb + buf * 2 * TILE + b * 32 * SPLIT_ROWB + kq * 32);
+                bl[b] = *reinterpret_cast<const bf16x8 *>(pb + buf * 2 * TILE + b * 32 * SPLIT_ROWB + 64 + kq * 32);
             }
             // the three products of a block are issued four MFMAs apart (no back-to-back dependency)
 #pragma unroll
@@ -403,6 +444,10 @@ __global__ __launch_bounds__(256, 2) void corr_split_kernel(MatrixView A, const 
                         acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(prod == 0 ? al[a] : ah[a],
                                                                             prod == 1 ? bl[b] : bh[b], acc[a][b], 0, 0, 0);
         }
+        if (kb + 1 < nkb)
+            store_lds(buf ^ 1, buf ^ 1); // stage kb + 1: register set (kb + 1) & 1 -> LDS buffer (kb + 1) & 1
+        if (kb + 3 < nkb)
+            load_global(buf ^ 1, kb + 3);
         __syncthreads();
     };
     for (int kb = 0; kb < nkb; kb += 2) {
@@ -414,12 +459,49 @@ __global__ __launch_bounds__(256, 2) void corr_split_kernel(MatrixView A, const 
                                         tiles_m, m0, n0, wm, wn);
 }
 
-static hipError_t corr_split_launch(const MatrixView &A, int32_t rows, const float *R, int32_t N,
+// rows of floats -> split32 rows (count4 float quads, r4 quads per row)
+__global__ __launch_bounds__(256) void split_rows_kernel(const float *__restrict__ src, int64_t count4, int32_t r4,
+                                                         unsigned char *__restrict__ dst)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < count4; e += stride) {
+        const int64_t row = e / r4;
+        const int32_t jb = (int32_t)(e - row * r4);
+        uint2 h, l;
+        split_bf16(load_once_f4(src + 4 * e), h, l);
+        unsigned char *o = dst + row * ((int64_t)r4 * 16) + split32_quad_offset(jb);
+        *reinterpret_cast<uint2 *>(o) = h;
+        *reinterpret_cast<uint2 *>(o + 64) = l;
+    }
+}
+
+static void launch_split_rows(const float *src, int64_t rows, int32_t r, uint16_t *dst, hipStream_t s)
+{
+    const int64_t count4 = rows * (r >> 2);
+    int64_t blocks = (count4 + 255) / 256;
+    if (blocks > 256 * 32)
+        blocks = 256 * 32;
+    if (blocks > 0)
+        split_rows_kernel<<<dim3((unsigned)blocks), 256, 0, s>>>(src, count4, r >> 2,
+                                                                  reinterpret_cast<unsigned char *>(dst));
+}
+
+static hipError_t corr_split_launch(const MatrixView &A, const uint16_t *rows_split, int32_t rows, int32_t N,
                                     const OmpWorkspace &ws, int32_t tiles_m, hipStream_t s)
 {
     constexpr size_t smem = (size_t)4 * 128 * SPLIT_ROWB;
+    static bool raised = false;
+    if (!raised) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_split_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess)
+            return e;
+        raised = true;
+    }
     const dim3 grid((unsigned)((rows + 127) / 128), (unsigned)((N + 127) / 128));
-    corr_split_kernel<<<grid, 256, smem, s>>>(A, R, N, ws.bitmap, ws.words, ws.partial, tiles_m);
+    corr_split_kernel<<<grid, 256, smem, s>>>(A, reinterpret_cast<const unsigned char *>(rows_split),
+                                              reinterpret_cast<const unsigned char *>(ws.res16), N, ws.bitmap, ws.words,
+                                              ws.partial, tiles_m);
     return hipSuccess;
 }
 
@@ -784,6 +866,7 @@ struct IterArgs {
     // NULL: the selected columns are kept per right-hand side in ws.cols.
     const float *At_rows;
     int32_t share_table; // update_kernel: its dynamic LDS also holds the [wavefront][k] table of shares
+    int32_t res_split;   // update_kernel: != 0: the residual's float copy goes out in split32 format
 };
 
 template <bool GENERATED>
@@ -1244,8 +1327,19 @@ __global__ __launch_bounds__(FACTOR_MAX_THREADS) void update_kernel(IterArgs P, 
             ro[1] = e1;
             ro[2] = e2;
             ro[3] = e3;
-            reinterpret_cast<float4 *>(W.res32 + n * r)[jb] =
-                make_float4((float)e0, (float)e1, (float)e2, (float)e3);
+            if (P.res_split) {
+                uint16_t h[4], l[4];
+                split_bf16_1((float)e0, h[0], l[0]);
+                split_bf16_1((float)e1, h[1], l[1]);
+                split_bf16_1((float)e2, h[2], l[2]);
+                split_bf16_1((float)e3, h[3], l[3]);
+                unsigned char *o = reinterpret_cast<unsigned char *>(W.res16) + n * ((int64_t)r * 4) + split32_quad_offset(jb);
+                *reinterpret_cast<uint2 *>(o) = make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
+                *reinterpret_cast<uint2 *>(o + 64) = make_uint2(l[0] | ((uint32_t)l[1] << 16), l[2] | ((uint32_t)l[3] << 16));
+            } else {
+                reinterpret_cast<float4 *>(W.res32 + n * r)[jb] =
+                    make_float4((float)e0, (float)e1, (float)e2, (float)e3);
+            }
         }
     }
 }
@@ -1309,7 +1403,7 @@ __global__ __launch_bounds__(REFIT_THREADS) void refit_kernel(IterArgs P, const 
 struct OmpPlan {
     bool panels;     // generated A produced into ws.panel and consumed from there
     bool pipelined;  // full tiles of stored rows: corr_pipelined_kernel
-    bool screen;     // resident rows and the matrix asks for it: corr_split_kernel
+    bool screen;     // resident rows that fit ws.a16 and the matrix asks for it: corr_split_kernel
     int32_t tiles_m; // position tiles of the contraction in use (stride of ws.partial)
     MatrixView Apick; // the view pick_kernel fetches columns from
     size_t pick_smem, factor_smem;
@@ -1326,6 +1420,7 @@ static OmpWorkspace shift_workspace(const OmpWorkspace &ws, int32_t n0, int32_t 
     w.avec += (int64_t)n0 * k;
     w.xs += (int64_t)n0 * k;
     w.res32 += (int64_t)n0 * r;
+    w.res16 += (int64_t)n0 * 2 * r;
     w.cols += (int64_t)n0 * k * r;
     w.partial += (int64_t)n0 * tiles_m * 2;
     w.bitmap += (int64_t)n0 * ws.words;
@@ -1353,14 +1448,21 @@ static hipError_t omp_contraction(const OmpPlan &pl, const MatrixView &A, int32_
             Ap.generated = 0;
             Ap.At = w.panel;
             Ap.row0 = p0;
-            e = pl.screen      ? corr_split_launch(Ap, rows, w.res32, Ng, w, pl.tiles_m, s)
-                : pl.pipelined ? corr_pipelined_launch(Ap, rows, w.res32, Ng, w, pl.tiles_m, s)
-                               : corr_dispatch<false>(Ap, rows, w.res32, Ng, w, pl.tiles_m, s);
+            if (pl.screen) {
+                // a whole-matrix panel was split once per call; a refilled panel is split after each fill
+                const bool whole = w.panel_rows >= A.d;
+                if (!whole)
+                    launch_split_rows(w.panel, rows, A.r, w.a16, s);
+                e = corr_split_launch(Ap, w.a16, rows, Ng, w, pl.tiles_m, s);
+            } else {
+                e = pl.pipelined ? corr_pipelined_launch(Ap, rows, w.res32, Ng, w, pl.tiles_m, s)
+                                 : corr_dispatch<false>(Ap, rows, w.res32, Ng, w, pl.tiles_m, s);
+            }
         }
     } else if (A.generated) {
         e = corr_dispatch<true>(A, A.d, w.res32, Ng, w, pl.tiles_m, s);
     } else {
-        e = pl.screen      ? corr_split_launch(A, A.d, w.res32, Ng, w, pl.tiles_m, s)
+        e = pl.screen      ? corr_split_launch(A, w.a16, A.d, Ng, w, pl.tiles_m, s)
             : pl.pipelined ? corr_pipelined_launch(A, A.d, w.res32, Ng, w, pl.tiles_m, s)
                            : corr_dispatch<false>(A, A.d, w.res32, Ng, w, pl.tiles_m, s);
     }
@@ -1377,7 +1479,8 @@ static void omp_select_update(const OmpPlan &pl, const MatrixView &A, const floa
     if (pl.Apick.gram)
         slices = 1; // no pass over the selected columns to spread
     const dim3 pgrid((unsigned)Ng, (unsigned)slices);
-    IterArgs P{y, k, it, sel, x, w, pl.Apick.generated ? nullptr : pl.Apick.At, pl.factor_share_table ? 1 : 0};
+    IterArgs P{y, k, it, sel, x, w, pl.Apick.generated ? nullptr : pl.Apick.At, pl.factor_share_table ? 1 : 0,
+               pl.screen ? 1 : 0};
     if (pl.Apick.generated)
         pick_kernel<true><<<pgrid, PICK_THREADS, pl.pick_smem, s>>>(pl.Apick, P);
     else
@@ -1425,10 +1528,6 @@ static hipError_t omp_iterations(const OmpPlan &pl, bool whole_matrix_panel, con
 hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k, int32_t *sel, float *x,
                       const OmpWorkspace &ws, hipStream_t s, const float *y_fit, float *z)
 {
-    {
-        ProfileScope prof(KC_OTHER, s);
-        omp_init_kernel<<<dim3((unsigned)N), 256, 0, s>>>(y, A.r, ws.words, ws.res64, ws.res32, ws.bitmap);
-    }
     // A generated matrix is regenerated inside the contraction when few right-hand-side tiles share
     // it; with many tiles (each would regenerate all of A) it is produced into a cache-sized scratch,
     // once per call if it fits, else panel by panel in every iteration, and consumed from there.
@@ -1439,7 +1538,8 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
     pl.pipelined = (!A.generated || pl.panels) && corr_pipelined_ok(A, N, ws.panel_rows);
     // the bfloat16 screening contraction needs resident rows; a matrix regenerated inside the
     // contraction keeps the float kernel (its time is the generator's anyway)
-    pl.screen = (A.flags & SGC_MATRIX_FLAG_SCREEN_BF16) && (!A.generated || pl.panels);
+    pl.screen = (A.flags & SGC_MATRIX_FLAG_SCREEN_BF16) && A.r % 32 == 0 &&
+                (A.generated ? pl.panels : ws.a16_rows >= A.d);
     if (pl.screen)
         pl.pipelined = false;
     pl.tiles_m = pl.pipelined ? A.d / CORRP_BM : corr_tiles_m(A.d);
@@ -1453,6 +1553,11 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
         const size_t scratch = pl.factor_share_table && table > parts ? table : parts;
         pl.factor_smem += scratch;
     }
+    {
+        ProfileScope prof(KC_OTHER, s);
+        omp_init_kernel<<<dim3((unsigned)N), 256, 0, s>>>(y, A.r, ws.words, ws.res64, ws.res32, ws.bitmap,
+                                                          pl.screen ? 1 : 0);
+    }
     pl.Apick = A;
     const bool whole_matrix_panel = pl.panels && ws.panel_rows >= A.d;
     if (whole_matrix_panel) {
@@ -1462,13 +1567,18 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
         pl.Apick.generated = 0;
         pl.Apick.At = ws.panel;
     }
+    // screening contraction: the rows of At as bfloat16 planes, once per call where they fit
+    if (pl.screen && (!A.generated || whole_matrix_panel)) {
+        ProfileScope prof(KC_FILL, s);
+        launch_split_rows(whole_matrix_panel ? ws.panel : A.At, A.d, A.r, ws.a16, s);
+    }
     hipError_t e = omp_iterations(pl, whole_matrix_panel, y, N, A, k, sel, x, ws, s);
     if (e != hipSuccess || !y_fit)
         return e;
     {
         ProfileScope prof(KC_SELECT, s);
         const OmpWorkspace w = shift_workspace(ws, 0, A.r, k, pl.tiles_m);
-        IterArgs P{y, k, k, sel, x, w, pl.Apick.generated ? nullptr : pl.Apick.At, 0};
+        IterArgs P{y, k, k, sel, x, w, pl.Apick.generated ? nullptr : pl.Apick.At, 0, 0};
         refit_kernel<<<dim3((unsigned)N), REFIT_THREADS, 2 * sizeof(double) * (size_t)k, s>>>(P, y_fit, z, A.r);
     }
     return hipGetLastError();

@@ -39,6 +39,10 @@ struct OmpWorkspace {
     double *xs;        // [2][N][k] least-squares solution: iteration j reads half (j+1)&1, writes half j&1
     int64_t xs_half;   // elements between the two halves of xs
     float *res32;      // [N][r] residual rounded to float (operand of the contraction)
+    uint16_t *res16;   // the same memory holding the residuals split in bfloat16 pairs (screening
+                       // contraction; [N] rows of 4 r bytes, format in omp.hip)
+    uint16_t *a16;     // [a16_rows] rows of At split the same way
+    int32_t a16_rows;  // d (padded to whole tiles) if the matrix fits, else the panel's rows
     float *cols;       // [N][k][r] selected columns of A
     uint64_t *partial; // [N][tiles_m][2] best and second-best packed (score, position) per tile
     uint32_t *bitmap;  // [N][words] selected positions

@@ -51,11 +51,11 @@ def run_omp(Y, A, k):
 
 
 @pytest.mark.parametrize("N,d,r,k", [
-    (1, 100, 16, 4),         # one ragged tile
-    (5, 1000, 96, 12),       # ragged positions, three depth steps
+    (1, 100, 32, 4),         # one ragged tile, one stage
+    (5, 1000, 96, 12),       # ragged positions, three stages (odd count)
     (2, 4096, 256, 32),      # cfg1 shape
     (130, 700, 64, 8),       # two tiles of right-hand sides, ragged
-    (3, 2000, 100, 10),      # depth not a multiple of the stage
+    (3, 2000, 100, 10),      # depth not a multiple of 32: the float contraction is used instead
     (128, 1024, 256, 8),     # full tiles
 ])
 def test_screened_recovery_matches_oracle(N, d, r, k):
