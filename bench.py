@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--screen-bf16", action="store_true",
                     help="screen the correlation contraction on the bfloat16 matrix cores (split operands, three "
                          "products); candidates are re-scored in double either way")
+    ap.add_argument("--no-variants", action="store_true",
+                    help="skip the short extra runs of the optional variants reported under \"variants\"")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (reference for the rocprofv3 FETCH_SIZE / "
@@ -108,9 +110,9 @@ def main():
         buf.v.zero_()
         Wt.copy_(W0)
 
-    def run(n):
+    def run(n, shared=None):
         for t in range(1, n + 1):
-            sgc.step(grads[t - 1], Wt, buf, A, t, h, shared_support=args.shared_support)
+            sgc.step(grads[t - 1], Wt, buf, A, t, h, shared_support=args.shared_support if shared is None else shared)
 
     run(Wm)
     torch.cuda.synchronize()
@@ -180,6 +182,26 @@ def main():
         "gram_build_ms": None if gram_ms is None else round(gram_ms, 2),
         "kernels": kernels,
     }
+
+    # ---- the optional variants of the recovery, three steps each (context, not the headline) ----
+    if not args.no_variants and not (args.shared_support or args.screen_bf16 or args.gram):
+        variants = {}
+        nv = min(3, nsteps)
+        for name, shared, flags in (("shared_support", True, 0),
+                                    ("screen_bf16", False, sgc.MATRIX_FLAG_SCREEN_BF16),
+                                    ("shared_support+screen_bf16", True, sgc.MATRIX_FLAG_SCREEN_BF16)):
+            A.flags = flags
+            reset()
+            run(1, shared)
+            reset()
+            torch.cuda.synchronize()
+            tv = time.perf_counter()
+            run(nv, shared)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - tv) * 1e3 / nv
+            variants[name] = {"ms_per_step": round(ms, 3), "value": round(C * d / (ms * 1e-3), 1), "steps": nv}
+        A.flags = 0
+        out["variants"] = variants
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
