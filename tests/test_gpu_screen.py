@@ -132,3 +132,25 @@ def test_cfg2_full_size_screened_two_steps_sampled():
     for n, j in [(0, 0), (64, 17), (31, 255)]:
         rep = orc.omp(hat[n], At, j + 1, norm=norm, forced=sel[n, :j])
         assert rep["sel"][j] == sel[n, j]
+
+
+def test_all_options_together_screen_gram_shared_support():
+    """Screening contraction + Gram table + shared support over consecutive steps, stage-wise
+    against the oracle on the GPU's own moments."""
+    w = synth.shrink(synth.CFG2, C=3, d=4096, r=256, k=32)
+    A, At = make_matrix(w.matrix, w.a_seed, w.d, w.r)
+    A.gram = torch.empty((w.d, w.d), dtype=torch.float64, device=DEV)
+    sgc.sgc_matrix_gram(A, A.gram)
+    buf = sgc.StepBuffers(w.C, w.d, w.r, w.k)
+    W = dev(synth.weights(w))
+    h = sgc.hyper()
+    C = w.C
+    for t in range(1, 4):
+        sgc.step(dev(synth.gradients(w, t)), W, buf, A, t, h, shared_support=True)
+        torch.cuda.synchronize()
+        mh, vh = buf.hat[:C].cpu().numpy(), buf.hat[C:].cpu().numpy()
+        rsel, rx, rz = orc.omp_shared(mh, vh, At, w.k)
+        assert np.array_equal(buf.sel[:C].cpu().numpy(), rsel)
+        x, z = buf.x[:C].cpu().numpy(), buf.x[C:].cpu().numpy()
+        for c in range(C):
+            assert relerr(x[c], rx[c]) < TOL and relerr(z[c], rz[c]) < TOL
