@@ -162,7 +162,10 @@ def main():
     # HBM-bound companions (algorithmic bytes / event time)
     bytes_adam = 32.0 * C * r
     bytes_topk = (2.0 if w.grad == "bf16" else 4.0) * C * d + 8.0 * C * k
-    for name, nbytes in (("adam", bytes_adam), ("topk", bytes_topk)):
+    companions = [("adam", bytes_adam), ("topk", bytes_topk)]
+    if w.matrix == "stored" or args.materialize:  # the gather of k rows of At per chunk, and p, q written
+        companions.append(("project", 4.0 * C * k * r + 8.0 * C * k + 8.0 * C * r))
+    for name, nbytes in companions:
         ms, cnt = prof[name]
         if cnt:
             kernels[name]["algorithmic_GBps"] = round(nbytes / (ms / cnt * 1e-3) / 1e9, 2)

@@ -551,7 +551,12 @@ constexpr int CORRP_BM = 256, CORRP_BN = 128;
 // NB = 2: the 256 x 128 tile described above. NB = 1: a 256 x 64 tile for at most 64 right-hand sides
 // (each wavefront 128 x 32, groups of 16 MFMAs; the LDS write and the global load of a staging piece
 // follow the same MFMA of group 2, so the load still leads its use by a whole stage).
-template <int NB>
+// BF16: the screening variant. At and R point to rows in split32 format (see corr_split_kernel: the same
+// 4 r bytes per row, a depth-32 stage of a row is 32 high parts then 32 low parts), so the data movement is
+// the float kernel's; a stage is two groups (16 depths each) of 3 * 8 MFMAs v_mfma_f32_32x32x16_bf16
+// (low*high, high*low, high*high per block), and because a stage is five times shorter the global loads
+// run three stages ahead through two sets of staging registers.
+template <int NB, bool BF16>
 __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, const float *__restrict__ R, int32_t N,
                                                                 const uint32_t *__restrict__ bitmap, int32_t words,
                                                                 uint64_t *__restrict__ partial, int32_t tiles_m)
@@ -583,8 +588,10 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
     const int ldst0 = (tid >> 3) * LD + ((tid & 7) << 2);
     const int nkb = r / BK;
 
-    floatx4 g[LA + LB];
-    floatx4 fa[2][MB], fb[2][NB];
+    constexpr int GS = BF16 ? 2 : 1; // staging register sets
+    constexpr int FH = BF16 ? 2 : 1; // fragment parts (high, low)
+    floatx4 g[GS][LA + LB];
+    floatx4 fa[2][MB][FH], fb[2][NB][FH];
     floatx16 acc[MB][NB];
 #pragma unroll
     for (int a = 0; a < MB; ++a)
@@ -596,29 +603,42 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
     const int ra = (wm * 128 + l32) * LD + lhalf * 4; // fragment read offsets (floats)
     const int rb = 2 * BM * LD + (wn * WN + l32) * LD + lhalf * 4;
 
-    auto gload = [&](int u, int kb) { // staging piece u of stage kb (the last stage again beyond the end)
+    auto gload = [&](int u, int kb, int set = 0) { // staging piece u of stage kb (the last stage again beyond the end)
         const int kk = (kb < nkb ? kb : nkb - 1) * BK;
         if (u < LA)
-            g[u] = *reinterpret_cast<const floatx4 *>(abase + ((int64_t)(32 * u) * r + kk) + lane_off);
+            g[set][u] = *reinterpret_cast<const floatx4 *>(abase + ((int64_t)(32 * u) * r + kk) + lane_off);
         else
-            g[u] = *reinterpret_cast<const floatx4 *>(bbase + kk + rhs_off[u < LA ? 0 : u - LA]);
+            g[set][u] = *reinterpret_cast<const floatx4 *>(bbase + kk + rhs_off[u < LA ? 0 : u - LA]);
     };
-    auto lwrite = [&](int u, int buf) {
+    auto lwrite = [&](int u, int buf, int set = 0) {
         const int off = u < LA ? buf * BM * LD + 32 * u * LD : 2 * BM * LD + buf * BN * LD + 32 * (u - LA) * LD;
-        *reinterpret_cast<floatx4 *>(lds + ldst0 + off) = g[u];
+        *reinterpret_cast<floatx4 *>(lds + ldst0 + off) = g[set][u];
     };
+    // float: ks = 0..3, eight depths each. BF16: ks = 0..1, sixteen depths each, high parts and, 16 floats
+    // (64 bytes) further in the row, low parts.
     auto fread = [&](int which, int op, int buf, int ks) { // op 0..3: block row of At, 4..5: block of R
-        if (op < MB)
-            fa[which][op] = *reinterpret_cast<const floatx4 *>(lds + ra + buf * BM * LD + op * 32 * LD + ks * 8);
-        else
-            fb[which][op - MB] = *reinterpret_cast<const floatx4 *>(lds + rb + buf * BN * LD + (op - MB) * 32 * LD + ks * 8);
+#pragma unroll
+        for (int h = 0; h < FH; ++h) {
+            if (op < MB)
+                fa[which][op][h] =
+                    *reinterpret_cast<const floatx4 *>(lds + ra + buf * BM * LD + op * 32 * LD + ks * 8 + h * 16);
+            else
+                fb[which][op - MB][h] = *reinterpret_cast<const floatx4 *>(lds + rb + buf * BN * LD +
+                                                                           (op - MB) * 32 * LD + ks * 8 + h * 16);
+        }
     };
     auto mfma = [&](int which, int m) { // m = 0..GM-1: depth t of the fragment, then block row a, block column b
         const int t = m / (MB * NB), a = (m % (MB * NB)) / NB, b = m % NB;
-        const floatx4 x4 = fa[which][a], y4 = fb[which][b];
-        const float x = t == 0 ? x4.x : (t == 1 ? x4.y : (t == 2 ? x4.z : x4.w));
-        const float y = t == 0 ? y4.x : (t == 1 ? y4.y : (t == 2 ? y4.z : y4.w));
-        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(x, y, acc[a][b], 0, 0, 0);
+        if constexpr (BF16) { // t = 0: low * high, 1: high * low, 2: high * high
+            const floatx4 x4 = fa[which][a][t == 0 ? FH - 1 : 0], y4 = fb[which][b][t == 1 ? FH - 1 : 0];
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, x4),
+                                                                __builtin_bit_cast(bf16x8, y4), acc[a][b], 0, 0, 0);
+        } else {
+            const floatx4 x4 = fa[which][a][0], y4 = fb[which][b][0];
+            const float x = t == 0 ? x4.x : (t == 1 ? x4.y : (t == 2 ? x4.z : x4.w));
+            const float y = t == 0 ? y4.x : (t == 1 ? y4.y : (t == 2 ? y4.z : y4.w));
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(x, y, acc[a][b], 0, 0, 0);
+        }
     };
 
     // prologue: stage 0 -> LDS, stage 1 -> staging registers, fragments of (stage 0, group 0); the
@@ -639,10 +659,39 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
             msk_s[tid + 256 * u] = mw[u];
     }
     static_for<0, LA + LB>([&](auto uc) { lwrite(decltype(uc)::value, 0); });
-    static_for<0, LA + LB>([&](auto uc) { gload(decltype(uc)::value, 1); });
+    static_for<0, LA + LB>([&](auto uc) { gload(decltype(uc)::value, 1, GS - 1); });
+    if constexpr (BF16)
+        static_for<0, LA + LB>([&](auto uc) { gload(decltype(uc)::value, 2, 0); });
     __syncthreads();
     static_for<0, MB + NB>([&](auto oc) { fread(0, decltype(oc)::value, 0, 0); });
 
+    // BF16 stage kb (LDS buffer buf = kb & 1): stage kb + 1 waits in staging set buf ^ 1, stage kb + 2 in
+    // set buf. Group 0 (first 16 depths, fragments read in the previous stage) reads the fragments of
+    // group 1 and copies set buf ^ 1 into the other LDS buffer; barrier; group 1 reads the first
+    // fragments of stage kb + 1 and refills set buf ^ 1 with stage kb + 3.
+    auto stage_bf16 = [&](int kb, auto bufc) {
+        constexpr int buf = decltype(bufc)::value;
+        constexpr int G3 = 3 * MB * NB;
+        static_for<0, G3>([&](auto mc) {
+            constexpr int m = decltype(mc)::value;
+            mfma(0, m);
+            if constexpr (m < MB + NB)
+                fread(1, m, buf, 1);
+            else if constexpr (m < MB + NB + LA + LB)
+                lwrite(m - (MB + NB), buf ^ 1, (buf ^ 1) & (GS - 1));
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        __syncthreads();
+        static_for<0, G3>([&](auto mc) {
+            constexpr int m = decltype(mc)::value;
+            mfma(1, m);
+            if constexpr (m < MB + NB)
+                fread(0, m, buf ^ 1, 0);
+            else if constexpr (m < MB + NB + LA + LB)
+                gload(m - (MB + NB), kb + 3, (buf ^ 1) & (GS - 1));
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
     auto stage = [&](int kb, auto bufc) {
         constexpr int buf = decltype(bufc)::value;
         static_for<0, GM>([&](auto mc) {
@@ -685,8 +734,13 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
         });
     };
     for (int kb = 0; kb < nkb; kb += 2) {
-        stage(kb, std::integral_constant<int, 0>{});
-        stage(kb + 1, std::integral_constant<int, 1>{});
+        if constexpr (BF16) {
+            stage_bf16(kb, std::integral_constant<int, 0>{});
+            stage_bf16(kb + 1, std::integral_constant<int, 1>{});
+        } else {
+            stage(kb, std::integral_constant<int, 0>{});
+            stage(kb + 1, std::integral_constant<int, 1>{});
+        }
     }
     __syncthreads();
 
@@ -787,7 +841,7 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
     }
 }
 
-template <int NB>
+template <int NB, bool BF16 = false>
 static hipError_t corr_pipelined_launch_nb(const MatrixView &A, int32_t rows, const float *R, int32_t N,
                                            const OmpWorkspace &ws, int32_t tiles_m, hipStream_t s)
 {
@@ -796,14 +850,14 @@ static hipError_t corr_pipelined_launch_nb(const MatrixView &A, int32_t rows, co
                             (size_t)BN * (CORRP_BM / 32) * sizeof(uint32_t);
     static bool raised = false;
     if (!raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_pipelined_kernel<NB>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_pipelined_kernel<NB, BF16>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess)
             return e;
         raised = true;
     }
     const dim3 grid((unsigned)(rows / CORRP_BM), (unsigned)((N + BN - 1) / BN));
-    corr_pipelined_kernel<NB><<<grid, 256, smem, s>>>(A, R, N, ws.bitmap, ws.words, ws.partial, tiles_m);
+    corr_pipelined_kernel<NB, BF16><<<grid, 256, smem, s>>>(A, R, N, ws.bitmap, ws.words, ws.partial, tiles_m);
     return hipSuccess;
 }
 
@@ -813,6 +867,17 @@ static hipError_t corr_pipelined_launch(const MatrixView &A, int32_t rows, const
     if (N <= 64)
         return corr_pipelined_launch_nb<1>(A, rows, R, N, ws, tiles_m, s);
     return corr_pipelined_launch_nb<2>(A, rows, R, N, ws, tiles_m, s);
+}
+
+// the split rows through the pipelined kernel: its data movement reads them as rows of r floats
+static hipError_t corr_screen_launch(bool pipelined, const MatrixView &A, const uint16_t *rows_split, int32_t rows,
+                                     int32_t N, const OmpWorkspace &ws, int32_t tiles_m, hipStream_t s)
+{
+    if (!pipelined)
+        return corr_split_launch(A, rows_split, rows, N, ws, tiles_m, s);
+    MatrixView As = A;
+    As.At = reinterpret_cast<const float *>(rows_split);
+    return corr_pipelined_launch_nb<2, true>(As, rows, reinterpret_cast<const float *>(ws.res16), N, ws, tiles_m, s);
 }
 
 // whether the pipelined kernel covers this problem (full tiles of positions, stored rows, even number
@@ -1403,7 +1468,8 @@ __global__ __launch_bounds__(REFIT_THREADS) void refit_kernel(IterArgs P, const 
 struct OmpPlan {
     bool panels;     // generated A produced into ws.panel and consumed from there
     bool pipelined;  // full tiles of stored rows: corr_pipelined_kernel
-    bool screen;     // resident rows that fit ws.a16 and the matrix asks for it: corr_split_kernel
+    bool screen;     // resident rows that fit ws.a16 and the matrix asks for it: corr_split_kernel, or
+    bool screen_pipelined; // on full tiles the bfloat16 form of corr_pipelined_kernel
     int32_t tiles_m; // position tiles of the contraction in use (stride of ws.partial)
     MatrixView Apick; // the view pick_kernel fetches columns from
     size_t pick_smem, factor_smem;
@@ -1453,7 +1519,7 @@ static hipError_t omp_contraction(const OmpPlan &pl, const MatrixView &A, int32_
                 const bool whole = w.panel_rows >= A.d;
                 if (!whole)
                     launch_split_rows(w.panel, rows, A.r, w.a16, s);
-                e = corr_split_launch(Ap, w.a16, rows, Ng, w, pl.tiles_m, s);
+                e = corr_screen_launch(pl.screen_pipelined, Ap, w.a16, rows, Ng, w, pl.tiles_m, s);
             } else {
                 e = pl.pipelined ? corr_pipelined_launch(Ap, rows, w.res32, Ng, w, pl.tiles_m, s)
                                  : corr_dispatch<false>(Ap, rows, w.res32, Ng, w, pl.tiles_m, s);
@@ -1462,7 +1528,7 @@ static hipError_t omp_contraction(const OmpPlan &pl, const MatrixView &A, int32_
     } else if (A.generated) {
         e = corr_dispatch<true>(A, A.d, w.res32, Ng, w, pl.tiles_m, s);
     } else {
-        e = pl.screen      ? corr_split_launch(A, w.a16, A.d, Ng, w, pl.tiles_m, s)
+        e = pl.screen      ? corr_screen_launch(pl.screen_pipelined, A, w.a16, A.d, Ng, w, pl.tiles_m, s)
             : pl.pipelined ? corr_pipelined_launch(A, A.d, w.res32, Ng, w, pl.tiles_m, s)
                            : corr_dispatch<false>(A, A.d, w.res32, Ng, w, pl.tiles_m, s);
     }
@@ -1540,9 +1606,10 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
     // contraction keeps the float kernel (its time is the generator's anyway)
     pl.screen = (A.flags & SGC_MATRIX_FLAG_SCREEN_BF16) && A.r % 32 == 0 &&
                 (A.generated ? pl.panels : ws.a16_rows >= A.d);
+    pl.screen_pipelined = pl.screen && N > 64 && corr_pipelined_ok(A, N, ws.panel_rows);
     if (pl.screen)
         pl.pipelined = false;
-    pl.tiles_m = pl.pipelined ? A.d / CORRP_BM : corr_tiles_m(A.d);
+    pl.tiles_m = pl.pipelined || pl.screen_pipelined ? A.d / CORRP_BM : corr_tiles_m(A.d);
     pl.pick_smem = ((size_t)A.r * 4 + 15) & ~(size_t)15;
     pl.factor_smem = 3 * sizeof(double) * (size_t)k;
     {

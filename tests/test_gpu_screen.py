@@ -56,7 +56,9 @@ def run_omp(Y, A, k):
     (2, 4096, 256, 32),      # cfg1 shape
     (130, 700, 64, 8),       # two tiles of right-hand sides, ragged
     (3, 2000, 100, 10),      # depth not a multiple of 32: the float contraction is used instead
-    (128, 1024, 256, 8),     # full tiles
+    (128, 1024, 256, 8),     # full tiles: the pipelined form of the screening contraction
+    (200, 768, 128, 6),      # the same with a ragged second tile of right-hand sides
+    (65, 512, 64, 5),        # ... and its shortest depth loop (two stages)
 ])
 def test_screened_recovery_matches_oracle(N, d, r, k):
     say("screen", N, d, r, k)
@@ -77,8 +79,9 @@ def test_screened_recovery_matches_oracle(N, d, r, k):
     assert np.array_equal(x.view(np.uint32), x2.view(np.uint32))   # the least squares never sees the contraction
 
 
-def test_screened_recovery_generated_matrix_many_right_hand_sides():
-    N, d, r, k = 600, 3000, 64, 6
+@pytest.mark.parametrize("d", [3000, 3072], ids=["ragged", "full_tiles"])
+def test_screened_recovery_generated_matrix_many_right_hand_sides(d):
+    N, r, k = 600, 64, 6
     rng = np.random.default_rng(N + d)
     A, At = make_matrix("philox", 33, d, r)
     Y = rng.standard_normal((N, r)).astype(np.float32)
