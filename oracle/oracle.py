@@ -221,6 +221,53 @@ def apply(W, d, sel_m, x_m, sel_v, x_v, alpha=1.0, eps=1e-8, lr=1e-3):
     return W
 
 
+def outer_project(B, G):
+    """Gc = B G (CESGC, Sec. 4.4). B: [rho, m], G: [m, n] -> [rho, n]."""
+    B = _c(B, np.float32)
+    G = _c(G, np.float32)
+    rho, m = B.shape
+    assert G.shape[0] == m
+    n = G.shape[1]
+    out = np.empty((rho, n), np.float32)
+    rc = lib().oracle_outer_project(_p(B, ctypes.c_float), _p(G, ctypes.c_float), rho, m, n, _p(out, ctypes.c_float))
+    if rc:
+        raise ValueError("oracle_outer_project rc=%d" % rc)
+    return out
+
+
+def outer_apply(W, B, d, sel_m, x_m, sel_v, x_v, alpha=1.0, eps=1e-8, lr=1e-3):
+    """W <- W - lr * B^T N with N the update of SGC in the compressed space (CESGC, Sec. 4.4).
+    W: [m, n]; the chunks are the row-major rho x n compressed gradient cut in pieces of d."""
+    W = np.array(W, np.float32, copy=True, order="C")
+    B = _c(B, np.float32)
+    sel_m = _c(sel_m, np.int32)
+    sel_v = _c(sel_v, np.int32)
+    x_m = _c(x_m, np.float32)
+    x_v = _c(x_v, np.float32)
+    rho, m = B.shape
+    n = W.shape[1]
+    C, k = sel_m.shape
+    assert W.shape[0] == m and C * d == rho * n
+    rc = lib().oracle_outer_apply(_p(W, ctypes.c_float), _p(B, ctypes.c_float), rho, m, n, d, k, _p(sel_m, ctypes.c_int32), _p(x_m, ctypes.c_float), _p(sel_v, ctypes.c_int32), _p(x_v, ctypes.c_float), ctypes.c_double(alpha), ctypes.c_double(eps), ctypes.c_double(lr))
+    if rc:
+        raise ValueError("oracle_outer_apply rc=%d" % rc)
+    return W
+
+
+def step_cesgc(G, W, B, m, v, t, At, d, k, beta1=0.9, beta2=0.999, eps=1e-8, lr=1e-3, alpha=1.0):
+    """One CESGC step (Sec. 4.4) on one weight matrix: compress with B, run Alg. 2 on the chunks of
+    the compressed gradient, take the update back with B^T. m, v: [C, r] with C = rho*n/d."""
+    Gc = outer_project(B, G)
+    C = Gc.size // d
+    idx, val = topk(Gc.reshape(C, d), k)
+    p, q = project(idx, val, At)
+    m2, v2, mh, vh = adam(p, q, m, v, t, beta1, beta2)
+    Y = np.concatenate([mh.reshape(C, -1), vh.reshape(C, -1)], axis=0)
+    sel, x = omp_batch(Y, At, k)
+    W2 = outer_apply(W, B, d, sel[:C], x[:C], sel[C:], x[C:], alpha, eps, lr)
+    return dict(Gc=Gc, idx=idx, val=val, p=p, q=q, m=m2, v=v2, mhat=mh, vhat=vh, sel_m=sel[:C], x_m=x[:C], sel_v=sel[C:], x_v=x[C:], W=W2)
+
+
 def step(g, W, m, v, t, At, k, beta1=0.9, beta2=0.999, eps=1e-8, lr=1e-3, alpha=1.0, shared_support=False,
          At_new=None):
     """One full SGC step (Alg. 2 + the weight update) on C chunks. g: [C, d].

@@ -22,7 +22,10 @@
  * support search and least-squares identities for OMP; a library least-squares
  * routine and exact joint recovery for the shared-support fit; a dense mat-vec
  * and the eq. 10 invariant across a change of matrix for the re-projection; the
- * closed form of the first full step in the exact-recovery regime.
+ * closed form of the first full step in the exact-recovery regime; for the
+ * outer projection of CESGC a hand-worked example, a library matrix product,
+ * the identity projection (which must reproduce the plain update) and the
+ * projector identities of a matrix with orthonormal rows.
  */
 #include <math.h>
 #include <stdint.h>
@@ -624,4 +627,77 @@ int oracle_apply(float *W, int64_t C, int32_t d, int32_t k, const int32_t *sel_m
     free(xd);
     free(zd);
     return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* CESGC (Sec. 4.4): the gradient of an m x n weight matrix is first compressed */
+/* with a projection B (rho x m, in the paper the leading left singular vectors */
+/* of the gradient, refreshed every fixed number of steps and an input here):   */
+/* Gc = B G (rho x n). SGC then runs on Gc, read row-major as rho*n/d chunks of  */
+/* d entries.                                                                    */
+/* ------------------------------------------------------------------------ */
+int oracle_outer_project(const float *B, const float *G, int32_t rho, int32_t m, int32_t n, float *Gc)
+{
+    if (rho <= 0 || m <= 0 || n <= 0)
+        return -1;
+    for (int32_t a = 0; a < rho; ++a)
+        for (int32_t j = 0; j < n; ++j) {
+            double s = 0.0;
+            for (int32_t i = 0; i < m; ++i)
+                s += (double)B[(int64_t)a * m + i] * (double)G[(int64_t)i * n + j];
+            Gc[(int64_t)a * n + j] = (float)s;
+        }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* CESGC update (Sec. 4.4, the last equation of the paragraph): the update N of */
+/* SGC lives in the compressed space (rho x n, built from the two recovered      */
+/* sparse vectors of every chunk exactly as in the plain update above) and is    */
+/* taken back with the transpose of B: W <- W - lr * B^T N.                      */
+/* ------------------------------------------------------------------------ */
+int oracle_outer_apply(float *W, const float *B, int32_t rho, int32_t m, int32_t n, int32_t d, int32_t k,
+                       const int32_t *sel_m, const float *x_m, const int32_t *sel_v, const float *x_v,
+                       double alpha, double eps, double lr)
+{
+    const int64_t total = (int64_t)rho * n;
+    if (rho <= 0 || m <= 0 || n <= 0 || d <= 0 || total % d != 0)
+        return -1;
+    const int64_t C = total / d;
+    double *N = (double *)calloc((size_t)total, sizeof(double));
+    double *xd = (double *)malloc(sizeof(double) * (size_t)d);
+    double *zd = (double *)malloc(sizeof(double) * (size_t)d);
+    int rc = 0;
+    for (int64_t c = 0; c < C && rc == 0; ++c) {
+        for (int32_t i = 0; i < d; ++i) {
+            xd[i] = 0.0;
+            zd[i] = 0.0;
+        }
+        for (int32_t t = 0; t < k; ++t) {
+            int32_t im = sel_m[c * k + t], iv = sel_v[c * k + t];
+            if (im < 0 || im >= d || iv < 0 || iv >= d) {
+                rc = -1;
+                break;
+            }
+            xd[im] = (double)x_m[c * k + t];
+            zd[iv] = (double)x_v[c * k + t];
+        }
+        for (int32_t i = 0; i < d && rc == 0; ++i) {
+            if (xd[i] == 0.0)
+                continue;
+            double z = zd[i] > 0.0 ? zd[i] : 0.0;
+            N[c * (int64_t)d + i] = alpha * xd[i] / (sqrt(z) + eps);
+        }
+    }
+    for (int32_t i = 0; i < m && rc == 0; ++i)
+        for (int32_t j = 0; j < n; ++j) {
+            double s = 0.0;
+            for (int32_t a = 0; a < rho; ++a)
+                s += (double)B[(int64_t)a * m + i] * N[(int64_t)a * n + j];
+            W[(int64_t)i * n + j] = (float)((double)W[(int64_t)i * n + j] - lr * s);
+        }
+    free(N);
+    free(xd);
+    free(zd);
+    return rc;
 }

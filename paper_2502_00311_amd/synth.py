@@ -125,3 +125,26 @@ def sparse_signal(seed, d, k, lo=0.5, hi=2.0):
     x = np.zeros(d, np.float64)
     x[pos] = mag
     return x, pos
+
+
+def orthonormal_rows(seed, rho, m):
+    """B [rho, m] float32 with orthonormal rows: the Q factor of a Gaussian matrix (an input of the
+    CESGC tests; in the paper B holds leading singular vectors of a gradient, Sec. 4.4)."""
+    g = _rng(555, seed)
+    q, _ = np.linalg.qr(g.standard_normal((m, rho)))
+    return np.ascontiguousarray(q.T.astype(np.float32))
+
+
+def matrix_gradient(seed, step, m, n, basis, decay=0.7, noise=0.02):
+    """Gradient of an m x n weight matrix for the CESGC workload: a fixed column space (`basis`,
+    [R, m] with orthonormal rows, e.g. orthonormal_rows) with geometrically decaying strengths and
+    heavy-tailed coefficients that change every step, plus dense Student-t noise. The first rows
+    of `basis` are, by construction, the leading left singular directions a truncated SVD of the
+    gradient would return, so they serve as the projection B without running an SVD here."""
+    g = _rng(556, seed, step)
+    R = basis.shape[0]
+    strength = (decay ** np.arange(R)).astype(np.float32)
+    coeff = g.standard_t(3.0, size=(R, n)).astype(np.float32) * strength[:, None]
+    out = basis.T.astype(np.float32) @ coeff
+    out += np.float32(noise) * g.standard_t(3.0, size=(m, n)).astype(np.float32)
+    return np.ascontiguousarray(out * np.float32(1e-3))

@@ -464,3 +464,92 @@ def test_sgca_keeps_the_moments_aligned_with_the_new_matrix(shared):
             assert np.abs(out["m"][c] - A64 @ Md[c]).max() < 2e-5 * np.abs(A64 @ Md[c]).max(), t
             assert np.abs(out["v"][c] - A64 @ Vd[c]).max() < 2e-5 * np.abs(A64 @ Vd[c]).max(), t
         m, v, W = out["m"], out["v"], out["W"]
+
+
+# --------------------------------------------------------------------------- CESGC outer projection
+def test_outer_projection_by_hand():
+    # Sec. 4.4: Gc = B G; update W - lr B^T N. One row B = (0.6, 0.8), G = [[1, 2], [3, 4]].
+    B = np.array([[0.6, 0.8]], np.float32)
+    G = np.array([[1.0, 2.0], [3.0, 4.0]], np.float32)
+    Gc = orc.outer_project(B, G)
+    assert np.allclose(Gc, [[0.6 + 2.4, 1.2 + 3.2]], rtol=1e-6)
+    # one chunk of d = 2, k = 1: x = 2 at position 1, z = 4 there: N = (0, 1 * 2 / (2 + 0.5)) = (0, 0.8)
+    W = np.array([[10.0, 20.0], [30.0, 40.0]], np.float32)
+    out = orc.outer_apply(W, B, 2, np.array([[1]], np.int32), np.array([[2.0]], np.float32),
+                          np.array([[1]], np.int32), np.array([[4.0]], np.float32), alpha=1.0, eps=0.5, lr=0.5)
+    assert np.allclose(out, [[10.0, 20.0 - 0.5 * 0.6 * 0.8], [30.0, 40.0 - 0.5 * 0.8 * 0.8]], rtol=1e-6)
+
+
+def test_outer_projection_equals_the_library_product():
+    rng = np.random.default_rng(3)
+    rho, m, n = 5, 37, 24          # all different: a transposed operand or a swapped size fails
+    B = rng.standard_normal((rho, m)).astype(np.float32)
+    G = rng.standard_normal((m, n)).astype(np.float32)
+    ref = B.astype(np.float64) @ G.astype(np.float64)
+    assert np.abs(orc.outer_project(B, G) - ref).max() < 1e-6 * np.abs(ref).max()
+    # back-projection: d = 8 -> 15 chunks of the 5 x 24 compressed space, k = 2
+    d, k = 8, 2
+    C = rho * n // d
+    sel_m = np.stack([rng.permutation(d)[:k] for _ in range(C)]).astype(np.int32)
+    sel_v = sel_m[:, ::-1].copy()
+    x = rng.standard_normal((C, k)).astype(np.float32)
+    z = np.abs(rng.standard_normal((C, k))).astype(np.float32) + 0.1
+    W = rng.standard_normal((m, n)).astype(np.float32)
+    out = orc.outer_apply(W, B, d, sel_m, x, sel_v, z, alpha=2.0, eps=1e-3, lr=0.01)
+    N = np.zeros((C, d))
+    for c in range(C):
+        zz = dict(zip(sel_v[c].tolist(), z[c].astype(np.float64)))
+        for t in range(k):
+            N[c, sel_m[c, t]] = 2.0 * float(x[c, t]) / (np.sqrt(zz[int(sel_m[c, t])]) + 1e-3)
+    ref = W.astype(np.float64) - 0.01 * B.astype(np.float64).T @ N.reshape(rho, n)
+    assert np.abs(out - ref).max() < 1e-6 * np.abs(ref).max()
+
+
+def test_identity_outer_projection_is_the_plain_sgc_step():
+    """B = I (rho = m): CESGC is SGC on the gradient read row-major."""
+    w = synth.shrink(synth.CFG1, C=4, d=512, r=128, k=6)
+    m_rows, n = 8, 256                                  # 8 x 256 weights = 4 chunks of 512
+    g = synth.gradients(w, 1)
+    At = synth.gaussian_matrix(1, w.d, w.r)
+    W0 = synth.weights(w)
+    z = np.zeros((w.C, w.r), np.float32)
+    plain = orc.step(g, W0, z, z, 1, At, w.k, alpha=2.0)
+    eye = np.eye(m_rows, dtype=np.float32)
+    ces = orc.step_cesgc(g.reshape(m_rows, n), W0.reshape(m_rows, n), eye, z, z, 1, At, w.d, w.k, alpha=2.0)
+    assert np.array_equal(ces["Gc"].ravel(), g.ravel())
+    assert np.array_equal(ces["sel_m"], plain["sel_m"]) and np.array_equal(ces["x_v"], plain["x_v"])
+    assert np.array_equal(ces["W"].ravel(), plain["W"].ravel())
+
+
+def test_outer_projection_with_orthonormal_rows():
+    """B B^T = I: compressing a gradient that lies in the row space of B loses nothing, and the
+    weight change, compressed again, is the update N itself."""
+    rho, m, n, d, k = 4, 64, 32, 16, 3
+    B = synth.orthonormal_rows(0, rho, m)
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((rho, n)).astype(np.float32)
+    G = (B.astype(np.float64).T @ X).astype(np.float32)
+    assert np.abs(orc.outer_project(B, G) - X).max() < 1e-6
+    C = rho * n // d
+    sel = np.stack([rng.permutation(d)[:k] for _ in range(C)]).astype(np.int32)
+    x = rng.standard_normal((C, k)).astype(np.float32)
+    zv = np.ones((C, k), np.float32)
+    W = np.zeros((m, n), np.float32)
+    out = orc.outer_apply(W, B, d, sel, x, sel, zv, alpha=1.0, eps=0.0, lr=1.0)
+    N = np.zeros((C, d))
+    for c in range(C):
+        N[c, sel[c]] = x[c]
+    back = B.astype(np.float64) @ (-out.astype(np.float64))
+    assert np.abs(back - N.reshape(rho, n)).max() < 1e-6
+
+
+def test_synthetic_matrix_gradient_has_the_given_leading_directions():
+    """The input recipe of the CESGC workload: the first rows of the basis span what a truncated SVD
+    of the gradient returns (checked against the library SVD on a small case)."""
+    m, n, rho = 96, 128, 4
+    basis = synth.orthonormal_rows(2, 12, m)
+    G = synth.matrix_gradient(2, 1, m, n, basis)
+    U = np.linalg.svd(G.astype(np.float64), full_matrices=False)[0][:, :rho]
+    P_svd = U @ U.T
+    P_b = basis[:rho].astype(np.float64).T @ basis[:rho].astype(np.float64)
+    assert np.abs(P_svd - P_b).max() < 0.15
