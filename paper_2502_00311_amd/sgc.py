@@ -21,10 +21,11 @@ MATRIX_FLAG_SCREEN_BF16 = 1
 EXPORTS = [
     "sgc_status_string", "sgc_matrix_fill", "sgc_matrix_colnorms", "sgc_matrix_gram", "sgc_sparsify_project",
     "sgc_adam_compressed", "sgc_omp_workspace_bytes", "sgc_recover_omp", "sgc_recover_omp_shared", "sgc_reproject",
-    "sgc_apply",
+    "sgc_apply", "sgc_outer_workspace_bytes", "sgc_outer_project", "sgc_outer_apply",
     "sgc_profile_enable", "sgc_profile_read",
 ]
-PROFILE_CLASSES = ["topk", "project", "adam", "omp_corr", "omp_select_update", "apply", "other", "omp_matrix_fill"]
+PROFILE_CLASSES = ["topk", "project", "adam", "omp_corr", "omp_select_update", "apply", "other", "omp_matrix_fill",
+                   "outer"]
 
 
 class sgc_matrix(ctypes.Structure):
@@ -41,7 +42,7 @@ class sgc_hyper(ctypes.Structure):
 
 
 class sgc_profile(ctypes.Structure):
-    _fields_ = [("ms", ctypes.c_double * 8), ("launches", ctypes.c_int64 * 8)]
+    _fields_ = [("ms", ctypes.c_double * 9), ("launches", ctypes.c_int64 * 9)]
 
 
 class SgcError(RuntimeError):
@@ -83,6 +84,12 @@ def lib():
         L.sgc_reproject.argtypes = [vp, vp, i64, i32, ctypes.POINTER(sgc_matrix), ctypes.c_double, vp, vp]
         L.sgc_apply.restype = i32
         L.sgc_apply.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, ctypes.POINTER(sgc_hyper), vp]
+        L.sgc_outer_workspace_bytes.restype = sz
+        L.sgc_outer_workspace_bytes.argtypes = [i32, i32, i32]
+        L.sgc_outer_project.restype = i32
+        L.sgc_outer_project.argtypes = [vp, vp, i32, i32, i32, vp, vp, sz, vp]
+        L.sgc_outer_apply.restype = i32
+        L.sgc_outer_apply.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, ctypes.POINTER(sgc_hyper), vp, sz, vp]
         L.sgc_profile_enable.restype = i32
         L.sgc_profile_enable.argtypes = [i32]
         L.sgc_profile_read.restype = i32
@@ -173,6 +180,18 @@ def sgc_apply(W, C, d, k, sel_m, x_m, sel_v, x_v, h, stream=None):
     _check(lib().sgc_apply(_ptr(W), C, d, k, _ptr(sel_m), _ptr(x_m), _ptr(sel_v), _ptr(x_v), ctypes.byref(h), _stream(stream)), "sgc_apply")
 
 
+def sgc_outer_workspace_bytes(rho, m, n):
+    return int(lib().sgc_outer_workspace_bytes(rho, m, n))
+
+
+def sgc_outer_project(B, G, rho, m, n, Gc, ws, stream=None):
+    _check(lib().sgc_outer_project(_ptr(B), _ptr(G), rho, m, n, _ptr(Gc), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_outer_project")
+
+
+def sgc_outer_apply(W, B, rho, m, n, d, k, sel_m, x_m, sel_v, x_v, h, ws, stream=None):
+    _check(lib().sgc_outer_apply(_ptr(W), _ptr(B), rho, m, n, d, k, _ptr(sel_m), _ptr(x_m), _ptr(sel_v), _ptr(x_v), ctypes.byref(h), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_outer_apply")
+
+
 def sgc_profile_enable(on):
     _check(lib().sgc_profile_enable(1 if on else 0), "sgc_profile_enable")
 
@@ -226,3 +245,27 @@ def step(grad, W, buf, A, t, h, stream=None, shared_support=False, A_new=None):
     if A_new is not None:
         sgc_reproject(buf.sel[:C], buf.x[:C], C, k, A_new, 1.0 - h.beta1 ** t, buf.m, stream)
         sgc_reproject(buf.sel[C:], buf.x[C:], C, k, A_new, 1.0 - h.beta2 ** t, buf.v, stream)
+
+
+class OuterBuffers:
+    """Device buffers of the outer projection of CESGC for one m x n weight matrix (allocation only)."""
+
+    def __init__(self, rho, m, n, device="cuda"):
+        self.rho, self.m, self.n = rho, m, n
+        self.Gc = torch.empty((rho, n), dtype=torch.float32, device=device)
+        nbytes = sgc_outer_workspace_bytes(rho, m, n)
+        if nbytes == 0:
+            raise SgcError(ERR_SHAPE, "sgc_outer_workspace_bytes")
+        self.ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def step_cesgc(G, W, B, obuf, buf, A, t, h, stream=None):
+    """One CESGC step (Sec. 4.4) on one weight matrix: Gc = B G, Alg. 2 on the chunks of Gc, then
+    W <- W - lr B^T N. buf: StepBuffers for rho*n/d chunks."""
+    rho, m, n = obuf.rho, obuf.m, obuf.n
+    C, d, r, k = buf.C, buf.d, buf.r, buf.k
+    sgc_outer_project(B, G, rho, m, n, obuf.Gc, obuf.ws, stream)
+    sgc_sparsify_project(obuf.Gc, C * d, d, k, A, buf.idx, buf.val, buf.p, buf.q, stream)
+    sgc_adam_compressed(buf.p, buf.q, buf.m, buf.v, buf.hat[:C], buf.hat[C:], C * r, t, h, stream)
+    sgc_recover_omp(buf.hat, 2 * C, A, k, buf.sel, buf.x, buf.ws, stream)
+    sgc_outer_apply(W, B, rho, m, n, d, k, buf.sel[:C], buf.x[:C], buf.sel[C:], buf.x[C:], h, obuf.ws, stream)

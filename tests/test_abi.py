@@ -170,3 +170,35 @@ def test_gram_rejects_bad_arguments():
     assert L.sgc_matrix_gram(ctypes.byref(big), FAKE, None) == sgc.ERR_SHAPE
     bad = mat(r=18)
     assert L.sgc_matrix_gram(ctypes.byref(bad), FAKE, None) == sgc.ERR_SHAPE
+
+
+def test_outer_projection_rejects_bad_arguments_and_sizes_workspace():
+    L = sgc.lib()
+    nbytes = sgc.sgc_outer_workspace_bytes(32, 4096, 4096)
+    assert nbytes >= 32 * 4096 * 4 and nbytes % 256 == 0
+    assert sgc.sgc_outer_workspace_bytes(0, 8, 8) == 0
+    assert sgc.sgc_outer_workspace_bytes(4, 8, 6) == 0          # n % 4
+    assert sgc.sgc_outer_workspace_bytes(4, 8, 1 << 23) == 0
+    small = sgc.sgc_outer_workspace_bytes(4, 8, 8)
+    p = L.sgc_outer_project
+    assert p(None, FAKE, 4, 8, 8, FAKE, FAKE, small, None) == sgc.ERR_NULL
+    assert p(FAKE, FAKE, 4, 8, 8, FAKE, None, small, None) == sgc.ERR_NULL
+    assert p(FAKE, FAKE, 4, 8, 6, FAKE, FAKE, small, None) == sgc.ERR_SHAPE
+    assert p(FAKE, FAKE, 0, 8, 8, FAKE, FAKE, small, None) == sgc.ERR_SHAPE
+    assert p(FAKE, ODD, 4, 8, 8, FAKE, FAKE, small, None) == sgc.ERR_ALIGN
+    assert p(FAKE, FAKE, 4, 8, 8, FAKE, ODD, small, None) == sgc.ERR_ALIGN
+    assert p(FAKE, FAKE, 4, 8, 8, FAKE, FAKE, small - 1, None) == sgc.ERR_WORKSPACE
+    a = L.sgc_outer_apply
+    h = sgc.hyper()
+
+    def call(W=FAKE, B=FAKE, rho=4, m=8, n=8, d=16, k=2, sel=FAKE, hh=ctypes.byref(h), ws=FAKE, nb=small):
+        return a(W, B, rho, m, n, d, k, sel, FAKE, FAKE, FAKE, hh, ws, nb, None)
+
+    assert call(W=None) == sgc.ERR_NULL
+    assert call(sel=None) == sgc.ERR_NULL
+    assert call(hh=None) == sgc.ERR_NULL
+    assert call(d=5) == sgc.ERR_SHAPE           # rho * n not a multiple of d
+    assert call(k=0) == sgc.ERR_SHAPE
+    assert call(k=17) == sgc.ERR_SHAPE          # k > d
+    assert call(W=ODD) == sgc.ERR_ALIGN
+    assert call(nb=small - 1) == sgc.ERR_WORKSPACE
