@@ -238,23 +238,27 @@ sgc_status sgc_apply(float *W, int64_t C, int32_t d, int32_t k, const int32_t *s
  *   the four calls of the plain step on Gc read as rho*n/d chunks of d entries (sgc_apply left out)
  *   sgc_outer_apply         W <- W - lr * B^T N,  N (rho x n) the update of eq. 11 in the compressed
  *                           space: on the support of x, N = alpha x / (sqrt(max(z, 0)) + eps)
+ * Both calls take a batch of `count` equal-sized matrices stored one after the other (one launch for
+ * all of them: a single matrix of a few tens of MB is too little work to fill the memory system):
+ *   B    [count][rho][m], G and W [count][m][n], Gc out [count][rho][n]; n % 4 == 0; G, W, Gc
+ *        16-byte aligned
+ *   sel_m, x_m, sel_v, x_v  [count*rho*n/d][k]: the chunks of the whole batch in order, as returned by
+ *        sgc_recover_omp on [mhat; vhat] of all of them
+ *   ws   at least sgc_outer_workspace_bytes(count, rho, m, n) bytes (0 for invalid sizes), 256-byte
+ *        aligned; holds partial products (project) or N written out densely (apply), and may be
+ *        the same memory for both calls
  * Products are accumulated in float on the matrix cores; the rows of G are summed in slices whose
  * partial results are added in a fixed order, so results are reproducible run to run.
- *   B    [rho][m], G and W [m][n], Gc out [rho][n]; n % 4 == 0; G, W, Gc 16-byte aligned
- *   sel_m, x_m, sel_v, x_v  [rho*n/d][k] as returned by sgc_recover_omp on [mhat; vhat]
- *   ws   at least sgc_outer_workspace_bytes(rho, m, n) bytes (0 for invalid sizes), 256-byte
- *        aligned; holds partial products (project) or N written out densely (apply), and may be
- *        the same memory for both calls and for the recovery in between
- * Errors: NULL, SHAPE (rho, m, n <= 0, rho above 2^20, m or n above 2^22, n % 4, rho*n % d, k <= 0,
- * k > d, k > 4096),
- * ALIGN, WORKSPACE, DEVICE.
+ * Errors: NULL, SHAPE (count, rho, m, n <= 0, rho above 2^20, m or n above 2^22, count * ceil(rho/32)
+ * above 65535, n % 4, rho*n % d, k <= 0, k > d, k > 4096), ALIGN, WORKSPACE, DEVICE.
  */
-size_t sgc_outer_workspace_bytes(int32_t rho, int32_t m, int32_t n);
-sgc_status sgc_outer_project(const float *B, const float *G, int32_t rho, int32_t m, int32_t n, float *Gc,
-                             void *ws, size_t ws_bytes, void *stream);
-sgc_status sgc_outer_apply(float *W, const float *B, int32_t rho, int32_t m, int32_t n, int32_t d, int32_t k,
-                           const int32_t *sel_m, const float *x_m, const int32_t *sel_v, const float *x_v,
-                           const sgc_hyper *h /* host */, void *ws, size_t ws_bytes, void *stream);
+size_t sgc_outer_workspace_bytes(int32_t count, int32_t rho, int32_t m, int32_t n);
+sgc_status sgc_outer_project(const float *B, const float *G, int32_t count, int32_t rho, int32_t m, int32_t n,
+                             float *Gc, void *ws, size_t ws_bytes, void *stream);
+sgc_status sgc_outer_apply(float *W, const float *B, int32_t count, int32_t rho, int32_t m, int32_t n, int32_t d,
+                           int32_t k, const int32_t *sel_m, const float *x_m, const int32_t *sel_v,
+                           const float *x_v, const sgc_hyper *h /* host */, void *ws, size_t ws_bytes,
+                           void *stream);
 
 /*
  * Instrumentation (not a step of the method): per-kernel timing with HIP events recorded on the
@@ -264,10 +268,10 @@ sgc_status sgc_outer_apply(float *W, const float *B, int32_t rho, int32_t m, int
  *   duration in milliseconds and the launch count per kernel class, and clears the collection.
  * Kernel classes: 0 top-k, 1 projection, 2 Adam, 3 OMP correlation contraction, 4 OMP
  * select+update, 5 apply, 6 other (init, matrix helpers), 7 refill of the generated-matrix panel
- * inside the OMP iterations, 8 the outer projection of CESGC (both directions).
+ * inside the OMP iterations, 8 sgc_outer_project, 9 sgc_outer_apply (its scatter of N counts as 5).
  * Not thread-safe; meant for a single measuring thread. Errors: NULL, DEVICE.
  */
-enum { SGC_PROFILE_CLASSES = 9 };
+enum { SGC_PROFILE_CLASSES = 10 };
 typedef struct sgc_profile {
     double ms[SGC_PROFILE_CLASSES];
     int64_t launches[SGC_PROFILE_CLASSES];

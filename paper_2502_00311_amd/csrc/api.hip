@@ -222,48 +222,49 @@ sgc_status sgc_apply(float *W, int64_t C, int32_t d, int32_t k, const int32_t *s
                                  (hipStream_t)stream));
 }
 
-static bool outer_sizes_ok(int32_t rho, int32_t m, int32_t n)
+static bool outer_sizes_ok(int32_t count, int32_t rho, int32_t m, int32_t n)
 {
     const int32_t most = 1 << 22;
-    return rho > 0 && m > 0 && n > 0 && rho <= (1 << 20) && m <= most && n <= most && (n & 3) == 0 &&
-           (int64_t)rho * n <= (1ll << 40);
+    // the batch and the blocks of rows of B share one grid dimension (at most 65535)
+    return count > 0 && rho > 0 && m > 0 && n > 0 && rho <= (1 << 20) && m <= most && n <= most && (n & 3) == 0 &&
+           (int64_t)count * ((rho + 31) / 32) <= 65535 && (int64_t)count * rho * n <= (1ll << 40);
 }
 
-size_t sgc_outer_workspace_bytes(int32_t rho, int32_t m, int32_t n)
+size_t sgc_outer_workspace_bytes(int32_t count, int32_t rho, int32_t m, int32_t n)
 {
-    if (!outer_sizes_ok(rho, m, n))
+    if (!outer_sizes_ok(count, rho, m, n))
         return 0;
-    return outer_plan(rho, m, n).ws_bytes;
+    return outer_plan(count, rho, m, n).ws_bytes;
 }
 
-sgc_status sgc_outer_project(const float *B, const float *G, int32_t rho, int32_t m, int32_t n, float *Gc, void *ws,
-                             size_t ws_bytes, void *stream)
+sgc_status sgc_outer_project(const float *B, const float *G, int32_t count, int32_t rho, int32_t m, int32_t n,
+                             float *Gc, void *ws, size_t ws_bytes, void *stream)
 {
     if (!B || !G || !Gc || !ws)
         return SGC_ERR_NULL;
-    if (!outer_sizes_ok(rho, m, n))
+    if (!outer_sizes_ok(count, rho, m, n))
         return SGC_ERR_SHAPE;
     if (!aligned16(G) || !aligned16(Gc) || ((uintptr_t)ws & 255u))
         return SGC_ERR_ALIGN;
-    if (ws_bytes < outer_plan(rho, m, n).ws_bytes)
+    if (ws_bytes < outer_plan(count, rho, m, n).ws_bytes)
         return SGC_ERR_WORKSPACE;
-    return from_hip(launch_outer_project(B, G, rho, m, n, Gc, ws, (hipStream_t)stream));
+    return from_hip(launch_outer_project(B, G, count, rho, m, n, Gc, ws, (hipStream_t)stream));
 }
 
-sgc_status sgc_outer_apply(float *W, const float *B, int32_t rho, int32_t m, int32_t n, int32_t d, int32_t k,
-                           const int32_t *sel_m, const float *x_m, const int32_t *sel_v, const float *x_v,
+sgc_status sgc_outer_apply(float *W, const float *B, int32_t count, int32_t rho, int32_t m, int32_t n, int32_t d,
+                           int32_t k, const int32_t *sel_m, const float *x_m, const int32_t *sel_v, const float *x_v,
                            const sgc_hyper *h, void *ws, size_t ws_bytes, void *stream)
 {
     if (!W || !B || !sel_m || !x_m || !sel_v || !x_v || !h || !ws)
         return SGC_ERR_NULL;
-    if (!outer_sizes_ok(rho, m, n) || d <= 0 || ((int64_t)rho * n) % d != 0 || k <= 0 || k > d || k > 4096)
+    if (!outer_sizes_ok(count, rho, m, n) || d <= 0 || ((int64_t)rho * n) % d != 0 || k <= 0 || k > d || k > 4096)
         return SGC_ERR_SHAPE;
     if (!aligned16(W) || ((uintptr_t)ws & 255u))
         return SGC_ERR_ALIGN;
-    if (ws_bytes < outer_plan(rho, m, n).ws_bytes)
+    if (ws_bytes < outer_plan(count, rho, m, n).ws_bytes)
         return SGC_ERR_WORKSPACE;
-    return from_hip(launch_outer_apply(W, B, rho, m, n, d, k, sel_m, x_m, sel_v, x_v, (float)h->alpha, (float)h->eps,
-                                       (float)h->lr, ws, (hipStream_t)stream));
+    return from_hip(launch_outer_apply(W, B, count, rho, m, n, d, k, sel_m, x_m, sel_v, x_v, (float)h->alpha,
+                                       (float)h->eps, (float)h->lr, ws, (hipStream_t)stream));
 }
 
 } // extern "C"

@@ -17,32 +17,80 @@ namespace sgc {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int OUTER_STRIP = 128; // columns per wavefront
+
+// v where keep, else zero, as four selects (an `if` around a loaded value becomes a branch with a wait)
+__device__ __forceinline__ float4 outer_keep(bool keep, float4 v)
+{
+    return make_float4(keep ? v.x : 0.f, keep ? v.y : 0.f, keep ? v.z : 0.f, keep ? v.w : 0.f);
+}
 constexpr int OUTER_FLIGHT = 8;  // row pairs in flight per wavefront
 
 // Partial products of one slice of rows of G: out[s][a][j] = sum over the slice's rows i of B[a][i] G[i][j]
 // (the slices are summed in order by outer_reduce_kernel; a single slice writes Gc itself).
-// grid (column strips, slices, blocks of 32 * RBLK rows of B); the four wavefronts share the slice's row
-// pairs (pair p goes to wavefront p % 4) and add their accumulators up in wavefront order at the end.
-template <int RBLK>
+// grid (column strips, slices of 32 * NG rows, blocks of 32 * RBLK rows of B). The slice is cut in groups of
+// 8 rows, group q going to wavefront q % 4 (NG groups each). Every load of the workgroup is issued at
+// the start and none sits under a branch (addresses past an end are clamped, the values replaced by
+// zero), so the MFMAs of a group start as soon as that group's rows have arrived while the later
+// groups are still in flight:
+//   - the slice of B goes through the LDS transposed (Bs[row of the slice][row of B], read back one
+//     float per lane and MFMA);
+//   - for the group at row k, lanes 0-31 read rows k .. k + 3 of G and lanes 32-63 rows k + 4 .. k + 7,
+//     16 bytes each; MFMA j sums the depths k + j and k + 4 + j.
+// The four wavefronts' accumulators are added in wavefront order at the end.
+template <int RBLK, int NG, bool BVEC>
 __global__ __launch_bounds__(256) void outer_project_kernel(const float *__restrict__ B, const float *__restrict__ G,
-                                                            int32_t rho, int32_t m, int32_t n, int32_t slice,
+                                                            int32_t rho, int32_t m, int32_t n, int32_t rho_blocks,
                                                             float *__restrict__ out)
 {
-    extern __shared__ __attribute__((aligned(16))) float outer_lds[];
-    constexpr int RB = 32 * RBLK, LDB = RB + 1; // odd stride: the transposing writes fall in distinct banks
+    extern __shared__ __attribute__((aligned(16))) float outer_lds[]; // Bs, later the accumulators of wavefronts 1..3
+    constexpr int RB = 32 * RBLK, LDB = RB + 1, SLICE = 32 * NG, PIECES = RBLK * NG;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, l32 = lane & 31, lhalf = lane >> 5;
-    const int32_t n0 = blockIdx.x * OUTER_STRIP, s = blockIdx.y, rho0 = blockIdx.z * RB;
-    const int32_t m0 = s * slice;
-    const int32_t mend = m0 + slice < m ? m0 + slice : m;
-    const int32_t rows = mend - m0;
+    const int32_t mat = blockIdx.z / rho_blocks; // matrix of the batch
+    const int32_t n0 = blockIdx.x * OUTER_STRIP, s = blockIdx.y, rho0 = (blockIdx.z - mat * rho_blocks) * RB;
+    const int32_t m0 = s * SLICE;
+    const int32_t mend = m0 + SLICE < m ? m0 + SLICE : m;
+    B += (int64_t)mat * rho * m;
+    G += (int64_t)mat * m * n;
+    out += (int64_t)mat * gridDim.y * rho * n;
 
-    // the slice of B, transposed: Bs[row of the slice][row of B], zero beyond either end
-    for (int32_t e = tid; e < RB * slice; e += 256) {
-        const int32_t a = e / slice, kk = e - a * slice;
-        float v = 0.f;
-        if (rho0 + a < rho && kk < rows)
-            v = B[(int64_t)(rho0 + a) * m + m0 + kk];
-        outer_lds[kk * LDB + a] = v;
+    // 16-byte pieces of the slice of B: piece e is row e / (SLICE / 4) of the block, depths 4 (e % (SLICE / 4)) ..
+    float4 bp[PIECES];
+#pragma unroll
+    for (int i = 0; i < PIECES; ++i) {
+        const int e = tid + 256 * i;
+        const int32_t a = rho0 + e / (SLICE / 4), k = m0 + 4 * (e % (SLICE / 4));
+        const float *row = B + (int64_t)(a < rho ? a : rho - 1) * m;
+        if (BVEC) {
+            bp[i] = *reinterpret_cast<const float4 *>(row + (k + 3 < m ? k : m - 4));
+        } else {
+            bp[i].x = row[k < m ? k : m - 1];
+            bp[i].y = row[k + 1 < m ? k + 1 : m - 1];
+            bp[i].z = row[k + 2 < m ? k + 2 : m - 1];
+            bp[i].w = row[k + 3 < m ? k + 3 : m - 1];
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0); // B first: its wait then leaves the loads of G in flight
+    const int32_t col = n0 + 4 * l32;
+    const bool col_ok = col < n;
+    const float *gcol = G + (col_ok ? col : n - 4);
+    float4 g[NG][4];
+#pragma unroll
+    for (int q = 0; q < NG; ++q)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int32_t row = m0 + 8 * (4 * q + w) + 4 * lhalf + j;
+            g[q][j] = load_once_f4(gcol + (int64_t)(row < m ? row : m - 1) * n);
+        }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < PIECES; ++i) {
+        const int e = tid + 256 * i;
+        const int32_t al = e / (SLICE / 4), kl = 4 * (e % (SLICE / 4));
+        const bool a_ok = rho0 + al < rho;
+        outer_lds[(kl + 0) * LDB + al] = (a_ok && m0 + kl + 0 < mend) ? bp[i].x : 0.f;
+        outer_lds[(kl + 1) * LDB + al] = (a_ok && m0 + kl + 1 < mend) ? bp[i].y : 0.f;
+        outer_lds[(kl + 2) * LDB + al] = (a_ok && m0 + kl + 2 < mend) ? bp[i].z : 0.f;
+        outer_lds[(kl + 3) * LDB + al] = (a_ok && m0 + kl + 3 < mend) ? bp[i].w : 0.f;
     }
     __syncthreads();
 
@@ -54,87 +102,88 @@ __global__ __launch_bounds__(256) void outer_project_kernel(const float *__restr
 #pragma unroll
             for (int v = 0; v < 16; ++v)
                 acc[rb][e][v] = 0.f;
-
-    const int32_t col = n0 + 4 * l32;
-    const bool col_ok = col < n;
-    const int32_t pairs = slice >> 1;
-    for (int32_t p0 = w; p0 < pairs; p0 += 4 * OUTER_FLIGHT) {
-        float4 g[OUTER_FLIGHT];
 #pragma unroll
-        for (int u = 0; u < OUTER_FLIGHT; ++u) {
-            const int32_t row = m0 + 2 * (p0 + 4 * u) + lhalf;
-            g[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (row < mend && col_ok)
-                g[u] = load_once_f4(G + (int64_t)row * n + col);
-        }
+    for (int q = 0; q < NG; ++q) {
 #pragma unroll
-        for (int u = 0; u < OUTER_FLIGHT; ++u) {
-            const int32_t p = p0 + 4 * u;
-            if (p < pairs) { // uniform over the wavefront
-                const int32_t kk = 2 * p + lhalf;
-                float a[RBLK];
+        for (int j = 0; j < 4; ++j) {
+            const int32_t kl = 8 * (4 * q + w) + 4 * lhalf + j;
+            // rows past the end of the matrix were read from a clamped address: they count as zero
+            // (their depths of Bs are zero too, but zero times a non-finite entry would not be)
+            const float4 gv = outer_keep(m0 + kl < mend, g[q][j]);
 #pragma unroll
-                for (int rb = 0; rb < RBLK; ++rb)
-                    a[rb] = outer_lds[kk * LDB + rb * 32 + l32];
-#pragma unroll
-                for (int rb = 0; rb < RBLK; ++rb) {
-                    acc[rb][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[rb], g[u].x, acc[rb][0], 0, 0, 0);
-                    acc[rb][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[rb], g[u].y, acc[rb][1], 0, 0, 0);
-                    acc[rb][2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[rb], g[u].z, acc[rb][2], 0, 0, 0);
-                    acc[rb][3] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[rb], g[u].w, acc[rb][3], 0, 0, 0);
-                }
+            for (int rb = 0; rb < RBLK; ++rb) {
+                const float a = outer_lds[kl * LDB + rb * 32 + l32];
+                acc[rb][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, gv.x, acc[rb][0], 0, 0, 0);
+                acc[rb][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, gv.y, acc[rb][1], 0, 0, 0);
+                acc[rb][2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, gv.z, acc[rb][2], 0, 0, 0);
+                acc[rb][3] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, gv.w, acc[rb][3], 0, 0, 0);
             }
         }
     }
 
-    // wavefronts 1..3 hand their accumulators to wavefront 0, one after the other (fixed order of the sums)
+    // wavefronts 1..3 hand their accumulators to wavefront 0, which adds them in wavefront order
+    constexpr int PER_WAVE = RBLK * 4 * 16 * 64;
     __syncthreads();
-    for (int ww = 1; ww < 4; ++ww) {
-        if (w == ww) {
+    if (w > 0) {
 #pragma unroll
-            for (int rb = 0; rb < RBLK; ++rb)
+        for (int rb = 0; rb < RBLK; ++rb)
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
+            for (int e = 0; e < 4; ++e)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        outer_lds[((rb * 4 + e) * 16 + v) * 64 + lane] = acc[rb][e][v];
-        }
-        __syncthreads();
-        if (w == 0) {
-#pragma unroll
-            for (int rb = 0; rb < RBLK; ++rb)
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        acc[rb][e][v] += outer_lds[((rb * 4 + e) * 16 + v) * 64 + lane];
-        }
-        __syncthreads();
+                for (int v = 0; v < 16; ++v)
+                    outer_lds[(w - 1) * PER_WAVE + ((rb * 4 + e) * 16 + v) * 64 + lane] = acc[rb][e][v];
     }
+    __syncthreads();
     if (w == 0 && col_ok) {
         // accumulator register v of lane l: row 8 (v / 4) + v % 4 + 4 (l / 32) of the block
 #pragma unroll
         for (int rb = 0; rb < RBLK; ++rb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
+                float o[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float t = acc[rb][e][v];
+#pragma unroll
+                    for (int ww = 0; ww < 3; ++ww)
+                        t += outer_lds[ww * PER_WAVE + ((rb * 4 + e) * 16 + v) * 64 + lane];
+                    o[e] = t;
+                }
                 const int32_t a = rho0 + rb * 32 + 8 * (v >> 2) + (v & 3) + 4 * lhalf;
                 if (a < rho)
                     *reinterpret_cast<float4 *>(out + ((int64_t)s * rho + a) * n + col) =
-                        make_float4(acc[rb][0][v], acc[rb][1][v], acc[rb][2][v], acc[rb][3][v]);
+                        make_float4(o[0], o[1], o[2], o[3]);
             }
     }
 }
 
-// Gc = sum of the slices' partial products, in slice order
+// Gc = sum of the slices' partial products, in slice order (the loads of four slices in flight);
+// blockIdx.y: matrix of the batch
 __global__ __launch_bounds__(256) void outer_reduce_kernel(const float *__restrict__ part, int32_t S, int64_t count4,
                                                            float *__restrict__ Gc)
 {
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (e >= count4)
         return;
-    float4 acc = reinterpret_cast<const float4 *>(part)[e];
-    for (int32_t s = 1; s < S; ++s) {
-        const float4 v = reinterpret_cast<const float4 *>(part)[(int64_t)s * count4 + e];
+    const float4 *src = reinterpret_cast<const float4 *>(part) + (int64_t)blockIdx.y * S * count4 + e;
+    Gc += (int64_t)blockIdx.y * count4 * 4;
+    float4 acc = src[0];
+    int32_t s = 1;
+    for (; s + 4 <= S; s += 4) {
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            v[u] = src[(int64_t)(s + u) * count4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            acc.x += v[u].x;
+            acc.y += v[u].y;
+            acc.z += v[u].z;
+            acc.w += v[u].w;
+        }
+    }
+    for (; s < S; ++s) {
+        const float4 v = src[(int64_t)s * count4];
         acc.x += v.x;
         acc.y += v.y;
         acc.z += v.z;
@@ -152,143 +201,222 @@ __global__ __launch_bounds__(256) void outer_zero_kernel(float *__restrict__ p, 
 
 // W[i][j] -= lr * sum over a of B[a][i] Nd[a][j], Nd the update in the compressed space written out
 // densely (rho x n, mostly zeros; it stays in the caches). grid (column strips, groups of `blocks`
-// 32-row blocks of W); a wavefront takes every fourth block of its group: the rho-deep product of a
-// 32 x 128 tile on the matrix cores, then one read-modify-write pass over the tile.
-__global__ __launch_bounds__(256) void outer_back_kernel(float *__restrict__ W, const float *__restrict__ B,
-                                                         const float *__restrict__ Nd, int32_t rho, int32_t m,
-                                                         int32_t n, int32_t blocks, float lr)
+// 32-row blocks of W); a wavefront takes every fourth block of its group, one wavefront per SIMD.
+// Per block: the rho-deep product of the 32 x 128 tile on the matrix cores, then the tile of W is updated
+// and stored; the loads of the next block's tile of W and of its values of B are issued before the
+// product, so they are in flight while the matrix cores work. RHO32: rho <= 32, the strip of Nd is read
+// once per wavefront and kept in registers for all its blocks. FULL: m % 32 == 0 and n % 128 == 0, no
+// bounds checks (and so no branches around the loads and stores).
+template <bool RHO32, bool FULL>
+__global__ __launch_bounds__(256, 1) void outer_back_kernel(float *__restrict__ W, const float *__restrict__ B,
+                                                            const float *__restrict__ Nd, int32_t rho, int32_t m,
+                                                            int32_t n, int32_t blocks, float lr)
 {
+    constexpr int FL = OUTER_FLIGHT;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, l32 = lane & 31, lhalf = lane >> 5;
     const int32_t col = blockIdx.x * OUTER_STRIP + 4 * l32;
-    const bool col_ok = col < n;
-    for (int32_t q = w; q < blocks; q += 4) {
-        const int32_t i0 = (blockIdx.y * blocks + q) * 32;
-        if (i0 >= m)
+    const bool col_ok = FULL || col < n;
+    W += (int64_t)blockIdx.z * m * n; // matrix of the batch
+    B += (int64_t)blockIdx.z * rho * m;
+    Nd += (int64_t)blockIdx.z * rho * n;
+    float4 nfix[RHO32 ? 16 : 1];
+    if (RHO32) {
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int32_t a = 2 * u + lhalf; // rows past rho: a clamped address, the value replaced by zero
+            nfix[u] = outer_keep(a < rho, *reinterpret_cast<const float4 *>(Nd + (int64_t)(a < rho ? a : rho - 1) * n +
+                                                                            (col_ok ? col : n - 4)));
+        }
+    }
+    // two sets of tile registers, used in turn: one holds the block being worked on, the other receives
+    // the next block's loads (no copies, so nothing waits for a load before its values are needed)
+    float4 wt[2][16];
+    float bt[2][RHO32 ? 16 : 1];
+    auto fetch = [&](int set, int32_t i0) { // the tile of W at rows i0.. and, RHO32, its values of B
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int32_t row = i0 + 8 * (v >> 2) + (v & 3) + 4 * lhalf;
+            if (FULL) {
+                wt[set][v] = load_once_f4(W + (int64_t)row * n + col);
+            } else {
+                wt[set][v] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (row < m && col_ok)
+                    wt[set][v] = load_once_f4(W + (int64_t)row * n + col);
+            }
+        }
+        if (RHO32) {
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int32_t a = 2 * u + lhalf;
+                const int32_t i = FULL || i0 + l32 < m ? i0 + l32 : m - 1;
+                const float bval = B[(int64_t)(a < rho ? a : rho - 1) * m + i];
+                bt[set][u] = (a < rho && (FULL || i0 + l32 < m)) ? bval : 0.f;
+            }
+        }
+    };
+    const int32_t first = blockIdx.y * blocks;
+    if ((first + w) * 32 < m && w < blocks)
+        fetch(0, (first + w) * 32);
+    for (int32_t q2 = w; q2 < blocks; q2 += 8) {
+#pragma unroll
+      for (int ph = 0; ph < 2; ++ph) {
+        const int32_t q = q2 + 4 * ph;
+        const int32_t i0 = (first + q) * 32;
+        if (q >= blocks || i0 >= m)
             break;
+        if (q + 4 < blocks && i0 + 128 < m)
+            fetch(ph ^ 1, i0 + 128);
         floatx16 acc[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e)
 #pragma unroll
             for (int v = 0; v < 16; ++v)
                 acc[e][v] = 0.f;
-        const bool row_ok = i0 + l32 < m;
-        for (int32_t k0 = 0; k0 < rho; k0 += 2 * OUTER_FLIGHT) {
-            float4 nv[OUTER_FLIGHT];
-            float bv[OUTER_FLIGHT];
+        if (RHO32) {
 #pragma unroll
-            for (int u = 0; u < OUTER_FLIGHT; ++u) {
-                const int32_t a = k0 + 2 * u + lhalf;
-                nv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-                bv[u] = 0.f;
-                if (a < rho) {
-                    if (col_ok)
-                        nv[u] = *reinterpret_cast<const float4 *>(Nd + (int64_t)a * n + col);
-                    if (row_ok)
-                        bv[u] = B[(int64_t)a * m + i0 + l32];
+            for (int u = 0; u < 16; ++u) {
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(bt[ph][u], nfix[u].x, acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(bt[ph][u], nfix[u].y, acc[1], 0, 0, 0);
+                acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(bt[ph][u], nfix[u].z, acc[2], 0, 0, 0);
+                acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(bt[ph][u], nfix[u].w, acc[3], 0, 0, 0);
+            }
+        } else {
+            const bool row_ok = FULL || i0 + l32 < m;
+            for (int32_t k0 = 0; k0 < rho; k0 += 2 * FL) {
+                float4 nv[FL];
+                float bk[FL];
+#pragma unroll
+                for (int u = 0; u < FL; ++u) {
+                    const int32_t a = k0 + 2 * u + lhalf;
+                    nv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    bk[u] = 0.f;
+                    if (a < rho) {
+                        if (col_ok)
+                            nv[u] = *reinterpret_cast<const float4 *>(Nd + (int64_t)a * n + col);
+                        if (row_ok)
+                            bk[u] = B[(int64_t)a * m + i0 + l32];
+                    }
                 }
-            }
 #pragma unroll
-            for (int u = 0; u < OUTER_FLIGHT; ++u) {
-                acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[u], nv[u].x, acc[0], 0, 0, 0);
-                acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[u], nv[u].y, acc[1], 0, 0, 0);
-                acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[u], nv[u].z, acc[2], 0, 0, 0);
-                acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[u], nv[u].w, acc[3], 0, 0, 0);
-            }
-        }
-        if (col_ok) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int32_t row = i0 + 8 * (v >> 2) + (v & 3) + 4 * lhalf;
-                if (row < m) {
-                    float4 *p = reinterpret_cast<float4 *>(W + (int64_t)row * n + col);
-                    float4 wv = *p;
-                    wv.x -= lr * acc[0][v];
-                    wv.y -= lr * acc[1][v];
-                    wv.z -= lr * acc[2][v];
-                    wv.w -= lr * acc[3][v];
-                    *p = wv;
+                for (int u = 0; u < FL; ++u) {
+                    acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(bk[u], nv[u].x, acc[0], 0, 0, 0);
+                    acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(bk[u], nv[u].y, acc[1], 0, 0, 0);
+                    acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(bk[u], nv[u].z, acc[2], 0, 0, 0);
+                    acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(bk[u], nv[u].w, acc[3], 0, 0, 0);
                 }
             }
         }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int32_t row = i0 + 8 * (v >> 2) + (v & 3) + 4 * lhalf;
+            if (FULL || (row < m && col_ok)) {
+                float4 o = wt[ph][v];
+                o.x -= lr * acc[0][v];
+                o.y -= lr * acc[1][v];
+                o.z -= lr * acc[2][v];
+                o.w -= lr * acc[3][v];
+                *reinterpret_cast<float4 *>(W + (int64_t)row * n + col) = o;
+            }
+        }
+      }
     }
 }
 
 // ---- host side ----
-// how the rows of G are cut in slices: enough workgroups to fill the chip, slices of at most 256 rows
-// (the transposed slice of B has to fit the LDS) and a multiple of 8 (row pairs, four wavefronts)
-OuterPlan outer_plan(int32_t rho, int32_t m, int32_t n)
+// how the rows of G are cut in slices: enough workgroups to fill the chip with slices of 32, 64, 128 or
+// 256 rows (1, 2, 4 or 8 groups of 8 rows for each of the four wavefronts)
+OuterPlan outer_plan(int32_t count, int32_t rho, int32_t m, int32_t n)
 {
     OuterPlan pl{};
     pl.rblk = rho <= 32 ? 1 : 2;
     pl.strips = (n + OUTER_STRIP - 1) / OUTER_STRIP;
     pl.rho_blocks = (rho + 32 * pl.rblk - 1) / (32 * pl.rblk);
-    int64_t S = (1024 + (int64_t)pl.strips * pl.rho_blocks - 1) / ((int64_t)pl.strips * pl.rho_blocks);
-    const int64_t most = (m + 63) / 64;
-    S = S < 1 ? 1 : (S > most ? most : S);
-    int64_t slice = ((m + S - 1) / S + 7) / 8 * 8;
-    if (slice > 256)
-        slice = 256;
+    const int64_t per_slice = (int64_t)pl.strips * pl.rho_blocks * count;
+    int64_t slice = 256;
+    while (slice > 32 && ((m + slice - 1) / slice) * per_slice < 512)
+        slice >>= 1;
     pl.slice = (int32_t)slice;
     pl.slices = (int32_t)((m + slice - 1) / slice);
-    const size_t partial = pl.slices > 1 ? (size_t)pl.slices * rho * n * sizeof(float) : 0;
-    const size_t dense = (size_t)rho * n * sizeof(float);
+    const size_t partial = pl.slices > 1 ? (size_t)count * pl.slices * rho * n * sizeof(float) : 0;
+    const size_t dense = (size_t)count * rho * n * sizeof(float);
     pl.ws_bytes = ((partial > dense ? partial : dense) + 255) & ~(size_t)255;
     return pl;
 }
 
-hipError_t launch_outer_project(const float *B, const float *G, int32_t rho, int32_t m, int32_t n, float *Gc,
-                                void *ws, hipStream_t s)
+hipError_t launch_outer_project(const float *B, const float *G, int32_t count, int32_t rho, int32_t m, int32_t n,
+                                float *Gc, void *ws, hipStream_t s)
 {
-    const OuterPlan pl = outer_plan(rho, m, n);
+    const OuterPlan pl = outer_plan(count, rho, m, n);
     float *out = pl.slices > 1 ? static_cast<float *>(ws) : Gc;
-    const dim3 grid((unsigned)pl.strips, (unsigned)pl.slices, (unsigned)pl.rho_blocks);
+    const dim3 grid((unsigned)pl.strips, (unsigned)pl.slices, (unsigned)(pl.rho_blocks * count));
     const size_t stage = (size_t)pl.slice * (32 * pl.rblk + 1) * sizeof(float);
-    const size_t handoff = (size_t)pl.rblk * 4 * 16 * 64 * sizeof(float);
+    const size_t handoff = (size_t)3 * pl.rblk * 4 * 16 * 64 * sizeof(float);
     const size_t smem = stage > handoff ? stage : handoff;
-    ProfileScope prof(KC_OUTER, s);
-    if (pl.rblk == 1) {
-        outer_project_kernel<1><<<grid, 256, smem, s>>>(B, G, rho, m, n, pl.slice, out);
-    } else {
-        static bool raised = false;
-        if (!raised) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(outer_project_kernel<2>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-            if (e != hipSuccess)
-                return e;
-            raised = true;
-        }
-        outer_project_kernel<2><<<grid, 256, smem, s>>>(B, G, rho, m, n, pl.slice, out);
+    const bool b_vec = m % 4 == 0 && ((uintptr_t)B & 15u) == 0;
+    typedef void (*Kernel)(const float *, const float *, int32_t, int32_t, int32_t, int32_t, float *);
+    Kernel kern = nullptr;
+    const int ng = pl.slice / 32;
+#define SGC_OUTER_PICK(R, N) \
+    if (pl.rblk == R && ng == N) \
+        kern = b_vec ? outer_project_kernel<R, N, true> : outer_project_kernel<R, N, false>;
+    SGC_OUTER_PICK(1, 1) SGC_OUTER_PICK(1, 2) SGC_OUTER_PICK(1, 4) SGC_OUTER_PICK(1, 8)
+    SGC_OUTER_PICK(2, 1) SGC_OUTER_PICK(2, 2) SGC_OUTER_PICK(2, 4) SGC_OUTER_PICK(2, 8)
+#undef SGC_OUTER_PICK
+    if (!kern)
+        return hipErrorInvalidValue;
+    static bool raised[3][9][2];
+    if (smem > 48 * 1024 && !raised[pl.rblk][ng][b_vec ? 1 : 0]) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess)
+            return e;
+        raised[pl.rblk][ng][b_vec ? 1 : 0] = true;
     }
+    ProfileScope prof(KC_OUTER_PROJECT, s);
+    kern<<<grid, 256, smem, s>>>(B, G, rho, m, n, pl.rho_blocks, out);
     if (pl.slices > 1) {
         const int64_t count4 = (int64_t)rho * n / 4;
-        outer_reduce_kernel<<<dim3((unsigned)((count4 + 255) / 256)), 256, 0, s>>>(out, pl.slices, count4, Gc);
+        outer_reduce_kernel<<<dim3((unsigned)((count4 + 255) / 256), (unsigned)count), 256, 0, s>>>(out, pl.slices,
+                                                                                                   count4, Gc);
     }
     return hipGetLastError();
 }
 
-hipError_t launch_outer_apply(float *W, const float *B, int32_t rho, int32_t m, int32_t n, int32_t d, int32_t k,
-                              const int32_t *sel_m, const float *x_m, const int32_t *sel_v, const float *x_v,
-                              float alpha, float eps, float lr, void *ws, hipStream_t s)
+hipError_t launch_outer_apply(float *W, const float *B, int32_t count, int32_t rho, int32_t m, int32_t n, int32_t d,
+                              int32_t k, const int32_t *sel_m, const float *x_m, const int32_t *sel_v,
+                              const float *x_v, float alpha, float eps, float lr, void *ws, hipStream_t s)
 {
     float *Nd = static_cast<float *>(ws);
-    const int64_t count4 = (int64_t)rho * n / 4;
+    const int64_t count4 = (int64_t)count * rho * n / 4;
     {
-        ProfileScope prof(KC_OUTER, s);
+        ProfileScope prof(KC_OUTER_APPLY, s);
         outer_zero_kernel<<<dim3((unsigned)((count4 + 255) / 256)), 256, 0, s>>>(Nd, count4);
     }
     // the update of the plain path applied to zeros with step -1 leaves N itself (0 - (-1) N is exact)
-    hipError_t e = launch_apply(Nd, (int64_t)rho * n / d, d, k, sel_m, x_m, sel_v, x_v, alpha, eps, -1.0f, s);
+    hipError_t e = launch_apply(Nd, (int64_t)count * rho * n / d, d, k, sel_m, x_m, sel_v, x_v, alpha, eps, -1.0f, s);
     if (e != hipSuccess)
         return e;
     const int32_t strips = (n + OUTER_STRIP - 1) / OUTER_STRIP;
     const int32_t row_blocks = (m + 31) / 32;
-    // eight blocks per workgroup (two per wavefront) unless that leaves the chip short of workgroups
-    int32_t blocks = 8;
-    while (blocks > 4 && (int64_t)strips * ((row_blocks + blocks - 1) / blocks) < 512)
+    // sixteen blocks per workgroup (four per wavefront, so the next tile's loads overlap the product)
+    // unless that leaves the chip short of workgroups
+    int32_t blocks = 16;
+    while (blocks > 4 && (int64_t)strips * ((row_blocks + blocks - 1) / blocks) * count < 256)
         blocks -= 4;
-    const dim3 grid((unsigned)strips, (unsigned)((row_blocks + blocks - 1) / blocks));
-    ProfileScope prof(KC_OUTER, s);
-    outer_back_kernel<<<grid, 256, 0, s>>>(W, B, Nd, rho, m, n, blocks, lr);
+    const dim3 grid((unsigned)strips, (unsigned)((row_blocks + blocks - 1) / blocks), (unsigned)count);
+    ProfileScope prof(KC_OUTER_APPLY, s);
+    const bool full = m % 32 == 0 && n % OUTER_STRIP == 0;
+    if (rho <= 32) {
+        if (full)
+            outer_back_kernel<true, true><<<grid, 256, 0, s>>>(W, B, Nd, rho, m, n, blocks, lr);
+        else
+            outer_back_kernel<true, false><<<grid, 256, 0, s>>>(W, B, Nd, rho, m, n, blocks, lr);
+    } else {
+        if (full)
+            outer_back_kernel<false, true><<<grid, 256, 0, s>>>(W, B, Nd, rho, m, n, blocks, lr);
+        else
+            outer_back_kernel<false, false><<<grid, 256, 0, s>>>(W, B, Nd, rho, m, n, blocks, lr);
+    }
     return hipGetLastError();
 }
 

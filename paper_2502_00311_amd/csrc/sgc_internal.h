@@ -57,7 +57,7 @@ struct OmpWorkspace {
 OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_t k);
 
 // kernel classes of the optional per-kernel timing (see profile.hip)
-enum KernelClass { KC_TOPK = 0, KC_PROJECT, KC_ADAM, KC_CORR, KC_SELECT, KC_APPLY, KC_OTHER, KC_FILL, KC_OUTER };
+enum KernelClass { KC_TOPK = 0, KC_PROJECT, KC_ADAM, KC_CORR, KC_SELECT, KC_APPLY, KC_OTHER, KC_FILL, KC_OUTER_PROJECT, KC_OUTER_APPLY };
 
 // launchers (each returns hipGetLastError() of its launches)
 hipError_t launch_topk(const void *grad, int grad_type, int64_t C, int32_t d, int32_t k, int32_t *idx,
@@ -86,12 +86,12 @@ struct OuterPlan {
     int32_t slices;
     size_t ws_bytes;
 };
-OuterPlan outer_plan(int32_t rho, int32_t m, int32_t n);
-hipError_t launch_outer_project(const float *B, const float *G, int32_t rho, int32_t m, int32_t n, float *Gc,
-                                void *ws, hipStream_t s);
-hipError_t launch_outer_apply(float *W, const float *B, int32_t rho, int32_t m, int32_t n, int32_t d, int32_t k,
-                              const int32_t *sel_m, const float *x_m, const int32_t *sel_v, const float *x_v,
-                              float alpha, float eps, float lr, void *ws, hipStream_t s);
+OuterPlan outer_plan(int32_t count, int32_t rho, int32_t m, int32_t n);
+hipError_t launch_outer_project(const float *B, const float *G, int32_t count, int32_t rho, int32_t m, int32_t n,
+                                float *Gc, void *ws, hipStream_t s);
+hipError_t launch_outer_apply(float *W, const float *B, int32_t count, int32_t rho, int32_t m, int32_t n, int32_t d,
+                              int32_t k, const int32_t *sel_m, const float *x_m, const int32_t *sel_v,
+                              const float *x_v, float alpha, float eps, float lr, void *ws, hipStream_t s);
 
 // ---- optional per-kernel timing (see profile.hip) ----
 extern bool g_profile_on;

@@ -25,7 +25,7 @@ EXPORTS = [
     "sgc_profile_enable", "sgc_profile_read",
 ]
 PROFILE_CLASSES = ["topk", "project", "adam", "omp_corr", "omp_select_update", "apply", "other", "omp_matrix_fill",
-                   "outer"]
+                   "outer_project", "outer_apply"]
 
 
 class sgc_matrix(ctypes.Structure):
@@ -42,7 +42,7 @@ class sgc_hyper(ctypes.Structure):
 
 
 class sgc_profile(ctypes.Structure):
-    _fields_ = [("ms", ctypes.c_double * 9), ("launches", ctypes.c_int64 * 9)]
+    _fields_ = [("ms", ctypes.c_double * 10), ("launches", ctypes.c_int64 * 10)]
 
 
 class SgcError(RuntimeError):
@@ -85,11 +85,11 @@ def lib():
         L.sgc_apply.restype = i32
         L.sgc_apply.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp, ctypes.POINTER(sgc_hyper), vp]
         L.sgc_outer_workspace_bytes.restype = sz
-        L.sgc_outer_workspace_bytes.argtypes = [i32, i32, i32]
+        L.sgc_outer_workspace_bytes.argtypes = [i32, i32, i32, i32]
         L.sgc_outer_project.restype = i32
-        L.sgc_outer_project.argtypes = [vp, vp, i32, i32, i32, vp, vp, sz, vp]
+        L.sgc_outer_project.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
         L.sgc_outer_apply.restype = i32
-        L.sgc_outer_apply.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, ctypes.POINTER(sgc_hyper), vp, sz, vp]
+        L.sgc_outer_apply.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, ctypes.POINTER(sgc_hyper), vp, sz, vp]
         L.sgc_profile_enable.restype = i32
         L.sgc_profile_enable.argtypes = [i32]
         L.sgc_profile_read.restype = i32
@@ -180,16 +180,16 @@ def sgc_apply(W, C, d, k, sel_m, x_m, sel_v, x_v, h, stream=None):
     _check(lib().sgc_apply(_ptr(W), C, d, k, _ptr(sel_m), _ptr(x_m), _ptr(sel_v), _ptr(x_v), ctypes.byref(h), _stream(stream)), "sgc_apply")
 
 
-def sgc_outer_workspace_bytes(rho, m, n):
-    return int(lib().sgc_outer_workspace_bytes(rho, m, n))
+def sgc_outer_workspace_bytes(count, rho, m, n):
+    return int(lib().sgc_outer_workspace_bytes(count, rho, m, n))
 
 
-def sgc_outer_project(B, G, rho, m, n, Gc, ws, stream=None):
-    _check(lib().sgc_outer_project(_ptr(B), _ptr(G), rho, m, n, _ptr(Gc), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_outer_project")
+def sgc_outer_project(B, G, count, rho, m, n, Gc, ws, stream=None):
+    _check(lib().sgc_outer_project(_ptr(B), _ptr(G), count, rho, m, n, _ptr(Gc), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_outer_project")
 
 
-def sgc_outer_apply(W, B, rho, m, n, d, k, sel_m, x_m, sel_v, x_v, h, ws, stream=None):
-    _check(lib().sgc_outer_apply(_ptr(W), _ptr(B), rho, m, n, d, k, _ptr(sel_m), _ptr(x_m), _ptr(sel_v), _ptr(x_v), ctypes.byref(h), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_outer_apply")
+def sgc_outer_apply(W, B, count, rho, m, n, d, k, sel_m, x_m, sel_v, x_v, h, ws, stream=None):
+    _check(lib().sgc_outer_apply(_ptr(W), _ptr(B), count, rho, m, n, d, k, _ptr(sel_m), _ptr(x_m), _ptr(sel_v), _ptr(x_v), ctypes.byref(h), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_outer_apply")
 
 
 def sgc_profile_enable(on):
@@ -248,24 +248,26 @@ def step(grad, W, buf, A, t, h, stream=None, shared_support=False, A_new=None):
 
 
 class OuterBuffers:
-    """Device buffers of the outer projection of CESGC for one m x n weight matrix (allocation only)."""
+    """Device buffers of the outer projection of CESGC for a batch of `count` m x n weight matrices
+    (allocation only)."""
 
-    def __init__(self, rho, m, n, device="cuda"):
-        self.rho, self.m, self.n = rho, m, n
-        self.Gc = torch.empty((rho, n), dtype=torch.float32, device=device)
-        nbytes = sgc_outer_workspace_bytes(rho, m, n)
+    def __init__(self, rho, m, n, count=1, device="cuda"):
+        self.rho, self.m, self.n, self.count = rho, m, n, count
+        self.Gc = torch.empty((count, rho, n) if count > 1 else (rho, n), dtype=torch.float32, device=device)
+        nbytes = sgc_outer_workspace_bytes(count, rho, m, n)
         if nbytes == 0:
             raise SgcError(ERR_SHAPE, "sgc_outer_workspace_bytes")
         self.ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
 
 
 def step_cesgc(G, W, B, obuf, buf, A, t, h, stream=None):
-    """One CESGC step (Sec. 4.4) on one weight matrix: Gc = B G, Alg. 2 on the chunks of Gc, then
-    W <- W - lr B^T N. buf: StepBuffers for rho*n/d chunks."""
-    rho, m, n = obuf.rho, obuf.m, obuf.n
+    """One CESGC step (Sec. 4.4) on a batch of equal weight matrices ([count, m, n], or [m, n] for one):
+    Gc = B G, Alg. 2 on the chunks of Gc, then W <- W - lr B^T N. buf: StepBuffers for count*rho*n/d
+    chunks."""
+    rho, m, n, count = obuf.rho, obuf.m, obuf.n, obuf.count
     C, d, r, k = buf.C, buf.d, buf.r, buf.k
-    sgc_outer_project(B, G, rho, m, n, obuf.Gc, obuf.ws, stream)
+    sgc_outer_project(B, G, count, rho, m, n, obuf.Gc, obuf.ws, stream)
     sgc_sparsify_project(obuf.Gc, C * d, d, k, A, buf.idx, buf.val, buf.p, buf.q, stream)
     sgc_adam_compressed(buf.p, buf.q, buf.m, buf.v, buf.hat[:C], buf.hat[C:], C * r, t, h, stream)
     sgc_recover_omp(buf.hat, 2 * C, A, k, buf.sel, buf.x, buf.ws, stream)
-    sgc_outer_apply(W, B, rho, m, n, d, k, buf.sel[:C], buf.x[:C], buf.sel[C:], buf.x[C:], h, obuf.ws, stream)
+    sgc_outer_apply(W, B, count, rho, m, n, d, k, buf.sel[:C], buf.x[:C], buf.sel[C:], buf.x[C:], h, obuf.ws, stream)

@@ -174,29 +174,36 @@ def test_gram_rejects_bad_arguments():
 
 def test_outer_projection_rejects_bad_arguments_and_sizes_workspace():
     L = sgc.lib()
-    nbytes = sgc.sgc_outer_workspace_bytes(32, 4096, 4096)
+    nbytes = sgc.sgc_outer_workspace_bytes(1, 32, 4096, 4096)
     assert nbytes >= 32 * 4096 * 4 and nbytes % 256 == 0
-    assert sgc.sgc_outer_workspace_bytes(0, 8, 8) == 0
-    assert sgc.sgc_outer_workspace_bytes(4, 8, 6) == 0          # n % 4
-    assert sgc.sgc_outer_workspace_bytes(4, 8, 1 << 23) == 0
-    small = sgc.sgc_outer_workspace_bytes(4, 8, 8)
+    assert sgc.sgc_outer_workspace_bytes(16, 32, 4096, 4096) >= 16 * 32 * 4096 * 4
+    assert sgc.sgc_outer_workspace_bytes(1, 0, 8, 8) == 0
+    assert sgc.sgc_outer_workspace_bytes(0, 4, 8, 8) == 0
+    assert sgc.sgc_outer_workspace_bytes(1, 4, 8, 6) == 0          # n % 4
+    assert sgc.sgc_outer_workspace_bytes(1, 4, 8, 1 << 23) == 0
+    assert sgc.sgc_outer_workspace_bytes(70000, 4, 8, 8) == 0      # batch beyond the grid limit
+    small = sgc.sgc_outer_workspace_bytes(1, 4, 8, 8)
     p = L.sgc_outer_project
-    assert p(None, FAKE, 4, 8, 8, FAKE, FAKE, small, None) == sgc.ERR_NULL
-    assert p(FAKE, FAKE, 4, 8, 8, FAKE, None, small, None) == sgc.ERR_NULL
-    assert p(FAKE, FAKE, 4, 8, 6, FAKE, FAKE, small, None) == sgc.ERR_SHAPE
-    assert p(FAKE, FAKE, 0, 8, 8, FAKE, FAKE, small, None) == sgc.ERR_SHAPE
-    assert p(FAKE, ODD, 4, 8, 8, FAKE, FAKE, small, None) == sgc.ERR_ALIGN
-    assert p(FAKE, FAKE, 4, 8, 8, FAKE, ODD, small, None) == sgc.ERR_ALIGN
-    assert p(FAKE, FAKE, 4, 8, 8, FAKE, FAKE, small - 1, None) == sgc.ERR_WORKSPACE
+    assert p(None, FAKE, 1, 4, 8, 8, FAKE, FAKE, small, None) == sgc.ERR_NULL
+    assert p(FAKE, FAKE, 1, 4, 8, 8, FAKE, None, small, None) == sgc.ERR_NULL
+    assert p(FAKE, FAKE, 1, 4, 8, 6, FAKE, FAKE, small, None) == sgc.ERR_SHAPE
+    assert p(FAKE, FAKE, 1, 0, 8, 8, FAKE, FAKE, small, None) == sgc.ERR_SHAPE
+    assert p(FAKE, FAKE, 0, 4, 8, 8, FAKE, FAKE, small, None) == sgc.ERR_SHAPE
+    assert p(FAKE, ODD, 1, 4, 8, 8, FAKE, FAKE, small, None) == sgc.ERR_ALIGN
+    assert p(FAKE, FAKE, 1, 4, 8, 8, FAKE, ODD, small, None) == sgc.ERR_ALIGN
+    assert p(FAKE, FAKE, 1, 4, 8, 8, FAKE, FAKE, small - 1, None) == sgc.ERR_WORKSPACE
+    one = sgc.sgc_outer_workspace_bytes(1, 4, 8, 256)
+    assert p(FAKE, FAKE, 2, 4, 8, 256, FAKE, FAKE, one, None) == sgc.ERR_WORKSPACE  # sized for one matrix
     a = L.sgc_outer_apply
     h = sgc.hyper()
 
-    def call(W=FAKE, B=FAKE, rho=4, m=8, n=8, d=16, k=2, sel=FAKE, hh=ctypes.byref(h), ws=FAKE, nb=small):
-        return a(W, B, rho, m, n, d, k, sel, FAKE, FAKE, FAKE, hh, ws, nb, None)
+    def call(W=FAKE, B=FAKE, count=1, rho=4, m=8, n=8, d=16, k=2, sel=FAKE, hh=ctypes.byref(h), ws=FAKE, nb=small):
+        return a(W, B, count, rho, m, n, d, k, sel, FAKE, FAKE, FAKE, hh, ws, nb, None)
 
     assert call(W=None) == sgc.ERR_NULL
     assert call(sel=None) == sgc.ERR_NULL
     assert call(hh=None) == sgc.ERR_NULL
+    assert call(count=0) == sgc.ERR_SHAPE
     assert call(d=5) == sgc.ERR_SHAPE           # rho * n not a multiple of d
     assert call(k=0) == sgc.ERR_SHAPE
     assert call(k=17) == sgc.ERR_SHAPE          # k > d

@@ -48,13 +48,13 @@ def test_outer_project_matches_oracle(rho, m, n):
     G = rng.standard_normal((m, n)).astype(np.float32)
     ob = sgc.OuterBuffers(rho, m, n)
     ob.Gc.fill_(7.0)
-    sgc.sgc_outer_project(dev(B), dev(G), rho, m, n, ob.Gc, ob.ws)
+    sgc.sgc_outer_project(dev(B), dev(G), 1, rho, m, n, ob.Gc, ob.ws)
     torch.cuda.synchronize()
     ref = orc.outer_project(B, G)
     assert relerr(ob.Gc.cpu().numpy(), ref) < 1e-5
     # reproducible: a second run gives the same bits
     first = ob.Gc.clone()
-    sgc.sgc_outer_project(dev(B), dev(G), rho, m, n, ob.Gc, ob.ws)
+    sgc.sgc_outer_project(dev(B), dev(G), 1, rho, m, n, ob.Gc, ob.ws)
     torch.cuda.synchronize()
     assert torch.equal(first, ob.Gc)
 
@@ -78,10 +78,41 @@ def test_outer_apply_matches_oracle(rho, m, n, d, k):
     h = sgc.hyper(alpha=2.0, lr=0.01, eps=1e-3)
     ob = sgc.OuterBuffers(rho, m, n)
     Wd = dev(W)
-    sgc.sgc_outer_apply(Wd, dev(B), rho, m, n, d, k, dev(sel_m), dev(x), dev(sel_v), dev(z), h, ob.ws)
+    sgc.sgc_outer_apply(Wd, dev(B), 1, rho, m, n, d, k, dev(sel_m), dev(x), dev(sel_v), dev(z), h, ob.ws)
     torch.cuda.synchronize()
     ref = orc.outer_apply(W, B, d, sel_m, x, sel_v, z, alpha=2.0, eps=1e-3, lr=0.01)
     assert relerr(Wd.cpu().numpy() - W, ref.astype(np.float64) - W) < TOL
+
+
+@pytest.mark.parametrize("count,rho,m,n,d,k", [(3, 5, 37, 24, 8, 2), (4, 32, 256, 256, 2048, 31), (2, 70, 96, 128, 64, 4)])
+def test_a_batch_equals_its_matrices_one_by_one(count, rho, m, n, d, k):
+    """Bitwise: the batch index only moves the base pointers."""
+    say("outer batch", count, rho, m, n)
+    rng = np.random.default_rng(count + rho)
+    B = dev(rng.standard_normal((count, rho, m)).astype(np.float32))
+    G = dev(rng.standard_normal((count, m, n)).astype(np.float32))
+    W = rng.standard_normal((count, m, n)).astype(np.float32)
+    Cm = rho * n // d
+    sel = dev(np.stack([rng.permutation(d)[:k] for _ in range(count * Cm)]).astype(np.int32))
+    x = dev(rng.standard_normal((count * Cm, k)).astype(np.float32))
+    z = dev((rng.standard_normal((count * Cm, k)) ** 2).astype(np.float32))
+    h = sgc.hyper(alpha=2.0, lr=0.01)
+    ob = sgc.OuterBuffers(rho, m, n, count=count)
+    one = sgc.OuterBuffers(rho, m, n)
+    sgc.sgc_outer_project(B, G, count, rho, m, n, ob.Gc, ob.ws)
+    Wb = dev(W)
+    sgc.sgc_outer_apply(Wb, B, count, rho, m, n, d, k, sel, x, sel, z, h, ob.ws)
+    torch.cuda.synchronize()
+    for c in range(count):
+        sgc.sgc_outer_project(B[c], G[c], 1, rho, m, n, one.Gc, one.ws)
+        W1 = dev(W[c])
+        lo, hi = c * Cm, (c + 1) * Cm
+        sgc.sgc_outer_apply(W1, B[c], 1, rho, m, n, d, k, sel[lo:hi], x[lo:hi], sel[lo:hi], z[lo:hi], h, one.ws)
+        torch.cuda.synchronize()
+        assert torch.equal(ob.Gc[c], one.Gc), c
+        assert torch.equal(Wb[c], W1), c
+    ref = orc.outer_project(B[1].cpu().numpy(), G[1].cpu().numpy())
+    assert relerr(ob.Gc[1].cpu().numpy(), ref) < 1e-5
 
 
 def test_outer_apply_of_an_empty_update_leaves_the_weights():
@@ -94,7 +125,7 @@ def test_outer_apply_of_an_empty_update_leaves_the_weights():
     zero = np.zeros((C, k), np.float32)
     ob = sgc.OuterBuffers(rho, m, n)
     Wd = dev(W)
-    sgc.sgc_outer_apply(Wd, dev(B), rho, m, n, d, k, dev(sel), dev(zero), dev(sel), dev(zero), sgc.hyper(), ob.ws)
+    sgc.sgc_outer_apply(Wd, dev(B), 1, rho, m, n, d, k, dev(sel), dev(zero), dev(sel), dev(zero), sgc.hyper(), ob.ws)
     torch.cuda.synchronize()
     assert np.array_equal(Wd.cpu().numpy(), W)
 
@@ -185,7 +216,7 @@ def test_llama_attention_matrix_full_size_sampled():
     G = rng.standard_t(3.0, size=(m, n)).astype(np.float32) * np.float32(1e-3)
     ob = sgc.OuterBuffers(rho, m, n)
     Bd = dev(B)
-    sgc.sgc_outer_project(Bd, dev(G), rho, m, n, ob.Gc, ob.ws)
+    sgc.sgc_outer_project(Bd, dev(G), 1, rho, m, n, ob.Gc, ob.ws)
     torch.cuda.synchronize()
     Gc = ob.Gc.cpu().numpy()
     cols = np.array([0, 1, 127, 128, 2049, 4095])
@@ -198,7 +229,7 @@ def test_llama_attention_matrix_full_size_sampled():
     W = rng.standard_normal((m, n)).astype(np.float32)
     Wd = dev(W)
     h = sgc.hyper(alpha=2.0, lr=0.01, eps=1e-3)
-    sgc.sgc_outer_apply(Wd, Bd, rho, m, n, d, k, dev(sel_m), dev(x), dev(sel_m), dev(z), h, ob.ws)
+    sgc.sgc_outer_apply(Wd, Bd, 1, rho, m, n, d, k, dev(sel_m), dev(x), dev(sel_m), dev(z), h, ob.ws)
     torch.cuda.synchronize()
     N = np.zeros((C, d))
     for c in range(C):
