@@ -25,74 +25,92 @@ __device__ __forceinline__ float4 outer_keep(bool keep, float4 v)
 }
 constexpr int OUTER_FLIGHT = 8;  // row pairs in flight per wavefront
 
-// Partial products of one slice of rows of G: out[s][a][j] = sum over the slice's rows i of B[a][i] G[i][j]
-// (the slices are summed in order by outer_reduce_kernel; a single slice writes Gc itself).
-// grid (column strips, slices of 32 * NG rows, blocks of 32 * RBLK rows of B). The slice is cut in groups of
-// 8 rows, group q going to wavefront q % 4 (NG groups each). Every load of the workgroup is issued at
-// the start and none sits under a branch (addresses past an end are clamped, the values replaced by
-// zero), so the MFMAs of a group start as soon as that group's rows have arrived while the later
-// groups are still in flight:
+// Partial products of a run of rows of G: out[g][a][j] = sum over the rows i of run g of B[a][i] G[i][j]
+// (the runs are summed in order by outer_reduce_kernel; a single run writes Gc itself).
+// grid (column strips, runs, matrices of the batch x blocks of 32 * RBLK rows of B). A run is `reps`
+// consecutive slices of 32 * NG rows; the workgroup takes them one after the other into the same
+// accumulators. A slice is cut in groups of 8 rows, group q going to wavefront q % 4 (NG groups each):
 //   - the slice of B goes through the LDS transposed (Bs[row of the slice][row of B], read back one
 //     float per lane and MFMA);
 //   - for the group at row k, lanes 0-31 read rows k .. k + 3 of G and lanes 32-63 rows k + 4 .. k + 7,
 //     16 bytes each; MFMA j sums the depths k + j and k + 4 + j.
-// The four wavefronts' accumulators are added in wavefront order at the end.
-template <int RBLK, int NG, bool BVEC>
+// Two sets of registers and two LDS buffers are used in turn: all loads of the next slice are issued
+// before the MFMAs of the current one, and no load sits under a branch (addresses past an end are
+// clamped, the values replaced by zero), so waits are counted and a group's MFMAs start as soon as its
+// rows have arrived. One barrier per slice. The four wavefronts' accumulators are added in wavefront
+// order at the end.
+// FULL: m a multiple of the slice, rho of the block of rows of B, n of 128 (and offsets that fit 32 bits):
+// no clamps or selects, and every address is a wavefront-uniform base plus a per-lane offset that
+// never changes, so the loads cost no vector arithmetic (which would take its time from the MFMAs).
+template <int RBLK, int NG, bool BVEC, bool FULL>
 __global__ __launch_bounds__(256) void outer_project_kernel(const float *__restrict__ B, const float *__restrict__ G,
                                                             int32_t rho, int32_t m, int32_t n, int32_t rho_blocks,
-                                                            float *__restrict__ out)
+                                                            int32_t reps, float *__restrict__ out)
 {
-    extern __shared__ __attribute__((aligned(16))) float outer_lds[]; // Bs, later the accumulators of wavefronts 1..3
-    constexpr int RB = 32 * RBLK, LDB = RB + 1, SLICE = 32 * NG, PIECES = RBLK * NG;
+    extern __shared__ __attribute__((aligned(16))) float outer_lds[]; // Bs x 2, later the accumulators of wavefronts 1..3
+    constexpr int RB = 32 * RBLK, LDB = RB + 1, SLICE = 32 * NG, PIECES = RBLK * NG, BSZ = SLICE * LDB;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, l32 = lane & 31, lhalf = lane >> 5;
     const int32_t mat = blockIdx.z / rho_blocks; // matrix of the batch
-    const int32_t n0 = blockIdx.x * OUTER_STRIP, s = blockIdx.y, rho0 = (blockIdx.z - mat * rho_blocks) * RB;
-    const int32_t m0 = s * SLICE;
-    const int32_t mend = m0 + SLICE < m ? m0 + SLICE : m;
+    const int32_t n0 = blockIdx.x * OUTER_STRIP, rho0 = (blockIdx.z - mat * rho_blocks) * RB;
     B += (int64_t)mat * rho * m;
     G += (int64_t)mat * m * n;
-    out += (int64_t)mat * gridDim.y * rho * n;
-
-    // 16-byte pieces of the slice of B: piece e is row e / (SLICE / 4) of the block, depths 4 (e % (SLICE / 4)) ..
-    float4 bp[PIECES];
-#pragma unroll
-    for (int i = 0; i < PIECES; ++i) {
-        const int e = tid + 256 * i;
-        const int32_t a = rho0 + e / (SLICE / 4), k = m0 + 4 * (e % (SLICE / 4));
-        const float *row = B + (int64_t)(a < rho ? a : rho - 1) * m;
-        if (BVEC) {
-            bp[i] = *reinterpret_cast<const float4 *>(row + (k + 3 < m ? k : m - 4));
-        } else {
-            bp[i].x = row[k < m ? k : m - 1];
-            bp[i].y = row[k + 1 < m ? k + 1 : m - 1];
-            bp[i].z = row[k + 2 < m ? k + 2 : m - 1];
-            bp[i].w = row[k + 3 < m ? k + 3 : m - 1];
-        }
-    }
-    __builtin_amdgcn_sched_barrier(0); // B first: its wait then leaves the loads of G in flight
+    out += ((int64_t)mat * gridDim.y + blockIdx.y) * rho * n;
     const int32_t col = n0 + 4 * l32;
     const bool col_ok = col < n;
     const float *gcol = G + (col_ok ? col : n - 4);
-    float4 g[NG][4];
-#pragma unroll
-    for (int q = 0; q < NG; ++q)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int32_t row = m0 + 8 * (4 * q + w) + 4 * lhalf + j;
-            g[q][j] = load_once_f4(gcol + (int64_t)(row < m ? row : m - 1) * n);
-        }
-    __builtin_amdgcn_sched_barrier(0);
+    const int32_t slices = (m + SLICE - 1) / SLICE;
+    const int32_t s_first = blockIdx.y * reps;
+    const int32_t s_end = s_first + reps < slices ? s_first + reps : slices;
+
+    float4 bp[2][PIECES], g[2][NG][4];
+    const int wu = __builtin_amdgcn_readfirstlane(w);
+    const uint32_t g_lane = (uint32_t)(4 * lhalf * n + col); // FULL: offsets in floats from a uniform base
+    uint32_t b_lane[PIECES];
 #pragma unroll
     for (int i = 0; i < PIECES; ++i) {
         const int e = tid + 256 * i;
-        const int32_t al = e / (SLICE / 4), kl = 4 * (e % (SLICE / 4));
-        const bool a_ok = rho0 + al < rho;
-        outer_lds[(kl + 0) * LDB + al] = (a_ok && m0 + kl + 0 < mend) ? bp[i].x : 0.f;
-        outer_lds[(kl + 1) * LDB + al] = (a_ok && m0 + kl + 1 < mend) ? bp[i].y : 0.f;
-        outer_lds[(kl + 2) * LDB + al] = (a_ok && m0 + kl + 2 < mend) ? bp[i].z : 0.f;
-        outer_lds[(kl + 3) * LDB + al] = (a_ok && m0 + kl + 3 < mend) ? bp[i].w : 0.f;
+        b_lane[i] = (uint32_t)((rho0 + e / (SLICE / 4)) * m + 4 * (e % (SLICE / 4)));
     }
-    __syncthreads();
+    auto fetch = [&](int set, int32_t s) {
+        const int32_t m0 = s * SLICE;
+        if constexpr (FULL) {
+#pragma unroll
+            for (int i = 0; i < PIECES; ++i)
+                bp[set][i] = *reinterpret_cast<const float4 *>(B + m0 + b_lane[i]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int q = 0; q < NG; ++q)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    g[set][q][j] = load_once_f4(G + (int64_t)(m0 + 8 * (4 * q + wu) + j) * n + g_lane);
+            __builtin_amdgcn_sched_barrier(0);
+            return;
+        }
+        // 16-byte pieces of the slice of B: piece e is row e / (SLICE / 4) of the block, depths 4 (e % (SLICE / 4)) ..
+#pragma unroll
+        for (int i = 0; i < PIECES; ++i) {
+            const int e = tid + 256 * i;
+            const int32_t a = rho0 + e / (SLICE / 4), k = m0 + 4 * (e % (SLICE / 4));
+            const float *row = B + (int64_t)(a < rho ? a : rho - 1) * m;
+            if (BVEC) {
+                bp[set][i] = *reinterpret_cast<const float4 *>(row + (k + 3 < m ? k : m - 4));
+            } else {
+                bp[set][i].x = row[k < m ? k : m - 1];
+                bp[set][i].y = row[k + 1 < m ? k + 1 : m - 1];
+                bp[set][i].z = row[k + 2 < m ? k + 2 : m - 1];
+                bp[set][i].w = row[k + 3 < m ? k + 3 : m - 1];
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0); // B first: its wait then leaves the loads of G in flight
+#pragma unroll
+        for (int q = 0; q < NG; ++q)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int32_t row = m0 + 8 * (4 * q + w) + 4 * lhalf + j;
+                g[set][q][j] = load_once_f4(gcol + (int64_t)(row < m ? row : m - 1) * n);
+            }
+        __builtin_amdgcn_sched_barrier(0);
+    };
 
     floatx16 acc[RBLK][4];
 #pragma unroll
@@ -102,24 +120,63 @@ __global__ __launch_bounds__(256) void outer_project_kernel(const float *__restr
 #pragma unroll
             for (int v = 0; v < 16; ++v)
                 acc[rb][e][v] = 0.f;
+
+    auto work = [&](int set, int32_t s) { // slice s is in register set `set`; LDS buffer `set`
+        const int32_t m0 = s * SLICE;
+        float *bs = outer_lds + set * BSZ;
 #pragma unroll
-    for (int q = 0; q < NG; ++q) {
+        for (int i = 0; i < PIECES; ++i) {
+            const int e = tid + 256 * i;
+            const int32_t al = e / (SLICE / 4), kl = 4 * (e % (SLICE / 4));
+            if constexpr (FULL) {
+                bs[(kl + 0) * LDB + al] = bp[set][i].x;
+                bs[(kl + 1) * LDB + al] = bp[set][i].y;
+                bs[(kl + 2) * LDB + al] = bp[set][i].z;
+                bs[(kl + 3) * LDB + al] = bp[set][i].w;
+                continue;
+            }
+            const bool a_ok = rho0 + al < rho;
+            bs[(kl + 0) * LDB + al] = (a_ok && m0 + kl + 0 < m) ? bp[set][i].x : 0.f;
+            bs[(kl + 1) * LDB + al] = (a_ok && m0 + kl + 1 < m) ? bp[set][i].y : 0.f;
+            bs[(kl + 2) * LDB + al] = (a_ok && m0 + kl + 2 < m) ? bp[set][i].z : 0.f;
+            bs[(kl + 3) * LDB + al] = (a_ok && m0 + kl + 3 < m) ? bp[set][i].w : 0.f;
+        }
+        __syncthreads();
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int32_t kl = 8 * (4 * q + w) + 4 * lhalf + j;
-            // rows past the end of the matrix were read from a clamped address: they count as zero
-            // (their depths of Bs are zero too, but zero times a non-finite entry would not be)
-            const float4 gv = outer_keep(m0 + kl < mend, g[q][j]);
+        for (int q = 0; q < NG; ++q) {
 #pragma unroll
-            for (int rb = 0; rb < RBLK; ++rb) {
-                const float a = outer_lds[kl * LDB + rb * 32 + l32];
-                acc[rb][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, gv.x, acc[rb][0], 0, 0, 0);
-                acc[rb][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, gv.y, acc[rb][1], 0, 0, 0);
-                acc[rb][2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, gv.z, acc[rb][2], 0, 0, 0);
-                acc[rb][3] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, gv.w, acc[rb][3], 0, 0, 0);
+            for (int j = 0; j < 4; ++j) {
+                const int32_t kl = 8 * (4 * q + w) + 4 * lhalf + j;
+                // rows past the end of the matrix were read from a clamped address: they count as zero
+                // (their depths of Bs are zero too, but zero times a non-finite entry would not be)
+                const float4 gv = FULL ? g[set][q][j] : outer_keep(m0 + kl < m, g[set][q][j]);
+#pragma unroll
+                for (int rb = 0; rb < RBLK; ++rb) {
+                    const float a = bs[kl * LDB + rb * 32 + l32];
+                    acc[rb][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, gv.x, acc[rb][0], 0, 0, 0);
+                    acc[rb][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, gv.y, acc[rb][1], 0, 0, 0);
+                    acc[rb][2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, gv.z, acc[rb][2], 0, 0, 0);
+                    acc[rb][3] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, gv.w, acc[rb][3], 0, 0, 0);
+                }
             }
         }
+    };
+
+    // A buffer of Bs written for slice s is read until the barrier of slice s + 1 and written again for
+    // slice s + 2, after that barrier.
+    // (pairs of slices in the loop and a possible last one after it: no branch around the MFMAs inside the
+    // loop, so the accumulators stay where they are)
+    fetch(0, s_first);
+    int32_t s2 = s_first;
+    for (; s2 + 1 < s_end; s2 += 2) {
+        fetch(1, s2 + 1);
+        work(0, s2);
+        if (s2 + 2 < s_end)
+            fetch(0, s2 + 2);
+        work(1, s2 + 1);
     }
+    if (s2 < s_end)
+        work(0, s2);
 
     // wavefronts 1..3 hand their accumulators to wavefront 0, which adds them in wavefront order
     constexpr int PER_WAVE = RBLK * 4 * 16 * 64;
@@ -151,8 +208,7 @@ __global__ __launch_bounds__(256) void outer_project_kernel(const float *__restr
                 }
                 const int32_t a = rho0 + rb * 32 + 8 * (v >> 2) + (v & 3) + 4 * lhalf;
                 if (a < rho)
-                    *reinterpret_cast<float4 *>(out + ((int64_t)s * rho + a) * n + col) =
-                        make_float4(o[0], o[1], o[2], o[3]);
+                    *reinterpret_cast<float4 *>(out + (int64_t)a * n + col) = make_float4(o[0], o[1], o[2], o[3]);
             }
     }
 }
@@ -205,8 +261,10 @@ __global__ __launch_bounds__(256) void outer_zero_kernel(float *__restrict__ p, 
 // Per block: the rho-deep product of the 32 x 128 tile on the matrix cores, then the tile of W is updated
 // and stored; the loads of the next block's tile of W and of its values of B are issued before the
 // product, so they are in flight while the matrix cores work. RHO32: rho <= 32, the strip of Nd is read
-// once per wavefront and kept in registers for all its blocks. FULL: m % 32 == 0 and n % 128 == 0, no
-// bounds checks (and so no branches around the loads and stores).
+// once per wavefront and kept in registers for all its blocks. FULL: m % 32 == 0, n % 128 == 0 and, with
+// RHO32, rho == 32: no bounds checks (so no branches around the loads and stores), and every address is
+// a wavefront-uniform base plus a per-lane offset that never changes, which leaves the vector
+// arithmetic to the update itself.
 template <bool RHO32, bool FULL>
 __global__ __launch_bounds__(256, 1) void outer_back_kernel(float *__restrict__ W, const float *__restrict__ B,
                                                             const float *__restrict__ Nd, int32_t rho, int32_t m,
@@ -232,7 +290,20 @@ __global__ __launch_bounds__(256, 1) void outer_back_kernel(float *__restrict__ 
     // the next block's loads (no copies, so nothing waits for a load before its values are needed)
     float4 wt[2][16];
     float bt[2][RHO32 ? 16 : 1];
+    const int wu = __builtin_amdgcn_readfirstlane(w);
+    const uint32_t w_lane = (uint32_t)(4 * lhalf * n + col), b_lane = (uint32_t)(lhalf * m + l32);
     auto fetch = [&](int set, int32_t i0) { // the tile of W at rows i0.. and, RHO32, its values of B
+        if constexpr (FULL) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                wt[set][v] = load_once_f4(W + (int64_t)(i0 + 8 * (v >> 2) + (v & 3)) * n + w_lane);
+            if (RHO32) {
+#pragma unroll
+                for (int u = 0; u < 16; ++u)
+                    bt[set][u] = (B + (int64_t)(2 * u) * m + i0)[b_lane];
+            }
+            return;
+        }
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int32_t row = i0 + 8 * (v >> 2) + (v & 3) + 4 * lhalf;
@@ -255,9 +326,9 @@ __global__ __launch_bounds__(256, 1) void outer_back_kernel(float *__restrict__ 
         }
     };
     const int32_t first = blockIdx.y * blocks;
-    if ((first + w) * 32 < m && w < blocks)
-        fetch(0, (first + w) * 32);
-    for (int32_t q2 = w; q2 < blocks; q2 += 8) {
+    if ((first + wu) * 32 < m && wu < blocks)
+        fetch(0, (first + wu) * 32);
+    for (int32_t q2 = wu; q2 < blocks; q2 += 8) {
 #pragma unroll
       for (int ph = 0; ph < 2; ++ph) {
         const int32_t q = q2 + 4 * ph;
@@ -315,7 +386,14 @@ __global__ __launch_bounds__(256, 1) void outer_back_kernel(float *__restrict__ 
                 o.y -= lr * acc[1][v];
                 o.z -= lr * acc[2][v];
                 o.w -= lr * acc[3][v];
-                *reinterpret_cast<float4 *>(W + (int64_t)row * n + col) = o;
+                if constexpr (FULL) {
+                    typedef float floatx4_t __attribute__((ext_vector_type(4)));
+                    const floatx4_t ov = {o.x, o.y, o.z, o.w};
+                    __builtin_nontemporal_store(
+                        ov, reinterpret_cast<floatx4_t *>(W + (int64_t)(i0 + 8 * (v >> 2) + (v & 3)) * n + w_lane));
+                }
+                else
+                    *reinterpret_cast<float4 *>(W + (int64_t)row * n + col) = o;
             }
         }
       }
@@ -323,8 +401,9 @@ __global__ __launch_bounds__(256, 1) void outer_back_kernel(float *__restrict__ 
 }
 
 // ---- host side ----
-// how the rows of G are cut in slices: enough workgroups to fill the chip with slices of 32, 64, 128 or
-// 256 rows (1, 2, 4 or 8 groups of 8 rows for each of the four wavefronts)
+// how the rows of G are cut: slices of 128 rows (64 with more than 32 rows of B; fewer when the matrix is too
+// small to fill the chip with those), and runs of consecutive slices per workgroup, as long as possible while at least 512
+// workgroups remain; with a large batch a run is the whole matrix and nothing partial is written
 OuterPlan outer_plan(int32_t count, int32_t rho, int32_t m, int32_t n)
 {
     OuterPlan pl{};
@@ -332,11 +411,15 @@ OuterPlan outer_plan(int32_t count, int32_t rho, int32_t m, int32_t n)
     pl.strips = (n + OUTER_STRIP - 1) / OUTER_STRIP;
     pl.rho_blocks = (rho + 32 * pl.rblk - 1) / (32 * pl.rblk);
     const int64_t per_slice = (int64_t)pl.strips * pl.rho_blocks * count;
-    int64_t slice = 256;
+    int64_t slice = 64; // two sets of a slice's rows in registers, and room for two workgroups per CU
     while (slice > 32 && ((m + slice - 1) / slice) * per_slice < 512)
         slice >>= 1;
+    const int64_t slices = (m + slice - 1) / slice;
+    int64_t reps = slices * per_slice / 512;
+    reps = reps < 1 ? 1 : (reps > slices ? slices : reps);
     pl.slice = (int32_t)slice;
-    pl.slices = (int32_t)((m + slice - 1) / slice);
+    pl.reps = (int32_t)reps;
+    pl.slices = (int32_t)((slices + reps - 1) / reps); // runs
     const size_t partial = pl.slices > 1 ? (size_t)count * pl.slices * rho * n * sizeof(float) : 0;
     const size_t dense = (size_t)count * rho * n * sizeof(float);
     pl.ws_bytes = ((partial > dense ? partial : dense) + 255) & ~(size_t)255;
@@ -349,31 +432,35 @@ hipError_t launch_outer_project(const float *B, const float *G, int32_t count, i
     const OuterPlan pl = outer_plan(count, rho, m, n);
     float *out = pl.slices > 1 ? static_cast<float *>(ws) : Gc;
     const dim3 grid((unsigned)pl.strips, (unsigned)pl.slices, (unsigned)(pl.rho_blocks * count));
-    const size_t stage = (size_t)pl.slice * (32 * pl.rblk + 1) * sizeof(float);
+    const size_t stage = (size_t)2 * pl.slice * (32 * pl.rblk + 1) * sizeof(float);
     const size_t handoff = (size_t)3 * pl.rblk * 4 * 16 * 64 * sizeof(float);
     const size_t smem = stage > handoff ? stage : handoff;
     const bool b_vec = m % 4 == 0 && ((uintptr_t)B & 15u) == 0;
-    typedef void (*Kernel)(const float *, const float *, int32_t, int32_t, int32_t, int32_t, float *);
+    const bool full = b_vec && m % pl.slice == 0 && rho % (32 * pl.rblk) == 0 && n % OUTER_STRIP == 0 &&
+                      (int64_t)rho * m < (1ll << 29) && (int64_t)n * 8 < (1ll << 29);
+    typedef void (*Kernel)(const float *, const float *, int32_t, int32_t, int32_t, int32_t, int32_t, float *);
     Kernel kern = nullptr;
     const int ng = pl.slice / 32;
 #define SGC_OUTER_PICK(R, N) \
     if (pl.rblk == R && ng == N) \
-        kern = b_vec ? outer_project_kernel<R, N, true> : outer_project_kernel<R, N, false>;
-    SGC_OUTER_PICK(1, 1) SGC_OUTER_PICK(1, 2) SGC_OUTER_PICK(1, 4) SGC_OUTER_PICK(1, 8)
-    SGC_OUTER_PICK(2, 1) SGC_OUTER_PICK(2, 2) SGC_OUTER_PICK(2, 4) SGC_OUTER_PICK(2, 8)
+        kern = full ? outer_project_kernel<R, N, true, true> \
+                    : (b_vec ? outer_project_kernel<R, N, true, false> : outer_project_kernel<R, N, false, false>);
+    SGC_OUTER_PICK(1, 1) SGC_OUTER_PICK(1, 2) SGC_OUTER_PICK(1, 4)
+    SGC_OUTER_PICK(2, 1) SGC_OUTER_PICK(2, 2)
 #undef SGC_OUTER_PICK
     if (!kern)
         return hipErrorInvalidValue;
-    static bool raised[3][9][2];
-    if (smem > 48 * 1024 && !raised[pl.rblk][ng][b_vec ? 1 : 0]) {
+    static bool raised[3][5][3];
+    const int variant = full ? 2 : (b_vec ? 1 : 0);
+    if (smem > 48 * 1024 && !raised[pl.rblk][ng][variant]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess)
             return e;
-        raised[pl.rblk][ng][b_vec ? 1 : 0] = true;
+        raised[pl.rblk][ng][variant] = true;
     }
     ProfileScope prof(KC_OUTER_PROJECT, s);
-    kern<<<grid, 256, smem, s>>>(B, G, rho, m, n, pl.rho_blocks, out);
+    kern<<<grid, 256, smem, s>>>(B, G, rho, m, n, pl.rho_blocks, pl.reps, out);
     if (pl.slices > 1) {
         const int64_t count4 = (int64_t)rho * n / 4;
         outer_reduce_kernel<<<dim3((unsigned)((count4 + 255) / 256), (unsigned)count), 256, 0, s>>>(out, pl.slices,
@@ -405,7 +492,8 @@ hipError_t launch_outer_apply(float *W, const float *B, int32_t count, int32_t r
         blocks -= 4;
     const dim3 grid((unsigned)strips, (unsigned)((row_blocks + blocks - 1) / blocks), (unsigned)count);
     ProfileScope prof(KC_OUTER_APPLY, s);
-    const bool full = m % 32 == 0 && n % OUTER_STRIP == 0;
+    const bool full = m % 32 == 0 && n % OUTER_STRIP == 0 && (rho >= 32) && (int64_t)n * 8 < (1ll << 29) &&
+                      (int64_t)m * 2 < (1ll << 29);
     if (rho <= 32) {
         if (full)
             outer_back_kernel<true, true><<<grid, 256, 0, s>>>(W, B, Nd, rho, m, n, blocks, lr);

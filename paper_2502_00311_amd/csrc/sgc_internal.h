@@ -83,7 +83,8 @@ struct OuterPlan {
     int32_t strips;     // column strips of 128
     int32_t rho_blocks; // blocks of 32 * rblk rows of B
     int32_t slice;      // rows of G per slice
-    int32_t slices;
+    int32_t reps;       // consecutive slices per workgroup (a run)
+    int32_t slices;     // runs: partial results per matrix
     size_t ws_bytes;
 };
 OuterPlan outer_plan(int32_t count, int32_t rho, int32_t m, int32_t n);
