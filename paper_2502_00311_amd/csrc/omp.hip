@@ -7,6 +7,9 @@
 //                  position tiles of resident rows, corr_kernel for everything else). P is never
 //                  written: the epilogue scales by 1/||A_:i||, leaves out selected positions and keeps
 //                  the two best (score, position) pairs of every position tile per right-hand side.
+//                  Optionally (a flag of the matrix) the same contraction on the bfloat16 matrix cores
+//                  from operands split in two bfloat16 terms: corr_split_kernel, or the bfloat16 form
+//                  of corr_pipelined_kernel on full tiles.
 //   pick / factor / residual   re-score the near-maximal candidates in double (so the argmax does
 //                  not depend on float rounding), append the winning column, extend F = L^-H
 //                  (App. B) by mat-vecs only, and recompute the residual y - A_Lambda x in double.
@@ -546,7 +549,7 @@ __device__ __forceinline__ void static_for(F &&f)
     }
 }
 
-constexpr int CORRP_BM = 256, CORRP_BN = 128;
+constexpr int CORRP_BM = 256;
 
 // NB = 2: the 256 x 128 tile described above. NB = 1: a 256 x 64 tile for at most 64 right-hand sides
 // (each wavefront 128 x 32, groups of 16 MFMAs; the LDS write and the global load of a staging piece
