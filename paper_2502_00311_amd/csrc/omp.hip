@@ -50,21 +50,31 @@ OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_
     w.cols = (float *)take(sizeof(float) * (size_t)N * k * r);
     w.partial = (uint64_t *)take(sizeof(uint64_t) * (size_t)N * w.tiles_m * 2);
     w.bitmap = (uint32_t *)take(sizeof(uint32_t) * (size_t)N * w.words);
-    // panel of a generated matrix: at most 64 MiB (stays in the 256 MiB memory-side cache), whole tiles
+    // Rows of a generated matrix, in whole tiles. A matrix of at most 64 MiB gets a panel of its own (it
+    // then stays in the 256 MiB memory-side cache). A larger one is written out whole where the column
+    // copies would be, if it is no larger than they are (d <= N k; the copies are not needed once the
+    // rows are resident), else it goes through a 64 MiB panel that is refilled in every iteration.
+    int64_t small_rows = ((int64_t)64 << 20) / ((int64_t)r * 4);
+    small_rows = small_rows / 256 * 256;
+    if (small_rows < 256)
+        small_rows = 256;
     {
-        int64_t rows = ((int64_t)64 << 20) / ((int64_t)r * 4);
-        rows = rows / 256 * 256;
-        if (rows < 256)
-            rows = 256;
         const int64_t dpad = ((int64_t)d + 255) / 256 * 256;
-        w.panel_rows = (int32_t)(rows < dpad ? rows : dpad);
-        w.panel = (float *)take(sizeof(float) * (size_t)w.panel_rows * r);
+        if (small_rows > dpad)
+            small_rows = dpad;
+        if (dpad > small_rows && dpad <= (int64_t)N * k) {
+            w.panel_rows = (int32_t)dpad;
+            w.panel = w.cols;
+        } else {
+            w.panel_rows = (int32_t)small_rows;
+            w.panel = (float *)take(sizeof(float) * (size_t)small_rows * r);
+        }
     }
     // bfloat16 planes of the matrix rows for the screening contraction: the whole matrix if that is at
-    // most 2 GiB, else one panel's worth (a stored matrix beyond that is split inside the contraction)
+    // most 2 GiB, else a 64 MiB panel's worth (larger resident matrices then keep the float contraction)
     {
         const int64_t dpad = ((int64_t)d + 127) / 128 * 128;
-        w.a16_rows = dpad * r * 4 <= ((int64_t)2 << 30) ? (int32_t)dpad : w.panel_rows;
+        w.a16_rows = dpad * r * 4 <= ((int64_t)2 << 30) ? (int32_t)dpad : (int32_t)small_rows;
         w.a16 = (uint16_t *)take(sizeof(float) * (size_t)w.a16_rows * r);
     }
     w.wv = (double *)take(sizeof(double) * (size_t)N * k);
@@ -1597,18 +1607,20 @@ static hipError_t omp_iterations(const OmpPlan &pl, bool whole_matrix_panel, con
 hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k, int32_t *sel, float *x,
                       const OmpWorkspace &ws, hipStream_t s, const float *y_fit, float *z)
 {
-    // A generated matrix is regenerated inside the contraction when few right-hand-side tiles share
-    // it; with many tiles (each would regenerate all of A) it is produced into a cache-sized scratch,
-    // once per call if it fits, else panel by panel in every iteration, and consumed from there.
+    // A generated matrix is written out once per call when the workspace has room for all of it. One
+    // that does not fit is regenerated inside the contraction when few right-hand-side tiles share it;
+    // with many tiles (each would regenerate all of A) it is produced panel by panel into a cache-sized
+    // scratch in every iteration, and consumed from there.
     // Stored rows in full tiles take the pipelined kernel (256-row tiles), everything else the
     // general one (128-row tiles).
     OmpPlan pl{};
-    pl.panels = A.generated && (N + CORR_BN - 1) / CORR_BN >= 4;
+    pl.panels = A.generated && (ws.panel_rows >= A.d || (N + CORR_BN - 1) / CORR_BN >= 4);
     pl.pipelined = (!A.generated || pl.panels) && corr_pipelined_ok(A, N, ws.panel_rows);
     // the bfloat16 screening contraction needs resident rows; a matrix regenerated inside the
     // contraction keeps the float kernel (its time is the generator's anyway)
     pl.screen = (A.flags & SGC_MATRIX_FLAG_SCREEN_BF16) && A.r % 32 == 0 &&
-                (A.generated ? pl.panels : ws.a16_rows >= A.d);
+                (A.generated ? pl.panels && ws.a16_rows >= (ws.panel_rows < A.d ? ws.panel_rows : A.d)
+                             : ws.a16_rows >= A.d);
     pl.screen_pipelined = pl.screen && N > 64 && corr_pipelined_ok(A, N, ws.panel_rows);
     if (pl.screen)
         pl.pipelined = false;

@@ -42,13 +42,15 @@ struct OmpWorkspace {
     uint16_t *res16;   // the same memory holding the residuals split in bfloat16 pairs (screening
                        // contraction; [N] rows of 4 r bytes, format in omp.hip)
     uint16_t *a16;     // [a16_rows] rows of At split the same way
-    int32_t a16_rows;  // d (padded to whole tiles) if the matrix fits, else the panel's rows
+    int32_t a16_rows;  // d (padded to whole tiles) if the matrix fits 2 GiB, else a 64 MiB panel's rows
     float *cols;       // [N][k][r] selected columns of A
     uint64_t *partial; // [N][tiles_m][2] best and second-best packed (score, position) per tile
     uint32_t *bitmap;  // [N][words] selected positions
     double *wv;        // [N][k] inner products of the new column with the earlier selections
     double *gb;        // [N][2] squared norm of the new column, its inner product with y
-    float *panel;      // [panel_rows][r] rows of a generated matrix, refilled every iteration
+    float *panel;      // [panel_rows][r] rows of a generated matrix: all of them (written once per call; a
+                       // matrix above 64 MiB then lies in the memory of `cols`, which is not needed with
+                       // resident rows) or a 64 MiB panel refilled in every iteration
     int32_t panel_rows; // multiple of 256
     int32_t words;     // bitmap words per right-hand side
     int32_t tiles_m;

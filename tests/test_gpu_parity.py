@@ -217,6 +217,8 @@ def run_omp(Y, A, k):
     (2, 2048, 512, 320, "stored"),   # k > 256: sixteen rows of F per lane in the update kernel
     (3, 32768, 64, 5, "stored"),     # many full position tiles, few right-hand sides: the half-width pipelined tile
     (64, 32768, 128, 3, "stored"),   # the same tile completely filled
+    (3, 20000, 1024, 4, "philox"),   # a generated matrix too large to write out (80 MB, few right-hand sides):
+                                     # regenerated inside the contraction and the selection kernel
 ])
 def test_omp_matches_oracle_on_noisy_right_hand_sides(N, d, r, k, mode):
     say("omp", N, d, r, k, mode)
@@ -230,8 +232,9 @@ def test_omp_matches_oracle_on_noisy_right_hand_sides(N, d, r, k, mode):
 
 
 @pytest.mark.parametrize("N,d,r,k", [
-    (600, 3000, 64, 6),      # many right-hand-side tiles: the generated matrix goes through one panel
-    (520, 2500, 8192, 3),    # long columns: two panels, the second one ragged
+    (600, 3000, 64, 6),      # the generated matrix is written out once (it fits the cache-sized panel)
+    (520, 2500, 8192, 3),    # long columns, 82 MB: two panels refilled in every iteration, the second one ragged
+    (400, 20480, 1024, 52),  # 80 MB but no larger than the column copies (d <= N k): written out whole in their place
 ])
 def test_omp_generated_matrix_with_many_right_hand_sides(N, d, r, k):
     say("omp panels", N, d, r, k)
