@@ -17,6 +17,9 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream). Every call only
  *     enqueues work on that stream and returns; results are ready after the stream is
  *     synchronised. Calls on one stream execute in order.
+ *   - No call allocates device memory, synchronises, or enqueues a memset: calls may be recorded in a
+ *     HIP graph (stream capture) and replayed. Scalars that depend on the step number are computed
+ *     on the host, so a captured sgc_adam_compressed replays the step it was captured for.
  *   - Arguments are validated on the host before anything is launched. On error nothing is
  *     launched and a negative sgc_status is returned; the library never aborts or throws.
  *   - Work goes to the device that is current when a call is made; all pointers of a call must

@@ -1,0 +1,73 @@
+"""The library under HIP graph capture: a whole step (every entry point allocates nothing and records
+no memset node) is captured once and replayed with new gradients; every replay must equal the eager
+step bit for bit, with eager work and synchronisations between the replays."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_00311_amd import sgc, synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+@pytest.mark.parametrize("shared,C,d,r,k", [
+    (False, 3, 4096, 256, 24), (True, 3, 4096, 256, 24),
+    (False, 300, 1024, 64, 4),     # 600 right-hand sides: the recovery forks onto its second stream inside the capture
+], ids=["two_supports", "shared_support", "two_streams"])
+def test_captured_step_replays_equal_eager_steps(shared, C, d, r, k):
+    w = synth.shrink(synth.CFG2, C=C, d=d, r=r, k=k)
+    C, d, r, k = w.C, w.d, w.r, w.k
+    At = synth.gaussian_matrix(5, d, r)
+    A = sgc.Matrix(d, r, At=dev(At))
+    A.inv_colnorm = torch.empty(d, dtype=torch.float32, device=DEV)
+    sgc.sgc_matrix_colnorms(A, A.inv_colnorm)
+    h = sgc.hyper(alpha=2.0)
+    grads = [dev(synth.gradients(w, t)) for t in range(1, 5)]
+    W0 = dev(synth.weights(w))
+
+    # eager reference: four steps from zero state (the step number is a host argument: the graph is
+    # captured for step 2 and replayed as step 2 on every state it is given)
+    ref = []
+    buf = sgc.StepBuffers(C, d, r, k)
+    for g in grads:
+        buf.m.zero_()
+        buf.v.zero_()
+        W = W0.clone()
+        sgc.step(g, W, buf, A, 2, h, shared_support=shared)
+        torch.cuda.synchronize()
+        ref.append((W.clone(), buf.m.clone(), buf.v.clone(), buf.sel.clone(), buf.x.clone()))
+
+    gin = torch.empty_like(grads[0])
+    Wg = W0.clone()
+    gbuf = sgc.StepBuffers(C, d, r, k)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                 # warm-up on the capture stream, eager
+        gin.copy_(grads[0])
+        sgc.step(gin, Wg, gbuf, A, 2, h, shared_support=shared)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        sgc.step(gin, Wg, gbuf, A, 2, h, shared_support=shared)
+    for i, g in enumerate(grads):
+        say("  replay", i)
+        gin.copy_(g)                              # eager work between the replays
+        gbuf.m.zero_()
+        gbuf.v.zero_()
+        Wg.copy_(W0)
+        graph.replay()
+        torch.cuda.synchronize()
+        W, m, v, sel, x = ref[i]
+        rows = C if shared else 2 * C
+        assert torch.equal(Wg, W) and torch.equal(gbuf.m, m) and torch.equal(gbuf.v, v), i
+        assert torch.equal(gbuf.sel[:rows], sel[:rows]) and torch.equal(gbuf.x, x), i
