@@ -23,7 +23,8 @@ sys.path.insert(0, ROOT)
 MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense float matrix peak
 # HBM bytes per launch of the correlation kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (profiles/), keyed by workload name; None until measured.
-MEASURED_TRAFFIC = {"cfg2_64x65536": 5.528e8}  # profiles/cfg2_corr_kernel_hbm_traffic.md
+MEASURED_TRAFFIC = {"cfg2_64x65536": 5.528e8,  # profiles/cfg2_corr_kernel_hbm_traffic.md
+                    "cesgc_16x4096x4096_rank32": 1.390e8}  # per matrix; profiles/cesgc_16x4096x4096_kernel_trace_stats.md
 
 
 def main():
@@ -304,7 +305,7 @@ def main_cesgc(args, dev):
                    "chunks": C, "d": d, "r": r, "k": k, "matrix": "stored", "rhs_per_omp_call": 2 * C},
         "roofline": {"bound": "hbm", "kernel": "CESGC back-projection W -= lr B^T N (zero fill + read-modify-write of W), per matrix of the batch",
                      "achieved": round(achieved, 1), "peak": 8000.0, "unit": "GB/s", "frac": round(achieved / 8000.0, 4),
-                     "traffic": None, "bytes_per_matrix": bytes_back, "avg_ms_per_matrix": round(back_ms, 5)},
+                     "traffic": MEASURED_TRAFFIC.get("cesgc_%dx4096x4096_rank32" % M), "bytes_per_matrix": bytes_back, "avg_ms_per_matrix": round(back_ms, 5)},
         "kernels": kernels,
     }
     if not args.no_cpu_baseline:
