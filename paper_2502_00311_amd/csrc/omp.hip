@@ -927,8 +927,7 @@ static hipError_t corr_dispatch(const MatrixView &A, int32_t rows, const float *
 //                    column of F and x = F a, all in double; then res = y - A_Lambda x in double (a
 //                    column-major mat-vec over the selected columns), plus the float copy for the
 //                    next contraction
-constexpr int PICK_THREADS = 512;
-constexpr int PICK_WAVES = PICK_THREADS / 64;
+constexpr int PICK_THREADS_WIDE = 512, PICK_THREADS_NARROW = 128; // narrow: short columns (r <= 512) and k <= 128
 constexpr int PICK_CAND_CAP = 64;
 constexpr int FACTOR_MAX_THREADS = 1024;
 
@@ -958,9 +957,10 @@ __device__ __forceinline__ float4 column_quad(const MatrixView &A, int32_t i, in
 // grid (N, slices). Every slice of a right-hand side repeats the (cheap) selection so that no
 // grid-wide synchronisation is needed; slice 0 also stores the column and the scalars.
 // dynamic LDS: float a_col[r]
-template <bool GENERATED>
+template <bool GENERATED, int PICK_THREADS>
 __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(MatrixView A, IterArgs P)
 {
+    constexpr int PICK_WAVES = PICK_THREADS / 64;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     float *a_col = reinterpret_cast<float *>(smem);
     __shared__ uint64_t s_u64[PICK_WAVES];
@@ -1553,6 +1553,9 @@ static void omp_select_update(const OmpPlan &pl, const MatrixView &A, const floa
                               int32_t it, int32_t *sel, float *x, const OmpWorkspace &w, hipStream_t s)
 {
     ProfileScope prof(KC_SELECT, s);
+    // short columns: two wavefronts per right-hand side keep their lanes busy and let sixteen workgroups
+    // share a CU, which hides the chain of dependent loads this kernel consists of
+    const bool narrow = A.r <= 512 && k <= 128;
     int slices = 2048 / Ng;
     slices = slices < 1 ? 1 : (slices > 8 ? 8 : slices);
     if (pl.Apick.gram)
@@ -1560,10 +1563,17 @@ static void omp_select_update(const OmpPlan &pl, const MatrixView &A, const floa
     const dim3 pgrid((unsigned)Ng, (unsigned)slices);
     IterArgs P{y, k, it, sel, x, w, pl.Apick.generated ? nullptr : pl.Apick.At, pl.factor_share_table ? 1 : 0,
                pl.screen ? 1 : 0};
-    if (pl.Apick.generated)
-        pick_kernel<true><<<pgrid, PICK_THREADS, pl.pick_smem, s>>>(pl.Apick, P);
-    else
-        pick_kernel<false><<<pgrid, PICK_THREADS, pl.pick_smem, s>>>(pl.Apick, P);
+    if (narrow) {
+        if (pl.Apick.generated)
+            pick_kernel<true, PICK_THREADS_NARROW><<<pgrid, PICK_THREADS_NARROW, pl.pick_smem, s>>>(pl.Apick, P);
+        else
+            pick_kernel<false, PICK_THREADS_NARROW><<<pgrid, PICK_THREADS_NARROW, pl.pick_smem, s>>>(pl.Apick, P);
+    } else {
+        if (pl.Apick.generated)
+            pick_kernel<true, PICK_THREADS_WIDE><<<pgrid, PICK_THREADS_WIDE, pl.pick_smem, s>>>(pl.Apick, P);
+        else
+            pick_kernel<false, PICK_THREADS_WIDE><<<pgrid, PICK_THREADS_WIDE, pl.pick_smem, s>>>(pl.Apick, P);
+    }
     // One workgroup per right-hand side, two when there are so few that half the chip would idle
     // (each repeats the factor pass and takes half of the residual). More slices were measured
     // slower: the repeated passes over F cost more than the wider residual pass saves.
