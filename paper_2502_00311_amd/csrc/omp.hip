@@ -913,7 +913,9 @@ template <bool GENERATED>
 static hipError_t corr_dispatch(const MatrixView &A, int32_t rows, const float *R, int32_t N, const OmpWorkspace &ws,
                                 int32_t tiles_m, hipStream_t s)
 {
-    if (N <= 64) // a single half-width tile of right-hand sides: no matrix-core work on padding
+    // a single half-width tile of right-hand sides (no matrix-core work on padding), or so few full tiles
+    // that only half-width ones give every CU the two workgroups it can hold
+    if (N <= 64 || (int64_t)corr_tiles_m(rows) * ((N + CORR_BN - 1) / CORR_BN) <= 256)
         return corr_launch<GENERATED, CORR_BM, 64, 32, 2, 2, 2>(A, rows, R, N, ws, tiles_m, s);
     return corr_launch<GENERATED, CORR_BM, CORR_BN, 32, 2, 2, 2>(A, rows, R, N, ws, tiles_m, s);
 }
