@@ -170,9 +170,10 @@ def test_empty_batch_is_a_no_op():
 
 
 # ------------------------------------------------------------------------------- Adam
-def test_adam_matches_oracle_over_steps():
-    rng = np.random.default_rng(3)
-    n = 5 * 96 + 3  # not a multiple of 4
+@pytest.mark.parametrize("n", [5 * 96 + 3, 4 * (3 * 1024 + 700) + 2, 4 * 1024 * 4100 + 1],
+                         ids=["small", "ragged_pass", "more_passes_than_workgroups"])
+def test_adam_matches_oracle_over_steps(n):
+    rng = np.random.default_rng(3)   # n: not a multiple of 4
     m = np.zeros(n, np.float32)
     v = np.zeros(n, np.float32)
     md, vd = dev(m), dev(v)
