@@ -143,7 +143,8 @@ def cesgc_case(m, n, rho, d, r, k, seed):
 @pytest.mark.parametrize("m,n,rho,d,r,k,steps", [
     (96, 128, 4, 64, 32, 4, 3),
     (512, 1024, 32, 2048, 220, 31, 2),       # the paper's CESGC setting (rank 32, chunks of 2048, 31 kept, r = 7 k)
-], ids=["tiny", "paper_setting"])
+    (4096, 4096, 32, 2048, 220, 31, 1),      # the same on a full attention matrix (the benchmark's shape, one matrix)
+], ids=["tiny", "paper_setting", "paper_setting_4096x4096"])
 def test_cesgc_steps_stage_wise(m, n, rho, d, r, k, steps):
     basis, B, At, A = cesgc_case(m, n, rho, d, r, k, 3)
     C = rho * n // d
