@@ -34,7 +34,9 @@ SHAPES = [
     (5, 37, 24),          # everything ragged
     (32, 300, 132),       # one full block of B, several slices, a second ragged column strip
     (33, 70, 256),        # the two-block kernel with one row in the second block
-    (64, 1000, 512),      # the two-block kernel, full
+    (64, 1000, 512),      # the two-block kernel, ragged rows
+    (64, 1024, 512),      # the two-block kernel on full tiles (the branch-free paths)
+    (96, 512, 384),       # three rows of blocks of 32: two launches' worth of 64, the last half empty
     (130, 64, 128),       # three blocks of 64 rows of B, the last ragged
     (32, 1024, 1024),     # the paper's rank on a square matrix: 8 strips x 16 slices
 ]
@@ -61,7 +63,7 @@ def test_outer_project_matches_oracle(rho, m, n):
 
 @pytest.mark.parametrize("rho,m,n,d,k", [
     (1, 2, 4, 4, 1), (5, 37, 24, 8, 2), (32, 300, 132, 64, 5), (64, 1000, 512, 2048, 31), (130, 64, 128, 1664, 40),
-    (32, 1024, 1024, 2048, 31),
+    (32, 1024, 1024, 2048, 31), (64, 1024, 512, 2048, 31), (96, 512, 384, 1024, 20), (16, 256, 128, 512, 7),
 ])
 def test_outer_apply_matches_oracle(rho, m, n, d, k):
     say("outer_apply", rho, m, n, d, k)
