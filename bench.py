@@ -353,6 +353,9 @@ def main_cesgc(args, dev):
     kernels["outer_project"]["algorithmic_GBps"] = round(bytes_proj / (proj_ms * 1e-3) / 1e9, 1)
     kernels["outer_apply"]["algorithmic_GBps"] = round(bytes_back / (back_ms * 1e-3) / 1e9, 1)
     achieved = bytes_back / (back_ms * 1e-3) / 1e9
+    corr_ms, corr_n = prof["omp_corr"]
+    if corr_n:  # one launch per iteration here (HIP events keep the recovery on one stream)
+        kernels["omp_corr"]["TFLOPs"] = round(2.0 * d * r * 2 * C / (corr_ms / corr_n * 1e-3) / 1e12, 1)
     out = {
         "metric": "gradient elements/s per full CESGC step (1 GPU)", "value": round(M * m * n / (ms_per_step * 1e-3), 1),
         "unit": "elements/s", "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(ms_per_step, 3),
