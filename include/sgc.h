@@ -52,7 +52,7 @@ enum {
     SGC_ERR_DEVICE = -7     /* a HIP call failed (launch error, no device) */
 };
 
-/* gradient element type of sgc_sparsify_project */
+/* gradient element type of sgc_sparsify_project and sgc_outer_project */
 enum { SGC_GRAD_F32 = 0, SGC_GRAD_BF16 = 1 };
 
 /*
@@ -244,7 +244,8 @@ sgc_status sgc_apply(float *W, int64_t C, int32_t d, int32_t k, const int32_t *s
  * Both calls take a batch of `count` equal-sized matrices stored one after the other (one launch for
  * all of them: a single matrix of a few tens of MB is too little work to fill the memory system):
  *   B    [count][rho][m], G and W [count][m][n], Gc out [count][rho][n]; n % 4 == 0; G, W, Gc
- *        16-byte aligned
+ *        16-byte aligned. G is float or bfloat16 bit patterns (grad_type: SGC_GRAD_F32 / SGC_GRAD_BF16,
+ *        widened exactly); everything else is float
  *   sel_m, x_m, sel_v, x_v  [count*rho*n/d][k]: the chunks of the whole batch in order, as returned by
  *        sgc_recover_omp on [mhat; vhat] of all of them
  *   ws   at least sgc_outer_workspace_bytes(count, rho, m, n) bytes (0 for invalid sizes), 256-byte
@@ -253,11 +254,11 @@ sgc_status sgc_apply(float *W, int64_t C, int32_t d, int32_t k, const int32_t *s
  * Products are accumulated in float on the matrix cores; the rows of G are summed in slices whose
  * partial results are added in a fixed order, so results are reproducible run to run.
  * Errors: NULL, SHAPE (count, rho, m, n <= 0, rho above 2^20, m or n above 2^22, count * ceil(rho/32)
- * above 65535, n % 4, rho*n % d, k <= 0, k > d, k > 4096), ALIGN, WORKSPACE, DEVICE.
+ * above 65535, n % 4, rho*n % d, k <= 0, k > d, k > 4096), DTYPE, ALIGN, WORKSPACE, DEVICE.
  */
 size_t sgc_outer_workspace_bytes(int32_t count, int32_t rho, int32_t m, int32_t n);
-sgc_status sgc_outer_project(const float *B, const float *G, int32_t count, int32_t rho, int32_t m, int32_t n,
-                             float *Gc, void *ws, size_t ws_bytes, void *stream);
+sgc_status sgc_outer_project(const float *B, const void *G, int32_t grad_type, int32_t count, int32_t rho,
+                             int32_t m, int32_t n, float *Gc, void *ws, size_t ws_bytes, void *stream);
 sgc_status sgc_outer_apply(float *W, const float *B, int32_t count, int32_t rho, int32_t m, int32_t n, int32_t d,
                            int32_t k, const int32_t *sel_m, const float *x_m, const int32_t *sel_v,
                            const float *x_v, const sgc_hyper *h /* host */, void *ws, size_t ws_bytes,

@@ -237,18 +237,21 @@ size_t sgc_outer_workspace_bytes(int32_t count, int32_t rho, int32_t m, int32_t 
     return outer_plan(count, rho, m, n).ws_bytes;
 }
 
-sgc_status sgc_outer_project(const float *B, const float *G, int32_t count, int32_t rho, int32_t m, int32_t n,
-                             float *Gc, void *ws, size_t ws_bytes, void *stream)
+sgc_status sgc_outer_project(const float *B, const void *G, int32_t grad_type, int32_t count, int32_t rho, int32_t m,
+                             int32_t n, float *Gc, void *ws, size_t ws_bytes, void *stream)
 {
     if (!B || !G || !Gc || !ws)
         return SGC_ERR_NULL;
+    if (grad_type != SGC_GRAD_F32 && grad_type != SGC_GRAD_BF16)
+        return SGC_ERR_DTYPE;
     if (!outer_sizes_ok(count, rho, m, n))
         return SGC_ERR_SHAPE;
     if (!aligned16(G) || !aligned16(Gc) || ((uintptr_t)ws & 255u))
         return SGC_ERR_ALIGN;
     if (ws_bytes < outer_plan(count, rho, m, n).ws_bytes)
         return SGC_ERR_WORKSPACE;
-    return from_hip(launch_outer_project(B, G, count, rho, m, n, Gc, ws, (hipStream_t)stream));
+    return from_hip(launch_outer_project(B, G, grad_type == SGC_GRAD_BF16, count, rho, m, n, Gc, ws,
+                                         (hipStream_t)stream));
 }
 
 sgc_status sgc_outer_apply(float *W, const float *B, int32_t count, int32_t rho, int32_t m, int32_t n, int32_t d,

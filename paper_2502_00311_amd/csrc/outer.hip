@@ -10,6 +10,8 @@
 // component e of that load to the MFMA of column block e, so that block e stands for the columns
 // 4 j + e. The permutation costs nothing: for a fixed accumulator register the four blocks are again four
 // adjacent columns, read and written as 16 bytes.
+#include <type_traits>
+
 #include "sgc_internal.h"
 
 namespace sgc {
@@ -17,6 +19,25 @@ namespace sgc {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int OUTER_STRIP = 128; // columns per wavefront
+
+// Four adjacent entries of a row of G as loaded: 16 bytes of floats, or 8 bytes of bfloat16 bit patterns
+// (widened to float, exactly, when they are used).
+template <bool GBF16> struct OuterPiece { typedef float4 type; };
+template <> struct OuterPiece<true> { typedef uint2 type; };
+
+__device__ __forceinline__ float4 outer_load_g(const float *p) { return load_once_f4(p); }
+__device__ __forceinline__ uint2 outer_load_g(const uint16_t *p)
+{
+    typedef unsigned int uintx2_t __attribute__((ext_vector_type(2)));
+    const uintx2_t t = __builtin_nontemporal_load(reinterpret_cast<const uintx2_t *>(p));
+    return make_uint2(t.x, t.y);
+}
+__device__ __forceinline__ float4 outer_widen(const float4 &v) { return v; }
+__device__ __forceinline__ float4 outer_widen(const uint2 &v)
+{
+    return make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u), __uint_as_float(v.y << 16),
+                       __uint_as_float(v.y & 0xffff0000u));
+}
 
 // v where keep, else zero, as four selects (an `if` around a loaded value becomes a branch with a wait)
 __device__ __forceinline__ float4 outer_keep(bool keep, float4 v)
@@ -42,11 +63,15 @@ constexpr int OUTER_FLIGHT = 8;  // row pairs in flight per wavefront
 // FULL: m a multiple of the slice, rho of the block of rows of B, n of 128 (and offsets that fit 32 bits):
 // no clamps or selects, and every address is a wavefront-uniform base plus a per-lane offset that
 // never changes, so the loads cost no vector arithmetic (which would take its time from the MFMAs).
-template <int RBLK, int NG, bool BVEC, bool FULL>
-__global__ __launch_bounds__(256) void outer_project_kernel(const float *__restrict__ B, const float *__restrict__ G,
+// GBF16: G holds bfloat16 bit patterns (8-byte pieces instead of 16-byte ones).
+template <int RBLK, int NG, bool BVEC, bool FULL, bool GBF16>
+__global__ __launch_bounds__(256) void outer_project_kernel(const float *__restrict__ B, const void *__restrict__ Gv,
                                                             int32_t rho, int32_t m, int32_t n, int32_t rho_blocks,
                                                             int32_t reps, float *__restrict__ out)
 {
+    typedef typename std::conditional<GBF16, uint16_t, float>::type GElem;
+    typedef typename OuterPiece<GBF16>::type GPiece;
+    const GElem *G = static_cast<const GElem *>(Gv);
     extern __shared__ __attribute__((aligned(16))) float outer_lds[]; // Bs x 2, later the accumulators of wavefronts 1..3
     constexpr int RB = 32 * RBLK, LDB = RB + 1, SLICE = 32 * NG, PIECES = RBLK * NG, BSZ = SLICE * LDB;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, l32 = lane & 31, lhalf = lane >> 5;
@@ -57,14 +82,15 @@ __global__ __launch_bounds__(256) void outer_project_kernel(const float *__restr
     out += ((int64_t)mat * gridDim.y + blockIdx.y) * rho * n;
     const int32_t col = n0 + 4 * l32;
     const bool col_ok = col < n;
-    const float *gcol = G + (col_ok ? col : n - 4);
+    const GElem *gcol = G + (col_ok ? col : n - 4);
     const int32_t slices = (m + SLICE - 1) / SLICE;
     const int32_t s_first = blockIdx.y * reps;
     const int32_t s_end = s_first + reps < slices ? s_first + reps : slices;
 
-    float4 bp[2][PIECES], g[2][NG][4];
+    float4 bp[2][PIECES];
+    GPiece g[2][NG][4];
     const int wu = __builtin_amdgcn_readfirstlane(w);
-    const uint32_t g_lane = (uint32_t)(4 * lhalf * n + col); // FULL: offsets in floats from a uniform base
+    const uint32_t g_lane = (uint32_t)(4 * lhalf * n + col); // FULL: offsets in entries from a uniform base
     uint32_t b_lane[PIECES];
 #pragma unroll
     for (int i = 0; i < PIECES; ++i) {
@@ -82,7 +108,7 @@ __global__ __launch_bounds__(256) void outer_project_kernel(const float *__restr
             for (int q = 0; q < NG; ++q)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    g[set][q][j] = load_once_f4(G + (int64_t)(m0 + 8 * (4 * q + wu) + j) * n + g_lane);
+                    g[set][q][j] = outer_load_g(G + (int64_t)(m0 + 8 * (4 * q + wu) + j) * n + g_lane);
             __builtin_amdgcn_sched_barrier(0);
             return;
         }
@@ -107,7 +133,7 @@ __global__ __launch_bounds__(256) void outer_project_kernel(const float *__restr
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int32_t row = m0 + 8 * (4 * q + w) + 4 * lhalf + j;
-                g[set][q][j] = load_once_f4(gcol + (int64_t)(row < m ? row : m - 1) * n);
+                g[set][q][j] = outer_load_g(gcol + (int64_t)(row < m ? row : m - 1) * n);
             }
         __builtin_amdgcn_sched_barrier(0);
     };
@@ -149,7 +175,8 @@ __global__ __launch_bounds__(256) void outer_project_kernel(const float *__restr
                 const int32_t kl = 8 * (4 * q + w) + 4 * lhalf + j;
                 // rows past the end of the matrix were read from a clamped address: they count as zero
                 // (their depths of Bs are zero too, but zero times a non-finite entry would not be)
-                const float4 gv = FULL ? g[set][q][j] : outer_keep(m0 + kl < m, g[set][q][j]);
+                const float4 gw = outer_widen(g[set][q][j]);
+                const float4 gv = FULL ? gw : outer_keep(m0 + kl < m, gw);
 #pragma unroll
                 for (int rb = 0; rb < RBLK; ++rb) {
                     const float a = bs[kl * LDB + rb * 32 + l32];
@@ -426,8 +453,8 @@ OuterPlan outer_plan(int32_t count, int32_t rho, int32_t m, int32_t n)
     return pl;
 }
 
-hipError_t launch_outer_project(const float *B, const float *G, int32_t count, int32_t rho, int32_t m, int32_t n,
-                                float *Gc, void *ws, hipStream_t s)
+hipError_t launch_outer_project(const float *B, const void *G, bool g_bf16, int32_t count, int32_t rho, int32_t m,
+                                int32_t n, float *Gc, void *ws, hipStream_t s)
 {
     const OuterPlan pl = outer_plan(count, rho, m, n);
     float *out = pl.slices > 1 ? static_cast<float *>(ws) : Gc;
@@ -438,20 +465,27 @@ hipError_t launch_outer_project(const float *B, const float *G, int32_t count, i
     const bool b_vec = m % 4 == 0 && ((uintptr_t)B & 15u) == 0;
     const bool full = b_vec && m % pl.slice == 0 && rho % (32 * pl.rblk) == 0 && n % OUTER_STRIP == 0 &&
                       (int64_t)rho * m < (1ll << 29) && (int64_t)n * 8 < (1ll << 29);
-    typedef void (*Kernel)(const float *, const float *, int32_t, int32_t, int32_t, int32_t, int32_t, float *);
+    typedef void (*Kernel)(const float *, const void *, int32_t, int32_t, int32_t, int32_t, int32_t, float *);
     Kernel kern = nullptr;
     const int ng = pl.slice / 32;
 #define SGC_OUTER_PICK(R, N) \
-    if (pl.rblk == R && ng == N) \
-        kern = full ? outer_project_kernel<R, N, true, true> \
-                    : (b_vec ? outer_project_kernel<R, N, true, false> : outer_project_kernel<R, N, false, false>);
+    if (pl.rblk == R && ng == N) { \
+        if (g_bf16) \
+            kern = full ? outer_project_kernel<R, N, true, true, true> \
+                        : (b_vec ? outer_project_kernel<R, N, true, false, true> \
+                                 : outer_project_kernel<R, N, false, false, true>); \
+        else \
+            kern = full ? outer_project_kernel<R, N, true, true, false> \
+                        : (b_vec ? outer_project_kernel<R, N, true, false, false> \
+                                 : outer_project_kernel<R, N, false, false, false>); \
+    }
     SGC_OUTER_PICK(1, 1) SGC_OUTER_PICK(1, 2) SGC_OUTER_PICK(1, 4)
     SGC_OUTER_PICK(2, 1) SGC_OUTER_PICK(2, 2)
 #undef SGC_OUTER_PICK
     if (!kern)
         return hipErrorInvalidValue;
-    static bool raised[3][5][3];
-    const int variant = full ? 2 : (b_vec ? 1 : 0);
+    static bool raised[3][5][6];
+    const int variant = (full ? 2 : (b_vec ? 1 : 0)) + (g_bf16 ? 3 : 0);
     if (smem > 48 * 1024 && !raised[pl.rblk][ng][variant]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);

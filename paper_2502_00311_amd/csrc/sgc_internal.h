@@ -90,8 +90,8 @@ struct OuterPlan {
     size_t ws_bytes;
 };
 OuterPlan outer_plan(int32_t count, int32_t rho, int32_t m, int32_t n);
-hipError_t launch_outer_project(const float *B, const float *G, int32_t count, int32_t rho, int32_t m, int32_t n,
-                                float *Gc, void *ws, hipStream_t s);
+hipError_t launch_outer_project(const float *B, const void *G, bool g_bf16, int32_t count, int32_t rho, int32_t m,
+                                int32_t n, float *Gc, void *ws, hipStream_t s);
 hipError_t launch_outer_apply(float *W, const float *B, int32_t count, int32_t rho, int32_t m, int32_t n, int32_t d,
                               int32_t k, const int32_t *sel_m, const float *x_m, const int32_t *sel_v,
                               const float *x_v, float alpha, float eps, float lr, void *ws, hipStream_t s);

@@ -87,7 +87,7 @@ def lib():
         L.sgc_outer_workspace_bytes.restype = sz
         L.sgc_outer_workspace_bytes.argtypes = [i32, i32, i32, i32]
         L.sgc_outer_project.restype = i32
-        L.sgc_outer_project.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, sz, vp]
+        L.sgc_outer_project.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, sz, vp]
         L.sgc_outer_apply.restype = i32
         L.sgc_outer_apply.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, ctypes.POINTER(sgc_hyper), vp, sz, vp]
         L.sgc_profile_enable.restype = i32
@@ -185,7 +185,8 @@ def sgc_outer_workspace_bytes(count, rho, m, n):
 
 
 def sgc_outer_project(B, G, count, rho, m, n, Gc, ws, stream=None):
-    _check(lib().sgc_outer_project(_ptr(B), _ptr(G), count, rho, m, n, _ptr(Gc), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_outer_project")
+    gt = GRAD_BF16 if G.dtype in (torch.bfloat16, torch.int16, torch.uint16) else GRAD_F32
+    _check(lib().sgc_outer_project(_ptr(B), _ptr(G), gt, count, rho, m, n, _ptr(Gc), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_outer_project")
 
 
 def sgc_outer_apply(W, B, count, rho, m, n, d, k, sel_m, x_m, sel_v, x_v, h, ws, stream=None):

@@ -184,16 +184,17 @@ def test_outer_projection_rejects_bad_arguments_and_sizes_workspace():
     assert sgc.sgc_outer_workspace_bytes(70000, 4, 8, 8) == 0      # batch beyond the grid limit
     small = sgc.sgc_outer_workspace_bytes(1, 4, 8, 8)
     p = L.sgc_outer_project
-    assert p(None, FAKE, 1, 4, 8, 8, FAKE, FAKE, small, None) == sgc.ERR_NULL
-    assert p(FAKE, FAKE, 1, 4, 8, 8, FAKE, None, small, None) == sgc.ERR_NULL
-    assert p(FAKE, FAKE, 1, 4, 8, 6, FAKE, FAKE, small, None) == sgc.ERR_SHAPE
-    assert p(FAKE, FAKE, 1, 0, 8, 8, FAKE, FAKE, small, None) == sgc.ERR_SHAPE
-    assert p(FAKE, FAKE, 0, 4, 8, 8, FAKE, FAKE, small, None) == sgc.ERR_SHAPE
-    assert p(FAKE, ODD, 1, 4, 8, 8, FAKE, FAKE, small, None) == sgc.ERR_ALIGN
-    assert p(FAKE, FAKE, 1, 4, 8, 8, FAKE, ODD, small, None) == sgc.ERR_ALIGN
-    assert p(FAKE, FAKE, 1, 4, 8, 8, FAKE, FAKE, small - 1, None) == sgc.ERR_WORKSPACE
+    assert p(None, FAKE, 0, 1, 4, 8, 8, FAKE, FAKE, small, None) == sgc.ERR_NULL
+    assert p(FAKE, FAKE, 0, 1, 4, 8, 8, FAKE, None, small, None) == sgc.ERR_NULL
+    assert p(FAKE, FAKE, 0, 1, 4, 8, 6, FAKE, FAKE, small, None) == sgc.ERR_SHAPE
+    assert p(FAKE, FAKE, 5, 1, 4, 8, 8, FAKE, FAKE, small, None) == sgc.ERR_DTYPE
+    assert p(FAKE, FAKE, 0, 1, 0, 8, 8, FAKE, FAKE, small, None) == sgc.ERR_SHAPE
+    assert p(FAKE, FAKE, 1, 0, 4, 8, 8, FAKE, FAKE, small, None) == sgc.ERR_SHAPE
+    assert p(FAKE, ODD, 0, 1, 4, 8, 8, FAKE, FAKE, small, None) == sgc.ERR_ALIGN
+    assert p(FAKE, FAKE, 0, 1, 4, 8, 8, FAKE, ODD, small, None) == sgc.ERR_ALIGN
+    assert p(FAKE, FAKE, 1, 1, 4, 8, 8, FAKE, FAKE, small - 1, None) == sgc.ERR_WORKSPACE
     one = sgc.sgc_outer_workspace_bytes(1, 4, 8, 256)
-    assert p(FAKE, FAKE, 2, 4, 8, 256, FAKE, FAKE, one, None) == sgc.ERR_WORKSPACE  # sized for one matrix
+    assert p(FAKE, FAKE, 0, 2, 4, 8, 256, FAKE, FAKE, one, None) == sgc.ERR_WORKSPACE  # sized for one matrix
     a = L.sgc_outer_apply
     h = sgc.hyper()
 

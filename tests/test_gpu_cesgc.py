@@ -61,6 +61,28 @@ def test_outer_project_matches_oracle(rho, m, n):
     assert torch.equal(first, ob.Gc)
 
 
+@pytest.mark.parametrize("count,rho,m,n", [(1, 5, 37, 24), (1, 32, 300, 132), (2, 64, 1000, 512), (3, 32, 256, 256),
+                                           (1, 32, 1024, 1024)])
+def test_outer_project_of_bf16_gradients(count, rho, m, n):
+    """G as bfloat16 bit patterns: the result is the projection of the widened values."""
+    say("outer_project bf16", count, rho, m, n)
+    rng = np.random.default_rng(rho + m + n + 1)
+    B = rng.standard_normal((count, rho, m)).astype(np.float32)
+    bits = synth.f32_to_bf16_bits(rng.standard_t(3.0, size=(count, m, n)).astype(np.float32))
+    G = synth.bf16_bits_to_f32(bits)
+    ob = sgc.OuterBuffers(rho, m, n, count=count)
+    sgc.sgc_outer_project(dev(B), dev(bits.view(np.int16)), count, rho, m, n, ob.Gc, ob.ws)
+    torch.cuda.synchronize()
+    got = ob.Gc.cpu().numpy().reshape(count, rho, n)
+    for c in range(count):
+        assert relerr(got[c], orc.outer_project(B[c], G[c])) < 1e-5, c
+    # and it equals, bit for bit, the projection of the same values handed over as floats
+    ob2 = sgc.OuterBuffers(rho, m, n, count=count)
+    sgc.sgc_outer_project(dev(B), dev(G), count, rho, m, n, ob2.Gc, ob2.ws)
+    torch.cuda.synchronize()
+    assert torch.equal(ob.Gc, ob2.Gc)
+
+
 @pytest.mark.parametrize("rho,m,n,d,k", [
     (1, 2, 4, 4, 1), (5, 37, 24, 8, 2), (32, 300, 132, 64, 5), (64, 1000, 512, 2048, 31), (130, 64, 128, 1664, 40),
     (32, 1024, 1024, 2048, 31), (64, 1024, 512, 2048, 31), (96, 512, 384, 1024, 20), (16, 256, 128, 512, 7),
