@@ -515,3 +515,33 @@ def test_large_batch_two_streams_equals_single_stream_and_profile_counts():
     assert prof["omp_matrix_fill"][1] == 1 and prof["omp_corr"][0] > 0.0
     c = run_omp(Y, A, k)    # and again on two streams after the collection is switched off
     assert np.array_equal(a[0], c[0]) and np.array_equal(a[1].view(np.uint32), c[1].view(np.uint32))
+
+
+def test_measurement_count_not_a_multiple_of_four_by_zero_rows():
+    """r = 217 (the paper's 7 x 31): the library wants r % 4 == 0; three zero measurement rows appended to a
+    stored matrix change nothing, so the padded run must match the oracle's run at r = 217."""
+    C, d, r, k = 3, 2048, 217, 31
+    rpad = 220
+    w = synth.shrink(synth.CFG2, C=C, d=d, r=rpad, k=k)
+    At = synth.gaussian_matrix(12, d, r)                       # [d, 217]
+    At_pad = np.zeros((d, rpad), np.float32)
+    At_pad[:, :r] = At
+    A = sgc.Matrix(d, rpad, At=dev(At_pad))
+    A.inv_colnorm = torch.empty(d, dtype=torch.float32, device=DEV)
+    sgc.sgc_matrix_colnorms(A, A.inv_colnorm)
+    g = synth.gradients(w, 1)
+    W0 = synth.weights(w)
+    W = dev(W0)
+    buf = sgc.StepBuffers(C, d, rpad, k)
+    sgc.step(dev(g), W, buf, A, 1, sgc.hyper(alpha=2.0))
+    torch.cuda.synchronize()
+    assert not buf.p[:, r:].any() and not buf.m[:, r:].any()
+    # stage-wise against the oracle at r = 217
+    idx, val = orc.topk(g, k)
+    assert np.array_equal(buf.idx.cpu().numpy(), idx)
+    p, q = orc.project(idx, val, At)
+    assert rowwise_relerr(buf.p.cpu().numpy()[:, :r], p) < 1e-5
+    hat = buf.hat.cpu().numpy()[:, :r]
+    rsel, rx = orc.omp_batch(hat, At, k)
+    assert np.array_equal(buf.sel.cpu().numpy(), rsel)
+    assert rowwise_relerr(buf.x.cpu().numpy(), rx) < TOL
