@@ -375,14 +375,9 @@ static hipError_t corr_split_launch(const MatrixView &A, const uint16_t *rows_sp
                                     const OmpWorkspace &ws, int32_t tiles_m, hipStream_t s)
 {
     constexpr size_t smem = (size_t)4 * 128 * SPLIT_ROWB;
-    static bool raised = false;
-    if (!raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_split_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess)
-            return e;
-        raised = true;
-    }
+    const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void *>(corr_split_kernel), smem);
+    if (e != hipSuccess)
+        return e;
     const dim3 grid((unsigned)((rows + 127) / 128), (unsigned)((N + 127) / 128));
     corr_split_kernel<<<grid, 256, smem, s>>>(A, reinterpret_cast<const unsigned char *>(rows_split),
                                               reinterpret_cast<const unsigned char *>(ws.res16), N, ws.bitmap, ws.words,
@@ -397,14 +392,9 @@ static hipError_t corr_launch(const MatrixView &A, int32_t rows, const float *R,
 {
     constexpr size_t smem = (size_t)2 * (BM + BN) * (BK + 4) * sizeof(float);
     auto kern = corr_kernel<GENERATED, BM, BN, BK, WMW, WNW, MINB>;
-    static bool raised = false;
-    if (!raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess)
-            return e;
-        raised = true;
-    }
+    const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void *>(kern), smem);
+    if (e != hipSuccess)
+        return e;
     const dim3 grid((unsigned)((rows + BM - 1) / BM), (unsigned)((N + BN - 1) / BN));
     kern<<<grid, WMW * WNW * 64, smem, s>>>(A, R, N, ws.bitmap, ws.words, ws.partial, tiles_m);
     return hipSuccess;
@@ -732,14 +722,9 @@ static hipError_t corr_pipelined_launch_nb(const MatrixView &A, int32_t rows, co
     constexpr int BN = 64 * NB;
     constexpr size_t smem = (size_t)2 * (CORRP_BM + BN) * 36 * sizeof(float) + CORRP_BM * sizeof(float) +
                             (size_t)BN * (CORRP_BM / 32) * sizeof(uint32_t);
-    static bool raised = false;
-    if (!raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(corr_pipelined_kernel<NB, BF16>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess)
-            return e;
-        raised = true;
-    }
+    const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void *>(corr_pipelined_kernel<NB, BF16>), smem);
+    if (e != hipSuccess)
+        return e;
     const dim3 grid((unsigned)(rows / CORRP_BM), (unsigned)((N + BN - 1) / BN));
     corr_pipelined_kernel<NB, BF16><<<grid, 256, smem, s>>>(A, R, N, ws.bitmap, ws.words, ws.partial, tiles_m);
     return hipSuccess;

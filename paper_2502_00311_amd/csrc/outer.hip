@@ -484,14 +484,10 @@ hipError_t launch_outer_project(const float *B, const void *G, bool g_bf16, int3
 #undef SGC_OUTER_PICK
     if (!kern)
         return hipErrorInvalidValue;
-    static bool raised[3][5][6];
-    const int variant = (full ? 2 : (b_vec ? 1 : 0)) + (g_bf16 ? 3 : 0);
-    if (smem > 48 * 1024 && !raised[pl.rblk][ng][variant]) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (smem > 48 * 1024) {
+        const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void *>(kern), smem);
         if (e != hipSuccess)
             return e;
-        raised[pl.rblk][ng][variant] = true;
     }
     ProfileScope prof(KC_OUTER_PROJECT, s);
     kern<<<grid, 256, smem, s>>>(B, G, rho, m, n, pl.rho_blocks, pl.reps, out);

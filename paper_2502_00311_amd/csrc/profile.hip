@@ -1,4 +1,5 @@
-// Per-kernel timing with HIP events on the caller's stream (instrumentation only).
+// Host-side helpers: per-kernel timing with HIP events on the caller's stream (instrumentation only),
+// and the once-per-device raising of a kernel's dynamic-LDS limit.
 #include <vector>
 
 #include "sgc_internal.h"
@@ -36,6 +37,27 @@ hipEvent_t get_event()
     return e;
 }
 } // namespace
+
+hipError_t raise_dynamic_lds(const void *kernel, size_t bytes)
+{
+    struct Done {
+        const void *kernel;
+        int device;
+        size_t bytes;
+    };
+    static std::vector<Done> done;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return e;
+    for (const Done &d : done)
+        if (d.kernel == kernel && d.device == dev && d.bytes >= bytes)
+            return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess)
+        done.push_back(Done{kernel, dev, bytes});
+    return e;
+}
 
 void profile_begin(int cls, hipStream_t s)
 {

@@ -115,6 +115,10 @@ struct ProfileScope {
     }
 };
 
+// Raise a kernel's dynamic-LDS limit to `bytes`, once per kernel and device (the attribute belongs to the
+// device's copy of the code object). Host state without a lock, like the rest of the library.
+hipError_t raise_dynamic_lds(const void *kernel, size_t bytes);
+
 // ---- small device helpers ----
 __device__ __forceinline__ double wave_sum(double v)
 {
