@@ -753,9 +753,10 @@ hipError_t corr_screen_launch(bool pipelined, const MatrixView &A, const uint16_
 // of stages; the last tile of right-hand sides may be ragged)
 bool corr_pipelined_ok(const MatrixView &A, int32_t N, int32_t panel_rows)
 {
-    // at most 64 right-hand sides and few position tiles: the general kernel's 128-row tiles give
-    // twice the workgroups, which matters more than the schedule when the chip is far from full
-    if (N <= 64 && A.d / CORRP_BM < 128)
+    // fewer than 128 workgroups of 256 positions: the general kernel's smaller tiles give several times
+    // the workgroups, which matters more than the schedule when the chip is far from full
+    const int64_t rhs_tiles = N <= 64 ? 1 : (N + CORR_BN - 1) / CORR_BN;
+    if ((int64_t)(A.d / CORRP_BM) * rhs_tiles < 128)
         return false;
     return A.d % CORRP_BM == 0 && A.r % 64 == 0 && panel_rows % CORRP_BM == 0;
 }

@@ -280,7 +280,7 @@ def test_omp_full_tiles_with_zero_and_sparse_right_hand_sides(N):
     """Full tiles of a stored matrix (the pipelined contraction): all-zero right-hand sides and ones
     sparser than k drive the residual to zero / rounding noise, where already selected positions can
     reach the top of a tile and must still never be selected twice."""
-    d, r, k = 1024, 256, 8
+    d, r, k = 32768, 512, 8     # 128 position tiles: enough workgroups for the pipelined kernel to be chosen
     A, At = make_matrix("stored", 20, d, r)
     A64 = At.astype(np.float64).T
     rng = np.random.default_rng(12)

@@ -56,9 +56,9 @@ def run_omp(Y, A, k):
     (2, 4096, 256, 32),      # cfg1 shape
     (130, 700, 64, 8),       # two tiles of right-hand sides, ragged
     (3, 2000, 100, 10),      # depth not a multiple of 32: the float contraction is used instead
-    (128, 1024, 256, 8),     # full tiles: the pipelined form of the screening contraction
-    (200, 768, 128, 6),      # the same with a ragged second tile of right-hand sides
-    (65, 512, 64, 5),        # ... and its shortest depth loop (two stages)
+    (128, 32768, 64, 4),     # full tiles, 128 of them: the pipelined form of the screening contraction
+    (200, 16384, 128, 4),    # the same with a ragged second tile of right-hand sides
+    (65, 32768, 64, 3),      # ... one right-hand side in the second tile; the shortest depth loop (two stages)
 ])
 def test_screened_recovery_matches_oracle(N, d, r, k):
     say("screen", N, d, r, k)
@@ -79,7 +79,7 @@ def test_screened_recovery_matches_oracle(N, d, r, k):
     assert np.array_equal(x.view(np.uint32), x2.view(np.uint32))   # the least squares never sees the contraction
 
 
-@pytest.mark.parametrize("d", [3000, 3072], ids=["ragged", "full_tiles"])
+@pytest.mark.parametrize("d", [3000, 8192], ids=["ragged", "full_tiles"])
 def test_screened_recovery_generated_matrix_many_right_hand_sides(d):
     N, r, k = 600, 64, 6
     rng = np.random.default_rng(N + d)
