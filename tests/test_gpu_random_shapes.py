@@ -1,0 +1,87 @@
+"""Seeded random shapes and option combinations of the recovery against the oracle: a net for the
+dispatch logic (which contraction kernel, panels, slices, two streams) rather than for any one kernel.
+Bar as everywhere: support bit-exact in selection order, values within 1e-4 of the per-vector maximum."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2502_00311_amd import sgc, synth
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4
+DEV = "cuda"
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def relerr(a, ref):
+    a = np.asarray(a, np.float64)
+    ref = np.asarray(ref, np.float64)
+    den = np.abs(ref).max()
+    return 0.0 if a.size == 0 else float(np.abs(a - ref).max() / (den if den > 0 else 1.0))
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def draw(seed):
+    rng = np.random.default_rng(1000 + seed)
+    r = 4 * int(rng.integers(1, 129))                       # 4 .. 512
+    if rng.random() < 0.4:
+        r = 32 * int(rng.integers(1, 17))                   # multiples of 32 (and often 64) reach more kernels
+    d = int(rng.integers(max(8, r // 8), 6000))
+    if rng.random() < 0.3:
+        d = 256 * int(rng.integers(1, 24))                  # full position tiles
+    k = int(rng.integers(1, min(r, d, 40) + 1))
+    budget = 1.5e9 / (float(d) * r * k)                     # oracle cost ~ N k d r
+    N = int(min(700, max(1, rng.integers(1, max(2, int(budget))))))
+    mode = "philox" if rng.random() < 0.5 else "stored"
+    return dict(N=N, d=d, r=r, k=k, mode=mode, screen=bool(rng.random() < 0.4), gram=bool(rng.random() < 0.25 and d <= 2048),
+                shared=bool(rng.random() < 0.3), rng=rng)
+
+
+@pytest.mark.parametrize("seed", range(28))
+def test_random_shape(seed):
+    c = draw(seed)
+    N, d, r, k, rng = c["N"], c["d"], c["r"], c["k"], c["rng"]
+    say("random shape", seed, {x: c[x] for x in ("N", "d", "r", "k", "mode", "screen", "gram", "shared")})
+    if c["mode"] == "stored":
+        At = synth.gaussian_matrix(seed, d, r)
+        A = sgc.Matrix(d, r, At=dev(At))
+    else:
+        At = orc.philox_matrix(seed, d, r)
+        A = sgc.Matrix(d, r, At=None, seed=seed)
+    A.inv_colnorm = torch.empty(d, dtype=torch.float32, device=DEV)
+    sgc.sgc_matrix_colnorms(A, A.inv_colnorm)
+    if c["screen"]:
+        A.flags = sgc.MATRIX_FLAG_SCREEN_BF16
+    if c["gram"]:
+        A.gram = torch.empty((d, d), dtype=torch.float64, device=DEV)
+        sgc.sgc_matrix_gram(A, A.gram)
+    Y = rng.standard_normal((N, r)).astype(np.float32)
+    if N > 3:
+        Y[N // 2] = 0.0
+    sel = torch.empty((N, k), dtype=torch.int32, device=DEV)
+    x = torch.empty((N, k), dtype=torch.float32, device=DEV)
+    ws = torch.empty(sgc.sgc_omp_workspace_bytes(N, d, r, k), dtype=torch.uint8, device=DEV)
+    if c["shared"]:
+        Yv = np.abs(rng.standard_normal((N, r))).astype(np.float32)
+        z = torch.empty((N, k), dtype=torch.float32, device=DEV)
+        sgc.sgc_recover_omp_shared(dev(Y), dev(Yv), N, A, k, sel, x, z, ws)
+        torch.cuda.synchronize()
+        rsel, rx, rz = orc.omp_shared(Y, Yv, At, k)
+        assert np.array_equal(sel.cpu().numpy(), rsel)
+        for n in range(N):
+            assert relerr(x[n].cpu().numpy(), rx[n]) < TOL and relerr(z[n].cpu().numpy(), rz[n]) < TOL, n
+    else:
+        sgc.sgc_recover_omp(dev(Y), N, A, k, sel, x, ws)
+        torch.cuda.synchronize()
+        rsel, rx = orc.omp_batch(Y, At, k)
+        assert np.array_equal(sel.cpu().numpy(), rsel)
+        xs = x.cpu().numpy()
+        for n in range(N):
+            assert relerr(xs[n], rx[n]) < TOL, n
