@@ -1,0 +1,110 @@
+"""Seeded random shapes of the other entry points against the oracle: sparsify + project (sizes on both
+sides of every kernel choice, ties, zeros, heavy tails, bfloat16 gradients, both matrix modes; top-k
+bit-exact) and the two outer products of CESGC (ragged and full tiles, batches)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2502_00311_amd import sgc, synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def relerr(a, ref):
+    a = np.asarray(a, np.float64)
+    ref = np.asarray(ref, np.float64)
+    den = np.abs(ref).max()
+    return 0.0 if a.size == 0 else float(np.abs(a - ref).max() / (den if den > 0 else 1.0))
+
+
+@pytest.mark.parametrize("seed", range(32))
+def test_sparsify_project_random_shape(seed):
+    rng = np.random.default_rng(5000 + seed)
+    d = int(rng.choice([int(rng.integers(4, 300)), int(rng.integers(300, 9000)), 4096, 16384, 65536,
+                        int(rng.integers(65537, 200000))]))
+    r = 4 * int(rng.integers(1, 80))
+    k = int(rng.integers(1, min(d, r, 600) + 1))
+    C = int(rng.integers(1, max(2, min(40, 3_000_000 // d))))
+    bf16 = rng.random() < 0.3
+    mode = "philox" if rng.random() < 0.5 else "stored"
+    kind = int(rng.integers(0, 4))
+    say("sparsify_project", seed, dict(C=C, d=d, r=r, k=k, bf16=bf16, mode=mode, kind=kind))
+    g = rng.standard_normal((C, d)).astype(np.float32)
+    if kind == 1:
+        g = np.round(g * 2) / 2                                  # many ties
+    elif kind == 2:
+        g[:, rng.integers(0, d, size=max(1, d // 3))] = 0        # many zeros
+    elif kind == 3:
+        g = (rng.standard_t(2.0, size=(C, d)) * 1e-3).astype(np.float32)
+    if bf16:
+        gref = synth.f32_to_bf16_bits(g)
+        gin = dev(gref.view(np.int16))
+    else:
+        gref = g
+        gin = dev(g)
+    if mode == "stored":
+        At = synth.gaussian_matrix(seed, d, r)
+        A = sgc.Matrix(d, r, At=dev(At))
+    else:
+        At = orc.philox_matrix(seed, d, r)
+        A = sgc.Matrix(d, r, At=None, seed=seed)
+    idx = torch.empty((C, k), dtype=torch.int32, device=DEV)
+    val = torch.empty((C, k), device=DEV)
+    p = torch.empty((C, r), device=DEV)
+    q = torch.empty((C, r), device=DEV)
+    sgc.sgc_sparsify_project(gin, C * d, d, k, A, idx, val, p, q)
+    torch.cuda.synchronize()
+    ridx, rval = orc.topk(gref, k)
+    assert np.array_equal(idx.cpu().numpy(), ridx)
+    assert np.array_equal(val.cpu().numpy().view(np.uint32), rval.view(np.uint32))
+    rp, rq = orc.project(ridx, rval, At)
+    pn, qn = p.cpu().numpy(), q.cpu().numpy()
+    for c in range(C):
+        assert relerr(pn[c], rp[c]) < 1e-5 and relerr(qn[c], rq[c]) < 1e-5, c
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_outer_products_random_shape(seed):
+    rng = np.random.default_rng(9000 + seed)
+    count = int(rng.integers(1, 4))
+    rho = int(rng.integers(1, 100))
+    m = int(rng.integers(1, 700))
+    n = 4 * int(rng.integers(1, 200))
+    if rng.random() < 0.4:                                       # full tiles: the branch-free paths
+        m = 32 * int(rng.integers(1, 20))
+        n = 128 * int(rng.integers(1, 6))
+        rho = int(rng.choice([16, 32, 64, 96]))
+    total = rho * n
+    d = int(rng.choice([x for x in range(2, min(total, 4096) + 1) if total % x == 0]))
+    k = int(rng.integers(1, min(d, 40) + 1))
+    say("outer", seed, dict(count=count, rho=rho, m=m, n=n, d=d, k=k))
+    B = rng.standard_normal((count, rho, m)).astype(np.float32)
+    G = rng.standard_normal((count, m, n)).astype(np.float32)
+    W = rng.standard_normal((count, m, n)).astype(np.float32)
+    Cm = total // d
+    sel = np.stack([rng.permutation(d)[:k] for _ in range(count * Cm)]).astype(np.int32)
+    x = rng.standard_normal((count * Cm, k)).astype(np.float32)
+    z = (rng.standard_normal((count * Cm, k)) ** 2).astype(np.float32)
+    ob = sgc.OuterBuffers(rho, m, n, count=count)
+    h = sgc.hyper(alpha=2.0, lr=0.01, eps=1e-3)
+    Bd, Wd = dev(B), dev(W)
+    sgc.sgc_outer_project(Bd, dev(G), count, rho, m, n, ob.Gc, ob.ws)
+    sgc.sgc_outer_apply(Wd, Bd, count, rho, m, n, d, k, dev(sel), dev(x), dev(sel), dev(z), h, ob.ws)
+    torch.cuda.synchronize()
+    Gc = ob.Gc.cpu().numpy().reshape(count, rho, n)
+    Wn = Wd.cpu().numpy()
+    for c in range(count):
+        assert relerr(Gc[c], orc.outer_project(B[c], G[c])) < 1e-5, c
+        lo, hi = c * Cm, (c + 1) * Cm
+        ref = orc.outer_apply(W[c], B[c], d, sel[lo:hi], x[lo:hi], sel[lo:hi], z[lo:hi], alpha=2.0, eps=1e-3, lr=0.01)
+        assert relerr(Wn[c] - W[c], ref.astype(np.float64) - W[c]) < 1e-4, c
