@@ -462,7 +462,8 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
     const int ldst0 = (tid >> 3) * LD + ((tid & 7) << 2);
     const int nkb = r / BK;
 
-    constexpr int GS = BF16 ? 2 : 1; // staging register sets
+    constexpr bool WIDE = BF16 && NB == 4;   // 128 x 128 outputs per wavefront: one staging set fits
+    constexpr int GS = BF16 && !WIDE ? 2 : 1; // staging register sets
     constexpr int FH = BF16 ? 2 : 1; // fragment parts (high, low)
     floatx4 g[GS][LA + LB];
     floatx4 fa[2][MB][FH], fb[2][NB][FH];
@@ -534,8 +535,12 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
     }
     static_for<0, LA + LB>([&](auto uc) { lwrite(decltype(uc)::value, 0); });
     static_for<0, LA + LB>([&](auto uc) { gload(decltype(uc)::value, 1, GS - 1); });
-    if constexpr (BF16)
+    if constexpr (WIDE) { // both LDS buffers filled, stage 2 in the staging registers
+        static_for<0, LA + LB>([&](auto uc) { lwrite(decltype(uc)::value, 1); });
+        static_for<0, LA + LB>([&](auto uc) { gload(decltype(uc)::value, 2); });
+    } else if constexpr (BF16) {
         static_for<0, LA + LB>([&](auto uc) { gload(decltype(uc)::value, 2, 0); });
+    }
     __syncthreads();
     static_for<0, MB + NB>([&](auto oc) { fread(0, decltype(oc)::value, 0, 0); });
 
@@ -563,6 +568,33 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
                 fread(0, m, buf ^ 1, 0);
             else if constexpr (m < MB + NB + LA + LB)
                 gload(m - (MB + NB), kb + 3, (buf ^ 1) & (GS - 1));
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+    // WIDE stage kb: the other LDS buffer already holds stage kb + 1 and the one staging set stage kb + 2.
+    // Group 0 reads the fragments of group 1; barrier, after which nobody reads this stage's buffer
+    // again; group 1 reads the first fragments of stage kb + 1, copies the staging set into this stage's
+    // buffer and refills it with stage kb + 3, which then has a whole stage to arrive.
+    auto stage_wide = [&](int kb, auto bufc) {
+        constexpr int buf = decltype(bufc)::value;
+        constexpr int G3 = 3 * MB * NB;
+        static_for<0, G3>([&](auto mc) {
+            constexpr int m = decltype(mc)::value;
+            mfma(0, m);
+            if constexpr (m < MB + NB)
+                fread(1, m, buf, 1);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        __syncthreads();
+        static_for<0, G3>([&](auto mc) {
+            constexpr int m = decltype(mc)::value;
+            mfma(1, m);
+            if constexpr (m < MB + NB)
+                fread(0, m, buf ^ 1, 0);
+            else if constexpr (m < MB + NB + LA + LB)
+                lwrite(m - (MB + NB), buf);
+            else if constexpr (m < MB + NB + 2 * (LA + LB))
+                gload(m - (MB + NB + LA + LB), kb + 3);
             __builtin_amdgcn_sched_barrier(0);
         });
     };
@@ -608,7 +640,10 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
         });
     };
     for (int kb = 0; kb < nkb; kb += 2) {
-        if constexpr (BF16) {
+        if constexpr (WIDE) {
+            stage_wide(kb, std::integral_constant<int, 0>{});
+            stage_wide(kb + 1, std::integral_constant<int, 1>{});
+        } else if constexpr (BF16) {
             stage_bf16(kb, std::integral_constant<int, 0>{});
             stage_bf16(kb + 1, std::integral_constant<int, 1>{});
         } else {
@@ -746,7 +781,12 @@ hipError_t corr_screen_launch(bool pipelined, const MatrixView &A, const uint16_
         return corr_split_launch(A, rows_split, rows, N, ws, tiles_m, s);
     MatrixView As = A;
     As.At = reinterpret_cast<const float *>(rows_split);
-    return corr_pipelined_launch_nb<2, true>(As, rows, reinterpret_cast<const float *>(ws.res16), N, ws, tiles_m, s);
+    const float *R = reinterpret_cast<const float *>(ws.res16);
+    // 256 right-hand sides per workgroup (128 x 128 outputs per wavefront: a third less LDS traffic per
+    // matrix-core instruction) once that still gives every CU a workgroup and wastes little on a ragged tile
+    if (N >= 1024 && (int64_t)(rows / CORRP_BM) * ((N + 255) / 256) >= 256)
+        return corr_pipelined_launch_nb<4, true>(As, rows, R, N, ws, tiles_m, s);
+    return corr_pipelined_launch_nb<2, true>(As, rows, R, N, ws, tiles_m, s);
 }
 
 // whether the pipelined kernel covers this problem (full tiles of positions, stored rows, even number

@@ -59,6 +59,8 @@ def run_omp(Y, A, k):
     (128, 32768, 64, 4),     # full tiles, 128 of them: the pipelined form of the screening contraction
     (200, 16384, 128, 4),    # the same with a ragged second tile of right-hand sides
     (65, 32768, 64, 3),      # ... one right-hand side in the second tile; the shortest depth loop (two stages)
+    (1040, 16384, 64, 3),    # 256 right-hand sides per workgroup, a ragged fifth tile of them, two stages
+    (1024, 16384, 128, 2),   # ... full tiles, four stages
 ])
 def test_screened_recovery_matches_oracle(N, d, r, k):
     say("screen", N, d, r, k)
