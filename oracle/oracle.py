@@ -254,6 +254,20 @@ def outer_apply(W, B, d, sel_m, x_m, sel_v, x_v, alpha=1.0, eps=1e-8, lr=1e-3):
     return W
 
 
+def outer_refresh(G, rho):
+    """The projection matrix of CESGC (Sec. 4.4): the singular value decomposition of the gradient
+    matrix G [m, n]; the rho leading left singular vectors are the ROWS of B [rho, m]. Returns (B, sigma)
+    with sigma the rho leading singular values, in double. A singular vector's sign is not defined; the
+    rows come back with their largest-magnitude entry positive."""
+    G = np.asarray(G, np.float64)
+    U, s, _ = np.linalg.svd(G, full_matrices=False)
+    B = U[:, :rho].T.copy()
+    for i in range(B.shape[0]):
+        if B[i, np.argmax(np.abs(B[i]))] < 0:
+            B[i] = -B[i]
+    return B, s[:rho].copy()
+
+
 def step_cesgc(G, W, B, m, v, t, At, d, k, beta1=0.9, beta2=0.999, eps=1e-8, lr=1e-3, alpha=1.0):
     """One CESGC step (Sec. 4.4) on one weight matrix: compress with B, run Alg. 2 on the chunks of
     the compressed gradient, take the update back with B^T. m, v: [C, r] with C = rho*n/d."""

@@ -553,3 +553,52 @@ def test_synthetic_matrix_gradient_has_the_given_leading_directions():
     P_svd = U @ U.T
     P_b = basis[:rho].astype(np.float64).T @ basis[:rho].astype(np.float64)
     assert np.abs(P_svd - P_b).max() < 0.15
+
+
+# --------------------------------------------------------------------------- CESGC: the refresh of B
+def _factors(rng, m, n, sigma):
+    """G = U diag(sigma) V^T with orthonormal columns U [m, q], V [n, q] built by Gram-Schmidt (QR) of
+    random matrices: the decomposition is known without calling the routine under test."""
+    q = len(sigma)
+    U, _ = np.linalg.qr(rng.standard_normal((m, q)))
+    V, _ = np.linalg.qr(rng.standard_normal((n, q)))
+    return U, V, (U * sigma) @ V.T
+
+
+def test_refresh_returns_the_factors_a_matrix_was_built_from():
+    # Sec. 4.4: B = the leading left singular vectors, as rows. Distinct singular values: unique up to sign.
+    rng = np.random.default_rng(41)
+    sigma = np.array([9.0, 5.0, 3.0, 2.0, 0.5, 0.1])
+    U, V, G = _factors(rng, 20, 31, sigma)
+    B, s = orc.outer_refresh(G, 4)
+    assert B.shape == (4, 20)
+    assert np.abs(s - sigma[:4]).max() < 1e-12
+    for i in range(4):
+        u = U[:, i] * np.sign(U[np.argmax(np.abs(U[:, i])), i])
+        assert np.abs(B[i] - u).max() < 1e-12, i           # a transposed or column-sliced result fails here
+
+
+def test_refresh_rows_are_orthonormal_and_capture_the_most_energy():
+    # Eckart-Young: among all rho x m matrices with orthonormal rows, B maximises ||B G||_F, and the
+    # maximum is the root of the sum of the rho largest squared singular values
+    rng = np.random.default_rng(42)
+    G = rng.standard_normal((15, 40)) * (0.8 ** np.arange(15))[:, None]
+    B, s = orc.outer_refresh(G, 5)
+    assert np.abs(B @ B.T - np.eye(5)).max() < 1e-12
+    best = np.linalg.norm(B @ G)
+    assert abs(best - np.sqrt((s ** 2).sum())) < 1e-10
+    evals = np.sort(np.linalg.eigvalsh(G @ G.T))[::-1]     # another route to the singular values
+    assert np.abs(s ** 2 - evals[:5]).max() < 1e-10 * evals[0]
+    for trial in range(20):
+        Q, _ = np.linalg.qr(rng.standard_normal((15, 5)))
+        assert np.linalg.norm(Q.T @ G) <= best + 1e-12
+
+
+def test_refresh_of_a_diagonal_matrix_picks_the_largest_entries():
+    G = np.zeros((5, 7))
+    for i, val in enumerate([2.0, -7.0, 0.5, 4.0, 1.0]):
+        G[i, i] = val
+    B, s = orc.outer_refresh(G, 3)
+    assert np.array_equal(s, [7.0, 4.0, 2.0])
+    assert np.array_equal(np.argmax(np.abs(B), axis=1), [1, 3, 0])
+    assert np.abs(np.abs(B).sum(axis=1) - 1).max() < 1e-15 and (B.sum(axis=1) > 0).all()
