@@ -235,8 +235,8 @@ sgc_status sgc_apply(float *W, int64_t C, int32_t d, int32_t k, const int32_t *s
 /*
  * CESGC (Sec. 4.4): SGC on a gradient that a projection B has compressed first. For a weight matrix
  * W (m x n, row-major) with gradient G (m x n) and B (rho x m, row-major; the paper takes the leading
- * left singular vectors of a gradient and refreshes them every fixed number of steps - obtaining B is
- * not part of this library, it is an input) one step is
+ * left singular vectors of a gradient and refreshes them every fixed number of steps: sgc_outer_refresh
+ * below; to the two calls here B is an input) one step is
  *   sgc_outer_project       Gc = B G  (rho x n, row-major)
  *   the four calls of the plain step on Gc read as rho*n/d chunks of d entries (sgc_apply left out)
  *   sgc_outer_apply         W <- W - lr * B^T N,  N (rho x n) the update of eq. 11 in the compressed
@@ -265,6 +265,28 @@ sgc_status sgc_outer_apply(float *W, const float *B, int32_t count, int32_t rho,
                            void *stream);
 
 /*
+ * CESGC (Sec. 4.4), the renewal of B every fixed number of steps: the rows of B become the rho leading
+ * left singular vectors of the gradient matrix G (m x n), in the order of decreasing singular value,
+ * each with its largest-magnitude entry positive (the sign of a singular vector is free).
+ * Method: `iters` rounds of orthogonal iteration on G G^T started from the B handed in (the previous
+ * matrix, or any rho x m matrix of full row rank, e.g. random), then a Rayleigh-Ritz step. Row i
+ * converges at the rate (sigma_{i+1}/sigma_i)^2 per round, the subspace as a whole at
+ * (sigma_{rho+1}/sigma_rho)^2; iters = 0 only rotates an orthonormal B inside its own subspace.
+ *   B      [rho][m] in/out, 16-byte aligned       G  [m][n], float or bfloat16 bit patterns, 16-byte aligned
+ *   sigma  [rho] out or NULL: the singular values, decreasing
+ *   ws     at least sgc_outer_refresh_workspace_bytes(rho, m, n, grad_type) bytes (0 for invalid
+ *          sizes), 256-byte aligned: a transposed copy of G, a rho x n matrix and small factors
+ * The passes over G run on the matrix cores in float; Gram matrices, their Cholesky and Jacobi
+ * factorisations and the rho x rho transforms are in double. Rows that depend on earlier rows to float
+ * accuracy (G of rank below rho) come out as zero rows, with sigma 0.
+ * Errors: NULL, SHAPE (rho, m, n <= 0, rho > 64, rho > m, rho > n, m or n above 2^22, m % 4, n % 4,
+ * iters < 0 or > 1000), DTYPE, ALIGN, WORKSPACE, DEVICE.
+ */
+size_t sgc_outer_refresh_workspace_bytes(int32_t rho, int32_t m, int32_t n, int32_t grad_type);
+sgc_status sgc_outer_refresh(float *B, const void *G, int32_t grad_type, int32_t rho, int32_t m, int32_t n,
+                             int32_t iters, float *sigma, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Instrumentation (not a step of the method): per-kernel timing with HIP events recorded on the
  * caller's stream around every kernel the library launches while enabled.
  *   sgc_profile_enable(1) starts collecting (and discards what was collected), (0) stops.
@@ -272,10 +294,11 @@ sgc_status sgc_outer_apply(float *W, const float *B, int32_t count, int32_t rho,
  *   duration in milliseconds and the launch count per kernel class, and clears the collection.
  * Kernel classes: 0 top-k, 1 projection, 2 Adam, 3 OMP correlation contraction, 4 OMP
  * select+update, 5 apply, 6 other (init, matrix helpers), 7 refill of the generated-matrix panel
- * inside the OMP iterations, 8 sgc_outer_project, 9 sgc_outer_apply (its scatter of N counts as 5).
+ * inside the OMP iterations, 8 sgc_outer_project, 9 sgc_outer_apply (its scatter of N counts as 5), 10 sgc_outer_refresh (its
+ * passes over G count as 8).
  * Not thread-safe; meant for a single measuring thread. Errors: NULL, DEVICE.
  */
-enum { SGC_PROFILE_CLASSES = 10 };
+enum { SGC_PROFILE_CLASSES = 11 };
 typedef struct sgc_profile {
     double ms[SGC_PROFILE_CLASSES];
     int64_t launches[SGC_PROFILE_CLASSES];

@@ -59,7 +59,7 @@ struct OmpWorkspace {
 OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_t k);
 
 // kernel classes of the optional per-kernel timing (see profile.hip)
-enum KernelClass { KC_TOPK = 0, KC_PROJECT, KC_ADAM, KC_CORR, KC_SELECT, KC_APPLY, KC_OTHER, KC_FILL, KC_OUTER_PROJECT, KC_OUTER_APPLY };
+enum KernelClass { KC_TOPK = 0, KC_PROJECT, KC_ADAM, KC_CORR, KC_SELECT, KC_APPLY, KC_OTHER, KC_FILL, KC_OUTER_PROJECT, KC_OUTER_APPLY, KC_OUTER_REFRESH };
 
 // launchers (each returns hipGetLastError() of its launches)
 hipError_t launch_topk(const void *grad, int grad_type, int64_t C, int32_t d, int32_t k, int32_t *idx,
@@ -95,6 +95,20 @@ hipError_t launch_outer_project(const float *B, const void *G, bool g_bf16, int3
 hipError_t launch_outer_apply(float *W, const float *B, int32_t count, int32_t rho, int32_t m, int32_t n, int32_t d,
                               int32_t k, const int32_t *sel_m, const float *x_m, const int32_t *sel_v,
                               const float *x_v, float alpha, float eps, float lr, void *ws, hipStream_t s);
+
+// ---- refresh of the CESGC projection matrix (refresh.hip) ----
+constexpr int REFRESH_MAX_RHO = 64; // the rho x rho factorisations run in one workgroup's LDS, in double
+struct RefreshPlan { // byte offsets into the workspace, 256-byte aligned
+    size_t gt_off;    // G^T in G's own element type
+    size_t z_off;     // rho x n floats
+    size_t part_off;  // partial Gram matrices, doubles
+    size_t m_off;     // the rho x rho transform, doubles
+    size_t outer_off; // workspace of the two outer projections
+    size_t ws_bytes;
+};
+RefreshPlan refresh_plan(int32_t rho, int32_t m, int32_t n, bool g_bf16);
+hipError_t launch_outer_refresh(float *B, const void *G, bool g_bf16, int32_t rho, int32_t m, int32_t n, int32_t iters,
+                                float *sigma, void *ws, hipStream_t s);
 
 // ---- optional per-kernel timing (see profile.hip) ----
 extern bool g_profile_on;

@@ -22,10 +22,11 @@ EXPORTS = [
     "sgc_status_string", "sgc_matrix_fill", "sgc_matrix_colnorms", "sgc_matrix_gram", "sgc_sparsify_project",
     "sgc_adam_compressed", "sgc_omp_workspace_bytes", "sgc_recover_omp", "sgc_recover_omp_shared", "sgc_reproject",
     "sgc_apply", "sgc_outer_workspace_bytes", "sgc_outer_project", "sgc_outer_apply",
+    "sgc_outer_refresh_workspace_bytes", "sgc_outer_refresh",
     "sgc_profile_enable", "sgc_profile_read",
 ]
 PROFILE_CLASSES = ["topk", "project", "adam", "omp_corr", "omp_select_update", "apply", "other", "omp_matrix_fill",
-                   "outer_project", "outer_apply"]
+                   "outer_project", "outer_apply", "outer_refresh"]
 
 
 class sgc_matrix(ctypes.Structure):
@@ -42,7 +43,7 @@ class sgc_hyper(ctypes.Structure):
 
 
 class sgc_profile(ctypes.Structure):
-    _fields_ = [("ms", ctypes.c_double * 10), ("launches", ctypes.c_int64 * 10)]
+    _fields_ = [("ms", ctypes.c_double * len(PROFILE_CLASSES)), ("launches", ctypes.c_int64 * len(PROFILE_CLASSES))]
 
 
 class SgcError(RuntimeError):
@@ -88,6 +89,10 @@ def lib():
         L.sgc_outer_workspace_bytes.argtypes = [i32, i32, i32, i32]
         L.sgc_outer_project.restype = i32
         L.sgc_outer_project.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, sz, vp]
+        L.sgc_outer_refresh_workspace_bytes.restype = sz
+        L.sgc_outer_refresh_workspace_bytes.argtypes = [i32, i32, i32, i32]
+        L.sgc_outer_refresh.restype = i32
+        L.sgc_outer_refresh.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, sz, vp]
         L.sgc_outer_apply.restype = i32
         L.sgc_outer_apply.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, ctypes.POINTER(sgc_hyper), vp, sz, vp]
         L.sgc_profile_enable.restype = i32
@@ -191,6 +196,16 @@ def sgc_outer_project(B, G, count, rho, m, n, Gc, ws, stream=None):
 
 def sgc_outer_apply(W, B, count, rho, m, n, d, k, sel_m, x_m, sel_v, x_v, h, ws, stream=None):
     _check(lib().sgc_outer_apply(_ptr(W), _ptr(B), count, rho, m, n, d, k, _ptr(sel_m), _ptr(x_m), _ptr(sel_v), _ptr(x_v), ctypes.byref(h), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_outer_apply")
+
+
+def sgc_outer_refresh_workspace_bytes(rho, m, n, grad_type=GRAD_F32):
+    return int(lib().sgc_outer_refresh_workspace_bytes(rho, m, n, grad_type))
+
+
+def sgc_outer_refresh(B, G, rho, m, n, iters, sigma, ws, stream=None):
+    gt = GRAD_BF16 if G.dtype in (torch.bfloat16, torch.int16, torch.uint16) else GRAD_F32
+    _check(lib().sgc_outer_refresh(_ptr(B), _ptr(G), gt, rho, m, n, iters, _ptr(sigma) if sigma is not None else None,
+                                   _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_outer_refresh")
 
 
 def sgc_profile_enable(on):
