@@ -104,54 +104,49 @@ __device__ __forceinline__ void sum_partials(const double *__restrict__ part, in
     }
 }
 
-// One workgroup: S = L L^T (Cholesky in double), M = L^-1, so that M X has orthonormal rows.
+// One workgroup: M = L^-1 for S = L L^T (Cholesky), so that M X has orthonormal rows. Computed in double
+// by elimination on the augmented matrix [S | I]: pivot j subtracts multiples of row j from the rows
+// below it, one barrier per pivot; what is left is [D L1^T | L1^-1] with S = L1 D L1^T, and
+// L^-1 = D^-1/2 L1^-1.
 // A pivot that is not above 1e-13 of the row's own squared norm (or not a number) marks a row that
 // depends on the rows before it to the accuracy float data has: its row of M is zero, the row of M X too.
-// dynamic LDS: double S[rho][REFRESH_LD], Xi[rho][REFRESH_LD], diag0[REFRESH_MAX_RHO]
+// dynamic LDS: double S[rho][REFRESH_LD], E[rho][REFRESH_LD], diag0[REFRESH_MAX_RHO]
 __global__ __launch_bounds__(256) void factor_kernel(const double *__restrict__ part, int32_t slices, int32_t rho,
                                                      double *__restrict__ M)
 {
     extern __shared__ __attribute__((aligned(16))) double refresh_lds[];
-    double *S = refresh_lds, *Xi = S + REFRESH_MAX_RHO * REFRESH_LD, *diag0 = Xi + REFRESH_MAX_RHO * REFRESH_LD;
-    __shared__ double piv;
+    double *S = refresh_lds, *E = S + REFRESH_MAX_RHO * REFRESH_LD, *diag0 = E + REFRESH_MAX_RHO * REFRESH_LD;
     const int tid = threadIdx.x;
     sum_partials(part, slices, rho, S);
+    for (int e = tid; e < rho * rho; e += 256)
+        E[(e / rho) * REFRESH_LD + e % rho] = (e / rho == e % rho) ? 1.0 : 0.0;
     __syncthreads();
     if (tid < rho)
         diag0[tid] = S[tid * REFRESH_LD + tid];
     __syncthreads();
-    for (int j = 0; j < rho; ++j) {
-        if (tid == 0) {
-            const double d = S[j * REFRESH_LD + j];
-            const bool live = d > 1e-13 * diag0[j] && d > 0.0 && d < 1e300;
-            piv = live ? sqrt(d) : 0.0;
-            S[j * REFRESH_LD + j] = piv;
-        }
-        __syncthreads();
-        const double p = piv;
-        if (tid > j && tid < rho)
-            S[tid * REFRESH_LD + j] = p > 0.0 ? S[tid * REFRESH_LD + j] / p : 0.0;
-        __syncthreads();
-        for (int e = tid; e < rho * rho; e += 256) {
-            const int i = e / rho, k = e % rho;
-            if (k > j && k <= i)
-                S[i * REFRESH_LD + k] -= S[i * REFRESH_LD + j] * S[k * REFRESH_LD + j];
+    auto live = [&](int j) {
+        const double d = S[j * REFRESH_LD + j];
+        return d > 1e-13 * diag0[j] && d > 0.0 && d < 1e300;
+    };
+    for (int j = 0; j + 1 < rho; ++j) {
+        if (live(j)) { // the same decision in every thread: S[j][j] is not written in this step
+            const double inv = 1.0 / S[j * REFRESH_LD + j];
+            const int below = rho - 1 - j, width = rho; // columns j+1 .. rho-1 of S and 0 .. j of E per row
+            for (int e = tid; e < below * width; e += 256) {
+                const int i = j + 1 + e / width, c = e % width;
+                const double f = S[i * REFRESH_LD + j] * inv; // column j itself is left as it is
+                if (c > j)
+                    S[i * REFRESH_LD + c] -= f * S[j * REFRESH_LD + c];
+                else
+                    E[i * REFRESH_LD + c] -= f * E[j * REFRESH_LD + c];
+            }
         }
         __syncthreads();
     }
-    if (tid < rho) { // column tid of L^-1 by forward substitution
-        const int c = tid;
-        for (int j = 0; j < rho; ++j) {
-            double v = j == c ? 1.0 : 0.0;
-            for (int k = c; k < j; ++k)
-                v -= S[j * REFRESH_LD + k] * Xi[k * REFRESH_LD + c];
-            const double ljj = S[j * REFRESH_LD + j];
-            Xi[j * REFRESH_LD + c] = (j >= c && ljj > 0.0) ? v / ljj : 0.0;
-        }
+    for (int e = tid; e < rho * rho; e += 256) {
+        const int j = e / rho, c = e % rho;
+        M[e] = (c <= j && live(j)) ? E[j * REFRESH_LD + c] / sqrt(S[j * REFRESH_LD + j]) : 0.0;
     }
-    __syncthreads();
-    for (int e = tid; e < rho * rho; e += 256)
-        M[e] = Xi[(e / rho) * REFRESH_LD + e % rho];
 }
 
 // One workgroup: T = V diag(lambda) V^T by two-sided Jacobi rotations in double, rho / 2 disjoint pairs
@@ -252,25 +247,26 @@ __global__ __launch_bounds__(256) void eig_kernel(const double *__restrict__ par
     }
 }
 
-// X <- M X in place (M rho x rho in double, X rho x L in float): a thread owns a column.
-// dynamic LDS: double Ms[rho * rho]; float xs[rho][256]
+// X <- M X in place (M rho x rho in double, X rho x L in float): a workgroup owns 64 columns, four
+// threads share a column and take every fourth row.
+// dynamic LDS: double Ms[rho * rho]; float xs[rho][64]
 __global__ __launch_bounds__(256) void transform_kernel(const double *__restrict__ M, float *__restrict__ X, int32_t rho,
                                                         int64_t L)
 {
     extern __shared__ __attribute__((aligned(16))) double refresh_lds[];
     double *Ms = refresh_lds;
     float *xs = reinterpret_cast<float *>(Ms + rho * rho);
-    const int tid = threadIdx.x;
-    const int64_t c = (int64_t)blockIdx.x * 256 + tid;
+    const int tid = threadIdx.x, col = tid & 63, grp = tid >> 6;
+    const int64_t c = (int64_t)blockIdx.x * 64 + col;
     for (int e = tid; e < rho * rho; e += 256)
         Ms[e] = M[e];
-    for (int j = 0; j < rho; ++j)
-        xs[j * 256 + tid] = c < L ? X[(int64_t)j * L + c] : 0.f;
-    __syncthreads();
-    for (int i = 0; i < rho; ++i) {
+    for (int j = grp; j < rho; j += 4)
+        xs[j * 64 + col] = c < L ? X[(int64_t)j * L + c] : 0.f;
+    __syncthreads(); // every row of the 64 columns is in LDS before any is overwritten
+    for (int i = grp; i < rho; i += 4) {
         double acc = 0.0;
         for (int j = 0; j < rho; ++j)
-            acc = __builtin_fma(Ms[i * rho + j], (double)xs[j * 256 + tid], acc);
+            acc = __builtin_fma(Ms[i * rho + j], (double)xs[j * 64 + col], acc);
         if (c < L)
             X[(int64_t)i * L + c] = (float)acc;
     }
@@ -357,11 +353,8 @@ static hipError_t orthonormalise_rows(float *X, int32_t rho, int64_t L, double *
 
 static hipError_t transform_rows(const double *M, float *X, int32_t rho, int64_t L, hipStream_t s)
 {
-    const size_t smem = (size_t)rho * rho * sizeof(double) + (size_t)rho * 256 * sizeof(float);
-    const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void *>(transform_kernel), smem);
-    if (e != hipSuccess)
-        return e;
-    transform_kernel<<<dim3((unsigned)((L + 255) / 256)), 256, smem, s>>>(M, X, rho, L);
+    const size_t smem = (size_t)rho * rho * sizeof(double) + (size_t)rho * 64 * sizeof(float);
+    transform_kernel<<<dim3((unsigned)((L + 63) / 64)), 256, smem, s>>>(M, X, rho, L);
     return hipGetLastError();
 }
 
