@@ -56,6 +56,10 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (reference for the rocprofv3 FETCH_SIZE / "
                          "WRITE_SIZE counters)")
+    ap.add_argument("--corr-depth-sweep", action="store_true",
+                    help="instead of a step: the correlation contraction alone (24704 right-hand sides, d = 16384, the "
+                         "shape of workload 4) at depths r = 128 .. 2048, with --screen-bf16 its bfloat16 form; the "
+                         "slope is the time per stage of 32 depths, the intercept the fixed cost per launch")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (chunks are independent and would shard by "
@@ -73,6 +77,8 @@ def main():
     dev = "cuda:0"
     if args.cesgc:
         return main_cesgc(args, dev)
+    if args.corr_depth_sweep:
+        return main_depth_sweep(args, dev)
     w = synth.CONFIGS[args.workload]
     if args.chunks:
         w = synth.shrink(w, C=args.chunks)
@@ -280,6 +286,39 @@ def micro_runs(dev):
     res["topk_12352x16384_k64"] = {"ms": round(ms, 4), "algorithmic_GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
                                    "frac_of_8TBps": round(nbytes / (ms * 1e-3) / 8e12, 3)}
     return res
+
+
+def main_depth_sweep(args, dev):
+    """The contraction of the recovery alone at several depths (a labelled micro-measurement, not a step)."""
+    import torch
+    from paper_2502_00311_amd import sgc
+
+    N, d, k = 24704, 16384, 4
+    rows = []
+    for r in (128, 256, 512, 1024, 2048):
+        A = sgc.Matrix(d, r, At=None, seed=5)
+        A.inv_colnorm = torch.empty(d, dtype=torch.float32, device=dev)
+        sgc.sgc_matrix_colnorms(A, A.inv_colnorm)
+        A.flags = sgc.MATRIX_FLAG_SCREEN_BF16 if args.screen_bf16 else 0
+        Y = torch.randn((N, r), device=dev)
+        sel = torch.empty((N, k), dtype=torch.int32, device=dev)
+        x = torch.empty((N, k), device=dev)
+        ws = torch.empty(sgc.sgc_omp_workspace_bytes(N, d, r, k), dtype=torch.uint8, device=dev)
+        sgc.sgc_recover_omp(Y, N, A, k, sel, x, ws)                 # warm-up
+        torch.cuda.synchronize()
+        sgc.sgc_profile_enable(True)
+        sgc.sgc_recover_omp(Y, N, A, k, sel, x, ws)
+        torch.cuda.synchronize()
+        ms, launches = sgc.sgc_profile_read()["omp_corr"]
+        sgc.sgc_profile_enable(False)
+        rows.append({"r": r, "stages": r // 32, "us_per_launch": round(ms / launches * 1e3, 1)})
+        del ws, Y
+    a, b = rows[-2], rows[-1]
+    slope = (b["us_per_launch"] - a["us_per_launch"]) / (b["stages"] - a["stages"])
+    print(json.dumps({"micro": "corr_depth_sweep", "rhs": N, "d": d, "contraction": "bf16 split" if args.screen_bf16 else "float",
+                      "launches": rows, "us_per_stage": round(slope, 2),
+                      "fixed_us": round(b["us_per_launch"] - slope * b["stages"], 1)}))
+    return 0
 
 
 def main_cesgc(args, dev):
