@@ -272,19 +272,22 @@ sgc_status sgc_outer_apply(float *W, const float *B, int32_t count, int32_t rho,
  * matrix, or any rho x m matrix of full row rank, e.g. random), then a Rayleigh-Ritz step. Row i
  * converges at the rate (sigma_{i+1}/sigma_i)^2 per round, the subspace as a whole at
  * (sigma_{rho+1}/sigma_rho)^2; iters = 0 only rotates an orthonormal B inside its own subspace.
- *   B      [rho][m] in/out, 16-byte aligned       G  [m][n], float or bfloat16 bit patterns, 16-byte aligned
- *   sigma  [rho] out or NULL: the singular values, decreasing
- *   ws     at least sgc_outer_refresh_workspace_bytes(rho, m, n, grad_type) bytes (0 for invalid
- *          sizes), 256-byte aligned: a transposed copy of G, a rho x n matrix and small factors
+ * Like the two calls above it takes a batch of `count` equal-sized matrices (every kernel covers the
+ * whole batch; the rho x rho factorisations of different matrices run in different workgroups):
+ *   B      [count][rho][m] in/out, 16-byte aligned
+ *   G      [count][m][n], float or bfloat16 bit patterns, 16-byte aligned
+ *   sigma  [count][rho] out or NULL: the singular values, decreasing
+ *   ws     at least sgc_outer_refresh_workspace_bytes(count, rho, m, n, grad_type) bytes (0 for invalid
+ *          sizes), 256-byte aligned: a transposed copy of G, count rho x n matrices and small factors
  * The passes over G run on the matrix cores in float; Gram matrices, their Cholesky and Jacobi
  * factorisations and the rho x rho transforms are in double. Rows that depend on earlier rows to float
  * accuracy (G of rank below rho) come out as zero rows, with sigma 0.
- * Errors: NULL, SHAPE (rho, m, n <= 0, rho > 64, rho > m, rho > n, m or n above 2^22, m % 4, n % 4,
- * iters < 0 or > 1000), DTYPE, ALIGN, WORKSPACE, DEVICE.
+ * Errors: NULL, SHAPE (count, rho, m, n <= 0, rho > 64, rho > m, rho > n, m or n above 2^22, m % 4, n % 4,
+ * count * ceil(rho/32) above 65535, iters < 0 or > 1000), DTYPE, ALIGN, WORKSPACE, DEVICE.
  */
-size_t sgc_outer_refresh_workspace_bytes(int32_t rho, int32_t m, int32_t n, int32_t grad_type);
-sgc_status sgc_outer_refresh(float *B, const void *G, int32_t grad_type, int32_t rho, int32_t m, int32_t n,
-                             int32_t iters, float *sigma, void *ws, size_t ws_bytes, void *stream);
+size_t sgc_outer_refresh_workspace_bytes(int32_t count, int32_t rho, int32_t m, int32_t n, int32_t grad_type);
+sgc_status sgc_outer_refresh(float *B, const void *G, int32_t grad_type, int32_t count, int32_t rho, int32_t m,
+                             int32_t n, int32_t iters, float *sigma, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Instrumentation (not a step of the method): per-kernel timing with HIP events recorded on the

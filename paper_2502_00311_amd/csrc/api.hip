@@ -270,33 +270,33 @@ sgc_status sgc_outer_apply(float *W, const float *B, int32_t count, int32_t rho,
                                        (float)h->eps, (float)h->lr, ws, (hipStream_t)stream));
 }
 
-static bool refresh_sizes_ok(int32_t rho, int32_t m, int32_t n)
+static bool refresh_sizes_ok(int32_t count, int32_t rho, int32_t m, int32_t n)
 {
-    return outer_sizes_ok(1, rho, m, n) && outer_sizes_ok(1, rho, n, m) && rho <= REFRESH_MAX_RHO && rho <= m &&
+    return outer_sizes_ok(count, rho, m, n) && outer_sizes_ok(count, rho, n, m) && rho <= REFRESH_MAX_RHO && rho <= m &&
            rho <= n && ((int64_t)((m + 31) / 32) * ((n + 31) / 32)) < (1ll << 31);
 }
 
-size_t sgc_outer_refresh_workspace_bytes(int32_t rho, int32_t m, int32_t n, int32_t grad_type)
+size_t sgc_outer_refresh_workspace_bytes(int32_t count, int32_t rho, int32_t m, int32_t n, int32_t grad_type)
 {
-    if (!refresh_sizes_ok(rho, m, n) || (grad_type != SGC_GRAD_F32 && grad_type != SGC_GRAD_BF16))
+    if (!refresh_sizes_ok(count, rho, m, n) || (grad_type != SGC_GRAD_F32 && grad_type != SGC_GRAD_BF16))
         return 0;
-    return refresh_plan(rho, m, n, grad_type == SGC_GRAD_BF16).ws_bytes;
+    return refresh_plan(count, rho, m, n, grad_type == SGC_GRAD_BF16).ws_bytes;
 }
 
-sgc_status sgc_outer_refresh(float *B, const void *G, int32_t grad_type, int32_t rho, int32_t m, int32_t n,
-                             int32_t iters, float *sigma, void *ws, size_t ws_bytes, void *stream)
+sgc_status sgc_outer_refresh(float *B, const void *G, int32_t grad_type, int32_t count, int32_t rho, int32_t m,
+                             int32_t n, int32_t iters, float *sigma, void *ws, size_t ws_bytes, void *stream)
 {
     if (!B || !G || !ws)
         return SGC_ERR_NULL;
     if (grad_type != SGC_GRAD_F32 && grad_type != SGC_GRAD_BF16)
         return SGC_ERR_DTYPE;
-    if (!refresh_sizes_ok(rho, m, n) || iters < 0 || iters > 1000)
+    if (!refresh_sizes_ok(count, rho, m, n) || iters < 0 || iters > 1000)
         return SGC_ERR_SHAPE;
     if (!aligned16(G) || !aligned16(B) || ((uintptr_t)ws & 255u))
         return SGC_ERR_ALIGN;
-    if (ws_bytes < refresh_plan(rho, m, n, grad_type == SGC_GRAD_BF16).ws_bytes)
+    if (ws_bytes < refresh_plan(count, rho, m, n, grad_type == SGC_GRAD_BF16).ws_bytes)
         return SGC_ERR_WORKSPACE;
-    return from_hip(launch_outer_refresh(B, G, grad_type == SGC_GRAD_BF16, rho, m, n, iters, sigma, ws,
+    return from_hip(launch_outer_refresh(B, G, grad_type == SGC_GRAD_BF16, count, rho, m, n, iters, sigma, ws,
                                          (hipStream_t)stream));
 }
 

@@ -23,12 +23,14 @@ constexpr int GRAM_SLICES = 64; // partial Gram matrices (fixed: the summation o
 constexpr int GRAM_COLS = 128;  // columns per block of the Gram kernel
 constexpr int REFRESH_LD = REFRESH_MAX_RHO + 1;
 
-// dst[n][m] = src[m][n]^T, elements of 2 or 4 bytes moved as they are; 1-D grid of 32 x 32 tiles
+// dst[n][m] = src[m][n]^T, elements of 2 or 4 bytes moved as they are; grid.x: 32 x 32 tiles, grid.y: batch
 template <typename T>
 __global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ src, T *__restrict__ dst, int32_t m,
                                                         int32_t n, int32_t tiles_x)
 {
     __shared__ T tile[32][33];
+    src += (int64_t)blockIdx.y * m * n; // matrix of the batch
+    dst += (int64_t)blockIdx.y * m * n;
     const int64_t bx = blockIdx.x % (uint32_t)tiles_x, by = blockIdx.x / (uint32_t)tiles_x;
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
 #pragma unroll
@@ -46,12 +48,15 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ sr
     }
 }
 
-// part[slice] = X_slice X_slice^T in double for the blocks of 128 columns the slice owns; X is rho x L.
+// part[slice] = X_slice X_slice^T in double for the blocks of 128 columns the slice owns; X is rho x L;
+// grid.y: matrix of the batch (GRAM_SLICES partial matrices are reserved for each).
 // Thread (ti, tj) of 16 x 16 accumulates the entries (ti + 16 a, tj + 16 b).
 __global__ __launch_bounds__(256) void gram_partial_kernel(const float *__restrict__ X, int32_t rho, int64_t L,
                                                            double *__restrict__ part)
 {
     __shared__ float xs[REFRESH_MAX_RHO][GRAM_COLS + 1];
+    X += (int64_t)blockIdx.y * rho * L;
+    part += (int64_t)blockIdx.y * GRAM_SLICES * rho * rho;
     const int ti = threadIdx.x >> 4, tj = threadIdx.x & 15;
     double acc[4][4];
 #pragma unroll
@@ -117,6 +122,8 @@ __global__ __launch_bounds__(256) void factor_kernel(const double *__restrict__ 
     extern __shared__ __attribute__((aligned(16))) double refresh_lds[];
     double *S = refresh_lds, *E = S + REFRESH_MAX_RHO * REFRESH_LD, *diag0 = E + REFRESH_MAX_RHO * REFRESH_LD;
     const int tid = threadIdx.x;
+    part += (int64_t)blockIdx.x * GRAM_SLICES * rho * rho; // one workgroup per matrix of the batch
+    M += (int64_t)blockIdx.x * rho * rho;
     sum_partials(part, slices, rho, S);
     for (int e = tid; e < rho * rho; e += 256)
         E[(e / rho) * REFRESH_LD + e % rho] = (e / rho == e % rho) ? 1.0 : 0.0;
@@ -164,6 +171,10 @@ __global__ __launch_bounds__(256) void eig_kernel(const double *__restrict__ par
     __shared__ int rotated;
     const int tid = threadIdx.x;
     const int P = rho + (rho & 1), half = P / 2; // an odd size gets a zero row and column, which never rotate
+    part += (int64_t)blockIdx.x * GRAM_SLICES * rho * rho; // one workgroup per matrix of the batch
+    M += (int64_t)blockIdx.x * rho * rho;
+    if (sigma)
+        sigma += (int64_t)blockIdx.x * rho;
     for (int e = tid; e < REFRESH_MAX_RHO * REFRESH_LD; e += 256) {
         T[e] = 0.0;
         V[e] = (e / REFRESH_LD == e % REFRESH_LD) ? 1.0 : 0.0;
@@ -257,6 +268,8 @@ __global__ __launch_bounds__(256) void transform_kernel(const double *__restrict
     double *Ms = refresh_lds;
     float *xs = reinterpret_cast<float *>(Ms + rho * rho);
     const int tid = threadIdx.x, col = tid & 63, grp = tid >> 6;
+    M += (int64_t)blockIdx.y * rho * rho; // matrix of the batch
+    X += (int64_t)blockIdx.y * rho * L;
     const int64_t c = (int64_t)blockIdx.x * 64 + col;
     for (int e = tid; e < rho * rho; e += 256)
         Ms[e] = M[e];
@@ -308,60 +321,60 @@ __global__ __launch_bounds__(256) void row_sign_kernel(float *__restrict__ B, in
             row[c] = -row[c];
 }
 
-RefreshPlan refresh_plan(int32_t rho, int32_t m, int32_t n, bool g_bf16)
+RefreshPlan refresh_plan(int32_t count, int32_t rho, int32_t m, int32_t n, bool g_bf16)
 {
     auto up = [](size_t b) { return (b + 255) & ~(size_t)255; };
     RefreshPlan p;
     size_t off = 0;
     p.gt_off = off;
-    off += up((size_t)m * n * (g_bf16 ? 2 : 4));
+    off += up((size_t)count * m * n * (g_bf16 ? 2 : 4));
     p.z_off = off;
-    off += up((size_t)rho * n * sizeof(float));
+    off += up((size_t)count * rho * n * sizeof(float));
     p.part_off = off;
-    off += up((size_t)GRAM_SLICES * rho * rho * sizeof(double));
+    off += up((size_t)count * GRAM_SLICES * rho * rho * sizeof(double));
     p.m_off = off;
-    off += up((size_t)rho * rho * sizeof(double));
+    off += up((size_t)count * rho * rho * sizeof(double));
     p.outer_off = off;
-    const size_t a = outer_plan(1, rho, m, n).ws_bytes, b = outer_plan(1, rho, n, m).ws_bytes;
+    const size_t a = outer_plan(count, rho, m, n).ws_bytes, b = outer_plan(count, rho, n, m).ws_bytes;
     off += up(a > b ? a : b);
     p.ws_bytes = off;
     return p;
 }
 
-static hipError_t orthonormalise_rows(float *X, int32_t rho, int64_t L, double *part, double *M, bool ritz, float *sigma,
-                                      hipStream_t s)
+static hipError_t orthonormalise_rows(float *X, int32_t count, int32_t rho, int64_t L, double *part, double *M, bool ritz,
+                                      float *sigma, hipStream_t s)
 {
     const int64_t blocks = (L + GRAM_COLS - 1) / GRAM_COLS;
     const int slices = (int)(blocks < GRAM_SLICES ? blocks : GRAM_SLICES);
-    gram_partial_kernel<<<dim3((unsigned)slices), 256, 0, s>>>(X, rho, L, part);
+    gram_partial_kernel<<<dim3((unsigned)slices, (unsigned)count), 256, 0, s>>>(X, rho, L, part);
     if (ritz) {
         const size_t smem = (size_t)2 * REFRESH_MAX_RHO * REFRESH_LD * sizeof(double) +
                             REFRESH_MAX_RHO * (sizeof(double) + sizeof(int));
         const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void *>(eig_kernel), smem);
         if (e != hipSuccess)
             return e;
-        eig_kernel<<<1, 256, smem, s>>>(part, slices, rho, M, sigma);
+        eig_kernel<<<dim3((unsigned)count), 256, smem, s>>>(part, slices, rho, M, sigma);
     } else {
         const size_t smem = (size_t)(2 * REFRESH_MAX_RHO * REFRESH_LD + REFRESH_MAX_RHO) * sizeof(double);
         const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void *>(factor_kernel), smem);
         if (e != hipSuccess)
             return e;
-        factor_kernel<<<1, 256, smem, s>>>(part, slices, rho, M);
+        factor_kernel<<<dim3((unsigned)count), 256, smem, s>>>(part, slices, rho, M);
     }
     return hipGetLastError();
 }
 
-static hipError_t transform_rows(const double *M, float *X, int32_t rho, int64_t L, hipStream_t s)
+static hipError_t transform_rows(const double *M, float *X, int32_t count, int32_t rho, int64_t L, hipStream_t s)
 {
     const size_t smem = (size_t)rho * rho * sizeof(double) + (size_t)rho * 64 * sizeof(float);
-    transform_kernel<<<dim3((unsigned)((L + 63) / 64)), 256, smem, s>>>(M, X, rho, L);
+    transform_kernel<<<dim3((unsigned)((L + 63) / 64), (unsigned)count), 256, smem, s>>>(M, X, rho, L);
     return hipGetLastError();
 }
 
-hipError_t launch_outer_refresh(float *B, const void *G, bool g_bf16, int32_t rho, int32_t m, int32_t n, int32_t iters,
-                                float *sigma, void *ws, hipStream_t s)
+hipError_t launch_outer_refresh(float *B, const void *G, bool g_bf16, int32_t count, int32_t rho, int32_t m, int32_t n,
+                                int32_t iters, float *sigma, void *ws, hipStream_t s)
 {
-    const RefreshPlan pl = refresh_plan(rho, m, n, g_bf16);
+    const RefreshPlan pl = refresh_plan(count, rho, m, n, g_bf16);
     char *base = static_cast<char *>(ws);
     void *Gt = base + pl.gt_off;
     float *Z = reinterpret_cast<float *>(base + pl.z_off);
@@ -372,7 +385,7 @@ hipError_t launch_outer_refresh(float *B, const void *G, bool g_bf16, int32_t rh
     {
         ProfileScope prof(KC_OUTER_REFRESH, s);
         const int64_t tiles_x = (n + 31) / 32, tiles_y = (m + 31) / 32;
-        const dim3 grid((unsigned)(tiles_x * tiles_y));
+        const dim3 grid((unsigned)(tiles_x * tiles_y), (unsigned)count);
         if (g_bf16)
             transpose_kernel<uint16_t><<<grid, 256, 0, s>>>(static_cast<const uint16_t *>(G),
                                                             static_cast<uint16_t *>(Gt), m, n, (int32_t)tiles_x);
@@ -384,28 +397,28 @@ hipError_t launch_outer_refresh(float *B, const void *G, bool g_bf16, int32_t rh
     }
     for (int32_t it = 0; it <= iters; ++it) {
         const bool last = it == iters;
-        if ((e = launch_outer_project(B, G, g_bf16, 1, rho, m, n, Z, ows, s)) != hipSuccess) // Z = Q G
+        if ((e = launch_outer_project(B, G, g_bf16, count, rho, m, n, Z, ows, s)) != hipSuccess) // Z = Q G
             return e;
         {
             ProfileScope prof(KC_OUTER_REFRESH, s);
-            if ((e = orthonormalise_rows(Z, rho, n, part, M, last, sigma, s)) != hipSuccess)
+            if ((e = orthonormalise_rows(Z, count, rho, n, part, M, last, sigma, s)) != hipSuccess)
                 return e;
             if (last) { // Rayleigh-Ritz: B = V^T Q, then the sign convention
-                if ((e = transform_rows(M, B, rho, m, s)) != hipSuccess)
+                if ((e = transform_rows(M, B, count, rho, m, s)) != hipSuccess)
                     return e;
-                row_sign_kernel<<<dim3((unsigned)rho), 256, 0, s>>>(B, m);
+                row_sign_kernel<<<dim3((unsigned)(rho * count)), 256, 0, s>>>(B, m);
                 return hipGetLastError();
             }
-            if ((e = transform_rows(M, Z, rho, n, s)) != hipSuccess)
+            if ((e = transform_rows(M, Z, count, rho, n, s)) != hipSuccess)
                 return e;
         }
-        if ((e = launch_outer_project(Z, Gt, g_bf16, 1, rho, n, m, B, ows, s)) != hipSuccess) // Y = Z G^T
+        if ((e = launch_outer_project(Z, Gt, g_bf16, count, rho, n, m, B, ows, s)) != hipSuccess) // Y = Z G^T
             return e;
         {
             ProfileScope prof(KC_OUTER_REFRESH, s);
-            if ((e = orthonormalise_rows(B, rho, m, part, M, false, nullptr, s)) != hipSuccess)
+            if ((e = orthonormalise_rows(B, count, rho, m, part, M, false, nullptr, s)) != hipSuccess)
                 return e;
-            if ((e = transform_rows(M, B, rho, m, s)) != hipSuccess)
+            if ((e = transform_rows(M, B, count, rho, m, s)) != hipSuccess)
                 return e;
         }
     }

@@ -98,7 +98,7 @@ hipError_t launch_outer_apply(float *W, const float *B, int32_t count, int32_t r
 
 // ---- refresh of the CESGC projection matrix (refresh.hip) ----
 constexpr int REFRESH_MAX_RHO = 64; // the rho x rho factorisations run in one workgroup's LDS, in double
-struct RefreshPlan { // byte offsets into the workspace, 256-byte aligned
+struct RefreshPlan { // byte offsets into the workspace, 256-byte aligned; every region holds the whole batch
     size_t gt_off;    // G^T in G's own element type
     size_t z_off;     // rho x n floats
     size_t part_off;  // partial Gram matrices, doubles
@@ -106,9 +106,9 @@ struct RefreshPlan { // byte offsets into the workspace, 256-byte aligned
     size_t outer_off; // workspace of the two outer projections
     size_t ws_bytes;
 };
-RefreshPlan refresh_plan(int32_t rho, int32_t m, int32_t n, bool g_bf16);
-hipError_t launch_outer_refresh(float *B, const void *G, bool g_bf16, int32_t rho, int32_t m, int32_t n, int32_t iters,
-                                float *sigma, void *ws, hipStream_t s);
+RefreshPlan refresh_plan(int32_t count, int32_t rho, int32_t m, int32_t n, bool g_bf16);
+hipError_t launch_outer_refresh(float *B, const void *G, bool g_bf16, int32_t count, int32_t rho, int32_t m, int32_t n,
+                                int32_t iters, float *sigma, void *ws, hipStream_t s);
 
 // ---- optional per-kernel timing (see profile.hip) ----
 extern bool g_profile_on;

@@ -90,9 +90,9 @@ def lib():
         L.sgc_outer_project.restype = i32
         L.sgc_outer_project.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, sz, vp]
         L.sgc_outer_refresh_workspace_bytes.restype = sz
-        L.sgc_outer_refresh_workspace_bytes.argtypes = [i32, i32, i32, i32]
+        L.sgc_outer_refresh_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
         L.sgc_outer_refresh.restype = i32
-        L.sgc_outer_refresh.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, sz, vp]
+        L.sgc_outer_refresh.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, sz, vp]
         L.sgc_outer_apply.restype = i32
         L.sgc_outer_apply.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, ctypes.POINTER(sgc_hyper), vp, sz, vp]
         L.sgc_profile_enable.restype = i32
@@ -198,13 +198,13 @@ def sgc_outer_apply(W, B, count, rho, m, n, d, k, sel_m, x_m, sel_v, x_v, h, ws,
     _check(lib().sgc_outer_apply(_ptr(W), _ptr(B), count, rho, m, n, d, k, _ptr(sel_m), _ptr(x_m), _ptr(sel_v), _ptr(x_v), ctypes.byref(h), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_outer_apply")
 
 
-def sgc_outer_refresh_workspace_bytes(rho, m, n, grad_type=GRAD_F32):
-    return int(lib().sgc_outer_refresh_workspace_bytes(rho, m, n, grad_type))
+def sgc_outer_refresh_workspace_bytes(count, rho, m, n, grad_type=GRAD_F32):
+    return int(lib().sgc_outer_refresh_workspace_bytes(count, rho, m, n, grad_type))
 
 
-def sgc_outer_refresh(B, G, rho, m, n, iters, sigma, ws, stream=None):
+def sgc_outer_refresh(B, G, count, rho, m, n, iters, sigma, ws, stream=None):
     gt = GRAD_BF16 if G.dtype in (torch.bfloat16, torch.int16, torch.uint16) else GRAD_F32
-    _check(lib().sgc_outer_refresh(_ptr(B), _ptr(G), gt, rho, m, n, iters, _ptr(sigma) if sigma is not None else None,
+    _check(lib().sgc_outer_refresh(_ptr(B), _ptr(G), gt, count, rho, m, n, iters, _ptr(sigma) if sigma is not None else None,
                                    _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_outer_refresh")
 
 

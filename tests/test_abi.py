@@ -212,19 +212,21 @@ def test_outer_projection_rejects_bad_arguments_and_sizes_workspace():
     assert call(nb=small - 1) == sgc.ERR_WORKSPACE
     # the renewal of B: sizes are validated before anything touches the device
     f = L.sgc_outer_refresh
-    need = sgc.sgc_outer_refresh_workspace_bytes(4, 64, 128)
+    need = sgc.sgc_outer_refresh_workspace_bytes(1, 4, 64, 128)
     assert need > 64 * 128 * 4 + 4 * 128 * 4                      # a transposed copy of G and a rho x n matrix
-    assert sgc.sgc_outer_refresh_workspace_bytes(4, 64, 128, sgc.GRAD_BF16) == need - 64 * 128 * 2
-    for bad in ((65, 64, 128), (0, 64, 128), (4, 62, 128), (4, 64, 126), (8, 4, 128), (8, 128, 4), (4, 64, 1 << 23)):
+    assert sgc.sgc_outer_refresh_workspace_bytes(1, 4, 64, 128, sgc.GRAD_BF16) == need - 64 * 128 * 2
+    assert sgc.sgc_outer_refresh_workspace_bytes(3, 4, 64, 128) > 2 * need
+    for bad in ((1, 65, 64, 128), (1, 0, 64, 128), (1, 4, 62, 128), (1, 4, 64, 126), (1, 8, 4, 128), (1, 8, 128, 4),
+                (1, 4, 64, 1 << 23), (0, 4, 64, 128), (70000, 4, 64, 128)):
         assert sgc.sgc_outer_refresh_workspace_bytes(*bad) == 0, bad
-    assert sgc.sgc_outer_refresh_workspace_bytes(4, 64, 128, 7) == 0
+    assert sgc.sgc_outer_refresh_workspace_bytes(1, 4, 64, 128, 7) == 0
 
-    def fresh(B=FAKE, G=FAKE, gt=0, rho=4, m=64, n=128, iters=2, ws=FAKE, nb=need):
-        return f(B, G, gt, rho, m, n, iters, None, ws, nb, None)
+    def fresh(B=FAKE, G=FAKE, gt=0, count=1, rho=4, m=64, n=128, iters=2, ws=FAKE, nb=need):
+        return f(B, G, gt, count, rho, m, n, iters, None, ws, nb, None)
 
     assert fresh(B=None) == sgc.ERR_NULL and fresh(G=None) == sgc.ERR_NULL and fresh(ws=None) == sgc.ERR_NULL
     assert fresh(gt=3) == sgc.ERR_DTYPE
     assert fresh(rho=65) == sgc.ERR_SHAPE and fresh(m=62) == sgc.ERR_SHAPE and fresh(n=126) == sgc.ERR_SHAPE
     assert fresh(iters=-1) == sgc.ERR_SHAPE and fresh(iters=1001) == sgc.ERR_SHAPE
     assert fresh(B=ODD) == sgc.ERR_ALIGN and fresh(G=ODD) == sgc.ERR_ALIGN and fresh(ws=ODD) == sgc.ERR_ALIGN
-    assert fresh(nb=need - 1) == sgc.ERR_WORKSPACE
+    assert fresh(nb=need - 1) == sgc.ERR_WORKSPACE and fresh(count=2) == sgc.ERR_WORKSPACE and fresh(count=0) == sgc.ERR_SHAPE

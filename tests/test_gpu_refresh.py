@@ -37,9 +37,9 @@ def refresh(G, rho, iters, start=None, seed=0):
     B = dev(start.astype(np.float32))
     Gd = G if isinstance(G, torch.Tensor) else dev(G)
     gt = sgc.GRAD_BF16 if Gd.dtype in (torch.int16, torch.bfloat16) else sgc.GRAD_F32
-    ws = torch.empty(sgc.sgc_outer_refresh_workspace_bytes(rho, m, n, gt), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(sgc.sgc_outer_refresh_workspace_bytes(1, rho, m, n, gt), dtype=torch.uint8, device=DEV)
     sigma = torch.empty(rho, dtype=torch.float32, device=DEV)
-    sgc.sgc_outer_refresh(B, Gd, rho, m, n, iters, sigma, ws)
+    sgc.sgc_outer_refresh(B, Gd, 1, rho, m, n, iters, sigma, ws)
     torch.cuda.synchronize()
     return B.cpu().numpy().astype(np.float64), sigma.cpu().numpy().astype(np.float64)
 
@@ -82,6 +82,26 @@ def test_refresh_bfloat16_gradient():
     assert np.abs(s / sref - 1).max() < 1e-3
     assert np.abs(B.T @ B - Bref.T @ Bref).max() < 1e-4
     assert np.abs(B - Bref).max() < 1e-4
+
+
+def test_refresh_batch_of_matrices():
+    # three different matrices in one call: every kernel covers the batch, results per matrix as alone
+    rng = np.random.default_rng(12)
+    count, m, n, rho = 3, 160, 288, 7
+    Gs = np.stack([spectrum_matrix(rng, m, n, (2.0 + j) * 0.55 ** np.arange(10)) for j in range(count)])
+    start = rng.standard_normal((count, rho, m)).astype(np.float32)
+    B = dev(start)
+    ws = torch.empty(sgc.sgc_outer_refresh_workspace_bytes(count, rho, m, n), dtype=torch.uint8, device=DEV)
+    sigma = torch.empty((count, rho), dtype=torch.float32, device=DEV)
+    sgc.sgc_outer_refresh(B, dev(Gs), count, rho, m, n, 14, sigma, ws)
+    torch.cuda.synchronize()
+    Bn, sn = B.cpu().numpy().astype(np.float64), sigma.cpu().numpy().astype(np.float64)
+    for j in range(count):
+        Bref, sref = orc.outer_refresh(Gs[j], rho)
+        assert np.abs(sn[j] / sref - 1).max() < 1e-3, j
+        assert np.abs(Bn[j] - Bref).max() < 1e-4, j
+        alone, s_alone = refresh(Gs[j], rho, 14, start=start[j])
+        assert np.array_equal(alone, Bn[j]) and np.array_equal(s_alone, sn[j]), j   # fixed summation orders
 
 
 def test_refresh_equal_singular_values_give_the_same_subspace():
@@ -170,17 +190,18 @@ def test_refresh_validation():
     L = sgc.lib()
     B = torch.zeros((4, 64), device=DEV)
     G = torch.zeros((64, 64), device=DEV)
-    ws = torch.empty(sgc.sgc_outer_refresh_workspace_bytes(4, 64, 64), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(sgc.sgc_outer_refresh_workspace_bytes(1, 4, 64, 64), dtype=torch.uint8, device=DEV)
     p = lambda t: t.data_ptr()
     ok = lambda **kw: L.sgc_outer_refresh(*[kw.get(k, d) for k, d in [
-        ("B", p(B)), ("G", p(G)), ("gt", 0), ("rho", 4), ("m", 64), ("n", 64), ("iters", 1), ("sigma", None),
+        ("B", p(B)), ("G", p(G)), ("gt", 0), ("count", 1), ("rho", 4), ("m", 64), ("n", 64), ("iters", 1), ("sigma", None),
         ("ws", p(ws)), ("wsb", ws.numel()), ("stream", None)]])
     assert ok() == 0
     assert ok(B=None) == sgc.ERR_NULL and ok(G=None) == sgc.ERR_NULL and ok(ws=None) == sgc.ERR_NULL
     assert ok(gt=5) == sgc.ERR_DTYPE
-    for bad in (dict(rho=0), dict(rho=65), dict(m=62), dict(n=30), dict(iters=-1), dict(iters=1001), dict(rho=4, m=2)):
+    assert ok(count=2) == sgc.ERR_WORKSPACE                        # sized for one matrix
+    for bad in (dict(count=0), dict(rho=0), dict(rho=65), dict(m=62), dict(n=30), dict(iters=-1), dict(iters=1001), dict(rho=4, m=2)):
         assert ok(**bad) == sgc.ERR_SHAPE, bad
     assert ok(B=p(B) + 4) == sgc.ERR_ALIGN and ok(ws=p(ws) + 16) == sgc.ERR_ALIGN
     assert ok(wsb=ws.numel() - 1) == sgc.ERR_WORKSPACE
-    assert sgc.sgc_outer_refresh_workspace_bytes(65, 64, 64) == 0
+    assert sgc.sgc_outer_refresh_workspace_bytes(1, 65, 64, 64) == 0
     torch.cuda.synchronize()
