@@ -1,6 +1,7 @@
 """Seeded random shapes of the other entry points against the oracle: sparsify + project (sizes on both
 sides of every kernel choice, ties, zeros, heavy tails, bfloat16 gradients, both matrix modes; top-k
-bit-exact) and the two outer products of CESGC (ragged and full tiles, batches)."""
+bit-exact), the two outer products of CESGC (ragged and full tiles, batches) and the renewal of its projection
+matrix (random sizes, ranks and batches; spectra that converge in the rounds given)."""
 import numpy as np
 import pytest
 import torch
@@ -108,3 +109,35 @@ def test_outer_products_random_shape(seed):
         lo, hi = c * Cm, (c + 1) * Cm
         ref = orc.outer_apply(W[c], B[c], d, sel[lo:hi], x[lo:hi], sel[lo:hi], z[lo:hi], alpha=2.0, eps=1e-3, lr=0.01)
         assert relerr(Wn[c] - W[c], ref.astype(np.float64) - W[c]) < 1e-4, c
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_outer_refresh_random_shape(seed):
+    rng = np.random.default_rng(7000 + seed)
+    rho = int(rng.integers(1, 65))
+    m = 4 * int(rng.integers((rho + 3) // 4, 160))
+    n = 4 * int(rng.integers((rho + 3) // 4, 160))
+    count = int(rng.integers(1, 4))
+    q = min(m, n, rho + 3)
+    ratio = 0.5 if rho <= 12 else (0.75 if rho <= 24 else 0.88)   # keeps the spectrum within float's reach
+    iters = {0.5: 14, 0.75: 30, 0.88: 70}[ratio]
+    say("outer_refresh", seed, dict(count=count, rho=rho, m=m, n=n, ratio=ratio))
+    Gs = []
+    for _ in range(count):
+        U, _r = np.linalg.qr(rng.standard_normal((m, q)))
+        V, _r = np.linalg.qr(rng.standard_normal((n, q)))
+        Gs.append(((U * (2.0 * ratio ** np.arange(q))) @ V.T).astype(np.float32))
+    Gs = np.stack(Gs)
+    B = dev(rng.standard_normal((count, rho, m)).astype(np.float32))
+    ws = torch.empty(sgc.sgc_outer_refresh_workspace_bytes(count, rho, m, n), dtype=torch.uint8, device=DEV)
+    sig = torch.empty((count, rho), device=DEV)
+    sgc.sgc_outer_refresh(B, dev(Gs), count, rho, m, n, iters, sig, ws)
+    torch.cuda.synchronize()
+    Bn, sn = B.cpu().numpy().astype(np.float64), sig.cpu().numpy().astype(np.float64)
+    for j in range(count):
+        Bref, sref = orc.outer_refresh(Gs[j], rho)
+        lead = max(1, int(np.sum(sref / sref[0] > 3e-2)))         # rows far enough above the float rounding of the passes
+        assert np.abs(Bn[j] @ Bn[j].T - np.eye(rho)).max() < 1e-5, j
+        assert np.abs(sn[j] / sref - 1).max() < 2e-3, j
+        assert np.abs(Bn[j][:lead] - Bref[:lead]).max() < 2e-4, j
+        assert np.abs(Bn[j].T @ Bn[j] - Bref.T @ Bref).max() < 5e-3, j
