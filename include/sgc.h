@@ -206,6 +206,30 @@ sgc_status sgc_recover_omp_shared(const float *y_m, const float *y_v, int32_t C,
                                   float *z, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * The same recovery with the correlation recurrence of App. B (Alg. 3) in place of the contraction:
+ * with the table G = A^H A (A->gram, see sgc_matrix_gram) the correlation vector p = A^H res is formed
+ * once, p0 = A^H y, and then updated in every iteration, p <- p - b_j a_j, where b_j = A^H q_j is the
+ * image of the new orthonormal direction and follows from the earlier ones,
+ * b_j = gamma_j (G_:lambda_j - sum_t c_t b_t). The b_t of every right-hand side are kept (the d x k
+ * matrix B of App. B, floats): an iteration streams them, one row of G, and p. Selection and
+ * least-squares update are those of sgc_recover_omp - the candidates near the maximum of p are re-scored
+ * in double against the residual, so the support is the same whenever the float recurrence keeps the true
+ * maximum within 2^-10 of its own (it does while the residual stays well above float rounding of y, i.e. not
+ * after an exact recovery with iterations to spare).
+ *   arguments as sgc_recover_omp; A->gram must be set; d % 4 == 0; a generated matrix must fit the
+ *   workspace's panel whole (at most 64 MiB, or d <= N k)
+ *   ws   at least sgc_omp_recurrence_workspace_bytes(N, d, r, k) bytes (0 for invalid sizes): the
+ *        workspace of sgc_recover_omp plus N (k + 1) d floats
+ * On this machine the recurrence is the slower engine at every benchmark shape (it moves 4 d (j + 5) bytes
+ * per right-hand side and iteration j where the contraction spends 2 d r flop): it is here for callers
+ * with r > 28 k, and as the measured form of that comparison.
+ * Errors: as sgc_recover_omp; NULL also when A->gram is not set.
+ */
+size_t sgc_omp_recurrence_workspace_bytes(int32_t N, int32_t d, int32_t r, int32_t k);
+sgc_status sgc_recover_omp_recurrence(const float *y, int32_t N, const sgc_matrix *A /* host */, int32_t k,
+                                      int32_t *sel, float *x, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * SGCA re-alignment of compressed moments with a new measurement matrix (App. C, Alg. 4 lines
  * 9-12: every T steps A' is drawn and M <- A' OMP_A(M), V <- A' OMP_A(V), A <- A'):
  *   out[n] = scale * A' x_n   for N sparse vectors given as (sel[n], x[n]), k entries each,

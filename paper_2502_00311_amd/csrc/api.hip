@@ -178,6 +178,36 @@ sgc_status sgc_recover_omp(const float *y, int32_t N, const sgc_matrix *A, int32
     return from_hip(launch_omp(y, N, make_view(A), k, sel, x, w, (hipStream_t)stream));
 }
 
+size_t sgc_omp_recurrence_workspace_bytes(int32_t N, int32_t d, int32_t r, int32_t k)
+{
+    if (!omp_sizes_ok(N, d, r, k) || d % 4 != 0)
+        return 0;
+    return carve_recurrence(nullptr, N, d, r, k).bytes;
+}
+
+sgc_status sgc_recover_omp_recurrence(const float *y, int32_t N, const sgc_matrix *A, int32_t k, int32_t *sel,
+                                      float *x, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!y || !sel || !x || !ws)
+        return SGC_ERR_NULL;
+    sgc_status st = check_matrix(A, true);
+    if (st != SGC_OK)
+        return st;
+    if (!A->gram)
+        return SGC_ERR_NULL;
+    if (!omp_sizes_ok(N, A->d, A->r, k) || A->d % 4 != 0)
+        return SGC_ERR_SHAPE;
+    if (!aligned16(y) || !aligned16(A->inv_colnorm) || !aligned16(A->gram) || ((uintptr_t)ws & 255u))
+        return SGC_ERR_ALIGN;
+    const OmpWorkspace w = carve_recurrence(ws, N, A->d, A->r, k);
+    // a generated matrix must fit the workspace's panel as a whole: the selection reads its columns from there
+    if (A->mode == SGC_MATRIX_PHILOX && w.panel_rows < A->d)
+        return SGC_ERR_SHAPE;
+    if (ws_bytes < w.bytes)
+        return SGC_ERR_WORKSPACE;
+    return from_hip(launch_omp(y, N, make_view(A), k, sel, x, w, (hipStream_t)stream, nullptr, nullptr, true));
+}
+
 sgc_status sgc_recover_omp_shared(const float *y_m, const float *y_v, int32_t C, const sgc_matrix *A, int32_t k,
                                   int32_t *sel, float *x, float *z, void *ws, size_t ws_bytes, void *stream)
 {

@@ -81,6 +81,22 @@ OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_
     return w;
 }
 
+OmpWorkspace carve_recurrence(void *base, int32_t N, int32_t d, int32_t r, int32_t k)
+{
+    OmpWorkspace w = carve_workspace(base, N, d, r, k);
+    size_t off = w.bytes;
+    auto take = [&](size_t bytes) {
+        void *p = base ? (void *)((char *)base + off) : nullptr;
+        off += (bytes + 255) & ~(size_t)255;
+        return p;
+    };
+    w.rc_p = (float *)take(sizeof(float) * (size_t)N * d);
+    w.rc_B = (float *)take(sizeof(float) * (size_t)N * k * d);
+    w.cvec = (double *)take(sizeof(double) * (size_t)N * k);
+    w.bytes = off;
+    return w;
+}
+
 // res_split != 0: the float copy of the residual is written in split32 format instead (see corr_split_kernel)
 __global__ __launch_bounds__(256) void omp_init_kernel(const float *__restrict__ y, int32_t r, int32_t words,
                                                        double *__restrict__ res64, float *__restrict__ res32,
@@ -437,6 +453,8 @@ __global__ __launch_bounds__(FACTOR_MAX_THREADS) void update_kernel(IterArgs P, 
                 facc[q] += v[c][q] * dt[c];
             cc += dt[c] * dt[c];
             ca += t < it ? dt[c] * a_s[t] : 0.0;
+            if (W.cvec && writer && lane == 0 && t < it)
+                W.cvec[n * k + t] = dt[c]; // the correlation recurrence combines the earlier image vectors with these
         }
     }
     if (lane == 0) {
@@ -674,6 +692,7 @@ struct OmpPlan {
     MatrixView Apick; // the view pick_kernel fetches columns from
     size_t pick_smem, factor_smem;
     bool factor_share_table; // update_kernel sums its wavefronts' shares through an LDS table
+    bool recurrence; // the correlation vector is updated by App. B's recurrence instead of contracted anew
 };
 
 // the workspace as seen by the right-hand sides [n0, ...): every per-right-hand-side array shifted
@@ -802,7 +821,7 @@ static hipError_t omp_iterations(const OmpPlan &pl, bool whole_matrix_panel, con
                                  hipStream_t s);
 
 hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k, int32_t *sel, float *x,
-                      const OmpWorkspace &ws, hipStream_t s, const float *y_fit, float *z)
+                      const OmpWorkspace &ws, hipStream_t s, const float *y_fit, float *z, bool recurrence)
 {
     // A generated matrix is written out once per call when the workspace has room for all of it. One
     // that does not fit is regenerated inside the contraction when few right-hand-side tiles share it;
@@ -822,6 +841,13 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
     if (pl.screen)
         pl.pipelined = false;
     pl.tiles_m = pl.pipelined || pl.screen_pipelined ? A.d / CORRP_BM : corr_tiles_m(A.d);
+    pl.recurrence = recurrence;
+    if (recurrence) { // no contraction inside the iterations: none of its operand copies is prepared
+        if (!A.gram || !ws.rc_p || A.d % 4 != 0 || (A.generated && ws.panel_rows < A.d))
+            return hipErrorInvalidValue;
+        pl.pipelined = pl.screen = pl.screen_pipelined = false;
+        pl.tiles_m = (A.d + 255) / 256;
+    }
     pl.pick_smem = ((size_t)A.r * 4 + 15) & ~(size_t)15;
     pl.factor_smem = 3 * sizeof(double) * (size_t)k;
     {
@@ -871,6 +897,28 @@ static hipError_t omp_iterations(const OmpPlan &pl, bool whole_matrix_panel, con
     // and not when both halves would have to share a panel that is refilled inside the iterations)
     const int32_t N0 = (N / 2 + CORR_BN - 1) / CORR_BN * CORR_BN;
     SideStream *ss = nullptr;
+    if (pl.recurrence) {
+        // p0 = A^H y and its best keys; then selection, update, and the recurrence for the next selection
+        const OmpWorkspace w = shift_workspace(ws, 0, A.r, k, pl.tiles_m);
+        {
+            ProfileScope prof(KC_CORR, s);
+            hipError_t e = recur_init_launch(pl.Apick, y, N, w, s);
+            if (e == hipSuccess)
+                e = recur_step_launch(true, A, N, k, 0, sel, w, pl.tiles_m, s);
+            if (e != hipSuccess)
+                return e;
+        }
+        for (int32_t it = 0; it < k; ++it) {
+            omp_select_update(pl, A, y, N, k, it, sel, x, w, s);
+            if (it + 1 < k) {
+                ProfileScope prof(KC_CORR, s);
+                const hipError_t e = recur_step_launch(false, A, N, k, it, sel, w, pl.tiles_m, s);
+                if (e != hipSuccess)
+                    return e;
+            }
+        }
+        return hipGetLastError();
+    }
     if (N >= 4 * CORR_BN && N0 < N && !g_profile_on && !(pl.panels && !whole_matrix_panel))
         ss = side_stream();
     if (!ss) {

@@ -49,6 +49,11 @@ hipError_t corr_general_launch(bool generated, const MatrixView &A, int32_t rows
 // the bfloat16 screening contraction on split rows
 hipError_t corr_screen_launch(bool pipelined, const MatrixView &A, const uint16_t *rows_split, int32_t rows, int32_t N,
                               const OmpWorkspace &ws, int32_t tiles_m, hipStream_t s);
+// the correlation recurrence of App. B (omp_recur.hip): p0 = A^H y written out; then per iteration the new
+// image vector, the update of p and the two best keys per tile of 256 positions (first: the keys only)
+hipError_t recur_init_launch(const MatrixView &A, const float *y, int32_t N, const OmpWorkspace &w, hipStream_t s);
+hipError_t recur_step_launch(bool first, const MatrixView &A, int32_t N, int32_t k, int32_t it, const int32_t *sel,
+                             const OmpWorkspace &w, int32_t tiles, hipStream_t s);
 // whether the pipelined kernel covers this problem
 bool corr_pipelined_ok(const MatrixView &A, int32_t N, int32_t panel_rows);
 

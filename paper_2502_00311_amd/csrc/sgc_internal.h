@@ -55,8 +55,14 @@ struct OmpWorkspace {
     int32_t words;     // bitmap words per right-hand side
     int32_t tiles_m;
     size_t bytes;
+    // only with the correlation recurrence of App. B (carve_recurrence), else null:
+    float *rc_p;       // [N][d] correlation vector
+    float *rc_B;       // [N][k][d] images b_t = A^H q_t of the orthonormal directions
+    double *cvec;      // [N][k] coordinates c_t of the newest column, exported by update_kernel
 };
 OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_t k);
+// the same workspace followed by the three arrays of the recurrence; `bytes` covers both
+OmpWorkspace carve_recurrence(void *base, int32_t N, int32_t d, int32_t r, int32_t k);
 
 // kernel classes of the optional per-kernel timing (see profile.hip)
 enum KernelClass { KC_TOPK = 0, KC_PROJECT, KC_ADAM, KC_CORR, KC_SELECT, KC_APPLY, KC_OTHER, KC_FILL, KC_OUTER_PROJECT, KC_OUTER_APPLY, KC_OUTER_REFRESH };
@@ -74,7 +80,8 @@ hipError_t launch_matrix_fill(uint32_t key0, uint32_t key1, float scale, int32_t
 hipError_t launch_colnorms(const MatrixView &A, float *out, hipStream_t s);
 hipError_t launch_gram(const MatrixView &A, double *out, hipStream_t s);
 hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k, int32_t *sel, float *x,
-                      const OmpWorkspace &ws, hipStream_t s, const float *y_fit = nullptr, float *z = nullptr);
+                      const OmpWorkspace &ws, hipStream_t s, const float *y_fit = nullptr, float *z = nullptr,
+                      bool recurrence = false);
 hipError_t launch_apply(float *W, int64_t C, int32_t d, int32_t k, const int32_t *sel_m, const float *x_m,
                         const int32_t *sel_v, const float *x_v, float alpha, float eps, float lr,
                         hipStream_t s);

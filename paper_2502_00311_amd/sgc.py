@@ -21,6 +21,7 @@ MATRIX_FLAG_SCREEN_BF16 = 1
 EXPORTS = [
     "sgc_status_string", "sgc_matrix_fill", "sgc_matrix_colnorms", "sgc_matrix_gram", "sgc_sparsify_project",
     "sgc_adam_compressed", "sgc_omp_workspace_bytes", "sgc_recover_omp", "sgc_recover_omp_shared", "sgc_reproject",
+    "sgc_omp_recurrence_workspace_bytes", "sgc_recover_omp_recurrence",
     "sgc_apply", "sgc_outer_workspace_bytes", "sgc_outer_project", "sgc_outer_apply",
     "sgc_outer_refresh_workspace_bytes", "sgc_outer_refresh",
     "sgc_profile_enable", "sgc_profile_read",
@@ -79,6 +80,10 @@ def lib():
         L.sgc_omp_workspace_bytes.argtypes = [i32, i32, i32, i32]
         L.sgc_recover_omp.restype = i32
         L.sgc_recover_omp.argtypes = [vp, i32, ctypes.POINTER(sgc_matrix), i32, vp, vp, vp, sz, vp]
+        L.sgc_omp_recurrence_workspace_bytes.restype = sz
+        L.sgc_omp_recurrence_workspace_bytes.argtypes = [i32, i32, i32, i32]
+        L.sgc_recover_omp_recurrence.restype = i32
+        L.sgc_recover_omp_recurrence.argtypes = [vp, i32, ctypes.POINTER(sgc_matrix), i32, vp, vp, vp, sz, vp]
         L.sgc_recover_omp_shared.restype = i32
         L.sgc_recover_omp_shared.argtypes = [vp, vp, i32, ctypes.POINTER(sgc_matrix), i32, vp, vp, vp, vp, sz, vp]
         L.sgc_reproject.restype = i32
@@ -171,6 +176,14 @@ def sgc_omp_workspace_bytes(N, d, r, k):
 
 def sgc_recover_omp(y, N, A, k, sel, x, ws, stream=None):
     _check(lib().sgc_recover_omp(_ptr(y), N, ctypes.byref(A.c()), k, _ptr(sel), _ptr(x), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_recover_omp")
+
+
+def sgc_omp_recurrence_workspace_bytes(N, d, r, k):
+    return int(lib().sgc_omp_recurrence_workspace_bytes(N, d, r, k))
+
+
+def sgc_recover_omp_recurrence(y, N, A, k, sel, x, ws, stream=None):
+    _check(lib().sgc_recover_omp_recurrence(_ptr(y), N, ctypes.byref(A.c()), k, _ptr(sel), _ptr(x), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_recover_omp_recurrence")
 
 
 def sgc_recover_omp_shared(y_m, y_v, C, A, k, sel, x, z, ws, stream=None):
