@@ -43,6 +43,9 @@ def main():
     ap.add_argument("--gram", action="store_true",
                     help="build the optional table of column inner products (sgc_matrix_gram, 8 d^2 bytes, once, "
                          "outside the timed region) and let the recovery use it")
+    ap.add_argument("--recurrence", action="store_true",
+                    help="recover with the correlation recurrence of App. B (sgc_recover_omp_recurrence; builds the "
+                         "Gram table like --gram and needs N (k + 1) d more floats of workspace): a variant")
     ap.add_argument("--screen-bf16", action="store_true",
                     help="screen the correlation contraction on the bfloat16 matrix cores (split operands, three "
                          "products); candidates are re-scored in double either way")
@@ -101,6 +104,11 @@ def main():
     if args.screen_bf16:
         A.flags = sgc.MATRIX_FLAG_SCREEN_BF16
     gram_ms = None
+    if args.recurrence:
+        if args.shared_support or args.screen_bf16:
+            print("bench.py: --recurrence goes with the two-support recovery and no screening", file=sys.stderr)
+            return 2
+        args.gram = True
     if args.gram:
         A.gram = torch.empty((d, d), dtype=torch.float64, device=dev)
         torch.cuda.synchronize()
@@ -115,7 +123,7 @@ def main():
         grads.append(torch.from_numpy(g.view(np.int16) if w.grad == "bf16" else g).to(dev))
     W0 = torch.from_numpy(synth.weights(w)).to(dev)
     Wt = W0.clone()
-    buf = sgc.StepBuffers(C, d, r, k, device=dev)
+    buf = sgc.StepBuffers(C, d, r, k, device=dev, recurrence=args.recurrence)
     h = sgc.hyper()
 
     def reset():
@@ -169,8 +177,18 @@ def main():
         "traffic": None if (args.shared_support or args.screen_bf16) else MEASURED_TRAFFIC.get(w.name),
         "flops_per_launch": flops_per_launch, "avg_launch_ms": round(avg_ms, 5), "launches": corr_n,
     }
+    if args.recurrence:
+        # no contraction inside the iterations: the class holds p0 = A^H y (once per call) and the k - 1 updates
+        # of p, which stream the image vectors b_t (4 d j bytes at iteration j), a row of the table (8 d), the
+        # new b (4 d written) and p (8 d) per right-hand side
+        total = float(nrhs) * d * sum(4.0 * j + 20.0 for j in range(1, k)) + 8.0 * nrhs * d
+        gbps = total / (corr_ms / K * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "correlation recurrence p <- p - b a (App. B), all its launches of a step",
+                    "achieved": round(gbps, 1), "peak": 8000.0, "unit": "GB/s", "frac": round(gbps / 8000.0, 4),
+                    "traffic": None, "bytes_per_step": total, "ms_per_step": round(corr_ms / K, 3), "launches": corr_n}
     if fill_ms > 0:  # generated A produced by a separate fill kernel: the rate including that time
-        roofline["achieved_incl_matrix_fill"] = round(flops_per_launch * corr_n / ((corr_ms + fill_ms) * 1e-3) / 1e12, 3)
+        if not args.recurrence:
+            roofline["achieved_incl_matrix_fill"] = round(flops_per_launch * corr_n / ((corr_ms + fill_ms) * 1e-3) / 1e12, 3)
     kernels = {n: {"ms_per_step": round(ms / K, 4), "launches_per_step": cnt / K} for n, (ms, cnt) in prof.items()}
     # HBM-bound companions (algorithmic bytes / event time)
     bytes_adam = 32.0 * C * r
@@ -192,7 +210,8 @@ def main():
                    "rhs_per_omp_call": nrhs,
                    "recovery": "shared_support" if args.shared_support else "two_supports",
                    "gram_table": bool(args.gram),
-                   "contraction": "bf16 split (3 products), float accumulate" if args.screen_bf16 else "float"},
+                   "contraction": "none inside the iterations (correlation recurrence)" if args.recurrence
+                   else ("bf16 split (3 products), float accumulate" if args.screen_bf16 else "float")},
         "roofline": roofline,
         "ms_per_step_with_events": round((t3 - t2) * 1e3 / K, 3),
         "gram_build_ms": None if gram_ms is None else round(gram_ms, 2),
@@ -200,7 +219,7 @@ def main():
     }
 
     # ---- the optional variants of the recovery, three steps each (context, not the headline) ----
-    if not args.no_variants and not (args.shared_support or args.screen_bf16 or args.gram):
+    if not args.no_variants and not (args.shared_support or args.screen_bf16 or args.gram or args.recurrence):
         variants = {}
         nv = min(3, nsteps)
         for name, shared, flags in (("shared_support", True, 0),

@@ -235,9 +235,10 @@ def sgc_profile_read():
 class StepBuffers:
     """Device buffers of one SGC step on C chunks (allocation only; no arithmetic)."""
 
-    def __init__(self, C, d, r, k, device="cuda"):
+    def __init__(self, C, d, r, k, device="cuda", recurrence=False):
         f32, i32 = torch.float32, torch.int32
         self.C, self.d, self.r, self.k = C, d, r, k
+        self.recurrence = recurrence  # workspace sized for sgc_recover_omp_recurrence, which step() then calls
         self.idx = torch.empty((C, k), dtype=i32, device=device)
         self.val = torch.empty((C, k), dtype=f32, device=device)
         self.p = torch.empty((C, r), dtype=f32, device=device)
@@ -247,7 +248,7 @@ class StepBuffers:
         self.hat = torch.empty((2 * C, r), dtype=f32, device=device)  # [mhat; vhat]
         self.sel = torch.empty((2 * C, k), dtype=i32, device=device)
         self.x = torch.empty((2 * C, k), dtype=f32, device=device)
-        nbytes = sgc_omp_workspace_bytes(2 * C, d, r, k)
+        nbytes = (sgc_omp_recurrence_workspace_bytes if recurrence else sgc_omp_workspace_bytes)(2 * C, d, r, k)
         if nbytes == 0:
             raise SgcError(ERR_SHAPE, "sgc_omp_workspace_bytes")
         self.ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
@@ -269,7 +270,7 @@ def step(grad, W, buf, A, t, h, stream=None, shared_support=False, A_new=None):
             sgc_reproject(buf.sel[:C], buf.x[:C], C, k, A_new, 1.0 - h.beta1 ** t, buf.m, stream)
             sgc_reproject(buf.sel[:C], buf.x[C:], C, k, A_new, 1.0 - h.beta2 ** t, buf.v, stream)
         return
-    sgc_recover_omp(buf.hat, 2 * C, A, k, buf.sel, buf.x, buf.ws, stream)
+    (sgc_recover_omp_recurrence if buf.recurrence else sgc_recover_omp)(buf.hat, 2 * C, A, k, buf.sel, buf.x, buf.ws, stream)
     sgc_apply(W, C, d, k, buf.sel[:C], buf.x[:C], buf.sel[C:], buf.x[C:], h, stream)
     if A_new is not None:
         sgc_reproject(buf.sel[:C], buf.x[:C], C, k, A_new, 1.0 - h.beta1 ** t, buf.m, stream)

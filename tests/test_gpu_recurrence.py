@@ -86,6 +86,27 @@ def test_recurrence_matches_oracle_and_contraction(N, d, r, k, mode):
     assert np.array_equal(x.view(np.uint32), x2.view(np.uint32))
 
 
+def test_recurrence_at_benchmark_shape_agrees_with_the_contraction_engine():
+    # configuration 3's shape (d = 16384, r = 1024, k = 64, generated matrix) on 192 right-hand sides with the
+    # heavy tails of the benchmark's moments: 64 updates of p per right-hand side, every selection identical.
+    # (The contraction engine is checked against the oracle at this size in test_gpu_full_size.py.)
+    rng = np.random.default_rng(17)
+    N, d, r, k = 192, 16384, 1024, 64
+    A, _ = make_matrix("philox", 9, d, r)
+    Y = (rng.standard_t(3.0, size=(N, r)) * 1e-3).astype(np.float32)
+    Y[N // 2:] = np.abs(Y[N // 2:]) * 1e-3               # like second moments: non-negative, much smaller
+    sel, x = run(Y, A, k, True)
+    sel2, x2 = run(Y, A, k, False)
+    assert np.array_equal(sel, sel2)
+    assert np.array_equal(x.view(np.uint32), x2.view(np.uint32))
+    # sampled right-hand sides against the oracle itself
+    At = orc.philox_matrix(9, d, r)
+    for n in (0, 77, 100, 191):
+        rsel, rx = orc.omp_batch(Y[n:n + 1], At, k)
+        assert np.array_equal(sel[n], rsel[0]), n
+        assert relerr(x[n], rx[0]) < TOL, n
+
+
 def test_recurrence_exact_recovery():
     # k-sparse vectors measured without noise, k iterations: every pick is made on a residual far above rounding
     rng = np.random.default_rng(3)
