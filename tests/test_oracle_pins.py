@@ -602,3 +602,48 @@ def test_refresh_of_a_diagonal_matrix_picks_the_largest_entries():
     assert np.array_equal(s, [7.0, 4.0, 2.0])
     assert np.array_equal(np.argmax(np.abs(B), axis=1), [1, 3, 0])
     assert np.abs(np.abs(B).sum(axis=1) - 1).max() < 1e-15 and (B.sum(axis=1) > 0).all()
+
+
+# --------------------------------------------------------------------------- App. B: the recurrences
+def test_appendix_b_recurrences_reach_the_definition():
+    """App. B (Alg. 3) never forms a residual: it carries the correlation vector p, the images
+    b_t = A^H q_t of the orthonormal directions and the inverse Cholesky factor F, and states
+    p <- p - b_j a_j, b_j = gamma_j (G_:lambda - B c), a_j = gamma_j p_lambda (p before the update),
+    gamma_j = 1/sqrt(G_ll - c.c), c = F^H w, x = F a. Written out here in double exactly as stated (with
+    F_1 = gamma_1, the only reading under which x = F a is the least-squares solution), it must make the
+    oracle's selections, reproduce its least-squares values and keep p equal to A^H (y - A_Lambda x):
+    the oracle follows the plain definition, so this pins both it and the reading of App. B the GPU
+    engines use."""
+    rng = np.random.default_rng(77)
+    d, r, k = 300, 48, 10
+    At = (rng.standard_normal((d, r)) / np.sqrt(r)).astype(np.float32)
+    y = rng.standard_normal(r).astype(np.float32)
+    ref = orc.omp(y, At, k)
+    A = At.astype(np.float64).T                       # r x d
+    G = A.T @ A
+    norms = np.sqrt(np.diag(G))
+    p = A.T @ y.astype(np.float64)
+    F = np.zeros((k, k))
+    a = np.zeros(k)
+    B = np.zeros((d, k))
+    lam_list = []
+    for j in range(k):
+        score = np.abs(p) / norms
+        score[lam_list] = -1.0
+        lam = int(np.argmax(score))
+        assert lam == ref["sel"][j], j
+        w = G[lam_list, lam]
+        c = F[:j, :j].T @ w
+        gamma = 1.0 / np.sqrt(G[lam, lam] - c @ c)
+        b = gamma * (G[:, lam] - B[:, :j] @ c)
+        F[:j, j] = -gamma * (F[:j, :j] @ c)
+        F[j, j] = gamma
+        a[j] = gamma * p[lam]
+        p = p - b * a[j]
+        B[:, j] = b
+        lam_list.append(lam)
+        x = F[:j + 1, :j + 1] @ a[:j + 1]
+        res = y.astype(np.float64) - A[:, lam_list] @ x
+        assert np.abs(p - A.T @ res).max() < 1e-12 * np.abs(y).max() * 10
+    assert np.abs(x - ref["x64"]).max() < 1e-10 * np.abs(ref["x64"]).max()
+    assert np.abs(res - ref["res"]).max() < 1e-10
