@@ -46,6 +46,9 @@ def main():
     ap.add_argument("--recurrence", action="store_true",
                     help="recover with the correlation recurrence of App. B (sgc_recover_omp_recurrence; builds the "
                          "Gram table like --gram and needs N (k + 1) d more floats of workspace): a variant")
+    ap.add_argument("--recurrence-head", type=int, default=0,
+                    help="with --recurrence: the recurrence serves only the first H iterations, the contraction "
+                         "the rest (0 = all k iterations)")
     ap.add_argument("--screen-bf16", action="store_true",
                     help="screen the correlation contraction on the bfloat16 matrix cores (split operands, three "
                          "products); candidates are re-scored in double either way")
@@ -105,8 +108,8 @@ def main():
         A.flags = sgc.MATRIX_FLAG_SCREEN_BF16
     gram_ms = None
     if args.recurrence:
-        if args.shared_support or args.screen_bf16:
-            print("bench.py: --recurrence goes with the two-support recovery and no screening", file=sys.stderr)
+        if args.shared_support:
+            print("bench.py: --recurrence goes with the two-support recovery", file=sys.stderr)
             return 2
         args.gram = True
     if args.gram:
@@ -123,7 +126,7 @@ def main():
         grads.append(torch.from_numpy(g.view(np.int16) if w.grad == "bf16" else g).to(dev))
     W0 = torch.from_numpy(synth.weights(w)).to(dev)
     Wt = W0.clone()
-    buf = sgc.StepBuffers(C, d, r, k, device=dev, recurrence=args.recurrence)
+    buf = sgc.StepBuffers(C, d, r, k, device=dev, recurrence=(args.recurrence_head or True) if args.recurrence else False)
     h = sgc.hyper()
 
     def reset():
@@ -181,11 +184,23 @@ def main():
         # no contraction inside the iterations: the class holds p0 = A^H y (once per call) and the k - 1 updates
         # of p, which stream the image vectors b_t (4 d j bytes at iteration j), a row of the table (8 d), the
         # new b (4 d written) and p (8 d) per right-hand side
-        total = float(nrhs) * d * sum(4.0 * j + 20.0 for j in range(1, k)) + 8.0 * nrhs * d
-        gbps = total / (corr_ms / K * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "correlation recurrence p <- p - b a (App. B), all its launches of a step",
-                    "achieved": round(gbps, 1), "peak": 8000.0, "unit": "GB/s", "frac": round(gbps / 8000.0, 4),
-                    "traffic": None, "bytes_per_step": total, "ms_per_step": round(corr_ms / K, 3), "launches": corr_n}
+        head = args.recurrence_head or k
+        total = float(nrhs) * d * sum(4.0 * j + 20.0 for j in range(1, head)) + 8.0 * nrhs * d
+        if head == k:
+            gbps = total / (corr_ms / K * 1e-3) / 1e9
+            roofline = {"bound": "hbm", "kernel": "correlation recurrence p <- p - b a (App. B), all its launches of a step",
+                        "achieved": round(gbps, 1), "peak": 8000.0, "unit": "GB/s", "frac": round(gbps / 8000.0, 4),
+                        "traffic": None, "bytes_per_step": total, "ms_per_step": round(corr_ms / K, 3), "launches": corr_n}
+        else:
+            # both engines inside one class of launches: the contraction's flop over the whole class's time is a
+            # lower bound of its rate
+            flops = 2.0 * d * r * nrhs * (k - head)
+            tf = flops / (corr_ms / K * 1e-3) / 1e12
+            roofline = {"bound": "mfma", "kernel": "recurrence for %d iterations, then the float contraction; rate = the "
+                        "contraction's flop over the time of both" % head,
+                        "achieved": round(tf, 3), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": round(tf / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None,
+                        "recurrence_bytes_per_step": total, "ms_per_step": round(corr_ms / K, 3), "launches": corr_n}
     if fill_ms > 0:  # generated A produced by a separate fill kernel: the rate including that time
         if not args.recurrence:
             roofline["achieved_incl_matrix_fill"] = round(flops_per_launch * corr_n / ((corr_ms + fill_ms) * 1e-3) / 1e12, 3)
@@ -210,7 +225,8 @@ def main():
                    "rhs_per_omp_call": nrhs,
                    "recovery": "shared_support" if args.shared_support else "two_supports",
                    "gram_table": bool(args.gram),
-                   "contraction": "none inside the iterations (correlation recurrence)" if args.recurrence
+                   "contraction": ("none inside the iterations (correlation recurrence)" if not args.recurrence_head
+                                   else "correlation recurrence for %d iterations, then float" % args.recurrence_head) if args.recurrence
                    else ("bf16 split (3 products), float accumulate" if args.screen_bf16 else "float")},
         "roofline": roofline,
         "ms_per_step_with_events": round((t3 - t2) * 1e3 / K, 3),

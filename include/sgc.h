@@ -216,18 +216,22 @@ sgc_status sgc_recover_omp_shared(const float *y_m, const float *y_v, int32_t C,
  * in double against the residual, so the support is the same whenever the float recurrence keeps the true
  * maximum within 2^-10 of its own (it does while the residual stays well above float rounding of y, i.e. not
  * after an exact recovery with iterations to spare).
- *   arguments as sgc_recover_omp; A->gram must be set; d % 4 == 0; a generated matrix must fit the
+ *   head  the recurrence serves the selections of iterations 0 .. head-1; from iteration `head` on the
+ *         correlations come from the contraction of sgc_recover_omp, which needs no state of its own.
+ *         head = k is App. B throughout. Iteration j of the recurrence moves 4 d (j + 5) bytes per right-hand
+ *         side where the contraction spends 2 d r flop, so on this machine the recurrence is the cheaper of the
+ *         two while j + 5 < r / 50 or so, and a head of that size the fastest choice for a caller that
+ *         holds the table anyway
+ *   other arguments as sgc_recover_omp; A->gram must be set; d % 4 == 0; a generated matrix must fit the
  *   workspace's panel whole (at most 64 MiB, or d <= N k)
- *   ws   at least sgc_omp_recurrence_workspace_bytes(N, d, r, k) bytes (0 for invalid sizes): the
- *        workspace of sgc_recover_omp plus N (k + 1) d floats
- * On this machine the recurrence is the slower engine at every benchmark shape (it moves 4 d (j + 5) bytes
- * per right-hand side and iteration j where the contraction spends 2 d r flop): it is here for callers
- * with r > 28 k, and as the measured form of that comparison.
- * Errors: as sgc_recover_omp; NULL also when A->gram is not set.
+ *   ws    at least sgc_omp_recurrence_workspace_bytes(N, d, r, k, head) bytes (0 for invalid sizes): the
+ *         workspace of sgc_recover_omp plus N (head + 1) d floats
+ * Errors: as sgc_recover_omp; SHAPE also for head < 1 or head > k; NULL also when A->gram is not set.
  */
-size_t sgc_omp_recurrence_workspace_bytes(int32_t N, int32_t d, int32_t r, int32_t k);
+size_t sgc_omp_recurrence_workspace_bytes(int32_t N, int32_t d, int32_t r, int32_t k, int32_t head);
 sgc_status sgc_recover_omp_recurrence(const float *y, int32_t N, const sgc_matrix *A /* host */, int32_t k,
-                                      int32_t *sel, float *x, void *ws, size_t ws_bytes, void *stream);
+                                      int32_t head, int32_t *sel, float *x, void *ws, size_t ws_bytes,
+                                      void *stream);
 
 /*
  * SGCA re-alignment of compressed moments with a new measurement matrix (App. C, Alg. 4 lines

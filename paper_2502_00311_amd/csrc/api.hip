@@ -178,15 +178,15 @@ sgc_status sgc_recover_omp(const float *y, int32_t N, const sgc_matrix *A, int32
     return from_hip(launch_omp(y, N, make_view(A), k, sel, x, w, (hipStream_t)stream));
 }
 
-size_t sgc_omp_recurrence_workspace_bytes(int32_t N, int32_t d, int32_t r, int32_t k)
+size_t sgc_omp_recurrence_workspace_bytes(int32_t N, int32_t d, int32_t r, int32_t k, int32_t head)
 {
-    if (!omp_sizes_ok(N, d, r, k) || d % 4 != 0)
+    if (!omp_sizes_ok(N, d, r, k) || d % 4 != 0 || head < 1 || head > k)
         return 0;
-    return carve_recurrence(nullptr, N, d, r, k).bytes;
+    return carve_recurrence(nullptr, N, d, r, k, head).bytes;
 }
 
-sgc_status sgc_recover_omp_recurrence(const float *y, int32_t N, const sgc_matrix *A, int32_t k, int32_t *sel,
-                                      float *x, void *ws, size_t ws_bytes, void *stream)
+sgc_status sgc_recover_omp_recurrence(const float *y, int32_t N, const sgc_matrix *A, int32_t k, int32_t head,
+                                      int32_t *sel, float *x, void *ws, size_t ws_bytes, void *stream)
 {
     if (!y || !sel || !x || !ws)
         return SGC_ERR_NULL;
@@ -195,11 +195,11 @@ sgc_status sgc_recover_omp_recurrence(const float *y, int32_t N, const sgc_matri
         return st;
     if (!A->gram)
         return SGC_ERR_NULL;
-    if (!omp_sizes_ok(N, A->d, A->r, k) || A->d % 4 != 0)
+    if (!omp_sizes_ok(N, A->d, A->r, k) || A->d % 4 != 0 || head < 1 || head > k)
         return SGC_ERR_SHAPE;
     if (!aligned16(y) || !aligned16(A->inv_colnorm) || !aligned16(A->gram) || ((uintptr_t)ws & 255u))
         return SGC_ERR_ALIGN;
-    const OmpWorkspace w = carve_recurrence(ws, N, A->d, A->r, k);
+    const OmpWorkspace w = carve_recurrence(ws, N, A->d, A->r, k, head);
     // a generated matrix must fit the workspace's panel as a whole: the selection reads its columns from there
     if (A->mode == SGC_MATRIX_PHILOX && w.panel_rows < A->d)
         return SGC_ERR_SHAPE;

@@ -81,7 +81,7 @@ OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_
     return w;
 }
 
-OmpWorkspace carve_recurrence(void *base, int32_t N, int32_t d, int32_t r, int32_t k)
+OmpWorkspace carve_recurrence(void *base, int32_t N, int32_t d, int32_t r, int32_t k, int32_t head)
 {
     OmpWorkspace w = carve_workspace(base, N, d, r, k);
     size_t off = w.bytes;
@@ -91,7 +91,9 @@ OmpWorkspace carve_recurrence(void *base, int32_t N, int32_t d, int32_t r, int32
         return p;
     };
     w.rc_p = (float *)take(sizeof(float) * (size_t)N * d);
-    w.rc_B = (float *)take(sizeof(float) * (size_t)N * k * d);
+    w.rc_head = head;
+    w.rc_d = d;
+    w.rc_B = (float *)take(sizeof(float) * (size_t)N * head * d);
     w.cvec = (double *)take(sizeof(double) * (size_t)N * k);
     w.bytes = off;
     return w;
@@ -707,10 +709,17 @@ static OmpWorkspace shift_workspace(const OmpWorkspace &ws, int32_t n0, int32_t 
     w.res32 += (int64_t)n0 * r;
     w.res16 += (int64_t)n0 * 2 * r;
     w.cols += (int64_t)n0 * k * r;
-    w.partial += (int64_t)n0 * tiles_m * 2;
+    // ws.tiles_m is the capacity the workspace was carved for: a half's keys start at the same place whatever
+    // tiling its current producer uses (the two producers of the hybrid recovery tile differently)
+    w.partial += (int64_t)n0 * ws.tiles_m * 2;
     w.bitmap += (int64_t)n0 * ws.words;
     w.wv += (int64_t)n0 * k;
     w.gb += (int64_t)n0 * 2;
+    if (w.rc_p) { // the recurrence's arrays
+        w.rc_p += (int64_t)n0 * ws.rc_d;
+        w.rc_B += (int64_t)n0 * ws.rc_head * ws.rc_d;
+        w.cvec += (int64_t)n0 * k;
+    }
     return w;
 }
 
@@ -842,12 +851,9 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
         pl.pipelined = false;
     pl.tiles_m = pl.pipelined || pl.screen_pipelined ? A.d / CORRP_BM : corr_tiles_m(A.d);
     pl.recurrence = recurrence;
-    if (recurrence) { // no contraction inside the iterations: none of its operand copies is prepared
-        if (!A.gram || !ws.rc_p || A.d % 4 != 0 || (A.generated && ws.panel_rows < A.d))
-            return hipErrorInvalidValue;
-        pl.pipelined = pl.screen = pl.screen_pipelined = false;
-        pl.tiles_m = (A.d + 255) / 256;
-    }
+    if (recurrence && (!A.gram || !ws.rc_p || ws.rc_head < 1 || ws.rc_head > k || A.d % 4 != 0 ||
+                       (A.generated && ws.panel_rows < A.d)))
+        return hipErrorInvalidValue;
     pl.pick_smem = ((size_t)A.r * 4 + 15) & ~(size_t)15;
     pl.factor_smem = 3 * sizeof(double) * (size_t)k;
     {
@@ -893,59 +899,64 @@ static hipError_t omp_iterations(const OmpPlan &pl, bool whole_matrix_panel, con
                                  const MatrixView &A, int32_t k, int32_t *sel, float *x, const OmpWorkspace &ws,
                                  hipStream_t s)
 {
+    // A group of right-hand sides [n0, n0 + Ng) advancing on one stream. What produces the keys of
+    // iteration `it`: the contraction, or - for the first rc_head iterations of the recurrence engine - p0
+    // and then the update of p after the selection before. The two tile the positions differently, so the
+    // selection kernel is handed the matching view of the workspace.
+    struct Group {
+        int32_t n0, Ng;
+        OmpWorkspace wc, wr;
+        hipStream_t st;
+    };
+    const int32_t head = pl.recurrence ? ws.rc_head : 0;
+    auto make_group = [&](int32_t n0, int32_t Ng, hipStream_t st) {
+        Group g{n0, Ng, shift_workspace(ws, n0, A.r, k, pl.tiles_m), shift_workspace(ws, n0, A.r, k, (A.d + 255) / 256), st};
+        g.wc.cvec = nullptr; // nothing reads the coordinates once the contraction has taken over
+        return g;
+    };
+    auto iterate = [&](const Group &g, int32_t it) -> hipError_t {
+        hipError_t e;
+        if (it < head) {
+            ProfileScope prof(KC_CORR, g.st);
+            if (it == 0) {
+                e = recur_init_launch(pl.Apick, y + (int64_t)g.n0 * A.r, g.Ng, g.wr, g.st);
+                if (e == hipSuccess)
+                    e = recur_step_launch(true, A, g.Ng, k, 0, sel + (int64_t)g.n0 * k, g.wr, g.wr.tiles_m, g.st);
+            } else {
+                e = recur_step_launch(false, A, g.Ng, k, it - 1, sel + (int64_t)g.n0 * k, g.wr, g.wr.tiles_m, g.st);
+            }
+        } else {
+            e = omp_contraction(pl, A, g.Ng, g.wc, g.st);
+        }
+        if (e != hipSuccess)
+            return e;
+        omp_select_update(pl, A, y + (int64_t)g.n0 * A.r, g.Ng, k, it, sel + (int64_t)g.n0 * k, x + (int64_t)g.n0 * k,
+                          it < head ? g.wr : g.wc, g.st);
+        return hipSuccess;
+    };
     // two halves side by side when the batch is large (not while kernels are being timed one by one,
     // and not when both halves would have to share a panel that is refilled inside the iterations)
     const int32_t N0 = (N / 2 + CORR_BN - 1) / CORR_BN * CORR_BN;
     SideStream *ss = nullptr;
-    if (pl.recurrence) {
-        // p0 = A^H y and its best keys; then selection, update, and the recurrence for the next selection
-        const OmpWorkspace w = shift_workspace(ws, 0, A.r, k, pl.tiles_m);
-        {
-            ProfileScope prof(KC_CORR, s);
-            hipError_t e = recur_init_launch(pl.Apick, y, N, w, s);
-            if (e == hipSuccess)
-                e = recur_step_launch(true, A, N, k, 0, sel, w, pl.tiles_m, s);
-            if (e != hipSuccess)
-                return e;
-        }
-        for (int32_t it = 0; it < k; ++it) {
-            omp_select_update(pl, A, y, N, k, it, sel, x, w, s);
-            if (it + 1 < k) {
-                ProfileScope prof(KC_CORR, s);
-                const hipError_t e = recur_step_launch(false, A, N, k, it, sel, w, pl.tiles_m, s);
-                if (e != hipSuccess)
-                    return e;
-            }
-        }
-        return hipGetLastError();
-    }
     if (N >= 4 * CORR_BN && N0 < N && !g_profile_on && !(pl.panels && !whole_matrix_panel))
         ss = side_stream();
     if (!ss) {
-        const OmpWorkspace w = shift_workspace(ws, 0, A.r, k, pl.tiles_m);
+        const Group g = make_group(0, N, s);
         for (int32_t it = 0; it < k; ++it) {
-            hipError_t e = omp_contraction(pl, A, N, w, s);
+            const hipError_t e = iterate(g, it);
             if (e != hipSuccess)
                 return e;
-            omp_select_update(pl, A, y, N, k, it, sel, x, w, s);
         }
         return hipGetLastError();
     }
-    const OmpWorkspace w0 = shift_workspace(ws, 0, A.r, k, pl.tiles_m);
-    const OmpWorkspace w1 = shift_workspace(ws, N0, A.r, k, pl.tiles_m);
+    const Group g0 = make_group(0, N0, s), g1 = make_group(N0, N - N0, ss->stream);
     if (hipEventRecord(ss->fork, s) != hipSuccess || hipStreamWaitEvent(ss->stream, ss->fork, 0) != hipSuccess)
         return hipErrorUnknown;
     hipError_t e = hipSuccess;
     for (int32_t it = 0; it < k && e == hipSuccess; ++it) {
-        e = omp_contraction(pl, A, N0, w0, s);
-        if (e != hipSuccess)
-            break;
-        omp_select_update(pl, A, y, N0, k, it, sel, x, w0, s);
-        e = omp_contraction(pl, A, N - N0, w1, ss->stream);
-        if (e != hipSuccess)
-            break;
-        omp_select_update(pl, A, y + (int64_t)N0 * A.r, N - N0, k, it, sel + (int64_t)N0 * k, x + (int64_t)N0 * k, w1,
-                          ss->stream);
+        e = iterate(g0, it);
+        if (e == hipSuccess)
+            e = iterate(g1, it);
     }
     // join even after a failed launch so that the caller's stream never runs ahead of the side stream
     if (hipEventRecord(ss->join, ss->stream) != hipSuccess || hipStreamWaitEvent(s, ss->join, 0) != hipSuccess)

@@ -84,7 +84,8 @@ struct RecurArgs {
     const double *avec;       // [N][k] coefficients a
     const double *cvec;       // [N][k] coordinates c of the iteration
     float *p;                 // [N][d]
-    float *B;                 // [N][k][d]
+    float *B;                 // [N][head][d]
+    int32_t head;             // image vectors kept per right-hand side (iterations the recurrence serves)
     const uint32_t *bitmap;   // [N][words]
     int32_t words, tiles;     // tiles of 256 positions
     uint64_t *partial;        // [N][tiles][2]
@@ -115,7 +116,7 @@ __global__ __launch_bounds__(256) void recur_step_kernel(RecurArgs R)
         const double *grow = R.gram + (int64_t)lam * d + at;
         double a0 = grow[0], a1 = grow[1], a2 = grow[2], a3 = grow[3];
         __syncthreads();
-        const float *Bn = R.B + (n * k) * (int64_t)d + at;
+        const float *Bn = R.B + (n * R.head) * (int64_t)d + at;
         int32_t t = 0;
         for (; t + 8 <= it; t += 8) {
             float4 b[8];
@@ -145,7 +146,7 @@ __global__ __launch_bounds__(256) void recur_step_kernel(RecurArgs R)
         p4.z = (float)((double)p4.z - coef * bn.z);
         p4.w = (float)((double)p4.w - coef * bn.w);
         if (in) {
-            *reinterpret_cast<float4 *>(R.B + (n * k + it) * (int64_t)d + pos) = bn;
+            *reinterpret_cast<float4 *>(R.B + (n * R.head + it) * (int64_t)d + pos) = bn;
             *reinterpret_cast<float4 *>(pn + pos) = p4;
         }
     }
@@ -185,7 +186,7 @@ hipError_t recur_init_launch(const MatrixView &A, const float *y, int32_t N, con
 hipError_t recur_step_launch(bool first, const MatrixView &A, int32_t N, int32_t k, int32_t it, const int32_t *sel,
                              const OmpWorkspace &w, int32_t tiles, hipStream_t s)
 {
-    RecurArgs R{A.gram, A.inv_colnorm, A.d, k, it, sel, w.F, w.f_stride, w.avec, w.cvec, w.rc_p, w.rc_B,
+    RecurArgs R{A.gram, A.inv_colnorm, A.d, k, it, sel, w.F, w.f_stride, w.avec, w.cvec, w.rc_p, w.rc_B, w.rc_head,
                 w.bitmap, w.words, tiles, w.partial};
     const dim3 grid((unsigned)N, (unsigned)((A.d + 1023) / 1024));
     if (first)

@@ -57,12 +57,14 @@ struct OmpWorkspace {
     size_t bytes;
     // only with the correlation recurrence of App. B (carve_recurrence), else null:
     float *rc_p;       // [N][d] correlation vector
-    float *rc_B;       // [N][k][d] images b_t = A^H q_t of the orthonormal directions
+    float *rc_B;       // [N][rc_head][d] images b_t = A^H q_t of the orthonormal directions
+    int32_t rc_head;   // iterations served by the recurrence (the rest by the contraction)
+    int32_t rc_d;      // d (row length of rc_p and rc_B)
     double *cvec;      // [N][k] coordinates c_t of the newest column, exported by update_kernel
 };
 OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_t k);
 // the same workspace followed by the three arrays of the recurrence; `bytes` covers both
-OmpWorkspace carve_recurrence(void *base, int32_t N, int32_t d, int32_t r, int32_t k);
+OmpWorkspace carve_recurrence(void *base, int32_t N, int32_t d, int32_t r, int32_t k, int32_t head);
 
 // kernel classes of the optional per-kernel timing (see profile.hip)
 enum KernelClass { KC_TOPK = 0, KC_PROJECT, KC_ADAM, KC_CORR, KC_SELECT, KC_APPLY, KC_OTHER, KC_FILL, KC_OUTER_PROJECT, KC_OUTER_APPLY, KC_OUTER_REFRESH };

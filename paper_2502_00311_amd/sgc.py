@@ -81,9 +81,9 @@ def lib():
         L.sgc_recover_omp.restype = i32
         L.sgc_recover_omp.argtypes = [vp, i32, ctypes.POINTER(sgc_matrix), i32, vp, vp, vp, sz, vp]
         L.sgc_omp_recurrence_workspace_bytes.restype = sz
-        L.sgc_omp_recurrence_workspace_bytes.argtypes = [i32, i32, i32, i32]
+        L.sgc_omp_recurrence_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
         L.sgc_recover_omp_recurrence.restype = i32
-        L.sgc_recover_omp_recurrence.argtypes = [vp, i32, ctypes.POINTER(sgc_matrix), i32, vp, vp, vp, sz, vp]
+        L.sgc_recover_omp_recurrence.argtypes = [vp, i32, ctypes.POINTER(sgc_matrix), i32, i32, vp, vp, vp, sz, vp]
         L.sgc_recover_omp_shared.restype = i32
         L.sgc_recover_omp_shared.argtypes = [vp, vp, i32, ctypes.POINTER(sgc_matrix), i32, vp, vp, vp, vp, sz, vp]
         L.sgc_reproject.restype = i32
@@ -178,12 +178,13 @@ def sgc_recover_omp(y, N, A, k, sel, x, ws, stream=None):
     _check(lib().sgc_recover_omp(_ptr(y), N, ctypes.byref(A.c()), k, _ptr(sel), _ptr(x), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_recover_omp")
 
 
-def sgc_omp_recurrence_workspace_bytes(N, d, r, k):
-    return int(lib().sgc_omp_recurrence_workspace_bytes(N, d, r, k))
+def sgc_omp_recurrence_workspace_bytes(N, d, r, k, head=None):
+    return int(lib().sgc_omp_recurrence_workspace_bytes(N, d, r, k, k if head is None else head))
 
 
-def sgc_recover_omp_recurrence(y, N, A, k, sel, x, ws, stream=None):
-    _check(lib().sgc_recover_omp_recurrence(_ptr(y), N, ctypes.byref(A.c()), k, _ptr(sel), _ptr(x), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_recover_omp_recurrence")
+def sgc_recover_omp_recurrence(y, N, A, k, sel, x, ws, stream=None, head=None):
+    """head: iterations served by the recurrence (default: all k)."""
+    _check(lib().sgc_recover_omp_recurrence(_ptr(y), N, ctypes.byref(A.c()), k, k if head is None else head, _ptr(sel), _ptr(x), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_recover_omp_recurrence")
 
 
 def sgc_recover_omp_shared(y_m, y_v, C, A, k, sel, x, z, ws, stream=None):
@@ -238,7 +239,9 @@ class StepBuffers:
     def __init__(self, C, d, r, k, device="cuda", recurrence=False):
         f32, i32 = torch.float32, torch.int32
         self.C, self.d, self.r, self.k = C, d, r, k
-        self.recurrence = recurrence  # workspace sized for sgc_recover_omp_recurrence, which step() then calls
+        # recurrence: False, True (all k iterations) or the number of iterations the recurrence serves; the
+        # workspace is then sized for sgc_recover_omp_recurrence, which step() calls
+        self.recurrence = (k if recurrence is True else int(recurrence)) if recurrence else 0
         self.idx = torch.empty((C, k), dtype=i32, device=device)
         self.val = torch.empty((C, k), dtype=f32, device=device)
         self.p = torch.empty((C, r), dtype=f32, device=device)
@@ -248,7 +251,8 @@ class StepBuffers:
         self.hat = torch.empty((2 * C, r), dtype=f32, device=device)  # [mhat; vhat]
         self.sel = torch.empty((2 * C, k), dtype=i32, device=device)
         self.x = torch.empty((2 * C, k), dtype=f32, device=device)
-        nbytes = (sgc_omp_recurrence_workspace_bytes if recurrence else sgc_omp_workspace_bytes)(2 * C, d, r, k)
+        nbytes = (sgc_omp_recurrence_workspace_bytes(2 * C, d, r, k, self.recurrence) if self.recurrence
+                  else sgc_omp_workspace_bytes(2 * C, d, r, k))
         if nbytes == 0:
             raise SgcError(ERR_SHAPE, "sgc_omp_workspace_bytes")
         self.ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
@@ -270,7 +274,10 @@ def step(grad, W, buf, A, t, h, stream=None, shared_support=False, A_new=None):
             sgc_reproject(buf.sel[:C], buf.x[:C], C, k, A_new, 1.0 - h.beta1 ** t, buf.m, stream)
             sgc_reproject(buf.sel[:C], buf.x[C:], C, k, A_new, 1.0 - h.beta2 ** t, buf.v, stream)
         return
-    (sgc_recover_omp_recurrence if buf.recurrence else sgc_recover_omp)(buf.hat, 2 * C, A, k, buf.sel, buf.x, buf.ws, stream)
+    if buf.recurrence:
+        sgc_recover_omp_recurrence(buf.hat, 2 * C, A, k, buf.sel, buf.x, buf.ws, stream, head=buf.recurrence)
+    else:
+        sgc_recover_omp(buf.hat, 2 * C, A, k, buf.sel, buf.x, buf.ws, stream)
     sgc_apply(W, C, d, k, buf.sel[:C], buf.x[:C], buf.sel[C:], buf.x[C:], h, stream)
     if A_new is not None:
         sgc_reproject(buf.sel[:C], buf.x[:C], C, k, A_new, 1.0 - h.beta1 ** t, buf.m, stream)

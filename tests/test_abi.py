@@ -118,16 +118,19 @@ def test_omp_rejects_bad_arguments_and_sizes_workspace():
     # the engine with App. B's recurrence: the same checks, a larger workspace, and the Gram table is required
     more = sgc.sgc_omp_recurrence_workspace_bytes(2, 4096, 256, 32)
     assert more >= need + 2 * 33 * 4096 * 4
+    assert need + 2 * 9 * 4096 * 4 <= sgc.sgc_omp_recurrence_workspace_bytes(2, 4096, 256, 32, 8) < more
     assert sgc.sgc_omp_recurrence_workspace_bytes(2, 4098, 256, 32) == 0   # d % 4
     assert sgc.sgc_omp_recurrence_workspace_bytes(2, 4096, 256, 300) == 0
+    assert sgc.sgc_omp_recurrence_workspace_bytes(2, 4096, 256, 32, 0) == 0 and sgc.sgc_omp_recurrence_workspace_bytes(2, 4096, 256, 32, 33) == 0
 
-    def rec(y=FAKE, N=2, AA=None, k=32, ws=FAKE, nbytes=more):
+    def rec(y=FAKE, N=2, AA=None, k=32, head=32, ws=FAKE, nbytes=more):
         AA = AA if AA is not None else mat(d=4096, r=256, gram=0x1000)
-        return L.sgc_recover_omp_recurrence(y, N, ctypes.byref(AA), k, FAKE, FAKE, ws, nbytes, None)
+        return L.sgc_recover_omp_recurrence(y, N, ctypes.byref(AA), k, head, FAKE, FAKE, ws, nbytes, None)
 
     assert rec(y=None) == sgc.ERR_NULL
     assert rec(AA=mat(d=4096, r=256)) == sgc.ERR_NULL              # no table
     assert rec(k=0) == sgc.ERR_SHAPE and rec(N=0) == sgc.ERR_SHAPE
+    assert rec(head=0) == sgc.ERR_SHAPE and rec(head=33) == sgc.ERR_SHAPE
     assert rec(AA=mat(d=4098, r=256, gram=0x1000)) == sgc.ERR_SHAPE  # d % 4
     assert rec(nbytes=need) == sgc.ERR_WORKSPACE                   # sized for the plain recovery
     assert rec(ws=ctypes.c_void_p(0x1010)) == sgc.ERR_ALIGN

@@ -45,13 +45,13 @@ def make_matrix(mode, seed, d, r):
     return A, At
 
 
-def run(Y, A, k, recurrence):
+def run(Y, A, k, recurrence, head=None):
     N, r = Y.shape
     sel = torch.empty((N, k), dtype=torch.int32, device=DEV)
     x = torch.empty((N, k), dtype=torch.float32, device=DEV)
     if recurrence:
-        ws = torch.empty(sgc.sgc_omp_recurrence_workspace_bytes(N, A.d, r, k), dtype=torch.uint8, device=DEV)
-        sgc.sgc_recover_omp_recurrence(dev(Y), N, A, k, sel, x, ws)
+        ws = torch.empty(sgc.sgc_omp_recurrence_workspace_bytes(N, A.d, r, k, head), dtype=torch.uint8, device=DEV)
+        sgc.sgc_recover_omp_recurrence(dev(Y), N, A, k, sel, x, ws, head=head)
     else:
         ws = torch.empty(sgc.sgc_omp_workspace_bytes(N, A.d, r, k), dtype=torch.uint8, device=DEV)
         sgc.sgc_recover_omp(dev(Y), N, A, k, sel, x, ws)
@@ -84,6 +84,26 @@ def test_recurrence_matches_oracle_and_contraction(N, d, r, k, mode):
     sel2, x2 = run(Y, A, k, False)
     assert np.array_equal(sel, sel2)
     assert np.array_equal(x.view(np.uint32), x2.view(np.uint32))
+    # the recurrence for the first iterations only, the contraction after: the same again
+    for head in sorted({1, max(1, k // 3), k - 1} - {0, k}):
+        sel3, x3 = run(Y, A, k, True, head=head)
+        assert np.array_equal(sel, sel3), head
+        assert np.array_equal(x.view(np.uint32), x3.view(np.uint32)), head
+
+
+@pytest.mark.parametrize("flags", [0, sgc.MATRIX_FLAG_SCREEN_BF16], ids=["float", "screen_bf16"])
+def test_recurrence_head_then_pipelined_contraction(flags):
+    # full tiles and enough of them for the hand-scheduled contraction kernels to take over after the head
+    rng = np.random.default_rng(29)
+    N, d, r, k, head = 130, 32768, 64, 6, 3
+    A, At = make_matrix("stored", 31, d, r)
+    A.flags = flags
+    Y = rng.standard_normal((N, r)).astype(np.float32)
+    sel, x = run(Y, A, k, True, head=head)
+    rsel, rx = orc.omp_batch(Y, At, k)
+    assert np.array_equal(sel, rsel)
+    for n in range(N):
+        assert relerr(x[n], rx[n]) < TOL, n
 
 
 def test_recurrence_at_benchmark_shape_agrees_with_the_contraction_engine():
@@ -137,9 +157,11 @@ def test_recurrence_validation():
     ws = torch.empty(need, dtype=torch.uint8, device=DEV)
     f = L.sgc_recover_omp_recurrence
     p = lambda t: t.data_ptr()
-    assert f(p(Y), 2, ctypes.byref(A.c()), 4, p(sel), p(x), p(ws), need, None) == 0
-    assert f(p(Y), 2, ctypes.byref(A.c()), 4, p(sel), p(x), p(ws), need - 1, None) == sgc.ERR_WORKSPACE
-    assert f(None, 2, ctypes.byref(A.c()), 4, p(sel), p(x), p(ws), need, None) == sgc.ERR_NULL
+    assert f(p(Y), 2, ctypes.byref(A.c()), 4, 4, p(sel), p(x), p(ws), need, None) == 0
+    assert f(p(Y), 2, ctypes.byref(A.c()), 4, 2, p(sel), p(x), p(ws), need, None) == 0
+    assert f(p(Y), 2, ctypes.byref(A.c()), 4, 5, p(sel), p(x), p(ws), need, None) == sgc.ERR_SHAPE
+    assert f(p(Y), 2, ctypes.byref(A.c()), 4, 4, p(sel), p(x), p(ws), need - 1, None) == sgc.ERR_WORKSPACE
+    assert f(None, 2, ctypes.byref(A.c()), 4, 4, p(sel), p(x), p(ws), need, None) == sgc.ERR_NULL
     A.gram = None
-    assert f(p(Y), 2, ctypes.byref(A.c()), 4, p(sel), p(x), p(ws), need, None) == sgc.ERR_NULL   # no table
+    assert f(p(Y), 2, ctypes.byref(A.c()), 4, 4, p(sel), p(x), p(ws), need, None) == sgc.ERR_NULL   # no table
     torch.cuda.synchronize()
