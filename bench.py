@@ -48,7 +48,7 @@ def main():
                          "Gram table like --gram and needs N (k + 1) d more floats of workspace): a variant")
     ap.add_argument("--recurrence-head", type=int, default=0,
                     help="with --recurrence: the recurrence serves only the first H iterations, the contraction "
-                         "the rest (0 = all k iterations)")
+                         "the rest (0 = all k iterations, -1 = r/64, about where the two cost the same)")
     ap.add_argument("--screen-bf16", action="store_true",
                     help="screen the correlation contraction on the bfloat16 matrix cores (split operands, three "
                          "products); candidates are re-scored in double either way")
@@ -108,6 +108,8 @@ def main():
         A.flags = sgc.MATRIX_FLAG_SCREEN_BF16
     gram_ms = None
     if args.recurrence:
+        if args.recurrence_head < 0:
+            args.recurrence_head = max(1, min(k, r // 64))
         if args.shared_support:
             print("bench.py: --recurrence goes with the two-support recovery", file=sys.stderr)
             return 2
@@ -252,6 +254,34 @@ def main():
             ms = (time.perf_counter() - tv) * 1e3 / nv
             variants[name] = {"ms_per_step": round(ms, 3), "value": round(C * d / (ms * 1e-3), 1), "steps": nv}
         A.flags = 0
+        # the two recovery engines combined (needs the Gram table, 8 d^2 bytes, and (r/64 + 1) d floats per
+        # right-hand side): the recurrence of App. B for the first r/64 iterations, the contraction after
+        if 8.0 * d * d <= 40 * 2.0 ** 30 and d % 4 == 0:
+            try:
+                head = max(1, min(k, r // 64))
+                A.gram = torch.empty((d, d), dtype=torch.float64, device=dev)
+                sgc.sgc_matrix_gram(A, A.gram)
+                hb = sgc.StepBuffers(C, d, r, k, device=dev, recurrence=head)
+
+                def run_h(n):
+                    hb.m.zero_()
+                    hb.v.zero_()
+                    Wt.copy_(W0)
+                    for t in range(1, n + 1):
+                        sgc.step(grads[t - 1], Wt, hb, A, t, h)
+
+                run_h(1)
+                torch.cuda.synchronize()
+                tv = time.perf_counter()
+                run_h(nv)
+                torch.cuda.synchronize()
+                ms = (time.perf_counter() - tv) * 1e3 / nv
+                variants["gram+recurrence_head_%d" % head] = {"ms_per_step": round(ms, 3),
+                                                              "value": round(C * d / (ms * 1e-3), 1), "steps": nv}
+                del hb
+            except Exception as exc:  # a variant must not take the headline line down with it
+                variants["gram+recurrence_head"] = {"error": str(exc)}
+            A.gram = None
         out["variants"] = variants
 
     # ---- labelled micro-runs of the HBM-bound kernels at a size where launch latency does not hide them
