@@ -107,7 +107,7 @@ __global__ __launch_bounds__(256) void recur_step_kernel(RecurArgs R)
     const bool in = pos < d; // d % 4 == 0: a quad is inside or outside as a whole
     const int32_t at = in ? pos : 0;
     float *pn = R.p + n * d;
-    float4 p4 = *reinterpret_cast<const float4 *>(pn + at);
+    float4 p4 = load_once_f4(pn + at);
     if (!FIRST) {
         for (int32_t t = tid; t < it; t += 256)
             c_s[t] = R.cvec[n * k + t];
@@ -122,7 +122,7 @@ __global__ __launch_bounds__(256) void recur_step_kernel(RecurArgs R)
             float4 b[8];
 #pragma unroll
             for (int q = 0; q < 8; ++q)
-                b[q] = *reinterpret_cast<const float4 *>(Bn + (int64_t)(t + q) * d);
+                b[q] = load_once_f4(Bn + (int64_t)(t + q) * d);
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
                 const double c = c_s[t + q];
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(256) void recur_step_kernel(RecurArgs R)
             }
         }
         for (; t < it; ++t) {
-            const float4 b = *reinterpret_cast<const float4 *>(Bn + (int64_t)t * d);
+            const float4 b = load_once_f4(Bn + (int64_t)t * d);
             const double c = c_s[t];
             a0 -= c * b.x;
             a1 -= c * b.y;
@@ -145,9 +145,11 @@ __global__ __launch_bounds__(256) void recur_step_kernel(RecurArgs R)
         p4.y = (float)((double)p4.y - coef * bn.y);
         p4.z = (float)((double)p4.z - coef * bn.z);
         p4.w = (float)((double)p4.w - coef * bn.w);
-        if (in) {
-            *reinterpret_cast<float4 *>(R.B + (n * R.head + it) * (int64_t)d + pos) = bn;
-            *reinterpret_cast<float4 *>(pn + pos) = p4;
+        if (in) { // neither is read again before the next iteration: past the caches
+            typedef float floatx4_t __attribute__((ext_vector_type(4)));
+            const floatx4_t bv = {bn.x, bn.y, bn.z, bn.w}, pv = {p4.x, p4.y, p4.z, p4.w};
+            __builtin_nontemporal_store(bv, reinterpret_cast<floatx4_t *>(R.B + (n * R.head + it) * (int64_t)d + pos));
+            __builtin_nontemporal_store(pv, reinterpret_cast<floatx4_t *>(pn + pos));
         }
     }
     // scores of the four positions, selected ones left out
