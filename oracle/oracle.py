@@ -7,6 +7,15 @@ HIP library never calls into this module.
 Every function takes and returns numpy arrays on the host. `step` strings the
 pieces together in the order of Alg. 2 of the paper for a batch of independent
 chunks (MESGC, Sec. 4.4).
+
+`outer_refresh` (the projection matrix of CESGC, Sec. 4.4) lives here rather than in the C file: it
+is the definition itself, a singular value decomposition, through numpy's LAPACK routine in double.
+Its pins: matrices built from known orthonormal factors and singular values (which must come back
+row by row), Eckart-Young optimality against random orthonormal competitors with the singular
+values cross-checked through an eigenvalue routine, and a diagonal matrix worked by hand.
+The OMP functions follow the plain definition; that App. B's recurrences (which the GPU engines
+use) reach the same selections, values and residual is pinned by writing them out in the tests.
+Nothing here is "parity unpinned".
 """
 import ctypes
 import os
