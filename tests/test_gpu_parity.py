@@ -473,7 +473,11 @@ def test_full_step_cfg1_as_specified():
     (synth.shrink(synth.CFG4, C=7, d=2048, r=128, k=8), 2),       # layer-scaled gradients
     (synth.shrink(synth.CFG5, C=2, d=8192, r=512, k=64), 1),      # bf16 gradients
     (synth.shrink(synth.CFG5, C=2, d=32768, r=1024, k=128), 1),   # the stress shape scaled down, run in full
-], ids=["cfg2s", "cfg3s", "cfg4s", "cfg5s", "cfg5_scaled_down"])
+    # the paper's own MESGC setting for one 4096 x 4096 weight (App. D: 256 chunks, sparsity 256, kappa = 8):
+    # one non-zero per chunk of 65536 and eight measurements - the smallest r and k the method is run with
+    (synth.shrink(synth.CFG2, C=256, d=65536, r=8, k=1), 3),
+    (synth.shrink(synth.CFG3, C=256, d=65536, r=8, k=1), 1),      # the same with a generated matrix
+], ids=["cfg2s", "cfg3s", "cfg4s", "cfg5s", "cfg5_scaled_down", "paper_mesgc", "paper_mesgc_generated"])
 def test_full_step_on_shrunk_workloads(w, steps):
     say(w.name, w.C, w.d, w.r, w.k)
     check_steps_against_oracle(w, steps, alpha=2.0)
