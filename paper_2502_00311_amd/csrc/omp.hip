@@ -694,6 +694,7 @@ struct OmpPlan {
     MatrixView Apick; // the view pick_kernel fetches columns from
     size_t pick_smem, factor_smem;
     bool factor_share_table; // update_kernel sums its wavefronts' shares through an LDS table
+    bool narrow;     // r <= 16 on resident rows: corr_narrow_kernel
     bool recurrence; // the correlation vector is updated by App. B's recurrence instead of contracted anew
 };
 
@@ -749,14 +750,16 @@ static hipError_t omp_contraction(const OmpPlan &pl, const MatrixView &A, int32_
                     launch_split_rows(w.panel, rows, A.r, w.a16, s);
                 e = corr_screen_launch(pl.screen_pipelined, Ap, w.a16, rows, Ng, w, pl.tiles_m, s);
             } else {
-                e = pl.pipelined ? corr_pipelined_launch(Ap, rows, w.res32, Ng, w, pl.tiles_m, s)
-                                 : corr_general_launch(false, Ap, rows, w.res32, Ng, w, pl.tiles_m, s);
+                e = pl.narrow      ? corr_narrow_launch(Ap, rows, w.res32, Ng, w, pl.tiles_m, s)
+                    : pl.pipelined ? corr_pipelined_launch(Ap, rows, w.res32, Ng, w, pl.tiles_m, s)
+                                   : corr_general_launch(false, Ap, rows, w.res32, Ng, w, pl.tiles_m, s);
             }
         }
     } else if (A.generated) {
         e = corr_general_launch(true, A, A.d, w.res32, Ng, w, pl.tiles_m, s);
     } else {
-        e = pl.screen      ? corr_screen_launch(pl.screen_pipelined, A, w.a16, A.d, Ng, w, pl.tiles_m, s)
+        e = pl.narrow      ? corr_narrow_launch(A, A.d, w.res32, Ng, w, pl.tiles_m, s)
+            : pl.screen    ? corr_screen_launch(pl.screen_pipelined, A, w.a16, A.d, Ng, w, pl.tiles_m, s)
             : pl.pipelined ? corr_pipelined_launch(A, A.d, w.res32, Ng, w, pl.tiles_m, s)
                            : corr_general_launch(false, A, A.d, w.res32, Ng, w, pl.tiles_m, s);
     }
@@ -850,6 +853,12 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
     if (pl.screen)
         pl.pipelined = false;
     pl.tiles_m = pl.pipelined || pl.screen_pipelined ? A.d / CORRP_BM : corr_tiles_m(A.d);
+    // very few measurements: neither the matrix cores nor the bfloat16 copy have anything to offer
+    pl.narrow = (!A.generated || pl.panels) && corr_narrow_ok(A.r, N);
+    if (pl.narrow) {
+        pl.pipelined = pl.screen = pl.screen_pipelined = false;
+        pl.tiles_m = (A.d + 255) / 256;
+    }
     pl.recurrence = recurrence;
     if (recurrence && (!A.gram || !ws.rc_p || ws.rc_head < 1 || ws.rc_head > k || A.d % 4 != 0 ||
                        (A.generated && ws.panel_rows < A.d)))

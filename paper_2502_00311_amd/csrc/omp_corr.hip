@@ -817,6 +817,130 @@ static hipError_t corr_dispatch(const MatrixView &A, int32_t rows, const float *
     return corr_launch<GENERATED, CORR_BM, CORR_BN, 32, 2, 2, 2>(A, rows, R, N, ws, tiles_m, s);
 }
 
+// The contraction for very few measurements (r <= 16; the paper's memory-efficient setting has r = 8): at
+// that depth a tile's matrix-core work is nothing and the tiled kernels spend their time on staging and
+// on the cross-lane reduction of the epilogue. Here a thread owns two right-hand sides (their r residual
+// entries in registers) and walks the 256 positions of the workgroup's tile, whose rows of At every
+// lane reads from LDS at the same address (a broadcast; one read serves both right-hand sides): r FMAs
+// per score, and the two best keys of the tile stay in the thread's own registers - no reduction across
+// lanes at all. (Scalar loads of the rows instead of LDS measured slower: they return out of order and
+// every use waits for all of them.) Keys as in the pipelined kernel's epilogue: score bits with the low
+// byte replaced by 255 - (position in the tile).
+// grid (tiles of 256 positions, ceil(N / 512)); rows of At resident; R4 = r / 4.
+constexpr int NARROW_RHS = 2; // right-hand sides per thread
+template <int R4>
+__global__ __launch_bounds__(256) void corr_narrow_kernel(MatrixView A, int32_t rows, const float *__restrict__ R,
+                                                          int32_t N, const uint32_t *__restrict__ bitmap, int32_t words,
+                                                          uint64_t *__restrict__ partial, int32_t tiles_m)
+{
+    constexpr int RR = 4 * R4;
+    __shared__ __attribute__((aligned(16))) float a_s[256 * RR];
+    __shared__ float inv_s[256];
+    const int tid = threadIdx.x;
+    const int32_t local0 = blockIdx.x * 256;         // first row of the tile within At
+    const int32_t m0 = A.row0 + local0;              // its position
+    const int32_t live = rows - local0 < 256 ? rows - local0 : 256; // rows of the tile that exist
+    // the tile's rows are contiguous in memory
+    for (int e = tid; e < 256 * R4; e += 256) {
+        const int row = e / R4;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (row < live)
+            v = reinterpret_cast<const float4 *>(A.At + (int64_t)local0 * RR)[e];
+        reinterpret_cast<float4 *>(a_s)[e] = v;
+    }
+    inv_s[tid] = tid < live ? A.inv_colnorm[m0 + tid] : 0.f;
+    int32_t n[NARROW_RHS];
+    float y[NARROW_RHS][RR];
+    uint32_t msk[NARROW_RHS][8];
+#pragma unroll
+    for (int u = 0; u < NARROW_RHS; ++u) {
+        n[u] = blockIdx.y * (256 * NARROW_RHS) + 256 * u + tid;
+        const int32_t nn = n[u] < N ? n[u] : N - 1; // past the end: the last right-hand side again, nothing stored
+#pragma unroll
+        for (int q = 0; q < R4; ++q) {
+            const float4 v = reinterpret_cast<const float4 *>(R + (int64_t)nn * RR)[q];
+            y[u][4 * q] = v.x;
+            y[u][4 * q + 1] = v.y;
+            y[u][4 * q + 2] = v.z;
+            y[u][4 * q + 3] = v.w;
+        }
+#pragma unroll
+        for (int w = 0; w < 8; ++w) {
+            const int32_t word = (m0 >> 5) + w;
+            msk[u][w] = word < words ? bitmap[(int64_t)nn * words + word] : 0xffffffffu;
+        }
+    }
+    __syncthreads();
+    uint32_t best[NARROW_RHS], second[NARROW_RHS];
+#pragma unroll
+    for (int u = 0; u < NARROW_RHS; ++u)
+        best[u] = second[u] = 0;
+#pragma unroll
+    for (int w = 0; w < 8; ++w) {
+#pragma unroll 8
+        for (int b = 0; b < 32; ++b) {
+            const int i = 32 * w + b;
+            float dot[NARROW_RHS];
+#pragma unroll
+            for (int u = 0; u < NARROW_RHS; ++u)
+                dot[u] = 0.f;
+#pragma unroll
+            for (int q = 0; q < R4; ++q) {
+                const float4 a = reinterpret_cast<const float4 *>(a_s)[i * R4 + q];
+#pragma unroll
+                for (int u = 0; u < NARROW_RHS; ++u) {
+                    dot[u] = __builtin_fmaf(a.x, y[u][4 * q], dot[u]);
+                    dot[u] = __builtin_fmaf(a.y, y[u][4 * q + 1], dot[u]);
+                    dot[u] = __builtin_fmaf(a.z, y[u][4 * q + 2], dot[u]);
+                    dot[u] = __builtin_fmaf(a.w, y[u][4 * q + 3], dot[u]);
+                }
+            }
+            const float in = inv_s[i];
+#pragma unroll
+            for (int u = 0; u < NARROW_RHS; ++u) {
+                const float score = fabsf(dot[u]) * in;
+                uint32_t key = (__float_as_uint(score) & 0xffffff00u) | (uint32_t)(255 - i);
+                key = ((msk[u][w] >> b) & 1u) || i >= live ? 0u : key;
+                second[u] = max(second[u], min(key, best[u]));
+                best[u] = max(best[u], key);
+            }
+        }
+    }
+    auto widen = [&](uint32_t k32) -> uint64_t { // (score bits, ~position) as the selection kernel reads it
+        if (k32 == 0)
+            return 0ull;
+        const uint32_t i = (uint32_t)m0 + (255u - (k32 & 0xffu));
+        return ((uint64_t)(k32 & 0xffffff00u) << 32) | (uint64_t)(0xffffffffu - i);
+    };
+#pragma unroll
+    for (int u = 0; u < NARROW_RHS; ++u) {
+        if (n[u] < N) {
+            uint64_t *o = partial + ((int64_t)n[u] * tiles_m + m0 / 256) * 2;
+            o[0] = widen(best[u]);
+            o[1] = widen(second[u]);
+        }
+    }
+}
+
+bool corr_narrow_ok(int32_t r, int32_t N)
+{
+    return r <= 16 && N >= 128;
+}
+
+hipError_t corr_narrow_launch(const MatrixView &A, int32_t rows, const float *R, int32_t N, const OmpWorkspace &ws,
+                              int32_t tiles_m, hipStream_t s)
+{
+    const dim3 grid((unsigned)((rows + 255) / 256), (unsigned)((N + 256 * NARROW_RHS - 1) / (256 * NARROW_RHS)));
+    switch (A.r / 4) {
+    case 1: corr_narrow_kernel<1><<<grid, 256, 0, s>>>(A, rows, R, N, ws.bitmap, ws.words, ws.partial, tiles_m); break;
+    case 2: corr_narrow_kernel<2><<<grid, 256, 0, s>>>(A, rows, R, N, ws.bitmap, ws.words, ws.partial, tiles_m); break;
+    case 3: corr_narrow_kernel<3><<<grid, 256, 0, s>>>(A, rows, R, N, ws.bitmap, ws.words, ws.partial, tiles_m); break;
+    case 4: corr_narrow_kernel<4><<<grid, 256, 0, s>>>(A, rows, R, N, ws.bitmap, ws.words, ws.partial, tiles_m); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 hipError_t corr_general_launch(bool generated, const MatrixView &A, int32_t rows, const float *R, int32_t N,
                                const OmpWorkspace &ws, int32_t tiles_m, hipStream_t s)
 {

@@ -54,6 +54,10 @@ hipError_t corr_screen_launch(bool pipelined, const MatrixView &A, const uint16_
 hipError_t recur_init_launch(const MatrixView &A, const float *y, int32_t N, const OmpWorkspace &w, hipStream_t s);
 hipError_t recur_step_launch(bool first, const MatrixView &A, int32_t N, int32_t k, int32_t it, const int32_t *sel,
                              const OmpWorkspace &w, int32_t tiles, hipStream_t s);
+// the contraction for r <= 16 on resident rows (a thread per right-hand side, no matrix cores)
+bool corr_narrow_ok(int32_t r, int32_t N);
+hipError_t corr_narrow_launch(const MatrixView &A, int32_t rows, const float *R, int32_t N, const OmpWorkspace &ws,
+                              int32_t tiles_m, hipStream_t s);
 // whether the pipelined kernel covers this problem
 bool corr_pipelined_ok(const MatrixView &A, int32_t N, int32_t panel_rows);
 

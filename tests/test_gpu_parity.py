@@ -232,6 +232,30 @@ def test_omp_matches_oracle_on_noisy_right_hand_sides(N, d, r, k, mode):
     assert rowwise_relerr(x, rx) < TOL
 
 
+@pytest.mark.parametrize("N,d,r,k,mode", [
+    (128, 512, 4, 2, "stored"),       # the smallest depth, exactly one tile of right-hand sides, full position tiles
+    (300, 1000, 8, 3, "stored"),      # ragged either way
+    (300, 1000, 8, 3, "philox"),      # generated matrix, consumed from the panel
+    (257, 777, 12, 5, "stored"),      # one right-hand side in the second tile, odd sizes
+    (600, 70000, 16, 4, "philox"),    # the largest depth of this kernel, two halves on two streams, 274 position tiles
+    (130, 65536, 8, 1, "stored"),     # the paper's memory-efficient setting: one pick from eight measurements
+])
+def test_omp_with_very_few_measurements(N, d, r, k, mode):
+    """r <= 16 and at least 128 right-hand sides: the contraction without matrix cores (a thread per
+    right-hand side). Exact ties, a zero and a tiny right-hand side included."""
+    say("omp narrow", N, d, r, k, mode)
+    rng = np.random.default_rng(N * 11 + d)
+    A, At = make_matrix(mode, 27, d, r)
+    Y = rng.standard_normal((N, r)).astype(np.float32)
+    Y[1] = 0.0
+    Y[2] *= 1e-20
+    Y[3] = np.round(Y[3])                           # small integers: equal scores are likely
+    sel, x = run_omp(Y, A, k)
+    rsel, rx = orc.omp_batch(Y, At, k)
+    assert np.array_equal(sel, rsel)
+    assert rowwise_relerr(x, rx) < TOL
+
+
 @pytest.mark.parametrize("N,d,r,k", [
     (600, 3000, 64, 6),      # the generated matrix is written out once (it fits the cache-sized panel)
     (520, 2500, 8192, 3),    # long columns, 82 MB: two panels refilled in every iteration, the second one ragged
