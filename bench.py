@@ -32,7 +32,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", type=int, default=2, help="configuration index 1..5 (default 2)")
+    ap.add_argument("--workload", type=int, default=2, help="configuration index 1..5 (default 2); 6 = the paper's own MESGC setting (r = 8, k = 1) on configuration 4's block")
     ap.add_argument("--chunks", type=int, default=0, help="override the number of chunks (0 = as defined)")
     ap.add_argument("--shared-support", action="store_true",
                     help="recover one support per chunk from mhat and fit vhat on it (sgc_recover_omp_shared) "
@@ -182,6 +182,21 @@ def main():
         "traffic": None if (args.shared_support or args.screen_bf16) else MEASURED_TRAFFIC.get(w.name),
         "flops_per_launch": flops_per_launch, "avg_launch_ms": round(avg_ms, 5), "launches": corr_n,
     }
+    if r <= 16 and 2 * C >= 128 and not args.recurrence:
+        # very few measurements: the contraction runs on the vector ALUs (corr_narrow_kernel: r FMAs and about
+        # 7 further instructions per score), and the top-k scan is the larger kernel of the step
+        ops = float(d) * nrhs * (r + 7) * k
+        rate = ops / (corr_ms / K * 1e-3)
+        roofline = {"bound": "alu", "kernel": "omp correlation on the vector ALUs (r <= 16), lane-instructions per second",
+                    "achieved": round(rate / 1e12, 3), "peak": 78.6, "unit": "T lane-instr/s",
+                    "frac": round(rate / 7.86e13, 4), "traffic": None, "avg_launch_ms": round(avg_ms, 5), "launches": corr_n}
+        tk_ms, tk_n = prof["topk"]
+        if tk_n and tk_ms > corr_ms:
+            gbps = ((2.0 if w.grad == "bf16" else 4.0) * C * d + 8.0 * C * k) / (tk_ms / tk_n * 1e-3) / 1e9
+            roofline = {"bound": "hbm", "kernel": "top-k scan of the gradients (the dominant kernel at this shape)",
+                        "achieved": round(gbps, 1), "peak": 8000.0, "unit": "GB/s", "frac": round(gbps / 8000.0, 4),
+                        "traffic": None, "avg_launch_ms": round(tk_ms / tk_n, 5), "launches": tk_n,
+                        "omp_corr_alu_frac": round(rate / 7.86e13, 4)}
     if args.recurrence:
         # no contraction inside the iterations: the class holds p0 = A^H y (once per call) and the k - 1 updates
         # of p, which stream the image vectors b_t (4 d j bytes at iteration j), a row of the table (8 d), the
@@ -203,7 +218,7 @@ def main():
                         "achieved": round(tf, 3), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
                         "frac": round(tf / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None,
                         "recurrence_bytes_per_step": total, "ms_per_step": round(corr_ms / K, 3), "launches": corr_n}
-    if fill_ms > 0:  # generated A produced by a separate fill kernel: the rate including that time
+    if fill_ms > 0 and roofline.get("bound") == "mfma":  # generated A produced by a separate fill kernel: the rate including that time
         if not args.recurrence:
             roofline["achieved_incl_matrix_fill"] = round(flops_per_launch * corr_n / ((corr_ms + fill_ms) * 1e-3) / 1e12, 3)
     kernels = {n: {"ms_per_step": round(ms / K, 4), "launches_per_step": cnt / K} for n, (ms, cnt) in prof.items()}

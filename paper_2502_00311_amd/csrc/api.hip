@@ -120,7 +120,9 @@ sgc_status sgc_sparsify_project(const void *grad, int32_t grad_type, int64_t n, 
         return SGC_ERR_ALIGN;
     const int64_t C = n / d;
     hipStream_t s = (hipStream_t)stream;
-    hipError_t e = launch_topk(grad, grad_type, C, d, k, idx, val, s);
+    // p and q are written by the projection afterwards: until then they are scratch for the top-k pass
+    hipError_t e = launch_topk(grad, grad_type, C, d, k, idx, val, s, reinterpret_cast<int32_t *>(p), q,
+                               q ? C * (int64_t)A->r : 0);
     if (e != hipSuccess)
         return SGC_ERR_DEVICE;
     return from_hip(launch_project(idx, val, C, k, make_view(A), p, q, s));

@@ -70,8 +70,11 @@ OmpWorkspace carve_recurrence(void *base, int32_t N, int32_t d, int32_t r, int32
 enum KernelClass { KC_TOPK = 0, KC_PROJECT, KC_ADAM, KC_CORR, KC_SELECT, KC_APPLY, KC_OTHER, KC_FILL, KC_OUTER_PROJECT, KC_OUTER_APPLY, KC_OUTER_REFRESH };
 
 // launchers (each returns hipGetLastError() of its launches)
+// scratch_i / scratch_v: optional memory for scratch_elems candidates each (positions, values) that the
+// call may overwrite; with it, long chunks take a faster two-pass path
 hipError_t launch_topk(const void *grad, int grad_type, int64_t C, int32_t d, int32_t k, int32_t *idx,
-                       float *val, hipStream_t s);
+                       float *val, hipStream_t s, int32_t *scratch_i = nullptr, float *scratch_v = nullptr,
+                       int64_t scratch_elems = 0);
 hipError_t launch_project(const int32_t *idx, const float *val, int64_t C, int32_t k, const MatrixView &A,
                           float *p, float *q, hipStream_t s, float out_scale = 1.0f);
 hipError_t launch_adam(const float *p, const float *q, float *m, float *v, float *mhat, float *vhat,

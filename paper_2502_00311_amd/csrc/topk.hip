@@ -401,8 +401,47 @@ __global__ __launch_bounds__(THREADS, MINBLOCKS) void topk_f32_regs_kernel(const
     topk_general<float, THREADS>(gc, d, k, oidx, oval);
 }
 
+// Second pass for long chunks (see launch_topk): the k largest of the S * k candidates that the register
+// kernel kept for the S pieces of a chunk, one wavefront per chunk. The candidates of a piece are in
+// ascending position and the pieces in order, so the list is in ascending position: the entries above
+// the k-th largest key, and the first of those equal to it, taken in list order, are the result in its
+// final order. Keys are sign-cleared bit patterns throughout, as in the first pass.
+__global__ __launch_bounds__(64) void topk_merge_kernel(const int32_t *__restrict__ cand_i,
+                                                        const float *__restrict__ cand_v, int32_t S, int32_t dsub,
+                                                        int32_t k, int32_t *__restrict__ idx, float *__restrict__ val)
+{
+    __shared__ uint32_t keys[4 * 256];
+    const uint32_t lane = threadIdx.x;
+    const uint32_t n = (uint32_t)(S * k);
+    const int64_t base = (int64_t)blockIdx.x * n;
+    for (uint32_t s = lane; s < n; s += 64)
+        keys[s] = __float_as_uint(cand_v[base + s]);
+    __syncthreads();
+    uint32_t gt, eq;
+    const uint32_t thr = wave_kth_largest(keys, n, (uint32_t)k, gt, eq);
+    const uint32_t need = (uint32_t)k - gt; // entries equal to the threshold that belong to the result
+    const uint64_t below = (1ull << lane) - 1ull;
+    uint32_t out = 0, ties = 0;
+    for (uint32_t s0 = 0; s0 < n; s0 += 64) {
+        const uint32_t s = s0 + lane;
+        const bool in = s < n;
+        const uint32_t key = in ? (keys[s] & 0x7fffffffu) : 0u;
+        const bool is_eq = in && key == thr;
+        const uint64_t beq = __ballot(is_eq);
+        const bool take = in && (key > thr || (is_eq && ties + (uint32_t)__popcll(beq & below) < need));
+        const uint64_t bt = __ballot(take);
+        if (take) {
+            const uint32_t o = out + (uint32_t)__popcll(bt & below);
+            idx[(int64_t)blockIdx.x * k + o] = (int32_t)(s / (uint32_t)k) * dsub + cand_i[base + s];
+            val[(int64_t)blockIdx.x * k + o] = cand_v[base + s];
+        }
+        out += (uint32_t)__popcll(bt);
+        ties += (uint32_t)__popcll(beq);
+    }
+}
+
 hipError_t launch_topk(const void *grad, int grad_type, int64_t C, int32_t d, int32_t k, int32_t *idx,
-                       float *val, hipStream_t s)
+                       float *val, hipStream_t s, int32_t *scratch_i, float *scratch_v, int64_t scratch_elems)
 {
     if (C == 0)
         return hipSuccess;
@@ -410,6 +449,21 @@ hipError_t launch_topk(const void *grad, int grad_type, int64_t C, int32_t d, in
     ProfileScope prof(KC_TOPK, s);
     if (grad_type == SGC_GRAD_F32) {
         const int32_t vec = (d % 4 == 0) ? 1 : 0; // every chunk then starts 16-byte aligned
+        // Chunks of 16385 .. 65536 floats: the register kernel for that length holds a whole chunk per
+        // 1024-thread workgroup, one workgroup per CU, and loads and selects in turn (3.2 TB/s). With
+        // scratch for S * k candidates per chunk the chunk is instead cut in S <= 4 pieces that go through
+        // the 256-thread kernel, five workgroups per CU, and a small second pass merges the candidates.
+        const int32_t S = (d + 16383) / 16384;
+        // (k <= 128: the 256-thread kernel bounds the threshold by the k-th largest of its 256 per-thread
+        // maxima, which is a useful bound only while k is well below 256)
+        if (d > 16384 && S <= 4 && d % (4 * S) == 0 && k <= 128 && k <= d / S && scratch_i && scratch_v &&
+            (int64_t)C * S * k <= scratch_elems && (int64_t)C * S < (1ll << 31)) {
+            const int32_t dsub = d / S;
+            topk_f32_regs_kernel<256, 5><<<dim3((unsigned)(C * S)), 256, 0, s>>>((const float *)grad, dsub, k, scratch_i,
+                                                                                 scratch_v, 1);
+            topk_merge_kernel<<<grid, 64, 0, s>>>(scratch_i, scratch_v, S, dsub, k, idx, val);
+            return hipGetLastError();
+        }
         if (d <= 16 * 4 * 256 && k <= 256)
             topk_f32_regs_kernel<256, 5><<<grid, 256, 0, s>>>((const float *)grad, d, k, idx, val, vec);
         else if (d <= 16 * 4 * 1024 && k <= 1024)

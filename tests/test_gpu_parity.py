@@ -111,6 +111,42 @@ def test_topk_ties_zeros_and_quantised_values():
         assert np.array_equal(val.view(np.uint32), rval.view(np.uint32))
 
 
+@pytest.mark.parametrize("d,k,r", [
+    (16392, 1, 8),        # two pieces, the smallest possible scratch (r = 2 k would do: 8 >= 2)
+    (32768, 64, 128),     # two pieces, r = S k exactly
+    (32768, 64, 124),     # one candidate short of the scratch: the single-pass kernel
+    (49152, 100, 300),    # three pieces
+    (65536, 128, 512),    # four pieces, the largest k of the two-pass path, r = S k exactly
+    (65536, 129, 1024),   # one more: single pass
+    (65536, 1, 8),        # the paper's memory-efficient setting
+    (40000, 30, 512),     # 40000 % 12 != 0: single pass
+])
+def test_topk_long_chunks_two_pass(d, k, r):
+    """Chunks of 16385 .. 65536 floats are cut in up to four pieces whose candidates are merged in a second
+    pass (p and q serve as scratch until the projection writes them). Heavy tails, thousands of ties at
+    the threshold, an all-zero and an all-equal chunk, ties across the piece boundaries, NaN patterns."""
+    say("topk two-pass", d, k, r)
+    rng = np.random.default_rng(d + 3 * k)
+    C = 7
+    g = (rng.standard_t(3, size=(C, d)) * 1e-3).astype(np.float32)
+    g[1] = rng.integers(-2, 3, size=d).astype(np.float32)        # ties everywhere, also across pieces
+    g[2] = 0.0
+    g[3] = -1.5
+    g[4, : d // 2] = 0.0                                         # the whole result lies in the last pieces
+    g[5, d // 3:] = 0.0                                          # ... in the first
+    bits = g.view(np.uint32)
+    bits[6, 5] = 0x7fc00000                                      # NaN patterns order above everything, by bits
+    bits[6, d - 1] = 0xffc00001
+    bits[6, d // 2] = 0x7f800000
+    A, At = make_matrix("stored", 12, d, r)
+    idx, val, p, q = run_topk_project(g, k, A)
+    ridx, rval = orc.topk(g, k)
+    assert np.array_equal(idx, ridx)
+    assert np.array_equal(val.view(np.uint32), rval.view(np.uint32))
+    rp, rq = orc.project(ridx[:6], rval[:6], At)
+    assert rowwise_relerr(p[:6], rp) < TOL and rowwise_relerr(q[:6], rq) < TOL
+
+
 def test_topk_nan_inf_and_subnormal_patterns():
     """Order is defined on the bit pattern with the sign cleared: NaN patterns above infinity,
     subnormals below every normal value. Chunks: NaNs and infinities among normal values; only
