@@ -868,44 +868,70 @@ __global__ __launch_bounds__(256) void corr_narrow_kernel(MatrixView A, int32_t 
         for (int w = 0; w < 8; ++w) {
             const int32_t word = (m0 >> 5) + w;
             msk[u][w] = word < words ? bitmap[(int64_t)nn * words + word] : 0xffffffffu;
+            // positions of the tile past the last row count as selected
+            const int32_t left = live - 32 * w;
+            if (left < 32)
+                msk[u][w] |= left <= 0 ? 0xffffffffu : ~((1u << left) - 1u);
         }
     }
     __syncthreads();
+    // Selected positions are left in on the first scan (their columns are orthogonal to the residual, so
+    // they reach the two best only when the residual is rounding noise or zero); if a winner of any lane
+    // turns out to be selected, the scan is repeated with the selected positions forced to key 0. Positions
+    // of the tile past the last row were marked as selected above and are caught the same way.
     uint32_t best[NARROW_RHS], second[NARROW_RHS];
+    auto scan = [&](auto maskedc) {
+        constexpr bool MASKED = decltype(maskedc)::value;
 #pragma unroll
-    for (int u = 0; u < NARROW_RHS; ++u)
-        best[u] = second[u] = 0;
+        for (int u = 0; u < NARROW_RHS; ++u)
+            best[u] = second[u] = 0;
 #pragma unroll
-    for (int w = 0; w < 8; ++w) {
+        for (int w = 0; w < 8; ++w) {
 #pragma unroll 8
-        for (int b = 0; b < 32; ++b) {
-            const int i = 32 * w + b;
-            float dot[NARROW_RHS];
+            for (int b = 0; b < 32; ++b) {
+                const int i = 32 * w + b;
+                float dot[NARROW_RHS];
 #pragma unroll
-            for (int u = 0; u < NARROW_RHS; ++u)
-                dot[u] = 0.f;
+                for (int u = 0; u < NARROW_RHS; ++u)
+                    dot[u] = 0.f;
 #pragma unroll
-            for (int q = 0; q < R4; ++q) {
-                const float4 a = reinterpret_cast<const float4 *>(a_s)[i * R4 + q];
+                for (int q = 0; q < R4; ++q) {
+                    const float4 a = reinterpret_cast<const float4 *>(a_s)[i * R4 + q];
+#pragma unroll
+                    for (int u = 0; u < NARROW_RHS; ++u) {
+                        dot[u] = __builtin_fmaf(a.x, y[u][4 * q], dot[u]);
+                        dot[u] = __builtin_fmaf(a.y, y[u][4 * q + 1], dot[u]);
+                        dot[u] = __builtin_fmaf(a.z, y[u][4 * q + 2], dot[u]);
+                        dot[u] = __builtin_fmaf(a.w, y[u][4 * q + 3], dot[u]);
+                    }
+                }
+                const float in = inv_s[i];
 #pragma unroll
                 for (int u = 0; u < NARROW_RHS; ++u) {
-                    dot[u] = __builtin_fmaf(a.x, y[u][4 * q], dot[u]);
-                    dot[u] = __builtin_fmaf(a.y, y[u][4 * q + 1], dot[u]);
-                    dot[u] = __builtin_fmaf(a.z, y[u][4 * q + 2], dot[u]);
-                    dot[u] = __builtin_fmaf(a.w, y[u][4 * q + 3], dot[u]);
+                    const float score = fabsf(dot[u]) * in;
+                    uint32_t key = (__float_as_uint(score) & 0xffffff00u) | (uint32_t)(255 - i);
+                    if (MASKED)
+                        key = ((msk[u][w] >> b) & 1u) ? 0u : key;
+                    second[u] = max(second[u], min(key, best[u]));
+                    best[u] = max(best[u], key);
                 }
             }
-            const float in = inv_s[i];
+        }
+    };
+    scan(std::false_type{});
+    uint32_t hit = 0;
 #pragma unroll
-            for (int u = 0; u < NARROW_RHS; ++u) {
-                const float score = fabsf(dot[u]) * in;
-                uint32_t key = (__float_as_uint(score) & 0xffffff00u) | (uint32_t)(255 - i);
-                key = ((msk[u][w] >> b) & 1u) || i >= live ? 0u : key;
-                second[u] = max(second[u], min(key, best[u]));
-                best[u] = max(best[u], key);
-            }
+    for (int u = 0; u < NARROW_RHS; ++u) {
+#pragma unroll
+        for (int which = 0; which < 2; ++which) {
+            const uint32_t pos = 255u - ((which ? second[u] : best[u]) & 0xffu); // within the tile
+#pragma unroll
+            for (int w = 0; w < 8; ++w) // straight-line: every word is tested
+                hit |= ((msk[u][w] >> (pos & 31u)) & 1u) & (uint32_t)((pos >> 5) == (uint32_t)w);
         }
     }
+    if (__builtin_amdgcn_ballot_w64(hit != 0u) != 0ull)
+        scan(std::true_type{});
     auto widen = [&](uint32_t k32) -> uint64_t { // (score bits, ~position) as the selection kernel reads it
         if (k32 == 0)
             return 0ull;
