@@ -310,7 +310,9 @@ sgc_status sgc_outer_apply(float *W, const float *B, int32_t count, int32_t rho,
  *          sizes), 256-byte aligned: a transposed copy of G, count rho x n matrices and small factors
  * The passes over G run on the matrix cores in float; Gram matrices, their Cholesky and Jacobi
  * factorisations and the rho x rho transforms are in double. Rows that depend on earlier rows to float
- * accuracy (G of rank below rho) come out as zero rows, with sigma 0.
+ * accuracy (G of rank below rho) come out as zero rows, with sigma 0; zero rows of a start matrix are
+ * given generic entries first, so a later renewal on a gradient of full rank fills them again (except
+ * with iters = 0, which only rotates what it is given).
  * Errors: NULL, SHAPE (count, rho, m, n <= 0, rho > 64, rho > m, rho > n, m or n above 2^22, m % 4, n % 4,
  * count * ceil(rho/32) above 65535, iters < 0 or > 1000), DTYPE, ALIGN, WORKSPACE, DEVICE.
  */

@@ -321,6 +321,35 @@ __global__ __launch_bounds__(256) void row_sign_kernel(float *__restrict__ B, in
             row[c] = -row[c];
 }
 
+// A start matrix may carry zero rows (the result of an earlier renewal on a gradient of lower rank): a zero
+// row stays zero through every product, so it is given generic entries again - a fixed integer hash of
+// its position, the same on every call - and takes part in the iteration like any other start vector.
+__global__ __launch_bounds__(256) void reseed_zero_rows_kernel(float *__restrict__ B, int64_t m)
+{
+    __shared__ int any_s;
+    float *row = B + (int64_t)blockIdx.x * m;
+    if (threadIdx.x == 0)
+        any_s = 0;
+    __syncthreads();
+    bool any = false;
+    for (int64_t c = threadIdx.x; c < m; c += 256)
+        any = any || !(row[c] == 0.f); // a NaN counts as content: it is not this kernel's to repair
+    if (any)
+        any_s = 1;
+    __syncthreads();
+    if (any_s)
+        return;
+    for (int64_t c = threadIdx.x; c < m; c += 256) {
+        uint32_t h = (uint32_t)(blockIdx.x * 0x9e3779b9u) ^ (uint32_t)c * 0x85ebca6bu;
+        h ^= h >> 16;
+        h *= 0x7feb352du;
+        h ^= h >> 15;
+        h *= 0x846ca68bu;
+        h ^= h >> 16;
+        row[c] = ((float)(h >> 8) + 0.5f) * (1.0f / 8388608.0f) - 1.0f; // in (-1, 1)
+    }
+}
+
 RefreshPlan refresh_plan(int32_t count, int32_t rho, int32_t m, int32_t n, bool g_bf16)
 {
     auto up = [](size_t b) { return (b + 255) & ~(size_t)255; };
@@ -384,6 +413,7 @@ hipError_t launch_outer_refresh(float *B, const void *G, bool g_bf16, int32_t co
     hipError_t e;
     {
         ProfileScope prof(KC_OUTER_REFRESH, s);
+        reseed_zero_rows_kernel<<<dim3((unsigned)(rho * count)), 256, 0, s>>>(B, m);
         const int64_t tiles_x = (n + 31) / 32, tiles_y = (m + 31) / 32;
         const dim3 grid((unsigned)(tiles_x * tiles_y), (unsigned)count);
         if (g_bf16)

@@ -132,6 +132,21 @@ def test_refresh_rank_below_rho_gives_zero_rows():
     assert np.array_equal(Bz, np.zeros((rho, m))) and np.array_equal(sz, np.zeros(rho))
 
 
+def test_refresh_fills_zero_rows_of_the_start_matrix_again():
+    # the sequence a periodic caller sees: a gradient of rank 3 leaves two zero rows in B; the next renewal,
+    # started from that B on a gradient of full rank, must return all five singular vectors
+    rng = np.random.default_rng(13)
+    m, n, rho = 96, 160, 5
+    G_low = spectrum_matrix(rng, m, n, np.array([3.0, 2.0, 1.0]))
+    B_low, s_low = refresh(G_low, rho, 8)
+    assert np.array_equal(B_low[3:], np.zeros((2, m)))
+    G_full = spectrum_matrix(rng, m, n, 2.0 * 0.5 ** np.arange(8))
+    B, s = refresh(G_full, rho, 14, start=B_low)
+    Bref, sref = orc.outer_refresh(G_full, rho)
+    assert np.abs(s / sref - 1).max() < 1e-3
+    assert np.abs(B - Bref).max() < 1e-4
+
+
 def test_refresh_from_the_previous_matrix_needs_few_rounds():
     # the periodic use: the gradient's subspace has drifted a little since the last decomposition
     rng = np.random.default_rng(10)
