@@ -141,3 +141,36 @@ def test_outer_refresh_random_shape(seed):
         assert np.abs(sn[j] / sref - 1).max() < 2e-3, j
         assert np.abs(Bn[j][:lead] - Bref[:lead]).max() < 2e-4, j
         assert np.abs(Bn[j].T @ Bn[j] - Bref.T @ Bref).max() < 5e-3, j
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_recovery_with_very_few_measurements_random_shape(seed):
+    """r <= 16 and at least 128 right-hand sides: the contraction on the vector ALUs (supports bit-exact)."""
+    rng = np.random.default_rng(11000 + seed)
+    N = int(rng.integers(128, 700))
+    r = 4 * int(rng.integers(1, 5))
+    d = int(rng.integers(r, 6000))
+    k = int(rng.integers(1, min(r, d) + 1))
+    mode = "stored" if rng.random() < 0.5 else "philox"
+    say("narrow", seed, dict(N=N, d=d, r=r, k=k, mode=mode))
+    if mode == "stored":
+        At = synth.gaussian_matrix(seed, d, r)
+        A = sgc.Matrix(d, r, At=dev(At))
+    else:
+        At = orc.philox_matrix(seed, d, r)
+        A = sgc.Matrix(d, r, At=None, seed=seed)
+    A.inv_colnorm = torch.empty(d, dtype=torch.float32, device=DEV)
+    sgc.sgc_matrix_colnorms(A, A.inv_colnorm)
+    Y = rng.standard_normal((N, r)).astype(np.float32)
+    Y[0] = 0.0
+    Y[5] = np.round(Y[5])
+    sel = torch.empty((N, k), dtype=torch.int32, device=DEV)
+    x = torch.empty((N, k), device=DEV)
+    ws = torch.empty(sgc.sgc_omp_workspace_bytes(N, d, r, k), dtype=torch.uint8, device=DEV)
+    sgc.sgc_recover_omp(dev(Y), N, A, k, sel, x, ws)
+    torch.cuda.synchronize()
+    rsel, rx = orc.omp_batch(Y, At, k)
+    assert np.array_equal(sel.cpu().numpy(), rsel)
+    xn = x.cpu().numpy()
+    for n in range(N):
+        assert relerr(xn[n], rx[n]) < 1e-4, n
