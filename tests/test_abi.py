@@ -133,6 +133,11 @@ def test_omp_rejects_bad_arguments_and_sizes_workspace():
     assert rec(head=0) == sgc.ERR_SHAPE and rec(head=33) == sgc.ERR_SHAPE
     assert rec(AA=mat(d=4098, r=256, gram=0x1000)) == sgc.ERR_SHAPE  # d % 4
     assert rec(nbytes=need) == sgc.ERR_WORKSPACE                   # sized for the plain recovery
+    # a generated matrix that does not fit the workspace's panel whole (256 MB of rows, few right-hand sides)
+    big_ws = sgc.sgc_omp_recurrence_workspace_bytes(2, 1 << 20, 64, 4)
+    assert big_ws > 0
+    assert L.sgc_recover_omp_recurrence(FAKE, 2, ctypes.byref(mat(mode=1, d=1 << 20, r=64, gram=0x1000)), 4, 4, FAKE, FAKE,
+                                        FAKE, big_ws, None) == sgc.ERR_SHAPE
     assert rec(ws=ctypes.c_void_p(0x1010)) == sgc.ERR_ALIGN
 
 
