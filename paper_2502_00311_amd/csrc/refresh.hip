@@ -413,7 +413,8 @@ hipError_t launch_outer_refresh(float *B, const void *G, bool g_bf16, int32_t co
     hipError_t e;
     {
         ProfileScope prof(KC_OUTER_REFRESH, s);
-        reseed_zero_rows_kernel<<<dim3((unsigned)(rho * count)), 256, 0, s>>>(B, m);
+        if (iters > 0) // without a round nothing would orthonormalise the new rows
+            reseed_zero_rows_kernel<<<dim3((unsigned)(rho * count)), 256, 0, s>>>(B, m);
         const int64_t tiles_x = (n + 31) / 32, tiles_y = (m + 31) / 32;
         const dim3 grid((unsigned)(tiles_x * tiles_y), (unsigned)count);
         if (g_bf16)

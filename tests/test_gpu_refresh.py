@@ -147,6 +147,19 @@ def test_refresh_fills_zero_rows_of_the_start_matrix_again():
     assert np.abs(B - Bref).max() < 1e-4
 
 
+def test_refresh_without_rounds_leaves_zero_rows_alone():
+    rng = np.random.default_rng(14)
+    m, n, rho = 64, 96, 4
+    G = rng.standard_normal((m, n)).astype(np.float32)
+    Q, _ = np.linalg.qr(rng.standard_normal((m, rho)))
+    start = Q.T.copy()
+    start[2] = 0.0
+    B, s = refresh(G, rho, 0, start=start)
+    live = np.delete(start, 2, axis=0)
+    assert np.abs(B.T @ B - live.T @ live).max() < 1e-5          # the three directions given, rotated; nothing invented
+    assert np.abs(B[3]).max() == 0.0 and s[3] == 0.0
+
+
 def test_refresh_from_the_previous_matrix_needs_few_rounds():
     # the periodic use: the gradient's subspace has drifted a little since the last decomposition
     rng = np.random.default_rng(10)
