@@ -145,6 +145,26 @@ def test_recurrence_exact_recovery():
         assert relerr(x[n], X[n, sel[n]]) < 1e-5
 
 
+def test_recurrence_with_iterations_to_spare_stays_valid():
+    # a 5-sparse vector recovered with k = 12: after the fifth pick the residual is rounding noise and the
+    # float correlation vector no longer decides the same picks as the oracle (the limit App. B's recurrence
+    # has by construction); what must still hold: the meaningful picks and values, and a valid support
+    rng = np.random.default_rng(5)
+    N, d, r, k, sp = 4, 1024, 128, 12, 5
+    A, At = make_matrix("stored", 6, d, r)
+    X = np.zeros((N, d), np.float32)
+    supp = [np.sort(rng.permutation(d)[:sp]) for _ in range(N)]
+    for n in range(N):
+        X[n, supp[n]] = (1.0 + rng.random(sp)).astype(np.float32) * np.sign(rng.standard_normal(sp)).astype(np.float32)
+    Y = (X.astype(np.float64) @ At.astype(np.float64)).astype(np.float32)
+    sel, x = run(Y, A, k, True)
+    for n in range(N):
+        assert sorted(sel[n][:sp].tolist()) == supp[n].tolist()
+        assert relerr(x[n][:sp], X[n, sel[n][:sp]]) < 1e-5
+        assert len(set(sel[n].tolist())) == k and sel[n].min() >= 0 and sel[n].max() < d
+        assert np.abs(x[n][sp:]).max() < 1e-4 and np.isfinite(x[n]).all()
+
+
 def test_recurrence_validation():
     L = sgc.lib()
     A, _ = make_matrix("stored", 4, 256, 32)
