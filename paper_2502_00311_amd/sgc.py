@@ -116,6 +116,15 @@ def _ptr(t):
     return ctypes.c_void_p(t.data_ptr()) if t is not None else None
 
 
+_GRAD_DTYPES = (torch.float32, torch.bfloat16, torch.int16, torch.uint16)
+
+
+def _expect(t, dtypes, what):
+    """The C ABI takes untyped pointers: a tensor of another element type would be read as garbage."""
+    if t is not None and t.dtype not in dtypes:
+        raise TypeError("%s must be %s, got %s" % (what, " or ".join(str(x) for x in dtypes), t.dtype))
+
+
 def _stream(stream):
     if stream is None:
         stream = torch.cuda.current_stream()
@@ -162,6 +171,10 @@ def sgc_matrix_gram(A, gram_out, stream=None):
 
 
 def sgc_sparsify_project(grad, n, d, k, A, idx, val, p, q, stream=None):
+    _expect(grad, _GRAD_DTYPES, "grad")
+    _expect(idx, (torch.int32,), "idx")
+    for t, nm in ((val, "val"), (p, "p"), (q, "q")):
+        _expect(t, (torch.float32,), nm)
     gt = GRAD_BF16 if grad.dtype in (torch.bfloat16, torch.int16, torch.uint16) else GRAD_F32
     _check(lib().sgc_sparsify_project(_ptr(grad), gt, n, d, k, ctypes.byref(A.c()), _ptr(idx), _ptr(val), _ptr(p), _ptr(q), _stream(stream)), "sgc_sparsify_project")
 
@@ -175,6 +188,9 @@ def sgc_omp_workspace_bytes(N, d, r, k):
 
 
 def sgc_recover_omp(y, N, A, k, sel, x, ws, stream=None):
+    _expect(y, (torch.float32,), "y")
+    _expect(sel, (torch.int32,), "sel")
+    _expect(x, (torch.float32,), "x")
     _check(lib().sgc_recover_omp(_ptr(y), N, ctypes.byref(A.c()), k, _ptr(sel), _ptr(x), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_recover_omp")
 
 
@@ -184,6 +200,10 @@ def sgc_omp_recurrence_workspace_bytes(N, d, r, k, head=None):
 
 def sgc_recover_omp_recurrence(y, N, A, k, sel, x, ws, stream=None, head=None):
     """head: iterations served by the recurrence (default: all k)."""
+    _expect(y, (torch.float32,), "y")
+    _expect(sel, (torch.int32,), "sel")
+    _expect(x, (torch.float32,), "x")
+    _expect(A.gram, (torch.float64,), "A.gram")
     _check(lib().sgc_recover_omp_recurrence(_ptr(y), N, ctypes.byref(A.c()), k, k if head is None else head, _ptr(sel), _ptr(x), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_recover_omp_recurrence")
 
 
@@ -204,11 +224,16 @@ def sgc_outer_workspace_bytes(count, rho, m, n):
 
 
 def sgc_outer_project(B, G, count, rho, m, n, Gc, ws, stream=None):
+    _expect(G, _GRAD_DTYPES, "G")
+    _expect(B, (torch.float32,), "B")
+    _expect(Gc, (torch.float32,), "Gc")
     gt = GRAD_BF16 if G.dtype in (torch.bfloat16, torch.int16, torch.uint16) else GRAD_F32
     _check(lib().sgc_outer_project(_ptr(B), _ptr(G), gt, count, rho, m, n, _ptr(Gc), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_outer_project")
 
 
 def sgc_outer_apply(W, B, count, rho, m, n, d, k, sel_m, x_m, sel_v, x_v, h, ws, stream=None):
+    _expect(W, (torch.float32,), "W")
+    _expect(B, (torch.float32,), "B")
     _check(lib().sgc_outer_apply(_ptr(W), _ptr(B), count, rho, m, n, d, k, _ptr(sel_m), _ptr(x_m), _ptr(sel_v), _ptr(x_v), ctypes.byref(h), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_outer_apply")
 
 
@@ -217,6 +242,9 @@ def sgc_outer_refresh_workspace_bytes(count, rho, m, n, grad_type=GRAD_F32):
 
 
 def sgc_outer_refresh(B, G, count, rho, m, n, iters, sigma, ws, stream=None):
+    _expect(G, _GRAD_DTYPES, "G")
+    _expect(B, (torch.float32,), "B")
+    _expect(sigma, (torch.float32,), "sigma")
     gt = GRAD_BF16 if G.dtype in (torch.bfloat16, torch.int16, torch.uint16) else GRAD_F32
     _check(lib().sgc_outer_refresh(_ptr(B), _ptr(G), gt, count, rho, m, n, iters, _ptr(sigma) if sigma is not None else None,
                                    _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_outer_refresh")

@@ -255,3 +255,19 @@ def test_outer_projection_rejects_bad_arguments_and_sizes_workspace():
     assert fresh(iters=-1) == sgc.ERR_SHAPE and fresh(iters=1001) == sgc.ERR_SHAPE
     assert fresh(B=ODD) == sgc.ERR_ALIGN and fresh(G=ODD) == sgc.ERR_ALIGN and fresh(ws=ODD) == sgc.ERR_ALIGN
     assert fresh(nb=need - 1) == sgc.ERR_WORKSPACE and fresh(count=2) == sgc.ERR_WORKSPACE and fresh(count=0) == sgc.ERR_SHAPE
+
+
+def test_binding_rejects_tensors_of_the_wrong_element_type():
+    """The C ABI takes untyped pointers; the binding refuses what would be read as garbage (no GPU needed:
+    the check comes before the library is called)."""
+    import torch
+    g64 = torch.zeros((4, 8), dtype=torch.float64)
+    f32 = torch.zeros((4, 8), dtype=torch.float32)
+    with pytest.raises(TypeError):
+        sgc.sgc_outer_project(f32, g64, 1, 4, 4, 8, f32, f32)
+    with pytest.raises(TypeError):
+        sgc.sgc_outer_refresh(f32, g64, 1, 4, 4, 8, 1, None, f32)
+    with pytest.raises(TypeError):
+        sgc.sgc_recover_omp(g64, 4, None, 1, f32, f32, f32)
+    with pytest.raises(TypeError):
+        sgc.sgc_sparsify_project(g64, 32, 8, 1, None, f32, f32, f32, f32)
