@@ -147,7 +147,7 @@ sgc_status sgc_matrix_gram(const sgc_matrix *A /* host */, double *gram_out, voi
  *   idx        out [n/d][k] chunk-local positions, ascending within a chunk
  *   val        out [n/d][k] the kept (signed) values widened to float
  *   p, q       out [n/d][r]; q may be NULL. Until the projection writes them, the call may use both as
- *              scratch (the top-k of chunks longer than 16384 floats keeps its candidates there)
+ *              scratch (the top-k of float chunks longer than 16384 keeps its candidates there)
  * Magnitudes are ordered by the bit pattern with the sign cleared; among equal magnitudes
  * the lower position is kept. Squares are formed in float; sums are accumulated in float in
  * the order of ascending position.

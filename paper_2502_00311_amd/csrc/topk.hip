@@ -410,7 +410,7 @@ __global__ __launch_bounds__(64) void topk_merge_kernel(const int32_t *__restric
                                                         const float *__restrict__ cand_v, int32_t S, int32_t dsub,
                                                         int32_t k, int32_t *__restrict__ idx, float *__restrict__ val)
 {
-    __shared__ uint32_t keys[4 * 256];
+    __shared__ uint32_t keys[1024]; // S * k <= 1024
     const uint32_t lane = threadIdx.x;
     const uint32_t n = (uint32_t)(S * k);
     const int64_t base = (int64_t)blockIdx.x * n;
@@ -449,14 +449,16 @@ hipError_t launch_topk(const void *grad, int grad_type, int64_t C, int32_t d, in
     ProfileScope prof(KC_TOPK, s);
     if (grad_type == SGC_GRAD_F32) {
         const int32_t vec = (d % 4 == 0) ? 1 : 0; // every chunk then starts 16-byte aligned
-        // Chunks of 16385 .. 65536 floats: the register kernel for that length holds a whole chunk per
-        // 1024-thread workgroup, one workgroup per CU, and loads and selects in turn (3.2 TB/s). With
-        // scratch for S * k candidates per chunk the chunk is instead cut in S <= 4 pieces that go through
-        // the 256-thread kernel, five workgroups per CU, and a small second pass merges the candidates.
+        // Chunks of more than 16384 floats: the register kernel for up to 65536 holds a whole chunk per
+        // 1024-thread workgroup, one workgroup per CU, and loads and selects in turn (3.2 TB/s); beyond that
+        // the general kernel makes several passes. With scratch for S * k candidates per chunk the chunk is
+        // instead cut in S <= 16 pieces of at most 16384 that go through the 256-thread kernel, five
+        // workgroups per CU, and a small second pass merges the (at most 1024) candidates.
         const int32_t S = (d + 16383) / 16384;
         // (k <= 128: the 256-thread kernel bounds the threshold by the k-th largest of its 256 per-thread
         // maxima, which is a useful bound only while k is well below 256)
-        if (d > 16384 && S <= 4 && d % (4 * S) == 0 && k <= 128 && k <= d / S && scratch_i && scratch_v &&
+        if (d > 16384 && S <= 16 && S * k <= 1024 && d % (4 * S) == 0 && k <= 128 && k <= d / S && scratch_i &&
+            scratch_v &&
             (int64_t)C * S * k <= scratch_elems && (int64_t)C * S < (1ll << 31)) {
             const int32_t dsub = d / S;
             topk_f32_regs_kernel<256, 5><<<dim3((unsigned)(C * S)), 256, 0, s>>>((const float *)grad, dsub, k, scratch_i,

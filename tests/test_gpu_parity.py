@@ -120,6 +120,9 @@ def test_topk_ties_zeros_and_quantised_values():
     (65536, 129, 1024),   # one more: single pass
     (65536, 1, 8),        # the paper's memory-efficient setting
     (40000, 30, 512),     # 40000 % 12 != 0: single pass
+    (131072, 100, 800),   # eight pieces
+    (262144, 64, 1024),   # sixteen pieces, 1024 candidates to merge
+    (262144, 65, 2048),   # 1040 candidates: the general kernel
 ])
 def test_topk_long_chunks_two_pass(d, k, r):
     """Chunks of 16385 .. 65536 floats are cut in up to four pieces whose candidates are merged in a second
