@@ -21,19 +21,49 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense float matrix peak
-# HBM bytes per launch of the correlation kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/), keyed by workload name; None until measured.
-MEASURED_TRAFFIC = {"cfg2_64x65536": 5.528e8,  # profiles/cfg2_corr_kernel_hbm_traffic.md
-                    "cesgc_16x4096x4096_rank32": 1.390e8}  # per matrix; profiles/cesgc_16x4096x4096_kernel_trace_stats.md
+# Vector-ALU issue peak in lane-instructions per second: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz (a wavefront's
+# plain float instruction occupies its SIMD for four cycles). The published 157.3 TFLOP/s vector figure is this
+# rate x 2 flop per FMA x 2 for the packed form, which this library does not use.
+VALU_PEAK_TLANE = 39.3
+PROJECT_INSTR_PER_QUAD = 200.0  # vector instructions per four generated entries of A in project_kernel (50 per normal)
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, keyed by
+# workload name: (bytes, the summary under profiles/ that holds the run). Stored figures: they describe the
+# kernel as it was when that profile was taken.
+MEASURED_TRAFFIC = {"cfg2_64x65536": (5.528e8, "profiles/cfg2_corr_kernel_hbm_traffic.md"),
+                    "cesgc_16x4096x4096_rank32": (1.390e8, "profiles/cesgc_16x4096x4096_kernel_trace_stats.md")}  # per matrix
+
+
+def host_gradients(w, step, workers):
+    """One step's gradient chunks, drawn on the host by `workers` threads (every chunk has its own seed, so the
+    result does not depend on the split)."""
+    import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
+    from paper_2502_00311_amd import synth
+
+    if w.C < 4 * workers:
+        return synth.gradients(w, step)
+    edges = np.linspace(0, w.C, 4 * workers + 1).astype(int)
+    with ThreadPoolExecutor(workers) as ex:
+        parts = list(ex.map(lambda i: synth.gradients(w, step, chunks=range(edges[i], edges[i + 1])), range(4 * workers)))
+    return np.concatenate(parts, axis=0)
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", type=int, default=2, help="configuration index 1..5 (default 2); 6 = the paper's own MESGC setting (r = 8, k = 1) on configuration 4's block")
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", type=int, default=4,
+                    help="configuration index 1..5 (default 4: the linear weights of one Llama-2-7B block, the largest "
+                         "configuration, 202 M gradient elements); 6 = the paper's own MESGC setting (r = 8, k = 1) on "
+                         "configuration 4's block")
     ap.add_argument("--chunks", type=int, default=0, help="override the number of chunks (0 = as defined)")
+    ap.add_argument("--distinct-steps", type=int, default=0,
+                    help="gradient draws kept resident and cycled through the steps (0 = one per step up to 4 GB of "
+                         "gradients, i.e. 4 draws for configuration 4)")
+    ap.add_argument("--event-steps", type=int, default=3,
+                    help="steps of the second pass that records HIP events around every kernel launch (the roofline's "
+                         "launch durations come from there)")
     ap.add_argument("--shared-support", action="store_true",
                     help="recover one support per chunk from mhat and fit vhat on it (sgc_recover_omp_shared) "
                          "instead of the two independent recoveries of Alg. 2")
@@ -57,7 +87,8 @@ def main():
                          "(LLaMA-7B attention projections), rank 32, chunks of 2048, k = 31, r = 220")
     ap.add_argument("--cesgc-matrices", type=int, default=16)
     ap.add_argument("--no-variants", action="store_true",
-                    help="skip the short extra runs of the optional variants reported under \"variants\"")
+                    help="skip the extra runs reported next to the headline: the shared-support variant, the micro-runs "
+                         "and the labelled secondary entry on configuration 2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies (reference for the rocprofv3 FETCH_SIZE / "
@@ -72,7 +103,6 @@ def main():
               "chunk range, but no multi-GPU path is built); run with --gpus 1", file=sys.stderr)
         return 2
 
-    import numpy as np
     import torch
     from paper_2502_00311_amd import sgc, synth
 
@@ -88,8 +118,41 @@ def main():
     w = synth.CONFIGS[args.workload]
     if args.chunks:
         w = synth.shrink(w, C=args.chunks)
+    if args.recurrence:
+        if args.shared_support:
+            print("bench.py: --recurrence goes with the two-support recovery", file=sys.stderr)
+            return 2
+        args.gram = True
+    out = run_workload(args, w, dev, args.steps, args.warmup, variants=not args.no_variants,
+                       baseline=not args.no_cpu_baseline)
+    if not args.no_variants:
+        # labelled micro-runs of the HBM-bound kernels at a size where launch latency does not hide them
+        out["micro"] = micro_runs(dev)
+        plain = not (args.shared_support or args.screen_bf16 or args.gram or args.recurrence or args.materialize or args.chunks)
+        if plain and args.workload != 2:
+            # secondary entry: configuration 2 (64 chunks of 65536, r 2048, k 256, stored matrix streamed from HBM
+            # in every iteration), a few steps, same code path
+            torch.cuda.empty_cache()
+            sec = run_workload(args, synth.CFG2, dev, min(args.steps, 5), 1, variants=False, baseline=False)
+            out["secondary"] = {key: sec[key] for key in ("value", "unit", "steps", "warmup", "ms_per_step", "config", "roofline", "kernels")}
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+    print(json.dumps(out))
+    return 0
+
+
+def run_workload(args, w, dev, K, Wm, variants, baseline):
+    """Time K steps of workload w after Wm warm-up steps; returns the dictionary of the JSON line."""
+    import numpy as np
+    import torch
+    from paper_2502_00311_amd import sgc, synth
+
     C, d, r, k = w.C, w.d, w.r, w.k
-    K, Wm = args.steps, args.warmup
+    workers = min(16, os.cpu_count() or 1)
 
     # ---- inputs, resident before timing ----
     At_host = None
@@ -107,13 +170,9 @@ def main():
     if args.screen_bf16:
         A.flags = sgc.MATRIX_FLAG_SCREEN_BF16
     gram_ms = None
-    if args.recurrence:
-        if args.recurrence_head < 0:
-            args.recurrence_head = max(1, min(k, r // 64))
-        if args.shared_support:
-            print("bench.py: --recurrence goes with the two-support recovery", file=sys.stderr)
-            return 2
-        args.gram = True
+    head = args.recurrence_head
+    if args.recurrence and head < 0:
+        head = max(1, min(k, r // 64))
     if args.gram:
         A.gram = torch.empty((d, d), dtype=torch.float64, device=dev)
         torch.cuda.synchronize()
@@ -122,13 +181,18 @@ def main():
         torch.cuda.synchronize()
         gram_ms = (time.perf_counter() - tg) * 1e3
     nsteps = max(K, Wm, 1)
+    step_bytes = (2.0 if w.grad == "bf16" else 4.0) * C * d
+    ndraw = args.distinct_steps or max(1, min(nsteps, int(4.0e9 // step_bytes)))
+    ndraw = min(ndraw, nsteps)
     grads = []
-    for t in range(1, nsteps + 1):
-        g = synth.gradients(w, t)
+    for t in range(1, ndraw + 1):
+        g = host_gradients(w, t, workers)
         grads.append(torch.from_numpy(g.view(np.int16) if w.grad == "bf16" else g).to(dev))
+        del g
     W0 = torch.from_numpy(synth.weights(w)).to(dev)
     Wt = W0.clone()
-    buf = sgc.StepBuffers(C, d, r, k, device=dev, recurrence=(args.recurrence_head or True) if args.recurrence else False)
+    buf = sgc.StepBuffers(C, d, r, k, device=dev, recurrence=(head or True) if args.recurrence else False,
+                          screen=args.screen_bf16)
     h = sgc.hyper()
 
     def reset():
@@ -138,7 +202,7 @@ def main():
 
     def run(n, shared=None):
         for t in range(1, n + 1):
-            sgc.step(grads[t - 1], Wt, buf, A, t, h, shared_support=args.shared_support if shared is None else shared)
+            sgc.step(grads[(t - 1) % ndraw], Wt, buf, A, t, h, shared_support=args.shared_support if shared is None else shared)
 
     run(Wm)
     torch.cuda.synchronize()
@@ -151,12 +215,13 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / K
     value = C * d / (ms_per_step * 1e-3)
 
-    # ---- same steps again with HIP events around every kernel launch ----
+    # ---- a second pass with HIP events around every kernel launch (on the stream the kernels run on) ----
+    Ke = max(1, min(K, args.event_steps))
     reset()
     torch.cuda.synchronize()
     sgc.sgc_profile_enable(True)
     t2 = time.perf_counter()
-    run(K)
+    run(Ke)
     torch.cuda.synchronize()
     t3 = time.perf_counter()
     prof = sgc.sgc_profile_read()
@@ -164,7 +229,7 @@ def main():
     corr_ms, corr_n = prof["omp_corr"]
     fill_ms, _ = prof["omp_matrix_fill"]
     # one launch covers all d positions (stored / in-kernel generated A) or one panel of them
-    launches_per_iter = corr_n / (K * k)
+    launches_per_iter = corr_n / (Ke * k)
     nrhs = C if args.shared_support else 2 * C
     flops_per_launch = 2.0 * d * r * nrhs / launches_per_iter
     avg_ms = corr_ms / max(corr_n, 1)
@@ -175,53 +240,56 @@ def main():
         achieved *= 3.0
         peak = 2500.0
         kernel_name = "omp correlation contraction At*R (3 x bf16 32x32x16 MFMA on split operands, fused argmax epilogue)"
+    traffic = None if (args.shared_support or args.screen_bf16 or args.chunks) else MEASURED_TRAFFIC.get(w.name)
     roofline = {
         "bound": "mfma", "kernel": kernel_name,
         "achieved": round(achieved, 3), "peak": peak, "unit": "TFLOP/s",
         "frac": round(achieved / peak, 4),
-        "traffic": None if (args.shared_support or args.screen_bf16) else MEASURED_TRAFFIC.get(w.name),
+        "traffic": traffic[0] if traffic else None,
+        "traffic_source": (traffic[1] + " (rocprofv3 --pmc runs of this command; a stored figure, not read in this run)") if traffic else None,
         "flops_per_launch": flops_per_launch, "avg_launch_ms": round(avg_ms, 5), "launches": corr_n,
+        "event_steps": Ke,
     }
     if r <= 16 and 2 * C >= 128 and not args.recurrence:
         # very few measurements: the contraction runs on the vector ALUs (corr_narrow_kernel: r FMAs and about
         # 7 further instructions per score), and the top-k scan is the larger kernel of the step
         ops = float(d) * nrhs * (r + 7) * k
-        rate = ops / (corr_ms / K * 1e-3)
+        rate = ops / (corr_ms / Ke * 1e-3)
         roofline = {"bound": "alu", "kernel": "omp correlation on the vector ALUs (r <= 16), lane-instructions per second",
-                    "achieved": round(rate / 1e12, 3), "peak": 78.6, "unit": "T lane-instr/s",
-                    "frac": round(rate / 7.86e13, 4), "traffic": None, "avg_launch_ms": round(avg_ms, 5), "launches": corr_n}
+                    "achieved": round(rate / 1e12, 3), "peak": VALU_PEAK_TLANE, "unit": "T lane-instr/s",
+                    "frac": round(rate / (VALU_PEAK_TLANE * 1e12), 4), "traffic": None, "avg_launch_ms": round(avg_ms, 5), "launches": corr_n}
         tk_ms, tk_n = prof["topk"]
         if tk_n and tk_ms > corr_ms:
             gbps = ((2.0 if w.grad == "bf16" else 4.0) * C * d + 8.0 * C * k) / (tk_ms / tk_n * 1e-3) / 1e9
             roofline = {"bound": "hbm", "kernel": "top-k scan of the gradients (the dominant kernel at this shape)",
                         "achieved": round(gbps, 1), "peak": 8000.0, "unit": "GB/s", "frac": round(gbps / 8000.0, 4),
                         "traffic": None, "avg_launch_ms": round(tk_ms / tk_n, 5), "launches": tk_n,
-                        "omp_corr_alu_frac": round(rate / 7.86e13, 4)}
+                        "omp_corr_alu_frac": round(rate / (VALU_PEAK_TLANE * 1e12), 4)}
     if args.recurrence:
         # no contraction inside the iterations: the class holds p0 = A^H y (once per call) and the k - 1 updates
         # of p, which stream the image vectors b_t (4 d j bytes at iteration j), a row of the table (8 d), the
         # new b (4 d written) and p (8 d) per right-hand side
-        head = args.recurrence_head or k
-        total = float(nrhs) * d * sum(4.0 * j + 20.0 for j in range(1, head)) + 8.0 * nrhs * d
-        if head == k:
-            gbps = total / (corr_ms / K * 1e-3) / 1e9
+        hd = head or k
+        total = float(nrhs) * d * sum(4.0 * j + 20.0 for j in range(1, hd)) + 8.0 * nrhs * d
+        if hd == k:
+            gbps = total / (corr_ms / Ke * 1e-3) / 1e9
             roofline = {"bound": "hbm", "kernel": "correlation recurrence p <- p - b a (App. B), all its launches of a step",
                         "achieved": round(gbps, 1), "peak": 8000.0, "unit": "GB/s", "frac": round(gbps / 8000.0, 4),
-                        "traffic": None, "bytes_per_step": total, "ms_per_step": round(corr_ms / K, 3), "launches": corr_n}
+                        "traffic": None, "bytes_per_step": total, "ms_per_step": round(corr_ms / Ke, 3), "launches": corr_n}
         else:
             # both engines inside one class of launches: the contraction's flop over the whole class's time is a
             # lower bound of its rate
-            flops = 2.0 * d * r * nrhs * (k - head)
-            tf = flops / (corr_ms / K * 1e-3) / 1e12
+            flops = 2.0 * d * r * nrhs * (k - hd)
+            tf = flops / (corr_ms / Ke * 1e-3) / 1e12
             roofline = {"bound": "mfma", "kernel": "recurrence for %d iterations, then the float contraction; rate = the "
-                        "contraction's flop over the time of both" % head,
+                        "contraction's flop over the time of both" % hd,
                         "achieved": round(tf, 3), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
                         "frac": round(tf / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None,
-                        "recurrence_bytes_per_step": total, "ms_per_step": round(corr_ms / K, 3), "launches": corr_n}
+                        "recurrence_bytes_per_step": total, "ms_per_step": round(corr_ms / Ke, 3), "launches": corr_n}
     if fill_ms > 0 and roofline.get("bound") == "mfma":  # generated A produced by a separate fill kernel: the rate including that time
         if not args.recurrence:
             roofline["achieved_incl_matrix_fill"] = round(flops_per_launch * corr_n / ((corr_ms + fill_ms) * 1e-3) / 1e12, 3)
-    kernels = {n: {"ms_per_step": round(ms / K, 4), "launches_per_step": cnt / K} for n, (ms, cnt) in prof.items()}
+    kernels = {n: {"ms_per_step": round(ms / Ke, 4), "launches_per_step": cnt / Ke} for n, (ms, cnt) in prof.items()}
     # HBM-bound companions (algorithmic bytes / event time)
     bytes_adam = 32.0 * C * r
     bytes_topk = (2.0 if w.grad == "bf16" else 4.0) * C * d + 8.0 * C * k
@@ -232,6 +300,21 @@ def main():
         ms, cnt = prof[name]
         if cnt:
             kernels[name]["algorithmic_GBps"] = round(nbytes / (ms / cnt * 1e-3) / 1e9, 2)
+            kernels[name]["frac_of_8TBps"] = round(nbytes / (ms / cnt * 1e-3) / 8e12, 3)
+    if w.matrix != "stored" and not args.materialize and prof["project"][1]:
+        # generated matrix: the projection is bound by the generator's vector arithmetic, PROJECT_INSTR_PER_QUAD
+        # lane-instructions per four entries of A
+        ms, cnt = prof["project"]
+        rate = float(C) * k * (r / 4) * PROJECT_INSTR_PER_QUAD / (ms / cnt * 1e-3)
+        kernels["project"]["T_lane_instr_per_s"] = round(rate / 1e12, 2)
+        kernels["project"]["frac_of_valu_peak"] = round(rate / (VALU_PEAK_TLANE * 1e12), 3)
+    # the least-squares update and residual against one read of the selected columns per iteration
+    # (N r j 4 bytes at iteration j) plus one pass over the factor F (N j^2 / 2 doubles)
+    su_ms, su_n = prof["omp_select_update"]
+    if su_n:
+        ls_bytes = sum(4.0 * nrhs * r * j + 4.0 * nrhs * j * j for j in range(1, k + 1))
+        kernels["omp_select_update"]["algorithmic_GBps"] = round(ls_bytes / (su_ms / Ke * 1e-3) / 1e9, 1)
+        kernels["omp_select_update"]["frac_of_8TBps"] = round(ls_bytes / (su_ms / Ke * 1e-3) / 8e12, 3)
 
     out = {
         "metric": "gradient elements/s per full SGC step (1 GPU)", "value": round(value, 1), "unit": "elements/s",
@@ -240,91 +323,87 @@ def main():
         "config": {"workload": w.name, "chunks": C, "d": d, "r": r, "k": k, "grad": w.grad,
                    "matrix": "philox, materialised by the caller" if (args.materialize and w.matrix != "stored") else w.matrix,
                    "rhs_per_omp_call": nrhs,
+                   "gradient_draws": "%d distinct steps resident in HBM, cycled over the %d steps; moments persist" % (ndraw, K),
                    "recovery": "shared_support" if args.shared_support else "two_supports",
                    "gram_table": bool(args.gram),
-                   "contraction": ("none inside the iterations (correlation recurrence)" if not args.recurrence_head
-                                   else "correlation recurrence for %d iterations, then float" % args.recurrence_head) if args.recurrence
+                   "contraction": ("none inside the iterations (correlation recurrence)" if not head
+                                   else "correlation recurrence for %d iterations, then float" % head) if args.recurrence
                    else ("bf16 split (3 products), float accumulate" if args.screen_bf16 else "float")},
         "roofline": roofline,
-        "ms_per_step_with_events": round((t3 - t2) * 1e3 / K, 3),
+        "ms_per_step_with_events": round((t3 - t2) * 1e3 / Ke, 3),
         "gram_build_ms": None if gram_ms is None else round(gram_ms, 2),
         "kernels": kernels,
     }
 
-    # ---- the optional variants of the recovery, three steps each (context, not the headline) ----
-    if not args.no_variants and not (args.shared_support or args.screen_bf16 or args.gram or args.recurrence):
-        variants = {}
+    # ---- the shared-support recovery (first widening), three steps (context, not the headline) ----
+    if variants and not (args.shared_support or args.screen_bf16 or args.gram or args.recurrence):
         nv = min(3, nsteps)
-        for name, shared, flags in (("shared_support", True, 0),
-                                    ("screen_bf16", False, sgc.MATRIX_FLAG_SCREEN_BF16),
-                                    ("shared_support+screen_bf16", True, sgc.MATRIX_FLAG_SCREEN_BF16)):
-            A.flags = flags
-            reset()
-            run(1, shared)
-            reset()
-            torch.cuda.synchronize()
-            tv = time.perf_counter()
-            run(nv, shared)
-            torch.cuda.synchronize()
-            ms = (time.perf_counter() - tv) * 1e3 / nv
-            variants[name] = {"ms_per_step": round(ms, 3), "value": round(C * d / (ms * 1e-3), 1), "steps": nv}
-        A.flags = 0
-        # the two recovery engines combined (needs the Gram table, 8 d^2 bytes, and (r/64 + 1) d floats per
-        # right-hand side): the recurrence of App. B for the first r/64 iterations, the contraction after
-        if 8.0 * d * d <= 40 * 2.0 ** 30 and d % 4 == 0:
-            try:
-                head = max(1, min(k, r // 64))
-                A.gram = torch.empty((d, d), dtype=torch.float64, device=dev)
-                sgc.sgc_matrix_gram(A, A.gram)
-                hb = sgc.StepBuffers(C, d, r, k, device=dev, recurrence=head)
-
-                def run_h(n):
-                    hb.m.zero_()
-                    hb.v.zero_()
-                    Wt.copy_(W0)
-                    for t in range(1, n + 1):
-                        sgc.step(grads[t - 1], Wt, hb, A, t, h)
-
-                run_h(1)
-                torch.cuda.synchronize()
-                tv = time.perf_counter()
-                run_h(nv)
-                torch.cuda.synchronize()
-                ms = (time.perf_counter() - tv) * 1e3 / nv
-                variants["gram+recurrence_head_%d" % head] = {"ms_per_step": round(ms, 3),
-                                                              "value": round(C * d / (ms * 1e-3), 1), "steps": nv}
-                del hb
-            except Exception as exc:  # a variant must not take the headline line down with it
-                variants["gram+recurrence_head"] = {"error": str(exc)}
-            A.gram = None
-        out["variants"] = variants
-
-    # ---- labelled micro-runs of the HBM-bound kernels at a size where launch latency does not hide them
-    #      (at this workload they move 4-17 MB per launch) ----
-    if not args.no_variants:
-        out["micro"] = micro_runs(dev)
-
-    if args.copy_calibration:
-        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
+        reset()
+        run(1, True)
+        reset()
         torch.cuda.synchronize()
+        tv = time.perf_counter()
+        run(nv, True)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - tv) * 1e3 / nv
+        out["variants"] = {"shared_support": {"ms_per_step": round(ms, 3), "value": round(C * d / (ms * 1e-3), 1), "steps": nv}}
 
-    if not args.no_cpu_baseline:
+    del grads, buf, Wt, W0
+    A.gram = None
+    torch.cuda.empty_cache()
+    if baseline:
         out["cpu_baseline"] = cpu_baseline(w, At_host, args.shared_support)
-    print(json.dumps(out))
-    return 0
+    return out
+
+
+def probe_runs(dev):
+    """What this machine delivers for the resources the kernels are bound by (sgc_probe; best of 5 launches):
+    plain v_fma_f32 issue rate, float MFMA rate, streaming read, the Adam kernel's 4-read / 4-write pattern,
+    and a plain copy."""
+    import torch
+    from paper_2502_00311_amd import sgc
+
+    res = {}
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    nbytes = 2 << 30
+    src = torch.empty(nbytes // 2, dtype=torch.uint8, device=dev)
+    dst = torch.empty(nbytes // 2, dtype=torch.uint8, device=dev)
+    src.fill_(1)
+
+    def best(kind, blocks, iters, nb, rd=src):
+        sgc.sgc_probe(kind, rd, dst, nb, blocks, iters)
+        t = 1e30
+        for _ in range(5):
+            a.record()
+            sgc.sgc_probe(kind, rd, dst, nb, blocks, iters)
+            b.record()
+            torch.cuda.synchronize()
+            t = min(t, a.elapsed_time(b))
+        return t
+
+    iters, blocks = 20000, 2048
+    ms = best(sgc.PROBE_VALU, blocks, iters, 0)
+    res["valu_fma_T_lane_instr_per_s"] = round(blocks * 256.0 * iters * 64 / (ms * 1e-3) / 1e12, 2)
+    ms = best(sgc.PROBE_MFMA, 1024, iters, 0)
+    res["mfma_f32_TFLOPs"] = round(1024 * 4.0 * iters * 16 * 4096 / (ms * 1e-3) / 1e12, 1)
+    ms = best(sgc.PROBE_READ, 4096, 0, nbytes // 2)
+    res["read_GBps"] = round(nbytes / 2 / (ms * 1e-3) / 1e9, 1)
+    ms = best(sgc.PROBE_RW44, 4096, 0, nbytes)
+    res["rw_4read_4write_GBps"] = round(nbytes / (ms * 1e-3) / 1e9, 1)
+    ms = best(sgc.PROBE_COPY, 4096, 0, nbytes)
+    res["copy_GBps"] = round(nbytes / (ms * 1e-3) / 1e9, 1)
+    del src, dst
+    return res
 
 
 def micro_runs(dev):
     """Top-k (+ projection with a generated matrix) on configuration 4's shape and the Adam update on
     64 M state elements: algorithmic bytes / HIP-event time per launch. Inputs: normal deviates drawn on
-    the device (only the memory traffic matters here)."""
+    the device (only the memory traffic matters here). Plus the machine probes."""
     import torch
     from paper_2502_00311_amd import sgc
 
-    res = {}
+    res = {"probes": probe_runs(dev)}
     reps = 10
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     # Adam: p, q, m, v read; m, v, mhat, vhat written = 32 B per element
@@ -341,30 +420,12 @@ def micro_runs(dev):
     b.record()
     torch.cuda.synchronize()
     ms = a.elapsed_time(b) / reps
-    res["adam_64M_elements"] = {"ms": round(ms, 4), "algorithmic_GBps": round(32.0 * n / (ms * 1e-3) / 1e9, 1),
-                                "frac_of_8TBps": round(32.0 * n / (ms * 1e-3) / 8e12, 3)}
+    gbps = 32.0 * n / (ms * 1e-3) / 1e9
+    res["adam_64M_elements"] = {"ms": round(ms, 4), "algorithmic_GBps": round(gbps, 1),
+                                "frac_of_8TBps": round(gbps / 8e3, 3),
+                                "ceiling_probe_GBps": res["probes"]["rw_4read_4write_GBps"],
+                                "frac_of_ceiling_probe": round(gbps / res["probes"]["rw_4read_4write_GBps"], 3)}
     del p, q, m, v, mh, vh
-    # top-k alone cannot be called; the projection with a generated matrix reads only the 8k B per chunk that
-    # top-k wrote, so the profile class "topk" of the fused call is the top-k kernel
-    C, d, r, k = 12352, 16384, 1024, 64
-    g = torch.randn(C * d, device=dev)
-    A = sgc.Matrix(d, r, At=None, seed=7)
-    idx = torch.empty((C, k), dtype=torch.int32, device=dev)
-    val = torch.empty((C, k), dtype=torch.float32, device=dev)
-    pp, qq = torch.empty((C, r), device=dev), torch.empty((C, r), device=dev)
-    for _ in range(2):
-        sgc.sgc_sparsify_project(g, C * d, d, k, A, idx, val, pp, qq)
-    torch.cuda.synchronize()
-    sgc.sgc_profile_enable(True)
-    for _ in range(reps):
-        sgc.sgc_sparsify_project(g, C * d, d, k, A, idx, val, pp, qq)
-    torch.cuda.synchronize()
-    prof = sgc.sgc_profile_read()
-    sgc.sgc_profile_enable(False)
-    ms = prof["topk"][0] / max(prof["topk"][1], 1)
-    nbytes = 4.0 * C * d + 8.0 * C * k
-    res["topk_12352x16384_k64"] = {"ms": round(ms, 4), "algorithmic_GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
-                                   "frac_of_8TBps": round(nbytes / (ms * 1e-3) / 8e12, 3)}
     return res
 
 
@@ -483,7 +544,7 @@ def main_cesgc(args, dev):
                    "chunks": C, "d": d, "r": r, "k": k, "matrix": "stored", "rhs_per_omp_call": 2 * C},
         "roofline": {"bound": "hbm", "kernel": "CESGC back-projection W -= lr B^T N (zero fill + read-modify-write of W), per matrix of the batch",
                      "achieved": round(achieved, 1), "peak": 8000.0, "unit": "GB/s", "frac": round(achieved / 8000.0, 4),
-                     "traffic": MEASURED_TRAFFIC.get("cesgc_%dx4096x4096_rank32" % M), "bytes_per_matrix": bytes_back, "avg_ms_per_matrix": round(back_ms, 5)},
+                     "traffic": (MEASURED_TRAFFIC.get("cesgc_%dx4096x4096_rank32" % M) or (None,))[0], "bytes_per_matrix": bytes_back, "avg_ms_per_matrix": round(back_ms, 5)},
         "kernels": kernels,
     }
     # the renewal of B (outside the step: the paper does it every fixed number of steps): all matrices in one
@@ -525,44 +586,57 @@ def main_cesgc(args, dev):
     return 0
 
 
-def cpu_baseline(w, At_host, shared_support=False):
-    """The CPU oracle (single thread, as it stands) on chunk 0 of step 1 of the same workload."""
+def cpu_baseline(w, At_host, shared_support=False, budget_s=20.0):
+    """The CPU oracle (single thread, as it stands) on a bounded sample of step 1 of the same workload: whole
+    chunks spread evenly over the batch (for configuration 4 that is over its seven weight matrices), each run
+    through the whole path - top-k, projection, Adam, OMP(mhat), OMP(vhat), apply - until about budget_s seconds
+    of CPU work are spent. A configuration whose single recovery would take minutes is timed on its first
+    iterations (every iteration scans all d columns, which dominates) and scaled to k."""
     import numpy as np
     from oracle import oracle as orc
     from paper_2502_00311_amd import synth
 
     if At_host is None:
         At_host = orc.philox_matrix(w.a_seed, w.d, w.r)
-    g = synth.gradients(w, 1, chunks=[0])
     norm = orc.colnorms(At_host)
-    t0 = time.perf_counter()
-    idx, val = orc.topk(g, w.k)
-    p, q = orc.project(idx, val, At_host)
-    z = np.zeros((1, w.r), np.float32)
-    m, v, mh, vh = orc.adam(p, q, z, z, 1)
-    t1 = time.perf_counter()
-    # OMP cost does not depend on the data: time OMP(mhat) with all k iterations, count OMP(vhat) the same.
-    # Configurations whose single right-hand side would take minutes are timed on the first iterations
-    # (every iteration scans all d columns, which dominates) and scaled to k.
-    per_iter = 2.0 * w.d * w.r / 2.0e9
-    iters = w.k if per_iter * w.k <= 45 else max(8, int(30 / per_iter))
-    o = orc.omp(mh[0], At_host, iters, norm=norm)
-    t2 = time.perf_counter()
-    Wc = synth.weights(w, chunks=[0])
-    orc.apply(Wc, w.d, o["sel"][None], o["x"][None], o["sel"][None], np.abs(o["x"])[None])
-    t3 = time.perf_counter()
-    t_fit = 0.0
-    if shared_support:
+    per_iter = 2.0 * w.d * w.r / 2.0e9          # seconds per iteration at ~2 Gflop/s, to plan the sample
+    full = per_iter * w.k * 2 <= budget_s
+    iters = w.k if full else max(4, int(budget_s / 2 / per_iter))
+    iters = min(iters, w.k)
+    want = max(1, min(w.C, 8, int(budget_s / max(per_iter * iters * 2, 1e-3))))
+    chunks = sorted(set(int(c) for c in np.linspace(0, w.C - 1, want + 2)[1:-1])) if want < w.C else list(range(w.C))
+    t_total, done = 0.0, []
+    t_begin = time.perf_counter()
+    for c in chunks:
+        g = synth.gradients(w, 1, chunks=[c])
+        Wc = synth.weights(w, chunks=[c])
+        z = np.zeros((1, w.r), np.float32)
+        t0 = time.perf_counter()
+        idx, val = orc.topk(g, w.k)
+        p, q = orc.project(idx, val, At_host)
+        m, v, mh, vh = orc.adam(p, q, z, z, 1)
+        t1 = time.perf_counter()
+        om = orc.omp(mh[0], At_host, iters, norm=norm)
+        t2 = time.perf_counter()
+        if shared_support:
+            ov = {"sel": om["sel"], "x": orc.lstsq_support(vh[0], At_host, om["sel"])}
+        else:
+            ov = orc.omp(vh[0], At_host, iters, norm=norm)
+        t3 = time.perf_counter()
+        orc.apply(Wc, w.d, om["sel"][None], om["x"][None], ov["sel"][None], np.asarray(ov["x"], np.float32)[None])
         t4 = time.perf_counter()
-        orc.lstsq_support(vh[0], At_host, o["sel"])
-        t_fit = time.perf_counter() - t4
-    t_chunk = (t1 - t0) + (1.0 if shared_support else 2.0) * (t2 - t1) * (w.k / iters) + (t3 - t2) + t_fit
+        scale = w.k / iters
+        t_total += (t1 - t0) + (t2 - t1) * scale + (t3 - t2) * (1.0 if shared_support else scale) + (t4 - t3)
+        done.append(c)
+        if time.perf_counter() - t_begin > budget_s:
+            break
     return {
-        "value": round(w.d / t_chunk, 2), "unit": "elements/s", "cores": 1, "kind": "oracle",
-        "sample": "chunk 0 of step 1 (1 of %d chunks): top-k, projection, Adam, OMP(mhat) timed for %d of %d "
-                  "iterations and scaled, %s, apply; %.1f s of CPU work measured"
-                  % (w.C, iters, w.k, "least-squares fit of vhat on the support" if shared_support
-                     else "OMP(vhat) counted at the same cost", t3 - t0 + t_fit),
+        "value": round(w.d * len(done) / t_total, 2), "unit": "elements/s", "cores": 1, "kind": "oracle",
+        "sample": "chunks %s of step 1 (%d of %d chunks), each through the whole path: top-k, projection, Adam, "
+                  "OMP(mhat), %s, apply; %s; %.1f s of CPU work counted"
+                  % (done, len(done), w.C, "least-squares fit of vhat on its support" if shared_support else "OMP(vhat)",
+                     "all %d iterations timed" % w.k if iters == w.k else
+                     "recoveries timed for %d of %d iterations and scaled" % (iters, w.k), t_total),
         "host_cores": os.cpu_count(),
     }
 

@@ -47,7 +47,7 @@ enum {
     SGC_ERR_SHAPE = -2,     /* k == 0, k > d, k > r, n % d != 0, r % 4 != 0, size out of range */
     SGC_ERR_DTYPE = -3,     /* unknown gradient type or matrix mode */
     SGC_ERR_ALIGN = -4,     /* a pointer is not aligned to 16 bytes */
-    SGC_ERR_WORKSPACE = -5, /* workspace smaller than sgc_omp_workspace_bytes() */
+    SGC_ERR_WORKSPACE = -5, /* workspace smaller than the size query says */
     SGC_ERR_STEP = -6,      /* step < 1, or a hyper-parameter outside its range */
     SGC_ERR_DEVICE = -7     /* a HIP call failed (launch error, no device) */
 };
@@ -168,8 +168,14 @@ sgc_status sgc_adam_compressed(const float *p, const float *q, float *m, float *
                                float *vhat, int64_t count, int32_t step,
                                const sgc_hyper *h /* host */, void *stream);
 
-/* bytes of workspace sgc_recover_omp needs for N right-hand sides; 0 on invalid sizes */
+/* bytes of workspace sgc_recover_omp / sgc_recover_omp_shared need for N right-hand sides; 0 on invalid
+ * sizes. sgc_omp_workspace_bytes covers any matrix without option flags (stored or generated);
+ * sgc_omp_workspace_bytes_for gives the exact need of one matrix (A->mode, A->d, A->r, A->flags are read): a
+ * stored matrix is read in place and needs neither the copies of the selected columns nor a panel of
+ * generated rows, and only a matrix with SGC_MATRIX_FLAG_SCREEN_BF16 needs the bfloat16 planes (4 d r bytes
+ * more, at most 2 GiB), so callers who set that flag must size the workspace with this query. */
 size_t sgc_omp_workspace_bytes(int32_t N, int32_t d, int32_t r, int32_t k);
+size_t sgc_omp_workspace_bytes_for(int32_t N, int32_t k, const sgc_matrix *A /* host */);
 
 /*
  * Batched orthogonal matching pursuit (eq. 9; selection rule and output of App. B): for each
@@ -179,8 +185,8 @@ size_t sgc_omp_workspace_bytes(int32_t N, int32_t d, int32_t r, int32_t k);
  *   y    [N][r]
  *   sel  out [N][k] selected positions in selection order
  *   x    out [N][k] least-squares values aligned with sel
- *   ws   workspace of at least sgc_omp_workspace_bytes(N, d, r, k) bytes, 256-byte aligned;
- *        contents are scratch
+ *   ws   workspace of at least sgc_omp_workspace_bytes_for(N, k, A) bytes (sgc_omp_workspace_bytes(N, d, r, k)
+ *        is enough for any A without option flags), 256-byte aligned; contents are scratch
  * All N correlations of one iteration are one dense contraction At * R on the float matrix
  * cores; the near-maximal candidates are then re-scored in double, and the least-squares
  * update (inverse-Cholesky form of App. B) and the residual are computed in double.
@@ -248,6 +254,12 @@ sgc_status sgc_recover_omp_recurrence(const float *y, int32_t N, const sgc_matri
  */
 sgc_status sgc_reproject(const int32_t *sel, const float *x, int64_t N, int32_t k,
                          const sgc_matrix *A_new /* host */, double scale, float *out, void *stream);
+/* The same with scale = 1 - beta^step formed on the host exactly as sgc_adam_compressed forms its bias
+ * correction (Alg. 4 lines 10-11 applied to the vectors recovered from mhat / vhat at step `step`).
+ * Errors: as sgc_reproject; STEP (step < 1, beta outside [0,1)). */
+sgc_status sgc_reproject_moment(const int32_t *sel, const float *x, int64_t N, int32_t k,
+                                const sgc_matrix *A_new /* host */, double beta, int32_t step, float *out,
+                                void *stream);
 
 /*
  * eq. 11 and eq. 3 on the recovered supports of C chunks:
@@ -339,6 +351,24 @@ typedef struct sgc_profile {
 } sgc_profile;
 sgc_status sgc_profile_enable(int32_t on);
 sgc_status sgc_profile_read(sgc_profile *out /* host */);
+
+/*
+ * Machine probes (instrumentation, not a step of the method): one launch of a small kernel that exercises
+ * a single resource, for the caller to time, so that fractions quoted against published peaks can be read
+ * next to what the same machine delivers.
+ *   SGC_PROBE_VALU  blocks x 256 threads, each `iters` x 64 dependent-chain v_fma_f32 (16 chains, plain
+ *                   non-packed form, registers only): lane-instructions = blocks * 256 * iters * 64
+ *   SGC_PROBE_MFMA  blocks x 4 wavefronts, each `iters` x 16 v_mfma_f32_32x32x2f32 (4096 flop each)
+ *   SGC_PROBE_READ  reads `bytes` of a with non-temporal 16-byte loads
+ *   SGC_PROBE_RW44  reads four arrays of bytes/8 from a and writes four of bytes/8 to b (the Adam kernel's
+ *                   traffic pattern: `bytes` moved in total); a and b must each hold bytes/2
+ *   SGC_PROBE_COPY  copies bytes/2 from a to b
+ * a (may be NULL for VALU / MFMA) and b (at least 4 bytes) are device pointers, 16-byte aligned; a
+ * multiple of 128 bytes keeps every access whole. Errors: NULL, SHAPE, DTYPE (unknown kind), ALIGN, DEVICE.
+ */
+enum { SGC_PROBE_VALU = 0, SGC_PROBE_MFMA = 1, SGC_PROBE_READ = 2, SGC_PROBE_RW44 = 3, SGC_PROBE_COPY = 4 };
+sgc_status sgc_probe(int32_t kind, const void *a, void *b, int64_t bytes, int32_t blocks, int32_t iters,
+                     void *stream);
 
 #ifdef __cplusplus
 }

@@ -159,7 +159,15 @@ size_t sgc_omp_workspace_bytes(int32_t N, int32_t d, int32_t r, int32_t k)
 {
     if (!omp_sizes_ok(N, d, r, k))
         return 0;
-    return carve_workspace(nullptr, N, d, r, k).bytes;
+    // enough for a stored or a generated matrix without option flags
+    return carve_workspace(nullptr, N, d, r, k, WS_NEED_GENERATED).bytes;
+}
+
+size_t sgc_omp_workspace_bytes_for(int32_t N, int32_t k, const sgc_matrix *A)
+{
+    if (check_matrix(A, false) != SGC_OK || !omp_sizes_ok(N, A->d, A->r, k))
+        return 0;
+    return carve_workspace(nullptr, N, A->d, A->r, k, workspace_need(A->mode, A->flags)).bytes;
 }
 
 sgc_status sgc_recover_omp(const float *y, int32_t N, const sgc_matrix *A, int32_t k, int32_t *sel, float *x,
@@ -174,7 +182,7 @@ sgc_status sgc_recover_omp(const float *y, int32_t N, const sgc_matrix *A, int32
         return SGC_ERR_SHAPE;
     if (!aligned16(y) || !aligned16(A->inv_colnorm) || ((uintptr_t)ws & 255u))
         return SGC_ERR_ALIGN;
-    const OmpWorkspace w = carve_workspace(ws, N, A->d, A->r, k);
+    const OmpWorkspace w = carve_workspace(ws, N, A->d, A->r, k, workspace_need(A->mode, A->flags));
     if (ws_bytes < w.bytes)
         return SGC_ERR_WORKSPACE;
     return from_hip(launch_omp(y, N, make_view(A), k, sel, x, w, (hipStream_t)stream));
@@ -184,7 +192,7 @@ size_t sgc_omp_recurrence_workspace_bytes(int32_t N, int32_t d, int32_t r, int32
 {
     if (!omp_sizes_ok(N, d, r, k) || d % 4 != 0 || head < 1 || head > k)
         return 0;
-    return carve_recurrence(nullptr, N, d, r, k, head).bytes;
+    return carve_recurrence(nullptr, N, d, r, k, head, WS_NEED_GENERATED | WS_NEED_SCREEN).bytes;
 }
 
 sgc_status sgc_recover_omp_recurrence(const float *y, int32_t N, const sgc_matrix *A, int32_t k, int32_t head,
@@ -201,7 +209,7 @@ sgc_status sgc_recover_omp_recurrence(const float *y, int32_t N, const sgc_matri
         return SGC_ERR_SHAPE;
     if (!aligned16(y) || !aligned16(A->inv_colnorm) || !aligned16(A->gram) || ((uintptr_t)ws & 255u))
         return SGC_ERR_ALIGN;
-    const OmpWorkspace w = carve_recurrence(ws, N, A->d, A->r, k, head);
+    const OmpWorkspace w = carve_recurrence(ws, N, A->d, A->r, k, head, WS_NEED_GENERATED | WS_NEED_SCREEN);
     // a generated matrix must fit the workspace's panel as a whole: the selection reads its columns from there
     if (A->mode == SGC_MATRIX_PHILOX && w.panel_rows < A->d)
         return SGC_ERR_SHAPE;
@@ -222,7 +230,7 @@ sgc_status sgc_recover_omp_shared(const float *y_m, const float *y_v, int32_t C,
         return SGC_ERR_SHAPE;
     if (!aligned16(y_m) || !aligned16(y_v) || !aligned16(A->inv_colnorm) || ((uintptr_t)ws & 255u))
         return SGC_ERR_ALIGN;
-    const OmpWorkspace w = carve_workspace(ws, C, A->d, A->r, k);
+    const OmpWorkspace w = carve_workspace(ws, C, A->d, A->r, k, workspace_need(A->mode, A->flags));
     if (ws_bytes < w.bytes)
         return SGC_ERR_WORKSPACE;
     return from_hip(launch_omp(y_m, C, make_view(A), k, sel, x, w, (hipStream_t)stream, y_v, z));
@@ -241,6 +249,15 @@ sgc_status sgc_reproject(const int32_t *sel, const float *x, int64_t N, int32_t 
     if (!aligned16(out))
         return SGC_ERR_ALIGN;
     return from_hip(launch_project(sel, x, N, k, make_view(A_new), out, nullptr, (hipStream_t)stream, (float)scale));
+}
+
+sgc_status sgc_reproject_moment(const int32_t *sel, const float *x, int64_t N, int32_t k, const sgc_matrix *A_new,
+                                double beta, int32_t step, float *out, void *stream)
+{
+    if (step < 1 || !(beta >= 0.0 && beta < 1.0))
+        return SGC_ERR_STEP;
+    // the same expression as the bias correction of sgc_adam_compressed
+    return sgc_reproject(sel, x, N, k, A_new, 1.0 - pow(beta, (double)step), out, stream);
 }
 
 sgc_status sgc_apply(float *W, int64_t C, int32_t d, int32_t k, const int32_t *sel_m, const float *x_m,

@@ -5,7 +5,7 @@ import sys
 from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SOURCES = ["api.hip", "topk.hip", "project.hip", "adam.hip", "apply.hip", "matrix.hip", "omp.hip", "omp_corr.hip", "omp_recur.hip", "outer.hip", "refresh.hip", "profile.hip"]
+SOURCES = ["api.hip", "topk.hip", "project.hip", "adam.hip", "apply.hip", "matrix.hip", "omp.hip", "omp_corr.hip", "omp_recur.hip", "outer.hip", "refresh.hip", "profile.hip", "probe.hip"]
 LIB = os.path.join(HERE, "libsgc.so")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",

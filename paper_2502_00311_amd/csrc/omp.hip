@@ -17,6 +17,7 @@
 // App. B precomputes the Gram matrix A^H A (d x d) to avoid the contraction; here the contraction
 // is kept (it is what the matrix cores are for) and only inner products with selected columns are
 // formed, so memory stays O(N k r).
+#include <mutex>
 #include <type_traits>
 
 #include "omp_internal.h"
@@ -26,7 +27,7 @@ namespace sgc {
 
 constexpr float RESCORE_TOL = 0x1.0p-10f; // candidates within this relative distance of the float maximum
 
-OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_t k)
+OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_t k, uint32_t need)
 {
     OmpWorkspace w{};
     size_t off = 0;
@@ -45,7 +46,10 @@ OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_
     w.xs_half = (int64_t)N * k;
     w.res32 = (float *)take(sizeof(float) * (size_t)N * r);
     w.res16 = reinterpret_cast<uint16_t *>(w.res32);
-    w.cols = (float *)take(sizeof(float) * (size_t)N * k * r);
+    // the per-right-hand-side copies of the selected columns and the panel serve generated matrices only:
+    // a stored matrix is read in place
+    const bool generated = (need & WS_NEED_GENERATED) != 0;
+    w.cols = generated ? (float *)take(sizeof(float) * (size_t)N * k * r) : nullptr;
     w.partial = (uint64_t *)take(sizeof(uint64_t) * (size_t)N * w.tiles_m * 2);
     w.bitmap = (uint32_t *)take(sizeof(uint32_t) * (size_t)N * w.words);
     // Rows of a generated matrix, in whole tiles. A matrix of at most 64 MiB gets a panel of its own (it
@@ -60,17 +64,20 @@ OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_
         const int64_t dpad = ((int64_t)d + 255) / 256 * 256;
         if (small_rows > dpad)
             small_rows = dpad;
-        if (dpad > small_rows && dpad <= (int64_t)N * k) {
+        if (generated && dpad > small_rows && dpad <= (int64_t)N * k) {
             w.panel_rows = (int32_t)dpad;
             w.panel = w.cols;
         } else {
             w.panel_rows = (int32_t)small_rows;
-            w.panel = (float *)take(sizeof(float) * (size_t)small_rows * r);
+            w.panel = generated ? (float *)take(sizeof(float) * (size_t)small_rows * r) : nullptr;
         }
     }
-    // bfloat16 planes of the matrix rows for the screening contraction: the whole matrix if that is at
-    // most 2 GiB, else a 64 MiB panel's worth (larger resident matrices then keep the float contraction)
-    {
+    // bfloat16 planes of the matrix rows for the screening contraction (only when the matrix asks for it): the
+    // whole matrix if that is at most 2 GiB, else a 64 MiB panel's worth (larger resident matrices then keep
+    // the float contraction)
+    w.a16_rows = 0;
+    w.a16 = nullptr;
+    if (need & WS_NEED_SCREEN) {
         const int64_t dpad = ((int64_t)d + 127) / 128 * 128;
         w.a16_rows = dpad * r * 4 <= ((int64_t)2 << 30) ? (int32_t)dpad : (int32_t)small_rows;
         w.a16 = (uint16_t *)take(sizeof(float) * (size_t)w.a16_rows * r);
@@ -81,9 +88,9 @@ OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_
     return w;
 }
 
-OmpWorkspace carve_recurrence(void *base, int32_t N, int32_t d, int32_t r, int32_t k, int32_t head)
+OmpWorkspace carve_recurrence(void *base, int32_t N, int32_t d, int32_t r, int32_t k, int32_t head, uint32_t need)
 {
-    OmpWorkspace w = carve_workspace(base, N, d, r, k);
+    OmpWorkspace w = carve_workspace(base, N, d, r, k, need);
     size_t off = w.bytes;
     auto take = [&](size_t bytes) {
         void *p = base ? (void *)((char *)base + off) : nullptr;
@@ -696,6 +703,7 @@ struct OmpPlan {
     bool factor_share_table; // update_kernel sums its wavefronts' shares through an LDS table
     bool narrow;     // r <= 16 on resident rows: corr_narrow_kernel
     bool recurrence; // the correlation vector is updated by App. B's recurrence instead of contracted anew
+    bool one_stream; // everything on the caller's stream (no library-owned stream or events are touched)
 };
 
 // the workspace as seen by the right-hand sides [n0, ...): every per-right-hand-side array shifted
@@ -815,9 +823,11 @@ struct SideStream {
 static SideStream *side_stream()
 {
     static SideStream per_device[64];
+    static std::mutex mu; // creation is guarded; the stream itself is still shared by all callers on the device
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
         return nullptr;
+    std::lock_guard<std::mutex> lock(mu);
     SideStream &ss = per_device[dev];
     if (!ss.tried) {
         ss.tried = true;
@@ -833,7 +843,8 @@ static hipError_t omp_iterations(const OmpPlan &pl, bool whole_matrix_panel, con
                                  hipStream_t s);
 
 hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k, int32_t *sel, float *x,
-                      const OmpWorkspace &ws, hipStream_t s, const float *y_fit, float *z, bool recurrence)
+                      const OmpWorkspace &ws, hipStream_t s, const float *y_fit, float *z, bool recurrence,
+                      bool one_stream)
 {
     // A generated matrix is written out once per call when the workspace has room for all of it. One
     // that does not fit is regenerated inside the contraction when few right-hand-side tiles share it;
@@ -860,6 +871,7 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
         pl.tiles_m = (A.d + 255) / 256;
     }
     pl.recurrence = recurrence;
+    pl.one_stream = one_stream;
     if (recurrence && (!A.gram || !ws.rc_p || ws.rc_head < 1 || ws.rc_head > k || A.d % 4 != 0 ||
                        (A.generated && ws.panel_rows < A.d)))
         return hipErrorInvalidValue;
@@ -947,7 +959,7 @@ static hipError_t omp_iterations(const OmpPlan &pl, bool whole_matrix_panel, con
     // and not when both halves would have to share a panel that is refilled inside the iterations)
     const int32_t N0 = (N / 2 + CORR_BN - 1) / CORR_BN * CORR_BN;
     SideStream *ss = nullptr;
-    if (N >= 4 * CORR_BN && N0 < N && !g_profile_on && !(pl.panels && !whole_matrix_panel))
+    if (N >= 4 * CORR_BN && N0 < N && !g_profile_on && !pl.one_stream && !(pl.panels && !whole_matrix_panel))
         ss = side_stream();
     if (!ss) {
         const Group g = make_group(0, N, s);

@@ -62,9 +62,16 @@ struct OmpWorkspace {
     int32_t rc_d;      // d (row length of rc_p and rc_B)
     double *cvec;      // [N][k] coordinates c_t of the newest column, exported by update_kernel
 };
-OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_t k);
+// `need`: which optional regions the matrix calls for. A stored matrix is read in place (no column copies, no
+// panel); the bfloat16 planes exist only for a matrix that asks for the screening contraction.
+enum : uint32_t { WS_NEED_GENERATED = 1u, WS_NEED_SCREEN = 2u };
+inline uint32_t workspace_need(int32_t mode, int32_t flags)
+{
+    return (mode == SGC_MATRIX_PHILOX ? WS_NEED_GENERATED : 0u) | ((flags & SGC_MATRIX_FLAG_SCREEN_BF16) ? WS_NEED_SCREEN : 0u);
+}
+OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_t k, uint32_t need);
 // the same workspace followed by the three arrays of the recurrence; `bytes` covers both
-OmpWorkspace carve_recurrence(void *base, int32_t N, int32_t d, int32_t r, int32_t k, int32_t head);
+OmpWorkspace carve_recurrence(void *base, int32_t N, int32_t d, int32_t r, int32_t k, int32_t head, uint32_t need);
 
 // kernel classes of the optional per-kernel timing (see profile.hip)
 enum KernelClass { KC_TOPK = 0, KC_PROJECT, KC_ADAM, KC_CORR, KC_SELECT, KC_APPLY, KC_OTHER, KC_FILL, KC_OUTER_PROJECT, KC_OUTER_APPLY, KC_OUTER_REFRESH };
@@ -86,7 +93,7 @@ hipError_t launch_colnorms(const MatrixView &A, float *out, hipStream_t s);
 hipError_t launch_gram(const MatrixView &A, double *out, hipStream_t s);
 hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k, int32_t *sel, float *x,
                       const OmpWorkspace &ws, hipStream_t s, const float *y_fit = nullptr, float *z = nullptr,
-                      bool recurrence = false);
+                      bool recurrence = false, bool one_stream = false);
 hipError_t launch_apply(float *W, int64_t C, int32_t d, int32_t k, const int32_t *sel_m, const float *x_m,
                         const int32_t *sel_v, const float *x_v, float alpha, float eps, float lr,
                         hipStream_t s);

@@ -20,12 +20,15 @@ MATRIX_FLAG_SCREEN_BF16 = 1
 
 EXPORTS = [
     "sgc_status_string", "sgc_matrix_fill", "sgc_matrix_colnorms", "sgc_matrix_gram", "sgc_sparsify_project",
-    "sgc_adam_compressed", "sgc_omp_workspace_bytes", "sgc_recover_omp", "sgc_recover_omp_shared", "sgc_reproject",
+    "sgc_adam_compressed", "sgc_omp_workspace_bytes", "sgc_omp_workspace_bytes_for", "sgc_recover_omp",
+    "sgc_recover_omp_shared", "sgc_reproject",
+    "sgc_reproject_moment",
     "sgc_omp_recurrence_workspace_bytes", "sgc_recover_omp_recurrence",
     "sgc_apply", "sgc_outer_workspace_bytes", "sgc_outer_project", "sgc_outer_apply",
     "sgc_outer_refresh_workspace_bytes", "sgc_outer_refresh",
-    "sgc_profile_enable", "sgc_profile_read",
+    "sgc_profile_enable", "sgc_profile_read", "sgc_probe",
 ]
+PROBE_VALU, PROBE_MFMA, PROBE_READ, PROBE_RW44, PROBE_COPY = 0, 1, 2, 3, 4
 PROFILE_CLASSES = ["topk", "project", "adam", "omp_corr", "omp_select_update", "apply", "other", "omp_matrix_fill",
                    "outer_project", "outer_apply", "outer_refresh"]
 
@@ -78,8 +81,12 @@ def lib():
         L.sgc_adam_compressed.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, ctypes.POINTER(sgc_hyper), vp]
         L.sgc_omp_workspace_bytes.restype = sz
         L.sgc_omp_workspace_bytes.argtypes = [i32, i32, i32, i32]
+        L.sgc_omp_workspace_bytes_for.restype = sz
+        L.sgc_omp_workspace_bytes_for.argtypes = [i32, i32, ctypes.POINTER(sgc_matrix)]
         L.sgc_recover_omp.restype = i32
         L.sgc_recover_omp.argtypes = [vp, i32, ctypes.POINTER(sgc_matrix), i32, vp, vp, vp, sz, vp]
+        L.sgc_reproject_moment.restype = i32
+        L.sgc_reproject_moment.argtypes = [vp, vp, i64, i32, ctypes.POINTER(sgc_matrix), ctypes.c_double, i32, vp, vp]
         L.sgc_omp_recurrence_workspace_bytes.restype = sz
         L.sgc_omp_recurrence_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
         L.sgc_recover_omp_recurrence.restype = i32
@@ -100,6 +107,8 @@ def lib():
         L.sgc_outer_refresh.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, sz, vp]
         L.sgc_outer_apply.restype = i32
         L.sgc_outer_apply.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, ctypes.POINTER(sgc_hyper), vp, sz, vp]
+        L.sgc_probe.restype = i32
+        L.sgc_probe.argtypes = [i32, vp, vp, i64, i32, i32, vp]
         L.sgc_profile_enable.restype = i32
         L.sgc_profile_enable.argtypes = [i32]
         L.sgc_profile_read.restype = i32
@@ -194,6 +203,10 @@ def sgc_recover_omp(y, N, A, k, sel, x, ws, stream=None):
     _check(lib().sgc_recover_omp(_ptr(y), N, ctypes.byref(A.c()), k, _ptr(sel), _ptr(x), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_recover_omp")
 
 
+def sgc_omp_workspace_bytes_for(N, k, A):
+    return int(lib().sgc_omp_workspace_bytes_for(N, k, ctypes.byref(A.c())))
+
+
 def sgc_omp_recurrence_workspace_bytes(N, d, r, k, head=None):
     return int(lib().sgc_omp_recurrence_workspace_bytes(N, d, r, k, k if head is None else head))
 
@@ -213,6 +226,10 @@ def sgc_recover_omp_shared(y_m, y_v, C, A, k, sel, x, z, ws, stream=None):
 
 def sgc_reproject(sel, x, N, k, A_new, scale, out, stream=None):
     _check(lib().sgc_reproject(_ptr(sel), _ptr(x), N, k, ctypes.byref(A_new.c()), scale, _ptr(out), _stream(stream)), "sgc_reproject")
+
+
+def sgc_reproject_moment(sel, x, N, k, A_new, beta, step, out, stream=None):
+    _check(lib().sgc_reproject_moment(_ptr(sel), _ptr(x), N, k, ctypes.byref(A_new.c()), beta, step, _ptr(out), _stream(stream)), "sgc_reproject_moment")
 
 
 def sgc_apply(W, C, d, k, sel_m, x_m, sel_v, x_v, h, stream=None):
@@ -250,6 +267,10 @@ def sgc_outer_refresh(B, G, count, rho, m, n, iters, sigma, ws, stream=None):
                                    _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)), "sgc_outer_refresh")
 
 
+def sgc_probe(kind, a, b, nbytes, blocks, iters, stream=None):
+    _check(lib().sgc_probe(kind, _ptr(a), _ptr(b), nbytes, blocks, iters, _stream(stream)), "sgc_probe")
+
+
 def sgc_profile_enable(on):
     _check(lib().sgc_profile_enable(1 if on else 0), "sgc_profile_enable")
 
@@ -264,7 +285,7 @@ def sgc_profile_read():
 class StepBuffers:
     """Device buffers of one SGC step on C chunks (allocation only; no arithmetic)."""
 
-    def __init__(self, C, d, r, k, device="cuda", recurrence=False):
+    def __init__(self, C, d, r, k, device="cuda", recurrence=False, screen=False):
         f32, i32 = torch.float32, torch.int32
         self.C, self.d, self.r, self.k = C, d, r, k
         # recurrence: False, True (all k iterations) or the number of iterations the recurrence serves; the
@@ -279,8 +300,15 @@ class StepBuffers:
         self.hat = torch.empty((2 * C, r), dtype=f32, device=device)  # [mhat; vhat]
         self.sel = torch.empty((2 * C, k), dtype=i32, device=device)
         self.x = torch.empty((2 * C, k), dtype=f32, device=device)
-        nbytes = (sgc_omp_recurrence_workspace_bytes(2 * C, d, r, k, self.recurrence) if self.recurrence
-                  else sgc_omp_workspace_bytes(2 * C, d, r, k))
+        # screen: the matrix will carry MATRIX_FLAG_SCREEN_BF16, whose bfloat16 planes take 4 d r bytes more
+        if self.recurrence:
+            nbytes = sgc_omp_recurrence_workspace_bytes(2 * C, d, r, k, self.recurrence)
+        elif screen:
+            probe = Matrix(d, r, seed=0)
+            probe.flags = MATRIX_FLAG_SCREEN_BF16
+            nbytes = sgc_omp_workspace_bytes_for(2 * C, k, probe)
+        else:
+            nbytes = sgc_omp_workspace_bytes(2 * C, d, r, k)
         if nbytes == 0:
             raise SgcError(ERR_SHAPE, "sgc_omp_workspace_bytes")
         self.ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
@@ -299,8 +327,8 @@ def step(grad, W, buf, A, t, h, stream=None, shared_support=False, A_new=None):
         sgc_recover_omp_shared(buf.hat[:C], buf.hat[C:], C, A, k, buf.sel[:C], buf.x[:C], buf.x[C:], buf.ws, stream)
         sgc_apply(W, C, d, k, buf.sel[:C], buf.x[:C], buf.sel[:C], buf.x[C:], h, stream)
         if A_new is not None:
-            sgc_reproject(buf.sel[:C], buf.x[:C], C, k, A_new, 1.0 - h.beta1 ** t, buf.m, stream)
-            sgc_reproject(buf.sel[:C], buf.x[C:], C, k, A_new, 1.0 - h.beta2 ** t, buf.v, stream)
+            sgc_reproject_moment(buf.sel[:C], buf.x[:C], C, k, A_new, h.beta1, t, buf.m, stream)
+            sgc_reproject_moment(buf.sel[:C], buf.x[C:], C, k, A_new, h.beta2, t, buf.v, stream)
         return
     if buf.recurrence:
         sgc_recover_omp_recurrence(buf.hat, 2 * C, A, k, buf.sel, buf.x, buf.ws, stream, head=buf.recurrence)
@@ -308,8 +336,8 @@ def step(grad, W, buf, A, t, h, stream=None, shared_support=False, A_new=None):
         sgc_recover_omp(buf.hat, 2 * C, A, k, buf.sel, buf.x, buf.ws, stream)
     sgc_apply(W, C, d, k, buf.sel[:C], buf.x[:C], buf.sel[C:], buf.x[C:], h, stream)
     if A_new is not None:
-        sgc_reproject(buf.sel[:C], buf.x[:C], C, k, A_new, 1.0 - h.beta1 ** t, buf.m, stream)
-        sgc_reproject(buf.sel[C:], buf.x[C:], C, k, A_new, 1.0 - h.beta2 ** t, buf.v, stream)
+        sgc_reproject_moment(buf.sel[:C], buf.x[:C], C, k, A_new, h.beta1, t, buf.m, stream)
+        sgc_reproject_moment(buf.sel[C:], buf.x[C:], C, k, A_new, h.beta2, t, buf.v, stream)
 
 
 class OuterBuffers:

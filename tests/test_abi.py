@@ -112,7 +112,17 @@ def test_omp_rejects_bad_arguments_and_sizes_workspace():
     assert call(N=0) == sgc.ERR_SHAPE
     assert call(k=0) == sgc.ERR_SHAPE
     assert call(k=257) == sgc.ERR_SHAPE
-    assert call(nbytes=need - 1) == sgc.ERR_WORKSPACE
+    # the exact need depends on the matrix: a stored one is read in place (no column copies, no panel), the
+    # bfloat16 planes of the screening contraction are counted only for a matrix that asks for them
+    exact = L.sgc_omp_workspace_bytes_for(2, 32, ctypes.byref(A))
+    gen = mat(mode=1, d=4096, r=256)
+    assert 0 < exact < L.sgc_omp_workspace_bytes_for(2, 32, ctypes.byref(gen)) == need
+    scr = sgc.sgc_matrix(0, 4096, 256, sgc.MATRIX_FLAG_SCREEN_BF16, 1, 0x1000, 0x1000, None)
+    assert L.sgc_omp_workspace_bytes_for(2, 32, ctypes.byref(scr)) >= exact + 4096 * 256 * 4
+    assert L.sgc_omp_workspace_bytes_for(2, 300, ctypes.byref(A)) == 0 and L.sgc_omp_workspace_bytes_for(2, 32, None) == 0
+    assert call(nbytes=exact - 1) == sgc.ERR_WORKSPACE
+    assert call(AA=gen, nbytes=need - 1) == sgc.ERR_WORKSPACE
+    assert call(AA=scr, nbytes=exact) == sgc.ERR_WORKSPACE         # sized without the planes
     assert call(ws=ctypes.c_void_p(0x1010)) == sgc.ERR_ALIGN
 
     # the engine with App. B's recurrence: the same checks, a larger workspace, and the Gram table is required
@@ -170,7 +180,7 @@ def test_shared_recovery_and_reprojection_reject_bad_arguments():
     assert shared(C=0) == sgc.ERR_SHAPE
     assert shared(k=1025) == sgc.ERR_SHAPE
     assert shared(yv=ODD) == sgc.ERR_ALIGN
-    assert shared(nbytes=need - 1) == sgc.ERR_WORKSPACE
+    assert shared(nbytes=L.sgc_omp_workspace_bytes_for(2, 32, ctypes.byref(A)) - 1) == sgc.ERR_WORKSPACE
 
     def reproject(sel=FAKE, x=FAKE, N=2, k=8, AA=A, scale=0.5, out=FAKE):
         return L.sgc_reproject(sel, x, N, k, ctypes.byref(AA) if AA is not None else None, scale, out, None)
@@ -183,6 +193,19 @@ def test_shared_recovery_and_reprojection_reject_bad_arguments():
     assert reproject(k=4097) == sgc.ERR_SHAPE
     assert reproject(out=ODD) == sgc.ERR_ALIGN
     assert reproject(AA=mat(mode=9)) == sgc.ERR_DTYPE
+
+    def moment(beta=0.9, step=3, out=FAKE, sel=FAKE):
+        return L.sgc_reproject_moment(sel, FAKE, 2, 8, ctypes.byref(A), beta, step, out, None)
+
+    assert moment(step=0) == sgc.ERR_STEP and moment(beta=1.0) == sgc.ERR_STEP and moment(beta=-0.5) == sgc.ERR_STEP
+    assert moment(sel=None) == sgc.ERR_NULL and moment(out=ODD) == sgc.ERR_ALIGN
+
+    # the machine probes validate like everything else
+    assert L.sgc_probe(99, FAKE, FAKE, 1024, 1, 1, None) == sgc.ERR_DTYPE
+    assert L.sgc_probe(sgc.PROBE_READ, None, FAKE, 1024, 1, 1, None) == sgc.ERR_NULL
+    assert L.sgc_probe(sgc.PROBE_VALU, None, None, 0, 1, 1, None) == sgc.ERR_NULL
+    assert L.sgc_probe(sgc.PROBE_VALU, None, FAKE, 0, 0, 1, None) == sgc.ERR_SHAPE
+    assert L.sgc_probe(sgc.PROBE_COPY, ODD, FAKE, 1024, 1, 1, None) == sgc.ERR_ALIGN
 
 
 def test_gram_rejects_bad_arguments():

@@ -47,7 +47,7 @@ def run_omp(Y, A, k):
     N, r = Y.shape
     sel = torch.empty((N, k), dtype=torch.int32, device=DEV)
     x = torch.empty((N, k), dtype=torch.float32, device=DEV)
-    ws = torch.empty(sgc.sgc_omp_workspace_bytes(N, A.d, r, k), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(sgc.sgc_omp_workspace_bytes_for(N, k, A), dtype=torch.uint8, device=DEV)
     sgc.sgc_recover_omp(dev(Y), N, A, k, sel, x, ws)
     torch.cuda.synchronize()
     return sel.cpu().numpy(), x.cpu().numpy()

@@ -67,7 +67,7 @@ def test_random_shape(seed):
         Y[N // 2] = 0.0
     sel = torch.empty((N, k), dtype=torch.int32, device=DEV)
     x = torch.empty((N, k), dtype=torch.float32, device=DEV)
-    ws = torch.empty(sgc.sgc_omp_workspace_bytes(N, d, r, k), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(sgc.sgc_omp_workspace_bytes_for(N, k, A), dtype=torch.uint8, device=DEV)
     if c["shared"]:
         Yv = np.abs(rng.standard_normal((N, r))).astype(np.float32)
         z = torch.empty((N, k), dtype=torch.float32, device=DEV)

@@ -53,7 +53,7 @@ def run(Y, A, k, recurrence, head=None):
         ws = torch.empty(sgc.sgc_omp_recurrence_workspace_bytes(N, A.d, r, k, head), dtype=torch.uint8, device=DEV)
         sgc.sgc_recover_omp_recurrence(dev(Y), N, A, k, sel, x, ws, head=head)
     else:
-        ws = torch.empty(sgc.sgc_omp_workspace_bytes(N, A.d, r, k), dtype=torch.uint8, device=DEV)
+        ws = torch.empty(sgc.sgc_omp_workspace_bytes_for(N, k, A), dtype=torch.uint8, device=DEV)
         sgc.sgc_recover_omp(dev(Y), N, A, k, sel, x, ws)
     torch.cuda.synchronize()
     return sel.cpu().numpy(), x.cpu().numpy()

@@ -44,7 +44,7 @@ def run_omp(Y, A, k):
     N, r = Y.shape
     sel = torch.empty((N, k), dtype=torch.int32, device=DEV)
     x = torch.empty((N, k), dtype=torch.float32, device=DEV)
-    ws = torch.empty(sgc.sgc_omp_workspace_bytes(N, A.d, r, k), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(sgc.sgc_omp_workspace_bytes_for(N, k, A), dtype=torch.uint8, device=DEV)
     sgc.sgc_recover_omp(dev(Y), N, A, k, sel, x, ws)
     torch.cuda.synchronize()
     return sel.cpu().numpy(), x.cpu().numpy()
@@ -119,7 +119,7 @@ def test_cfg2_full_size_screened_two_steps_sampled():
     A.inv_colnorm = torch.empty(d, dtype=torch.float32, device=DEV)
     sgc.sgc_matrix_colnorms(A, A.inv_colnorm)
     norm = orc.colnorms(At)
-    buf = sgc.StepBuffers(C, d, r, k)
+    buf = sgc.StepBuffers(C, d, r, k, screen=True)
     buf2 = sgc.StepBuffers(C, d, r, k)
     W = dev(synth.weights(w))
     W2 = W.clone()
@@ -146,7 +146,7 @@ def test_all_options_together_screen_gram_shared_support():
     A, At = make_matrix(w.matrix, w.a_seed, w.d, w.r)
     A.gram = torch.empty((w.d, w.d), dtype=torch.float64, device=DEV)
     sgc.sgc_matrix_gram(A, A.gram)
-    buf = sgc.StepBuffers(w.C, w.d, w.r, w.k)
+    buf = sgc.StepBuffers(w.C, w.d, w.r, w.k, screen=True)
     W = dev(synth.weights(w))
     h = sgc.hyper()
     C = w.C
