@@ -47,7 +47,7 @@ enum {
     SGC_ERR_SHAPE = -2,     /* k == 0, k > d, k > r, n % d != 0, r % 4 != 0, size out of range */
     SGC_ERR_DTYPE = -3,     /* unknown gradient type or matrix mode */
     SGC_ERR_ALIGN = -4,     /* a pointer is not aligned to 16 bytes */
-    SGC_ERR_WORKSPACE = -5, /* workspace smaller than the size query says */
+    SGC_ERR_WORKSPACE = -5, /* workspace smaller than the size query says (or than the static array) */
     SGC_ERR_STEP = -6,      /* step < 1, or a hyper-parameter outside its range */
     SGC_ERR_DEVICE = -7     /* a HIP call failed (launch error, no device) */
 };
@@ -195,6 +195,25 @@ size_t sgc_omp_workspace_bytes_for(int32_t N, int32_t k, const sgc_matrix *A /* 
  */
 sgc_status sgc_recover_omp(const float *y, int32_t N, const sgc_matrix *A /* host */, int32_t k,
                            int32_t *sel, float *x, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * sgc_recover_omp for callers that cannot allocate device memory or hand over a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels, with the
+ * workspace in a static device array of SGC_OMP_STATIC_WORKSPACE_BYTES that each GPU the library runs on
+ * holds until the process ends. The call allocates and frees nothing and keeps all work on `stream`
+ * (no library-owned second stream). Arguments and results as sgc_recover_omp.
+ * Limit: sgc_omp_workspace_bytes_for(N, k, A) must not exceed sgc_omp_static_workspace_bytes(), else
+ * SGC_ERR_WORKSPACE is returned and nothing is launched (32 MiB hold e.g. 2048 right-hand sides of
+ * d = 2048, r = 220, k = 31 with a stored matrix, or 16 of d = 16384, r = 1024, k = 64).
+ * All calls on one GPU share that GPU's array: two such calls whose kernels may overlap (different streams,
+ * different host threads) race; calls on one stream are safe. The array keeps the previous call's contents;
+ * every region read is written earlier in the same call.
+ * Errors: as sgc_recover_omp; WORKSPACE as above; DEVICE if the array's address cannot be resolved.
+ */
+enum { SGC_OMP_STATIC_WORKSPACE_BYTES = 32 << 20 };
+size_t sgc_omp_static_workspace_bytes(void);
+sgc_status sgc_recover_omp_static(const float *y, int32_t N, const sgc_matrix *A /* host */, int32_t k,
+                                  int32_t *sel, float *x, void *stream);
 
 /*
  * Shared-support recovery for C chunks. Sec. 4.3 (the remark after eq. 11) rests the element-wise

@@ -2,6 +2,8 @@
 // every step of the path runs in the kernels of the sibling files.
 #include <math.h>
 
+#include <mutex>
+
 #include "sgc_internal.h"
 
 namespace sgc {
@@ -186,6 +188,55 @@ sgc_status sgc_recover_omp(const float *y, int32_t N, const sgc_matrix *A, int32
     if (ws_bytes < w.bytes)
         return SGC_ERR_WORKSPACE;
     return from_hip(launch_omp(y, N, make_view(A), k, sel, x, w, (hipStream_t)stream));
+}
+
+// ---- recovery for callers that cannot allocate: the workspace is a static device array ----
+// Every device the library runs on holds its own copy of the array at its own address; in host code the
+// array's name is only a handle for hipGetSymbolAddress, never a pointer to hand to a kernel.
+static __device__ __align__(256) unsigned char scratch[SGC_OMP_STATIC_WORKSPACE_BYTES];
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[64]; // per device, resolved on the first call made with that device current
+
+static void *scratch_of_current_device()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+        return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr)
+            return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+
+size_t sgc_omp_static_workspace_bytes(void) { return SGC_OMP_STATIC_WORKSPACE_BYTES; }
+
+sgc_status sgc_recover_omp_static(const float *y, int32_t N, const sgc_matrix *A, int32_t k, int32_t *sel, float *x,
+                                  void *stream)
+{
+    if (!y || !sel || !x)
+        return SGC_ERR_NULL;
+    sgc_status st = check_matrix(A, true);
+    if (st != SGC_OK)
+        return st;
+    if (!omp_sizes_ok(N, A->d, A->r, k))
+        return SGC_ERR_SHAPE;
+    if (!aligned16(y) || !aligned16(A->inv_colnorm))
+        return SGC_ERR_ALIGN;
+    const uint32_t need = workspace_need(A->mode, A->flags);
+    if (carve_workspace(nullptr, N, A->d, A->r, k, need).bytes > SGC_OMP_STATIC_WORKSPACE_BYTES)
+        return SGC_ERR_WORKSPACE;
+    void *ptr = scratch_of_current_device();
+    if (!ptr)
+        return SGC_ERR_DEVICE;
+    // every region the kernels read is written earlier in the same call (the first kernel clears the
+    // selection bitmaps and sets the residuals), so what the previous call left behind does not matter
+    const OmpWorkspace w = carve_workspace(ptr, N, A->d, A->r, k, need);
+    return from_hip(launch_omp(y, N, make_view(A), k, sel, x, w, (hipStream_t)stream, nullptr, nullptr, false,
+                               /*one_stream=*/true));
 }
 
 size_t sgc_omp_recurrence_workspace_bytes(int32_t N, int32_t d, int32_t r, int32_t k, int32_t head)

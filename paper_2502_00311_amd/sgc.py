@@ -21,7 +21,7 @@ MATRIX_FLAG_SCREEN_BF16 = 1
 EXPORTS = [
     "sgc_status_string", "sgc_matrix_fill", "sgc_matrix_colnorms", "sgc_matrix_gram", "sgc_sparsify_project",
     "sgc_adam_compressed", "sgc_omp_workspace_bytes", "sgc_omp_workspace_bytes_for", "sgc_recover_omp",
-    "sgc_recover_omp_shared", "sgc_reproject",
+    "sgc_omp_static_workspace_bytes", "sgc_recover_omp_static", "sgc_recover_omp_shared", "sgc_reproject",
     "sgc_reproject_moment",
     "sgc_omp_recurrence_workspace_bytes", "sgc_recover_omp_recurrence",
     "sgc_apply", "sgc_outer_workspace_bytes", "sgc_outer_project", "sgc_outer_apply",
@@ -85,6 +85,10 @@ def lib():
         L.sgc_omp_workspace_bytes_for.argtypes = [i32, i32, ctypes.POINTER(sgc_matrix)]
         L.sgc_recover_omp.restype = i32
         L.sgc_recover_omp.argtypes = [vp, i32, ctypes.POINTER(sgc_matrix), i32, vp, vp, vp, sz, vp]
+        L.sgc_omp_static_workspace_bytes.restype = sz
+        L.sgc_omp_static_workspace_bytes.argtypes = []
+        L.sgc_recover_omp_static.restype = i32
+        L.sgc_recover_omp_static.argtypes = [vp, i32, ctypes.POINTER(sgc_matrix), i32, vp, vp, vp]
         L.sgc_reproject_moment.restype = i32
         L.sgc_reproject_moment.argtypes = [vp, vp, i64, i32, ctypes.POINTER(sgc_matrix), ctypes.c_double, i32, vp, vp]
         L.sgc_omp_recurrence_workspace_bytes.restype = sz
@@ -205,6 +209,17 @@ def sgc_recover_omp(y, N, A, k, sel, x, ws, stream=None):
 
 def sgc_omp_workspace_bytes_for(N, k, A):
     return int(lib().sgc_omp_workspace_bytes_for(N, k, ctypes.byref(A.c())))
+
+
+def sgc_omp_static_workspace_bytes():
+    return int(lib().sgc_omp_static_workspace_bytes())
+
+
+def sgc_recover_omp_static(y, N, A, k, sel, x, stream=None):
+    _expect(y, (torch.float32,), "y")
+    _expect(sel, (torch.int32,), "sel")
+    _expect(x, (torch.float32,), "x")
+    _check(lib().sgc_recover_omp_static(_ptr(y), N, ctypes.byref(A.c()), k, _ptr(sel), _ptr(x), _stream(stream)), "sgc_recover_omp_static")
 
 
 def sgc_omp_recurrence_workspace_bytes(N, d, r, k, head=None):

@@ -125,6 +125,21 @@ def test_omp_rejects_bad_arguments_and_sizes_workspace():
     assert call(AA=scr, nbytes=exact) == sgc.ERR_WORKSPACE         # sized without the planes
     assert call(ws=ctypes.c_void_p(0x1010)) == sgc.ERR_ALIGN
 
+    # the variant with the workspace in a static device array: same checks, and sizes beyond the array are refused
+    cap = L.sgc_omp_static_workspace_bytes()
+    assert cap == 32 << 20
+
+    def stat(y=FAKE, N=2, AA=A, k=32, sel=FAKE, x=FAKE):
+        return L.sgc_recover_omp_static(y, N, ctypes.byref(AA) if AA is not None else None, k, sel, x, None)
+
+    assert stat(y=None) == sgc.ERR_NULL and stat(sel=None) == sgc.ERR_NULL and stat(AA=None) == sgc.ERR_NULL
+    assert stat(AA=mat(d=4096, r=256, inv=None)) == sgc.ERR_NULL
+    assert stat(N=0) == sgc.ERR_SHAPE and stat(k=257) == sgc.ERR_SHAPE
+    assert stat(y=ODD) == sgc.ERR_ALIGN
+    big = mat(d=65536, r=2048)
+    assert L.sgc_omp_workspace_bytes_for(128, 256, ctypes.byref(big)) > cap
+    assert stat(N=128, AA=big, k=256) == sgc.ERR_WORKSPACE
+
     # the engine with App. B's recurrence: the same checks, a larger workspace, and the Gram table is required
     more = sgc.sgc_omp_recurrence_workspace_bytes(2, 4096, 256, 32)
     assert more >= need + 2 * 33 * 4096 * 4
