@@ -21,10 +21,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense float matrix peak
-# Vector-ALU issue peak in lane-instructions per second: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz (a wavefront's
-# plain float instruction occupies its SIMD for four cycles). The published 157.3 TFLOP/s vector figure is this
-# rate x 2 flop per FMA x 2 for the packed form, which this library does not use.
-VALU_PEAK_TLANE = 39.3
+# Vector-ALU issue peak in lane-instructions per second: 256 CUs x 128 lanes per clock x 2.4 GHz, i.e. the
+# published 157.3 TFLOP/s vector figure at 2 flop per FMA. The register-only probe of plain (non-packed)
+# v_fma_f32 (sgc_probe, reported under micro.probes in every default run) sustains 66 T/s on this machine,
+# 108 lanes per CU and nominal clock, so the figure is reachable without packed instructions.
+VALU_PEAK_TLANE = 78.6
 PROJECT_INSTR_PER_QUAD = 200.0  # vector instructions per four generated entries of A in project_kernel (50 per normal)
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, keyed by
 # workload name: (bytes, the summary under profiles/ that holds the run). Stored figures: they describe the

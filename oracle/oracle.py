@@ -181,6 +181,42 @@ def lstsq_support(y, At, sel):
     return x64
 
 
+def omp_pick(y, At, prefix, norm=None):
+    """One iteration of OMP's definition after the selections `prefix`: least squares on the prefix, residual,
+    normalised argmax over the unselected positions. Returns dict(lam, top2, res)."""
+    y = _c(y, np.float32)
+    At = _c(At, np.float32)
+    prefix = _c(prefix, np.int32)
+    d, r = At.shape
+    norm = _c(norm if norm is not None else colnorms(At), np.float64)
+    lam = ctypes.c_int32(-1)
+    top2 = np.empty(2, np.float64)
+    res = np.empty(r, np.float64)
+    rc = lib().oracle_omp_pick(_p(y, ctypes.c_float), _p(At, ctypes.c_float), d, r, _p(norm, ctypes.c_double), _p(prefix, ctypes.c_int32), prefix.size, ctypes.byref(lam), _p(top2, ctypes.c_double), _p(res, ctypes.c_double))
+    if rc:
+        raise ValueError("oracle_omp_pick rc=%d" % rc)
+    return dict(lam=int(lam.value), top2=top2, res=res)
+
+
+def philox_matrix_threads(seed, d, r, workers=8):
+    """philox_matrix for a large matrix: row ranges filled by several host threads (the generator is
+    counter-based, so the result is the same whatever the split)."""
+    from concurrent.futures import ThreadPoolExecutor
+    out = np.empty((d, r), np.float32)
+    edges = np.linspace(0, d, 4 * workers + 1).astype(np.int64)
+
+    def fill(i):
+        a, b = int(edges[i]), int(edges[i + 1])
+        if b > a:
+            rc = lib().oracle_philox_matrix(ctypes.c_uint64(seed), r, ctypes.c_int64(a), ctypes.c_int64(b - a), _p(out[a:b], ctypes.c_float))
+            if rc:
+                raise ValueError("oracle_philox_matrix rc=%d" % rc)
+
+    with ThreadPoolExecutor(workers) as ex:
+        list(ex.map(fill, range(4 * workers)))
+    return out
+
+
 def omp_shared(Ym, Yv, At, k, norm=None):
     """Shared-support recovery of C chunks: support and x from OMP on Ym[c], z = least-squares fit
     of Yv[c] on that support (Sec. 4.3, the remark after eq. 11). Returns sel, x, z, each [C, k]."""

@@ -544,6 +544,73 @@ int oracle_lstsq_support(const float *y, const float *At, int32_t d, int32_t r, 
     return rc;
 }
 
+/* One iteration of the definition of OMP (Sec. 4.3 eq. 9; selection rule of App. B) given the
+ * positions selected so far: x = argmin || y - A_prefix x ||_2 (oracle_lstsq_support), res = y - A_prefix x,
+ * and the next position = argmax over the unselected i of |<A_:i, res>| / ||A_:i||, lowest i on ties.
+ * This is what iteration n_prefix of oracle_omp computes when its earlier picks were `prefix`; it exists
+ * so that a single late pick of a long recovery (n_prefix in the hundreds) can be checked without solving
+ * every earlier least-squares problem again. norm[d]: column norms (oracle_colnorms).
+ * Outputs: *lam the position, top2[2] the best and second-best score (may be NULL), res_out[r] (may be NULL).
+ * returns 0, -1 bad argument, -3 a prefix position repeated or out of range, -4 Gram not positive definite */
+int oracle_omp_pick(const float *y, const float *At, int32_t d, int32_t r, const double *norm,
+                    const int32_t *prefix, int32_t n_prefix, int32_t *lam, double *top2, double *res_out)
+{
+    if (n_prefix < 0 || n_prefix >= d || n_prefix > r || !norm || !lam)
+        return -1;
+    unsigned char *taken = (unsigned char *)calloc((size_t)d, 1);
+    for (int32_t t = 0; t < n_prefix; ++t) {
+        if (prefix[t] < 0 || prefix[t] >= d || taken[prefix[t]]) {
+            free(taken);
+            return -3;
+        }
+        taken[prefix[t]] = 1;
+    }
+    double *xs = (double *)calloc((size_t)(n_prefix > 0 ? n_prefix : 1), sizeof(double));
+    int rc = oracle_lstsq_support(y, At, d, r, prefix, n_prefix, xs);
+    if (rc) {
+        free(taken);
+        free(xs);
+        return rc;
+    }
+    double *res = (double *)malloc(sizeof(double) * (size_t)r);
+    for (int32_t j = 0; j < r; ++j)
+        res[j] = (double)y[j];
+    for (int32_t t = 0; t < n_prefix; ++t) {
+        const float *at = At + (int64_t)prefix[t] * r;
+        for (int32_t j = 0; j < r; ++j)
+            res[j] -= xs[t] * (double)at[j];
+    }
+    int32_t best_i = -1;
+    double best = -1.0, second = -1.0;
+    for (int32_t i = 0; i < d; ++i) {
+        if (taken[i])
+            continue;
+        const float *a = At + (int64_t)i * r;
+        double corr = 0.0;
+        for (int32_t j = 0; j < r; ++j)
+            corr += (double)a[j] * res[j];
+        const double score = norm[i] > 0.0 ? fabs(corr) / norm[i] : 0.0;
+        if (score > best) {
+            second = best;
+            best = score;
+            best_i = i;
+        } else if (score > second) {
+            second = score;
+        }
+    }
+    *lam = best_i;
+    if (top2) {
+        top2[0] = best;
+        top2[1] = second;
+    }
+    if (res_out)
+        memcpy(res_out, res, sizeof(double) * (size_t)r);
+    free(taken);
+    free(xs);
+    free(res);
+    return 0;
+}
+
 /* y_m[r], y_v[r]: the two bias-corrected moments of one chunk. sel[k], x[k]: OMP_A(y_m);
  * z[k]: least-squares fit of y_v on the same support, aligned with sel. */
 int oracle_omp_shared(const float *y_m, const float *y_v, const float *At, int32_t d, int32_t r,

@@ -105,6 +105,24 @@ def gradients(w, step=1, chunks=None):
     return out
 
 
+def ulp_cluster_gradients(seed, C, d, k):
+    """Chunks [C, d] whose k-th largest magnitude sits inside a cluster of values one unit in the last place
+    apart: about 3k entries with magnitudes 1.5 + j ulp (j in a window of about 2k/3 values, so every
+    magnitude occurs several times: ties and one-ulp neighbours), random signs, plus about 2k/3 clearly
+    larger entries and small noise elsewhere. An input generator for top-k tests, nothing more."""
+    g = _rng(4242, seed, d, k)
+    out = (g.standard_normal((C, d)) * 0.01).astype(np.float32)
+    base = np.float32(1.5).view(np.uint32)
+    for c in range(C):
+        cluster = g.choice(d, size=min(d, 3 * k), replace=False)
+        bits = base + g.integers(0, max(2, 2 * k // 3), size=cluster.size).astype(np.uint32)
+        out[c, cluster] = bits.view(np.float32) * g.choice([-1.0, 1.0], size=cluster.size).astype(np.float32)
+        rest = np.setdiff1d(np.arange(d), cluster)
+        big = g.choice(rest, size=max(0, min(rest.size, k - k // 3)), replace=False)
+        out[c, big] = (10.0 + g.random(big.size)).astype(np.float32)
+    return out
+
+
 def gaussian_matrix(seed, d, r):
     """At [d, r] float32 with iid N(0, 1/r) entries (the stored-matrix mode; Sec. 4.3)."""
     g = _rng(1000003, seed)

@@ -110,3 +110,64 @@ def test_cfg4_full_size():
     C = w.C
     picks = [(0, 0), (C - 1, 63), (C, 10), (2 * C - 1, 63), (9000, 31), (C + 4321, 50)]
     run_and_check(w, 1, list(range(0, C, 997)), picks)
+
+
+@pytest.mark.timeout(600)
+def test_cfg5_full_size():
+    """Configuration 5 as specified: 128 chunks of 262144 bfloat16 gradients, r = 8192, k = 1024, generated
+    matrix, one step through the launch configuration bench.py times. The oracle's matrix (8 GiB) is
+    generated once on the host. Checked: top-k (bit-exact) and projection on sampled chunks, Adam on all
+    elements, every support a set of distinct valid positions, single picks replayed in the oracle from
+    the GPU's own prefix (first, early, middle, beyond the thousandth, last), the least-squares values of
+    one whole support against oracle.lstsq_support, and the weight update from the recovered vectors."""
+    w = synth.CFG5
+    C, d, r, k = w.C, w.d, w.r, w.k
+    say(w.name, "C", C, "d", d, "r", r, "k", k, ": host matrix")
+    At = orc.philox_matrix_threads(w.a_seed, d, r, workers=16)
+    norm = orc.colnorms(At)
+    A = sgc.Matrix(d, r, At=None, seed=w.a_seed)
+    A.inv_colnorm = torch.empty(d, dtype=torch.float32, device=DEV)
+    sgc.sgc_matrix_colnorms(A, A.inv_colnorm)
+    assert relerr(A.inv_colnorm.cpu().numpy(), 1.0 / norm) < 1e-6
+    buf = sgc.StepBuffers(C, d, r, k)
+    W0 = synth.weights(w)
+    W = dev(W0)
+    h = sgc.hyper()
+    say("  gradients")
+    g = synth.gradients(w, 1)
+    say("  GPU step")
+    sgc.step(dev(g.view(np.int16)), W, buf, A, 1, h)
+    torch.cuda.synchronize()
+    idx, val = buf.idx.cpu().numpy(), buf.val.cpu().numpy()
+    p, q = buf.p.cpu().numpy(), buf.q.cpu().numpy()
+    m, v = buf.m.cpu().numpy(), buf.v.cpu().numpy()
+    hat = buf.hat.cpu().numpy()
+    sel, x = buf.sel.cpu().numpy(), buf.x.cpu().numpy()
+    chunk_sample = [0, 41, 86, 127]
+    say("  top-k / projection on chunks", chunk_sample)
+    ridx, rval = orc.topk(g[chunk_sample], k)
+    assert np.array_equal(idx[chunk_sample], ridx)
+    assert np.array_equal(val[chunk_sample].view(np.uint32), rval.view(np.uint32))
+    rp, rq = orc.project(ridx, rval, At)
+    for o, c in enumerate(chunk_sample):
+        assert relerr(p[c], rp[o]) < TOL and relerr(q[c], rq[o]) < TOL
+    zero = np.zeros((C, r), np.float32)
+    rm, rv, rmh, rvh = orc.adam(p, q, zero, zero, 1)
+    assert relerr(m, rm) < 1e-6 and relerr(v, rv) < 1e-6
+    assert relerr(hat[:C], rmh) < 1e-6 and relerr(hat[C:], rvh) < 1e-6
+    assert sel.min() >= 0 and sel.max() < d
+    srt = np.sort(sel, axis=1)
+    assert (srt[:, 1:] != srt[:, :-1]).all()
+    for n, j in [(0, 0), (200, 3), (77, 150), (128, 511), (255, 1000), (19, 1023), (141, 1023)]:
+        say("  pick", j, "of right-hand side", n)
+        rep = orc.omp_pick(hat[n], At, sel[n, :j], norm=norm)
+        assert rep["lam"] == sel[n, j], "rhs %d pick %d: gpu %d oracle %d (scores %r)" % (n, j, sel[n, j], rep["lam"], rep["top2"])
+    for n in (5, 133):
+        say("  least squares on the whole support of right-hand side", n)
+        assert relerr(x[n], orc.lstsq_support(hat[n], At, sel[n])) < TOL
+    rW = orc.apply(W0, d, sel[:C], x[:C], sel[C:], x[C:])
+    Wn = W.cpu().numpy()
+    dW, rdW = (Wn - W0).reshape(C, d), (rW - W0).reshape(C, d)
+    for c in chunk_sample:
+        assert relerr(dW[c], rdW[c]) < TOL
+    assert np.array_equal(Wn[rW == W0], W0[rW == W0])

@@ -112,6 +112,23 @@ def test_topk_ties_zeros_and_quantised_values():
 
 
 @pytest.mark.parametrize("d,k,r", [
+    (64, 8, 8), (5000, 64, 64), (16384, 64, 64),      # the register-resident single-pass kernel
+    (32768, 64, 128), (65536, 100, 512),              # two and four pieces merged in a second pass
+    (65536, 256, 256), (70000, 100, 128),             # the single pass for long chunks, the general kernel
+])
+def test_topk_values_one_ulp_apart_around_the_kth_place(d, k, r):
+    """The k-th largest magnitude sits in a cluster of values one unit in the last place apart (with ties):
+    any comparison that drops the lowest mantissa bit, or compares rounded values, picks a different set."""
+    say("topk one-ulp cluster", d, k, r)
+    g = synth.ulp_cluster_gradients(2, 5, d, k)
+    A, At = make_matrix("stored", 13, d, r)
+    idx, val, p, q = run_topk_project(g, k, A)
+    ridx, rval = orc.topk(g, k)
+    assert np.array_equal(idx, ridx)
+    assert np.array_equal(val.view(np.uint32), rval.view(np.uint32))
+
+
+@pytest.mark.parametrize("d,k,r", [
     (16392, 1, 8),        # two pieces, the smallest possible scratch (r = 2 k would do: 8 >= 2)
     (32768, 64, 128),     # two pieces, r = S k exactly
     (32768, 64, 124),     # one candidate short of the scratch: the single-pass kernel

@@ -48,6 +48,22 @@ def test_topk_ties_lower_position_wins_and_sign_is_kept():
         assert np.array_equal(idx[c], pos) and np.array_equal(val[c], v)
 
 
+@pytest.mark.parametrize("d,k", [(64, 8), (5000, 64), (16384, 64), (70000, 100)])
+def test_topk_orders_values_one_ulp_apart_around_the_kth_place(d, k):
+    """Many entries one unit in the last place apart on both sides of the k-th largest magnitude (and
+    exact ties at it): the order must be that of the full bit pattern, down to the lowest mantissa bit."""
+    g = synth.ulp_cluster_gradients(1, 3, d, k)
+    idx, val = orc.topk(g, k)
+    for c in range(3):
+        pos, v = brute_topk(g[c], k)
+        assert np.array_equal(idx[c], pos)
+        assert np.array_equal(val[c].view(np.uint32), v.view(np.uint32))
+        # the threshold really sits among neighbours one ulp apart: kept and dropped magnitudes touch
+        kept = np.abs(g[c, pos]).min().view(np.uint32)
+        dropped = np.abs(np.delete(g[c], pos)).max().view(np.uint32)
+        assert kept >= dropped and int(kept) - int(dropped) <= 1
+
+
 def test_topk_bf16_matches_full_sort_on_widened_values():
     rng = np.random.default_rng(11)
     g32 = rng.standard_t(2.5, size=(4, 3000)).astype(np.float32)
@@ -320,6 +336,41 @@ def test_omp_forced_prefix_and_zero_input():
     sel, x = orc.omp_batch(np.stack([y, np.zeros(r, np.float32)]), At, k)
     assert np.array_equal(sel[0], full["sel"]) and np.array_equal(x[0], full["x"])
     assert sel[1].tolist() == list(range(k))
+
+
+def test_single_pick_after_a_given_prefix():
+    """oracle.omp_pick (one iteration of the definition after a given prefix) against numpy: a library least
+    squares on an ARBITRARY prefix (not one OMP would choose), the residual, and the argmax of the
+    normalised correlation over the unselected positions; and against oracle.omp's own picks."""
+    rng = np.random.default_rng(21)
+    d, r = 500, 80
+    At = synth.gaussian_matrix(8, d, r) * rng.uniform(0.2, 5.0, size=(d, 1)).astype(np.float32)  # unequal norms
+    A = At.astype(np.float64).T
+    nrm = np.linalg.norm(A, axis=0)
+    y = rng.standard_normal(r).astype(np.float32)
+    for n_prefix in (0, 1, 7, 40):
+        prefix = rng.choice(d, size=n_prefix, replace=False).astype(np.int32)
+        got = orc.omp_pick(y, At, prefix)
+        res = y.astype(np.float64)
+        if n_prefix:
+            sol, *_ = np.linalg.lstsq(A[:, prefix], y.astype(np.float64), rcond=None)
+            res = res - A[:, prefix] @ sol
+        score = np.abs(A.T @ res) / nrm
+        score[prefix] = -1
+        assert got["lam"] == int(np.argmax(score))
+        assert np.allclose(got["top2"], np.sort(score)[::-1][:2], rtol=1e-10)
+        assert np.allclose(got["res"], res, atol=1e-12)
+    full = orc.omp(y, At, 12)
+    for j in range(12):
+        assert orc.omp_pick(y, At, full["sel"][:j])["lam"] == full["sel"][j]
+    # exact ties go to the lowest unselected position; a repeated prefix position is refused
+    assert orc.omp_pick(np.zeros(r, np.float32), At, np.array([0, 2], np.int32))["lam"] == 1
+    with pytest.raises(ValueError):
+        orc.omp_pick(y, At, np.array([3, 3], np.int32))
+
+
+def test_philox_matrix_filled_by_threads_is_the_same_matrix():
+    assert np.array_equal(orc.philox_matrix_threads(77, 1000, 36, workers=3), orc.philox_matrix(77, 1000, 36))
 
 
 # ----------------------------------------------------------------------- full step
