@@ -65,12 +65,22 @@ def main():
     ap.add_argument("--event-steps", type=int, default=3,
                     help="steps of the second pass that records HIP events around every kernel launch (the roofline's "
                          "launch durations come from there)")
+    ap.add_argument("--events-only", action="store_true",
+                    help="profiling aid: every step of the run (warm-up included) is taken with HIP events around each "
+                         "launch, which also keeps the recovery on one stream with whole-batch launches, so that a "
+                         "rocprofv3 kernel trace of this command holds launches of one size per kernel; the timed pass, "
+                         "variants, micro-runs and the CPU baseline are skipped")
+    ap.add_argument("--probes-only", action="store_true", help="only the machine probes (sgc_probe), as one JSON line")
     ap.add_argument("--shared-support", action="store_true",
                     help="recover one support per chunk from mhat and fit vhat on it (sgc_recover_omp_shared) "
                          "instead of the two independent recoveries of Alg. 2")
     ap.add_argument("--materialize", action="store_true",
                     help="a generated matrix is written out once with sgc_matrix_fill (outside the timed region) "
                          "and handed over as a stored one: what a caller with HBM to spare would do")
+    ap.add_argument("--whole-matrix", action="store_true",
+                    help="a generated matrix of more than 64 MiB is written out once per call into the recovery's "
+                         "workspace (SGC_MATRIX_FLAG_MATERIALIZE; needs d <= N k) instead of being regenerated inside "
+                         "the contraction")
     ap.add_argument("--gram", action="store_true",
                     help="build the optional table of column inner products (sgc_matrix_gram, 8 d^2 bytes, once, "
                          "outside the timed region) and let the recovery use it")
@@ -112,6 +122,11 @@ def main():
         return 2
     sgc.lib()  # fails loudly if the HIP library is not built
     dev = "cuda:0"
+    if args.probes_only:
+        print(json.dumps({"probes": probe_runs(dev)}))
+        return 0
+    if args.events_only:
+        args.no_variants = args.no_cpu_baseline = True
     if args.cesgc:
         return main_cesgc(args, dev)
     if args.corr_depth_sweep:
@@ -129,7 +144,7 @@ def main():
     if not args.no_variants:
         # labelled micro-runs of the HBM-bound kernels at a size where launch latency does not hide them
         out["micro"] = micro_runs(dev)
-        plain = not (args.shared_support or args.screen_bf16 or args.gram or args.recurrence or args.materialize or args.chunks)
+        plain = not (args.shared_support or args.screen_bf16 or args.gram or args.recurrence or args.materialize or args.chunks or args.whole_matrix)
         if plain and args.workload != 2:
             # secondary entry: configuration 2 (64 chunks of 65536, r 2048, k 256, stored matrix streamed from HBM
             # in every iteration), a few steps, same code path
@@ -170,6 +185,8 @@ def run_workload(args, w, dev, K, Wm, variants, baseline):
     sgc.sgc_matrix_colnorms(A, A.inv_colnorm)
     if args.screen_bf16:
         A.flags = sgc.MATRIX_FLAG_SCREEN_BF16
+    if args.whole_matrix:
+        A.flags |= sgc.MATRIX_FLAG_MATERIALIZE
     gram_ms = None
     head = args.recurrence_head
     if args.recurrence and head < 0:
@@ -205,19 +222,21 @@ def run_workload(args, w, dev, K, Wm, variants, baseline):
         for t in range(1, n + 1):
             sgc.step(grads[(t - 1) % ndraw], Wt, buf, A, t, h, shared_support=args.shared_support if shared is None else shared)
 
+    if args.events_only:
+        sgc.sgc_profile_enable(True)
     run(Wm)
     torch.cuda.synchronize()
     reset()
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run(K)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / K
-    value = C * d / (ms_per_step * 1e-3)
+    if not args.events_only:
+        t0 = time.perf_counter()
+        run(K)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ms_per_step = (t1 - t0) * 1e3 / K
 
     # ---- a second pass with HIP events around every kernel launch (on the stream the kernels run on) ----
-    Ke = max(1, min(K, args.event_steps))
+    Ke = K if args.events_only else max(1, min(K, args.event_steps))
     reset()
     torch.cuda.synchronize()
     sgc.sgc_profile_enable(True)
@@ -227,6 +246,9 @@ def run_workload(args, w, dev, K, Wm, variants, baseline):
     t3 = time.perf_counter()
     prof = sgc.sgc_profile_read()
     sgc.sgc_profile_enable(False)
+    if args.events_only:
+        ms_per_step = (t3 - t2) * 1e3 / Ke
+    value = C * d / (ms_per_step * 1e-3)
     corr_ms, corr_n = prof["omp_corr"]
     fill_ms, _ = prof["omp_matrix_fill"]
     # one launch covers all d positions (stored / in-kernel generated A) or one panel of them
@@ -322,7 +344,8 @@ def run_workload(args, w, dev, K, Wm, variants, baseline):
         "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "chunks": C, "d": d, "r": r, "k": k, "grad": w.grad,
-                   "matrix": "philox, materialised by the caller" if (args.materialize and w.matrix != "stored") else w.matrix,
+                   "matrix": "philox, materialised by the caller" if (args.materialize and w.matrix != "stored") else
+                             ("philox, written out once per call into the workspace" if args.whole_matrix else w.matrix),
                    "rhs_per_omp_call": nrhs,
                    "gradient_draws": "%d distinct steps resident in HBM, cycled over the %d steps; moments persist" % (ndraw, K),
                    "recovery": "shared_support" if args.shared_support else "two_supports",
@@ -332,22 +355,34 @@ def run_workload(args, w, dev, K, Wm, variants, baseline):
                    else ("bf16 split (3 products), float accumulate" if args.screen_bf16 else "float")},
         "roofline": roofline,
         "ms_per_step_with_events": round((t3 - t2) * 1e3 / Ke, 3),
+        "timing": "events pass only (one stream, HIP events around every launch)" if args.events_only else "eager steps, no events",
         "gram_build_ms": None if gram_ms is None else round(gram_ms, 2),
         "kernels": kernels,
     }
 
-    # ---- the shared-support recovery (first widening), three steps (context, not the headline) ----
-    if variants and not (args.shared_support or args.screen_bf16 or args.gram or args.recurrence):
-        nv = min(3, nsteps)
-        reset()
-        run(1, True)
-        reset()
-        torch.cuda.synchronize()
-        tv = time.perf_counter()
-        run(nv, True)
-        torch.cuda.synchronize()
-        ms = (time.perf_counter() - tv) * 1e3 / nv
-        out["variants"] = {"shared_support": {"ms_per_step": round(ms, 3), "value": round(C * d / (ms * 1e-3), 1), "steps": nv}}
+    # ---- variants, a few steps each (context, not the headline): the shared-support recovery (first
+    #      widening), and for a generated matrix of more than 64 MiB the option that writes it out once per
+    #      call into the workspace instead of regenerating it inside the contraction ----
+    if variants and not (args.shared_support or args.screen_bf16 or args.gram or args.recurrence or args.whole_matrix):
+        nv = 1 if ms_per_step > 2000 else min(3, nsteps)
+
+        def timed(shared):
+            reset()
+            if ms_per_step <= 2000:
+                run(1, shared)
+                reset()
+            torch.cuda.synchronize()
+            tv = time.perf_counter()
+            run(nv, shared)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - tv) * 1e3 / nv
+            return {"ms_per_step": round(ms, 3), "value": round(C * d / (ms * 1e-3), 1), "steps": nv}
+
+        out["variants"] = {"shared_support": timed(True)}
+        if A.mode == sgc.MATRIX_PHILOX and 4.0 * d * r > 64 * 2 ** 20 and d <= 2 * C * k:
+            A.flags = sgc.MATRIX_FLAG_MATERIALIZE
+            out["variants"]["whole_matrix_in_workspace"] = timed(False)
+            A.flags = 0
 
     del grads, buf, Wt, W0
     A.gram = None

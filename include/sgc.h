@@ -65,6 +65,16 @@ enum { SGC_GRAD_F32 = 0, SGC_GRAD_BF16 = 1 };
  * Off by default: the default contraction is float throughout.
  */
 enum { SGC_MATRIX_FLAG_SCREEN_BF16 = 1 };
+/*
+ * Option bit of sgc_matrix.flags for a generated (SGC_MATRIX_PHILOX) matrix, read by sgc_recover_omp* only.
+ * By default a generated matrix of more than 64 MiB is never written to memory: its entries are regenerated
+ * inside the contraction kernel and only the selected columns are kept. With this bit the call may instead
+ * write the whole matrix once into its workspace (where the copies of the selected columns would be, so it
+ * applies when d <= N k) and read it from there in every iteration: faster, at the price of d r 4 bytes of
+ * HBM holding A for the duration of the call. Matrices of at most 64 MiB always go through a scratch panel
+ * of that size, which stays in the memory-side cache.
+ */
+enum { SGC_MATRIX_FLAG_MATERIALIZE = 2 };
 
 /* how the measurement matrix is provided */
 enum {
@@ -89,7 +99,7 @@ typedef struct sgc_matrix {
     int32_t mode; /* SGC_MATRIX_STORED | SGC_MATRIX_PHILOX */
     int32_t d;    /* columns of A = chunk length */
     int32_t r;    /* rows of A = measurements per chunk; multiple of 4 */
-    int32_t flags; /* 0, or SGC_MATRIX_FLAG_SCREEN_BF16 */
+    int32_t flags; /* 0, or SGC_MATRIX_FLAG_* bits */
     uint64_t seed;            /* PHILOX mode */
     const float *At;          /* device [d][r], STORED mode; 16-byte aligned */
     const float *inv_colnorm; /* device [d]; may be NULL for sgc_sparsify_project */
@@ -169,7 +179,7 @@ sgc_status sgc_adam_compressed(const float *p, const float *q, float *m, float *
                                const sgc_hyper *h /* host */, void *stream);
 
 /* bytes of workspace sgc_recover_omp / sgc_recover_omp_shared need for N right-hand sides; 0 on invalid
- * sizes. sgc_omp_workspace_bytes covers any matrix without option flags (stored or generated);
+ * sizes. sgc_omp_workspace_bytes covers any matrix (stored or generated) without the screening flag;
  * sgc_omp_workspace_bytes_for gives the exact need of one matrix (A->mode, A->d, A->r, A->flags are read): a
  * stored matrix is read in place and needs neither the copies of the selected columns nor a panel of
  * generated rows, and only a matrix with SGC_MATRIX_FLAG_SCREEN_BF16 needs the bfloat16 planes (4 d r bytes
@@ -186,7 +196,7 @@ size_t sgc_omp_workspace_bytes_for(int32_t N, int32_t k, const sgc_matrix *A /* 
  *   sel  out [N][k] selected positions in selection order
  *   x    out [N][k] least-squares values aligned with sel
  *   ws   workspace of at least sgc_omp_workspace_bytes_for(N, k, A) bytes (sgc_omp_workspace_bytes(N, d, r, k)
- *        is enough for any A without option flags), 256-byte aligned; contents are scratch
+ *        is enough for any A without the screening flag), 256-byte aligned; contents are scratch
  * All N correlations of one iteration are one dense contraction At * R on the float matrix
  * cores; the near-maximal candidates are then re-scored in double, and the least-squares
  * update (inverse-Cholesky form of App. B) and the residual are computed in double.
@@ -378,6 +388,8 @@ sgc_status sgc_profile_read(sgc_profile *out /* host */);
  *   SGC_PROBE_VALU  blocks x 256 threads, each `iters` x 64 dependent-chain v_fma_f32 (16 chains, plain
  *                   non-packed form, registers only): lane-instructions = blocks * 256 * iters * 64
  *   SGC_PROBE_MFMA  blocks x 4 wavefronts, each `iters` x 16 v_mfma_f32_32x32x2f32 (4096 flop each)
+ *   SGC_PROBE_MFMA_VALU4, _VALU8  the MFMA probe with 4 (8) independent v_fma_f32 behind every MFMA: whether
+ *                   vector-ALU work rides in the shadow of float matrix instructions or adds to their time
  *   SGC_PROBE_READ  reads `bytes` of a with non-temporal 16-byte loads
  *   SGC_PROBE_RW44  reads four arrays of bytes/8 from a and writes four of bytes/8 to b (the Adam kernel's
  *                   traffic pattern: `bytes` moved in total); a and b must each hold bytes/2
@@ -385,7 +397,8 @@ sgc_status sgc_profile_read(sgc_profile *out /* host */);
  * a (may be NULL for VALU / MFMA) and b (at least 4 bytes) are device pointers, 16-byte aligned; a
  * multiple of 128 bytes keeps every access whole. Errors: NULL, SHAPE, DTYPE (unknown kind), ALIGN, DEVICE.
  */
-enum { SGC_PROBE_VALU = 0, SGC_PROBE_MFMA = 1, SGC_PROBE_READ = 2, SGC_PROBE_RW44 = 3, SGC_PROBE_COPY = 4 };
+enum { SGC_PROBE_VALU = 0, SGC_PROBE_MFMA = 1, SGC_PROBE_READ = 2, SGC_PROBE_RW44 = 3, SGC_PROBE_COPY = 4,
+       SGC_PROBE_MFMA_VALU4 = 5, SGC_PROBE_MFMA_VALU8 = 6 };
 sgc_status sgc_probe(int32_t kind, const void *a, void *b, int64_t bytes, int32_t blocks, int32_t iters,
                      void *stream);
 

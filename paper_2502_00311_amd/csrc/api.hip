@@ -243,7 +243,7 @@ size_t sgc_omp_recurrence_workspace_bytes(int32_t N, int32_t d, int32_t r, int32
 {
     if (!omp_sizes_ok(N, d, r, k) || d % 4 != 0 || head < 1 || head > k)
         return 0;
-    return carve_recurrence(nullptr, N, d, r, k, head, WS_NEED_GENERATED | WS_NEED_SCREEN).bytes;
+    return carve_recurrence(nullptr, N, d, r, k, head, WS_NEED_GENERATED | WS_NEED_SCREEN | WS_NEED_WHOLE_MATRIX).bytes;
 }
 
 sgc_status sgc_recover_omp_recurrence(const float *y, int32_t N, const sgc_matrix *A, int32_t k, int32_t head,
@@ -260,7 +260,7 @@ sgc_status sgc_recover_omp_recurrence(const float *y, int32_t N, const sgc_matri
         return SGC_ERR_SHAPE;
     if (!aligned16(y) || !aligned16(A->inv_colnorm) || !aligned16(A->gram) || ((uintptr_t)ws & 255u))
         return SGC_ERR_ALIGN;
-    const OmpWorkspace w = carve_recurrence(ws, N, A->d, A->r, k, head, WS_NEED_GENERATED | WS_NEED_SCREEN);
+    const OmpWorkspace w = carve_recurrence(ws, N, A->d, A->r, k, head, WS_NEED_GENERATED | WS_NEED_SCREEN | WS_NEED_WHOLE_MATRIX);
     // a generated matrix must fit the workspace's panel as a whole: the selection reads its columns from there
     if (A->mode == SGC_MATRIX_PHILOX && w.panel_rows < A->d)
         return SGC_ERR_SHAPE;

@@ -53,9 +53,10 @@ OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_
     w.partial = (uint64_t *)take(sizeof(uint64_t) * (size_t)N * w.tiles_m * 2);
     w.bitmap = (uint32_t *)take(sizeof(uint32_t) * (size_t)N * w.words);
     // Rows of a generated matrix, in whole tiles. A matrix of at most 64 MiB gets a panel of its own (it
-    // then stays in the 256 MiB memory-side cache). A larger one is written out whole where the column
-    // copies would be, if it is no larger than they are (d <= N k; the copies are not needed once the
-    // rows are resident), else it goes through a 64 MiB panel that is refilled in every iteration.
+    // then stays in the 256 MiB memory-side cache). A larger one is regenerated inside the contraction, or
+    // goes through a 64 MiB panel that is refilled in every iteration; only if the matrix asks for it
+    // (SGC_MATRIX_FLAG_MATERIALIZE) is it written out whole where the column copies would be, when it is
+    // no larger than they are (d <= N k; the copies are not needed once the rows are resident).
     int64_t small_rows = ((int64_t)64 << 20) / ((int64_t)r * 4);
     small_rows = small_rows / 256 * 256;
     if (small_rows < 256)
@@ -64,7 +65,7 @@ OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_
         const int64_t dpad = ((int64_t)d + 255) / 256 * 256;
         if (small_rows > dpad)
             small_rows = dpad;
-        if (generated && dpad > small_rows && dpad <= (int64_t)N * k) {
+        if (generated && (need & WS_NEED_WHOLE_MATRIX) && dpad > small_rows && dpad <= (int64_t)N * k) {
             w.panel_rows = (int32_t)dpad;
             w.panel = w.cols;
         } else {
@@ -846,14 +847,15 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
                       const OmpWorkspace &ws, hipStream_t s, const float *y_fit, float *z, bool recurrence,
                       bool one_stream)
 {
-    // A generated matrix is written out once per call when the workspace has room for all of it. One
-    // that does not fit is regenerated inside the contraction when few right-hand-side tiles share it;
-    // with many tiles (each would regenerate all of A) it is produced panel by panel into a cache-sized
-    // scratch in every iteration, and consumed from there.
+    // A generated matrix is written out once per call when the workspace holds a panel for all of it (at
+    // most 64 MiB, or the whole-matrix option). Otherwise it is regenerated inside the contraction when few
+    // right-hand-side tiles share it (fewer than 1024 right-hand sides: every tile of 256 regenerates all
+    // of A); with many tiles it is produced panel by panel into a cache-sized scratch in every iteration,
+    // and consumed from there.
     // Stored rows in full tiles take the pipelined kernel (256-row tiles), everything else the
     // general one (128-row tiles).
     OmpPlan pl{};
-    pl.panels = A.generated && (ws.panel_rows >= A.d || (N + CORR_BN - 1) / CORR_BN >= 4);
+    pl.panels = A.generated && (ws.panel_rows >= A.d || (N + CORR_BN - 1) / CORR_BN >= 8);
     pl.pipelined = (!A.generated || pl.panels) && corr_pipelined_ok(A, N, ws.panel_rows);
     // the bfloat16 screening contraction needs resident rows; a matrix regenerated inside the
     // contraction keeps the float kernel (its time is the generator's anyway)

@@ -814,6 +814,15 @@ static hipError_t corr_dispatch(const MatrixView &A, int32_t rows, const float *
     // that only half-width ones give every CU the two workgroups it can hold
     if (N <= 64 || (int64_t)corr_tiles_m(rows) * ((N + CORR_BN - 1) / CORR_BN) <= 256)
         return corr_launch<GENERATED, CORR_BM, 64, 32, 2, 2, 2>(A, rows, R, N, ws, tiles_m, s);
+    // a matrix generated in the kernel: every tile of right-hand sides regenerates its 128 x r slice of A, so
+    // the generator's vector-ALU time per flop falls with the tile's width: 256 right-hand sides per
+    // workgroup halve it against the 128-wide tile. Float MFMAs and vector-ALU instructions of a SIMD do not
+    // overlap on this chip (sgc_probe: their times add exactly), so the generator's time comes on top of the
+    // matrix-core time whatever the schedule; sixteen wavefronts of 32 x 64 outputs (four per SIMD) hide
+    // everything else - LDS reads, barriers, the loads of R - behind one another: measured at d = 262144,
+    // r = 8192, N = 256: 9.9 ms per launch = 111 TFLOP/s, against 10.3 ms with eight wavefronts and 11.5 ms with four
+    if (GENERATED && N > CORR_BN && (int64_t)corr_tiles_m(rows) * ((N + 255) / 256) >= 256)
+        return corr_launch<GENERATED, CORR_BM, 256, 32, 4, 4, 1>(A, rows, R, N, ws, tiles_m, s);
     return corr_launch<GENERATED, CORR_BM, CORR_BN, 32, 2, 2, 2>(A, rows, R, N, ws, tiles_m, s);
 }
 

@@ -3,6 +3,7 @@
 // published peak can be read next to the rate measured on the same machine. The caller times them.
 //   SGC_PROBE_VALU   register-only chains of plain (non-packed) v_fma_f32: vector-ALU issue rate
 //   SGC_PROBE_MFMA   register-only v_mfma_f32_32x32x2f32: float matrix-core rate
+//   SGC_PROBE_MFMA_VALU4 / 8   the MFMA loop with 4 / 8 independent v_fma_f32 behind every MFMA
 //   SGC_PROBE_READ   streaming read with non-temporal 16-byte loads
 //   SGC_PROBE_RW44   four arrays read and four written, in the loop structure of the Adam kernel
 //   SGC_PROBE_COPY   one array read, one written
@@ -52,6 +53,50 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(float *out, int32_t ite
     float s = 0.f;
     for (int v = 0; v < 16; ++v)
         s += a0[v] + a1[v] + a2[v] + a3[v];
+    if (s == 123.456f)
+        out[0] = s;
+}
+
+// per iteration 16 MFMAs and, between them, VALU_PER_MFMA independent v_fma_f32 each: does vector-ALU work ride in
+// the shadow of the float matrix instructions of the same wavefront / SIMD, or does it add to their time?
+template <int VALU_PER_MFMA>
+__global__ __launch_bounds__(256) void probe_mix_kernel(float *out, int32_t iters)
+{
+    typedef float floatx16 __attribute__((ext_vector_type(16)));
+    floatx16 a0 = {0}, a1 = {0}, a2 = {0}, a3 = {0};
+    float acc[PROBE_CHAINS];
+    const float x = threadIdx.x * 1e-3f, y = blockIdx.x * 1e-3f;
+    const float fx = 1.0f + 1e-7f * (float)threadIdx.x, fy = 1e-9f * (float)blockIdx.x;
+#pragma unroll
+    for (int c = 0; c < PROBE_CHAINS; ++c)
+        acc[c] = (float)c;
+    for (int32_t i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            a0 = __builtin_amdgcn_mfma_f32_32x32x2f32(x, y, a0, 0, 0, 0);
+#pragma unroll
+            for (int c = 0; c < VALU_PER_MFMA; ++c)
+                asm volatile("v_fma_f32 %0, %1, %0, %2" : "+v"(acc[(4 * u * VALU_PER_MFMA + c) % PROBE_CHAINS]) : "v"(fx), "v"(fy));
+            a1 = __builtin_amdgcn_mfma_f32_32x32x2f32(y, x, a1, 0, 0, 0);
+#pragma unroll
+            for (int c = 0; c < VALU_PER_MFMA; ++c)
+                asm volatile("v_fma_f32 %0, %1, %0, %2" : "+v"(acc[((4 * u + 1) * VALU_PER_MFMA + c) % PROBE_CHAINS]) : "v"(fx), "v"(fy));
+            a2 = __builtin_amdgcn_mfma_f32_32x32x2f32(x, x, a2, 0, 0, 0);
+#pragma unroll
+            for (int c = 0; c < VALU_PER_MFMA; ++c)
+                asm volatile("v_fma_f32 %0, %1, %0, %2" : "+v"(acc[((4 * u + 2) * VALU_PER_MFMA + c) % PROBE_CHAINS]) : "v"(fx), "v"(fy));
+            a3 = __builtin_amdgcn_mfma_f32_32x32x2f32(y, y, a3, 0, 0, 0);
+#pragma unroll
+            for (int c = 0; c < VALU_PER_MFMA; ++c)
+                asm volatile("v_fma_f32 %0, %1, %0, %2" : "+v"(acc[((4 * u + 3) * VALU_PER_MFMA + c) % PROBE_CHAINS]) : "v"(fx), "v"(fy));
+        }
+    }
+    float s = 0.f;
+    for (int v = 0; v < 16; ++v)
+        s += a0[v] + a1[v] + a2[v] + a3[v];
+#pragma unroll
+    for (int c = 0; c < PROBE_CHAINS; ++c)
+        s += acc[c];
     if (s == 123.456f)
         out[0] = s;
 }
@@ -125,6 +170,12 @@ extern "C" sgc_status sgc_probe(int32_t kind, const void *a, void *b, int64_t by
         break;
     case SGC_PROBE_MFMA:
         probe_mfma_kernel<<<dim3((unsigned)blocks), 256, 0, s>>>((float *)b, iters);
+        break;
+    case SGC_PROBE_MFMA_VALU4:
+        probe_mix_kernel<4><<<dim3((unsigned)blocks), 256, 0, s>>>((float *)b, iters);
+        break;
+    case SGC_PROBE_MFMA_VALU8:
+        probe_mix_kernel<8><<<dim3((unsigned)blocks), 256, 0, s>>>((float *)b, iters);
         break;
     case SGC_PROBE_READ:
         if (!a)

@@ -64,10 +64,11 @@ struct OmpWorkspace {
 };
 // `need`: which optional regions the matrix calls for. A stored matrix is read in place (no column copies, no
 // panel); the bfloat16 planes exist only for a matrix that asks for the screening contraction.
-enum : uint32_t { WS_NEED_GENERATED = 1u, WS_NEED_SCREEN = 2u };
+enum : uint32_t { WS_NEED_GENERATED = 1u, WS_NEED_SCREEN = 2u, WS_NEED_WHOLE_MATRIX = 4u };
 inline uint32_t workspace_need(int32_t mode, int32_t flags)
 {
-    return (mode == SGC_MATRIX_PHILOX ? WS_NEED_GENERATED : 0u) | ((flags & SGC_MATRIX_FLAG_SCREEN_BF16) ? WS_NEED_SCREEN : 0u);
+    return (mode == SGC_MATRIX_PHILOX ? WS_NEED_GENERATED : 0u) | ((flags & SGC_MATRIX_FLAG_SCREEN_BF16) ? WS_NEED_SCREEN : 0u) |
+           ((flags & SGC_MATRIX_FLAG_MATERIALIZE) ? WS_NEED_WHOLE_MATRIX : 0u);
 }
 OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_t k, uint32_t need);
 // the same workspace followed by the three arrays of the recurrence; `bytes` covers both

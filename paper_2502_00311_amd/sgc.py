@@ -17,6 +17,7 @@ ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_ALIGN, ERR_WORKSPACE, ERR_STEP, ERR_DEVICE =
 GRAD_F32, GRAD_BF16 = 0, 1
 MATRIX_STORED, MATRIX_PHILOX = 0, 1
 MATRIX_FLAG_SCREEN_BF16 = 1
+MATRIX_FLAG_MATERIALIZE = 2
 
 EXPORTS = [
     "sgc_status_string", "sgc_matrix_fill", "sgc_matrix_colnorms", "sgc_matrix_gram", "sgc_sparsify_project",
@@ -28,7 +29,7 @@ EXPORTS = [
     "sgc_outer_refresh_workspace_bytes", "sgc_outer_refresh",
     "sgc_profile_enable", "sgc_profile_read", "sgc_probe",
 ]
-PROBE_VALU, PROBE_MFMA, PROBE_READ, PROBE_RW44, PROBE_COPY = 0, 1, 2, 3, 4
+PROBE_VALU, PROBE_MFMA, PROBE_READ, PROBE_RW44, PROBE_COPY, PROBE_MFMA_VALU4, PROBE_MFMA_VALU8 = 0, 1, 2, 3, 4, 5, 6
 PROFILE_CLASSES = ["topk", "project", "adam", "omp_corr", "omp_select_update", "apply", "other", "omp_matrix_fill",
                    "outer_project", "outer_apply", "outer_refresh"]
 
@@ -300,7 +301,7 @@ def sgc_profile_read():
 class StepBuffers:
     """Device buffers of one SGC step on C chunks (allocation only; no arithmetic)."""
 
-    def __init__(self, C, d, r, k, device="cuda", recurrence=False, screen=False):
+    def __init__(self, C, d, r, k, device="cuda", recurrence=False, screen=False, flags=0):
         f32, i32 = torch.float32, torch.int32
         self.C, self.d, self.r, self.k = C, d, r, k
         # recurrence: False, True (all k iterations) or the number of iterations the recurrence serves; the
@@ -318,9 +319,9 @@ class StepBuffers:
         # screen: the matrix will carry MATRIX_FLAG_SCREEN_BF16, whose bfloat16 planes take 4 d r bytes more
         if self.recurrence:
             nbytes = sgc_omp_recurrence_workspace_bytes(2 * C, d, r, k, self.recurrence)
-        elif screen:
+        elif screen or flags:
             probe = Matrix(d, r, seed=0)
-            probe.flags = MATRIX_FLAG_SCREEN_BF16
+            probe.flags = flags | (MATRIX_FLAG_SCREEN_BF16 if screen else 0)
             nbytes = sgc_omp_workspace_bytes_for(2 * C, k, probe)
         else:
             nbytes = sgc_omp_workspace_bytes(2 * C, d, r, k)

@@ -113,9 +113,11 @@ def test_cfg4_full_size():
 
 
 @pytest.mark.timeout(600)
-def test_cfg5_full_size():
+@pytest.mark.parametrize("flags", [0, sgc.MATRIX_FLAG_MATERIALIZE], ids=["never_materialised", "whole_matrix_in_workspace"])
+def test_cfg5_full_size(flags):
     """Configuration 5 as specified: 128 chunks of 262144 bfloat16 gradients, r = 8192, k = 1024, generated
-    matrix, one step through the launch configuration bench.py times. The oracle's matrix (8 GiB) is
+    matrix, one step through the launch configurations bench.py times: the matrix regenerated inside the
+    contraction (never in memory, the default), and written out once per call into the workspace (an option). The oracle's matrix (8 GiB) is
     generated once on the host. Checked: top-k (bit-exact) and projection on sampled chunks, Adam on all
     elements, every support a set of distinct valid positions, single picks replayed in the oracle from
     the GPU's own prefix (first, early, middle, beyond the thousandth, last), the least-squares values of
@@ -126,10 +128,11 @@ def test_cfg5_full_size():
     At = orc.philox_matrix_threads(w.a_seed, d, r, workers=16)
     norm = orc.colnorms(At)
     A = sgc.Matrix(d, r, At=None, seed=w.a_seed)
+    A.flags = flags
     A.inv_colnorm = torch.empty(d, dtype=torch.float32, device=DEV)
     sgc.sgc_matrix_colnorms(A, A.inv_colnorm)
     assert relerr(A.inv_colnorm.cpu().numpy(), 1.0 / norm) < 1e-6
-    buf = sgc.StepBuffers(C, d, r, k)
+    buf = sgc.StepBuffers(C, d, r, k, flags=flags)
     W0 = synth.weights(w)
     W = dev(W0)
     h = sgc.hyper()

@@ -312,20 +312,24 @@ def test_omp_with_very_few_measurements(N, d, r, k, mode):
     assert rowwise_relerr(x, rx) < TOL
 
 
-@pytest.mark.parametrize("N,d,r,k", [
-    (600, 3000, 64, 6),      # the generated matrix is written out once (it fits the cache-sized panel)
-    (520, 2500, 8192, 3),    # long columns, 82 MB: two panels refilled in every iteration, the second one ragged
-    (400, 20480, 1024, 52),  # 80 MB but no larger than the column copies (d <= N k): written out whole in their place
+@pytest.mark.parametrize("N,d,r,k,flags", [
+    (600, 3000, 64, 6, 0),       # the generated matrix is written out once (it fits the cache-sized panel)
+    (1030, 2500, 8192, 3, 0),    # long columns, 82 MB, many right-hand sides: two panels refilled in every iteration, the second one ragged
+    (520, 2500, 8192, 3, 0),     # the same matrix with fewer right-hand sides: regenerated inside the contraction (128-wide tiles)
+    (300, 16640, 1024, 4, 0),    # 68 MB, regenerated inside the contraction in tiles of 256 right-hand sides, the second one ragged
+    (400, 20480, 1024, 52, 0),   # 80 MB, the same kernel with the column copies of 52 iterations
+    (400, 20480, 1024, 52, sgc.MATRIX_FLAG_MATERIALIZE),  # no larger than the column copies (d <= N k): written out whole in their place
 ])
-def test_omp_generated_matrix_with_many_right_hand_sides(N, d, r, k):
+def test_omp_generated_matrix_with_many_right_hand_sides(N, d, r, k, flags):
     say("omp panels", N, d, r, k)
     rng = np.random.default_rng(N + d)
     A, At = make_matrix("philox", 33, d, r)
+    A.flags = flags
     Y = rng.standard_normal((N, r)).astype(np.float32)
     Y[7] = 0.0
     sel, x = run_omp(Y, A, k)
     norm = orc.colnorms(At)
-    for n in [0, 1, 7, 127, 128, 300, N - 2, N - 1]:   # the oracle checks a sample of the right-hand sides
+    for n in [0, 1, 7, 127, 128, 255, 256, N - 2, N - 1]:   # the oracle checks a sample of the right-hand sides
         ref = orc.omp(Y[n], At, k, norm=norm)
         assert np.array_equal(sel[n], ref["sel"]), n
         assert relerr(x[n], ref["x"]) < TOL
