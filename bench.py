@@ -417,11 +417,17 @@ def probe_runs(dev):
             t = min(t, a.elapsed_time(b))
         return t
 
-    iters, blocks = 20000, 2048
+    iters, blocks = 5000, 8192          # 32 workgroups per CU: the rate no longer grows with the grid
     ms = best(sgc.PROBE_VALU, blocks, iters, 0)
     res["valu_fma_T_lane_instr_per_s"] = round(blocks * 256.0 * iters * 64 / (ms * 1e-3) / 1e12, 2)
     ms = best(sgc.PROBE_MFMA, 1024, iters, 0)
     res["mfma_f32_TFLOPs"] = round(1024 * 4.0 * iters * 16 * 4096 / (ms * 1e-3) / 1e12, 1)
+    # 16 MFMAs + 64 v_fma per iteration against the two alone: if vector-ALU work rode in the shadow of the float
+    # MFMAs the mix would take the MFMA time; on this chip it takes the sum
+    t_m = ms
+    t_v = best(sgc.PROBE_VALU, 1024, iters, 0)
+    t_mix = best(sgc.PROBE_MFMA_VALU4, 1024, iters, 0)
+    res["mfma_plus_valu_ms"] = {"mfma_alone": round(t_m, 3), "valu_alone": round(t_v, 3), "both_in_one_loop": round(t_mix, 3)}
     ms = best(sgc.PROBE_READ, 4096, 0, nbytes // 2)
     res["read_GBps"] = round(nbytes / 2 / (ms * 1e-3) / 1e9, 1)
     ms = best(sgc.PROBE_RW44, 4096, 0, nbytes)

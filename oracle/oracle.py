@@ -42,11 +42,27 @@ def _p(a, ct):
     return a.ctypes.data_as(ctypes.POINTER(ct)) if a is not None else None
 
 
+def build_sanitized():
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer (any finding aborts), as a separate
+    library; a process that wants it sets SGC_ORACLE_LIB to its path and preloads the sanitizer runtime."""
+    out = os.path.join(_HERE, "liboracle_san.so")
+    if not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O1", "-g", "-std=c11", "-ffp-contract=off", "-fsanitize=address,undefined",
+             "-fno-sanitize-recover=all", "-fno-omit-frame-pointer", "-fPIC", "-shared", "-o", out, _SRC, "-lm"]
+        )
+    return out
+
+
 def lib():
     global _lib
     if _lib is None:
-        build()
-        _lib = ctypes.CDLL(_LIB)
+        override = os.environ.get("SGC_ORACLE_LIB")
+        if override:
+            _lib = ctypes.CDLL(override)
+        else:
+            build()
+            _lib = ctypes.CDLL(_LIB)
     return _lib
 
 

@@ -30,8 +30,10 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
 
 
-def run_and_check(w, steps, chunk_sample, pick_sample):
-    """pick_sample: list of (rhs index in [0, 2C), iteration j) pairs replayed in the oracle."""
+def run_and_check(w, steps, chunk_sample, pick_sample, snapshot_at=None):
+    """pick_sample: list of (rhs index in [0, 2C), iteration j) pairs replayed in the oracle.
+    snapshot_at: a step after which the state (m, v, W) is kept for the caller."""
+    snap = None
     C, d, r, k = w.C, w.d, w.r, w.k
     say(w.name, "C", C, "d", d, "r", r, "k", k)
     if w.matrix == "stored":
@@ -77,12 +79,11 @@ def run_and_check(w, steps, chunk_sample, pick_sample):
         assert (srt[:, 1:] != srt[:, :-1]).all()
         # a4: sampled single picks, replaying the GPU's own prefix in the oracle
         for n, j in pick_sample:
-            rep = orc.omp(hat[n], At, j + 1, norm=norm, forced=sel[n, :j])
-            assert rep["sel"][j] == sel[n, j], "rhs %d pick %d: gpu %d oracle %d" % (n, j, sel[n, j], rep["sel"][j])
+            rep = orc.omp_pick(hat[n], At, sel[n, :j], norm=norm)
+            assert rep["lam"] == sel[n, j], "rhs %d pick %d: gpu %d oracle %d" % (n, j, sel[n, j], rep["lam"])
         # a4: least-squares values on the full support for two right-hand sides
         for n in sorted({ps[0] for ps in pick_sample})[:2]:
-            rep = orc.omp(hat[n], At, k, norm=norm, forced=sel[n])
-            assert relerr(x[n], rep["x"]) < TOL
+            assert relerr(x[n], orc.lstsq_support(hat[n], At, sel[n])) < TOL
         # a5 from the GPU's recovered vectors
         rW = orc.apply(W_prev, d, sel[:C], x[:C], sel[C:], x[C:])
         Wn = W.cpu().numpy()
@@ -91,12 +92,31 @@ def run_and_check(w, steps, chunk_sample, pick_sample):
             assert relerr(dW[c], rdW[c]) < TOL
         assert np.array_equal(Wn[rW == W_prev], W_prev[rW == W_prev])
         m_prev, v_prev = m, v
+        if snapshot_at == t:
+            snap = dict(m=m.copy(), v=v.copy(), W=Wn.copy())
+    return dict(A=A, m=m, v=v, W=Wn, snapshot=snap)
 
 
-def test_cfg2_full_size_two_steps():
+def test_cfg2_full_size_ten_steps_and_resume():
+    """Configuration 2 as specified: ten consecutive steps with persistent moments at full size, every step
+    checked against the oracle on samples; then the resume property at the same size: five steps, the state
+    (m, v, W) copied out and into fresh buffers, five more steps - bitwise equal to the ten steps straight."""
     w = synth.CFG2
     picks = [(0, 0), (5, 1), (64, 17), (127, 100), (31, 255), (100, 200)]
-    run_and_check(w, 2, list(range(0, w.C, 7)), picks)
+    out = run_and_check(w, 10, list(range(0, w.C, 7)), picks, snapshot_at=5)
+    say("  resume from the state after step 5")
+    snap, A = out["snapshot"], out["A"]
+    buf = sgc.StepBuffers(w.C, w.d, w.r, w.k)
+    buf.m.copy_(dev(snap["m"]))
+    buf.v.copy_(dev(snap["v"]))
+    W = dev(snap["W"])
+    h = sgc.hyper()
+    for t in range(6, 11):
+        sgc.step(dev(synth.gradients(w, t)), W, buf, A, t, h)
+    torch.cuda.synchronize()
+    assert np.array_equal(W.cpu().numpy().view(np.uint32), out["W"].view(np.uint32))
+    assert np.array_equal(buf.m.cpu().numpy().view(np.uint32), out["m"].view(np.uint32))
+    assert np.array_equal(buf.v.cpu().numpy().view(np.uint32), out["v"].view(np.uint32))
 
 
 def test_cfg3_full_size():
