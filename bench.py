@@ -30,7 +30,9 @@ PROJECT_INSTR_PER_QUAD = 200.0  # vector instructions per four generated entries
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, keyed by
 # workload name: (bytes, the summary under profiles/ that holds the run). Stored figures: they describe the
 # kernel as it was when that profile was taken.
-MEASURED_TRAFFIC = {"cfg2_64x65536": (5.528e8, "profiles/cfg2_corr_kernel_hbm_traffic.md"),
+MEASURED_TRAFFIC = {"cfg4_llama7b_block": (4.357e9, "profiles/cfg4_kernel_trace_and_hbm_traffic.md: bytes leaving the L2s, served by the "
+                                                  "memory-side cache where the 64 MiB matrix stays; algorithmic 2.44e8"),
+                    "cfg2_64x65536": (5.528e8, "profiles/cfg2_corr_kernel_hbm_traffic.md"),
                     "cesgc_16x4096x4096_rank32": (1.390e8, "profiles/cesgc_16x4096x4096_kernel_trace_stats.md")}  # per matrix
 
 
