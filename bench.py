@@ -340,6 +340,10 @@ def run_workload(args, w, dev, K, Wm, variants, baseline):
         ls_bytes = sum(4.0 * nrhs * r * j + 4.0 * nrhs * j * j for j in range(1, k + 1))
         kernels["omp_select_update"]["algorithmic_GBps"] = round(ls_bytes / (su_ms / Ke * 1e-3) / 1e9, 1)
         kernels["omp_select_update"]["frac_of_8TBps"] = round(ls_bytes / (su_ms / Ke * 1e-3) / 8e12, 3)
+        # what this formulation moves: the selected columns twice per iteration (inner products with the new
+        # column, then the residual, which needs the solution those inner products lead to) plus the factor
+        two = sum(8.0 * nrhs * r * j + 4.0 * nrhs * j * j for j in range(1, k + 1))
+        kernels["omp_select_update"]["two_pass_GBps"] = round(two / (su_ms / Ke * 1e-3) / 1e9, 1)
 
     out = {
         "metric": "gradient elements/s per full SGC step (1 GPU)", "value": round(value, 1), "unit": "elements/s",

@@ -31,7 +31,7 @@ __global__ __launch_bounds__(APPLY_THREADS) void apply_kernel(float *__restrict_
         for (int32_t u = 0; u < k; ++u)
             z = (s_pos[u] == i) ? s_z[u] : z;
         z = z > 0.f ? z : 0.f;
-        if (x != 0.f) {
+        if (x != 0.f && i >= 0 && i < d) { // a position outside the chunk (a recovery that gave up) updates nothing
             const float nv = alpha * x / (sqrtf(z) + eps);
             float *w = W + c * (int64_t)d + i;
             *w = *w - lr * nv;

@@ -50,7 +50,13 @@ OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_
     // a stored matrix is read in place
     const bool generated = (need & WS_NEED_GENERATED) != 0;
     w.cols = generated ? (float *)take(sizeof(float) * (size_t)N * k * r) : nullptr;
-    w.partial = (uint64_t *)take(sizeof(uint64_t) * (size_t)N * w.tiles_m * 2);
+    // two keys per tile of positions; a small batch may be served by the single-launch recovery, whose
+    // workgroups (up to SMALL_MAX_GROUPS) each leave two keys per right-hand side
+    {
+        const int32_t slots = N <= SMALL_MAX_RHS && w.tiles_m < SMALL_MAX_GROUPS ? SMALL_MAX_GROUPS : w.tiles_m;
+        w.partial = (uint64_t *)take(sizeof(uint64_t) * (size_t)N * slots * 2);
+    }
+    w.sync = (uint32_t *)take(sizeof(uint32_t) * (64 + SMALL_MAX_GROUPS));
     w.bitmap = (uint32_t *)take(sizeof(uint32_t) * (size_t)N * w.words);
     // Rows of a generated matrix, in whole tiles. A matrix of at most 64 MiB gets a panel of its own (it
     // then stays in the 256 MiB memory-side cache). A larger one is regenerated inside the contraction, or
@@ -110,9 +116,13 @@ OmpWorkspace carve_recurrence(void *base, int32_t N, int32_t d, int32_t r, int32
 // res_split != 0: the float copy of the residual is written in split32 format instead (see corr_split_kernel)
 __global__ __launch_bounds__(256) void omp_init_kernel(const float *__restrict__ y, int32_t r, int32_t words,
                                                        double *__restrict__ res64, float *__restrict__ res32,
-                                                       uint32_t *__restrict__ bitmap, int32_t res_split)
+                                                       uint32_t *__restrict__ bitmap, int32_t res_split,
+                                                       uint32_t *__restrict__ sync)
 {
     const int64_t n = blockIdx.x;
+    if (n == 0)
+        for (int i = threadIdx.x; i < 64 + SMALL_MAX_GROUPS; i += 256)
+            sync[i] = 0u; // a fill by a kernel, not a memset node: the call may be captured in a graph
     uint16_t *res16 = reinterpret_cast<uint16_t *>(res32);
     for (int32_t j = threadIdx.x; j < r; j += 256) {
         const float v = y[n * r + j];
@@ -170,11 +180,19 @@ __device__ __forceinline__ float4 column_quad(const MatrixView &A, int32_t i, in
 // grid (N, slices). Every slice of a right-hand side repeats the (cheap) selection so that no
 // grid-wide synchronisation is needed; slice 0 also stores the column and the scalars.
 // dynamic LDS: float a_col[r]
-template <bool GENERATED, int PICK_THREADS>
-__global__ __launch_bounds__(PICK_THREADS) void pick_kernel(MatrixView A, IterArgs P)
+// COHERENT (the single-launch recovery): data that another workgroup of the same launch wrote or will read - the
+// tile keys, the selected position - moves with device-scope atomic loads and stores, which pass by the caches
+// that are not coherent between workgroups on different XCDs; everything else belongs to this workgroup alone.
+__device__ __forceinline__ uint64_t load_key(const uint64_t *p, bool coherent)
+{
+    return coherent ? __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *p;
+}
+
+template <bool GENERATED, int PICK_THREADS, bool COHERENT = false>
+__device__ __forceinline__ void pick_body(const MatrixView &A, const IterArgs &P, const int64_t n, const int slice,
+                                          const int nslices, unsigned char *smem)
 {
     constexpr int PICK_WAVES = PICK_THREADS / 64;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     float *a_col = reinterpret_cast<float *>(smem);
     __shared__ uint64_t s_u64[PICK_WAVES];
     __shared__ double s_red[2][PICK_WAVES];
@@ -185,8 +203,6 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(MatrixView A, IterAr
 
     const int32_t r = A.r, r4 = A.r >> 2, k = P.k, it = P.it;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t n = blockIdx.x;
-    const int slice = blockIdx.y, nslices = gridDim.y;
     if (slice != 0 && slice * PICK_WAVES >= it)
         return; // no earlier selection falls to this slice
     const OmpWorkspace &W = P.ws;
@@ -197,7 +213,7 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(MatrixView A, IterAr
     // (1) float maximum over the tile partials
     uint64_t best = 0;
     for (int32_t e = tid; e < np; e += PICK_THREADS) {
-        const uint64_t v = part[e];
+        const uint64_t v = load_key(part + e, COHERENT);
         best = v > best ? v : best;
     }
 #pragma unroll
@@ -218,7 +234,7 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(MatrixView A, IterAr
 
     // (2) candidates: every kept pair whose float score is within the tolerance of the maximum
     for (int32_t e = tid; e < np; e += PICK_THREADS) {
-        const uint64_t v = part[e];
+        const uint64_t v = load_key(part + e, COHERENT);
         if (v != 0 && __uint_as_float((uint32_t)(v >> 32)) >= thr) {
             const int32_t slot = atomicAdd(&s_ncand, 1);
             if (slot < PICK_CAND_CAP)
@@ -244,7 +260,7 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(MatrixView A, IterAr
             if (listed) {
                 i = s_cand[e];
             } else {
-                const uint64_t v = part[e];
+                const uint64_t v = load_key(part + e, COHERENT);
                 if (v == 0 || !(__uint_as_float((uint32_t)(v >> 32)) >= thr))
                     continue;
                 i = (int32_t)(0xffffffffu - (uint32_t)v);
@@ -337,6 +353,8 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(MatrixView A, IterAr
         W.gb[n * 2] = g;
         W.gb[n * 2 + 1] = b;
         P.sel[n * k + it] = lam;
+        if (COHERENT)
+            __hip_atomic_store(P.sel + n * k + it, lam, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         W.bitmap[n * W.words + (lam >> 5)] |= 1u << (lam & 31);
     }
 
@@ -382,6 +400,13 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(MatrixView A, IterAr
     }
 }
 
+template <bool GENERATED, int PICK_THREADS>
+__global__ __launch_bounds__(PICK_THREADS) void pick_kernel(MatrixView A, IterArgs P)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    pick_body<GENERATED, PICK_THREADS>(A, P, blockIdx.x, blockIdx.y, gridDim.y, smem);
+}
+
 // grid (N, slices); 256 threads (k <= 128) or 1024. dynamic LDS: double w[k]; double fsum[k]; double a[k];
 // scratch (the table of shares [wavefronts][k] if it fits, later the partial residuals)
 // First the small dense part of App. B in one pass over F: a wavefront takes column t of F (entries
@@ -392,10 +417,10 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(MatrixView A, IterAr
 // fewer such quads than threads, several threads share one and take every G-th column, and their
 // parts are added in a fixed order.
 // ROWS = rows of F per lane (k <= 64 * ROWS); FLIGHT = columns in flight per wavefront
-template <int FACTOR_ROWS, int FLIGHT>
-__global__ __launch_bounds__(FACTOR_MAX_THREADS) void update_kernel(IterArgs P, int32_t r)
+template <int FACTOR_ROWS, int FLIGHT, bool COHERENT = false>
+__device__ __forceinline__ void update_body(const IterArgs &P, const int32_t r, const int64_t n, const int slice,
+                                            const int nslices, unsigned char *smem)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int32_t k = P.k, it = P.it;
     double *w_s = reinterpret_cast<double *>(smem);
     double *fsum = w_s + k;
@@ -403,14 +428,12 @@ __global__ __launch_bounds__(FACTOR_MAX_THREADS) void update_kernel(IterArgs P, 
     __shared__ double s_gamma, s_coef;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nthreads = blockDim.x, nwaves = blockDim.x >> 6;
-    const int64_t n = blockIdx.x;
     const OmpWorkspace &W = P.ws;
     double *F = W.F + n * W.f_stride;
     double *avec = W.avec + n * k;
     // several workgroups (slices) may serve one right-hand side: each repeats the factor pass and takes
     // its share of the residual; slice 0 stores the factor and the solution. The solution is
     // double-buffered so that a late slice still reads the previous iteration's values.
-    const int slice = blockIdx.y, nslices = gridDim.y;
     const bool writer = slice == 0;
     const double *xs = W.xs + (int64_t)((it + 1) & 1) * W.xs_half + n * k;
     double *xs_new = W.xs + (int64_t)(it & 1) * W.xs_half + n * k;
@@ -630,11 +653,26 @@ __global__ __launch_bounds__(FACTOR_MAX_THREADS) void update_kernel(IterArgs P, 
                 *reinterpret_cast<uint2 *>(o) = make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
                 *reinterpret_cast<uint2 *>(o + 64) = make_uint2(l[0] | ((uint32_t)l[1] << 16), l[2] | ((uint32_t)l[3] << 16));
             } else {
-                reinterpret_cast<float4 *>(W.res32 + n * r)[jb] =
-                    make_float4((float)e0, (float)e1, (float)e2, (float)e3);
+                if (COHERENT) { // read by every workgroup of the launch in its next correlation phase
+                    uint32_t *o = reinterpret_cast<uint32_t *>(W.res32 + n * r + 4 * jb);
+                    __hip_atomic_store(o + 0, __float_as_uint((float)e0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(o + 1, __float_as_uint((float)e1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(o + 2, __float_as_uint((float)e2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(o + 3, __float_as_uint((float)e3), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } else {
+                    reinterpret_cast<float4 *>(W.res32 + n * r)[jb] =
+                        make_float4((float)e0, (float)e1, (float)e2, (float)e3);
+                }
             }
         }
     }
+}
+
+template <int FACTOR_ROWS, int FLIGHT>
+__global__ __launch_bounds__(FACTOR_MAX_THREADS) void update_kernel(IterArgs P, int32_t r)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    update_body<FACTOR_ROWS, FLIGHT>(P, r, blockIdx.x, blockIdx.y, gridDim.y, smem);
 }
 
 // Least-squares fit of a second right-hand side on the support already found (shared-support
@@ -689,6 +727,223 @@ __global__ __launch_bounds__(REFIT_THREADS) void refit_kernel(IterArgs P, const 
             acc += F[(int64_t)t * k + v] * u_s[t];
         z[n * k + v] = (float)acc;
     }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The whole recovery of a small batch in ONE launch (at most SMALL_MAX_RHS right-hand sides, resident rows
+// of At that fit the workgroups' LDS together). With so few right-hand sides every kernel of the
+// iteration is a few microseconds of work behind a launch, and three dependent launches per iteration
+// are the cost (28 us per iteration for one chunk of d = 4096, r = 256). Here G workgroups stay resident
+// for all k iterations; each keeps a slice of rows of At in LDS for the whole call, so the matrix is read
+// from memory once, not once per iteration:
+//   phase 1 (all workgroups)   correlations of the workgroup's rows with the N residuals on the vector ALUs
+//                              (a wavefront per row, float accumulation; with so few right-hand sides there is
+//                              nothing for the matrix cores), scaled and masked, two best keys per right-hand side
+//                              and workgroup written where the contraction's epilogue would put its tile keys
+//   grid barrier
+//   phase 2 (workgroup n < N)  the selection and least-squares update of right-hand side n: exactly the bodies
+//                              of pick_kernel and update_kernel (double re-scoring, App. B's factor update,
+//                              residual in double)
+//   grid barrier, then every workgroup fetches the new residuals.
+// The barrier is one word per workgroup in the workspace (cleared by omp_init_kernel): see small_grid_barrier.
+// All G workgroups must be resident at once: G is at most the number of CUs and a workgroup fits a CU, so they
+// are whenever the kernel gets the device; if they are not within SMALL_SPIN_LIMIT polls (seconds: some other
+// work holds the CUs), the polling wavefront raises the abort flag, every workgroup leaves at its next barrier
+// and the selected positions are set to -1 (values 0, which sgc_apply skips) - the grid always drains.
+constexpr uint32_t SMALL_SPIN_LIMIT = 1u << 22;
+constexpr int SMALL_THREADS = 256;
+constexpr int SMALL_ROW_PAD = 4; // floats between rows in LDS: rows read side by side by a wavefront fall in different banks
+
+// Barrier over the G workgroups of the launch: workgroup g publishes the number of the barrier in its own word
+// (no read-modify-write, G different addresses), one wavefront polls all G words with one load per 64 of them.
+// Data exchanged across the barrier is stored and loaded with device-scope atomics, so the only ordering needed is
+// that a wavefront's stores are acknowledged before its workgroup's word is published.
+__device__ __forceinline__ bool small_grid_barrier(uint32_t *sync, int G, int g, uint32_t epoch, int32_t *s_flag)
+{
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        uint32_t *flags = sync + 64, *abort_flag = sync;
+        if (threadIdx.x == 0)
+            __hip_atomic_store(flags + g, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        uint32_t spins = 0;
+        int32_t stop = 0;
+        for (;;) {
+            bool ok = true;
+            for (int q = threadIdx.x; q < G; q += 64)
+                ok = ok && __hip_atomic_load(flags + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= epoch;
+            if (__builtin_amdgcn_ballot_w64(!ok) == 0ull)
+                break;
+            const uint32_t ab = __hip_atomic_load(abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (__builtin_amdgcn_ballot_w64(ab != 0u) != 0ull || ++spins > SMALL_SPIN_LIMIT) {
+                if (threadIdx.x == 0)
+                    __hip_atomic_store(abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                stop = 1;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        if (threadIdx.x == 0)
+            *s_flag = stop;
+    }
+    __syncthreads();
+    return *s_flag != 0;
+}
+
+// dynamic LDS: float rows[rows_per_group][r + SMALL_ROW_PAD]; float inv[rows_per_group rounded up to 4];
+//              float res[N][r]; unsigned char taken[N][rows_per_group]; then (16-byte aligned) the scratch of the bodies
+__global__ __launch_bounds__(SMALL_THREADS) void omp_small_kernel(MatrixView A, IterArgs P, int32_t N, int32_t rows_per_group,
+                                                                  int32_t body_offset)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    __shared__ uint64_t s_keys[SMALL_THREADS / 64][SMALL_MAX_RHS][2];
+    __shared__ int32_t s_flag;
+    const int32_t r = A.r, r4 = r >> 2, k = P.k, d = A.d;
+    const int32_t ld = r + SMALL_ROW_PAD;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int G = gridDim.x, g = blockIdx.x;
+    const int32_t row0 = g * rows_per_group;
+    const int32_t rows = row0 >= d ? 0 : (d - row0 < rows_per_group ? d - row0 : rows_per_group);
+    float *a_rows = reinterpret_cast<float *>(smem);
+    float *inv = a_rows + (size_t)rows_per_group * ld;
+    float *res = inv + ((rows_per_group + 3) & ~3); // keeps the residuals 16-byte aligned
+    unsigned char *taken = reinterpret_cast<unsigned char *>(res + (size_t)N * r);
+    unsigned char *body = smem + body_offset;
+    const OmpWorkspace &W = P.ws;
+
+    // the workgroup's rows of At and their reciprocal norms, once for the whole call; the residuals = y
+    for (int32_t e = tid; e < rows * r4; e += SMALL_THREADS) {
+        const int32_t i = e / r4, jb = e - i * r4;
+        *reinterpret_cast<float4 *>(a_rows + (size_t)i * ld + 4 * jb) =
+            reinterpret_cast<const float4 *>(P.At_rows + (int64_t)(row0 + i) * r)[jb];
+    }
+    for (int32_t i = tid; i < rows; i += SMALL_THREADS)
+        inv[i] = A.inv_colnorm[row0 + i];
+    for (int32_t e = tid; e < N * r4; e += SMALL_THREADS)
+        reinterpret_cast<float4 *>(res)[e] = reinterpret_cast<const float4 *>(P.y)[e];
+    for (int32_t e = tid; e < N * rows_per_group; e += SMALL_THREADS)
+        taken[e] = 0;
+    __syncthreads();
+
+    // phase 1 mapping: a wavefront takes 16 rows at a time, four lanes per row, each lane a quarter of the depth
+    const int sub = lane >> 2, part = lane & 3;
+    bool aborted = false;
+    uint32_t epoch = 0;
+    for (int32_t it = 0; it < k; ++it) {
+        // ---- phase 1: this workgroup's rows against every residual ----
+        uint64_t best[SMALL_MAX_RHS], second[SMALL_MAX_RHS];
+#pragma unroll
+        for (int u = 0; u < SMALL_MAX_RHS; ++u)
+            best[u] = second[u] = 0;
+        for (int32_t i0 = wave * 16; i0 < rows; i0 += (SMALL_THREADS / 64) * 16) {
+            const int32_t i = i0 + sub;
+            const bool live = i < rows;
+            const float4 *ar = reinterpret_cast<const float4 *>(a_rows + (size_t)(live ? i : i0) * ld);
+            float acc[SMALL_MAX_RHS];
+#pragma unroll
+            for (int u = 0; u < SMALL_MAX_RHS; ++u)
+                acc[u] = 0.f;
+            for (int32_t jb = part; jb < r4; jb += 4) {
+                const float4 a = ar[jb];
+#pragma unroll
+                for (int u = 0; u < SMALL_MAX_RHS; ++u) {
+                    if (u < N) {
+                        const float4 b = reinterpret_cast<const float4 *>(res + (size_t)u * r)[jb];
+                        acc[u] = __builtin_fmaf(a.x, b.x, acc[u]);
+                        acc[u] = __builtin_fmaf(a.y, b.y, acc[u]);
+                        acc[u] = __builtin_fmaf(a.z, b.z, acc[u]);
+                        acc[u] = __builtin_fmaf(a.w, b.w, acc[u]);
+                    }
+                }
+            }
+            const float in = live ? inv[i] : 0.f;
+#pragma unroll
+            for (int u = 0; u < SMALL_MAX_RHS; ++u) {
+                if (u < N) {
+                    float v = acc[u];
+                    v += __shfl_xor(v, 1, 64);
+                    v += __shfl_xor(v, 2, 64);
+                    const float score = fabsf(v) * in;
+                    const bool ok = live && part == 0 && !taken[u * rows_per_group + (live ? i : 0)];
+                    const uint64_t key = ok ? (((uint64_t)__float_as_uint(score) << 32) | (uint64_t)(0xffffffffu - (uint32_t)(row0 + i))) : 0ull;
+                    const uint64_t lo = key < best[u] ? key : best[u];
+                    best[u] = key < best[u] ? best[u] : key;
+                    second[u] = lo < second[u] ? second[u] : lo;
+                }
+            }
+        }
+        // the two best of the wavefront's lanes, then of the workgroup's wavefronts
+#pragma unroll
+        for (int u = 0; u < SMALL_MAX_RHS; ++u) {
+            if (u < N) {
+#pragma unroll
+                for (int off = 32; off > 0; off >>= 1) {
+                    const uint64_t ob = shfl_xor_u64(best[u], off), os = shfl_xor_u64(second[u], off);
+                    // merge two (best, second) pairs
+                    const uint64_t hi = ob > best[u] ? ob : best[u];
+                    const uint64_t mid = ob > best[u] ? best[u] : ob;
+                    const uint64_t s2 = os > second[u] ? os : second[u];
+                    best[u] = hi;
+                    second[u] = mid > s2 ? mid : s2;
+                }
+                if (lane == 0) {
+                    s_keys[wave][u][0] = best[u];
+                    s_keys[wave][u][1] = second[u];
+                }
+            }
+        }
+        __syncthreads();
+        if (tid < N) {
+            uint64_t b = 0, sc = 0;
+            for (int wv = 0; wv < SMALL_THREADS / 64; ++wv) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const uint64_t key = s_keys[wv][tid][h];
+                    const uint64_t lo = key < b ? key : b;
+                    b = key < b ? b : key;
+                    sc = lo < sc ? sc : lo;
+                }
+            }
+            uint64_t *o = W.partial + ((int64_t)tid * G + g) * 2; // W.tiles_m == G
+            __hip_atomic_store(o, b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(o + 1, sc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (small_grid_barrier(W.sync, G, g, ++epoch, &s_flag)) {
+            aborted = true;
+            break;
+        }
+        // ---- phase 2: selection and least-squares update, one workgroup per right-hand side ----
+        if (g < N) {
+            IterArgs Q = P;
+            Q.it = it;
+            pick_body<false, SMALL_THREADS, true>(A, Q, g, 0, 1, body);
+            __threadfence_block();
+            __syncthreads();
+            update_body<2, 4, true>(Q, r, g, 0, 1, body);
+        }
+        if (small_grid_barrier(W.sync, G, g, ++epoch, &s_flag)) {
+            aborted = true;
+            break;
+        }
+        if (it + 1 < k) {
+            for (int32_t e = tid; e < N * (r >> 1); e += SMALL_THREADS) {
+                const uint64_t v = __hip_atomic_load(reinterpret_cast<const uint64_t *>(W.res32) + e, __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+                reinterpret_cast<uint64_t *>(res)[e] = v;
+            }
+            if (tid < N) {
+                const int32_t lam = __hip_atomic_load(P.sel + (int64_t)tid * k + it, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - row0;
+                if (lam >= 0 && lam < rows)
+                    taken[tid * rows_per_group + lam] = 1;
+            }
+            __syncthreads();
+        }
+    }
+    if (aborted && g == 0)
+        for (int32_t e = tid; e < N * k; e += SMALL_THREADS) {
+            P.sel[e] = -1;
+            P.x[e] = 0.f;
+        }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -813,6 +1068,70 @@ static void omp_select_update(const OmpPlan &pl, const MatrixView &A, const floa
         update_kernel<16, 1><<<ugrid, FACTOR_MAX_THREADS, pl.factor_smem, s>>>(P, A.r);
 }
 
+// Whether a recovery is served by the single-launch kernel, and its shape: at most SMALL_MAX_RHS right-hand sides,
+// resident rows without any option, and a matrix whose rows fit the LDS of at most SMALL_MAX_GROUPS workgroups
+// (96 KiB of rows each at most; 64 KiB slices are preferred). The limits are where it was measured to win: a
+// barrier over 64 workgroups costs about 4 us (a store and a poll that both travel to the memory side, since
+// the workgroups sit on different XCDs), two per iteration plus the reload of the residuals 10 us, the two
+// bodies 4 + 6 us, against 27 us per iteration for three dependent launches. With 8 right-hand sides or 256
+// workgroups the launches are no slower any more (0.96 vs 0.87 ms at N = 8, d = 4096, r = 256, k = 32).
+struct SmallPlan {
+    int32_t groups, rows_per_group, body_offset;
+    size_t smem;
+};
+static int device_cu_count()
+{
+    static int count[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+        return 0;
+    if (count[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = -1;
+        count[dev] = n;
+    }
+    return count[dev] > 0 ? count[dev] : 0;
+}
+static bool small_plan(const OmpPlan &pl, int32_t N, int32_t k, SmallPlan &sp)
+{
+    const MatrixView &A = pl.Apick;
+    if (N > SMALL_MAX_RHS || A.generated || A.gram || pl.screen || pl.recurrence || pl.narrow || k > 128 || A.r > 2048 ||
+        (int64_t)N * A.r > 8192 || (A.flags & SGC_MATRIX_FLAG_MULTI_LAUNCH))
+        return false;
+    int cus = device_cu_count();
+    if (cus > SMALL_MAX_GROUPS)
+        cus = SMALL_MAX_GROUPS;
+    if (cus < 2 * N || cus < 8)
+        return false;
+    const int64_t row_bytes = (int64_t)(A.r + SMALL_ROW_PAD) * 4; // as laid out in LDS
+    int64_t rows_per_group = (64 * 1024) / row_bytes;
+    if (rows_per_group < 1)
+        rows_per_group = 1;
+    int64_t groups = ((int64_t)A.d + rows_per_group - 1) / rows_per_group;
+    if (groups > cus) { // larger slices, up to 96 KiB
+        groups = cus;
+        rows_per_group = ((int64_t)A.d + groups - 1) / groups;
+        if (rows_per_group * row_bytes > 96 * 1024)
+            return false;
+    }
+    if (groups < 2 * N) { // a short matrix: still one workgroup per right-hand side for the second phase, and some to spare
+        groups = 2 * N;
+        rows_per_group = ((int64_t)A.d + groups - 1) / groups;
+    }
+    groups = ((int64_t)A.d + rows_per_group - 1) / rows_per_group; // no workgroup without rows ...
+    if (groups < N)
+        groups = N;                                                // ... except those that serve a right-hand side
+    size_t off = (size_t)rows_per_group * row_bytes + (size_t)((rows_per_group + 3) & ~(int64_t)3) * 4 +
+                 (size_t)N * A.r * 4 + (size_t)N * rows_per_group;
+    off = (off + 15) & ~(size_t)15;
+    sp.groups = (int32_t)groups;
+    sp.rows_per_group = (int32_t)rows_per_group;
+    sp.body_offset = (int32_t)off;
+    sp.smem = off + (pl.pick_smem > pl.factor_smem ? pl.pick_smem : pl.factor_smem);
+    return sp.smem <= 150 * 1024;
+}
+
 // A second stream (default priority) and two events per device, created on first use, so that the
 // two halves of a large batch can run their iterations side by side: while one half is in its
 // memory-bound selection / update kernels the other half's contraction keeps the matrix cores busy.
@@ -890,7 +1209,7 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
     {
         ProfileScope prof(KC_OTHER, s);
         omp_init_kernel<<<dim3((unsigned)N), 256, 0, s>>>(y, A.r, ws.words, ws.res64, ws.res32, ws.bitmap,
-                                                          pl.screen ? 1 : 0);
+                                                          pl.screen ? 1 : 0, ws.sync);
     }
     pl.Apick = A;
     const bool whole_matrix_panel = pl.panels && ws.panel_rows >= A.d;
@@ -906,7 +1225,22 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
         ProfileScope prof(KC_FILL, s);
         launch_split_rows(whole_matrix_panel ? ws.panel : A.At, A.d, A.r, ws.a16, s);
     }
-    hipError_t e = omp_iterations(pl, whole_matrix_panel, y, N, A, k, sel, x, ws, s);
+    hipError_t e;
+    SmallPlan sp{};
+    if (small_plan(pl, N, k, sp)) {
+        // a small batch: the whole iteration loop is one launch
+        ProfileScope prof(KC_CORR, s);
+        e = raise_dynamic_lds(reinterpret_cast<const void *>(omp_small_kernel), sp.smem);
+        if (e != hipSuccess)
+            return e;
+        const OmpWorkspace w = shift_workspace(ws, 0, A.r, k, sp.groups);
+        IterArgs P{y, k, 0, sel, x, w, pl.Apick.At, pl.factor_share_table ? 1 : 0, 0};
+        omp_small_kernel<<<dim3((unsigned)sp.groups), SMALL_THREADS, sp.smem, s>>>(pl.Apick, P, N, sp.rows_per_group,
+                                                                                  sp.body_offset);
+        e = hipGetLastError();
+    } else {
+        e = omp_iterations(pl, whole_matrix_panel, y, N, A, k, sel, x, ws, s);
+    }
     if (e != hipSuccess || !y_fit)
         return e;
     {

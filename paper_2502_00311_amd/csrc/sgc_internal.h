@@ -29,6 +29,10 @@ constexpr int CORR_BN = 128; // right-hand sides per workgroup
 
 inline int corr_tiles_m(int d) { return (d + CORR_BM - 1) / CORR_BM; }
 
+// the single-launch recovery serves at most this many right-hand sides, with at most this many workgroups
+constexpr int SMALL_MAX_RHS = 4;
+constexpr int SMALL_MAX_GROUPS = 64;
+
 // Workspace layout of sgc_recover_omp (all offsets 256-byte aligned).
 struct OmpWorkspace {
     double *res64;     // [N][r] residual
@@ -61,6 +65,8 @@ struct OmpWorkspace {
     int32_t rc_head;   // iterations served by the recurrence (the rest by the contraction)
     int32_t rc_d;      // d (row length of rc_p and rc_B)
     double *cvec;      // [N][k] coordinates c_t of the newest column, exported by update_kernel
+    uint32_t *sync;    // [64 + SMALL_MAX_GROUPS] abort flag (word 0) and one arrival word per workgroup (from word 64)
+                       // of the single-launch recovery for small batches
 };
 // `need`: which optional regions the matrix calls for. A stored matrix is read in place (no column copies, no
 // panel); the bfloat16 planes exist only for a matrix that asks for the screening contraction.

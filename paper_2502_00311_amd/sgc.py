@@ -18,6 +18,7 @@ GRAD_F32, GRAD_BF16 = 0, 1
 MATRIX_STORED, MATRIX_PHILOX = 0, 1
 MATRIX_FLAG_SCREEN_BF16 = 1
 MATRIX_FLAG_MATERIALIZE = 2
+MATRIX_FLAG_MULTI_LAUNCH = 4
 
 EXPORTS = [
     "sgc_status_string", "sgc_matrix_fill", "sgc_matrix_colnorms", "sgc_matrix_gram", "sgc_sparsify_project",

@@ -336,6 +336,48 @@ def test_omp_generated_matrix_with_many_right_hand_sides(N, d, r, k, flags):
     assert all(len(set(row.tolist())) == k for row in sel)
 
 
+@pytest.mark.parametrize("N,d,r,k,mode", [
+    (2, 4096, 256, 32, "stored"),     # configuration 1's shape with both moments: 64 workgroups of 64 rows
+    (1, 4096, 256, 32, "stored"),
+    (4, 1000, 96, 12, "stored"),      # ragged: the last workgroup holds fewer rows
+    (3, 2048, 220, 31, "stored"),     # the CESGC chunk shape (r not a multiple of 64)
+    (2, 37, 16, 16, "stored"),        # fewer positions than lanes, k = r
+    (4, 5, 8, 5, "stored"),           # d barely above the batch: workgroups without rows, k = d
+    (2, 6000, 64, 1, "philox"),       # generated matrix written to the workspace panel first; one iteration
+    (2, 300, 128, 128, "stored"),     # the largest k of this path
+    (4, 24000, 64, 8, "stored"),      # 6 MB of rows: 96 KiB slices in 64 workgroups
+])
+def test_small_batch_single_launch_recovery(N, d, r, k, mode):
+    """At most four right-hand sides on a small resident matrix are recovered in one launch (resident workgroups
+    that keep their rows of At in LDS and meet at a barrier twice per iteration). Against the oracle, and
+    against the three-launches-per-iteration form of the same recovery (SGC_MATRIX_FLAG_MULTI_LAUNCH)."""
+    say("omp single launch", N, d, r, k, mode)
+    rng = np.random.default_rng(N * 1000 + d + k)
+    A, At = make_matrix(mode, 41, d, r)
+    Y = rng.standard_normal((N, r)).astype(np.float32)
+    if N > 2:
+        Y[1] = 0.0                                   # all-zero right-hand side: every position ties
+        Y[2] = np.round(2 * Y[2])                    # small integers: equal float scores are likely
+    sel, x = run_omp(Y, A, k)
+    assert sel.min() >= 0                            # -1 would mean the launch gave up waiting for its workgroups
+    rsel, rx = orc.omp_batch(Y, At, k)
+    assert np.array_equal(sel, rsel)
+    assert rowwise_relerr(x, rx) < TOL
+    A.flags = sgc.MATRIX_FLAG_MULTI_LAUNCH
+    sel2, x2 = run_omp(Y, A, k)
+    assert np.array_equal(sel, sel2) and rowwise_relerr(x, x2) < 1e-6
+    # twice in a row on the same workspace: the barrier words of the first call must not leak into the second
+    A.flags = 0
+    yd = dev(Y)
+    s3 = torch.empty((N, k), dtype=torch.int32, device=DEV)
+    x3 = torch.empty((N, k), dtype=torch.float32, device=DEV)
+    ws = torch.empty(sgc.sgc_omp_workspace_bytes(N, d, r, k), dtype=torch.uint8, device=DEV)
+    for _ in range(3):
+        sgc.sgc_recover_omp(yd, N, A, k, s3, x3, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(s3.cpu().numpy(), sel) and np.array_equal(x3.cpu().numpy().view(np.uint32), x.view(np.uint32))
+
+
 def test_omp_exact_recovery_zero_and_oversized_k():
     d, r, k = 1024, 256, 8
     A, At = make_matrix("stored", 20, d, r)
