@@ -2,8 +2,8 @@
 // magnitude, emitted in ascending position with their signed values.
 //
 // One workgroup per chunk. Float chunks of up to 65536 elements take the register-resident kernel
-// (one HBM read); longer chunks and bfloat16 take the general kernel, which re-reads the chunk
-// (from L2) in every pass. In both, the k-th largest magnitude key is found exactly by a most-significant-
+// (one HBM read); bfloat16 chunks a two-sweep kernel that selects on a short list of candidates; everything
+// else the general kernel, which re-reads the chunk (from L2) in every pass. In both, the k-th largest magnitude key is found exactly by a most-significant-
 // digit radix select over the sign-cleared bit patterns (integer work only, so the result is the
 // unique one under the rule "larger magnitude first, lower position among equals"). The output is
 // then written in position order without a sort: every wavefront owns a contiguous slice of the
@@ -175,7 +175,7 @@ constexpr uint32_t TOPK_CAND_CAP = 2048; // candidate entries kept in LDS
 // ignored), found by one wavefront: a bitwise binary search on the 31-bit key whose counts are
 // wavefront ballots. Also returns how many keys are larger than / equal to the result.
 __device__ __forceinline__ uint32_t wave_kth_largest(const uint32_t *keys, uint32_t n, uint32_t kth, uint32_t &gt,
-                                                     uint32_t &eq)
+                                                     uint32_t &eq, int key_bits = 31)
 {
     const uint32_t lane = threadIdx.x & 63;
     uint32_t thr = 0;
@@ -189,7 +189,7 @@ __device__ __forceinline__ uint32_t wave_kth_largest(const uint32_t *keys, uint3
             const uint32_t s = q * 64 + lane;
             kr[q] = s < n ? (keys[s] & 0x7fffffffu) : 0u; // padding keys are 0: never >= a candidate
         }
-        for (int bit = 30; bit >= 0; --bit) {
+        for (int bit = key_bits - 1; bit >= 0; --bit) {
             const uint32_t cand = thr | (1u << bit);
             uint32_t cnt = 0;
 #pragma unroll
@@ -205,7 +205,7 @@ __device__ __forceinline__ uint32_t wave_kth_largest(const uint32_t *keys, uint3
         }
         return thr;
     }
-    for (int bit = 30; bit >= 0; --bit) {
+    for (int bit = key_bits - 1; bit >= 0; --bit) {
         const uint32_t cand = thr | (1u << bit);
         uint32_t cnt = 0;
         for (uint32_t s0 = 0; s0 < n; s0 += 64) {
@@ -401,6 +401,249 @@ __global__ __launch_bounds__(THREADS, MINBLOCKS) void topk_f32_regs_kernel(const
     topk_general<float, THREADS>(gc, d, k, oidx, oval);
 }
 
+// bfloat16 chunks (d % 8 == 0, k <= THREADS): two sweeps over the chunk with 16-byte loads instead of the general
+// kernel's four with 2-byte loads and an LDS atomic per element. Sweep 1 takes every thread's largest key; the
+// k-th largest of those maxima is a lower bound of the threshold that at least k entries reach (the maxima are
+// k distinct entries). Sweep 2 collects the entries that reach the bound - a few per cent of the chunk for
+// heavy-tailed data - into LDS: every wavefront owns a contiguous slice of the chunk and a segment of the list,
+// and appends in position order (a prefix sum over the lanes' counts), so the list as a whole is in ascending
+// position. The exact threshold is then a radix select over the list (15-bit keys: 11 + 4 bits), and the
+// output is written by walking the list in order, exactly as the general kernel walks the chunk: entries
+// above the threshold, and the first `need` of those equal to it. bfloat16 has so few distinct magnitudes
+// that ties at the threshold are the rule; they cost nothing here. A segment that overflows (quantised or
+// constant data: everything reaches the bound) or a bound of 0 sends the chunk to the general kernel.
+// dynamic LDS: uint32_t pos[NW][SEG]; uint16_t raw[NW][SEG]
+constexpr int TOPK_BF16_SEG = 1024; // list entries per wavefront
+
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void topk_bf16_list_kernel(const uint16_t *__restrict__ g, int32_t d, int32_t k,
+                                                                 int32_t *__restrict__ idx, float *__restrict__ val)
+{
+    constexpr int NW = THREADS / 64;
+    constexpr int SEG = TOPK_BF16_SEG;
+    extern __shared__ __attribute__((aligned(16))) unsigned char topk_smem[];
+    uint32_t *cand_pos = reinterpret_cast<uint32_t *>(topk_smem);           // [NW][SEG]
+    uint16_t *cand_raw = reinterpret_cast<uint16_t *>(cand_pos + NW * SEG); // [NW][SEG]
+    __shared__ uint32_t tmax_s[THREADS];
+    __shared__ uint32_t hist[2048];
+    __shared__ uint32_t wave_tot[NW];
+    __shared__ uint32_t w_cnt[NW], w_gt[NW], w_eq[NW];
+    __shared__ uint32_t s_bound, s_bin, s_need, s_overflow;
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const uint16_t *gc = g + (int64_t)blockIdx.x * d;
+    int32_t *oidx = idx + (int64_t)blockIdx.x * k;
+    float *oval = val + (int64_t)blockIdx.x * k;
+
+    // wavefront slices in whole steps of 512 positions (64 lanes x 8)
+    int32_t seg = (d + NW - 1) / NW;
+    seg = (seg + 511) & ~511;
+    const int32_t beg = w * seg < d ? w * seg : d;
+    const int32_t end = beg + seg < d ? beg + seg : d;
+    auto load8 = [&](int32_t i0, uint32_t (&key)[8], uint16_t (&raw)[8]) {
+        // positions i0 .. i0 + 7 of the chunk (i0 % 8 == 0; d % 8 == 0, so the eight are inside or outside together)
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (i0 < end)
+            v = *reinterpret_cast<const uint4 *>(gc + i0);
+        const uint32_t wd[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            raw[2 * e] = (uint16_t)(wd[e] & 0xffffu);
+            raw[2 * e + 1] = (uint16_t)(wd[e] >> 16);
+            key[2 * e] = wd[e] & 0x7fffu;
+            key[2 * e + 1] = (wd[e] >> 16) & 0x7fffu;
+        }
+    };
+
+    // ---- sweep 1: the largest key of every thread ----
+    uint32_t tmax = 0;
+    for (int32_t i0 = beg + lane * 8; i0 < end; i0 += 8 * 512) {
+        // eight 16-byte loads in flight per lane; the largest key of a 32-bit pair of entries without unpacking:
+        // clear both sign bits, compare the halves
+        uint4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int32_t i = i0 + u * 512;
+            v[u] = i < end ? *reinterpret_cast<const uint4 *>(gc + i) : make_uint4(0u, 0u, 0u, 0u);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const uint32_t wd[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t lo = wd[e] & 0x7fffu, hi = (wd[e] >> 16) & 0x7fffu;
+                const uint32_t m = lo > hi ? lo : hi;
+                tmax = m > tmax ? m : tmax;
+            }
+        }
+    }
+    tmax_s[tid] = tmax;
+    if (tid == 0)
+        s_overflow = 0;
+    __syncthreads();
+    if (w == 0) {
+        uint32_t gt, eq;
+        const uint32_t b = wave_kth_largest(tmax_s, THREADS, (uint32_t)k, gt, eq, 15);
+        if (lane == 0)
+            s_bound = b;
+    }
+    __syncthreads();
+    const uint32_t bound = s_bound;
+    if (bound == 0u) { // fewer than k threads saw a non-zero entry: no useful bound
+        topk_general<uint16_t, THREADS>(gc, d, k, oidx, oval);
+        return;
+    }
+
+    // ---- sweep 2: the entries that reach the bound, appended in position order to the wavefront's segment ----
+    uint32_t count = 0; // entries of this wavefront so far (the same in every lane)
+    constexpr int U2 = 4; // 16-byte loads in flight per lane
+    for (int32_t s0 = beg; s0 < end; s0 += U2 * 512) {
+        uint32_t key[U2][8];
+        uint16_t raw[U2][8];
+#pragma unroll
+        for (int u = 0; u < U2; ++u)
+            load8(s0 + u * 512 + lane * 8, key[u], raw[u]);
+#pragma unroll
+        for (int u = 0; u < U2; ++u) {
+            uint32_t mine = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                mine += key[u][e] >= bound ? 1u : 0u;
+            if (__ballot(mine != 0u) == 0ull)
+                continue;
+            uint32_t incl = mine; // inclusive prefix over the lanes
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const uint32_t t = __shfl_up(incl, off, 64);
+                if (lane >= off)
+                    incl += t;
+            }
+            const uint32_t total = __shfl(incl, 63, 64);
+            if (count + total > (uint32_t)SEG) {
+                s_overflow = 1;
+            } else {
+                uint32_t slot = w * SEG + count + incl - mine;
+                const int32_t p0 = s0 + u * 512 + lane * 8;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    if (key[u][e] >= bound) {
+                        cand_pos[slot] = (uint32_t)(p0 + e);
+                        cand_raw[slot] = raw[u][e];
+                        ++slot;
+                    }
+                }
+            }
+            count += total;
+        }
+    }
+    if (lane == 0)
+        w_cnt[w] = count;
+    __syncthreads();
+    if (s_overflow != 0u) {
+        topk_general<uint16_t, THREADS>(gc, d, k, oidx, oval);
+        return;
+    }
+
+    // ---- the exact k-th largest key of the list: radix select, 11 then 4 bits ----
+    uint32_t prefix = 0, need = (uint32_t)k;
+    int decided = 15;
+    for (int pass = 0; pass < 2; ++pass) {
+        const int shift = pass == 0 ? 4 : 0;
+        const int nb = pass == 0 ? 2048 : 16;
+        for (int b = tid; b < nb; b += THREADS)
+            hist[b] = 0;
+        __syncthreads();
+        for (int ww = 0; ww < NW; ++ww) {
+            const uint32_t n = w_cnt[ww];
+            for (uint32_t e = tid; e < n; e += THREADS) {
+                const uint32_t key = (uint32_t)cand_raw[ww * SEG + e] & 0x7fffu;
+                if (pass == 0 || (key >> decided) == prefix)
+                    atomicAdd(&hist[(key >> shift) & (uint32_t)(nb - 1)], 1u);
+            }
+        }
+        __syncthreads();
+        // thread t owns `per` bins counted from the top
+        const int per = (nb + THREADS - 1) / THREADS;
+        const int hi = nb - tid * per;
+        const int lo = hi - per < 0 ? 0 : hi - per;
+        uint32_t local = 0;
+        for (int b = hi - 1; b >= lo && b >= 0; --b)
+            local += hist[b];
+        const uint32_t incl = block_inclusive_scan<THREADS>(local, wave_tot);
+        const uint32_t excl = incl - local;
+        if (excl < need && need <= incl) { // exactly one thread
+            uint32_t run = excl;
+            for (int b = hi - 1; b >= lo; --b) {
+                const uint32_t h = hist[b];
+                if (run + h >= need) {
+                    s_bin = (uint32_t)b;
+                    s_need = need - run;
+                    break;
+                }
+                run += h;
+            }
+        }
+        __syncthreads();
+        prefix = (prefix << (pass == 0 ? 11 : 4)) | s_bin;
+        need = s_need;
+        decided = shift;
+        __syncthreads();
+    }
+    const uint32_t thr = prefix;
+
+    // ---- emit: the list is in ascending position; every wavefront walks its own segment ----
+    const uint32_t n_mine = w_cnt[w];
+    uint32_t cgt = 0, ceq = 0;
+    for (uint32_t e0 = 0; e0 < n_mine; e0 += 64) {
+        const uint32_t e = e0 + lane;
+        const bool in = e < n_mine;
+        const uint32_t key = in ? ((uint32_t)cand_raw[w * SEG + e] & 0x7fffu) : 0u;
+        cgt += (uint32_t)__popcll(__ballot(in && key > thr));
+        ceq += (uint32_t)__popcll(__ballot(in && key == thr));
+    }
+    if (lane == 0) {
+        w_gt[w] = cgt;
+        w_eq[w] = ceq;
+    }
+    __syncthreads();
+    uint32_t run_gt = 0, run_eq = 0;
+    for (int u = 0; u < w; ++u) {
+        run_gt += w_gt[u];
+        run_eq += w_eq[u];
+    }
+    const uint64_t below = (1ull << lane) - 1ull;
+    for (uint32_t e0 = 0; e0 < n_mine; e0 += 64) {
+        const uint32_t e = e0 + lane;
+        const bool in = e < n_mine;
+        const uint16_t raw = in ? cand_raw[w * SEG + e] : (uint16_t)0;
+        const uint32_t key = (uint32_t)raw & 0x7fffu;
+        const bool gt = in && key > thr, eq = in && key == thr;
+        const uint64_t bgt = __ballot(gt), beq = __ballot(eq);
+        const uint32_t gt_before = run_gt + (uint32_t)__popcll(bgt & below);
+        const uint32_t eq_before = run_eq + (uint32_t)__popcll(beq & below);
+        if (gt || (eq && eq_before < need)) {
+            const uint32_t slot = gt_before + (eq_before < need ? eq_before : need);
+            oidx[slot] = (int32_t)cand_pos[w * SEG + e];
+            oval[slot] = Elem<uint16_t>::widen(raw);
+        }
+        run_gt += (uint32_t)__popcll(bgt);
+        run_eq += (uint32_t)__popcll(beq);
+    }
+}
+
+template <int THREADS>
+static hipError_t launch_topk_bf16_list(const uint16_t *g, int64_t C, int32_t d, int32_t k, int32_t *idx, float *val,
+                                        hipStream_t s)
+{
+    constexpr size_t smem = (size_t)(THREADS / 64) * TOPK_BF16_SEG * (sizeof(uint32_t) + sizeof(uint16_t));
+    auto kern = topk_bf16_list_kernel<THREADS>;
+    const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void *>(kern), smem);
+    if (e != hipSuccess)
+        return e;
+    kern<<<dim3((unsigned)C), THREADS, smem, s>>>(g, d, k, idx, val);
+    return hipGetLastError();
+}
+
 // Second pass for long chunks (see launch_topk): the k largest of the S * k candidates that the register
 // kernel kept for the S pieces of a chunk, one wavefront per chunk. The candidates of a piece are in
 // ascending position and the pieces in order, so the list is in ascending position: the entries above
@@ -473,10 +716,16 @@ hipError_t launch_topk(const void *grad, int grad_type, int64_t C, int32_t d, in
         else
             topk_kernel<float, 1024><<<grid, 1024, 0, s>>>((const float *)grad, d, k, idx, val);
     } else {
-        if (d <= 16384)
+        const bool vec = d % 8 == 0; // every chunk then starts 16-byte aligned
+        if (d <= 16384) {
+            if (vec && k <= 256 && d >= 2048)
+                return launch_topk_bf16_list<256>((const uint16_t *)grad, C, d, k, idx, val, s);
             topk_kernel<uint16_t, 256><<<grid, 256, 0, s>>>((const uint16_t *)grad, d, k, idx, val);
-        else
+        } else {
+            if (vec && k <= 1024)
+                return launch_topk_bf16_list<1024>((const uint16_t *)grad, C, d, k, idx, val, s);
             topk_kernel<uint16_t, 1024><<<grid, 1024, 0, s>>>((const uint16_t *)grad, d, k, idx, val);
+        }
     }
     return hipGetLastError();
 }

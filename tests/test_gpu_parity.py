@@ -214,6 +214,43 @@ def test_topk_bf16(C, d, k):
         assert rowwise_relerr(p.cpu().numpy(), rp) < TOL and rowwise_relerr(q.cpu().numpy(), rq) < TOL
 
 
+@pytest.mark.parametrize("d,k", [
+    (2048, 1), (2048, 256), (2056, 37), (4104, 100), (16384, 256), (16392, 5), (20008, 300), (65536, 1024),
+    (262144, 1), (262144, 777), (100000, 1024), (1000, 10), (20004, 64),
+])
+def test_topk_bf16_edge_cases(d, k):
+    """bfloat16 chunks through the two-sweep kernel (d % 8 == 0) and the general one: heavy tails, ties at the
+    threshold (certain with 8-bit mantissas), quantised and constant chunks (everything reaches the bound: the
+    list overflows and the chunk falls back), zeros, a single large entry, NaN and infinity patterns, values
+    only in the last / first part of the chunk."""
+    say("topk bf16 edge", d, k)
+    rng = np.random.default_rng(d * 7 + k)
+    C = 9
+    g = rng.standard_t(2.5, size=(C, d)).astype(np.float32)
+    g[1] = rng.integers(-2, 3, size=d).astype(np.float32)
+    g[2] = 0.0
+    g[3] = -1.5
+    g[4, : d // 2] = 0.0
+    g[5, d // 3:] = 0.0
+    g[6] = 0.0
+    g[6, d // 2] = 3.0
+    g[7] *= 1e-30                                            # tiny magnitudes: small exponents, still bfloat16 normals
+    bits = synth.f32_to_bf16_bits(g)
+    bits[8, 5] = 0x7fc0
+    bits[8, d - 1] = 0xffc1
+    bits[8, d // 2] = 0x7f80
+    bits[8, 7] = 0xff80
+    A = sgc.Matrix(d, 1024, At=None, seed=9)
+    idx = torch.empty((C, k), dtype=torch.int32, device=DEV)
+    val = torch.empty((C, k), dtype=torch.float32, device=DEV)
+    p = torch.empty((C, 1024), dtype=torch.float32, device=DEV)
+    sgc.sgc_sparsify_project(dev(bits.view(np.int16)), C * d, d, k, A, idx, val, p, None)
+    torch.cuda.synchronize()
+    ridx, rval = orc.topk(bits, k)
+    assert np.array_equal(idx.cpu().numpy(), ridx)
+    assert np.array_equal(val.cpu().numpy().view(np.uint32), rval.view(np.uint32))
+
+
 def test_empty_batch_is_a_no_op():
     A, _ = make_matrix("stored", 5, 64, 16)
     e = torch.empty(0, device=DEV)
