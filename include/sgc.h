@@ -383,6 +383,9 @@ sgc_status sgc_outer_refresh(float *B, const void *G, int32_t grad_type, int32_t
  * inside the OMP iterations, 8 sgc_outer_project, 9 sgc_outer_apply (its scatter of N counts as 5), 10 sgc_outer_refresh (its
  * passes over G count as 8).
  * Not thread-safe; meant for a single measuring thread. Errors: NULL, DEVICE.
+ * Independently of this, sgc_sparsify_project, sgc_adam_compressed, sgc_recover_omp, sgc_recover_omp_shared and
+ * sgc_apply put a named range (the function's name) around their launches through the ROCTx marker library
+ * when that library can be found at run time, so that `rocprofv3 --marker-trace` shows the four calls of a step.
  */
 enum { SGC_PROFILE_CLASSES = 11 };
 typedef struct sgc_profile {

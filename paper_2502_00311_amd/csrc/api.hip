@@ -122,6 +122,7 @@ sgc_status sgc_sparsify_project(const void *grad, int32_t grad_type, int64_t n, 
         return SGC_ERR_ALIGN;
     const int64_t C = n / d;
     hipStream_t s = (hipStream_t)stream;
+    RangeScope range("sgc_sparsify_project");
     // p and q are written by the projection afterwards: until then they are scratch for the top-k pass
     hipError_t e = launch_topk(grad, grad_type, C, d, k, idx, val, s, reinterpret_cast<int32_t *>(p), q,
                                q ? C * (int64_t)A->r : 0);
@@ -142,6 +143,7 @@ sgc_status sgc_adam_compressed(const float *p, const float *q, float *m, float *
     if (!aligned16(p) || !aligned16(q) || !aligned16(m) || !aligned16(v) || !aligned16(mhat) || !aligned16(vhat))
         return SGC_ERR_ALIGN;
     const double c1 = 1.0 - pow(h->beta1, (double)step), c2 = 1.0 - pow(h->beta2, (double)step);
+    RangeScope range("sgc_adam_compressed");
     return from_hip(launch_adam(p, q, m, v, mhat, vhat, count, (float)h->beta1, (float)(1.0 - h->beta1),
                                 (float)h->beta2, (float)(1.0 - h->beta2), (float)(1.0 / c1), (float)(1.0 / c2),
                                 (hipStream_t)stream));
@@ -187,6 +189,7 @@ sgc_status sgc_recover_omp(const float *y, int32_t N, const sgc_matrix *A, int32
     const OmpWorkspace w = carve_workspace(ws, N, A->d, A->r, k, workspace_need(A->mode, A->flags));
     if (ws_bytes < w.bytes)
         return SGC_ERR_WORKSPACE;
+    RangeScope range("sgc_recover_omp");
     return from_hip(launch_omp(y, N, make_view(A), k, sel, x, w, (hipStream_t)stream));
 }
 
@@ -284,6 +287,7 @@ sgc_status sgc_recover_omp_shared(const float *y_m, const float *y_v, int32_t C,
     const OmpWorkspace w = carve_workspace(ws, C, A->d, A->r, k, workspace_need(A->mode, A->flags));
     if (ws_bytes < w.bytes)
         return SGC_ERR_WORKSPACE;
+    RangeScope range("sgc_recover_omp_shared");
     return from_hip(launch_omp(y_m, C, make_view(A), k, sel, x, w, (hipStream_t)stream, y_v, z));
 }
 
@@ -318,6 +322,7 @@ sgc_status sgc_apply(float *W, int64_t C, int32_t d, int32_t k, const int32_t *s
         return SGC_ERR_NULL;
     if (C < 0 || d <= 0 || k <= 0 || k > d || k > 4096)
         return SGC_ERR_SHAPE;
+    RangeScope range("sgc_apply");
     return from_hip(launch_apply(W, C, d, k, sel_m, x_m, sel_v, x_v, (float)h->alpha, (float)h->eps, (float)h->lr,
                                  (hipStream_t)stream));
 }

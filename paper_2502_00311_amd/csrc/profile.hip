@@ -1,5 +1,8 @@
 // Host-side helpers: per-kernel timing with HIP events on the caller's stream (instrumentation only),
 // and the once-per-device raising of a kernel's dynamic-LDS limit.
+#include <dlfcn.h>
+
+#include <mutex>
 #include <vector>
 
 #include "sgc_internal.h"
@@ -57,6 +60,45 @@ hipError_t raise_dynamic_lds(const void *kernel, size_t bytes)
     if (e == hipSuccess)
         done.push_back(Done{kernel, dev, bytes});
     return e;
+}
+
+// ---- named ranges for external profilers (rocprofv3 --marker-trace): the marker library is looked up at run
+// time so that the library does not depend on it; without it the ranges are no-ops ----
+namespace {
+typedef int (*roctx_push_fn)(const char *);
+typedef int (*roctx_pop_fn)();
+roctx_push_fn g_roctx_push = nullptr;
+roctx_pop_fn g_roctx_pop = nullptr;
+std::once_flag g_roctx_once;
+void roctx_resolve()
+{
+    for (const char *name : {"librocprofiler-sdk-roctx.so.1", "librocprofiler-sdk-roctx.so", "libroctx64.so.4", "libroctx64.so"}) {
+        void *h = dlopen(name, RTLD_LAZY | RTLD_LOCAL);
+        if (!h)
+            continue;
+        roctx_push_fn push = reinterpret_cast<roctx_push_fn>(dlsym(h, "roctxRangePushA"));
+        roctx_pop_fn pop = reinterpret_cast<roctx_pop_fn>(dlsym(h, "roctxRangePop"));
+        if (push && pop) {
+            g_roctx_push = push;
+            g_roctx_pop = pop;
+            return;
+        }
+    }
+}
+} // namespace
+
+RangeScope::RangeScope(const char *name)
+{
+    std::call_once(g_roctx_once, roctx_resolve);
+    on = g_roctx_push != nullptr;
+    if (on)
+        g_roctx_push(name);
+}
+
+RangeScope::~RangeScope()
+{
+    if (on)
+        g_roctx_pop();
 }
 
 void profile_begin(int cls, hipStream_t s)

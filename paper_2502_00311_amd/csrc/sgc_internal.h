@@ -155,6 +155,14 @@ struct ProfileScope {
     }
 };
 
+// A named range around an entry point's launches, visible to rocprofv3 --marker-trace (a no-op when the marker
+// library is not there).
+struct RangeScope {
+    bool on;
+    explicit RangeScope(const char *name);
+    ~RangeScope();
+};
+
 // Raise a kernel's dynamic-LDS limit to `bytes`, once per kernel and device (the attribute belongs to the
 // device's copy of the code object). Host state without a lock, like the rest of the library.
 hipError_t raise_dynamic_lds(const void *kernel, size_t bytes);
