@@ -56,7 +56,9 @@ OmpWorkspace carve_workspace(void *base, int32_t N, int32_t d, int32_t r, int32_
         const int32_t slots = N <= SMALL_MAX_RHS && w.tiles_m < SMALL_MAX_GROUPS ? SMALL_MAX_GROUPS : w.tiles_m;
         w.partial = (uint64_t *)take(sizeof(uint64_t) * (size_t)N * slots * 2);
     }
-    w.sync = (uint32_t *)take(sizeof(uint32_t) * (64 + SMALL_MAX_GROUPS));
+    w.sync = (uint32_t *)take(sizeof(uint32_t) * 64);
+    // the single-launch recovery's exchange area: per right-hand side r tagged residual words and the selected position
+    w.xchg = N <= SMALL_MAX_RHS ? (uint64_t *)take(sizeof(uint64_t) * (size_t)N * (r + SMALL_XCHG_PAD)) : nullptr;
     w.bitmap = (uint32_t *)take(sizeof(uint32_t) * (size_t)N * w.words);
     // Rows of a generated matrix, in whole tiles. A matrix of at most 64 MiB gets a panel of its own (it
     // then stays in the 256 MiB memory-side cache). A larger one is regenerated inside the contraction, or
@@ -117,12 +119,19 @@ OmpWorkspace carve_recurrence(void *base, int32_t N, int32_t d, int32_t r, int32
 __global__ __launch_bounds__(256) void omp_init_kernel(const float *__restrict__ y, int32_t r, int32_t words,
                                                        double *__restrict__ res64, float *__restrict__ res32,
                                                        uint32_t *__restrict__ bitmap, int32_t res_split,
-                                                       uint32_t *__restrict__ sync)
+                                                       uint32_t *__restrict__ sync, uint64_t *__restrict__ keys,
+                                                       int32_t keys_per_rhs, uint64_t *__restrict__ xchg,
+                                                       int32_t xchg_per_rhs)
 {
     const int64_t n = blockIdx.x;
-    if (n == 0)
-        for (int i = threadIdx.x; i < 64 + SMALL_MAX_GROUPS; i += 256)
-            sync[i] = 0u; // a fill by a kernel, not a memset node: the call may be captured in a graph
+    // fills by a kernel, not memset nodes: the call may be captured in a graph
+    if (n == 0 && threadIdx.x < 64)
+        sync[threadIdx.x] = 0u;
+    // a small batch may go to the single-launch recovery, whose tagged words must not carry tags of an earlier call
+    for (int32_t i = threadIdx.x; i < keys_per_rhs; i += 256)
+        keys[n * keys_per_rhs + i] = 0ull;
+    for (int32_t i = threadIdx.x; i < xchg_per_rhs; i += 256)
+        xchg[n * xchg_per_rhs + i] = 0ull;
     uint16_t *res16 = reinterpret_cast<uint16_t *>(res32);
     for (int32_t j = threadIdx.x; j < r; j += 256) {
         const float v = y[n * r + j];
@@ -180,17 +189,11 @@ __device__ __forceinline__ float4 column_quad(const MatrixView &A, int32_t i, in
 // grid (N, slices). Every slice of a right-hand side repeats the (cheap) selection so that no
 // grid-wide synchronisation is needed; slice 0 also stores the column and the scalars.
 // dynamic LDS: float a_col[r]
-// COHERENT (the single-launch recovery): data that another workgroup of the same launch wrote or will read - the
-// tile keys, the selected position - moves with device-scope atomic loads and stores, which pass by the caches
-// that are not coherent between workgroups on different XCDs; everything else belongs to this workgroup alone.
-__device__ __forceinline__ uint64_t load_key(const uint64_t *p, bool coherent)
-{
-    return coherent ? __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *p;
-}
-
-template <bool GENERATED, int PICK_THREADS, bool COHERENT = false>
+// part_in: where the tile keys of right-hand side n are (default: the workspace; the single-launch recovery hands
+// over a copy in LDS that it has collected from the other workgroups)
+template <bool GENERATED, int PICK_THREADS>
 __device__ __forceinline__ void pick_body(const MatrixView &A, const IterArgs &P, const int64_t n, const int slice,
-                                          const int nslices, unsigned char *smem)
+                                          const int nslices, unsigned char *smem, const uint64_t *part_in = nullptr)
 {
     constexpr int PICK_WAVES = PICK_THREADS / 64;
     float *a_col = reinterpret_cast<float *>(smem);
@@ -207,13 +210,13 @@ __device__ __forceinline__ void pick_body(const MatrixView &A, const IterArgs &P
         return; // no earlier selection falls to this slice
     const OmpWorkspace &W = P.ws;
     const int32_t np = W.tiles_m * 2;
-    const uint64_t *part = W.partial + n * np;
+    const uint64_t *part = part_in ? part_in : W.partial + n * np;
     const double *res64 = W.res64 + n * r;
 
     // (1) float maximum over the tile partials
     uint64_t best = 0;
     for (int32_t e = tid; e < np; e += PICK_THREADS) {
-        const uint64_t v = load_key(part + e, COHERENT);
+        const uint64_t v = part[e];
         best = v > best ? v : best;
     }
 #pragma unroll
@@ -234,7 +237,7 @@ __device__ __forceinline__ void pick_body(const MatrixView &A, const IterArgs &P
 
     // (2) candidates: every kept pair whose float score is within the tolerance of the maximum
     for (int32_t e = tid; e < np; e += PICK_THREADS) {
-        const uint64_t v = load_key(part + e, COHERENT);
+        const uint64_t v = part[e];
         if (v != 0 && __uint_as_float((uint32_t)(v >> 32)) >= thr) {
             const int32_t slot = atomicAdd(&s_ncand, 1);
             if (slot < PICK_CAND_CAP)
@@ -260,7 +263,7 @@ __device__ __forceinline__ void pick_body(const MatrixView &A, const IterArgs &P
             if (listed) {
                 i = s_cand[e];
             } else {
-                const uint64_t v = load_key(part + e, COHERENT);
+                const uint64_t v = part[e];
                 if (v == 0 || !(__uint_as_float((uint32_t)(v >> 32)) >= thr))
                     continue;
                 i = (int32_t)(0xffffffffu - (uint32_t)v);
@@ -353,8 +356,6 @@ __device__ __forceinline__ void pick_body(const MatrixView &A, const IterArgs &P
         W.gb[n * 2] = g;
         W.gb[n * 2 + 1] = b;
         P.sel[n * k + it] = lam;
-        if (COHERENT)
-            __hip_atomic_store(P.sel + n * k + it, lam, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         W.bitmap[n * W.words + (lam >> 5)] |= 1u << (lam & 31);
     }
 
@@ -653,12 +654,17 @@ __device__ __forceinline__ void update_body(const IterArgs &P, const int32_t r, 
                 *reinterpret_cast<uint2 *>(o) = make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
                 *reinterpret_cast<uint2 *>(o + 64) = make_uint2(l[0] | ((uint32_t)l[1] << 16), l[2] | ((uint32_t)l[3] << 16));
             } else {
-                if (COHERENT) { // read by every workgroup of the launch in its next correlation phase
-                    uint32_t *o = reinterpret_cast<uint32_t *>(W.res32 + n * r + 4 * jb);
-                    __hip_atomic_store(o + 0, __float_as_uint((float)e0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    __hip_atomic_store(o + 1, __float_as_uint((float)e1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    __hip_atomic_store(o + 2, __float_as_uint((float)e2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    __hip_atomic_store(o + 3, __float_as_uint((float)e3), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (COHERENT) {
+                    // the single-launch recovery: every workgroup of the launch reads the float residual in its
+                    // next correlation phase. Each value travels in a 64-bit word with the number of the
+                    // iteration in its upper half, stored with one device-scope atomic store: a reader sees the
+                    // old word or the new one, never a mixture, and needs no other signal
+                    uint64_t *o = W.xchg + n * (int64_t)(r + SMALL_XCHG_PAD) + 4 * jb;
+                    const uint64_t tag = (uint64_t)(it + 1) << 32;
+                    __hip_atomic_store(o + 0, tag | __float_as_uint((float)e0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(o + 1, tag | __float_as_uint((float)e1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(o + 2, tag | __float_as_uint((float)e2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(o + 3, tag | __float_as_uint((float)e3), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 } else {
                     reinterpret_cast<float4 *>(W.res32 + n * r)[jb] =
                         make_float4((float)e0, (float)e1, (float)e2, (float)e3);
@@ -733,61 +739,43 @@ __global__ __launch_bounds__(REFIT_THREADS) void refit_kernel(IterArgs P, const 
 // The whole recovery of a small batch in ONE launch (at most SMALL_MAX_RHS right-hand sides, resident rows
 // of At that fit the workgroups' LDS together). With so few right-hand sides every kernel of the
 // iteration is a few microseconds of work behind a launch, and three dependent launches per iteration
-// are the cost (28 us per iteration for one chunk of d = 4096, r = 256). Here G workgroups stay resident
+// are the cost (27 us per iteration for one chunk of d = 4096, r = 256). Here G workgroups stay resident
 // for all k iterations; each keeps a slice of rows of At in LDS for the whole call, so the matrix is read
 // from memory once, not once per iteration:
 //   phase 1 (all workgroups)   correlations of the workgroup's rows with the N residuals on the vector ALUs
-//                              (a wavefront per row, float accumulation; with so few right-hand sides there is
-//                              nothing for the matrix cores), scaled and masked, two best keys per right-hand side
-//                              and workgroup written where the contraction's epilogue would put its tile keys
-//   grid barrier
-//   phase 2 (workgroup n < N)  the selection and least-squares update of right-hand side n: exactly the bodies
-//                              of pick_kernel and update_kernel (double re-scoring, App. B's factor update,
-//                              residual in double)
-//   grid barrier, then every workgroup fetches the new residuals.
-// The barrier is one word per workgroup in the workspace (cleared by omp_init_kernel): see small_grid_barrier.
-// All G workgroups must be resident at once: G is at most the number of CUs and a workgroup fits a CU, so they
-// are whenever the kernel gets the device; if they are not within SMALL_SPIN_LIMIT polls (seconds: some other
-// work holds the CUs), the polling wavefront raises the abort flag, every workgroup leaves at its next barrier
-// and the selected positions are set to -1 (values 0, which sgc_apply skips) - the grid always drains.
+//                              (four lanes per row, float accumulation; with so few right-hand sides there is
+//                              nothing for the matrix cores), scaled and masked; the two best keys per
+//                              right-hand side go to the workspace, tagged with the iteration
+//   phase 2 (workgroup n < N)  collects the keys of right-hand side n from all workgroups, then runs its selection
+//                              and least-squares update: exactly the bodies of pick_kernel and update_kernel
+//                              (double re-scoring, App. B's factor update, residual in double); the float
+//                              residual and the selected position go out as tagged words
+//   every workgroup            collects the new residuals and selected positions, and goes on.
+// There is no barrier: every word that crosses between workgroups is 64 bits wide, carries the number of the
+// iteration it belongs to, and is stored and loaded with device-scope atomics (which pass by the caches that
+// are not coherent between XCDs), so a reader polls the data itself until every word shows the tag it waits
+// for - one trip to the memory side per exchange, two per iteration. A writer cannot overwrite a word that a
+// slower workgroup still needs: the keys of iteration it + 1 are written after the residual of iteration it has
+// been read, and that residual is replaced only after all keys of iteration it + 1 have arrived.
+// All G workgroups must be resident at once: G is at most SMALL_MAX_GROUPS and a workgroup fits a CU, so they
+// are whenever the kernel gets the device; if some word does not arrive within SMALL_SPIN_LIMIT polls (seconds:
+// some other work holds the CUs), the poller raises the give-up flag in the workspace, every workgroup leaves at
+// its next poll, and the selected positions of the unfinished right-hand sides are set to -1 (values 0, which
+// sgc_apply skips) - the grid always drains.
 constexpr uint32_t SMALL_SPIN_LIMIT = 1u << 22;
 constexpr int SMALL_THREADS = 256;
 constexpr int SMALL_ROW_PAD = 4; // floats between rows in LDS: rows read side by side by a wavefront fall in different banks
 
-// Barrier over the G workgroups of the launch: workgroup g publishes the number of the barrier in its own word
-// (no read-modify-write, G different addresses), one wavefront polls all G words with one load per 64 of them.
-// Data exchanged across the barrier is stored and loaded with device-scope atomics, so the only ordering needed is
-// that a wavefront's stores are acknowledged before its workgroup's word is published.
-__device__ __forceinline__ bool small_grid_barrier(uint32_t *sync, int G, int g, uint32_t epoch, int32_t *s_flag)
+// key as the selection reads it (score bits, ~position) <-> the same with the iteration's tag in bits 24..31 of
+// the low word (positions are below 2^24 here, so those bits of ~position are all ones); 0 = no candidate
+__device__ __forceinline__ uint64_t small_tag_key(uint64_t key, uint32_t tag)
 {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (threadIdx.x < 64) {
-        uint32_t *flags = sync + 64, *abort_flag = sync;
-        if (threadIdx.x == 0)
-            __hip_atomic_store(flags + g, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        uint32_t spins = 0;
-        int32_t stop = 0;
-        for (;;) {
-            bool ok = true;
-            for (int q = threadIdx.x; q < G; q += 64)
-                ok = ok && __hip_atomic_load(flags + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= epoch;
-            if (__builtin_amdgcn_ballot_w64(!ok) == 0ull)
-                break;
-            const uint32_t ab = __hip_atomic_load(abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (__builtin_amdgcn_ballot_w64(ab != 0u) != 0ull || ++spins > SMALL_SPIN_LIMIT) {
-                if (threadIdx.x == 0)
-                    __hip_atomic_store(abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                stop = 1;
-                break;
-            }
-            __builtin_amdgcn_s_sleep(1);
-        }
-        if (threadIdx.x == 0)
-            *s_flag = stop;
-    }
-    __syncthreads();
-    return *s_flag != 0;
+    return (key & 0xffffffff00ffffffull) | ((uint64_t)tag << 24);
+}
+__device__ __forceinline__ uint64_t small_untag_key(uint64_t word)
+{
+    const uint64_t body = word & 0xffffffff00ffffffull;
+    return body == 0ull ? 0ull : (body | 0xff000000ull);
 }
 
 // dynamic LDS: float rows[rows_per_group][r + SMALL_ROW_PAD]; float inv[rows_per_group rounded up to 4];
@@ -797,7 +785,7 @@ __global__ __launch_bounds__(SMALL_THREADS) void omp_small_kernel(MatrixView A, 
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     __shared__ uint64_t s_keys[SMALL_THREADS / 64][SMALL_MAX_RHS][2];
-    __shared__ int32_t s_flag;
+    __shared__ uint64_t s_part[2 * SMALL_MAX_GROUPS]; // the keys of this workgroup's right-hand side, all workgroups
     const int32_t r = A.r, r4 = r >> 2, k = P.k, d = A.d;
     const int32_t ld = r + SMALL_ROW_PAD;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -810,6 +798,8 @@ __global__ __launch_bounds__(SMALL_THREADS) void omp_small_kernel(MatrixView A, 
     unsigned char *taken = reinterpret_cast<unsigned char *>(res + (size_t)N * r);
     unsigned char *body = smem + body_offset;
     const OmpWorkspace &W = P.ws;
+    uint32_t *giveup = W.sync;
+    const int32_t xw = r + SMALL_XCHG_PAD; // exchange words per right-hand side
 
     // the workgroup's rows of At and their reciprocal norms, once for the whole call; the residuals = y
     for (int32_t e = tid; e < rows * r4; e += SMALL_THREADS) {
@@ -825,11 +815,30 @@ __global__ __launch_bounds__(SMALL_THREADS) void omp_small_kernel(MatrixView A, 
         taken[e] = 0;
     __syncthreads();
 
+    // polls until `ready` holds in every thread; false if the launch gives up. `fetch` loads this thread's words
+    // and says whether all of them carry the tag
+    auto wait_for = [&](auto &&fetch) -> bool {
+        for (uint32_t spins = 0;; ++spins) {
+            const bool ok = fetch();
+            if (__syncthreads_and(ok ? 1 : 0))
+                return true;
+            if ((spins & 15u) == 15u) { // now and then: has the launch given up, or is it time to
+                const bool stop = spins > SMALL_SPIN_LIMIT ||
+                                  __hip_atomic_load(giveup, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
+                if (__syncthreads_or(stop ? 1 : 0)) {
+                    if (tid == 0)
+                        __hip_atomic_store(giveup, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    return false;
+                }
+            }
+        }
+    };
+
     // phase 1 mapping: a wavefront takes 16 rows at a time, four lanes per row, each lane a quarter of the depth
     const int sub = lane >> 2, part = lane & 3;
     bool aborted = false;
-    uint32_t epoch = 0;
-    for (int32_t it = 0; it < k; ++it) {
+    for (int32_t it = 0; it < k && !aborted; ++it) {
+        const uint32_t tag = (uint32_t)(it + 1);
         // ---- phase 1: this workgroup's rows against every residual ----
         uint64_t best[SMALL_MAX_RHS], second[SMALL_MAX_RHS];
 #pragma unroll
@@ -879,7 +888,6 @@ __global__ __launch_bounds__(SMALL_THREADS) void omp_small_kernel(MatrixView A, 
 #pragma unroll
                 for (int off = 32; off > 0; off >>= 1) {
                     const uint64_t ob = shfl_xor_u64(best[u], off), os = shfl_xor_u64(second[u], off);
-                    // merge two (best, second) pairs
                     const uint64_t hi = ob > best[u] ? ob : best[u];
                     const uint64_t mid = ob > best[u] ? best[u] : ob;
                     const uint64_t s2 = os > second[u] ? os : second[u];
@@ -904,45 +912,65 @@ __global__ __launch_bounds__(SMALL_THREADS) void omp_small_kernel(MatrixView A, 
                     sc = lo < sc ? sc : lo;
                 }
             }
-            uint64_t *o = W.partial + ((int64_t)tid * G + g) * 2; // W.tiles_m == G
-            __hip_atomic_store(o, b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(o + 1, sc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        if (small_grid_barrier(W.sync, G, g, ++epoch, &s_flag)) {
-            aborted = true;
-            break;
+            uint64_t *o = W.partial + ((int64_t)tid * G + g) * 2;
+            __hip_atomic_store(o, small_tag_key(b, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(o + 1, small_tag_key(sc, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         // ---- phase 2: selection and least-squares update, one workgroup per right-hand side ----
         if (g < N) {
+            const uint64_t *mine = W.partial + (int64_t)g * G * 2;
+            if (!wait_for([&]() {
+                    bool ok = true;
+                    for (int32_t e = tid; e < 2 * G; e += SMALL_THREADS) {
+                        const uint64_t word = __hip_atomic_load(mine + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        ok = ok && (uint32_t)((word >> 24) & 0xffu) == tag;
+                        s_part[e] = small_untag_key(word);
+                    }
+                    return ok;
+                })) {
+                aborted = true;
+                break;
+            }
             IterArgs Q = P;
             Q.it = it;
-            pick_body<false, SMALL_THREADS, true>(A, Q, g, 0, 1, body);
+            pick_body<false, SMALL_THREADS>(A, Q, g, 0, 1, body, s_part); // Q.ws.tiles_m == G
             __threadfence_block();
             __syncthreads();
             update_body<2, 4, true>(Q, r, g, 0, 1, body);
+            if (tid == 0) // the selected position, for the other workgroups' masks
+                __hip_atomic_store(W.xchg + (int64_t)g * xw + r, ((uint64_t)tag << 32) | (uint32_t)P.sel[(int64_t)g * k + it],
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        if (small_grid_barrier(W.sync, G, g, ++epoch, &s_flag)) {
+        if (it + 1 == k)
+            break; // nobody needs the last residual
+        // ---- every workgroup: the new residuals and selected positions ----
+        if (!wait_for([&]() {
+                bool ok = true;
+                for (int32_t e = tid; e < N * (r + 1); e += SMALL_THREADS) {
+                    const int32_t u = e / (r + 1), j = e - u * (r + 1);
+                    const uint64_t word = __hip_atomic_load(W.xchg + (int64_t)u * xw + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    const bool mine_ok = (uint32_t)(word >> 32) == tag;
+                    ok = ok && mine_ok;
+                    if (mine_ok) {
+                        if (j < r) {
+                            res[(size_t)u * r + j] = __uint_as_float((uint32_t)word);
+                        } else {
+                            const int32_t lam = (int32_t)(uint32_t)word - row0;
+                            if (lam >= 0 && lam < rows)
+                                taken[u * rows_per_group + lam] = 1;
+                        }
+                    }
+                }
+                return ok;
+            })) {
             aborted = true;
             break;
         }
-        if (it + 1 < k) {
-            for (int32_t e = tid; e < N * (r >> 1); e += SMALL_THREADS) {
-                const uint64_t v = __hip_atomic_load(reinterpret_cast<const uint64_t *>(W.res32) + e, __ATOMIC_RELAXED,
-                                                     __HIP_MEMORY_SCOPE_AGENT);
-                reinterpret_cast<uint64_t *>(res)[e] = v;
-            }
-            if (tid < N) {
-                const int32_t lam = __hip_atomic_load(P.sel + (int64_t)tid * k + it, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - row0;
-                if (lam >= 0 && lam < rows)
-                    taken[tid * rows_per_group + lam] = 1;
-            }
-            __syncthreads();
-        }
     }
-    if (aborted && g == 0)
-        for (int32_t e = tid; e < N * k; e += SMALL_THREADS) {
-            P.sel[e] = -1;
-            P.x[e] = 0.f;
+    if (aborted && g < N) // the right-hand side this workgroup serves was not finished
+        for (int32_t e = tid; e < k; e += SMALL_THREADS) {
+            P.sel[(int64_t)g * k + e] = -1;
+            P.x[(int64_t)g * k + e] = 0.f;
         }
 }
 
@@ -980,6 +1008,8 @@ static OmpWorkspace shift_workspace(const OmpWorkspace &ws, int32_t n0, int32_t 
     w.bitmap += (int64_t)n0 * ws.words;
     w.wv += (int64_t)n0 * k;
     w.gb += (int64_t)n0 * 2;
+    if (w.xchg)
+        w.xchg += (int64_t)n0 * (r + SMALL_XCHG_PAD);
     if (w.rc_p) { // the recurrence's arrays
         w.rc_p += (int64_t)n0 * ws.rc_d;
         w.rc_B += (int64_t)n0 * ws.rc_head * ws.rc_d;
@@ -1070,11 +1100,11 @@ static void omp_select_update(const OmpPlan &pl, const MatrixView &A, const floa
 
 // Whether a recovery is served by the single-launch kernel, and its shape: at most SMALL_MAX_RHS right-hand sides,
 // resident rows without any option, and a matrix whose rows fit the LDS of at most SMALL_MAX_GROUPS workgroups
-// (96 KiB of rows each at most; 64 KiB slices are preferred). The limits are where it was measured to win: a
-// barrier over 64 workgroups costs about 4 us (a store and a poll that both travel to the memory side, since
-// the workgroups sit on different XCDs), two per iteration plus the reload of the residuals 10 us, the two
-// bodies 4 + 6 us, against 27 us per iteration for three dependent launches. With 8 right-hand sides or 256
-// workgroups the launches are no slower any more (0.96 vs 0.87 ms at N = 8, d = 4096, r = 256, k = 32).
+// (96 KiB of rows each at most; 64 KiB slices are preferred). The limits are where it was measured to win: an
+// exchange between workgroups on different XCDs costs about 3.5 us, two per iteration, the correlation phase
+// 1.5 us, the two bodies 4 + 6 us: 18.5 us against 27 us per iteration for three dependent launches. With 8
+// right-hand sides or 256 workgroups the launches are no slower any more (0.87 vs 0.87 ms at N = 8, d = 4096,
+// r = 256, k = 32).
 struct SmallPlan {
     int32_t groups, rows_per_group, body_offset;
     size_t smem;
@@ -1097,7 +1127,7 @@ static bool small_plan(const OmpPlan &pl, int32_t N, int32_t k, SmallPlan &sp)
 {
     const MatrixView &A = pl.Apick;
     if (N > SMALL_MAX_RHS || A.generated || A.gram || pl.screen || pl.recurrence || pl.narrow || k > 128 || A.r > 2048 ||
-        (int64_t)N * A.r > 8192 || (A.flags & SGC_MATRIX_FLAG_MULTI_LAUNCH))
+        (int64_t)N * A.r > 8192 || A.d >= (1 << 24) || (A.flags & SGC_MATRIX_FLAG_MULTI_LAUNCH))
         return false;
     int cus = device_cu_count();
     if (cus > SMALL_MAX_GROUPS)
@@ -1208,8 +1238,11 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
     }
     {
         ProfileScope prof(KC_OTHER, s);
+        const bool small = N <= SMALL_MAX_RHS;
         omp_init_kernel<<<dim3((unsigned)N), 256, 0, s>>>(y, A.r, ws.words, ws.res64, ws.res32, ws.bitmap,
-                                                          pl.screen ? 1 : 0, ws.sync);
+                                                          pl.screen ? 1 : 0, ws.sync, ws.partial,
+                                                          small ? 2 * SMALL_MAX_GROUPS : 0, ws.xchg,
+                                                          small ? A.r + SMALL_XCHG_PAD : 0);
     }
     pl.Apick = A;
     const bool whole_matrix_panel = pl.panels && ws.panel_rows >= A.d;

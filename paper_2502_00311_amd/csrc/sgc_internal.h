@@ -32,6 +32,7 @@ inline int corr_tiles_m(int d) { return (d + CORR_BM - 1) / CORR_BM; }
 // the single-launch recovery serves at most this many right-hand sides, with at most this many workgroups
 constexpr int SMALL_MAX_RHS = 4;
 constexpr int SMALL_MAX_GROUPS = 64;
+constexpr int SMALL_XCHG_PAD = 8; // words after the r residual words of a right-hand side: [0] the selected position
 
 // Workspace layout of sgc_recover_omp (all offsets 256-byte aligned).
 struct OmpWorkspace {
@@ -65,8 +66,8 @@ struct OmpWorkspace {
     int32_t rc_head;   // iterations served by the recurrence (the rest by the contraction)
     int32_t rc_d;      // d (row length of rc_p and rc_B)
     double *cvec;      // [N][k] coordinates c_t of the newest column, exported by update_kernel
-    uint32_t *sync;    // [64 + SMALL_MAX_GROUPS] abort flag (word 0) and one arrival word per workgroup (from word 64)
-                       // of the single-launch recovery for small batches
+    uint32_t *sync;    // [64] word 0: the give-up flag of the single-launch recovery for small batches
+    uint64_t *xchg;    // [N][r + SMALL_XCHG_PAD] that kernel's exchange area (tagged residual words, selected position)
 };
 // `need`: which optional regions the matrix calls for. A stored matrix is read in place (no column copies, no
 // panel); the bfloat16 planes exist only for a matrix that asks for the screening contraction.
