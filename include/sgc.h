@@ -77,10 +77,10 @@ enum { SGC_MATRIX_FLAG_SCREEN_BF16 = 1 };
 enum { SGC_MATRIX_FLAG_MATERIALIZE = 2 };
 /*
  * Option bit of sgc_matrix.flags, read by sgc_recover_omp* only. A batch of at most 4 right-hand sides on
- * resident rows (a stored matrix, or a generated one of at most 64 MiB) of at most 6 MiB, with r <= 2048 and
- * k <= 128, is recovered in ONE launch: up to 64 workgroups stay resident for all k iterations, keep their rows
- * of At in LDS and exchange keys and residuals through tagged words in the workspace, polling until they
- * arrive. That needs all its workgroups on the device at once, which holds whenever the kernel gets the GPU to
+ * resident rows (a stored matrix, or a generated one of at most 64 MiB) of at most 6 MiB, with r <= 2048,
+ * k <= 64 and k r <= 16384, is recovered in ONE launch: up to 68 workgroups stay resident for all k iterations,
+ * keep their rows of At (or the least-squares state of a right-hand side) in LDS and exchange keys and
+ * residuals through tagged words in the workspace, polling until they arrive. That needs all its workgroups on the device at once, which holds whenever the kernel gets the GPU to
  * itself; a caller that shares the GPU with other long-running kernels sets this bit to keep the three
  * launches per iteration (same results). Should a word of the single launch not arrive within seconds, the
  * call gives up: for every right-hand side that was not finished sel is filled with -1 and x with 0, which

@@ -186,32 +186,21 @@ __device__ __forceinline__ float4 column_quad(const MatrixView &A, int32_t i, in
     return reinterpret_cast<const float4 *>(A.At + (int64_t)i * A.r)[jb];
 }
 
-// grid (N, slices). Every slice of a right-hand side repeats the (cheap) selection so that no
-// grid-wide synchronisation is needed; slice 0 also stores the column and the scalars.
-// dynamic LDS: float a_col[r]
-// part_in: where the tile keys of right-hand side n are (default: the workspace; the single-launch recovery hands
-// over a copy in LDS that it has collected from the other workgroups)
+// The selection of one right-hand side from its np tile keys (App. B's rule, decided in double): the float maximum,
+// the candidates within RESCORE_TOL of it, their re-scoring against the double residual res64[r], lowest
+// position on equal scores. Called by a whole workgroup; every thread returns the selected position.
 template <bool GENERATED, int PICK_THREADS>
-__device__ __forceinline__ void pick_body(const MatrixView &A, const IterArgs &P, const int64_t n, const int slice,
-                                          const int nslices, unsigned char *smem, const uint64_t *part_in = nullptr)
+__device__ __forceinline__ int32_t select_lambda(const MatrixView &A, const uint64_t *part, const int32_t np,
+                                                 const double *res64)
 {
     constexpr int PICK_WAVES = PICK_THREADS / 64;
-    float *a_col = reinterpret_cast<float *>(smem);
     __shared__ uint64_t s_u64[PICK_WAVES];
-    __shared__ double s_red[2][PICK_WAVES];
     __shared__ double s_cscore[PICK_WAVES];
     __shared__ int32_t s_cidx[PICK_WAVES];
     __shared__ int32_t s_cand[PICK_CAND_CAP];
     __shared__ int32_t s_lambda, s_ncand;
-
-    const int32_t r = A.r, r4 = A.r >> 2, k = P.k, it = P.it;
+    const int32_t r4 = A.r >> 2;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (slice != 0 && slice * PICK_WAVES >= it)
-        return; // no earlier selection falls to this slice
-    const OmpWorkspace &W = P.ws;
-    const int32_t np = W.tiles_m * 2;
-    const uint64_t *part = part_in ? part_in : W.partial + n * np;
-    const double *res64 = W.res64 + n * r;
 
     // (1) float maximum over the tile partials
     uint64_t best = 0;
@@ -306,7 +295,26 @@ __device__ __forceinline__ void pick_body(const MatrixView &A, const IterArgs &P
         s_lambda = bi;
     }
     __syncthreads();
-    const int32_t lam = s_lambda;
+    return s_lambda;
+}
+
+// grid (N, slices). Every slice of a right-hand side repeats the (cheap) selection so that no
+// grid-wide synchronisation is needed; slice 0 also stores the column and the scalars.
+// dynamic LDS: float a_col[r]
+template <bool GENERATED, int PICK_THREADS>
+__device__ __forceinline__ void pick_body(const MatrixView &A, const IterArgs &P, const int64_t n, const int slice,
+                                          const int nslices, unsigned char *smem)
+{
+    constexpr int PICK_WAVES = PICK_THREADS / 64;
+    float *a_col = reinterpret_cast<float *>(smem);
+    __shared__ double s_red[2][PICK_WAVES];
+    const int32_t r = A.r, r4 = A.r >> 2, k = P.k, it = P.it;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (slice != 0 && slice * PICK_WAVES >= it)
+        return; // no earlier selection falls to this slice
+    const OmpWorkspace &W = P.ws;
+    const int32_t lam = select_lambda<GENERATED, PICK_THREADS>(A, W.partial + n * (int64_t)(W.tiles_m * 2), W.tiles_m * 2,
+                                                               W.res64 + n * r);
     // with a table of column inner products, w_t = <A_:lambda_t, a> is a gather from its row lambda:
     // requested here, before the column itself is fetched, so that both travel at the same time
     constexpr int GQ = (1024 + PICK_THREADS - 1) / PICK_THREADS; // k <= 1024
@@ -736,35 +744,40 @@ __global__ __launch_bounds__(REFIT_THREADS) void refit_kernel(IterArgs P, const 
 }
 
 // ---------------------------------------------------------------------------------------------
-// The whole recovery of a small batch in ONE launch (at most SMALL_MAX_RHS right-hand sides, resident rows
-// of At that fit the workgroups' LDS together). With so few right-hand sides every kernel of the
-// iteration is a few microseconds of work behind a launch, and three dependent launches per iteration
-// are the cost (27 us per iteration for one chunk of d = 4096, r = 256). Here G workgroups stay resident
-// for all k iterations; each keeps a slice of rows of At in LDS for the whole call, so the matrix is read
-// from memory once, not once per iteration:
-//   phase 1 (all workgroups)   correlations of the workgroup's rows with the N residuals on the vector ALUs
-//                              (four lanes per row, float accumulation; with so few right-hand sides there is
-//                              nothing for the matrix cores), scaled and masked; the two best keys per
-//                              right-hand side go to the workspace, tagged with the iteration
-//   phase 2 (workgroup n < N)  collects the keys of right-hand side n from all workgroups, then runs its selection
-//                              and least-squares update: exactly the bodies of pick_kernel and update_kernel
-//                              (double re-scoring, App. B's factor update, residual in double); the float
-//                              residual and the selected position go out as tagged words
-//   every workgroup            collects the new residuals and selected positions, and goes on.
+// The whole recovery of a small batch in ONE launch (at most SMALL_MAX_RHS right-hand sides, k <= 64,
+// k r <= 16384, resident rows of At that fit the workgroups' LDS together). With so few right-hand sides every
+// kernel of the iteration is a few microseconds of work behind a launch, and three dependent launches per
+// iteration are the cost (27 us per iteration for one chunk of d = 4096, r = 256). Here G + N workgroups stay
+// resident for all k iterations and nothing but a few words per iteration travels through memory:
+//   workers (G workgroups)   each keeps a slice of rows of At in LDS for the whole call (the matrix is read from
+//                            memory once, not once per iteration); per iteration the correlations of its rows
+//                            with the N residuals on the vector ALUs (four lanes per row, float accumulation;
+//                            with so few right-hand sides there is nothing for the matrix cores), scaled and
+//                            masked; the two best keys per right-hand side go out, tagged with the iteration
+//   owners (N workgroups)    each keeps the whole least-squares state of one right-hand side in LDS: the selected
+//                            columns, the inverse Cholesky factor, coefficients, solution and the double
+//                            residual. Per iteration: collect the keys of all workers, select (float maximum,
+//                            double re-scoring of the near-maximal candidates: the same routine as pick_kernel),
+//                            fetch the new column, App. B's factor update and the residual in double (the
+//                            formulas of update_kernel); the float residual and the selected position go out
+//                            as tagged words
+//   workers                  collect the new residuals and selected positions, and go on.
 // There is no barrier: every word that crosses between workgroups is 64 bits wide, carries the number of the
 // iteration it belongs to, and is stored and loaded with device-scope atomics (which pass by the caches that
 // are not coherent between XCDs), so a reader polls the data itself until every word shows the tag it waits
 // for - one trip to the memory side per exchange, two per iteration. A writer cannot overwrite a word that a
 // slower workgroup still needs: the keys of iteration it + 1 are written after the residual of iteration it has
 // been read, and that residual is replaced only after all keys of iteration it + 1 have arrived.
-// All G workgroups must be resident at once: G is at most SMALL_MAX_GROUPS and a workgroup fits a CU, so they
-// are whenever the kernel gets the device; if some word does not arrive within SMALL_SPIN_LIMIT polls (seconds:
-// some other work holds the CUs), the poller raises the give-up flag in the workspace, every workgroup leaves at
-// its next poll, and the selected positions of the unfinished right-hand sides are set to -1 (values 0, which
-// sgc_apply skips) - the grid always drains.
+// All workgroups must be resident at once: there are at most SMALL_MAX_GROUPS + SMALL_MAX_RHS and each fits a CU,
+// so they are whenever the kernel gets the device; if some word does not arrive within SMALL_SPIN_LIMIT polls
+// (seconds: some other work holds the CUs), the poller raises the give-up flag in the workspace, every workgroup
+// leaves at its next poll, and the selected positions of the unfinished right-hand sides are set to -1 (values
+// 0, which sgc_apply skips) - the grid always drains.
 constexpr uint32_t SMALL_SPIN_LIMIT = 1u << 22;
 constexpr int SMALL_THREADS = 256;
 constexpr int SMALL_ROW_PAD = 4; // floats between rows in LDS: rows read side by side by a wavefront fall in different banks
+constexpr int SMALL_MAX_K = 64;
+constexpr int SMALL_MAX_KR = 16384;
 
 // key as the selection reads it (score bits, ~position) <-> the same with the iteration's tag in bits 24..31 of
 // the low word (positions are below 2^24 here, so those bits of ~position are all ones); 0 = no candidate
@@ -778,28 +791,208 @@ __device__ __forceinline__ uint64_t small_untag_key(uint64_t word)
     return body == 0ull ? 0ull : (body | 0xff000000ull);
 }
 
-// dynamic LDS: float rows[rows_per_group][r + SMALL_ROW_PAD]; float inv[rows_per_group rounded up to 4];
-//              float res[N][r]; unsigned char taken[N][rows_per_group]; then (16-byte aligned) the scratch of the bodies
-__global__ __launch_bounds__(SMALL_THREADS) void omp_small_kernel(MatrixView A, IterArgs P, int32_t N, int32_t rows_per_group,
-                                                                  int32_t body_offset)
+// polls until `fetch` (which loads this thread's words and says whether all of them carry the tag) holds in
+// every thread of the workgroup; false if the launch gives up
+template <typename Fetch>
+__device__ __forceinline__ bool small_wait(uint32_t *giveup, Fetch &&fetch)
+{
+    for (uint32_t spins = 0;; ++spins) {
+        const bool ok = fetch();
+        if (__syncthreads_and(ok ? 1 : 0))
+            return true;
+        if ((spins & 15u) == 15u) { // now and then: has the launch given up, or is it time to
+            const bool stop = spins > SMALL_SPIN_LIMIT ||
+                              __hip_atomic_load(giveup, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
+            if (__syncthreads_or(stop ? 1 : 0)) {
+                if (threadIdx.x == 0)
+                    __hip_atomic_store(giveup, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                return false;
+            }
+        }
+    }
+}
+
+// grid G + N: workgroups 0 .. G-1 are workers, G .. G+N-1 owners. dynamic LDS, workers: float rows[rows_per_group]
+// [r + SMALL_ROW_PAD]; float inv[rows_per_group rounded up to 4]; float res[N][r]; unsigned char taken[N][rows_per_group].
+// owners: double F[k][k]; double res[r]; double w[k], c[k], fc[k], x[k], a[k]; float y[r]; float cols[k][r]
+__global__ __launch_bounds__(SMALL_THREADS) void omp_small_kernel(MatrixView A, IterArgs P, int32_t N, int32_t G,
+                                                                  int32_t rows_per_group)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    __shared__ uint64_t s_keys[SMALL_THREADS / 64][SMALL_MAX_RHS][2];
-    __shared__ uint64_t s_part[2 * SMALL_MAX_GROUPS]; // the keys of this workgroup's right-hand side, all workgroups
     const int32_t r = A.r, r4 = r >> 2, k = P.k, d = A.d;
-    const int32_t ld = r + SMALL_ROW_PAD;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int G = gridDim.x, g = blockIdx.x;
+    const int g = blockIdx.x;
+    const OmpWorkspace &W = P.ws;
+    uint32_t *giveup = W.sync;
+    const int32_t xw = r + SMALL_XCHG_PAD; // exchange words per right-hand side
+
+    if (g >= G) {
+        // =============================== owner of right-hand side n ===============================
+        const int64_t n = g - G;
+        __shared__ uint64_t s_part[2 * SMALL_MAX_GROUPS]; // the keys of this right-hand side, all workers
+        __shared__ double s_red[2][SMALL_THREADS / 64];
+        __shared__ double s_gamma, s_coef;
+        double *F_s = reinterpret_cast<double *>(smem); // column t at F_s[t * k + u], u <= t
+        double *res_s = F_s + (size_t)k * k;
+        double *w_s = res_s + r;
+        double *c_s = w_s + k;
+        double *fc_s = c_s + k;
+        double *x_s = fc_s + k;
+        double *av_s = x_s + k;
+        float *y_s = reinterpret_cast<float *>(av_s + k);
+        float *cols_s = y_s + r;
+        const uint64_t *mine = W.partial + n * (int64_t)G * 2;
+        uint64_t *out = W.xchg + n * xw;
+        for (int32_t j = tid; j < r; j += SMALL_THREADS) {
+            const float v = P.y[n * r + j];
+            y_s[j] = v;
+            res_s[j] = (double)v;
+        }
+        __syncthreads();
+        bool aborted = false;
+        for (int32_t it = 0; it < k; ++it) {
+            const uint32_t tag = (uint32_t)(it + 1);
+            if (!small_wait(giveup, [&]() {
+                    bool ok = true;
+                    for (int32_t e = tid; e < 2 * G; e += SMALL_THREADS) {
+                        const uint64_t word = __hip_atomic_load(mine + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        ok = ok && (uint32_t)((word >> 24) & 0xffu) == tag;
+                        s_part[e] = small_untag_key(word);
+                    }
+                    return ok;
+                })) {
+                aborted = true;
+                break;
+            }
+            const int32_t lam = select_lambda<false, SMALL_THREADS>(A, s_part, 2 * G, res_s);
+            // the new column: to LDS, with g = ||a||^2 and b = <a, y> in double
+            {
+                double gg = 0.0, bb = 0.0;
+                float *dst = cols_s + (size_t)it * r;
+                for (int32_t jb = tid; jb < r4; jb += SMALL_THREADS) {
+                    const float4 a = reinterpret_cast<const float4 *>(P.At_rows + (int64_t)lam * r)[jb];
+                    reinterpret_cast<float4 *>(dst)[jb] = a;
+                    const float4 yv = reinterpret_cast<const float4 *>(y_s)[jb];
+                    gg += (double)a.x * a.x + (double)a.y * a.y + (double)a.z * a.z + (double)a.w * a.w;
+                    bb += (double)a.x * yv.x + (double)a.y * yv.y + (double)a.z * yv.z + (double)a.w * yv.w;
+                }
+                gg = wave_sum(gg);
+                bb = wave_sum(bb);
+                if (lane == 0) {
+                    s_red[0][wave] = gg;
+                    s_red[1][wave] = bb;
+                }
+            }
+            __syncthreads();
+            // w_t = <A_:lambda_t, a> for the earlier selections, one wavefront per column
+            {
+                const float4 *an = reinterpret_cast<const float4 *>(cols_s + (size_t)it * r);
+                for (int32_t t = wave; t < it; t += SMALL_THREADS / 64) {
+                    const float4 *ct = reinterpret_cast<const float4 *>(cols_s + (size_t)t * r);
+                    double acc = 0.0;
+                    for (int32_t jb = lane; jb < r4; jb += 64) {
+                        const float4 u = ct[jb], a = an[jb];
+                        acc += (double)u.x * a.x + (double)u.y * a.y + (double)u.z * a.z + (double)u.w * a.w;
+                    }
+                    acc = wave_sum(acc);
+                    if (lane == 0)
+                        w_s[t] = acc;
+                }
+            }
+            __syncthreads();
+            // App. B: c = F^H w (coordinates of the new column in the orthonormal basis), F c, gamma, the new
+            // coefficient, the new column of F and x = F a
+            if (tid < it) {
+                double acc = 0.0;
+                for (int32_t u = 0; u <= tid; ++u)
+                    acc += F_s[(size_t)tid * k + u] * w_s[u];
+                c_s[tid] = acc;
+            }
+            __syncthreads();
+            if (tid < it) {
+                double acc = 0.0;
+                for (int32_t t = tid; t < it; ++t)
+                    acc += F_s[(size_t)t * k + tid] * c_s[t];
+                fc_s[tid] = acc;
+            }
+            if (tid == 0) {
+                double gg = 0.0, bb = 0.0, cc = 0.0, ca = 0.0;
+                for (int u = 0; u < SMALL_THREADS / 64; ++u) {
+                    gg += s_red[0][u];
+                    bb += s_red[1][u];
+                }
+                for (int32_t t = 0; t < it; ++t) {
+                    cc += c_s[t] * c_s[t];
+                    ca += c_s[t] * av_s[t];
+                }
+                const double rem = gg - cc;
+                const double gamma = rem > 0.0 ? 1.0 / sqrt(rem) : 0.0;
+                const double coef = gamma * (bb - ca);
+                av_s[it] = coef;
+                F_s[(size_t)it * k + it] = gamma;
+                s_gamma = gamma;
+                s_coef = coef;
+            }
+            __syncthreads();
+            {
+                const double gamma = s_gamma, coef = s_coef;
+                if (tid < it) {
+                    const double f = -gamma * fc_s[tid];
+                    F_s[(size_t)it * k + tid] = f;
+                    x_s[tid] += coef * f;
+                } else if (tid == it) {
+                    x_s[it] = coef * gamma;
+                }
+            }
+            __syncthreads();
+            // residual y - A_Lambda x in double; its float copy goes out in tagged words
+            {
+                const uint64_t tagw = (uint64_t)tag << 32;
+                for (int32_t j = tid; j < r; j += SMALL_THREADS) {
+                    double e = (double)y_s[j];
+                    for (int32_t t = 0; t <= it; ++t)
+                        e -= x_s[t] * (double)cols_s[(size_t)t * r + j];
+                    res_s[j] = e;
+                    __hip_atomic_store(out + j, tagw | __float_as_uint((float)e), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                if (tid == 0) {
+                    P.sel[n * k + it] = lam;
+                    __hip_atomic_store(out + r, tagw | (uint32_t)lam, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+            __syncthreads();
+        }
+        if (aborted) { // this right-hand side was not finished
+            for (int32_t e = tid; e < k; e += SMALL_THREADS) {
+                P.sel[n * k + e] = -1;
+                P.x[n * k + e] = 0.f;
+            }
+            return;
+        }
+        // results: x, and the factor and coefficients where the batched kernels keep them (the shared-support
+        // fit of a second right-hand side reads the factor from there)
+        for (int32_t u = tid; u < k; u += SMALL_THREADS) {
+            P.x[n * k + u] = (float)x_s[u];
+            W.avec[n * k + u] = av_s[u];
+        }
+        double *Fg = W.F + n * W.f_stride;
+        for (int32_t e = tid; e < k * k; e += SMALL_THREADS) {
+            const int32_t t = e / k, u = e - t * k;
+            if (u <= t)
+                Fg[e] = F_s[e];
+        }
+        return;
+    }
+
+    // ======================================== worker ========================================
+    __shared__ uint64_t s_keys[SMALL_THREADS / 64][SMALL_MAX_RHS][2];
+    const int32_t ld = r + SMALL_ROW_PAD;
     const int32_t row0 = g * rows_per_group;
     const int32_t rows = row0 >= d ? 0 : (d - row0 < rows_per_group ? d - row0 : rows_per_group);
     float *a_rows = reinterpret_cast<float *>(smem);
     float *inv = a_rows + (size_t)rows_per_group * ld;
     float *res = inv + ((rows_per_group + 3) & ~3); // keeps the residuals 16-byte aligned
     unsigned char *taken = reinterpret_cast<unsigned char *>(res + (size_t)N * r);
-    unsigned char *body = smem + body_offset;
-    const OmpWorkspace &W = P.ws;
-    uint32_t *giveup = W.sync;
-    const int32_t xw = r + SMALL_XCHG_PAD; // exchange words per right-hand side
 
     // the workgroup's rows of At and their reciprocal norms, once for the whole call; the residuals = y
     for (int32_t e = tid; e < rows * r4; e += SMALL_THREADS) {
@@ -815,31 +1008,10 @@ __global__ __launch_bounds__(SMALL_THREADS) void omp_small_kernel(MatrixView A, 
         taken[e] = 0;
     __syncthreads();
 
-    // polls until `ready` holds in every thread; false if the launch gives up. `fetch` loads this thread's words
-    // and says whether all of them carry the tag
-    auto wait_for = [&](auto &&fetch) -> bool {
-        for (uint32_t spins = 0;; ++spins) {
-            const bool ok = fetch();
-            if (__syncthreads_and(ok ? 1 : 0))
-                return true;
-            if ((spins & 15u) == 15u) { // now and then: has the launch given up, or is it time to
-                const bool stop = spins > SMALL_SPIN_LIMIT ||
-                                  __hip_atomic_load(giveup, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
-                if (__syncthreads_or(stop ? 1 : 0)) {
-                    if (tid == 0)
-                        __hip_atomic_store(giveup, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    return false;
-                }
-            }
-        }
-    };
-
-    // phase 1 mapping: a wavefront takes 16 rows at a time, four lanes per row, each lane a quarter of the depth
+    // a wavefront takes 16 rows at a time, four lanes per row, each lane a quarter of the depth
     const int sub = lane >> 2, part = lane & 3;
-    bool aborted = false;
-    for (int32_t it = 0; it < k && !aborted; ++it) {
+    for (int32_t it = 0; it < k; ++it) {
         const uint32_t tag = (uint32_t)(it + 1);
-        // ---- phase 1: this workgroup's rows against every residual ----
         uint64_t best[SMALL_MAX_RHS], second[SMALL_MAX_RHS];
 #pragma unroll
         for (int u = 0; u < SMALL_MAX_RHS; ++u)
@@ -916,35 +1088,10 @@ __global__ __launch_bounds__(SMALL_THREADS) void omp_small_kernel(MatrixView A, 
             __hip_atomic_store(o, small_tag_key(b, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(o + 1, small_tag_key(sc, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        // ---- phase 2: selection and least-squares update, one workgroup per right-hand side ----
-        if (g < N) {
-            const uint64_t *mine = W.partial + (int64_t)g * G * 2;
-            if (!wait_for([&]() {
-                    bool ok = true;
-                    for (int32_t e = tid; e < 2 * G; e += SMALL_THREADS) {
-                        const uint64_t word = __hip_atomic_load(mine + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        ok = ok && (uint32_t)((word >> 24) & 0xffu) == tag;
-                        s_part[e] = small_untag_key(word);
-                    }
-                    return ok;
-                })) {
-                aborted = true;
-                break;
-            }
-            IterArgs Q = P;
-            Q.it = it;
-            pick_body<false, SMALL_THREADS>(A, Q, g, 0, 1, body, s_part); // Q.ws.tiles_m == G
-            __threadfence_block();
-            __syncthreads();
-            update_body<2, 4, true>(Q, r, g, 0, 1, body);
-            if (tid == 0) // the selected position, for the other workgroups' masks
-                __hip_atomic_store(W.xchg + (int64_t)g * xw + r, ((uint64_t)tag << 32) | (uint32_t)P.sel[(int64_t)g * k + it],
-                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
         if (it + 1 == k)
             break; // nobody needs the last residual
-        // ---- every workgroup: the new residuals and selected positions ----
-        if (!wait_for([&]() {
+        // the new residuals and selected positions
+        if (!small_wait(giveup, [&]() {
                 bool ok = true;
                 for (int32_t e = tid; e < N * (r + 1); e += SMALL_THREADS) {
                     const int32_t u = e / (r + 1), j = e - u * (r + 1);
@@ -962,16 +1109,9 @@ __global__ __launch_bounds__(SMALL_THREADS) void omp_small_kernel(MatrixView A, 
                     }
                 }
                 return ok;
-            })) {
-            aborted = true;
+            }))
             break;
-        }
     }
-    if (aborted && g < N) // the right-hand side this workgroup serves was not finished
-        for (int32_t e = tid; e < k; e += SMALL_THREADS) {
-            P.sel[(int64_t)g * k + e] = -1;
-            P.x[(int64_t)g * k + e] = 0.f;
-        }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1100,13 +1240,12 @@ static void omp_select_update(const OmpPlan &pl, const MatrixView &A, const floa
 
 // Whether a recovery is served by the single-launch kernel, and its shape: at most SMALL_MAX_RHS right-hand sides,
 // resident rows without any option, and a matrix whose rows fit the LDS of at most SMALL_MAX_GROUPS workgroups
-// (96 KiB of rows each at most; 64 KiB slices are preferred). The limits are where it was measured to win: an
-// exchange between workgroups on different XCDs costs about 3.5 us, two per iteration, the correlation phase
-// 1.5 us, the two bodies 4 + 6 us: 18.5 us against 27 us per iteration for three dependent launches. With 8
-// right-hand sides or 256 workgroups the launches are no slower any more (0.87 vs 0.87 ms at N = 8, d = 4096,
-// r = 256, k = 32).
+// (96 KiB of rows each at most; 64 KiB slices are preferred), k and k r small enough for an owner's LDS. The
+// limits are where it was measured to win: an exchange between workgroups on different XCDs costs about 3.5 us,
+// two per iteration, the correlation phase 1.5 us, the owner's work about 5 us: 14 us against 27 us per
+// iteration for three dependent launches. With 8 right-hand sides or 256 workers the launches are no slower.
 struct SmallPlan {
-    int32_t groups, rows_per_group, body_offset;
+    int32_t groups, rows_per_group; // workers and their rows of At
     size_t smem;
 };
 static int device_cu_count()
@@ -1126,13 +1265,14 @@ static int device_cu_count()
 static bool small_plan(const OmpPlan &pl, int32_t N, int32_t k, SmallPlan &sp)
 {
     const MatrixView &A = pl.Apick;
-    if (N > SMALL_MAX_RHS || A.generated || A.gram || pl.screen || pl.recurrence || pl.narrow || k > 128 || A.r > 2048 ||
-        (int64_t)N * A.r > 8192 || A.d >= (1 << 24) || (A.flags & SGC_MATRIX_FLAG_MULTI_LAUNCH))
+    if (N > SMALL_MAX_RHS || A.generated || A.gram || pl.screen || pl.recurrence || pl.narrow || k > SMALL_MAX_K ||
+        A.r > 2048 || (int64_t)k * A.r > SMALL_MAX_KR || (int64_t)N * A.r > 8192 || A.d >= (1 << 24) ||
+        (A.flags & SGC_MATRIX_FLAG_MULTI_LAUNCH))
         return false;
-    int cus = device_cu_count();
+    int cus = device_cu_count() - N; // the owners take a CU each
     if (cus > SMALL_MAX_GROUPS)
         cus = SMALL_MAX_GROUPS;
-    if (cus < 2 * N || cus < 8)
+    if (cus < 8)
         return false;
     const int64_t row_bytes = (int64_t)(A.r + SMALL_ROW_PAD) * 4; // as laid out in LDS
     int64_t rows_per_group = (64 * 1024) / row_bytes;
@@ -1145,20 +1285,17 @@ static bool small_plan(const OmpPlan &pl, int32_t N, int32_t k, SmallPlan &sp)
         if (rows_per_group * row_bytes > 96 * 1024)
             return false;
     }
-    if (groups < 2 * N) { // a short matrix: still one workgroup per right-hand side for the second phase, and some to spare
-        groups = 2 * N;
+    if (groups < 8 && A.d >= 8) { // a short matrix: a few workers still, so that the rows are scored side by side
+        groups = 8;
         rows_per_group = ((int64_t)A.d + groups - 1) / groups;
     }
-    groups = ((int64_t)A.d + rows_per_group - 1) / rows_per_group; // no workgroup without rows ...
-    if (groups < N)
-        groups = N;                                                // ... except those that serve a right-hand side
-    size_t off = (size_t)rows_per_group * row_bytes + (size_t)((rows_per_group + 3) & ~(int64_t)3) * 4 +
-                 (size_t)N * A.r * 4 + (size_t)N * rows_per_group;
-    off = (off + 15) & ~(size_t)15;
+    groups = ((int64_t)A.d + rows_per_group - 1) / rows_per_group; // no worker without rows
+    const size_t worker = (size_t)rows_per_group * row_bytes + (size_t)((rows_per_group + 3) & ~(int64_t)3) * 4 +
+                          (size_t)N * A.r * 4 + (size_t)N * rows_per_group;
+    const size_t owner = sizeof(double) * ((size_t)k * k + A.r + 5 * (size_t)k) + sizeof(float) * ((size_t)A.r + (size_t)k * A.r);
     sp.groups = (int32_t)groups;
     sp.rows_per_group = (int32_t)rows_per_group;
-    sp.body_offset = (int32_t)off;
-    sp.smem = off + (pl.pick_smem > pl.factor_smem ? pl.pick_smem : pl.factor_smem);
+    sp.smem = ((worker > owner ? worker : owner) + 15) & ~(size_t)15;
     return sp.smem <= 150 * 1024;
 }
 
@@ -1267,9 +1404,9 @@ hipError_t launch_omp(const float *y, int32_t N, const MatrixView &A, int32_t k,
         if (e != hipSuccess)
             return e;
         const OmpWorkspace w = shift_workspace(ws, 0, A.r, k, sp.groups);
-        IterArgs P{y, k, 0, sel, x, w, pl.Apick.At, pl.factor_share_table ? 1 : 0, 0};
-        omp_small_kernel<<<dim3((unsigned)sp.groups), SMALL_THREADS, sp.smem, s>>>(pl.Apick, P, N, sp.rows_per_group,
-                                                                                  sp.body_offset);
+        IterArgs P{y, k, 0, sel, x, w, pl.Apick.At, 0, 0};
+        omp_small_kernel<<<dim3((unsigned)(sp.groups + N)), SMALL_THREADS, sp.smem, s>>>(pl.Apick, P, N, sp.groups,
+                                                                                      sp.rows_per_group);
         e = hipGetLastError();
     } else {
         e = omp_iterations(pl, whole_matrix_panel, y, N, A, k, sel, x, ws, s);
