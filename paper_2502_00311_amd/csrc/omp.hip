@@ -426,7 +426,7 @@ __global__ __launch_bounds__(PICK_THREADS) void pick_kernel(MatrixView A, IterAr
 // fewer such quads than threads, several threads share one and take every G-th column, and their
 // parts are added in a fixed order.
 // ROWS = rows of F per lane (k <= 64 * ROWS); FLIGHT = columns in flight per wavefront
-template <int FACTOR_ROWS, int FLIGHT, bool COHERENT = false>
+template <int FACTOR_ROWS, int FLIGHT>
 __device__ __forceinline__ void update_body(const IterArgs &P, const int32_t r, const int64_t n, const int slice,
                                             const int nslices, unsigned char *smem)
 {
@@ -662,21 +662,8 @@ __device__ __forceinline__ void update_body(const IterArgs &P, const int32_t r, 
                 *reinterpret_cast<uint2 *>(o) = make_uint2(h[0] | ((uint32_t)h[1] << 16), h[2] | ((uint32_t)h[3] << 16));
                 *reinterpret_cast<uint2 *>(o + 64) = make_uint2(l[0] | ((uint32_t)l[1] << 16), l[2] | ((uint32_t)l[3] << 16));
             } else {
-                if (COHERENT) {
-                    // the single-launch recovery: every workgroup of the launch reads the float residual in its
-                    // next correlation phase. Each value travels in a 64-bit word with the number of the
-                    // iteration in its upper half, stored with one device-scope atomic store: a reader sees the
-                    // old word or the new one, never a mixture, and needs no other signal
-                    uint64_t *o = W.xchg + n * (int64_t)(r + SMALL_XCHG_PAD) + 4 * jb;
-                    const uint64_t tag = (uint64_t)(it + 1) << 32;
-                    __hip_atomic_store(o + 0, tag | __float_as_uint((float)e0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    __hip_atomic_store(o + 1, tag | __float_as_uint((float)e1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    __hip_atomic_store(o + 2, tag | __float_as_uint((float)e2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    __hip_atomic_store(o + 3, tag | __float_as_uint((float)e3), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                } else {
-                    reinterpret_cast<float4 *>(W.res32 + n * r)[jb] =
-                        make_float4((float)e0, (float)e1, (float)e2, (float)e3);
-                }
+                reinterpret_cast<float4 *>(W.res32 + n * r)[jb] =
+                    make_float4((float)e0, (float)e1, (float)e2, (float)e3);
             }
         }
     }
