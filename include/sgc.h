@@ -81,8 +81,9 @@ enum { SGC_MATRIX_FLAG_MATERIALIZE = 2 };
  * k <= 64 and k r <= 16384, is recovered in ONE launch: up to 68 workgroups stay resident for all k iterations,
  * keep their rows of At (or the least-squares state of a right-hand side) in LDS and exchange keys and
  * residuals through tagged words in the workspace, polling until they arrive. That needs all its workgroups on the device at once, which holds whenever the kernel gets the GPU to
- * itself; a caller that shares the GPU with other long-running kernels sets this bit to keep the three
- * launches per iteration (same results). Should a word of the single launch not arrive within seconds, the
+ * itself; a caller that shares the GPU with other long-running kernels, or keeps more than three such
+ * recoveries in flight at once on different streams (each wants up to 68 CUs for itself), sets this bit to keep
+ * the three launches per iteration (same results). Should a word of the single launch not arrive within seconds, the
  * call gives up: for every right-hand side that was not finished sel is filled with -1 and x with 0, which
  * sgc_apply skips.
  */

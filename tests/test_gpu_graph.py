@@ -21,8 +21,9 @@ def dev(a):
 
 @pytest.mark.parametrize("shared,C,d,r,k", [
     (False, 3, 4096, 256, 24), (True, 3, 4096, 256, 24),
+    (False, 2, 4096, 256, 24),     # four right-hand sides: the single-launch recovery inside the capture
     (False, 300, 1024, 64, 4),     # 600 right-hand sides: the recovery forks onto its second stream inside the capture
-], ids=["two_supports", "shared_support", "two_streams"])
+], ids=["two_supports", "shared_support", "single_launch", "two_streams"])
 def test_captured_step_replays_equal_eager_steps(shared, C, d, r, k):
     w = synth.shrink(synth.CFG2, C=C, d=d, r=r, k=k)
     C, d, r, k = w.C, w.d, w.r, w.k
