@@ -382,7 +382,12 @@ def test_omp_generated_matrix_with_many_right_hand_sides(N, d, r, k, flags):
     (4, 5, 8, 5, "stored"),           # d barely above the batch: workgroups without rows, k = d
     (2, 6000, 64, 1, "philox"),       # generated matrix written to the workspace panel first; one iteration
     (2, 300, 128, 128, "stored"),     # the largest k of this path
-    (4, 24000, 64, 8, "stored"),      # 6 MB of rows: 96 KiB slices in 64 workgroups
+    (4, 24000, 64, 8, "stored"),      # 6.5 MB of rows: too much for 64 workers, the launches serve it
+    (3, 70000, 16, 16, "stored"),     # 5.6 MB of short rows: 87 KiB slices of 1094 rows in 64 workers
+    (1, 1, 4, 1, "stored"),           # the smallest problem there is
+    (4, 513, 2048, 8, "stored"),      # the longest columns (N r = 8192, k r = 16384): one row more than 64 slices of 8
+    (1, 9000, 1024, 16, "philox"),    # generated, 35 MB: written to the panel, too large for the workers' LDS
+    (2, 3000, 256, 64, "stored"),     # the largest k of this path, k r = 16384
 ])
 def test_small_batch_single_launch_recovery(N, d, r, k, mode):
     """At most four right-hand sides on a small resident matrix are recovered in one launch (resident workgroups
