@@ -200,7 +200,8 @@ __device__ __forceinline__ int32_t select_lambda(const MatrixView &A, const uint
     __shared__ int32_t s_cand[PICK_CAND_CAP];
     __shared__ int32_t s_lambda, s_ncand;
     const int32_t r4 = A.r >> 2;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6); // known to be the same in all lanes: loops over wavefronts stay scalar
 
     // (1) float maximum over the tile partials
     uint64_t best = 0;
@@ -309,7 +310,8 @@ __device__ __forceinline__ void pick_body(const MatrixView &A, const IterArgs &P
     float *a_col = reinterpret_cast<float *>(smem);
     __shared__ double s_red[2][PICK_WAVES];
     const int32_t r = A.r, r4 = A.r >> 2, k = P.k, it = P.it;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6); // known to be the same in all lanes: loops over wavefronts stay scalar
     if (slice != 0 && slice * PICK_WAVES >= it)
         return; // no earlier selection falls to this slice
     const OmpWorkspace &W = P.ws;
@@ -435,7 +437,8 @@ __device__ __forceinline__ void update_body(const IterArgs &P, const int32_t r, 
     double *fsum = w_s + k;
     __shared__ double s_red[2][FACTOR_MAX_THREADS / 64];
     __shared__ double s_gamma, s_coef;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6); // known to be the same in all lanes: loops over wavefronts stay scalar
     const int nthreads = blockDim.x, nwaves = blockDim.x >> 6;
     const OmpWorkspace &W = P.ws;
     double *F = W.F + n * W.f_stride;
@@ -687,7 +690,8 @@ __global__ __launch_bounds__(REFIT_THREADS) void refit_kernel(IterArgs P, const 
     double *b_s = reinterpret_cast<double *>(smem);
     double *u_s = b_s + P.k;
     const int32_t k = P.k, r4 = r >> 2;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6); // known to be the same in all lanes: loops over wavefronts stay scalar
     constexpr int NW = REFIT_THREADS / 64;
     const int64_t n = blockIdx.x;
     const OmpWorkspace &W = P.ws;
@@ -807,7 +811,8 @@ __global__ __launch_bounds__(SMALL_THREADS) void omp_small_kernel(MatrixView A, 
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int32_t r = A.r, r4 = r >> 2, k = P.k, d = A.d;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6); // known to be the same in all lanes: loops over wavefronts stay scalar
     const int g = blockIdx.x;
     const OmpWorkspace &W = P.ws;
     uint32_t *giveup = W.sync;
