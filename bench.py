@@ -636,7 +636,7 @@ def main_cesgc(args, dev):
     return 0
 
 
-def cpu_baseline(w, At_host, shared_support=False, budget_s=20.0):
+def cpu_baseline(w, At_host, shared_support=False, budget_s=30.0):
     """The CPU oracle (single thread, as it stands) on a bounded sample of step 1 of the same workload: whole
     chunks spread evenly over the batch (for configuration 4 that is over its seven weight matrices), each run
     through the whole path - top-k, projection, Adam, OMP(mhat), OMP(vhat), apply - until about budget_s seconds
@@ -653,7 +653,7 @@ def cpu_baseline(w, At_host, shared_support=False, budget_s=20.0):
     full = per_iter * w.k * 2 <= budget_s
     iters = w.k if full else max(4, int(budget_s / 2 / per_iter))
     iters = min(iters, w.k)
-    want = max(1, min(w.C, 8, int(budget_s / max(per_iter * iters * 2, 1e-3))))
+    want = max(1, min(w.C, 16, int(budget_s / max(per_iter * iters * 2, 1e-3))))
     chunks = sorted(set(int(c) for c in np.linspace(0, w.C - 1, want + 2)[1:-1])) if want < w.C else list(range(w.C))
     t_total, done = 0.0, []
     t_begin = time.perf_counter()
