@@ -369,7 +369,7 @@ def run_workload(args, w, dev, K, Wm, variants, baseline):
     }
 
     # ---- variants, a few steps each (context, not the headline): the shared-support recovery (first
-    #      widening), and for a generated matrix of more than 64 MiB the option that writes it out once per
+    #      widening), the Gram table where it is at most 2 GiB, and for a generated matrix of more than 64 MiB the option that writes it out once per
     #      call into the workspace instead of regenerating it inside the contraction ----
     if variants and not (args.shared_support or args.screen_bf16 or args.gram or args.recurrence or args.whole_matrix):
         nv = 1 if ms_per_step > 2000 else min(3, nsteps)
@@ -387,6 +387,17 @@ def run_workload(args, w, dev, K, Wm, variants, baseline):
             return {"ms_per_step": round(ms, 3), "value": round(C * d / (ms * 1e-3), 1), "steps": nv}
 
         out["variants"] = {"shared_support": timed(True)}
+        if d <= 16384:
+            # App. B's precomputed table of column inner products (built once per matrix, 8 d^2 bytes): the
+            # update's inner products become look-ups; the contraction stays
+            A.gram = torch.empty((d, d), dtype=torch.float64, device=dev)
+            torch.cuda.synchronize()
+            tg = time.perf_counter()
+            sgc.sgc_matrix_gram(A, A.gram)
+            torch.cuda.synchronize()
+            build_ms = (time.perf_counter() - tg) * 1e3
+            out["variants"]["gram_table"] = dict(timed(False), table_build_ms=round(build_ms, 3), table_bytes=8 * d * d)
+            A.gram = None
         if A.mode == sgc.MATRIX_PHILOX and 4.0 * d * r > 64 * 2 ** 20 and d <= 2 * C * k:
             A.flags = sgc.MATRIX_FLAG_MATERIALIZE
             out["variants"]["whole_matrix_in_workspace"] = timed(False)
