@@ -447,6 +447,10 @@ def probe_runs(dev):
     t_v = best(sgc.PROBE_VALU, 1024, iters, 0)
     t_mix = best(sgc.PROBE_MFMA_VALU4, 1024, iters, 0)
     res["mfma_plus_valu_ms"] = {"mfma_alone": round(t_m, 3), "valu_alone": round(t_v, 3), "both_in_one_loop": round(t_mix, 3)}
+    # the same question for wavefronts that share a SIMD: four wavefronts of MFMAs and four of FMAs per workgroup
+    res["mfma_beside_valu_ms"] = {"mfma_wavefronts_alone": round(best(sgc.PROBE_SPLIT_MFMA, 1024, iters, 0), 3),
+                                  "valu_wavefronts_alone": round(best(sgc.PROBE_SPLIT_VALU, 1024, iters, 0), 3),
+                                  "both": round(best(sgc.PROBE_SPLIT_BOTH, 1024, iters, 0), 3)}
     ms = best(sgc.PROBE_READ, 4096, 0, nbytes // 2)
     res["read_GBps"] = round(nbytes / 2 / (ms * 1e-3) / 1e9, 1)
     ms = best(sgc.PROBE_RW44, 4096, 0, nbytes)

@@ -406,15 +406,20 @@ sgc_status sgc_profile_read(sgc_profile *out /* host */);
  *   SGC_PROBE_MFMA  blocks x 4 wavefronts, each `iters` x 16 v_mfma_f32_32x32x2f32 (4096 flop each)
  *   SGC_PROBE_MFMA_VALU4, _VALU8  the MFMA probe with 4 (8) independent v_fma_f32 behind every MFMA: whether
  *                   vector-ALU work rides in the shadow of float matrix instructions or adds to their time
+ *   SGC_PROBE_SPLIT_BOTH, _SPLIT_MFMA, _SPLIT_VALU  blocks x 8 wavefronts (two per SIMD): wavefronts 0-3 issue only
+ *                   `iters` x 16 MFMAs, wavefronts 4-7 only `iters` x 256 plain v_fma_f32; both groups, or one of
+ *                   them alone (the other leaves at once): whether vector-ALU work of other wavefronts on the same
+ *                   SIMD runs beside float matrix instructions
  *   SGC_PROBE_READ  reads `bytes` of a with non-temporal 16-byte loads
  *   SGC_PROBE_RW44  reads four arrays of bytes/8 from a and writes four of bytes/8 to b (the Adam kernel's
  *                   traffic pattern: `bytes` moved in total); a and b must each hold bytes/2
  *   SGC_PROBE_COPY  copies bytes/2 from a to b
- * a (may be NULL for VALU / MFMA) and b (at least 4 bytes) are device pointers, 16-byte aligned; a
+ * a (may be NULL for the VALU / MFMA / SPLIT kinds) and b (at least 4 bytes) are device pointers, 16-byte aligned; a
  * multiple of 128 bytes keeps every access whole. Errors: NULL, SHAPE, DTYPE (unknown kind), ALIGN, DEVICE.
  */
 enum { SGC_PROBE_VALU = 0, SGC_PROBE_MFMA = 1, SGC_PROBE_READ = 2, SGC_PROBE_RW44 = 3, SGC_PROBE_COPY = 4,
-       SGC_PROBE_MFMA_VALU4 = 5, SGC_PROBE_MFMA_VALU8 = 6 };
+       SGC_PROBE_MFMA_VALU4 = 5, SGC_PROBE_MFMA_VALU8 = 6, SGC_PROBE_SPLIT_BOTH = 7, SGC_PROBE_SPLIT_MFMA = 8,
+       SGC_PROBE_SPLIT_VALU = 9 };
 sgc_status sgc_probe(int32_t kind, const void *a, void *b, int64_t bytes, int32_t blocks, int32_t iters,
                      void *stream);
 

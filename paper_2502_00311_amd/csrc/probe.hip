@@ -4,6 +4,8 @@
 //   SGC_PROBE_VALU   register-only chains of plain (non-packed) v_fma_f32: vector-ALU issue rate
 //   SGC_PROBE_MFMA   register-only v_mfma_f32_32x32x2f32: float matrix-core rate
 //   SGC_PROBE_MFMA_VALU4 / 8   the MFMA loop with 4 / 8 independent v_fma_f32 behind every MFMA
+//   SGC_PROBE_SPLIT_BOTH / _MFMA / _VALU   workgroups of eight wavefronts, two per SIMD: four issue only the MFMAs
+//                    of SGC_PROBE_MFMA, four only plain v_fma_f32 (256 per 16 MFMAs); both groups, or one of them alone
 //   SGC_PROBE_READ   streaming read with non-temporal 16-byte loads
 //   SGC_PROBE_RW44   four arrays read and four written, in the loop structure of the Adam kernel
 //   SGC_PROBE_COPY   one array read, one written
@@ -101,6 +103,55 @@ __global__ __launch_bounds__(256) void probe_mix_kernel(float *out, int32_t iter
         out[0] = s;
 }
 
+// Does vector-ALU work of OTHER wavefronts on the same SIMD run beside float matrix instructions? Wavefronts 0-3 of a
+// workgroup (one per SIMD) issue iters x 16 MFMAs, wavefronts 4-7 iters x 256 plain FMAs; WHICH: 0 both, 1 the
+// MFMA wavefronts alone (the others leave at once), 2 the FMA wavefronts alone.
+template <int WHICH>
+__global__ __launch_bounds__(512) void probe_split_kernel(float *out, int32_t iters)
+{
+    typedef float floatx16 __attribute__((ext_vector_type(16)));
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    float s = 0.f;
+    if (wave < 4) {
+        if (WHICH == 2)
+            return;
+        floatx16 a0 = {0}, a1 = {0}, a2 = {0}, a3 = {0};
+        const float x = threadIdx.x * 1e-3f, y = blockIdx.x * 1e-3f;
+        for (int32_t i = 0; i < iters; ++i) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                a0 = __builtin_amdgcn_mfma_f32_32x32x2f32(x, y, a0, 0, 0, 0);
+                a1 = __builtin_amdgcn_mfma_f32_32x32x2f32(y, x, a1, 0, 0, 0);
+                a2 = __builtin_amdgcn_mfma_f32_32x32x2f32(x, x, a2, 0, 0, 0);
+                a3 = __builtin_amdgcn_mfma_f32_32x32x2f32(y, y, a3, 0, 0, 0);
+            }
+        }
+        for (int v = 0; v < 16; ++v)
+            s += a0[v] + a1[v] + a2[v] + a3[v];
+    } else {
+        if (WHICH == 1)
+            return;
+        float acc[PROBE_CHAINS];
+        const float x = 1.0f + 1e-7f * (float)threadIdx.x, y = 1e-9f * (float)blockIdx.x;
+#pragma unroll
+        for (int c = 0; c < PROBE_CHAINS; ++c)
+            acc[c] = (float)c;
+        for (int32_t i = 0; i < iters; ++i) {
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+#pragma unroll
+                for (int c = 0; c < PROBE_CHAINS; ++c)
+                    asm volatile("v_fma_f32 %0, %1, %0, %2" : "+v"(acc[c]) : "v"(x), "v"(y));
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < PROBE_CHAINS; ++c)
+            s += acc[c];
+    }
+    if (s == 123.456f)
+        out[0] = s;
+}
+
 __global__ __launch_bounds__(256) void probe_read_kernel(const float *__restrict__ a, float *out, int64_t n4)
 {
     constexpr int U = 16;
@@ -176,6 +227,15 @@ extern "C" sgc_status sgc_probe(int32_t kind, const void *a, void *b, int64_t by
         break;
     case SGC_PROBE_MFMA_VALU8:
         probe_mix_kernel<8><<<dim3((unsigned)blocks), 256, 0, s>>>((float *)b, iters);
+        break;
+    case SGC_PROBE_SPLIT_BOTH:
+        probe_split_kernel<0><<<dim3((unsigned)blocks), 512, 0, s>>>((float *)b, iters);
+        break;
+    case SGC_PROBE_SPLIT_MFMA:
+        probe_split_kernel<1><<<dim3((unsigned)blocks), 512, 0, s>>>((float *)b, iters);
+        break;
+    case SGC_PROBE_SPLIT_VALU:
+        probe_split_kernel<2><<<dim3((unsigned)blocks), 512, 0, s>>>((float *)b, iters);
         break;
     case SGC_PROBE_READ:
         if (!a)

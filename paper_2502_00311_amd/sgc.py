@@ -31,6 +31,7 @@ EXPORTS = [
     "sgc_profile_enable", "sgc_profile_read", "sgc_probe",
 ]
 PROBE_VALU, PROBE_MFMA, PROBE_READ, PROBE_RW44, PROBE_COPY, PROBE_MFMA_VALU4, PROBE_MFMA_VALU8 = 0, 1, 2, 3, 4, 5, 6
+PROBE_SPLIT_BOTH, PROBE_SPLIT_MFMA, PROBE_SPLIT_VALU = 7, 8, 9
 PROFILE_CLASSES = ["topk", "project", "adam", "omp_corr", "omp_select_update", "apply", "other", "omp_matrix_fill",
                    "outer_project", "outer_apply", "outer_refresh"]
 
