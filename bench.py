@@ -347,6 +347,15 @@ def run_workload(args, w, dev, K, Wm, variants, baseline):
         two = sum(8.0 * nrhs * r * j + 4.0 * nrhs * j * j for j in range(1, k + 1))
         kernels["omp_select_update"]["two_pass_GBps"] = round(two / (su_ms / Ke * 1e-3) / 1e9, 1)
 
+    # how far the two supports of a chunk are apart after the last step (the paper treats them as identical, which holds
+    # only in the exact-recovery regime): mean over the chunks of |support(mhat) symmetric-difference support(vhat)|
+    supports = None
+    if not args.shared_support:
+        both = torch.cat([buf.sel[:C], buf.sel[C:2 * C]], dim=1).sort(dim=1).values
+        common = (both[:, 1:] == both[:, :-1]).sum(dim=1).double()
+        supports = {"k": k, "mean_symmetric_difference": round(float((2.0 * (k - common)).mean().item()), 3),
+                    "after_steps": Ke}
+
     out = {
         "metric": "gradient elements/s per full SGC step (1 GPU)", "value": round(value, 1), "unit": "elements/s",
         "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
@@ -365,6 +374,7 @@ def run_workload(args, w, dev, K, Wm, variants, baseline):
         "ms_per_step_with_events": round((t3 - t2) * 1e3 / Ke, 3),
         "timing": "events pass only (one stream, HIP events around every launch)" if args.events_only else "eager steps, no events",
         "gram_build_ms": None if gram_ms is None else round(gram_ms, 2),
+        "supports": supports,
         "kernels": kernels,
     }
 
