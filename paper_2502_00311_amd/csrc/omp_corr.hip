@@ -430,10 +430,12 @@ __device__ __forceinline__ void static_for(F &&f)
 // the float kernel's; a stage is two groups (16 depths each) of 3 * 8 MFMAs v_mfma_f32_32x32x16_bf16
 // (low*high, high*low, high*high per block), and because a stage is five times shorter the global loads
 // run three stages ahead through two sets of staging registers.
-template <int NB, bool BF16>
+// PERSIST (float only): gridDim.x workgroups share total_tiles tiles (measured on 12352 tiles: 5.93 -> 5.87 ms per launch).
+template <int NB, bool BF16, bool PERSIST>
 __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, const float *__restrict__ R, int32_t N,
                                                                 const uint32_t *__restrict__ bitmap, int32_t words,
-                                                                uint64_t *__restrict__ partial, int32_t tiles_m)
+                                                                uint64_t *__restrict__ partial, int32_t tiles_m,
+                                                                int32_t tiles_x, int32_t total_tiles)
 {
     constexpr int BM = CORRP_BM, BN = 64 * NB, BK = 32, LD = BK + 4, MB = 4;
     constexpr int WN = 32 * NB;            // right-hand sides per wavefront
@@ -441,26 +443,46 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
     constexpr int LA = 8, LB = 2 * NB;     // 16-byte pieces per thread per stage
     typedef float floatx4 __attribute__((ext_vector_type(4)));
     extern __shared__ __attribute__((aligned(16))) float corr_lds[];
-    float *lds = corr_lds; // A stages [2][BM*LD], then R stages [2][BN*LD], then what the epilogue needs:
-    float *inv_s = corr_lds + 2 * (BM + BN) * LD;                       // reciprocal norms of the BM positions
-    uint32_t *msk_s = reinterpret_cast<uint32_t *>(inv_s + BM);         // selection words [BN][BM/32]
+    float *lds = corr_lds; // A stages [2][BM*LD], then R stages [2][BN*LD], then what the epilogue needs, twice
+    // (a workgroup that takes several tiles fetches the next tile's while it scans the current one's):
+    constexpr int COPIES = PERSIST ? 2 : 1; // PERSIST: the workgroup goes on to further tiles
+    float *inv_s = corr_lds + 2 * (BM + BN) * LD;                            // [COPIES][BM] reciprocal norms of the positions
+    uint32_t *msk_s = reinterpret_cast<uint32_t *>(inv_s + COPIES * BM);     // [COPIES][BN][BM/32] selection words
+    // [COPIES][2][BN][2] keys of the two halves of the tile; with one tile per workgroup they go where the stages were
+    uint64_t *red = PERSIST ? reinterpret_cast<uint64_t *>(msk_s + COPIES * BN * (BM / 32)) : reinterpret_cast<uint64_t *>(corr_lds);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int32_t r = A.r;
-    const int32_t m0 = A.row0 + blockIdx.x * BM, n0 = blockIdx.y * BN;
     const int l32 = lane & 31, lhalf = lane >> 5;
-    const float *abase = A.At + (int64_t)(blockIdx.x * BM) * r;
-    const float *bbase = R + (int64_t)n0 * r;
     const uint32_t lane_off = (uint32_t)((tid >> 3) * r + ((tid & 7) << 2));
-    // right-hand sides past the end of a ragged last tile re-read the last one; their results are dropped
-    uint32_t rhs_off[LB];
-#pragma unroll
-    for (int u = 0; u < LB; ++u) {
-        const int32_t n = n0 + 32 * u + (tid >> 3);
-        rhs_off[u] = (uint32_t)(((n < N ? n : N - 1) - n0) * r + ((tid & 7) << 2));
-    }
     const int ldst0 = (tid >> 3) * LD + ((tid & 7) << 2);
     const int nkb = r / BK;
+    // The tiles of this workgroup: blockIdx.x, blockIdx.x + gridDim.x, ... (tile t = block row t % tiles_x of At,
+    // block t / tiles_x of right-hand sides). With one tile per workgroup the loop below runs once. PERSIST: the
+    // float kernel launched with a workgroup per CU; the depth loop then simply runs on across the tile
+    // boundary - the last two stages of a tile load the first two of the next, so a new tile starts without
+    // waiting for memory, and only the scan of the finished tile lies between two tiles' matrix instructions.
+    struct Tile {
+        int32_t m0, n0;     // first position, first right-hand side
+        const float *abase; // its rows of At
+        const float *bbase; // its right-hand sides
+        uint32_t rhs_off[LB]; // right-hand sides past the end of a ragged last tile re-read the last one
+    };
+    auto set_tile = [&](Tile &c, int32_t t) {
+        const int32_t bx = t % tiles_x, by = t / tiles_x;
+        c.m0 = A.row0 + bx * BM;
+        c.n0 = by * BN;
+        c.abase = A.At + (int64_t)(bx * BM) * r;
+        c.bbase = R + (int64_t)c.n0 * r;
+#pragma unroll
+        for (int u = 0; u < LB; ++u) {
+            const int32_t n = c.n0 + 32 * u + (tid >> 3);
+            c.rhs_off[u] = (uint32_t)(((n < N ? n : N - 1) - c.n0) * r + ((tid & 7) << 2));
+        }
+    };
+    int32_t tile = blockIdx.x;
+    Tile cur, nxt;
+    set_tile(cur, tile);
 
     constexpr bool WIDE = BF16 && NB == 4;   // 128 x 128 outputs per wavefront: one staging set fits
     constexpr int GS = BF16 && !WIDE ? 2 : 1; // staging register sets
@@ -478,13 +500,14 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
     const int ra = (wm * 128 + l32) * LD + lhalf * 4; // fragment read offsets (floats)
     const int rb = 2 * BM * LD + (wn * WN + l32) * LD + lhalf * 4;
 
-    auto gload = [&](int u, int kb, int set = 0) { // staging piece u of stage kb (the last stage again beyond the end)
+    auto gload_of = [&](const Tile &c, int u, int kb, int set) { // staging piece u of stage kb of tile c (the last stage again beyond the end)
         const int kk = (kb < nkb ? kb : nkb - 1) * BK;
         if (u < LA)
-            g[set][u] = *reinterpret_cast<const floatx4 *>(abase + ((int64_t)(32 * u) * r + kk) + lane_off);
+            g[set][u] = *reinterpret_cast<const floatx4 *>(c.abase + ((int64_t)(32 * u) * r + kk) + lane_off);
         else
-            g[set][u] = *reinterpret_cast<const floatx4 *>(bbase + kk + rhs_off[u < LA ? 0 : u - LA]);
+            g[set][u] = *reinterpret_cast<const floatx4 *>(c.bbase + kk + c.rhs_off[u < LA ? 0 : u - LA]);
     };
+    auto gload = [&](int u, int kb, int set = 0) { gload_of(cur, u, kb, set); };
     auto lwrite = [&](int u, int buf, int set = 0) {
         const int off = u < LA ? buf * BM * LD + 32 * u * LD : 2 * BM * LD + buf * BN * LD + 32 * (u - LA) * LD;
         *reinterpret_cast<floatx4 *>(lds + ldst0 + off) = g[set][u];
@@ -520,13 +543,13 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
     // epilogue's operands are fetched here too, so that it does not wait for memory at the end
     static_for<0, LA + LB>([&](auto uc) { gload(decltype(uc)::value, 0); });
     {
-        const float nv = A.inv_colnorm[m0 + tid];
+        const float nv = A.inv_colnorm[cur.m0 + tid];
         uint32_t mw[BN * (BM / 32) / 256];
 #pragma unroll
         for (int u = 0; u < BN * (BM / 32) / 256; ++u) {
             const int e = tid + 256 * u;
-            const int32_t n = n0 + (e >> 3);
-            mw[u] = bitmap[(int64_t)(n < N ? n : N - 1) * words + (m0 >> 5) + (e & 7)];
+            const int32_t n = cur.n0 + (e >> 3);
+            mw[u] = bitmap[(int64_t)(n < N ? n : N - 1) * words + (cur.m0 >> 5) + (e & 7)];
         }
         inv_s[tid] = nv;
 #pragma unroll
@@ -598,8 +621,16 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
             __builtin_amdgcn_sched_barrier(0);
         });
     };
-    auto stage = [&](int kb, auto bufc) {
+    // NEXT: the stage two ahead belongs to the workgroup's next tile (the last two stages of a tile)
+    auto stage = [&](int kb, auto bufc, auto nextc) {
         constexpr int buf = decltype(bufc)::value;
+        constexpr bool NEXT = decltype(nextc)::value;
+        auto gahead = [&](int u) {
+            if constexpr (NEXT)
+                gload_of(nxt, u, kb + 2 - nkb, 0);
+            else
+                gload_of(cur, u, kb + 2, 0);
+        };
         static_for<0, GM>([&](auto mc) {
             constexpr int m = decltype(mc)::value;
             mfma(0, m);
@@ -623,10 +654,10 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
                 if constexpr (m >= 6 && m < 6 + LA + LB)
                     lwrite(m - 6, buf ^ 1);
                 else if constexpr (m >= 20 && m < 20 + LA + LB)
-                    gload(m - 20, kb + 2);
+                    gahead(m - 20);
             } else if constexpr (m < MB + NB + LA + LB) {
                 lwrite(m - (MB + NB), buf ^ 1);
-                gload(m - (MB + NB), kb + 2);
+                gahead(m - (MB + NB));
             }
             __builtin_amdgcn_sched_barrier(0);
         });
@@ -639,19 +670,52 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
             __builtin_amdgcn_sched_barrier(0);
         });
     };
-    for (int kb = 0; kb < nkb; kb += 2) {
-        if constexpr (WIDE) {
-            stage_wide(kb, std::integral_constant<int, 0>{});
-            stage_wide(kb + 1, std::integral_constant<int, 1>{});
-        } else if constexpr (BF16) {
-            stage_bf16(kb, std::integral_constant<int, 0>{});
-            stage_bf16(kb + 1, std::integral_constant<int, 1>{});
-        } else {
-            stage(kb, std::integral_constant<int, 0>{});
-            stage(kb + 1, std::integral_constant<int, 1>{});
+    int half = 0; // which copy of inv_s / msk_s / red the current tile uses
+    while (true) {
+    const int32_t tile_next = tile + (int32_t)gridDim.x;
+    const bool more = PERSIST && tile_next < total_tiles;
+    if constexpr (PERSIST)
+        set_tile(nxt, more ? tile_next : tile); // after the last tile its own first stages are loaded again, unused
+    if constexpr (BF16) {
+        for (int kb = 0; kb < nkb; kb += 2) {
+            if constexpr (WIDE) {
+                stage_wide(kb, std::integral_constant<int, 0>{});
+                stage_wide(kb + 1, std::integral_constant<int, 1>{});
+            } else {
+                stage_bf16(kb, std::integral_constant<int, 0>{});
+                stage_bf16(kb + 1, std::integral_constant<int, 1>{});
+            }
+        }
+    } else if constexpr (PERSIST) {
+        for (int kb = 0; kb < nkb - 2; kb += 2) {
+            stage(kb, std::integral_constant<int, 0>{}, std::false_type{});
+            stage(kb + 1, std::integral_constant<int, 1>{}, std::false_type{});
+        }
+        stage(nkb - 2, std::integral_constant<int, 0>{}, std::true_type{});
+        stage(nkb - 1, std::integral_constant<int, 1>{}, std::true_type{});
+    } else {
+        for (int kb = 0; kb < nkb; kb += 2) {
+            stage(kb, std::integral_constant<int, 0>{}, std::false_type{});
+            stage(kb + 1, std::integral_constant<int, 1>{}, std::false_type{});
         }
     }
     __syncthreads();
+    // the next tile's reciprocal norms and selection words: requested now, stored after the scan of this tile
+    float nv_next = 0.f;
+    uint32_t mw_next[BN * (BM / 32) / 256];
+    if (more) {
+        nv_next = A.inv_colnorm[nxt.m0 + tid];
+#pragma unroll
+        for (int u = 0; u < BN * (BM / 32) / 256; ++u) {
+            const int e = tid + 256 * u;
+            const int32_t n = nxt.n0 + (e >> 3);
+            mw_next[u] = bitmap[(int64_t)(n < N ? n : N - 1) * words + (nxt.m0 >> 5) + (e & 7)];
+        }
+    }
+    const int32_t m0 = cur.m0, n0 = cur.n0;
+    const float *inv_h = inv_s + half * BM;
+    const uint32_t *msk_h = msk_s + half * BN * (BM / 32);
+    uint64_t *red_h = red + half * BN * 4;
 
     // epilogue, one 32-row block of accumulators at a time (keeps the register peak low). Inside a
     // wavefront's 128 positions the two best are kept as 32-bit keys: the float score bits with the
@@ -663,13 +727,12 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
     // so they only reach the top two when the whole residual is rounding noise or zero; the two
     // winners are then tested against the selection bitmap and, if any lane of the wavefront holds a
     // selected one, the scan is repeated with the selected positions forced to key 0.
-    uint64_t *red = reinterpret_cast<uint64_t *>(corr_lds);
     uint32_t best[NB], second[NB], msk[MB][NB];
 #pragma unroll
     for (int a = 0; a < MB; ++a)
 #pragma unroll
         for (int b = 0; b < NB; ++b)
-            msk[a][b] = msk_s[(wn * WN + b * 32 + l32) * (BM / 32) + wm * 4 + a];
+            msk[a][b] = msk_h[(wn * WN + b * 32 + l32) * (BM / 32) + wm * 4 + a];
     auto scan = [&](auto maskedc) {
         constexpr bool MASKED = decltype(maskedc)::value;
 #pragma unroll
@@ -682,7 +745,7 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
             float4 inv[4];
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd)
-                inv[qd] = *reinterpret_cast<const float4 *>(inv_s + wm * 128 + a * 32 + 8 * qd + 4 * lhalf);
+                inv[qd] = *reinterpret_cast<const float4 *>(inv_h + wm * 128 + a * 32 + 8 * qd + 4 * lhalf);
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 // this lane's 16 positions of the block are bits 8*(v/4) + v%4 of the shifted word
@@ -734,20 +797,54 @@ __global__ __launch_bounds__(256, 1) void corr_pipelined_kernel(MatrixView A, co
         top2_insert(ob, wb, ws2);
         top2_insert(os, wb, ws2);
         if (lhalf == 0) {
-            red[(wm * BN + nl) * 2 + 0] = wb;
-            red[(wm * BN + nl) * 2 + 1] = ws2;
+            red_h[(wm * BN + nl) * 2 + 0] = wb;
+            red_h[(wm * BN + nl) * 2 + 1] = ws2;
         }
     }
     __syncthreads();
     if (tid < BN && n0 + tid < N) {
         const int32_t n = n0 + tid;
-        uint64_t b0 = red[tid * 2], s0 = red[tid * 2 + 1];
-        top2_insert(red[(BN + tid) * 2], b0, s0);
-        top2_insert(red[(BN + tid) * 2 + 1], b0, s0);
+        uint64_t b0 = red_h[tid * 2], s0 = red_h[tid * 2 + 1];
+        top2_insert(red_h[(BN + tid) * 2], b0, s0);
+        top2_insert(red_h[(BN + tid) * 2 + 1], b0, s0);
         uint64_t *o = partial + ((int64_t)n * tiles_m + m0 / BM) * 2;
         o[0] = b0;
         o[1] = s0;
     }
+    if (!more)
+        break;
+    // on to the next tile: its first stage already lies in LDS, its second in the staging registers, and the
+    // fragments of its first group were read at the end of the last stage
+    half ^= 1;
+    inv_s[half * BM + tid] = nv_next;
+#pragma unroll
+    for (int u = 0; u < BN * (BM / 32) / 256; ++u)
+        msk_s[half * BN * (BM / 32) + tid + 256 * u] = mw_next[u];
+#pragma unroll
+    for (int a = 0; a < MB; ++a)
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                acc[a][b][v] = 0.f;
+    cur = nxt;
+    tile = tile_next;
+    } // tiles of this workgroup
+}
+
+static int corr_cu_count()
+{
+    static int count[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+        return 0;
+    if (count[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = -1;
+        count[dev] = n;
+    }
+    return count[dev] > 0 ? count[dev] : 0;
 }
 
 template <int NB, bool BF16 = false>
@@ -755,13 +852,28 @@ static hipError_t corr_pipelined_launch_nb(const MatrixView &A, int32_t rows, co
                                            const OmpWorkspace &ws, int32_t tiles_m, hipStream_t s)
 {
     constexpr int BN = 64 * NB;
+    const int32_t tiles_x = rows / CORRP_BM, tiles_y = (N + BN - 1) / BN;
+    const int64_t total = (int64_t)tiles_x * tiles_y;
+    // The float kernel with more tiles than CUs: one workgroup per CU (all that fits anyway), each walking its share
+    // of the tiles without a pause between them. Otherwise (and for the bfloat16 variants) a workgroup per tile.
+    const int cus = BF16 ? 0 : corr_cu_count();
+    if constexpr (!BF16) if (cus > 0 && total > cus) {
+        constexpr size_t smem = (size_t)2 * (CORRP_BM + BN) * 36 * sizeof(float) + 2 * CORRP_BM * sizeof(float) +
+                                (size_t)2 * BN * (CORRP_BM / 32) * sizeof(uint32_t) + (size_t)2 * BN * 4 * sizeof(uint64_t);
+        const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void *>(corr_pipelined_kernel<NB, BF16, true>), smem);
+        if (e != hipSuccess)
+            return e;
+        corr_pipelined_kernel<NB, BF16, true><<<dim3((unsigned)cus), 256, smem, s>>>(A, R, N, ws.bitmap, ws.words, ws.partial,
+                                                                                    tiles_m, tiles_x, (int32_t)total);
+        return hipSuccess;
+    }
     constexpr size_t smem = (size_t)2 * (CORRP_BM + BN) * 36 * sizeof(float) + CORRP_BM * sizeof(float) +
                             (size_t)BN * (CORRP_BM / 32) * sizeof(uint32_t);
-    const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void *>(corr_pipelined_kernel<NB, BF16>), smem);
+    const hipError_t e = raise_dynamic_lds(reinterpret_cast<const void *>(corr_pipelined_kernel<NB, BF16, false>), smem);
     if (e != hipSuccess)
         return e;
-    const dim3 grid((unsigned)(rows / CORRP_BM), (unsigned)((N + BN - 1) / BN));
-    corr_pipelined_kernel<NB, BF16><<<grid, 256, smem, s>>>(A, R, N, ws.bitmap, ws.words, ws.partial, tiles_m);
+    corr_pipelined_kernel<NB, BF16, false><<<dim3((unsigned)total), 256, smem, s>>>(A, R, N, ws.bitmap, ws.words, ws.partial,
+                                                                                   tiles_m, tiles_x, (int32_t)total);
     return hipSuccess;
 }
 
