@@ -30,7 +30,7 @@ PROJECT_INSTR_PER_QUAD = 200.0  # vector instructions per four generated entries
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, keyed by
 # workload name: (bytes, the summary under profiles/ that holds the run). Stored figures: they describe the
 # kernel as it was when that profile was taken.
-MEASURED_TRAFFIC = {"cfg4_llama7b_block": (4.357e9, "profiles/cfg4_kernel_trace_and_hbm_traffic.md: bytes leaving the L2s, served by the "
+MEASURED_TRAFFIC = {"cfg4_llama7b_block": (4.360e9, "profiles/cfg4_kernel_trace_and_hbm_traffic.md: bytes leaving the L2s, served by the "
                                                   "memory-side cache where the 64 MiB matrix stays; algorithmic 2.44e8"),
                     "cfg5_stress_bf16": (6.22e8, "profiles/cfg5_kernel_trace_stats.md: the residuals re-read by 2048 workgroups; the 8 GiB "
                                                   "matrix is generated in the kernel and never read; algorithmic 2.6e7"),
