@@ -374,6 +374,33 @@ def test_omp_generated_matrix_with_many_right_hand_sides(N, d, r, k, flags):
 
 
 @pytest.mark.parametrize("N,d,r,k,mode", [
+    (8400, 2048, 64, 4, "stored"),    # two halves of 8 x 33 = 264 tiles of 256 x 128 each: eight workgroups take a second tile; ragged last tiles
+    (40000, 1024, 64, 3, "stored"),   # halves of 4 x 157 = 628 tiles: two or three per workgroup
+    (9000, 4096, 128, 5, "philox"),   # generated matrix written to the panel; halves of 16 x 36 = 576 tiles
+    (5000, 768, 192, 6, "stored"),    # 3 x 40 = 120 tiles: fewer than 128, the general kernel (one tile per workgroup)
+])
+def test_contraction_with_more_tiles_than_compute_units(N, d, r, k, mode):
+    """The float contraction on full tiles runs as one workgroup per CU that walks its tiles (the next tile's first
+    stages are loaded during the last stages of the current one). Sampled right-hand sides against the oracle, chosen
+    at the edges of tiles and of the shares of a workgroup; supports distinct everywhere."""
+    say("omp many tiles", N, d, r, k, mode)
+    rng = np.random.default_rng(N + 3 * d + k)
+    A, At = make_matrix(mode, 35, d, r)
+    Y = rng.standard_normal((N, r)).astype(np.float32)
+    Y[129] = 0.0
+    sel, x = run_omp(Y, A, k)
+    norm = orc.colnorms(At)
+    sample = sorted(set([0, 1, 127, 128, 129, 255, 256, N // 3, N // 2, (N // 128) * 128 - 1, (N // 128) * 128 if N % 128 else N - 128,
+                         N - 2, N - 1] + [int(v) for v in rng.integers(0, N, size=24)]))
+    for n in sample:
+        ref = orc.omp(Y[n], At, k, norm=norm)
+        assert np.array_equal(sel[n], ref["sel"]), n
+        assert relerr(x[n], ref["x"]) < TOL, n
+    assert all(len(set(row.tolist())) == k for row in sel)
+    assert sel.min() >= 0 and sel.max() < d
+
+
+@pytest.mark.parametrize("N,d,r,k,mode", [
     (2, 4096, 256, 32, "stored"),     # configuration 1's shape with both moments: 64 workgroups of 64 rows
     (1, 4096, 256, 32, "stored"),
     (4, 1000, 96, 12, "stored"),      # ragged: the last workgroup holds fewer rows
