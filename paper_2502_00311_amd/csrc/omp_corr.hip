@@ -854,6 +854,8 @@ static hipError_t corr_pipelined_launch_nb(const MatrixView &A, int32_t rows, co
     constexpr int BN = 64 * NB;
     const int32_t tiles_x = rows / CORRP_BM, tiles_y = (N + BN - 1) / BN;
     const int64_t total = (int64_t)tiles_x * tiles_y;
+    if (total > 0x7fffffff) // tile numbers are 32-bit (a launch of that size would run for days)
+        return hipErrorInvalidValue;
     // The float kernel with more tiles than CUs: one workgroup per CU (all that fits anyway), each walking its share
     // of the tiles without a pause between them. Otherwise (and for the bfloat16 variants) a workgroup per tile.
     const int cus = BF16 ? 0 : corr_cu_count();
